@@ -1,0 +1,157 @@
+/*
+ * ssa.h -- C ABI of the MI355X (gfx950) Spatial Sparse Attention library.
+ *
+ * Spatial Sparse Attention (SSA; paper Sec. "Spatial Sparse Attention", eq. (4)): for every token t and
+ * query head h,
+ *     o[t,h] = w_cmp * Attn(q, K_cmp, V_cmp) + w_slc * Attn(q, K_slc(t), V_slc(t)) + w_win * Attn(q, K_win(t), V_win(t))
+ * where each Attn is softmax attention (eq. (2)-(3)) over a key set defined by 3D blocks of the voxel grid:
+ *   cmp: one mean-pooled key/value per non-empty m_cmp^3 block of the token's batch item (eq. (5), mean pool);
+ *   slc: all tokens of the T selection blocks (m_slc^3) with the largest score, the score of a block being the
+ *        sum of the compression-attention probabilities of its child compression blocks, summed over the
+ *        query heads that share a KV head (eq. (6)); ties go to the lowest block id (Algorithm 1 consumes the
+ *        resulting index tensor I);
+ *   win: all tokens of the token's own m_win^3 window (window paragraph).
+ *
+ * General conventions
+ *   - Every pointer marked "dev" is device memory on the current HIP device; "host" is host memory.
+ *   - All tensors are dense, row-major, in the CALLER'S token order.  Query head h uses KV head h / (Hq/Hkv).
+ *   - dtype selects the element type of q,k,v,gates,out,out_branch,dout,dq,dk,dv,dgates: SSA_BF16 (2 bytes,
+ *     bfloat16) or SSA_F32.  lse is always float, indices are int32.
+ *   - The caller owns every tensor and the workspace.  The library owns only ssa_blocks_t.
+ *   - ssa_forward / ssa_backward enqueue work on `stream` (a hipStream_t passed as void*) and return without
+ *     synchronising; they never allocate.  ssa_build_blocks allocates the handle's arrays and synchronises
+ *     the stream once to learn the block counts.
+ *   - Return value: 0 on success, a negative ssa_status_t otherwise.  On a validation error nothing is
+ *     launched and no output is written.
+ */
+#ifndef SSA_H_
+#define SSA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ssa_blocks ssa_blocks_t; /* opaque: sorted token order + block start arrays (device) */
+
+typedef enum { SSA_BF16 = 0, SSA_F32 = 1 } ssa_dtype_t;
+
+typedef enum {
+  SSA_OK = 0,
+  SSA_ERR_NULL = -1,            /* a required pointer is NULL */
+  SSA_ERR_BAD_SHAPE = -2,       /* n_tokens < 0, n_batch < 1, grid < 1 or > 1024, topk < 1 or > 64, bad dtype */
+  SSA_ERR_BAD_BLOCK_SIZES = -3, /* m_slc <= m_cmp or m_slc % m_cmp != 0 or a side < 1 */
+  SSA_ERR_BAD_HEADS = -4,       /* Hq % Hkv != 0 or a count < 1 */
+  SSA_ERR_BAD_OFFSETS = -5,     /* batch_offsets not monotone from 0 to n_tokens */
+  SSA_ERR_COORD_RANGE = -6,     /* a coordinate outside [0, grid) */
+  SSA_ERR_WORKSPACE = -7,       /* workspace NULL or smaller than ssa_workspace_bytes() */
+  SSA_ERR_UNSUPPORTED = -8,     /* block side not a power of two; head_dim not a multiple of 8 or > 128 */
+  SSA_ERR_HIP = -9,             /* a HIP runtime call failed */
+  SSA_ERR_MISMATCH = -10        /* params disagree with the ones the blocks handle was built with */
+} ssa_status_t;
+
+typedef struct {
+  int32_t n_tokens, n_batch, grid;         /* N, B, G: coordinates lie in [0,G)^3                         */
+  int32_t m_cmp, m_slc, m_win, topk;       /* block sides (powers of two, m_cmp | m_slc, m_slc > m_cmp), T */
+  int32_t n_heads_q, n_heads_kv, head_dim; /* Hq, Hkv (Hq % Hkv == 0), d (multiple of 8, <= 128)          */
+  int32_t dtype;                           /* ssa_dtype_t                                                 */
+  float scale;                             /* softmax scale; <= 0 means 1/sqrt(d) (eq. (3))               */
+} ssa_params_t;
+
+/* Which array ssa_blocks_export copies out (all int32). */
+typedef enum {
+  SSA_ARR_PERM = 0,            /* [N]     sorted position -> caller index                                    */
+  SSA_ARR_INV_PERM = 1,        /* [N]     caller index -> sorted position                                    */
+  SSA_ARR_CMP_START = 2,       /* [Nc+1]  first sorted position of each compression block                    */
+  SSA_ARR_SLC_START = 3,       /* [Ns+1]  same for selection blocks: the array C of Algorithm 1              */
+  SSA_ARR_WIN_START = 4,       /* [Nw+1]  same for windows                                                   */
+  SSA_ARR_SLC_CHILD_START = 5, /* [Ns+1]  compression-block range of each selection block                    */
+  SSA_ARR_CMP_BATCH = 6,       /* [B+1]   compression-block range of each batch item                         */
+  SSA_ARR_SLC_BATCH = 7,       /* [B+1]   selection-block range of each batch item                           */
+  SSA_ARR_TOK_WIN = 8          /* [N]     window id of the token at each sorted position                     */
+} ssa_array_t;
+
+/*
+ * Block partition, token sort and block start arrays (paper: "we divide the 3D space into subgrids of size
+ * m^3 ... tokens residing in the same subgrid are grouped into one block"; "sort the input tokens based on
+ * their block indices, then compute the starting index C of each block"; Algorithm 1, Require + line 2).
+ *
+ * Block ids are dense ranks of (batch item, Morton code of floor(coord/m)) among non-empty blocks, Morton
+ * interleaving x -> bit 3i+2, y -> 3i+1, z -> 3i.  Tokens are ordered by (item, full-resolution Morton code),
+ * equal voxels by caller index.  Results are bit-exact and deterministic.
+ *
+ *   params        host; n_tokens, n_batch, grid, m_cmp, m_slc, m_win are read (head fields are ignored)
+ *   coords        dev int32 [N,3] voxel coordinates (x,y,z), caller order
+ *   batch_offsets dev int32 [B+1], batch_offsets[0]=0, nondecreasing, batch_offsets[B]=N
+ *   stream        hipStream_t
+ *   out           host; receives a handle to free with ssa_blocks_destroy
+ * Errors: NULL, BAD_SHAPE, BAD_BLOCK_SIZES, UNSUPPORTED (before any launch); BAD_OFFSETS, COORD_RANGE (found
+ * on the device, reported after the synchronisation; no handle is returned); HIP.
+ */
+int ssa_build_blocks(const ssa_params_t *params, const int32_t *coords, const int32_t *batch_offsets,
+                     void *stream, ssa_blocks_t **out);
+
+/* Number of non-empty compression / selection / window blocks (host ints; any may be NULL). */
+int ssa_blocks_counts(const ssa_blocks_t *blocks, int32_t *n_cmp, int32_t *n_slc, int32_t *n_win);
+
+/* Largest number of selection blocks in one batch item (the row length S_max of ssa_topk_from_scores). */
+int ssa_blocks_max_slc_per_item(const ssa_blocks_t *blocks, int32_t *s_max);
+
+/* Copy one index array to dst_dev (dev, `bytes` must be at least its size) on `stream`. */
+int ssa_blocks_export(const ssa_blocks_t *blocks, int which, void *dst_dev, size_t bytes, void *stream);
+
+/* Free the handle and its device arrays (NULL is allowed). */
+void ssa_blocks_destroy(ssa_blocks_t *blocks);
+
+/* Bytes of device workspace ssa_forward (for_backward == 0) or ssa_backward (!= 0) needs; 0 on bad input. */
+size_t ssa_workspace_bytes(const ssa_params_t *params, const ssa_blocks_t *blocks, int for_backward);
+
+/*
+ * SSA forward (eq. (4); compression eq. (5); selection score eq. (6) and top-k; Algorithm 1; window
+ * paragraph).
+ *   q        dev [N,Hq,d]      k, v   dev [N,Hkv,d]      gates  dev [N,Hq,3], order (cmp, slc, win)
+ *   out      dev [N,Hq,d]      written
+ *   lse      dev float [3,N,Hq] or NULL: natural-log log-sum-exp of each branch's scaled logits (Algorithm 1's l)
+ *   topk_idx dev int32 [N,Hkv,T] or NULL: selected selection-block ids (global over the batch, ascending,
+ *            -1 padded when the item has fewer than T blocks): Algorithm 1's I
+ *   out_branch dev [3,N,Hq,d] or NULL: the three branch outputs before gating
+ *   lse, topk_idx and out_branch are optional for inference; ssa_backward needs all three.
+ * Errors: NULL, BAD_SHAPE, BAD_HEADS, UNSUPPORTED, MISMATCH, WORKSPACE, HIP.
+ */
+int ssa_forward(const ssa_params_t *params, const ssa_blocks_t *blocks, const void *q, const void *k,
+                const void *v, const void *gates, void *out, float *lse, int32_t *topk_idx, void *out_branch,
+                void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * SSA backward: gradients of sum(dout * out) w.r.t. q, k, v, gates, with the selected index sets held
+ * constant (no gradient flows through the selection scores or the top-k).  The paper states no backward;
+ * this is the softmax-attention gradient of eq. (2)-(4) and of the mean pool of eq. (5).
+ *   q,k,v,gates as in ssa_forward; out_branch, lse, topk_idx: what ssa_forward wrote for the same inputs
+ *   dout   dev [N,Hq,d]
+ *   dq     dev [N,Hq,d]   dk, dv dev [N,Hkv,d]   dgates dev [N,Hq,3]   all overwritten
+ * Errors: as ssa_forward.
+ */
+int ssa_backward(const ssa_params_t *params, const ssa_blocks_t *blocks, const void *q, const void *k,
+                 const void *v, const void *gates, const void *out_branch, const float *lse,
+                 const int32_t *topk_idx, const void *dout, void *dq, void *dk, void *dv, void *dgates,
+                 void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The top-k decision alone (paper: "The top-k selection blocks with the highest s_slc scores are selected"),
+ * on caller-supplied scores: row (t,g) of `scores` (dev float [N,Hkv,S_max]) holds in column j the score of
+ * the j-th selection block of t's batch item; columns past the item's block count are ignored.  Writes
+ * topk_idx (dev int32 [N,Hkv,T]) exactly as ssa_forward does: the T largest, ties to the lowest block id,
+ * ascending ids, -1 padded.  Only n_tokens, n_heads_kv and topk of params are read.
+ */
+int ssa_topk_from_scores(const ssa_params_t *params, const ssa_blocks_t *blocks, const float *scores,
+                         int32_t *topk_idx, void *stream);
+
+/* Static description of a status code. */
+const char *ssa_error_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SSA_H_ */

@@ -1,0 +1,319 @@
+// Block partition, token sort and block start arrays for SSA on gfx950.
+//
+// Paper, Sec. "Spatial Sparse Attention": tokens whose voxels fall into the same m^3 sub-grid form a block;
+// tokens are sorted by block and the first-token index of every block (array C of Algorithm 1) is kept.
+// Here one Morton-order sort serves the three block granularities (all sides are powers of two, so every
+// aligned cube is a contiguous run of the Morton order): key = (batch item << 3*bits) | Morton(x,y,z).
+// Integer work only; results are bit-exact and independent of scheduling (stable LSD radix sort, no
+// order-dependent atomics).
+#include "ssa_internal.h"
+
+namespace {
+
+constexpr int SORT_TILE = 256;  // one key per thread, 4 wavefronts per workgroup
+
+enum { META_ERR = 0, META_NC, META_NS, META_NW, META_SMAX, META_CMAX, META_SLC_TOK, META_WIN_TOK, META_CMP_TOK, META_N };
+
+// Spread the low 10 bits of v so that bit i lands on bit 3i.
+__device__ inline uint32_t spread3(uint32_t v) {
+  v &= 0x3FFu;
+  v = (v | (v << 16)) & 0x030000FFu;
+  v = (v | (v << 8)) & 0x0300F00Fu;
+  v = (v | (v << 4)) & 0x030C30C3u;
+  v = (v | (v << 2)) & 0x09249249u;
+  return v;
+}
+
+__global__ void k_make_keys(const int32_t *__restrict__ coords, const int32_t *__restrict__ offs, int N, int B, int G,
+                            int bits, uint64_t *__restrict__ keys, uint32_t *__restrict__ vals, int32_t *meta) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  for (int j = i; j <= B; j += gridDim.x * blockDim.x) {
+    const int o = offs[j];
+    const bool bad = (j == 0 && o != 0) || (j == B && o != N) || (j > 0 && o < offs[j - 1]) || o < 0 || o > N;
+    if (bad) atomicOr(&meta[META_ERR], 1);
+  }
+  if (i >= N) return;
+  int lo = 0, hi = B;  // offs[lo] <= i < offs[hi] for valid offsets
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (offs[mid] <= i) lo = mid; else hi = mid;
+  }
+  int x = coords[3 * i], y = coords[3 * i + 1], z = coords[3 * i + 2];
+  if ((unsigned)x >= (unsigned)G || (unsigned)y >= (unsigned)G || (unsigned)z >= (unsigned)G) {
+    atomicOr(&meta[META_ERR], 2);
+    x = y = z = 0;
+  }
+  const uint64_t code = (uint64_t)((spread3((uint32_t)x) << 2) | (spread3((uint32_t)y) << 1) | spread3((uint32_t)z));
+  keys[i] = ((uint64_t)lo << (3 * bits)) | code;
+  vals[i] = (uint32_t)i;
+}
+
+// Per-tile digit histogram, stored digit-major so that one linear scan yields the scatter offsets.
+__global__ void k_sort_hist(const uint64_t *__restrict__ keys, int N, int shift, int nTiles, uint32_t *__restrict__ hist) {
+  __shared__ uint32_t h[256];
+  h[threadIdx.x] = 0;
+  __syncthreads();
+  const int i = blockIdx.x * SORT_TILE + threadIdx.x;
+  if (i < N) atomicAdd(&h[(uint32_t)(keys[i] >> shift) & 255u], 1u);
+  __syncthreads();
+  hist[threadIdx.x * nTiles + blockIdx.x] = h[threadIdx.x];
+}
+
+// In-place exclusive scan of n values by one workgroup of 1024 threads.
+__global__ void k_scan_u32(uint32_t *data, int n) {
+  __shared__ uint32_t part[1024];
+  const int tid = threadIdx.x;
+  const int per = (n + 1023) / 1024;
+  const int b = min(n, tid * per), e = min(n, b + per);
+  uint32_t s = 0;
+  for (int i = b; i < e; ++i) s += data[i];
+  part[tid] = s;
+  __syncthreads();
+  for (int off = 1; off < 1024; off <<= 1) {
+    const uint32_t v = tid >= off ? part[tid - off] : 0u;
+    __syncthreads();
+    part[tid] += v;
+    __syncthreads();
+  }
+  uint32_t run = part[tid] - s;
+  for (int i = b; i < e; ++i) {
+    const uint32_t v = data[i];
+    data[i] = run;
+    run += v;
+  }
+}
+
+// Stable scatter of one 8-bit digit: rank inside the wavefront by ballot matching, wavefronts in order.
+__global__ void k_sort_scatter(const uint64_t *__restrict__ kin, const uint32_t *__restrict__ vin,
+                               uint64_t *__restrict__ kout, uint32_t *__restrict__ vout, int N, int shift, int nTiles,
+                               const uint32_t *__restrict__ offs) {
+  __shared__ uint32_t wcnt[SORT_TILE / 64][256];
+  for (int w = 0; w < SORT_TILE / 64; ++w) wcnt[w][threadIdx.x] = 0;
+  __syncthreads();
+  const int i = blockIdx.x * SORT_TILE + threadIdx.x;
+  const bool valid = i < N;
+  const uint64_t key = valid ? kin[i] : 0ull;
+  const uint32_t digit = (uint32_t)(key >> shift) & 255u;
+  uint64_t peers = __ballot(valid);
+#pragma unroll
+  for (int b = 0; b < 8; ++b) {
+    const bool bit = (digit >> b) & 1u;
+    const uint64_t m = __ballot(bit);
+    peers &= bit ? m : ~m;
+  }
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const uint32_t rank = (uint32_t)__popcll(peers & ((1ull << lane) - 1ull));
+  if (valid && rank == 0) wcnt[w][digit] = (uint32_t)__popcll(peers);
+  __syncthreads();
+  if (valid) {
+    uint32_t pos = offs[digit * nTiles + blockIdx.x] + rank;
+    for (int ww = 0; ww < w; ++ww) pos += wcnt[ww][digit];
+    kout[pos] = key;
+    vout[pos] = vin[i];
+  }
+}
+
+struct CsrOut {
+  int32_t *perm, *inv_perm, *tok_item, *tok_cmp, *tok_slc, *tok_win;
+  int32_t *cmp_start, *slc_start, *win_start, *slc_child_start, *cmp_slc, *cmp_batch, *slc_batch;
+};
+
+// One workgroup: block ids (= running count of block heads) at the three granularities and every start array.
+__global__ void k_csr(const uint64_t *__restrict__ ks, const uint32_t *__restrict__ vals, int N, int B, int bits, int sc,
+                      int ss, int sw, CsrOut o, int32_t *meta) {
+  __shared__ int part[3][1024];
+  const int tid = threadIdx.x;
+  const int per = (N + 1023) / 1024;
+  const int b = min(N, tid * per), e = min(N, b + per);
+  int c[3] = {0, 0, 0};
+  for (int i = b; i < e; ++i) {
+    const uint64_t k = ks[i];
+    const bool first = i == 0;
+    const uint64_t p = first ? 0ull : ks[i - 1];
+    c[0] += first || (k >> sc) != (p >> sc);
+    c[1] += first || (k >> ss) != (p >> ss);
+    c[2] += first || (k >> sw) != (p >> sw);
+  }
+  for (int x = 0; x < 3; ++x) part[x][tid] = c[x];
+  __syncthreads();
+  for (int off = 1; off < 1024; off <<= 1) {
+    int v[3];
+    for (int x = 0; x < 3; ++x) v[x] = tid >= off ? part[x][tid - off] : 0;
+    __syncthreads();
+    for (int x = 0; x < 3; ++x) part[x][tid] += v[x];
+    __syncthreads();
+  }
+  int run[3];
+  for (int x = 0; x < 3; ++x) run[x] = part[x][tid] - c[x];
+  for (int i = b; i < e; ++i) {
+    const uint64_t k = ks[i];
+    const bool first = i == 0;
+    const uint64_t p = first ? 0ull : ks[i - 1];
+    const bool hc = first || (k >> sc) != (p >> sc);
+    const bool hs = first || (k >> ss) != (p >> ss);
+    const bool hw = first || (k >> sw) != (p >> sw);
+    run[0] += hc; run[1] += hs; run[2] += hw;
+    const int idc = run[0] - 1, ids = run[1] - 1, idw = run[2] - 1;
+    const int item = (int)(k >> (3 * bits));
+    const int pitem = first ? -1 : (int)(p >> (3 * bits));
+    const uint32_t src = vals[i];
+    o.perm[i] = (int32_t)src;
+    o.inv_perm[src] = i;
+    o.tok_item[i] = item;
+    o.tok_cmp[i] = idc;
+    o.tok_slc[i] = ids;
+    o.tok_win[i] = idw;
+    if (hc) { o.cmp_start[idc] = i; o.cmp_slc[idc] = ids; }
+    if (hs) { o.slc_start[ids] = i; o.slc_child_start[ids] = idc; }
+    if (hw) o.win_start[idw] = i;
+    for (int it = pitem + 1; it <= item; ++it) { o.cmp_batch[it] = idc; o.slc_batch[it] = ids; }
+    if (i == N - 1) {
+      const int Nc = idc + 1, Ns = ids + 1, Nw = idw + 1;
+      o.cmp_start[Nc] = N; o.slc_start[Ns] = N; o.win_start[Nw] = N; o.slc_child_start[Ns] = Nc;
+      for (int it = item + 1; it <= B; ++it) { o.cmp_batch[it] = Nc; o.slc_batch[it] = Ns; }
+      meta[META_NC] = Nc; meta[META_NS] = Ns; meta[META_NW] = Nw;
+    }
+  }
+}
+
+// Largest per-item block counts and per-block token counts (integer max: order independent).
+__global__ void k_maxima(CsrOut o, int B, int32_t *meta) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  const int Nc = meta[META_NC], Ns = meta[META_NS], Nw = meta[META_NW];
+  if (i < B) {
+    atomicMax(&meta[META_SMAX], o.slc_batch[i + 1] - o.slc_batch[i]);
+    atomicMax(&meta[META_CMAX], o.cmp_batch[i + 1] - o.cmp_batch[i]);
+  }
+  if (i < Nc) atomicMax(&meta[META_CMP_TOK], o.cmp_start[i + 1] - o.cmp_start[i]);
+  if (i < Ns) atomicMax(&meta[META_SLC_TOK], o.slc_start[i + 1] - o.slc_start[i]);
+  if (i < Nw) atomicMax(&meta[META_WIN_TOK], o.win_start[i + 1] - o.win_start[i]);
+}
+
+}  // namespace
+
+extern "C" int ssa_build_blocks(const ssa_params_t *p, const int32_t *coords, const int32_t *batch_offsets,
+                                void *stream_, ssa_blocks_t **out) {
+  if (!p || !out) return SSA_ERR_NULL;
+  *out = nullptr;
+  if (p->n_tokens < 0 || p->n_batch < 1 || p->grid < 1 || p->grid > 1024) return SSA_ERR_BAD_SHAPE;
+  if (p->m_cmp < 1 || p->m_slc < 1 || p->m_win < 1 || p->m_slc <= p->m_cmp || p->m_slc % p->m_cmp != 0)
+    return SSA_ERR_BAD_BLOCK_SIZES;
+  auto pow2 = [](int m) { return (m & (m - 1)) == 0; };
+  if (!pow2(p->m_cmp) || !pow2(p->m_slc) || !pow2(p->m_win)) return SSA_ERR_UNSUPPORTED;
+  if (!batch_offsets || (p->n_tokens > 0 && !coords)) return SSA_ERR_NULL;
+  hipStream_t stream = (hipStream_t)stream_;
+  const int N = p->n_tokens, B = p->n_batch;
+  int bits = 1;
+  while ((1 << bits) < p->grid) ++bits;
+  int item_bits = 1;
+  while ((1ll << item_bits) < (long long)B) ++item_bits;
+
+  ssa_blocks *h = new ssa_blocks();
+  h->N = N; h->B = B; h->G = p->grid; h->m_cmp = p->m_cmp; h->m_slc = p->m_slc; h->m_win = p->m_win; h->bits = bits;
+  if (hipGetDevice(&h->device) != hipSuccess) { delete h; return SSA_ERR_HIP; }
+  const size_t n1 = (size_t)N + 1;
+  const size_t ints = 6 * (size_t)N + 4 * n1 + (size_t)N + 2 * ((size_t)B + 1) + 64;
+  if (hipMalloc(&h->base, ints * sizeof(int32_t)) != hipSuccess) { delete h; return SSA_ERR_HIP; }
+  int32_t *w = (int32_t *)h->base;
+  auto take = [&](size_t n) { int32_t *r = w; w += n; return r; };
+  h->perm = take(N); h->inv_perm = take(N); h->tok_item = take(N); h->tok_cmp = take(N); h->tok_slc = take(N);
+  h->tok_win = take(N); h->cmp_start = take(n1); h->slc_start = take(n1); h->win_start = take(n1);
+  h->slc_child_start = take(n1); h->cmp_slc = take(N); h->cmp_batch = take(B + 1); h->slc_batch = take(B + 1);
+
+  int32_t meta_h[META_N] = {0};
+  const int nTiles = (N + SORT_TILE - 1) / SORT_TILE;
+  void *tmp = nullptr;
+  const size_t key_b = align_up((size_t)N * 8, 256), val_b = align_up((size_t)N * 4, 256);
+  const size_t hist_b = align_up((size_t)256 * (nTiles > 0 ? nTiles : 1) * 4, 256);
+  const size_t tmp_bytes = 2 * key_b + 2 * val_b + hist_b + 256;
+  auto fail = [&](int code) {
+    if (tmp) (void)hipFree(tmp);
+    (void)hipFree(h->base);
+    delete h;
+    return code;
+  };
+  if (hipMalloc(&tmp, tmp_bytes) != hipSuccess) return fail(SSA_ERR_HIP);
+  char *tp = (char *)tmp;
+  uint64_t *k0 = (uint64_t *)tp; tp += key_b;
+  uint64_t *k1 = (uint64_t *)tp; tp += key_b;
+  uint32_t *v0 = (uint32_t *)tp; tp += val_b;
+  uint32_t *v1 = (uint32_t *)tp; tp += val_b;
+  uint32_t *hist = (uint32_t *)tp; tp += hist_b;
+  int32_t *meta = (int32_t *)tp;
+  if (hipMemsetAsync(meta, 0, 256, stream) != hipSuccess) return fail(SSA_ERR_HIP);
+  CsrOut o{h->perm, h->inv_perm, h->tok_item, h->tok_cmp, h->tok_slc, h->tok_win, h->cmp_start, h->slc_start,
+           h->win_start, h->slc_child_start, h->cmp_slc, h->cmp_batch, h->slc_batch};
+  if (N > 0) {
+    k_make_keys<<<(N + 255) / 256, 256, 0, stream>>>(coords, batch_offsets, N, B, p->grid, bits, k0, v0, meta);
+    const int total_bits = 3 * bits + item_bits;
+    for (int shift = 0; shift < total_bits; shift += 8) {
+      k_sort_hist<<<nTiles, SORT_TILE, 0, stream>>>(k0, N, shift, nTiles, hist);
+      k_scan_u32<<<1, 1024, 0, stream>>>(hist, 256 * nTiles);
+      k_sort_scatter<<<nTiles, SORT_TILE, 0, stream>>>(k0, v0, k1, v1, N, shift, nTiles, hist);
+      uint64_t *tk = k0; k0 = k1; k1 = tk;
+      uint32_t *tv = v0; v0 = v1; v1 = tv;
+    }
+    k_csr<<<1, 1024, 0, stream>>>(k0, v0, N, B, bits, 3 * ilog2_exact(p->m_cmp), 3 * ilog2_exact(p->m_slc),
+                                  3 * ilog2_exact(p->m_win), o, meta);
+    const int span = (N > B ? N : B);
+    k_maxima<<<(span + 255) / 256, 256, 0, stream>>>(o, B, meta);
+  } else {
+    // no tokens: every start array is a single zero; the offsets are still validated (all must be zero)
+    if (hipMemsetAsync(h->base, 0, ints * sizeof(int32_t), stream) != hipSuccess) return fail(SSA_ERR_HIP);
+    k_make_keys<<<1, 256, 0, stream>>>(coords, batch_offsets, 0, B, p->grid, bits, k0, v0, meta);
+  }
+  if (hipGetLastError() != hipSuccess) return fail(SSA_ERR_HIP);
+  if (hipMemcpyAsync(meta_h, meta, sizeof(meta_h), hipMemcpyDeviceToHost, stream) != hipSuccess) return fail(SSA_ERR_HIP);
+  if (hipStreamSynchronize(stream) != hipSuccess) return fail(SSA_ERR_HIP);
+  if (meta_h[META_ERR] & 1) return fail(SSA_ERR_BAD_OFFSETS);
+  if (meta_h[META_ERR] & 2) return fail(SSA_ERR_COORD_RANGE);
+  (void)hipFree(tmp);
+  tmp = nullptr;
+  h->Nc = meta_h[META_NC]; h->Ns = meta_h[META_NS]; h->Nw = meta_h[META_NW];
+  h->s_max = meta_h[META_SMAX]; h->c_max = meta_h[META_CMAX]; h->slc_tok_max = meta_h[META_SLC_TOK];
+  h->win_tok_max = meta_h[META_WIN_TOK]; h->cmp_tok_max = meta_h[META_CMP_TOK];
+  *out = h;
+  return SSA_OK;
+}
+
+extern "C" int ssa_blocks_counts(const ssa_blocks_t *b, int32_t *n_cmp, int32_t *n_slc, int32_t *n_win) {
+  if (!b) return SSA_ERR_NULL;
+  if (n_cmp) *n_cmp = b->Nc;
+  if (n_slc) *n_slc = b->Ns;
+  if (n_win) *n_win = b->Nw;
+  return SSA_OK;
+}
+
+extern "C" int ssa_blocks_max_slc_per_item(const ssa_blocks_t *b, int32_t *s_max) {
+  if (!b || !s_max) return SSA_ERR_NULL;
+  *s_max = b->s_max;
+  return SSA_OK;
+}
+
+extern "C" int ssa_blocks_export(const ssa_blocks_t *b, int which, void *dst, size_t bytes, void *stream) {
+  if (!b || !dst) return SSA_ERR_NULL;
+  const int32_t *src = nullptr;
+  size_t n = 0;
+  switch (which) {
+    case SSA_ARR_PERM: src = b->perm; n = b->N; break;
+    case SSA_ARR_INV_PERM: src = b->inv_perm; n = b->N; break;
+    case SSA_ARR_CMP_START: src = b->cmp_start; n = (size_t)b->Nc + 1; break;
+    case SSA_ARR_SLC_START: src = b->slc_start; n = (size_t)b->Ns + 1; break;
+    case SSA_ARR_WIN_START: src = b->win_start; n = (size_t)b->Nw + 1; break;
+    case SSA_ARR_SLC_CHILD_START: src = b->slc_child_start; n = (size_t)b->Ns + 1; break;
+    case SSA_ARR_CMP_BATCH: src = b->cmp_batch; n = (size_t)b->B + 1; break;
+    case SSA_ARR_SLC_BATCH: src = b->slc_batch; n = (size_t)b->B + 1; break;
+    case SSA_ARR_TOK_WIN: src = b->tok_win; n = b->N; break;
+    default: return SSA_ERR_BAD_SHAPE;
+  }
+  if (bytes < n * sizeof(int32_t)) return SSA_ERR_WORKSPACE;
+  if (n == 0) return SSA_OK;
+  SSA_HIP_TRY(hipMemcpyAsync(dst, src, n * sizeof(int32_t), hipMemcpyDeviceToDevice, (hipStream_t)stream));
+  return SSA_OK;
+}
+
+extern "C" void ssa_blocks_destroy(ssa_blocks_t *b) {
+  if (!b) return;
+  if (b->base) (void)hipFree(b->base);
+  delete b;
+}

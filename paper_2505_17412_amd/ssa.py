@@ -1,0 +1,165 @@
+"""Thin Python binding of the SSA C ABI (``include/ssa.h``): argument marshalling only.
+
+PyTorch supplies device memory and the stream; every step of the path runs in the HIP library.  The
+functions mirror the C entry points by name.  Loading fails loudly when ``lib/libssa_hip.so`` has not been
+built (``python -m paper_2505_17412_amd.build``); there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libssa_hip.so")
+
+SSA_BF16, SSA_F32 = 0, 1
+ARRAYS = dict(perm=0, inv_perm=1, cmp_start=2, slc_start=3, win_start=4, slc_child_start=5, cmp_batch=6,
+              slc_batch=7, tok_win=8)
+EXPORTED_SYMBOLS = (
+    "ssa_build_blocks", "ssa_blocks_counts", "ssa_blocks_max_slc_per_item", "ssa_blocks_export",
+    "ssa_blocks_destroy", "ssa_workspace_bytes", "ssa_forward", "ssa_backward", "ssa_topk_from_scores",
+    "ssa_error_string",
+)
+
+
+class ssa_params_t(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_tokens", "n_batch", "grid", "m_cmp", "m_slc", "m_win", "topk",
+                                         "n_heads_q", "n_heads_kv", "head_dim", "dtype")] + [("scale", C.c_float)]
+
+
+class SSAError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {error_string(status)} ({status})")
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2505_17412_amd.build`")
+        L = C.CDLL(_LIB_PATH)
+        vp, i32p = C.c_void_p, C.POINTER(C.c_int32)
+        L.ssa_build_blocks.argtypes = [C.POINTER(ssa_params_t), vp, vp, vp, C.POINTER(vp)]
+        L.ssa_blocks_counts.argtypes = [vp, i32p, i32p, i32p]
+        L.ssa_blocks_max_slc_per_item.argtypes = [vp, i32p]
+        L.ssa_blocks_export.argtypes = [vp, C.c_int, vp, C.c_size_t, vp]
+        L.ssa_blocks_destroy.argtypes = [vp]
+        L.ssa_blocks_destroy.restype = None
+        L.ssa_workspace_bytes.argtypes = [C.POINTER(ssa_params_t), vp, C.c_int]
+        L.ssa_workspace_bytes.restype = C.c_size_t
+        L.ssa_forward.argtypes = [C.POINTER(ssa_params_t), vp] + [vp] * 8 + [vp, C.c_size_t, vp]
+        L.ssa_backward.argtypes = [C.POINTER(ssa_params_t), vp] + [vp] * 12 + [vp, C.c_size_t, vp]
+        L.ssa_topk_from_scores.argtypes = [C.POINTER(ssa_params_t), vp, vp, vp, vp]
+        L.ssa_error_string.argtypes = [C.c_int]
+        L.ssa_error_string.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+def error_string(status: int) -> str:
+    return lib().ssa_error_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise SSAError(status, where)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    assert t.is_contiguous(), "tensors must be contiguous"
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def make_params(n_tokens, n_batch, grid, m_cmp, m_slc, m_win, topk, n_heads_q, n_heads_kv, head_dim, dtype,
+                scale: float = 0.0) -> ssa_params_t:
+    code = {"bf16": SSA_BF16, "f32": SSA_F32, torch.bfloat16: SSA_BF16, torch.float32: SSA_F32}.get(dtype, dtype)
+    return ssa_params_t(n_tokens, n_batch, grid, m_cmp, m_slc, m_win, topk, n_heads_q, n_heads_kv, head_dim,
+                        int(code), float(scale))
+
+
+class Blocks:
+    """Owner of an ``ssa_blocks_t*``."""
+
+    def __init__(self, handle: int, params: ssa_params_t):
+        self.handle = handle
+        self.params = params
+
+    def counts(self) -> Tuple[int, int, int]:
+        a, b, c = C.c_int32(), C.c_int32(), C.c_int32()
+        _check(lib().ssa_blocks_counts(self.handle, C.byref(a), C.byref(b), C.byref(c)), "ssa_blocks_counts")
+        return a.value, b.value, c.value
+
+    def max_slc_per_item(self) -> int:
+        a = C.c_int32()
+        _check(lib().ssa_blocks_max_slc_per_item(self.handle, C.byref(a)), "ssa_blocks_max_slc_per_item")
+        return a.value
+
+    def export(self, name: str) -> torch.Tensor:
+        nc, ns, nw = self.counts()
+        p = self.params
+        n = dict(perm=p.n_tokens, inv_perm=p.n_tokens, cmp_start=nc + 1, slc_start=ns + 1, win_start=nw + 1,
+                 slc_child_start=ns + 1, cmp_batch=p.n_batch + 1, slc_batch=p.n_batch + 1, tok_win=p.n_tokens)[name]
+        dst = torch.empty(max(n, 1), dtype=torch.int32, device="cuda")
+        _check(lib().ssa_blocks_export(self.handle, ARRAYS[name], dst.data_ptr(), dst.numel() * 4, _stream()),
+               "ssa_blocks_export")
+        return dst[:n]
+
+    def destroy(self) -> None:
+        if self.handle:
+            lib().ssa_blocks_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def ssa_build_blocks(params: ssa_params_t, coords: torch.Tensor, batch_offsets: torch.Tensor) -> Blocks:
+    """coords: cuda int32 [N,3]; batch_offsets: cuda int32 [B+1]."""
+    assert coords.dtype == torch.int32 and batch_offsets.dtype == torch.int32
+    h = C.c_void_p()
+    _check(lib().ssa_build_blocks(C.byref(params), _ptr(coords), _ptr(batch_offsets), _stream(), C.byref(h)),
+           "ssa_build_blocks")
+    return Blocks(h.value, params)
+
+
+def ssa_workspace_bytes(params: ssa_params_t, blocks: Blocks, for_backward: bool) -> int:
+    return int(lib().ssa_workspace_bytes(C.byref(params), blocks.handle, int(for_backward)))
+
+
+def ssa_forward(params, blocks: Blocks, q, k, v, gates, out, lse=None, topk_idx=None, out_branch=None,
+                workspace: Optional[torch.Tensor] = None) -> None:
+    if workspace is None:
+        workspace = torch.empty(ssa_workspace_bytes(params, blocks, False), dtype=torch.uint8, device="cuda")
+    _check(lib().ssa_forward(C.byref(params), blocks.handle, _ptr(q), _ptr(k), _ptr(v), _ptr(gates), _ptr(out),
+                             _ptr(lse), _ptr(topk_idx), _ptr(out_branch), _ptr(workspace), workspace.numel(),
+                             _stream()), "ssa_forward")
+
+
+def ssa_backward(params, blocks: Blocks, q, k, v, gates, out_branch, lse, topk_idx, dout, dq, dk, dv, dgates,
+                 workspace: Optional[torch.Tensor] = None) -> None:
+    if workspace is None:
+        workspace = torch.empty(ssa_workspace_bytes(params, blocks, True), dtype=torch.uint8, device="cuda")
+    _check(lib().ssa_backward(C.byref(params), blocks.handle, _ptr(q), _ptr(k), _ptr(v), _ptr(gates),
+                              _ptr(out_branch), _ptr(lse), _ptr(topk_idx), _ptr(dout), _ptr(dq), _ptr(dk), _ptr(dv),
+                              _ptr(dgates), _ptr(workspace), workspace.numel(), _stream()), "ssa_backward")
+
+
+def ssa_topk_from_scores(params, blocks: Blocks, scores: torch.Tensor, topk_idx: torch.Tensor) -> None:
+    assert scores.dtype == torch.float32 and topk_idx.dtype == torch.int32
+    _check(lib().ssa_topk_from_scores(C.byref(params), blocks.handle, _ptr(scores), _ptr(topk_idx), _stream()),
+           "ssa_topk_from_scores")

@@ -1,0 +1,136 @@
+"""GPU: ssa_forward / ssa_backward / ssa_topk_from_scores against the fp64 oracle, element by element.
+
+Tolerances (relative to max|reference| of each tensor): bf16 2e-2 max / 1e-3 mean, fp32 1e-5 both.
+Selected sets: equal to the oracle's, except that blocks whose oracle score lies within a relative margin
+(2e-3 bf16, 1e-5 fp32) of the T-th best may swap; outputs are compared against the oracle run on the HIP
+path's own selected sets (the selection is an explicit input of Algorithm 1).
+"""
+import numpy as np
+import pytest
+
+from oracle.ssa_oracle import oracle_for
+from paper_2505_17412_amd import inputs
+from tests import util
+
+pytestmark = pytest.mark.gpu
+
+
+def full_parity(wl, backward=True, queries=None, tol_scale=1.0):
+    print("parity", wl.name, wl.n_tokens, wl.dtype, wl.n_heads_q, wl.n_heads_kv, wl.head_dim, flush=True)
+    orc = oracle_for(wl)
+    dout = wl.dout
+    if queries is not None:
+        dout = np.zeros_like(wl.dout)
+        dout[queries] = wl.dout[queries]
+    g = util.run_gpu(wl, backward=backward, dout=dout)
+    sel = slice(None) if queries is None else queries
+    ref_own = orc.forward(wl.q, wl.k, wl.v, wl.gates, queries=queries, want_scores=True)
+    ndiff = util.check_topk(g.topk_idx, ref_own, orc, wl.dtype, queries=queries)
+    ref = orc.forward(wl.q, wl.k, wl.v, wl.gates, queries=queries, topk_idx=g.topk_idx)
+    errs = {}
+    errs["out"] = util.assert_close(g.out[sel], ref.out[sel], wl.dtype, "out", tol_scale)
+    for b, nm in enumerate(("cmp", "slc", "win")):
+        errs["out_" + nm] = util.assert_close(g.out_branch[b][sel], ref.out_branch[b][sel], wl.dtype, "out_" + nm, tol_scale)
+        errs["lse_" + nm] = util.assert_close(g.lse[b][sel], ref.lse[b][sel], wl.dtype, "lse_" + nm, tol_scale)
+    if backward:
+        rb = orc.backward(wl.q, wl.k, wl.v, wl.gates, dout, g.topk_idx, out_branch=ref.out_branch, queries=queries)
+        errs["dq"] = util.assert_close(g.dq[sel], rb.dq[sel], wl.dtype, "dq", tol_scale)
+        errs["dk"] = util.assert_close(g.dk, rb.dk, wl.dtype, "dk", tol_scale)
+        errs["dv"] = util.assert_close(g.dv, rb.dv, wl.dtype, "dv", tol_scale)
+        errs["dgates"] = util.assert_close(g.dgates[sel], rb.dgates[sel], wl.dtype, "dgates", tol_scale)
+    print("  topk rows differing:", ndiff, " errors:", {k: f"{v[0]:.1e}/{v[1]:.1e}" for k, v in errs.items()}, flush=True)
+    return ndiff, errs
+
+
+def test_tiny_fp32_full():
+    """Config "tiny": 32^3 grid, three spheres, fp32, 4 heads (2 KV heads), d=32, T=4."""
+    ndiff, _ = full_parity(inputs.make_workload("tiny"))
+    assert ndiff == 0
+
+
+@pytest.mark.parametrize("hq,hkv", [(4, 4), (4, 1), (8, 2)])
+def test_tiny_fp32_head_groupings(hq, hkv):
+    wl = inputs.make_workload("tiny", hq=hq, hkv=hkv, seed=1011)
+    full_parity(wl, queries=np.arange(0, wl.n_tokens, 3, dtype=np.int32))
+
+
+@pytest.mark.parametrize("seed,grid,n,hq,hkv,d,m,topk,dtype", [
+    (11, 16, (300, 1, 170), 4, 2, 16, (2, 4, 4), 3, "f32"),
+    (12, 16, (257,), 8, 1, 64, (2, 4, 8), 40, "f32"),      # T larger than the block count: -1 padding
+    (13, 32, (700, 650), 16, 2, 64, (4, 8, 8), 4, "bf16"),
+    (14, 32, (900,), 16, 1, 64, (4, 8, 4), 6, "bf16"),
+    (15, 32, (640,), 16, 2, 128, (4, 8, 8), 5, "bf16"),
+    (16, 16, (500,), 4, 4, 32, (2, 4, 4), 3, "bf16"),
+    (17, 8, (400,), 4, 2, 24, (1, 2, 2), 2, "f32"),        # duplicates allowed below, odd head_dim
+])
+def test_random_points(seed, grid, n, hq, hkv, d, m, topk, dtype):
+    wl = inputs.random_points_workload(seed, grid, n, hq, hkv, d, m, topk, dtype, allow_duplicates=(seed == 17))
+    full_parity(wl)
+
+
+def test_topk_from_scores_is_bit_exact():
+    """The decision alone, on the oracle's fp32 scores plus planted ties, must match exactly."""
+    import torch
+    from paper_2505_17412_amd import ssa
+    wl = inputs.make_workload("tiny", topk=6)
+    orc = oracle_for(wl)
+    f = orc.forward(wl.q, wl.k, wl.v, wl.gates, want_scores=True)
+    sc = f.scores.copy()
+    sc[::3] = np.round(sc[::3] * 8) / 8            # many exact ties
+    sc[1::7, :, :5] = 0.0
+    rng = np.random.default_rng(0)
+    sc[2::11] = rng.standard_normal(sc[2::11].shape).astype(np.float32)  # negative scores are ordered too
+    expect = orc.topk_from_scores(sc)
+    p, blk = util.build_blocks_gpu(wl)
+    got = torch.full((wl.n_tokens, wl.n_heads_kv, wl.topk), -9, dtype=torch.int32, device="cuda")
+    ssa.ssa_topk_from_scores(p, blk, torch.from_numpy(sc).cuda(), got)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), expect)
+    # untouched scores reproduce the forward pass's own sets
+    ssa.ssa_topk_from_scores(p, blk, torch.from_numpy(f.scores).cuda(), got)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), f.topk_idx)
+
+
+def test_zero_queries_select_by_child_count():
+    """Q = 0 makes the compression softmax uniform: the selected set is the closed form of eq. (6)."""
+    wl = inputs.make_workload("tiny", topk=6)
+    wl.q[:] = 0
+    orc = oracle_for(wl)
+    g = util.run_gpu(wl, backward=False)
+    children = np.diff(orc.blocks.slc_child_start)
+    expect = np.array(sorted(sorted(range(len(children)), key=lambda j: (-int(children[j]), j))[:6]), dtype=np.int32)
+    assert np.all(g.topk_idx == expect[None, None, :])
+
+
+def test_validation_on_gpu():
+    import torch
+    from paper_2505_17412_amd import ssa
+    wl = inputs.random_points_workload(1, 8, (40,), 4, 2, 16, (2, 4, 4), 2)
+    p, blk = util.build_blocks_gpu(wl)
+    q, k, v, g = (util.to_dev(a, "f32") for a in (wl.q, wl.k, wl.v, wl.gates))
+    out = torch.zeros_like(q)
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(ssa.SSAError) as e:
+        ssa.ssa_forward(p, blk, q, k, v, g, out, workspace=small)
+    assert e.value.status == -7
+    p2 = util.params_of(wl)
+    p2.n_tokens = 39
+    with pytest.raises(ssa.SSAError) as e:
+        ssa.ssa_forward(p2, blk, q, k, v, g, out)
+    assert e.value.status == -10
+    p3 = util.params_of(wl)
+    p3.n_heads_kv = 3
+    with pytest.raises(ssa.SSAError) as e:
+        ssa.ssa_forward(p3, blk, q, k, v, g, out)
+    assert e.value.status == -4
+    p4 = util.params_of(wl)
+    p4.head_dim = 20
+    with pytest.raises(ssa.SSAError) as e:
+        ssa.ssa_forward(p4, blk, q, k, v, g, out)
+    assert e.value.status == -8
+    assert torch.all(out == 0)  # nothing was written
+    ssa.ssa_forward(p, blk, q, k, v, g, out)  # inference call: optional outputs omitted
+    torch.cuda.synchronize()
+    ref = oracle_for(wl).forward(wl.q, wl.k, wl.v, wl.gates)
+    util.assert_close(util.to_np(out), ref.out, "f32", "out")
