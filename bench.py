@@ -1,0 +1,169 @@
+"""SSA forward+backward throughput on one MI355X (config: ~60k-token shell on a 128^3 grid).
+
+Prints ONE JSON line: whole-step tokens/s, the roofline position of the dominant kernel (live HIP-event timing
+through the library's profiling hook) and the fp64 CPU oracle timed on a bounded query sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_flops(wl, blk_arrays, idx):
+    """Pair counts from the run's real block structure and selected sets (never dense N^2)."""
+    import numpy as np
+    d, hq, hkv = wl.head_dim, wl.n_heads_q, wl.n_heads_kv
+    hs = hq // hkv
+    perm, tok_win, win_start = blk_arrays["perm"], blk_arrays["tok_win"], blk_arrays["win_start"]
+    cmp_batch, slc_start = blk_arrays["cmp_batch"], blk_arrays["slc_start"]
+    n_item = np.diff(wl.batch_offsets.astype(np.int64))
+    pairs_cmp = int(np.sum(n_item * np.diff(cmp_batch.astype(np.int64)))) * hq
+    win_len = np.diff(win_start.astype(np.int64))
+    pairs_win = int(np.sum(win_len[tok_win])) * hq
+    blk_len = np.concatenate([np.diff(slc_start.astype(np.int64)), [0]])  # index -1 -> 0
+    pairs_slc = int(np.sum(blk_len[idx])) * hs
+    return dict(cmp=pairs_cmp, slc=pairs_slc, win=pairs_win, d=d)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="g128")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline leg")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding or collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2505_17412_amd import inputs, ssa
+    from tests import util
+
+    wl = inputs.make_workload(args.workload)
+    n, hq, hkv, d, T = wl.n_tokens, wl.n_heads_q, wl.n_heads_kv, wl.head_dim, wl.topk
+    torch.cuda.set_device(0)
+    p, blk = util.build_blocks_gpu(wl)
+    t0 = time.perf_counter()
+    for _ in range(3):
+        util.build_blocks_gpu(wl)[1].destroy()
+    torch.cuda.synchronize()
+    build_ms = (time.perf_counter() - t0) / 3 * 1e3
+
+    q, k, v, g, do = (util.to_dev(a, wl.dtype) for a in (wl.q, wl.k, wl.v, wl.gates, wl.dout))
+    out = torch.empty_like(q)
+    ob = torch.empty((3,) + tuple(q.shape), dtype=q.dtype, device="cuda")
+    lse = torch.empty((3, n, hq), dtype=torch.float32, device="cuda")
+    idx = torch.empty((n, hkv, T), dtype=torch.int32, device="cuda")
+    dq, dk, dv, dg = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v), torch.empty_like(g)
+    wsf = torch.empty(ssa.ssa_workspace_bytes(p, blk, False), dtype=torch.uint8, device="cuda")
+    wsb = torch.empty(ssa.ssa_workspace_bytes(p, blk, True), dtype=torch.uint8, device="cuda")
+
+    def step():
+        ssa.ssa_forward(p, blk, q, k, v, g, out, lse, idx, ob, wsf)
+        ssa.ssa_backward(p, blk, q, k, v, g, ob, lse, idx, do, dq, dk, dv, dg, wsb)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+
+    # forward / backward split (separate loops, HIP events on the launch stream)
+    def timed(fn, reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    reps = max(3, args.steps // 2)
+    fwd_ms = timed(lambda: ssa.ssa_forward(p, blk, q, k, v, g, out, lse, idx, ob, wsf), reps)
+    bwd_ms = timed(lambda: ssa.ssa_backward(p, blk, q, k, v, g, ob, lse, idx, do, dq, dk, dv, dg, wsb), reps)
+
+    # per-kernel durations over the same steps, HIP events recorded by the library on the launch stream
+    ssa.ssa_profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = ssa.ssa_profile_get()
+    ssa.ssa_profile_enable(False)
+    kern_ms = {nm: tot / cnt for nm, (tot, cnt) in prof.items()}
+
+    arrays = {nm: blk.export(nm).cpu().numpy() for nm in ("perm", "tok_win", "win_start", "cmp_batch", "slc_start")}
+    pairs = algorithmic_flops(wl, arrays, idx.cpu().numpy())
+    all_pairs = pairs["cmp"] + pairs["slc"] + pairs["win"]
+    # algorithmic FLOPs per kernel: forward 2 contractions (4d per pair); backward 5 (10d): S, dP, dQ booked on the
+    # dQ kernel (6d), dV, dK on the dK/dV kernels (4d)
+    kflops = {
+        "cmp_fwd_scores_topk": 4 * d * pairs["cmp"], "slc_fwd": 4 * d * pairs["slc"], "win_fwd": 4 * d * pairs["win"],
+        "bwd_dq": 6 * d * all_pairs, "bwd_dkv_cmp": 4 * d * pairs["cmp"], "bwd_dkv_slc": 4 * d * pairs["slc"],
+        "bwd_dkv_win": 4 * d * pairs["win"], "generic_path": 10 * d * all_pairs,
+    }
+    dom = max(kern_ms, key=kern_ms.get) if kern_ms else None
+    roofline = None
+    if dom is not None and dom in kflops:
+        ach = kflops[dom] / (kern_ms[dom] * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": dom, "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                    "kernel_ms": round(kern_ms[dom], 4)}
+    total_flops = 14 * d * all_pairs
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import ssa_oracle
+        from oracle.ssa_oracle import oracle_for
+        orc = oracle_for(wl)
+        I = idx.cpu().numpy()
+
+        def oracle_step(sub):
+            f = orc.forward(wl.q, wl.k, wl.v, wl.gates, queries=sub)
+            orc.backward(wl.q, wl.k, wl.v, wl.gates, wl.dout, f.topk_idx, out_branch=f.out_branch, queries=sub)
+
+        probe = np.arange(0, n, max(1, n // 64), dtype=np.int32)[:64]
+        t0 = time.perf_counter()
+        oracle_step(probe)
+        per_q = (time.perf_counter() - t0) / len(probe)
+        ns = int(min(n, max(64, args.cpu_seconds / max(per_q, 1e-9))))
+        sub = np.arange(0, n, max(1, n // ns), dtype=np.int32)[:ns]
+        t0 = time.perf_counter()
+        oracle_step(sub)
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(len(sub) / dt, 2), "unit": "tokens/s", "cores": ssa_oracle.n_threads(), "kind": "oracle",
+               "sample": f"fwd+bwd of {len(sub)} evenly spaced query tokens of the same {n}-token workload, {dt:.1f} s wall",
+               "seconds": round(dt, 2)}
+
+    line = {
+        "metric": "SSA fwd+bwd tokens/sec", "value": round(n / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: union-of-primitives shell on a {wl.grid}^3 grid, N={n} tokens, Hq={hq}, "
+                               f"Hkv={hkv}, d={d}, m_cmp/m_slc/m_win={wl.m_cmp}/{wl.m_slc}/{wl.m_win}, top-k={T}, fwd+bwd",
+                   "n_tokens": n, "blocks_cmp_slc_win": list(blk.counts())},
+        "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4), "build_blocks_ms": round(build_ms, 3),
+        "algorithmic_tflop_per_step": round(total_flops / 1e12, 4),
+        "mfma_frac_whole_step": round(total_flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+        "kernel_ms": {k_: round(v_, 4) for k_, v_ in kern_ms.items()},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

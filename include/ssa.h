@@ -148,6 +148,17 @@ int ssa_backward(const ssa_params_t *params, const ssa_blocks_t *blocks, const v
 int ssa_topk_from_scores(const ssa_params_t *params, const ssa_blocks_t *blocks, const float *scores,
                          int32_t *topk_idx, void *stream);
 
+/*
+ * Measurement hook (not an operation of the paper; for benchmarks that need the duration of single kernels).
+ * While enabled, every kernel the library launches is bracketed by a HIP event pair recorded on the launch
+ * stream.  ssa_profile_enable(on) clears the totals; ssa_profile_get(i, ...) waits for the recorded events and
+ * returns kernel i's name (static string), total milliseconds and number of launches since the last enable.
+ * Not thread-safe.
+ */
+int ssa_profile_enable(int on);
+int ssa_profile_num_kernels(void);
+int ssa_profile_get(int i, const char **name, double *total_ms, int64_t *launches);
+
 /* Static description of a status code. */
 const char *ssa_error_string(int status);
 

@@ -212,13 +212,14 @@ extern "C" int ssa_build_blocks(const ssa_params_t *p, const int32_t *coords, co
   h->N = N; h->B = B; h->G = p->grid; h->m_cmp = p->m_cmp; h->m_slc = p->m_slc; h->m_win = p->m_win; h->bits = bits;
   if (hipGetDevice(&h->device) != hipSuccess) { delete h; return SSA_ERR_HIP; }
   const size_t n1 = (size_t)N + 1;
-  const size_t ints = 6 * (size_t)N + 4 * n1 + (size_t)N + 2 * ((size_t)B + 1) + 64;
+  const size_t ints = 6 * (size_t)N + 4 * n1 + (size_t)N + 3 * ((size_t)B + 1) + 64;
   if (hipMalloc(&h->base, ints * sizeof(int32_t)) != hipSuccess) { delete h; return SSA_ERR_HIP; }
   int32_t *w = (int32_t *)h->base;
   auto take = [&](size_t n) { int32_t *r = w; w += n; return r; };
   h->perm = take(N); h->inv_perm = take(N); h->tok_item = take(N); h->tok_cmp = take(N); h->tok_slc = take(N);
   h->tok_win = take(N); h->cmp_start = take(n1); h->slc_start = take(n1); h->win_start = take(n1);
   h->slc_child_start = take(n1); h->cmp_slc = take(N); h->cmp_batch = take(B + 1); h->slc_batch = take(B + 1);
+  h->item_start = take(B + 1);
 
   int32_t meta_h[META_N] = {0};
   const int nTiles = (N + SORT_TILE - 1) / SORT_TILE;
@@ -262,6 +263,9 @@ extern "C" int ssa_build_blocks(const ssa_params_t *p, const int32_t *coords, co
     if (hipMemsetAsync(h->base, 0, ints * sizeof(int32_t), stream) != hipSuccess) return fail(SSA_ERR_HIP);
     k_make_keys<<<1, 256, 0, stream>>>(coords, batch_offsets, 0, B, p->grid, bits, k0, v0, meta);
   }
+  if (hipMemcpyAsync(h->item_start, batch_offsets, ((size_t)B + 1) * sizeof(int32_t), hipMemcpyDeviceToDevice, stream) !=
+      hipSuccess)
+    return fail(SSA_ERR_HIP);
   if (hipGetLastError() != hipSuccess) return fail(SSA_ERR_HIP);
   if (hipMemcpyAsync(meta_h, meta, sizeof(meta_h), hipMemcpyDeviceToHost, stream) != hipSuccess) return fail(SSA_ERR_HIP);
   if (hipStreamSynchronize(stream) != hipSuccess) return fail(SSA_ERR_HIP);

@@ -1,0 +1,62 @@
+// Shared pieces of the bf16 MFMA kernels (gfx950, wave64, v_mfma_f32_16x16x32_bf16).
+//
+// Operand convention used throughout (hardware layout of the 16x16x32 instruction):
+//   A (16 x 32): lane l supplies row (l & 15), contraction indices 8*(l >> 4) .. +7   (8 bf16 = 16 bytes)
+//   B (32 x 16): lane l supplies column (l & 15), contraction indices 8*(l >> 4) .. +7
+//   C/D (16 x 16 fp32): lane l holds column (l & 15), rows 4*(l >> 4) .. +3
+// "quad" below is l >> 4, "n" is l & 15.
+//
+// Key-tile convention: a tile covers 32 consecutive rows kb..kb+31 of a key array, kb a multiple of 8.  It is
+// processed as two 16-row sub-tiles whose row r maps to key kb + 8*(r >> 2) + 4*a + (r & 3) (a = sub-tile), so
+// that after the two MFMAs lane l holds the eight CONSECUTIVE keys kb + 8*quad .. +7 of column n -- exactly
+// the contraction slice the next MFMA wants from it as a B operand, with no cross-lane movement.
+#pragma once
+
+#include "ssa_internal.h"
+
+typedef uint16_t bf16_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+__device__ inline bf16x8 ld8(const bf16_t *p) { return *reinterpret_cast<const bf16x8 *>(p); }
+__device__ inline bf16x8 zero8() {
+  bf16x8 z;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) z[i] = (__bf16)0.0f;
+  return z;
+}
+__device__ inline f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ inline int wave_min_i(int v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v = min(v, __shfl_xor(v, off));
+  return v;
+}
+__device__ inline int wave_max_i(int v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v = max(v, __shfl_xor(v, off));
+  return v;
+}
+
+// Row of the A operand a lane feeds for sub-tile `a` of the key tile starting at kb.
+__device__ inline int tile_key_row(int kb, int a) {
+  const int r = threadIdx.x & 15;
+  return kb + 8 * (r >> 2) + 4 * a + (r & 3);
+}
+
+// Device arrays of the block structure and the sorted / transposed K,V copies the kernels read.
+struct MfmaView {
+  const int32_t *perm, *tok_item, *tok_cmp, *tok_win, *cmp_start, *slc_start, *win_start, *slc_child_start, *cmp_slc,
+      *cmp_batch, *slc_batch, *item_start;
+  int N, Nc, Ns, Hq, Hkv, hs, T, s_max;
+  float scale, sl2;  // softmax scale, scale * log2(e)
+  // sorted copies (bf16): row-major [rows][Hkv][D] and chunk-transposed [rows/8][Hkv][D][8]
+  const bf16_t *Ks, *Vs, *Kt, *Vt, *Kc, *Vc, *Kct, *Vct;
+};

@@ -1,9 +1,127 @@
-// bf16 MFMA path (placeholder until the kernels land): reports "unsupported" so every problem takes the generic path.
-#include "ssa_internal.h"
-bool mfma_supported(const ssa_ctx &) { return false; }
-size_t mfma_forward_workspace(const ssa_ctx &) { return 0; }
-size_t mfma_backward_workspace(const ssa_ctx &) { return 0; }
-int mfma_forward(const ssa_ctx &, const void *, const void *, const void *, const void *, void *, float *, int32_t *, void *,
-                 void *, size_t) { return SSA_ERR_UNSUPPORTED; }
-int mfma_backward(const ssa_ctx &, const void *, const void *, const void *, const void *, const void *, const float *,
-                  const int32_t *, const void *, void *, void *, void *, void *, void *, size_t) { return SSA_ERR_UNSUPPORTED; }
+// bf16 MFMA path: workspace layout, K/V preparation (sort, transpose, mean pool) and launch sequence.
+#include "mfma_common.h"
+#include "mfma_launch.h"
+#include "profile.h"
+
+namespace {
+
+struct Tail { bf16_t *p; size_t begin, end; };  // element range to clear
+struct Tails { Tail t[8]; };
+
+__global__ void m_zero_tails(Tails ts) {
+  const Tail t = ts.t[blockIdx.y];
+  if (!t.p) return;
+  for (size_t i = t.begin + (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < t.end; i += (size_t)gridDim.x * blockDim.x)
+    t.p[i] = 0;
+}
+
+struct PrepOut { bf16_t *Ks, *Vs, *Kt, *Vt, *Kc, *Vc, *Kct, *Vct; };
+
+// One workgroup per compression block: gathers its tokens' K,V rows into sorted order (row-major copy and the
+// 8-token chunk-transposed copy) and writes the block mean (eq. (5), mean pool over the active tokens).
+// Any output pointer may be NULL.
+__global__ void m_prep(const bf16_t *__restrict__ K, const bf16_t *__restrict__ V, const int32_t *__restrict__ perm,
+                       const int32_t *__restrict__ cmp_start, int Hkv, int D, PrepOut o) {
+  const int c = blockIdx.x, row = Hkv * D;
+  const int b = cmp_start[c], e = cmp_start[c + 1];
+  const float inv = 1.0f / (float)(e - b);
+  for (int f = threadIdx.x; f < row; f += blockDim.x) {
+    const int g = f / D, dim = f % D;
+    float sk = 0.f, sv = 0.f;
+    for (int pos = b; pos < e; ++pos) {
+      const size_t src = (size_t)perm[pos] * row + f;
+      const bf16_t kk = K[src], vv = V[src];
+      const size_t tr = (((size_t)(pos >> 3) * Hkv + g) * D + dim) * 8 + (pos & 7);
+      if (o.Ks) o.Ks[(size_t)pos * row + f] = kk;
+      if (o.Vs) o.Vs[(size_t)pos * row + f] = vv;
+      if (o.Kt) o.Kt[tr] = kk;
+      if (o.Vt) o.Vt[tr] = vv;
+      sk += bf16_to_f32(kk);
+      sv += bf16_to_f32(vv);
+    }
+    const bf16_t kc = f32_to_bf16(sk * inv), vc = f32_to_bf16(sv * inv);
+    const size_t tr = (((size_t)(c >> 3) * Hkv + g) * D + dim) * 8 + (c & 7);
+    if (o.Kc) o.Kc[(size_t)c * row + f] = kc;
+    if (o.Vc) o.Vc[(size_t)c * row + f] = vc;
+    if (o.Kct) o.Kct[tr] = kc;
+    if (o.Vct) o.Vct[tr] = vc;
+  }
+}
+
+size_t padded_rows(int n) { return align_up((size_t)n, 8) + SSA_KEY_PAD; }
+
+struct FwdPlan { size_t ks, vt, kc, vct, ob, lse, idx, total; };
+
+FwdPlan fwd_plan(const ssa_ctx &c) {
+  FwdPlan p{};
+  const size_t row = (size_t)c.Hkv * c.d * 2;
+  size_t off = 0;
+  auto take = [&](size_t n) { size_t r = off; off += align_up(n, 256); return r; };
+  p.ks = take(padded_rows(c.N) * row); p.vt = take(padded_rows(c.N) * row);
+  p.kc = take(padded_rows(c.blk->Nc) * row); p.vct = take(padded_rows(c.blk->Nc) * row);
+  p.ob = take((size_t)3 * c.N * c.Hq * c.d * 2);
+  p.lse = take((size_t)3 * c.N * c.Hq * 4);
+  p.idx = take((size_t)c.N * c.Hkv * c.T * 4);
+  p.total = off;
+  return p;
+}
+
+MfmaView make_view(const ssa_ctx &c) {
+  const ssa_blocks *b = c.blk;
+  MfmaView v{};
+  v.perm = b->perm; v.tok_item = b->tok_item; v.tok_cmp = b->tok_cmp; v.tok_win = b->tok_win;
+  v.cmp_start = b->cmp_start; v.slc_start = b->slc_start; v.win_start = b->win_start;
+  v.slc_child_start = b->slc_child_start; v.cmp_slc = b->cmp_slc; v.cmp_batch = b->cmp_batch;
+  v.slc_batch = b->slc_batch; v.item_start = b->item_start;
+  v.N = c.N; v.Nc = b->Nc; v.Ns = b->Ns; v.Hq = c.Hq; v.Hkv = c.Hkv; v.hs = c.hs; v.T = c.T; v.s_max = b->s_max;
+  v.scale = c.scale; v.sl2 = c.scale * LOG2E;
+  return v;
+}
+
+int run_prep(const ssa_ctx &c, const void *k, const void *v, const PrepOut &o) {
+  ProfScope ps(PROF_PREP, c.stream);
+  const size_t row = (size_t)c.Hkv * c.d;
+  const size_t nt = padded_rows(c.N) * row, nc = padded_rows(c.blk->Nc) * row;
+  const size_t t0 = (size_t)(c.N / 8) * 8 * row, c0 = (size_t)(c.blk->Nc / 8) * 8 * row;
+  Tails ts{{{o.Ks, t0, nt}, {o.Vs, t0, nt}, {o.Kt, t0, nt}, {o.Vt, t0, nt},
+            {o.Kc, c0, nc}, {o.Vc, c0, nc}, {o.Kct, c0, nc}, {o.Vct, c0, nc}}};
+  m_zero_tails<<<dim3(8, 8), 256, 0, c.stream>>>(ts);
+  m_prep<<<c.blk->Nc, 128, 0, c.stream>>>((const bf16_t *)k, (const bf16_t *)v, c.blk->perm, c.blk->cmp_start, c.Hkv, c.d, o);
+  return hipGetLastError() == hipSuccess ? SSA_OK : SSA_ERR_HIP;
+}
+
+}  // namespace
+
+bool mfma_supported(const ssa_ctx &c) {
+  if (c.dtype != SSA_BF16) return false;
+  if (c.d != 32 && c.d != 64 && c.d != 128) return false;
+  if (c.hs != 1 && c.hs != 2 && c.hs != 4 && c.hs != 8 && c.hs != 16) return false;
+  if (mfma_cmp_lds_bytes(c.hs, c.blk->s_max) > 64 * 1024) return false;
+  return true;
+}
+
+size_t mfma_forward_workspace(const ssa_ctx &c) { return fwd_plan(c).total; }
+size_t mfma_backward_workspace(const ssa_ctx &c) { return generic_backward_workspace(c); }
+
+int mfma_forward(const ssa_ctx &c, const void *q, const void *k, const void *v, const void *gates, void *out,
+                 float *lse, int32_t *topk_idx, void *out_branch, void *ws_, size_t ws_bytes) {
+  const FwdPlan p = fwd_plan(c);
+  if (ws_bytes < p.total) return SSA_ERR_WORKSPACE;
+  char *ws = (char *)ws_;
+  PrepOut o{};
+  o.Ks = (bf16_t *)(ws + p.ks); o.Vt = (bf16_t *)(ws + p.vt); o.Kc = (bf16_t *)(ws + p.kc); o.Vct = (bf16_t *)(ws + p.vct);
+  int rc = run_prep(c, k, v, o);
+  if (rc != SSA_OK) return rc;
+  MfmaView view = make_view(c);
+  view.Ks = o.Ks; view.Vt = o.Vt; view.Kc = o.Kc; view.Vct = o.Vct;
+  return mfma_forward_kernels(view, c.d, q, gates, out, lse ? lse : (float *)(ws + p.lse),
+                              topk_idx ? topk_idx : (int32_t *)(ws + p.idx), out_branch ? out_branch : (void *)(ws + p.ob),
+                              c.stream);
+}
+
+int mfma_backward(const ssa_ctx &c, const void *q, const void *k, const void *v, const void *gates,
+                  const void *out_branch, const float *lse, const int32_t *topk_idx, const void *dout, void *dq,
+                  void *dk, void *dv, void *dgates, void *ws, size_t ws_bytes) {
+  ProfScope ps(PROF_GENERIC, c.stream);
+  return generic_backward(c, q, k, v, gates, out_branch, lse, topk_idx, dout, dq, dk, dv, dgates, ws, ws_bytes);
+}

@@ -29,6 +29,7 @@ struct ssa_blocks {
   void *base;  // single device allocation holding every array below
   int32_t *perm, *inv_perm, *tok_item, *tok_cmp, *tok_slc, *tok_win;
   int32_t *cmp_start, *slc_start, *win_start, *slc_child_start, *cmp_slc, *cmp_batch, *slc_batch;
+  int32_t *item_start;  // [B+1] sorted-position range of each batch item (a copy of the batch offsets)
 };
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

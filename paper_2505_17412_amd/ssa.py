@@ -20,7 +20,7 @@ ARRAYS = dict(perm=0, inv_perm=1, cmp_start=2, slc_start=3, win_start=4, slc_chi
 EXPORTED_SYMBOLS = (
     "ssa_build_blocks", "ssa_blocks_counts", "ssa_blocks_max_slc_per_item", "ssa_blocks_export",
     "ssa_blocks_destroy", "ssa_workspace_bytes", "ssa_forward", "ssa_backward", "ssa_topk_from_scores",
-    "ssa_error_string",
+    "ssa_error_string", "ssa_profile_enable", "ssa_profile_num_kernels", "ssa_profile_get",
 )
 
 
@@ -56,6 +56,8 @@ def lib() -> C.CDLL:
         L.ssa_forward.argtypes = [C.POINTER(ssa_params_t), vp] + [vp] * 8 + [vp, C.c_size_t, vp]
         L.ssa_backward.argtypes = [C.POINTER(ssa_params_t), vp] + [vp] * 12 + [vp, C.c_size_t, vp]
         L.ssa_topk_from_scores.argtypes = [C.POINTER(ssa_params_t), vp, vp, vp, vp]
+        L.ssa_profile_enable.argtypes = [C.c_int]
+        L.ssa_profile_get.argtypes = [C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         L.ssa_error_string.argtypes = [C.c_int]
         L.ssa_error_string.restype = C.c_char_p
         _lib = L
@@ -163,3 +165,18 @@ def ssa_topk_from_scores(params, blocks: Blocks, scores: torch.Tensor, topk_idx:
     assert scores.dtype == torch.float32 and topk_idx.dtype == torch.int32
     _check(lib().ssa_topk_from_scores(C.byref(params), blocks.handle, _ptr(scores), _ptr(topk_idx), _stream()),
            "ssa_topk_from_scores")
+
+
+def ssa_profile_enable(on: bool) -> None:
+    _check(lib().ssa_profile_enable(int(on)), "ssa_profile_enable")
+
+
+def ssa_profile_get() -> dict:
+    """{kernel name: (total_ms, launches)} since the last ssa_profile_enable."""
+    res = {}
+    for i in range(lib().ssa_profile_num_kernels()):
+        name, ms, cnt = C.c_char_p(), C.c_double(), C.c_int64()
+        _check(lib().ssa_profile_get(i, C.byref(name), C.byref(ms), C.byref(cnt)), "ssa_profile_get")
+        if cnt.value:
+            res[name.value.decode()] = (ms.value, cnt.value)
+    return res

@@ -134,3 +134,9 @@ def test_validation_on_gpu():
     torch.cuda.synchronize()
     ref = oracle_for(wl).forward(wl.q, wl.k, wl.v, wl.gates)
     util.assert_close(util.to_np(out), ref.out, "f32", "out")
+
+
+def test_g64_bf16_forward_sampled():
+    """Config "g64": 64^3 grid, ~11k tokens, bf16, 16 heads (2 KV heads), d=64, T=8, forward; every 8th query."""
+    wl = inputs.make_workload("g64")
+    full_parity(wl, backward=False, queries=np.arange(0, wl.n_tokens, 8, dtype=np.int32))
