@@ -1,0 +1,553 @@
+// bf16 MFMA backward kernels of SSA for gfx950.
+//
+// The paper states no backward pass; this is the softmax-attention gradient of eq. (2)-(4) with the selected
+// index sets held constant, plus the gradient of the mean pool of eq. (5).  Per (query row, key) pair of a
+// branch b with gate w_b:  P = exp(S - lse_b),  dP = <dO, V>,  dS = P (w_b dP - delta_b) scale,
+// delta_b = w_b <dO, O_b>;  dV += w_b P dO,  dQ += dS K,  dK += dS Q.
+//
+// Two kernel families, both free of floating-point atomics (results do not depend on scheduling):
+//   * m_bwd_dq: query-centric, same walk as the forward kernels (transposed scores, keys in the lanes);
+//   * m_bwd_dkv: key-centric; a wavefront owns 16*KB keys and streams the query rows that attend to them
+//     (scores with the query rows in the lanes), reading Q and dO also from per-token transposed copies so
+//     that the contractions over query rows get 16-byte operands.
+#include "mfma_common.h"
+#include "mfma_launch.h"
+#include "profile.h"
+
+namespace {
+
+__device__ inline float wave_sum_f(float v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+  return v;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Pre-pass: dgates, per-row scalars in sorted order, per-token transposed copies of Q and dO.
+// One workgroup per sorted token position.
+// ---------------------------------------------------------------------------------------------------------
+struct PreArgs {
+  const bf16_t *Q, *dO, *Ob, *gates;
+  const float *lse;
+  const int32_t *perm;
+  int N, Hq, Hkv, hs, D;
+  bf16_t *dgates;               // [N,Hq,3] caller order
+  float *lse2s, *deltas, *gws;  // [3][N(pos)][Hq]
+  bf16_t *QT, *dOT;             // [N(pos)][Hkv][D][hs]
+};
+
+__global__ __launch_bounds__(256) void m_bwd_pre(PreArgs a) {
+  extern __shared__ bf16_t tile[];  // [2][Hq*D]
+  const int pos = blockIdx.x, tok = a.perm[pos];
+  const int HD = a.Hq * a.D;
+  const size_t base = (size_t)tok * HD;
+  bf16_t *tq = tile, *td = tile + HD;
+  for (int e = threadIdx.x * 8; e < HD; e += blockDim.x * 8) {
+    *reinterpret_cast<bf16x8 *>(tq + e) = ld8(a.Q + base + e);
+    *reinterpret_cast<bf16x8 *>(td + e) = ld8(a.dO + base + e);
+  }
+  __syncthreads();
+  // transposed copies: out[(g*D + dim)*hs + hl] = in[(g*hs + hl)*D + dim]
+  for (int o = threadIdx.x; o < HD; o += blockDim.x) {
+    const int hl = o % a.hs, gd = o / a.hs, dim = gd % a.D, g = gd / a.D;
+    const int e = (g * a.hs + hl) * a.D + dim;
+    a.QT[(size_t)pos * HD + o] = tq[e];
+    a.dOT[(size_t)pos * HD + o] = td[e];
+  }
+  // dgates and the row scalars: one wavefront per head, lanes over the head dimension
+  const int wid = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  for (int h = wid; h < a.Hq; h += 4) {
+    float acc[3] = {0.f, 0.f, 0.f};
+    for (int i = lane; i < a.D; i += 64) {
+      const float go = bf16_to_f32(td[h * a.D + i]);
+#pragma unroll
+      for (int b = 0; b < 3; ++b)
+        acc[b] += go * bf16_to_f32(a.Ob[(((size_t)b * a.N + tok) * a.Hq + h) * a.D + i]);
+    }
+#pragma unroll
+    for (int b = 0; b < 3; ++b) acc[b] = wave_sum_f(acc[b]);
+    if (lane < 3) {
+      const int b = lane;
+      const float dot = b == 0 ? acc[0] : (b == 1 ? acc[1] : acc[2]);
+      const size_t th = (size_t)tok * a.Hq + h;
+      const float w = bf16_to_f32(a.gates[th * 3 + b]);
+      a.dgates[th * 3 + b] = f32_to_bf16(dot);
+      const size_t s = ((size_t)b * a.N + pos) * a.Hq + h;
+      a.lse2s[s] = a.lse[((size_t)b * a.N + tok) * a.Hq + h] * LOG2E;
+      a.deltas[s] = w * dot;
+      a.gws[s] = w;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// dQ: query-centric
+// ---------------------------------------------------------------------------------------------------------
+struct DqArgs {
+  MfmaView v;
+  const bf16_t *Q, *dO;
+  const int32_t *idx;
+  const float *lse2s, *deltas, *gws;  // [3][N(pos)][Hq]
+  bf16_t *dQ;
+};
+
+template <int D>
+struct DqState {
+  f32x4 acc[D / 16];  // dQ^T: dim 16*dt + 4*quad + i of query column n
+};
+
+// One 32-key tile: transposed scores and dP, then dQ^T += K^T dS^T.
+template <int D, bool MASK>
+__device__ inline void dq_tile(DqState<D> &st, const bf16x8 (&qop)[D / 32], const bf16x8 (&dop)[D / 32],
+                               const bf16_t *__restrict__ Kg, const bf16_t *__restrict__ Vg, size_t kstride,
+                               const bf16_t *__restrict__ Ktg, size_t kchunk, int kb, int lo, int hi, float sl2,
+                               float scale, float lse2, float delta, float gw) {
+  const int n = threadIdx.x & 15, quad = threadIdx.x >> 4 & 3;
+  const size_t r0 = (size_t)tile_key_row(kb, 0) * kstride + 8 * quad, r1 = r0 + 4 * kstride;
+  f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0, p0 = s0, p1 = s0;
+#pragma unroll
+  for (int ks = 0; ks < D / 32; ++ks) {
+    s0 = mfma16(ld8(Kg + r0 + 32 * ks), qop[ks], s0);
+    s1 = mfma16(ld8(Kg + r1 + 32 * ks), qop[ks], s1);
+    p0 = mfma16(ld8(Vg + r0 + 32 * ks), dop[ks], p0);
+    p1 = mfma16(ld8(Vg + r1 + 32 * ks), dop[ks], p1);
+  }
+  bf16x8 dsb;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const float s = (j < 4 ? s0[j & 3] : s1[j & 3]) * sl2;
+    const float dp = j < 4 ? p0[j & 3] : p1[j & 3];
+    float p = fast_exp2(s - lse2);
+    if (MASK) {
+      const int key = kb + 8 * quad + j;
+      if (key < lo || key >= hi) p = 0.f;
+    }
+    dsb[j] = (__bf16)(p * (gw * dp - delta) * scale);
+  }
+  const bf16_t *kt = Ktg + (size_t)((kb >> 3) + quad) * kchunk + (size_t)n * 8;
+#pragma unroll
+  for (int dt = 0; dt < D / 16; ++dt) st.acc[dt] = mfma16(ld8(kt + dt * 128), dsb, st.acc[dt]);
+}
+
+template <int D>
+__device__ inline void dq_range(DqState<D> &st, const bf16x8 (&qop)[D / 32], const bf16x8 (&dop)[D / 32],
+                                const bf16_t *Kg, const bf16_t *Vg, size_t kstride, const bf16_t *Ktg, size_t kchunk,
+                                int wlo, int whi, int lo, int hi, bool uniform, float sl2, float scale, float lse2,
+                                float delta, float gw) {
+  for (int kb = wlo & ~7; kb < whi; kb += 32) {
+    if (uniform && kb >= wlo && kb + 32 <= whi)
+      dq_tile<D, false>(st, qop, dop, Kg, Vg, kstride, Ktg, kchunk, kb, lo, hi, sl2, scale, lse2, delta, gw);
+    else
+      dq_tile<D, true>(st, qop, dop, Kg, Vg, kstride, Ktg, kchunk, kb, lo, hi, sl2, scale, lse2, delta, gw);
+  }
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void m_bwd_dq(DqArgs a) {
+  const int wid = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 15, quad = lane >> 4;
+  const int hs = a.v.hs, tpw = 16 / hs, g = blockIdx.y, T = a.v.T, N = a.v.N;
+  const int pos0 = (blockIdx.x * 4 + wid) * tpw;
+  if (pos0 >= N) return;
+  const int pos = pos0 + n / hs;
+  const bool valid = pos < N;
+  const int tok = valid ? a.v.perm[pos] : 0;
+  const int h = g * hs + n % hs;
+  bf16x8 qop[D / 32], dop[D / 32];
+  {
+    const size_t off = ((size_t)tok * a.v.Hq + h) * D + 8 * quad;
+#pragma unroll
+    for (int ks = 0; ks < D / 32; ++ks) {
+      qop[ks] = valid ? ld8(a.Q + off + 32 * ks) : zero8();
+      dop[ks] = valid ? ld8(a.dO + off + 32 * ks) : zero8();
+    }
+  }
+  const size_t kstride = (size_t)a.v.Hkv * D, kchunk = kstride * 8;
+  const size_t NH = (size_t)N * a.v.Hq, rs = (size_t)(valid ? pos : 0) * a.v.Hq + h;
+  DqState<D> st;
+#pragma unroll
+  for (int dt = 0; dt < D / 16; ++dt) st.acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const float sl2 = a.v.sl2, scale = a.v.scale;
+  // compression branch
+  {
+    const int item = valid ? a.v.tok_item[pos] : 0;
+    const int lo = valid ? a.v.cmp_batch[item] : 0, hi = valid ? a.v.cmp_batch[item + 1] : 0;
+    const int wlo = wave_min_i(valid ? lo : 0x7fffffff), whi = wave_max_i(hi);
+    const bool uniform = __all(valid && lo == wlo && hi == whi);
+    dq_range<D>(st, qop, dop, a.v.Kc + (size_t)g * D, a.v.Vc + (size_t)g * D, kstride, a.v.Kct + (size_t)g * D * 8, kchunk,
+                wlo, whi, lo, hi, uniform, sl2, scale, a.lse2s[rs], a.deltas[rs], a.gws[rs]);
+  }
+  const bf16_t *Kg = a.v.Ks + (size_t)g * D, *Vg = a.v.Vs + (size_t)g * D, *Ktg = a.v.Kt + (size_t)g * D * 8;
+  // selection branch
+  {
+    const float lse2 = a.lse2s[NH + rs], delta = a.deltas[NH + rs], gw = a.gws[NH + rs];
+    const int32_t *row = a.idx + ((size_t)tok * a.v.Hkv + g) * T;
+    int j = 0;
+    for (;;) {
+      const int cur = (valid && j < T) ? row[j] : -1;
+      const int key = cur < 0 ? 0x7fffffff : cur;
+      const int b = wave_min_i(key);
+      if (b == 0x7fffffff) break;
+      const bool sel = key == b;
+      if (sel) ++j;
+      const int bs = a.v.slc_start[b], be = a.v.slc_start[b + 1];
+      dq_range<D>(st, qop, dop, Kg, Vg, kstride, Ktg, kchunk, bs, be, sel ? bs : 0, sel ? be : 0, __all(sel), sl2, scale,
+                  lse2, delta, gw);
+    }
+  }
+  // window branch
+  {
+    const int w = valid ? a.v.tok_win[pos] : 0;
+    const int lo = valid ? a.v.win_start[w] : 0, hi = valid ? a.v.win_start[w + 1] : 0;
+    const int wlo = wave_min_i(valid ? lo : 0x7fffffff), whi = wave_max_i(hi);
+    const bool uniform = __all(valid && lo == wlo && hi == whi);
+    dq_range<D>(st, qop, dop, Kg, Vg, kstride, Ktg, kchunk, wlo, whi, lo, hi, uniform, sl2, scale, a.lse2s[2 * NH + rs],
+                a.deltas[2 * NH + rs], a.gws[2 * NH + rs]);
+  }
+  if (valid) {
+    bf16_t *o = a.dQ + ((size_t)tok * a.v.Hq + h) * D + 4 * quad;
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) {
+      bf16x4 w;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) w[i] = (__bf16)st.acc[dt][i];
+      *reinterpret_cast<bf16x4 *>(o + 16 * dt) = w;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// dK/dV: key-centric
+// ---------------------------------------------------------------------------------------------------------
+enum { DKV_WIN = 0, DKV_SLC = 1, DKV_CMP = 2 };
+
+struct DkvArgs {
+  MfmaView v;
+  const bf16_t *Q, *dO, *QT, *dOT;
+  const float *lse2s, *deltas, *gws;  // already offset to the branch: [N(pos)][Hq]
+  const int32_t *sel_start, *sel_list;  // selection branch: query positions per (g, block)
+  float *dK, *dV;                       // [rows][Hkv][D] fp32 (rows: sorted tokens, or compression blocks)
+  int tiles_per_block;                  // key tiles reserved per block in the grid
+  int q_splits;                         // compression branch: query range split into this many parts
+};
+
+// 32 query rows = 32/hs token slots.  slot_pos(s) gives the sorted position of slot s of the current tile, or -1.
+template <int D, int KB, int MODE>
+__global__ __launch_bounds__(256) void m_bwd_dkv(DkvArgs a) {
+  const int wid = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 15, quad = lane >> 4;
+  const int hs = a.v.hs, g = blockIdx.y, Hq = a.v.Hq;
+  constexpr int WG_KEYS = 64 * KB;
+  const int blk = blockIdx.x / a.tiles_per_block, tile = blockIdx.x % a.tiles_per_block;
+  // key range of the block and query source
+  int kbeg, kend, qbeg = 0, qend = 0;
+  const bf16_t *Kr, *Vr;
+  if (MODE == DKV_WIN) {
+    kbeg = a.v.win_start[blk]; kend = a.v.win_start[blk + 1];
+    qbeg = kbeg; qend = kend;
+    Kr = a.v.Ks; Vr = a.v.Vs;
+  } else if (MODE == DKV_SLC) {
+    kbeg = a.v.slc_start[blk]; kend = a.v.slc_start[blk + 1];
+    qbeg = a.sel_start[g * a.v.Ns + blk]; qend = a.sel_start[g * a.v.Ns + blk + 1];
+    Kr = a.v.Ks; Vr = a.v.Vs;
+  } else {
+    kbeg = a.v.cmp_batch[blk]; kend = a.v.cmp_batch[blk + 1];  // blk = batch item
+    const int q0 = a.v.item_start[blk], q1 = a.v.item_start[blk + 1];
+    const int per = ((q1 - q0 + a.q_splits - 1) / a.q_splits + 3) & ~3;  // whole token slots per tile stay aligned
+    qbeg = min(q1, q0 + (int)blockIdx.z * per); qend = min(q1, qbeg + per);
+    Kr = a.v.Kc; Vr = a.v.Vc;
+  }
+  const int k0 = kbeg + tile * WG_KEYS + wid * 16 * KB;  // this wave's first key
+  if (k0 >= kend) return;  // nothing for this wavefront (no workgroup barrier is used below)
+  const size_t kstride = (size_t)a.v.Hkv * D;
+  // B operands: this wave's keys (column n of key block kbk), all of D
+  bf16x8 kop[KB][D / 32], vop[KB][D / 32];
+#pragma unroll
+  for (int kbk = 0; kbk < KB; ++kbk) {
+    const size_t off = (size_t)(k0 + 16 * kbk + n) * kstride + (size_t)g * D + 8 * quad;  // padded rows: in bounds
+#pragma unroll
+    for (int ks = 0; ks < D / 32; ++ks) {
+      kop[kbk][ks] = ld8(Kr + off + 32 * ks);
+      vop[kbk][ks] = ld8(Vr + off + 32 * ks);
+    }
+  }
+  f32x4 dk[KB][D / 16], dv[KB][D / 16];
+#pragma unroll
+  for (int kbk = 0; kbk < KB; ++kbk)
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) dk[kbk][dt] = dv[kbk][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int slots = 32 / hs;  // token slots per 32-row tile (hs is 8 or 16)
+  const float sl2 = a.v.sl2, scale = a.v.scale;
+  for (int qb = qbeg; qb < qend; qb += slots) {
+    // --- rows this lane feeds as A operand (sub-tile a): q-row 8*(n>>2) + 4a + (n&3)
+    f32x4 s[KB][2], dp[KB][2];
+#pragma unroll
+    for (int kbk = 0; kbk < KB; ++kbk)
+#pragma unroll
+      for (int sa = 0; sa < 2; ++sa) s[kbk][sa] = dp[kbk][sa] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int sa = 0; sa < 2; ++sa) {
+      const int qr = 8 * (n >> 2) + 4 * sa + (n & 3);
+      const int sl = qb + qr / hs;
+      const int pos = sl < qend ? (MODE == DKV_SLC ? a.sel_list[sl] : sl) : -1;
+      const int tok = a.v.perm[pos < 0 ? 0 : pos];
+      const size_t off = ((size_t)tok * Hq + g * hs + qr % hs) * D + 8 * quad;
+#pragma unroll
+      for (int ks = 0; ks < D / 32; ++ks) {
+        const bf16x8 qa = ld8(a.Q + off + 32 * ks), da = ld8(a.dO + off + 32 * ks);
+#pragma unroll
+        for (int kbk = 0; kbk < KB; ++kbk) {
+          s[kbk][sa] = mfma16(qa, kop[kbk][ks], s[kbk][sa]);
+          dp[kbk][sa] = mfma16(da, vop[kbk][ks], dp[kbk][sa]);
+        }
+      }
+    }
+    // --- this lane's eight consecutive q-rows 8*quad .. +7: one token slot, heads h0 .. h0+7
+    const int sl = qb + (8 * quad) / hs, h0 = (8 * quad) % hs;
+    const int pos = sl < qend ? (MODE == DKV_SLC ? a.sel_list[sl] : sl) : -1;
+    const int psafe = pos < 0 ? 0 : pos;
+    const size_t rs = (size_t)psafe * Hq + g * hs + h0;
+    float lse2[8], delta[8], gw[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      lse2[j] = pos < 0 ? INFINITY : a.lse2s[rs + j];  // a missing row contributes exp2(-inf) = 0
+      delta[j] = a.deltas[rs + j];
+      gw[j] = a.gws[rs + j];
+    }
+    const size_t toff = (((size_t)psafe * a.v.Hkv + g) * D + n) * hs + h0;  // [pos][g][dim][hs]
+    bf16x8 qt[D / 16], dot[D / 16];
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) {
+      qt[dt] = ld8(a.QT + toff + (size_t)dt * 16 * hs);
+      dot[dt] = ld8(a.dOT + toff + (size_t)dt * 16 * hs);
+    }
+#pragma unroll
+    for (int kbk = 0; kbk < KB; ++kbk) {
+      bf16x8 pw, ds;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float sv = (j < 4 ? s[kbk][0][j & 3] : s[kbk][1][j & 3]) * sl2;
+        const float dpv = j < 4 ? dp[kbk][0][j & 3] : dp[kbk][1][j & 3];
+        const float p = fast_exp2(sv - lse2[j]);
+        pw[j] = (__bf16)(p * gw[j]);
+        ds[j] = (__bf16)(p * (gw[j] * dpv - delta[j]) * scale);
+      }
+#pragma unroll
+      for (int dt = 0; dt < D / 16; ++dt) {
+        dv[kbk][dt] = mfma16(dot[dt], pw, dv[kbk][dt]);
+        dk[kbk][dt] = mfma16(qt[dt], ds, dk[kbk][dt]);
+      }
+    }
+  }
+  // --- store: lane holds dims 16*dt + 4*quad + i of key column n
+#pragma unroll
+  for (int kbk = 0; kbk < KB; ++kbk) {
+    const int key = k0 + 16 * kbk + n;
+    if (key >= kend) continue;
+    size_t off = ((size_t)key * a.v.Hkv + g) * D + 4 * quad;
+    if (MODE == DKV_CMP) off += (size_t)blockIdx.z * a.v.Nc * kstride;
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) {
+      float4 *pk = reinterpret_cast<float4 *>(a.dK + off + 16 * dt), *pv = reinterpret_cast<float4 *>(a.dV + off + 16 * dt);
+      float4 ok = make_float4(dk[kbk][dt][0], dk[kbk][dt][1], dk[kbk][dt][2], dk[kbk][dt][3]);
+      float4 ov = make_float4(dv[kbk][dt][0], dv[kbk][dt][1], dv[kbk][dt][2], dv[kbk][dt][3]);
+      if (MODE == DKV_SLC) {  // the window kernel wrote these rows earlier on the same stream
+        const float4 ck = *pk, cv = *pv;
+        ok.x += ck.x; ok.y += ck.y; ok.z += ck.z; ok.w += ck.w;
+        ov.x += cv.x; ov.y += cv.y; ov.z += cv.z; ov.w += cv.w;
+      }
+      *pk = ok;
+      *pv = ov;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Inverse of the selection: for every (KV head, selection block) the ascending list of query positions that
+// selected it.  Built from a bit matrix (integer OR: order independent), then compacted in order.
+// ---------------------------------------------------------------------------------------------------------
+__global__ void m_fill_u32(uint32_t *p, size_t n, uint32_t v) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+__global__ void m_sel_bits(const int32_t *__restrict__ idx, const int32_t *__restrict__ perm, int N, int Hkv, int T, int Ns,
+                           int words, uint32_t *bits) {
+  const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= (size_t)N * Hkv * T) return;
+  const int pos = (int)(e / ((size_t)Hkv * T)), g = (int)(e / T % Hkv), j = (int)(e % T);
+  const int b = idx[((size_t)perm[pos] * Hkv + g) * T + j];
+  if (b < 0 || b >= Ns) return;
+  atomicOr(&bits[((size_t)g * Ns + b) * words + (pos >> 5)], 1u << (pos & 31));
+}
+
+__global__ __launch_bounds__(256) void m_sel_count(const uint32_t *__restrict__ bits, int words, uint32_t *counts) {
+  __shared__ uint32_t part[4];
+  const uint32_t *row = bits + (size_t)blockIdx.x * words;
+  uint32_t c = 0;
+  for (int i = threadIdx.x; i < words; i += 256) c += __popc(row[i]);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) c += __shfl_xor(c, off);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = c;
+  __syncthreads();
+  if (threadIdx.x == 0) counts[blockIdx.x] = part[0] + part[1] + part[2] + part[3];
+}
+
+// single workgroup: exclusive scan of n counts into start[0..n]
+__global__ void m_scan_counts(const uint32_t *counts, int n, int32_t *start) {
+  __shared__ uint32_t part[1024];
+  const int tid = threadIdx.x;
+  const int per = (n + 1023) / 1024;
+  const int b = min(n, tid * per), e = min(n, b + per);
+  uint32_t s = 0;
+  for (int i = b; i < e; ++i) s += counts[i];
+  part[tid] = s;
+  __syncthreads();
+  for (int off = 1; off < 1024; off <<= 1) {
+    const uint32_t v = tid >= off ? part[tid - off] : 0u;
+    __syncthreads();
+    part[tid] += v;
+    __syncthreads();
+  }
+  uint32_t run = part[tid] - s;
+  for (int i = b; i < e; ++i) {
+    start[i] = (int32_t)run;
+    run += counts[i];
+  }
+  if (tid == 1023) start[n] = (int32_t)part[1023];
+}
+
+__global__ __launch_bounds__(256) void m_sel_fill(const uint32_t *__restrict__ bits, int words,
+                                                  const int32_t *__restrict__ start, int32_t *list) {
+  __shared__ uint32_t wsum[4];
+  __shared__ uint32_t base;
+  const uint32_t *row = bits + (size_t)blockIdx.x * words;
+  if (threadIdx.x == 0) base = (uint32_t)start[blockIdx.x];
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+  for (int i0 = 0; i0 < words; i0 += 256) {
+    const int i = i0 + threadIdx.x;
+    uint32_t w = i < words ? row[i] : 0u;
+    const uint32_t c = __popc(w);
+    uint32_t incl = c;  // inclusive scan inside the wavefront
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t o = __shfl_up(incl, off);
+      if (lane >= off) incl += o;
+    }
+    if (lane == 63) wsum[wid] = incl;
+    __syncthreads();
+    uint32_t off = base + incl - c;
+    for (int ww = 0; ww < wid; ++ww) off += wsum[ww];
+    while (w) {
+      const int bit = __ffs(w) - 1;
+      list[off++] = i * 32 + bit;
+      w &= w - 1;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) base += wsum[0] + wsum[1] + wsum[2] + wsum[3];
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Finish: dK[tok] = dKs[pos] + (sum over query splits of dKc[c]) / count(c)  (gradient of the mean pool),
+// scattered back to caller order.  One workgroup per compression block.
+// ---------------------------------------------------------------------------------------------------------
+__global__ void m_bwd_finish(const int32_t *__restrict__ perm, const int32_t *__restrict__ cmp_start, int Nc, int row,
+                             int splits, const float *__restrict__ dKs, const float *__restrict__ dVs,
+                             const float *__restrict__ dKc, const float *__restrict__ dVc, bf16_t *__restrict__ dK,
+                             bf16_t *__restrict__ dV) {
+  const int c = blockIdx.x;
+  const int b = cmp_start[c], e = cmp_start[c + 1];
+  const float inv = 1.0f / (float)(e - b);
+  for (int f = threadIdx.x; f < row; f += blockDim.x) {
+    float ck = 0.f, cv = 0.f;
+    for (int s = 0; s < splits; ++s) {
+      ck += dKc[((size_t)s * Nc + c) * row + f];
+      cv += dVc[((size_t)s * Nc + c) * row + f];
+    }
+    ck *= inv;
+    cv *= inv;
+    for (int pos = b; pos < e; ++pos) {
+      const size_t dst = (size_t)perm[pos] * row + f;
+      dK[dst] = f32_to_bf16(dKs[(size_t)pos * row + f] + ck);
+      dV[dst] = f32_to_bf16(dVs[(size_t)pos * row + f] + cv);
+    }
+  }
+}
+
+constexpr int KB_KEYS = 2;  // key blocks of 16 per wavefront in the dK/dV kernels
+
+template <int D>
+int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const void *gates, const void *out_branch,
+                    const float *lse, const int32_t *idx, const void *dout, void *dq, void *dk, void *dv, void *dgates,
+                    const ssa_blocks *blk, int B, hipStream_t s) {
+  const int N = v.N, Hq = v.Hq, Hkv = v.Hkv, row = Hkv * D;
+  const size_t NH = (size_t)N * Hq;
+  {
+    ProfScope ps(PROF_BWD_PRE, s);
+    PreArgs a{(const bf16_t *)q, (const bf16_t *)dout, (const bf16_t *)out_branch, (const bf16_t *)gates, lse, v.perm,
+              N, Hq, Hkv, v.hs, D, (bf16_t *)dgates, w.lse2s, w.deltas, w.gws, w.QT, w.dOT};
+    m_bwd_pre<<<N, 256, (size_t)2 * Hq * D * sizeof(bf16_t), s>>>(a);
+  }
+  {
+    ProfScope ps(PROF_BWD_DQ, s);
+    DqArgs a{v, (const bf16_t *)q, (const bf16_t *)dout, idx, w.lse2s, w.deltas, w.gws, (bf16_t *)dq};
+    const int tpw = 16 / v.hs;
+    m_bwd_dq<D><<<dim3((N + 4 * tpw - 1) / (4 * tpw), Hkv), 256, 0, s>>>(a);
+  }
+  constexpr int WG_KEYS = 64 * KB_KEYS;
+  DkvArgs base{v, (const bf16_t *)q, (const bf16_t *)dout, w.QT, w.dOT, nullptr, nullptr, nullptr, w.sel_start, w.sel_list,
+               w.dKs, w.dVs, 1, 1};
+  {
+    ProfScope ps(PROF_BWD_DKV_WIN, s);
+    DkvArgs a = base;
+    a.lse2s = w.lse2s + 2 * NH; a.deltas = w.deltas + 2 * NH; a.gws = w.gws + 2 * NH;
+    a.tiles_per_block = (blk->win_tok_max + WG_KEYS - 1) / WG_KEYS;
+    m_bwd_dkv<D, KB_KEYS, DKV_WIN><<<dim3(blk->Nw * a.tiles_per_block, Hkv), 256, 0, s>>>(a);
+  }
+  {
+    ProfScope ps(PROF_BWD_INVERT, s);
+    const int words = (N + 31) / 32, keys = Hkv * v.Ns;
+    m_fill_u32<<<1024, 256, 0, s>>>(w.sel_bits, (size_t)keys * words, 0u);
+    const size_t entries = (size_t)N * Hkv * v.T;
+    m_sel_bits<<<(unsigned)((entries + 255) / 256), 256, 0, s>>>(idx, v.perm, N, Hkv, v.T, v.Ns, words, w.sel_bits);
+    m_sel_count<<<keys, 256, 0, s>>>(w.sel_bits, words, w.sel_counts);
+    m_scan_counts<<<1, 1024, 0, s>>>(w.sel_counts, keys, w.sel_start);
+    m_sel_fill<<<keys, 256, 0, s>>>(w.sel_bits, words, w.sel_start, w.sel_list);
+  }
+  {
+    ProfScope ps(PROF_BWD_DKV_SLC, s);
+    DkvArgs a = base;
+    a.lse2s = w.lse2s + NH; a.deltas = w.deltas + NH; a.gws = w.gws + NH;
+    a.tiles_per_block = (blk->slc_tok_max + WG_KEYS - 1) / WG_KEYS;
+    m_bwd_dkv<D, KB_KEYS, DKV_SLC><<<dim3(v.Ns * a.tiles_per_block, Hkv), 256, 0, s>>>(a);
+  }
+  {
+    ProfScope ps(PROF_BWD_DKV_CMP, s);
+    DkvArgs a = base;
+    a.lse2s = w.lse2s; a.deltas = w.deltas; a.gws = w.gws;
+    a.dK = w.dKc; a.dV = w.dVc;
+    a.tiles_per_block = (blk->c_max + WG_KEYS - 1) / WG_KEYS;
+    a.q_splits = w.q_splits;
+    m_bwd_dkv<D, KB_KEYS, DKV_CMP><<<dim3(B * a.tiles_per_block, Hkv, w.q_splits), 256, 0, s>>>(a);
+  }
+  {
+    ProfScope ps(PROF_BWD_FINISH, s);
+    m_bwd_finish<<<v.Nc, 128, 0, s>>>(v.perm, v.cmp_start, v.Nc, row, w.q_splits, w.dKs, w.dVs, w.dKc, w.dVc, (bf16_t *)dk,
+                                      (bf16_t *)dv);
+  }
+  return hipGetLastError() == hipSuccess ? SSA_OK : SSA_ERR_HIP;
+}
+
+}  // namespace
+
+int mfma_backward_kernels(const MfmaView &v, int D, const BwdBuffers &w, const void *q, const void *gates,
+                          const void *out_branch, const float *lse, const int32_t *idx, const void *dout, void *dq,
+                          void *dk, void *dv, void *dgates, const ssa_blocks *blk, int B, hipStream_t s) {
+  switch (D) {
+    case 32: return launch_backward<32>(v, w, q, gates, out_branch, lse, idx, dout, dq, dk, dv, dgates, blk, B, s);
+    case 64: return launch_backward<64>(v, w, q, gates, out_branch, lse, idx, dout, dq, dk, dv, dgates, blk, B, s);
+    case 128: return launch_backward<128>(v, w, q, gates, out_branch, lse, idx, dout, dq, dk, dv, dgates, blk, B, s);
+    default: return SSA_ERR_UNSUPPORTED;
+  }
+}

@@ -5,3 +5,18 @@
 size_t mfma_cmp_lds_bytes(int hs, int s_max);
 int mfma_forward_kernels(const MfmaView &v, int D, const void *q, const void *gates, void *out, float *lse,
                          int32_t *idx, void *out_branch, hipStream_t s);
+
+// Device buffers of the backward pass (carved from the caller's workspace).
+struct BwdBuffers {
+  float *lse2s, *deltas, *gws;  // [3][N(pos)][Hq]: lse*log2(e), gate*<dO,O_b>, gate
+  bf16_t *QT, *dOT;             // [N(pos)][Hkv][D][hs]: per-token transposed Q and dO
+  float *dKs, *dVs;             // [N(pos)][Hkv][D] token-level gradients in sorted order
+  float *dKc, *dVc;             // [q_splits][Nc][Hkv][D] partial gradients of the pooled keys/values
+  uint32_t *sel_bits;           // [Hkv*Ns][ceil(N/32)] bit (key, pos): token at pos selected the block
+  uint32_t *sel_counts;         // [Hkv*Ns]
+  int32_t *sel_start, *sel_list;  // [Hkv*Ns+1], [N*Hkv*T]
+  int q_splits;
+};
+int mfma_backward_kernels(const MfmaView &v, int D, const BwdBuffers &w, const void *q, const void *gates,
+                          const void *out_branch, const float *lse, const int32_t *idx, const void *dout, void *dq,
+                          void *dk, void *dv, void *dgates, const ssa_blocks *blk, int B, hipStream_t s);

@@ -90,6 +90,39 @@ int run_prep(const ssa_ctx &c, const void *k, const void *v, const PrepOut &o) {
   return hipGetLastError() == hipSuccess ? SSA_OK : SSA_ERR_HIP;
 }
 
+struct BwdPlan {
+  size_t ks, vs, kt, kc, vc, kct, lse2s, deltas, gws, qt, dot, dks, dvs, dkc, dvc, bits, counts, start, list, total;
+  int q_splits;
+};
+
+constexpr int DKV_WG_KEYS = 128;  // keys per workgroup of the dK/dV kernels (4 waves x 2 blocks of 16)
+
+BwdPlan bwd_plan(const ssa_ctx &c) {
+  BwdPlan p{};
+  const ssa_blocks *b = c.blk;
+  const size_t row = (size_t)c.Hkv * c.d;
+  const int tiles = (b->c_max + DKV_WG_KEYS - 1) / DKV_WG_KEYS;
+  const long long wgs = (long long)c.B * (tiles > 0 ? tiles : 1) * c.Hkv;
+  long long sp = (1024 + wgs - 1) / wgs;
+  p.q_splits = (int)(sp < 1 ? 1 : (sp > 64 ? 64 : sp));
+  size_t off = 0;
+  auto take = [&](size_t n) { size_t r = off; off += align_up(n, 256); return r; };
+  p.ks = take(padded_rows(c.N) * row * 2); p.vs = take(padded_rows(c.N) * row * 2); p.kt = take(padded_rows(c.N) * row * 2);
+  p.kc = take(padded_rows(b->Nc) * row * 2); p.vc = take(padded_rows(b->Nc) * row * 2); p.kct = take(padded_rows(b->Nc) * row * 2);
+  const size_t nh = (size_t)3 * c.N * c.Hq * 4;
+  p.lse2s = take(nh); p.deltas = take(nh); p.gws = take(nh);
+  p.qt = take((size_t)c.N * c.Hq * c.d * 2); p.dot = take((size_t)c.N * c.Hq * c.d * 2);
+  p.dks = take((size_t)c.N * row * 4); p.dvs = take((size_t)c.N * row * 4);
+  p.dkc = take((size_t)p.q_splits * b->Nc * row * 4); p.dvc = take((size_t)p.q_splits * b->Nc * row * 4);
+  const size_t keys = (size_t)c.Hkv * b->Ns, words = ((size_t)c.N + 31) / 32;
+  p.bits = take(keys * words * 4); p.counts = take(keys * 4 + 4); p.start = take((keys + 1) * 4);
+  p.list = take((size_t)c.N * c.Hkv * c.T * 4);
+  p.total = off;
+  return p;
+}
+
+bool mfma_bwd_supported(const ssa_ctx &c) { return c.hs == 8 || c.hs == 16; }
+
 }  // namespace
 
 bool mfma_supported(const ssa_ctx &c) {
@@ -101,7 +134,37 @@ bool mfma_supported(const ssa_ctx &c) {
 }
 
 size_t mfma_forward_workspace(const ssa_ctx &c) { return fwd_plan(c).total; }
-size_t mfma_backward_workspace(const ssa_ctx &c) { return generic_backward_workspace(c); }
+size_t mfma_backward_workspace(const ssa_ctx &c) {
+  return mfma_bwd_supported(c) ? bwd_plan(c).total : generic_backward_workspace(c);
+}
+
+int mfma_backward(const ssa_ctx &c, const void *q, const void *k, const void *v, const void *gates,
+                  const void *out_branch, const float *lse, const int32_t *topk_idx, const void *dout, void *dq,
+                  void *dk, void *dv, void *dgates, void *ws_, size_t ws_bytes) {
+  if (!mfma_bwd_supported(c)) {  // head groupings the key-centric kernels do not cover
+    ProfScope ps(PROF_GENERIC, c.stream);
+    return generic_backward(c, q, k, v, gates, out_branch, lse, topk_idx, dout, dq, dk, dv, dgates, ws_, ws_bytes);
+  }
+  const BwdPlan p = bwd_plan(c);
+  if (ws_bytes < p.total) return SSA_ERR_WORKSPACE;
+  char *ws = (char *)ws_;
+  PrepOut o{};
+  o.Ks = (bf16_t *)(ws + p.ks); o.Vs = (bf16_t *)(ws + p.vs); o.Kt = (bf16_t *)(ws + p.kt);
+  o.Kc = (bf16_t *)(ws + p.kc); o.Vc = (bf16_t *)(ws + p.vc); o.Kct = (bf16_t *)(ws + p.kct);
+  int rc = run_prep(c, k, v, o);
+  if (rc != SSA_OK) return rc;
+  MfmaView view = make_view(c);
+  view.Ks = o.Ks; view.Vs = o.Vs; view.Kt = o.Kt; view.Kc = o.Kc; view.Vc = o.Vc; view.Kct = o.Kct;
+  BwdBuffers w{};
+  w.lse2s = (float *)(ws + p.lse2s); w.deltas = (float *)(ws + p.deltas); w.gws = (float *)(ws + p.gws);
+  w.QT = (bf16_t *)(ws + p.qt); w.dOT = (bf16_t *)(ws + p.dot);
+  w.dKs = (float *)(ws + p.dks); w.dVs = (float *)(ws + p.dvs); w.dKc = (float *)(ws + p.dkc); w.dVc = (float *)(ws + p.dvc);
+  w.sel_bits = (uint32_t *)(ws + p.bits); w.sel_counts = (uint32_t *)(ws + p.counts);
+  w.sel_start = (int32_t *)(ws + p.start); w.sel_list = (int32_t *)(ws + p.list);
+  w.q_splits = p.q_splits;
+  return mfma_backward_kernels(view, c.d, w, q, gates, out_branch, lse, topk_idx, dout, dq, dk, dv, dgates, c.blk, c.B,
+                               c.stream);
+}
 
 int mfma_forward(const ssa_ctx &c, const void *q, const void *k, const void *v, const void *gates, void *out,
                  float *lse, int32_t *topk_idx, void *out_branch, void *ws_, size_t ws_bytes) {
@@ -117,11 +180,4 @@ int mfma_forward(const ssa_ctx &c, const void *q, const void *k, const void *v, 
   return mfma_forward_kernels(view, c.d, q, gates, out, lse ? lse : (float *)(ws + p.lse),
                               topk_idx ? topk_idx : (int32_t *)(ws + p.idx), out_branch ? out_branch : (void *)(ws + p.ob),
                               c.stream);
-}
-
-int mfma_backward(const ssa_ctx &c, const void *q, const void *k, const void *v, const void *gates,
-                  const void *out_branch, const float *lse, const int32_t *topk_idx, const void *dout, void *dq,
-                  void *dk, void *dv, void *dgates, void *ws, size_t ws_bytes) {
-  ProfScope ps(PROF_GENERIC, c.stream);
-  return generic_backward(c, q, k, v, gates, out_branch, lse, topk_idx, dout, dq, dk, dv, dgates, ws, ws_bytes);
 }

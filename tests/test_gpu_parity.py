@@ -140,3 +140,10 @@ def test_g64_bf16_forward_sampled():
     """Config "g64": 64^3 grid, ~11k tokens, bf16, 16 heads (2 KV heads), d=64, T=8, forward; every 8th query."""
     wl = inputs.make_workload("g64")
     full_parity(wl, backward=False, queries=np.arange(0, wl.n_tokens, 8, dtype=np.int32))
+
+
+def test_g128_bf16_forward_backward_sampled():
+    """Config "g128" (the benchmark workload): 128^3 grid, ~62k tokens, bf16, 16 heads (2 KV heads), d=64, T=16.
+    The oracle visits every 97th query; dO is zero elsewhere (backward is linear in dO), so dK/dV compare in full."""
+    wl = inputs.make_workload("g128")
+    full_parity(wl, backward=True, queries=np.arange(5, wl.n_tokens, 97, dtype=np.int32))
