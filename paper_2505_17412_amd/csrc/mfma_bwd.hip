@@ -226,6 +226,9 @@ struct DkvArgs {
   const float *lse2s, *deltas, *gws;  // already offset to the branch: [N(pos)][Hq]
   const int32_t *sel_start, *sel_list;  // selection branch: query positions per (g, block)
   float *dK, *dV;                       // [rows][Hkv][D] fp32 (rows: sorted tokens, or compression blocks)
+  const int32_t *chunk_start;           // selection branch: [Hkv*Ns+1] first work chunk of each (g, block)
+  const int32_t *part_row_start;        // selection branch: [Hkv*Ns+1] first row of each (g, block)'s partial sums
+  int chunk_len;                        // selection branch: query tokens per work chunk
   int tiles_per_block;                  // key tiles reserved per block in the grid
   int q_splits;                         // compression branch: query range split into this many parts
 };
@@ -234,24 +237,39 @@ struct DkvArgs {
 template <int D, int KB, int MODE>
 __global__ __launch_bounds__(256) void m_bwd_dkv(DkvArgs a) {
   const int wid = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 15, quad = lane >> 4;
-  const int hs = a.v.hs, g = blockIdx.y, Hq = a.v.Hq;
+  const int hs = a.v.hs, Hq = a.v.Hq;
   constexpr int WG_KEYS = 64 * KB;
-  const int blk = blockIdx.x / a.tiles_per_block, tile = blockIdx.x % a.tiles_per_block;
+  int g = blockIdx.y, blk, tile;
   // key range of the block and query source
   int kbeg, kend, qbeg = 0, qend = 0;
+  size_t out_row0 = 0;  // selection branch: first row of this chunk's partial sums
   const bf16_t *Kr, *Vr;
   if (MODE == DKV_WIN) {
+    blk = blockIdx.x / a.tiles_per_block; tile = blockIdx.x % a.tiles_per_block;
     kbeg = a.v.win_start[blk]; kend = a.v.win_start[blk + 1];
     qbeg = kbeg; qend = kend;
     Kr = a.v.Ks; Vr = a.v.Vs;
   } else if (MODE == DKV_SLC) {
+    // blockIdx.x is a work chunk; find its (g, block) by bisection over the chunk prefix sums
+    const int nkeys = a.v.Hkv * a.v.Ns, w = blockIdx.x;
+    if (w >= a.chunk_start[nkeys]) return;
+    int lo = 0, hi = nkeys;  // chunk_start[lo] <= w < chunk_start[hi]
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (a.chunk_start[mid] <= w) lo = mid; else hi = mid;
+    }
+    const int key = lo, chunk = w - a.chunk_start[key];
+    g = key / a.v.Ns; blk = key % a.v.Ns; tile = blockIdx.y;
     kbeg = a.v.slc_start[blk]; kend = a.v.slc_start[blk + 1];
-    qbeg = a.sel_start[g * a.v.Ns + blk]; qend = a.sel_start[g * a.v.Ns + blk + 1];
+    qbeg = a.sel_start[key] + chunk * a.chunk_len;
+    qend = min(a.sel_start[key + 1], qbeg + a.chunk_len);
+    out_row0 = (size_t)a.part_row_start[key] + (size_t)chunk * (kend - kbeg);
     Kr = a.v.Ks; Vr = a.v.Vs;
   } else {
-    kbeg = a.v.cmp_batch[blk]; kend = a.v.cmp_batch[blk + 1];  // blk = batch item
+    blk = blockIdx.x / a.tiles_per_block; tile = blockIdx.x % a.tiles_per_block;  // blk = batch item
+    kbeg = a.v.cmp_batch[blk]; kend = a.v.cmp_batch[blk + 1];
     const int q0 = a.v.item_start[blk], q1 = a.v.item_start[blk + 1];
-    const int per = ((q1 - q0 + a.q_splits - 1) / a.q_splits + 3) & ~3;  // whole token slots per tile stay aligned
+    const int per = (q1 - q0 + a.q_splits - 1) / a.q_splits;
     qbeg = min(q1, q0 + (int)blockIdx.z * per); qend = min(q1, qbeg + per);
     Kr = a.v.Kc; Vr = a.v.Vc;
   }
@@ -345,20 +363,43 @@ __global__ __launch_bounds__(256) void m_bwd_dkv(DkvArgs a) {
     if (key >= kend) continue;
     size_t off = ((size_t)key * a.v.Hkv + g) * D + 4 * quad;
     if (MODE == DKV_CMP) off += (size_t)blockIdx.z * a.v.Nc * kstride;
+    if (MODE == DKV_SLC) off = (out_row0 + (size_t)(key - kbeg)) * D + 4 * quad;  // partial sums: [row][D]
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt) {
-      float4 *pk = reinterpret_cast<float4 *>(a.dK + off + 16 * dt), *pv = reinterpret_cast<float4 *>(a.dV + off + 16 * dt);
-      float4 ok = make_float4(dk[kbk][dt][0], dk[kbk][dt][1], dk[kbk][dt][2], dk[kbk][dt][3]);
-      float4 ov = make_float4(dv[kbk][dt][0], dv[kbk][dt][1], dv[kbk][dt][2], dv[kbk][dt][3]);
-      if (MODE == DKV_SLC) {  // the window kernel wrote these rows earlier on the same stream
-        const float4 ck = *pk, cv = *pv;
-        ok.x += ck.x; ok.y += ck.y; ok.z += ck.z; ok.w += ck.w;
-        ov.x += cv.x; ov.y += cv.y; ov.z += cv.z; ov.w += cv.w;
-      }
-      *pk = ok;
-      *pv = ov;
+      *reinterpret_cast<float4 *>(a.dK + off + 16 * dt) =
+          make_float4(dk[kbk][dt][0], dk[kbk][dt][1], dk[kbk][dt][2], dk[kbk][dt][3]);
+      *reinterpret_cast<float4 *>(a.dV + off + 16 * dt) =
+          make_float4(dv[kbk][dt][0], dv[kbk][dt][1], dv[kbk][dt][2], dv[kbk][dt][3]);
     }
   }
+}
+
+// Selection branch: add the per-chunk partial sums of every key, in chunk order, onto the token-level gradients
+// (which the window kernel wrote earlier on the same stream).  One thread per (sorted position, group, 4 dims).
+__global__ void m_slc_reduce(const int32_t *__restrict__ tok_slc, const int32_t *__restrict__ slc_start,
+                             const int32_t *__restrict__ chunk_start, const int32_t *__restrict__ part_row_start, int N,
+                             int Hkv, int Ns, int D, const float *__restrict__ pK, const float *__restrict__ pV,
+                             float *__restrict__ dKs, float *__restrict__ dVs) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int per_row = D / 4;
+  if (i >= (size_t)N * Hkv * per_row) return;
+  const int d4 = (int)(i % per_row), g = (int)(i / per_row % Hkv), pos = (int)(i / ((size_t)per_row * Hkv));
+  const int b = tok_slc[pos], key = g * Ns + b;
+  const int klen = slc_start[b + 1] - slc_start[b], nch = chunk_start[key + 1] - chunk_start[key];
+  const size_t row0 = (size_t)part_row_start[key] + (size_t)(pos - slc_start[b]);
+  float4 sk = make_float4(0.f, 0.f, 0.f, 0.f), sv = sk;
+  for (int c = 0; c < nch; ++c) {
+    const size_t off = (row0 + (size_t)c * klen) * D + 4 * d4;
+    const float4 ak = *reinterpret_cast<const float4 *>(pK + off), av = *reinterpret_cast<const float4 *>(pV + off);
+    sk.x += ak.x; sk.y += ak.y; sk.z += ak.z; sk.w += ak.w;
+    sv.x += av.x; sv.y += av.y; sv.z += av.z; sv.w += av.w;
+  }
+  const size_t dst = ((size_t)pos * Hkv + g) * D + 4 * d4;
+  float4 ck = *reinterpret_cast<float4 *>(dKs + dst), cv = *reinterpret_cast<float4 *>(dVs + dst);
+  ck.x += sk.x; ck.y += sk.y; ck.z += sk.z; ck.w += sk.w;
+  cv.x += sv.x; cv.y += sv.y; cv.z += sv.z; cv.w += sv.w;
+  *reinterpret_cast<float4 *>(dKs + dst) = ck;
+  *reinterpret_cast<float4 *>(dVs + dst) = cv;
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -391,28 +432,41 @@ __global__ __launch_bounds__(256) void m_sel_count(const uint32_t *__restrict__ 
   if (threadIdx.x == 0) counts[blockIdx.x] = part[0] + part[1] + part[2] + part[3];
 }
 
-// single workgroup: exclusive scan of n counts into start[0..n]
-__global__ void m_scan_counts(const uint32_t *counts, int n, int32_t *start) {
-  __shared__ uint32_t part[1024];
+// single workgroup: from the per-(g, block) selector counts, three exclusive prefix sums over the n keys:
+// start (list offsets), chunk_start (work chunks of chunk_len query tokens), part_row_start (rows of partial sums:
+// chunks x keys of the block).
+__global__ void m_scan_counts(const uint32_t *counts, int n, int Ns, int chunk_len, const int32_t *slc_start,
+                              int32_t *start, int32_t *chunk_start, int32_t *part_row_start) {
+  __shared__ uint32_t part[3][1024];
   const int tid = threadIdx.x;
   const int per = (n + 1023) / 1024;
   const int b = min(n, tid * per), e = min(n, b + per);
-  uint32_t s = 0;
-  for (int i = b; i < e; ++i) s += counts[i];
-  part[tid] = s;
+  uint32_t s[3] = {0u, 0u, 0u};
+  for (int i = b; i < e; ++i) {
+    const uint32_t c = counts[i], nch = (c + chunk_len - 1) / chunk_len;
+    const int blk = i % Ns;
+    s[0] += c; s[1] += nch; s[2] += nch * (uint32_t)(slc_start[blk + 1] - slc_start[blk]);
+  }
+  for (int x = 0; x < 3; ++x) part[x][tid] = s[x];
   __syncthreads();
   for (int off = 1; off < 1024; off <<= 1) {
-    const uint32_t v = tid >= off ? part[tid - off] : 0u;
+    uint32_t v[3];
+    for (int x = 0; x < 3; ++x) v[x] = tid >= off ? part[x][tid - off] : 0u;
     __syncthreads();
-    part[tid] += v;
+    for (int x = 0; x < 3; ++x) part[x][tid] += v[x];
     __syncthreads();
   }
-  uint32_t run = part[tid] - s;
+  uint32_t run[3];
+  for (int x = 0; x < 3; ++x) run[x] = part[x][tid] - s[x];
   for (int i = b; i < e; ++i) {
-    start[i] = (int32_t)run;
-    run += counts[i];
+    const uint32_t c = counts[i], nch = (c + chunk_len - 1) / chunk_len;
+    const int blk = i % Ns;
+    start[i] = (int32_t)run[0]; chunk_start[i] = (int32_t)run[1]; part_row_start[i] = (int32_t)run[2];
+    run[0] += c; run[1] += nch; run[2] += nch * (uint32_t)(slc_start[blk + 1] - slc_start[blk]);
   }
-  if (tid == 1023) start[n] = (int32_t)part[1023];
+  if (tid == 1023) {
+    start[n] = (int32_t)part[0][1023]; chunk_start[n] = (int32_t)part[1][1023]; part_row_start[n] = (int32_t)part[2][1023];
+  }
 }
 
 __global__ __launch_bounds__(256) void m_sel_fill(const uint32_t *__restrict__ bits, int words,
@@ -497,7 +551,7 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
   }
   constexpr int WG_KEYS = 64 * KB_KEYS;
   DkvArgs base{v, (const bf16_t *)q, (const bf16_t *)dout, w.QT, w.dOT, nullptr, nullptr, nullptr, w.sel_start, w.sel_list,
-               w.dKs, w.dVs, 1, 1};
+               w.dKs, w.dVs, w.chunk_start, w.part_row_start, w.chunk_len, 1, 1};
   {
     ProfScope ps(PROF_BWD_DKV_WIN, s);
     DkvArgs a = base;
@@ -512,15 +566,20 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
     const size_t entries = (size_t)N * Hkv * v.T;
     m_sel_bits<<<(unsigned)((entries + 255) / 256), 256, 0, s>>>(idx, v.perm, N, Hkv, v.T, v.Ns, words, w.sel_bits);
     m_sel_count<<<keys, 256, 0, s>>>(w.sel_bits, words, w.sel_counts);
-    m_scan_counts<<<1, 1024, 0, s>>>(w.sel_counts, keys, w.sel_start);
+    m_scan_counts<<<1, 1024, 0, s>>>(w.sel_counts, keys, v.Ns, w.chunk_len, v.slc_start, w.sel_start, w.chunk_start,
+                                     w.part_row_start);
     m_sel_fill<<<keys, 256, 0, s>>>(w.sel_bits, words, w.sel_start, w.sel_list);
   }
   {
     ProfScope ps(PROF_BWD_DKV_SLC, s);
     DkvArgs a = base;
     a.lse2s = w.lse2s + NH; a.deltas = w.deltas + NH; a.gws = w.gws + NH;
+    a.dK = w.pK; a.dV = w.pV;
     a.tiles_per_block = (blk->slc_tok_max + WG_KEYS - 1) / WG_KEYS;
-    m_bwd_dkv<D, KB_KEYS, DKV_SLC><<<dim3(v.Ns * a.tiles_per_block, Hkv), 256, 0, s>>>(a);
+    m_bwd_dkv<D, KB_KEYS, DKV_SLC><<<dim3(w.max_chunks, a.tiles_per_block), 256, 0, s>>>(a);
+    const size_t items = (size_t)N * Hkv * (D / 4);
+    m_slc_reduce<<<(unsigned)((items + 255) / 256), 256, 0, s>>>(blk->tok_slc, v.slc_start, w.chunk_start, w.part_row_start, N,
+                                                                 Hkv, v.Ns, D, w.pK, w.pV, w.dKs, w.dVs);
   }
   {
     ProfScope ps(PROF_BWD_DKV_CMP, s);

@@ -15,6 +15,9 @@ struct BwdBuffers {
   uint32_t *sel_bits;           // [Hkv*Ns][ceil(N/32)] bit (key, pos): token at pos selected the block
   uint32_t *sel_counts;         // [Hkv*Ns]
   int32_t *sel_start, *sel_list;  // [Hkv*Ns+1], [N*Hkv*T]
+  int32_t *chunk_start, *part_row_start;  // [Hkv*Ns+1] each: work chunks and partial-sum rows per (g, block)
+  float *pK, *pV;               // [max_part_rows][D] per-chunk partial dK/dV of the selection branch
+  int chunk_len, max_chunks;    // query tokens per chunk; upper bound of the number of chunks
   int q_splits;
 };
 int mfma_backward_kernels(const MfmaView &v, int D, const BwdBuffers &w, const void *q, const void *gates,

@@ -91,8 +91,9 @@ int run_prep(const ssa_ctx &c, const void *k, const void *v, const PrepOut &o) {
 }
 
 struct BwdPlan {
-  size_t ks, vs, kt, kc, vc, kct, lse2s, deltas, gws, qt, dot, dks, dvs, dkc, dvc, bits, counts, start, list, total;
-  int q_splits;
+  size_t ks, vs, kt, kc, vc, kct, lse2s, deltas, gws, qt, dot, dks, dvs, dkc, dvc, bits, counts, start, list, cstart, prow,
+      pk, pv, total;
+  int q_splits, chunk_len, max_chunks;
 };
 
 constexpr int DKV_WG_KEYS = 128;  // keys per workgroup of the dK/dV kernels (4 waves x 2 blocks of 16)
@@ -117,6 +118,20 @@ BwdPlan bwd_plan(const ssa_ctx &c) {
   const size_t keys = (size_t)c.Hkv * b->Ns, words = ((size_t)c.N + 31) / 32;
   p.bits = take(keys * words * 4); p.counts = take(keys * 4 + 4); p.start = take((keys + 1) * 4);
   p.list = take((size_t)c.N * c.Hkv * c.T * 4);
+  // selection-branch work chunks: every (g, block) list is cut into pieces of chunk_len query tokens whose partial
+  // dK/dV are summed afterwards in a fixed order.  Bounds: chunks <= entries/chunk_len + keys; partial rows <=
+  // slc_tok_max * entries/chunk_len + N*Hkv.  chunk_len grows until the partial sums fit in about 1 GiB.
+  const size_t entries = (size_t)c.N * c.Hkv * c.T;
+  p.chunk_len = 1024;
+  size_t rows;
+  for (;;) {
+    rows = (size_t)b->slc_tok_max * (entries / p.chunk_len + 1) + (size_t)c.N * c.Hkv;
+    if (rows * c.d * 8 <= ((size_t)1 << 30) || p.chunk_len >= (1 << 20)) break;
+    p.chunk_len *= 2;
+  }
+  p.max_chunks = (int)(entries / p.chunk_len + keys + 1);
+  p.cstart = take((keys + 1) * 4); p.prow = take((keys + 1) * 4);
+  p.pk = take(rows * c.d * 4); p.pv = take(rows * c.d * 4);
   p.total = off;
   return p;
 }
@@ -162,6 +177,8 @@ int mfma_backward(const ssa_ctx &c, const void *q, const void *k, const void *v,
   w.sel_bits = (uint32_t *)(ws + p.bits); w.sel_counts = (uint32_t *)(ws + p.counts);
   w.sel_start = (int32_t *)(ws + p.start); w.sel_list = (int32_t *)(ws + p.list);
   w.q_splits = p.q_splits;
+  w.chunk_start = (int32_t *)(ws + p.cstart); w.part_row_start = (int32_t *)(ws + p.prow);
+  w.pK = (float *)(ws + p.pk); w.pV = (float *)(ws + p.pv); w.chunk_len = p.chunk_len; w.max_chunks = p.max_chunks;
   return mfma_backward_kernels(view, c.d, w, q, gates, out_branch, lse, topk_idx, dout, dq, dk, dv, dgates, c.blk, c.B,
                                c.stream);
 }
