@@ -45,6 +45,21 @@ __device__ inline int wave_max_i(int v) {
   return v;
 }
 
+// Sum over aligned groups of hs lanes (hs a power of two <= 16) inside each 16-lane row, with DPP lane
+// permutations only (no LDS traffic): xor 1, xor 2 by quad permutes; once the lanes of a quad agree, the
+// half-row and row mirrors act as xor 4 and xor 8.
+template <int CTRL>
+__device__ inline float dpp_add(float v) {
+  return v + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
+}
+__device__ inline float group_sum(float v, int hs) {
+  if (hs >= 2) v = dpp_add<0xB1>(v);    // quad_perm [1,0,3,2]
+  if (hs >= 4) v = dpp_add<0x4E>(v);    // quad_perm [2,3,0,1]
+  if (hs >= 8) v = dpp_add<0x141>(v);   // row_half_mirror
+  if (hs >= 16) v = dpp_add<0x140>(v);  // row_mirror
+  return v;
+}
+
 // Row of the A operand a lane feeds for sub-tile `a` of the key tile starting at kb.
 __device__ inline int tile_key_row(int kb, int a) {
   const int r = threadIdx.x & 15;

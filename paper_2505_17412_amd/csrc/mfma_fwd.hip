@@ -1,93 +1,19 @@
 // bf16 MFMA forward kernels of SSA (paper eq. (4)-(6), Algorithm 1, window paragraph) for gfx950.
 //
-// One wavefront owns 16 query rows = (16 / h_s) consecutive sorted tokens x the h_s heads of one KV group and
-// keeps their running softmax state in registers (Algorithm 1's m, l, o).  Scores are produced TRANSPOSED
-// (S^T = K Q^T, keys x queries) so that the probabilities land in the lanes exactly as the B operand of the
-// second contraction O^T = V^T P^T needs them; V is read from a copy stored in chunks of 8 tokens, transposed
-// inside each chunk, which makes every MFMA operand one 16-byte load.
+// A workgroup of 4 wavefronts owns 4*CB*16 query rows = consecutive sorted tokens x the h_s heads of one KV
+// group; each wavefront keeps CB blocks of 16 query columns and their running softmax state (Algorithm 1's
+// m, l, o) in registers.  Scores are produced TRANSPOSED (S^T = K Q^T, keys x queries) so that the
+// probabilities land in the lanes exactly as the B operand of the second contraction O^T = V^T P^T needs them;
+// V comes from a copy stored in chunks of 8 tokens, transposed inside each chunk.  Key tiles are staged through
+// LDS once per workgroup (see mfma_qc.h) and every MFMA A operand is one 16-byte LDS read shared by the CB
+// column blocks.
 #include "mfma_common.h"
 #include "topk_device.h"
 #include "mfma_launch.h"
+#include "mfma_qc.h"
 #include "profile.h"
 
 namespace {
-
-template <int D>
-struct FwdState {
-  f32x4 o[D / 16];  // o[dt][i]: output dim 16*dt + 4*quad + i of query column n
-  float m, l;       // running max (log2 domain) and this lane's share of the running sum
-};
-
-// Scores of one 32-key tile for the wave's 16 queries, scaled into the log2 domain.
-// v[j]: key kb + 8*quad + j, query n.
-template <int D>
-__device__ inline void score_tile(const bf16x8 (&qop)[D / 32], const bf16_t *__restrict__ Kg, size_t kstride, int kb,
-                                  float sl2, float (&v)[8]) {
-  const int quad = threadIdx.x >> 4 & 3;
-  const bf16_t *r0 = Kg + (size_t)tile_key_row(kb, 0) * kstride + 8 * quad;
-  const bf16_t *r1 = r0 + 4 * kstride;
-  f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int ks = 0; ks < D / 32; ++ks) {
-    s0 = mfma16(ld8(r0 + 32 * ks), qop[ks], s0);
-    s1 = mfma16(ld8(r1 + 32 * ks), qop[ks], s1);
-  }
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    v[i] = s0[i] * sl2;
-    v[4 + i] = s1[i] * sl2;
-  }
-}
-
-// One online-softmax step (Algorithm 1, inner loop body) over a 32-key tile.
-template <int D, bool MASK>
-__device__ inline void fwd_tile(FwdState<D> &st, const bf16x8 (&qop)[D / 32], const bf16_t *__restrict__ Kg,
-                                size_t kstride, const bf16_t *__restrict__ Vtg, size_t vchunk, int kb, int lo, int hi,
-                                float sl2) {
-  const int n = threadIdx.x & 15, quad = threadIdx.x >> 4 & 3;
-  float v[8];
-  score_tile<D>(qop, Kg, kstride, kb, sl2, v);
-  if (MASK) {
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int key = kb + 8 * quad + j;
-      if (key < lo || key >= hi) v[j] = -INFINITY;
-    }
-  }
-  float tmax = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
-  tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-  tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-  const float mn = fmaxf(st.m, tmax);
-  const float ms = mn == -INFINITY ? 0.f : mn;  // nothing seen yet: keep exp2 arguments finite or -inf
-  const float alpha = fast_exp2(st.m - ms);
-  float psum = 0.f;
-  bf16x8 pb;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const float p = fast_exp2(v[j] - ms);
-    psum += p;
-    pb[j] = (__bf16)p;
-  }
-  st.l = st.l * alpha + psum;
-  st.m = mn;
-  const bf16_t *vt = Vtg + (size_t)((kb >> 3) + quad) * vchunk + (size_t)n * 8;
-#pragma unroll
-  for (int dt = 0; dt < D / 16; ++dt) {
-    st.o[dt] *= alpha;
-    st.o[dt] = mfma16(ld8(vt + dt * 128), pb, st.o[dt]);
-  }
-}
-
-// All tiles of the key range [wlo, whi) (wave-uniform); each lane only sees keys inside its own [lo, hi).
-template <int D>
-__device__ inline void fwd_range(FwdState<D> &st, const bf16x8 (&qop)[D / 32], const bf16_t *Kg, size_t kstride,
-                                 const bf16_t *Vtg, size_t vchunk, int wlo, int whi, int lo, int hi, bool uniform,
-                                 float sl2) {
-  for (int kb = wlo & ~7; kb < whi; kb += 32) {
-    if (uniform && kb >= wlo && kb + 32 <= whi) fwd_tile<D, false>(st, qop, Kg, kstride, Vtg, vchunk, kb, lo, hi, sl2);
-    else fwd_tile<D, true>(st, qop, Kg, kstride, Vtg, vchunk, kb, lo, hi, sl2);
-  }
-}
 
 struct FwdArgs {
   MfmaView v;
@@ -97,54 +23,201 @@ struct FwdArgs {
   int32_t *idx;  // [N,Hkv,T]
 };
 
-struct Row {  // what a lane knows about its query column
-  int pos, tok, h;
-  bool valid;
+// The query rows of one wavefront: CB blocks of 16 columns; column n of block cb is workgroup row
+// (wave*CB + cb)*16 + n = (token slot) * h_s + (head inside the group).
+template <int D, int CB>
+struct QRows {
+  bf16x8 qop[CB][D / 32];
+  int slot[CB], pos[CB], tok[CB], h[CB];
+  bool valid[CB];
 };
 
-template <int D>
-__device__ inline Row load_query(const FwdArgs &a, int pos0, int g, bf16x8 (&qop)[D / 32]) {
-  const int n = threadIdx.x & 15, quad = threadIdx.x >> 4 & 3;
-  Row r;
-  r.pos = pos0 + n / a.v.hs;
-  r.valid = r.pos < a.v.N;
-  r.tok = r.valid ? a.v.perm[r.pos] : 0;
-  r.h = g * a.v.hs + n % a.v.hs;
-  const bf16_t *q = a.Q + ((size_t)r.tok * a.v.Hq + r.h) * D + 8 * quad;
+template <int D, int CB>
+__device__ inline void load_rows(const bf16_t *Q, const MfmaView &v, int wg_pos0, int g, QRows<D, CB> &q) {
+  const int wid = threadIdx.x >> 6, n = threadIdx.x & 15, quad = threadIdx.x >> 4 & 3;
 #pragma unroll
-  for (int ks = 0; ks < D / 32; ++ks) qop[ks] = r.valid ? ld8(q + 32 * ks) : zero8();
-  return r;
-}
-
-template <int D>
-__device__ inline void init_state(FwdState<D> &st) {
+  for (int cb = 0; cb < CB; ++cb) {
+    const int row = (wid * CB + cb) * 16 + n;
+    q.slot[cb] = row / v.hs;
+    q.pos[cb] = wg_pos0 + q.slot[cb];
+    q.valid[cb] = q.pos[cb] < v.N;
+    q.tok[cb] = q.valid[cb] ? v.perm[q.pos[cb]] : 0;
+    q.h[cb] = g * v.hs + row % v.hs;
+    const bf16_t *src = Q + ((size_t)q.tok[cb] * v.Hq + q.h[cb]) * D + 8 * quad;
 #pragma unroll
-  for (int dt = 0; dt < D / 16; ++dt) st.o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  st.m = -INFINITY;
-  st.l = 0.f;
-}
-
-// Normalise (Algorithm 1: o * exp(m - l)), store the branch output and its log-sum-exp; returns lse in log2 units.
-template <int D>
-__device__ inline float finish(const FwdArgs &a, FwdState<D> &st, int branch, const Row &r) {
-  const int quad = threadIdx.x >> 4 & 3;
-  float l = st.l;
-  l += __shfl_xor(l, 16);
-  l += __shfl_xor(l, 32);
-  const float inv = l > 0.f ? 1.0f / l : 0.f;
-  const float lse2 = l > 0.f ? st.m + __log2f(l) : -INFINITY;
-  if (r.valid) {
-    bf16_t *o = a.Ob + (((size_t)branch * a.v.N + r.tok) * a.v.Hq + r.h) * D + 4 * quad;
-#pragma unroll
-    for (int dt = 0; dt < D / 16; ++dt) {
-      bf16x4 w;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) w[i] = (__bf16)(st.o[dt][i] * inv);
-      *reinterpret_cast<bf16x4 *>(o + 16 * dt) = w;
-    }
-    if (quad == 0) a.lse[((size_t)branch * a.v.N + r.tok) * a.v.Hq + r.h] = lse2 * LN2;
+    for (int ks = 0; ks < D / 32; ++ks) q.qop[cb][ks] = q.valid[cb] ? ld8(src + 32 * ks) : zero8();
   }
-  return lse2;
+}
+
+template <int D, int CB>
+struct FwdState {
+  f32x4 o[CB][D / 16];  // o[cb][dt][i]: output dim 16*dt + 4*quad + i of query column n
+  float m[CB], l[CB];   // running max (raw score units) and this lane's share of the running sum
+};
+
+template <int D, int CB>
+__device__ inline void init_state(FwdState<D, CB> &st) {
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb) {
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) st.o[cb][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    st.m[cb] = -INFINITY;
+    st.l[cb] = 0.f;
+  }
+}
+
+// Raw transposed scores of the staged 32-key tile: s[cb][j] = <q column n of block cb, key kb + 8*quad + j>.
+template <int D, int CB>
+__device__ inline void score_tile(const bf16_t *ktile, const QRows<D, CB> &q, const bool (&act)[CB], float (&s)[CB][8]) {
+  f32x4 s0[CB], s1[CB];
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb) s0[cb] = s1[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int ks = 0; ks < D / 32; ++ks) {
+    const bf16x8 a0 = lds_row_operand<D>(ktile, 0, ks), a1 = lds_row_operand<D>(ktile, 1, ks);
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+      if (act[cb]) {
+        s0[cb] = mfma16(a0, q.qop[cb][ks], s0[cb]);
+        s1[cb] = mfma16(a1, q.qop[cb][ks], s1[cb]);
+      }
+  }
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      s[cb][i] = s0[cb][i];
+      s[cb][4 + i] = s1[cb][i];
+    }
+}
+
+// One online-softmax step (Algorithm 1, inner loop body) over the staged tile.  lo/hi: the keys each lane may
+// see; act: wave-uniform "this column block has keys in the current range".
+template <int D, int CB, bool MASK>
+__device__ inline void fwd_tile(FwdState<D, CB> &st, const QRows<D, CB> &q, const bf16_t *ktile, const bf16_t *vtile, int kb,
+                                const int (&lo)[CB], const int (&hi)[CB], const bool (&act)[CB], float sl2) {
+  const int quad = threadIdx.x >> 4 & 3;
+  float s[CB][8];
+  score_tile<D, CB>(ktile, q, act, s);
+  bf16x8 pb[CB];
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb) {
+    if (!act[cb]) continue;
+    float(&v)[8] = s[cb];
+    if (MASK) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int key = kb + 8 * quad + j;
+        if (key < lo[cb] || key >= hi[cb]) v[j] = -INFINITY;
+      }
+    }
+    float tmax = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+    const float mn = fmaxf(st.m[cb], tmax);
+    const float neg = mn == -INFINITY ? 0.f : -mn * sl2;  // nothing seen yet: keep exp2 arguments finite or -inf
+    const float alpha = fast_exp2(__builtin_fmaf(st.m[cb], sl2, neg));
+    float psum = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float p = fast_exp2(__builtin_fmaf(v[j], sl2, neg));
+      psum += p;
+      pb[cb][j] = (__bf16)p;
+    }
+    st.l[cb] = st.l[cb] * alpha + psum;
+    st.m[cb] = mn;
+    if (!__all(alpha == 1.0f)) {
+#pragma unroll
+      for (int dt = 0; dt < D / 16; ++dt) st.o[cb][dt] *= alpha;
+    }
+  }
+#pragma unroll
+  for (int dt = 0; dt < D / 16; ++dt) {
+    const bf16x8 av = lds_t_operand<D>(vtile, dt);
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+      if (act[cb]) st.o[cb][dt] = mfma16(av, pb[cb], st.o[cb][dt]);
+  }
+}
+
+// Normalise (Algorithm 1: o * exp(m - l)), store the branch output and its log-sum-exp; lse2[cb] in log2 units.
+template <int D, int CB>
+__device__ inline void finish(const FwdArgs &a, FwdState<D, CB> &st, int branch, const QRows<D, CB> &q, float (&lse2)[CB]) {
+  const int quad = threadIdx.x >> 4 & 3;
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb) {
+    float l = st.l[cb];
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    const float inv = l > 0.f ? 1.0f / l : 0.f;
+    lse2[cb] = l > 0.f ? st.m[cb] * a.v.sl2 + __log2f(l) : -INFINITY;
+    if (q.valid[cb]) {
+      bf16_t *o = a.Ob + (((size_t)branch * a.v.N + q.tok[cb]) * a.v.Hq + q.h[cb]) * D + 4 * quad;
+#pragma unroll
+      for (int dt = 0; dt < D / 16; ++dt) {
+        bf16x4 w;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = (__bf16)(st.o[cb][dt][i] * inv);
+        *reinterpret_cast<bf16x4 *>(o + 16 * dt) = w;
+      }
+      if (quad == 0) a.lse[((size_t)branch * a.v.N + q.tok[cb]) * a.v.Hq + q.h[cb]] = lse2[cb] * LN2;
+    }
+  }
+}
+
+// Walk the tiles of the key ranges rng_s/rng_e[0..nr) (LDS, workgroup-uniform): stage tile i+1 while tile i is
+// consumed.  enter(r) runs when the walk reaches range r, tile(stage, kb, r) consumes one staged tile.
+template <int D, int NROW, int NT, class Enter, class Tile>
+__device__ inline void run_pipeline(const TileSrc<NROW, NT> &src, bf16_t *stage0, const int *rng_s, const int *rng_e, int nr,
+                                    Enter enter, Tile tile) {
+  using L = StageLayout<D, NROW, NT>;
+  if (nr > 0) {
+    TileRegs<D, NROW, NT> regs;
+    TileIter it = iter_begin(rng_s, nr);
+    tile_load<D, NROW, NT>(regs, src, it.kb);
+    int buf = 0, cur_r = -1;
+    while (it.r < nr) {
+      bf16_t *st = stage0 + buf * L::ELEMS;
+      tile_store<D, NROW, NT>(regs, st);
+      __syncthreads();
+      const TileIter nx = iter_next(it, rng_s, rng_e, nr);
+      if (nx.r < nr) tile_load<D, NROW, NT>(regs, src, nx.kb);
+      if (it.r != cur_r) {
+        cur_r = it.r;
+        enter(cur_r);
+      }
+      tile(st, it.kb, cur_r);
+      it = nx;
+      buf ^= 1;
+    }
+  }
+  __syncthreads();
+}
+
+// Workgroup-wide [min lo, max hi) of the per-lane key ranges, and whether every row has exactly that range.
+// scratch: 3 ints of LDS.  Returns through rs, re, uniform (all workgroup-uniform).
+template <int CB>
+__device__ inline void wg_range(int *scratch, const int (&lo)[CB], const int (&hi)[CB], const bool (&valid)[CB], int &rs,
+                                int &re, bool &uniform) {
+  if (threadIdx.x == 0) { scratch[0] = 0x7fffffff; scratch[1] = 0; scratch[2] = 1; }
+  __syncthreads();
+  int wlo = 0x7fffffff, whi = 0;
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb)
+    if (valid[cb]) { wlo = min(wlo, lo[cb]); whi = max(whi, hi[cb]); }
+  wlo = wave_min_i(wlo);
+  whi = wave_max_i(whi);
+  if ((threadIdx.x & 63) == 0) { atomicMin(&scratch[0], wlo); atomicMax(&scratch[1], whi); }
+  __syncthreads();
+  rs = lds_uniform(&scratch[0]);
+  re = lds_uniform(&scratch[1]);
+  bool u = true;
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb) u = u && valid[cb] && lo[cb] == rs && hi[cb] == re;
+  if (!__all(u) && (threadIdx.x & 63) == 0) scratch[2] = 0;
+  __syncthreads();
+  uniform = lds_uniform(&scratch[2]) != 0;
+  if (re <= rs) { rs = 0; re = 0; }
 }
 
 // ---- top-k over unsigned fixed-point scores held in LDS by one wavefront (ties -> lowest id) ----
@@ -181,128 +254,245 @@ __device__ inline void topk_wave_u32(const uint32_t *S, int n, int T, int base, 
 
 constexpr float SCORE_FIX = 134217728.0f;  // 2^27: a row's scores sum to h_s <= 16 < 2^5
 
+// LDS plan of the compression kernel (bytes): two tile stages | 8 ints | scores [TW][s_max] | top-k marks [4][words]
+template <int D>
+__host__ __device__ inline size_t cmp_lds_bytes(int tw, int s_max) {
+  return (size_t)2 * StageLayout<D, 1, 1>::ELEMS * sizeof(bf16_t) + 32 + ((size_t)tw * s_max + 4 * ((s_max + 31) / 32)) * 4;
+}
+
 // Compression branch (eq. (4) first term over the mean-pooled keys of eq. (5)), then the selection scores of
 // eq. (6) accumulated per selection block in LDS as fixed-point integers (integer adds commute, so the result
 // does not depend on scheduling), then the top-k.
-template <int D>
+template <int D, int CB>
 __global__ __launch_bounds__(256) void m_cmp_fwd(FwdArgs a) {
-  extern __shared__ uint32_t lds[];
+  extern __shared__ __align__(16) unsigned char smem[];
+  using L = StageLayout<D, 1, 1>;
+  bf16_t *stage0 = (bf16_t *)smem;
+  int *ints = (int *)(stage0 + 2 * L::ELEMS);
   const int wid = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 15, quad = lane >> 4;
-  const int hs = a.v.hs, tpw = 16 / hs, g = blockIdx.y;
-  const int pos0 = (blockIdx.x * 4 + wid) * tpw;
-  if (pos0 >= a.v.N) return;
-  bf16x8 qop[D / 32];
-  const Row r = load_query<D>(a, pos0, g, qop);
-  const int item = r.valid ? a.v.tok_item[r.pos] : 0;
-  const int lo = r.valid ? a.v.cmp_batch[item] : 0, hi = r.valid ? a.v.cmp_batch[item + 1] : 0;
-  const int wlo = wave_min_i(r.valid ? lo : 0x7fffffff), whi = wave_max_i(hi);
-  const bool uniform = __all(r.valid && lo == wlo && hi == whi);
-  const size_t kstride = (size_t)a.v.Hkv * D, vchunk = kstride * 8;
-  const bf16_t *Kg = a.v.Kc + (size_t)g * D, *Vtg = a.v.Vct + (size_t)g * D * 8;
-  FwdState<D> st;
-  init_state(st);
-  fwd_range<D>(st, qop, Kg, kstride, Vtg, vchunk, wlo, whi, lo, hi, uniform, a.v.sl2);
-  const float lse2 = finish<D>(a, st, 0, r);
-  if (!a.idx) return;
-
-  // ---- selection scores, eq. (6)
-  const int s_max = a.v.s_max;
-  uint32_t *S = lds + (size_t)wid * tpw * s_max;
-  uint32_t *sel = lds + (size_t)4 * tpw * s_max + (size_t)wid * ((s_max + 31) >> 5);
-  for (int i = lane; i < tpw * s_max; i += 64) S[i] = 0u;
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  const int s0 = r.valid ? a.v.slc_batch[item] : 0;
-  uint32_t *Srow = S + (size_t)(n / hs) * s_max;
-  for (int kb = wlo & ~7; kb < whi; kb += 32) {
-    float v[8];
-    score_tile<D>(qop, Kg, kstride, kb, a.v.sl2, v);
-    float p[8];
+  const int hs = a.v.hs, g = blockIdx.y, s_max = a.v.s_max;
+  const int TW = 4 * CB * 16 / hs, wg_pos0 = blockIdx.x * TW;
+  uint32_t *S = (uint32_t *)(ints + 8);
+  uint32_t *sel = S + (size_t)TW * s_max + (size_t)wid * ((s_max + 31) >> 5);
+  QRows<D, CB> q;
+  load_rows<D, CB>(a.Q, a.v, wg_pos0, g, q);
+  int lo[CB], hi[CB], s0[CB];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int key = kb + 8 * quad + j;
-      p[j] = (key >= lo && key < hi) ? fast_exp2(v[j] - lse2) : 0.f;
-      for (int off = 1; off < hs; off <<= 1) p[j] += __shfl_xor(p[j], off);  // sum over the group's heads
-    }
-    if (r.valid && (n % hs) == 0) {
-      int cur = -1;
-      float acc = 0.f;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int key = kb + 8 * quad + j;
-        if (key >= lo && key < hi) {
-          const int b = a.v.cmp_slc[key] - s0;
-          if (b != cur) {
-            if (cur >= 0) atomicAdd(&Srow[cur], (uint32_t)(acc * SCORE_FIX));
-            cur = b;
-            acc = 0.f;
-          }
-          acc += p[j];
-        }
-      }
-      if (cur >= 0) atomicAdd(&Srow[cur], (uint32_t)(acc * SCORE_FIX));
-    }
+  for (int cb = 0; cb < CB; ++cb) {
+    const int item = q.valid[cb] ? a.v.tok_item[q.pos[cb]] : 0;
+    lo[cb] = q.valid[cb] ? a.v.cmp_batch[item] : 0;
+    hi[cb] = q.valid[cb] ? a.v.cmp_batch[item + 1] : 0;
+    s0[cb] = q.valid[cb] ? a.v.slc_batch[item] : 0;
   }
-  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  // ---- top-k, one token of the wave after the other
-  for (int tl = 0; tl < tpw; ++tl) {
-    const int pos = pos0 + tl;
+  int rs, re;
+  bool uniform;
+  wg_range<CB>(ints, lo, hi, q.valid, rs, re, uniform);
+  if (threadIdx.x == 0) { ints[4] = rs; ints[5] = re; }
+  __syncthreads();
+  const int nr = re > rs ? 1 : 0;
+  bool act[CB];
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb) act[cb] = true;
+  TileSrc<1, 1> src{{a.v.Kc + (size_t)g * D}, {a.v.Vct + (size_t)g * D * 8}, (size_t)a.v.Hkv * D};
+  FwdState<D, CB> st;
+  init_state(st);
+  const float sl2 = a.v.sl2;
+  run_pipeline<D, 1, 1>(
+      src, stage0, ints + 4, ints + 5, nr, [](int) {},
+      [&](const bf16_t *stg, int kb, int) {
+        if (uniform && kb >= rs && kb + 32 <= re)
+          fwd_tile<D, CB, false>(st, q, L::row_tile((bf16_t *)stg, 0), L::t_tile((bf16_t *)stg, 0), kb, lo, hi, act, sl2);
+        else
+          fwd_tile<D, CB, true>(st, q, L::row_tile((bf16_t *)stg, 0), L::t_tile((bf16_t *)stg, 0), kb, lo, hi, act, sl2);
+      });
+  float lse2[CB];
+  finish<D, CB>(a, st, 0, q, lse2);
+
+  // ---- selection scores, eq. (6): second walk over the pooled keys with the normaliser known
+  for (int i = threadIdx.x; i < TW * s_max; i += 256) S[i] = 0u;
+  __syncthreads();
+  TileSrc<1, 0> ksrc{{a.v.Kc + (size_t)g * D}, {}, (size_t)a.v.Hkv * D};
+  run_pipeline<D, 1, 0>(
+      ksrc, stage0, ints + 4, ints + 5, nr, [](int) {},
+      [&](const bf16_t *stg, int kb, int) {
+        float s[CB][8];
+        score_tile<D, CB>(stg, q, act, s);
+        const bool inner = uniform && kb >= rs && kb + 32 <= re;
+        const int hl = n % hs;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+          float p[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const int key = kb + 8 * quad + j;
+            const float e = fast_exp2(__builtin_fmaf(s[cb][j], sl2, -lse2[cb]));
+            p[j] = (inner || (key >= lo[cb] && key < hi[cb])) ? e : 0.f;
+            p[j] = group_sum(p[j], hs);  // sum over the group's heads (eq. (6), inner sum)
+          }
+          // every lane of a head group now holds the same 8 sums; lane hl adds the sums of keys j = hl (mod hs)
+          // onto their selection blocks (eq. (6), outer sum over the child blocks)
+          uint32_t *Srow = S + (size_t)q.slot[cb] * s_max;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const int key = kb + 8 * quad + j;
+            if (q.valid[cb] && (j % hs) == hl && hl < 8 && key >= lo[cb] && key < hi[cb])
+              atomicAdd(&Srow[a.v.cmp_slc[key] - s0[cb]], (uint32_t)(p[j] * SCORE_FIX));
+          }
+        }
+      });
+  // ---- top-k: each wavefront serves its own token slots, one after the other
+  const int spw = CB * 16 / hs;  // token slots per wavefront
+  for (int tl = 0; tl < spw; ++tl) {
+    const int slot = wid * spw + tl, pos = wg_pos0 + slot;
     if (pos >= a.v.N) break;
     const int tok = a.v.perm[pos], it = a.v.tok_item[pos];
     const int b0 = a.v.slc_batch[it], nb = a.v.slc_batch[it + 1] - b0;
-    topk_wave_u32(S + (size_t)tl * s_max, nb, a.v.T, b0, a.idx + ((size_t)tok * a.v.Hkv + g) * a.v.T, sel);
+    topk_wave_u32(S + (size_t)slot * s_max, nb, a.v.T, b0, a.idx + ((size_t)tok * a.v.Hkv + g) * a.v.T, sel);
   }
 }
 
-// Selection branch: Algorithm 1.  The wave's tokens walk the union of their selected blocks in ascending id;
-// a token that did not select the current block sees it fully masked.
+// LDS plan of the selection kernel (bytes): two stages | 8 ints | I rows [TW][T] | union bits | range lists 3 x [TW*T]
 template <int D>
+__host__ __device__ inline size_t slc_lds_bytes(int tw, int T, int Ns) {
+  return (size_t)2 * StageLayout<D, 1, 1>::ELEMS * sizeof(bf16_t) + 32 + ((size_t)tw * T * 4 + (size_t)(Ns + 31) / 32 + 4) * 4;
+}
+
+// Selection branch: Algorithm 1.  The workgroup walks the union of the blocks its tokens selected, in ascending
+// id; a token that did not select the current block sees it fully masked, a wavefront none of whose tokens
+// selected it skips the arithmetic.
+template <int D, int CB>
 __global__ __launch_bounds__(256) void m_slc_fwd(FwdArgs a) {
-  const int wid = threadIdx.x >> 6;
-  const int hs = a.v.hs, tpw = 16 / hs, g = blockIdx.y, T = a.v.T;
-  const int pos0 = (blockIdx.x * 4 + wid) * tpw;
-  if (pos0 >= a.v.N) return;
-  bf16x8 qop[D / 32];
-  const Row r = load_query<D>(a, pos0, g, qop);
-  const size_t kstride = (size_t)a.v.Hkv * D, vchunk = kstride * 8;
-  const bf16_t *Kg = a.v.Ks + (size_t)g * D, *Vtg = a.v.Vt + (size_t)g * D * 8;
-  const int32_t *row = a.idx + ((size_t)r.tok * a.v.Hkv + g) * T;
-  FwdState<D> st;
-  init_state(st);
-  int j = 0;
-  for (;;) {
-    const int cur = (r.valid && j < T) ? row[j] : -1;
-    const int key = cur < 0 ? 0x7fffffff : cur;
-    const int b = wave_min_i(key);
-    if (b == 0x7fffffff) break;
-    const bool sel = key == b;
-    if (sel) ++j;
-    const int bs = a.v.slc_start[b], be = a.v.slc_start[b + 1];
-    fwd_range<D>(st, qop, Kg, kstride, Vtg, vchunk, bs, be, sel ? bs : 0, sel ? be : 0, __all(sel), a.v.sl2);
+  extern __shared__ __align__(16) unsigned char smem[];
+  using L = StageLayout<D, 1, 1>;
+  bf16_t *stage0 = (bf16_t *)smem;
+  int *ints = (int *)(stage0 + 2 * L::ELEMS);
+  const int lane = threadIdx.x & 63;
+  const int hs = a.v.hs, g = blockIdx.y, T = a.v.T, Ns = a.v.Ns;
+  const int TW = 4 * CB * 16 / hs, wg_pos0 = blockIdx.x * TW;
+  int *Irows = ints + 8;                 // [TW][T]
+  int *ub = Irows + TW * T;              // union list: block ids
+  int *us = ub + TW * T, *ue = us + TW * T;
+  uint32_t *bits = (uint32_t *)(ue + TW * T);
+  const int words = (Ns + 31) >> 5;
+  QRows<D, CB> q;
+  load_rows<D, CB>(a.Q, a.v, wg_pos0, g, q);
+  for (int i = threadIdx.x; i < TW * T; i += 256) {
+    const int pos = wg_pos0 + i / T;
+    Irows[i] = pos < a.v.N ? a.idx[((size_t)a.v.perm[pos] * a.v.Hkv + g) * T + i % T] : -1;
   }
-  finish<D>(a, st, 1, r);
+  for (int i = threadIdx.x; i < words; i += 256) bits[i] = 0u;
+  __syncthreads();
+  for (int i = threadIdx.x; i < TW * T; i += 256) {
+    const int b = Irows[i];
+    if (b >= 0 && b < Ns) atomicOr(&bits[b >> 5], 1u << (b & 31));
+  }
+  __syncthreads();
+  if (threadIdx.x < 64) {  // ordered compaction of the union into (id, start, end) lists
+    int base = 0;
+    for (int w0 = 0; w0 < words; w0 += 64) {
+      uint32_t w = (w0 + lane) < words ? bits[w0 + lane] : 0u;
+      const int c = __popc(w);
+      int incl = c;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(incl, off);
+        if (lane >= off) incl += o;
+      }
+      int at = base + incl - c;
+      while (w) {
+        const int b = (w0 + lane) * 32 + __ffs(w) - 1;
+        ub[at] = b; us[at] = a.v.slc_start[b]; ue[at] = a.v.slc_start[b + 1];
+        ++at;
+        w &= w - 1;
+      }
+      base += __shfl(incl, 63);
+    }
+    if (lane == 0) ints[0] = base;
+  }
+  __syncthreads();
+  const int nr = lds_uniform(&ints[0]);
+  int jc[CB], lo[CB], hi[CB];
+  bool act[CB];
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb) { jc[cb] = 0; lo[cb] = hi[cb] = 0; act[cb] = false; }
+  TileSrc<1, 1> src{{a.v.Ks + (size_t)g * D}, {a.v.Vt + (size_t)g * D * 8}, (size_t)a.v.Hkv * D};
+  FwdState<D, CB> st;
+  init_state(st);
+  const float sl2 = a.v.sl2;
+  bool full = false;
+  int rs = 0, re = 0;
+  run_pipeline<D, 1, 1>(
+      src, stage0, us, ue, nr,
+      [&](int r) {
+        const int b = lds_uniform(&ub[r]);
+        rs = lds_uniform(&us[r]);
+        re = lds_uniform(&ue[r]);
+        bool all_sel = true;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+          const int cur = (q.valid[cb] && jc[cb] < T) ? Irows[q.slot[cb] * T + jc[cb]] : -1;
+          const bool sel = cur == b;
+          if (sel) ++jc[cb];
+          lo[cb] = sel ? rs : 0;
+          hi[cb] = sel ? re : 0;
+          act[cb] = __any(sel);
+          all_sel = all_sel && __all(sel);
+        }
+        full = all_sel;
+      },
+      [&](const bf16_t *stg, int kb, int) {
+        bool any = false;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) any = any || act[cb];
+        if (!any) return;
+        if (full && kb >= rs && kb + 32 <= re)
+          fwd_tile<D, CB, false>(st, q, L::row_tile((bf16_t *)stg, 0), L::t_tile((bf16_t *)stg, 0), kb, lo, hi, act, sl2);
+        else
+          fwd_tile<D, CB, true>(st, q, L::row_tile((bf16_t *)stg, 0), L::t_tile((bf16_t *)stg, 0), kb, lo, hi, act, sl2);
+      });
+  float lse2[CB];
+  finish<D, CB>(a, st, 1, q, lse2);
 }
 
 // Window branch: keys are the tokens of the query's own window.
-template <int D>
+template <int D, int CB>
 __global__ __launch_bounds__(256) void m_win_fwd(FwdArgs a) {
-  const int wid = threadIdx.x >> 6;
-  const int hs = a.v.hs, tpw = 16 / hs, g = blockIdx.y;
-  const int pos0 = (blockIdx.x * 4 + wid) * tpw;
-  if (pos0 >= a.v.N) return;
-  bf16x8 qop[D / 32];
-  const Row r = load_query<D>(a, pos0, g, qop);
-  const int w = r.valid ? a.v.tok_win[r.pos] : 0;
-  const int lo = r.valid ? a.v.win_start[w] : 0, hi = r.valid ? a.v.win_start[w + 1] : 0;
-  const int wlo = wave_min_i(r.valid ? lo : 0x7fffffff), whi = wave_max_i(hi);
-  const bool uniform = __all(r.valid && lo == wlo && hi == whi);
-  const size_t kstride = (size_t)a.v.Hkv * D, vchunk = kstride * 8;
-  FwdState<D> st;
+  extern __shared__ __align__(16) unsigned char smem[];
+  using L = StageLayout<D, 1, 1>;
+  bf16_t *stage0 = (bf16_t *)smem;
+  int *ints = (int *)(stage0 + 2 * L::ELEMS);
+  const int hs = a.v.hs, g = blockIdx.y;
+  const int TW = 4 * CB * 16 / hs, wg_pos0 = blockIdx.x * TW;
+  QRows<D, CB> q;
+  load_rows<D, CB>(a.Q, a.v, wg_pos0, g, q);
+  int lo[CB], hi[CB];
+  bool act[CB];
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb) {
+    const int w = q.valid[cb] ? a.v.tok_win[q.pos[cb]] : 0;
+    lo[cb] = q.valid[cb] ? a.v.win_start[w] : 0;
+    hi[cb] = q.valid[cb] ? a.v.win_start[w + 1] : 0;
+    act[cb] = true;
+  }
+  int rs, re;
+  bool uniform;
+  wg_range<CB>(ints, lo, hi, q.valid, rs, re, uniform);
+  if (threadIdx.x == 0) { ints[4] = rs; ints[5] = re; }
+  __syncthreads();
+  TileSrc<1, 1> src{{a.v.Ks + (size_t)g * D}, {a.v.Vt + (size_t)g * D * 8}, (size_t)a.v.Hkv * D};
+  FwdState<D, CB> st;
   init_state(st);
-  fwd_range<D>(st, qop, a.v.Ks + (size_t)g * D, kstride, a.v.Vt + (size_t)g * D * 8, vchunk, wlo, whi, lo, hi, uniform,
-               a.v.sl2);
-  finish<D>(a, st, 2, r);
+  const float sl2 = a.v.sl2;
+  run_pipeline<D, 1, 1>(
+      src, stage0, ints + 4, ints + 5, re > rs ? 1 : 0, [](int) {},
+      [&](const bf16_t *stg, int kb, int) {
+        if (uniform && kb >= rs && kb + 32 <= re)
+          fwd_tile<D, CB, false>(st, q, L::row_tile((bf16_t *)stg, 0), L::t_tile((bf16_t *)stg, 0), kb, lo, hi, act, sl2);
+        else
+          fwd_tile<D, CB, true>(st, q, L::row_tile((bf16_t *)stg, 0), L::t_tile((bf16_t *)stg, 0), kb, lo, hi, act, sl2);
+      });
+  float lse2[CB];
+  finish<D, CB>(a, st, 2, q, lse2);
 }
 
 // eq. (4): out = sum_b gate_b * out_b, 8 elements per thread.
@@ -327,21 +517,31 @@ __global__ void m_combine(const bf16_t *__restrict__ Ob, const bf16_t *__restric
   *reinterpret_cast<bf16x8 *>(out + off) = o;
 }
 
+constexpr int FWD_CB = 1;  // blocks of 16 query columns per wavefront
+
 template <int D>
-int launch_forward(const FwdArgs &a, const bf16_t *gates, bf16_t *out, size_t lds_bytes, hipStream_t s) {
-  const int tpw = 16 / a.v.hs;
-  const dim3 grid((a.v.N + 4 * tpw - 1) / (4 * tpw), a.v.Hkv);
+int launch_forward(const FwdArgs &a, const bf16_t *gates, bf16_t *out, hipStream_t s) {
+  const int tw = 4 * FWD_CB * 16 / a.v.hs;
+  const dim3 grid((a.v.N + tw - 1) / tw, a.v.Hkv);
+  const size_t lds_cmp = cmp_lds_bytes<D>(tw, a.v.s_max), lds_slc = slc_lds_bytes<D>(tw, a.v.T, a.v.Ns);
+  const size_t lds_win = (size_t)2 * StageLayout<D, 1, 1>::ELEMS * sizeof(bf16_t) + 32;
+  static bool attr_done = false;  // raise the dynamic LDS limit once per process for these instantiations
+  if (!attr_done) {
+    (void)hipFuncSetAttribute((const void *)m_cmp_fwd<D, FWD_CB>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    (void)hipFuncSetAttribute((const void *)m_slc_fwd<D, FWD_CB>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    attr_done = true;
+  }
   {
     ProfScope ps(PROF_CMP_FWD, s);
-    m_cmp_fwd<D><<<grid, 256, lds_bytes, s>>>(a);
+    m_cmp_fwd<D, FWD_CB><<<grid, 256, lds_cmp, s>>>(a);
   }
   {
     ProfScope ps(PROF_SLC_FWD, s);
-    m_slc_fwd<D><<<grid, 256, 0, s>>>(a);
+    m_slc_fwd<D, FWD_CB><<<grid, 256, lds_slc, s>>>(a);
   }
   {
     ProfScope ps(PROF_WIN_FWD, s);
-    m_win_fwd<D><<<grid, 256, 0, s>>>(a);
+    m_win_fwd<D, FWD_CB><<<grid, 256, lds_win, s>>>(a);
   }
   {
     ProfScope ps(PROF_COMBINE, s);
@@ -353,19 +553,25 @@ int launch_forward(const FwdArgs &a, const bf16_t *gates, bf16_t *out, size_t ld
 
 }  // namespace
 
-size_t mfma_cmp_lds_bytes(int hs, int s_max) {
-  const int tpw = 16 / hs;
-  return ((size_t)4 * tpw * s_max + (size_t)4 * ((s_max + 31) / 32) + 16) * sizeof(uint32_t);
+// Largest dynamic LDS request of the forward kernels for this problem (bytes).
+size_t mfma_fwd_lds_bytes(int D, int hs, int s_max, int T, int Ns) {
+  const int tw = 4 * FWD_CB * 16 / hs;
+  size_t a = 0, b = 0;
+  switch (D) {
+    case 32: a = cmp_lds_bytes<32>(tw, s_max); b = slc_lds_bytes<32>(tw, T, Ns); break;
+    case 64: a = cmp_lds_bytes<64>(tw, s_max); b = slc_lds_bytes<64>(tw, T, Ns); break;
+    default: a = cmp_lds_bytes<128>(tw, s_max); b = slc_lds_bytes<128>(tw, T, Ns); break;
+  }
+  return a > b ? a : b;
 }
 
 int mfma_forward_kernels(const MfmaView &v, int D, const void *q, const void *gates, void *out, float *lse,
                          int32_t *idx, void *out_branch, hipStream_t s) {
   FwdArgs a{v, (const bf16_t *)q, (bf16_t *)out_branch, lse, idx};
-  const size_t lds = mfma_cmp_lds_bytes(v.hs, v.s_max);
   switch (D) {
-    case 32: return launch_forward<32>(a, (const bf16_t *)gates, (bf16_t *)out, lds, s);
-    case 64: return launch_forward<64>(a, (const bf16_t *)gates, (bf16_t *)out, lds, s);
-    case 128: return launch_forward<128>(a, (const bf16_t *)gates, (bf16_t *)out, lds, s);
+    case 32: return launch_forward<32>(a, (const bf16_t *)gates, (bf16_t *)out, s);
+    case 64: return launch_forward<64>(a, (const bf16_t *)gates, (bf16_t *)out, s);
+    case 128: return launch_forward<128>(a, (const bf16_t *)gates, (bf16_t *)out, s);
     default: return SSA_ERR_UNSUPPORTED;
   }
 }

@@ -2,7 +2,7 @@
 #pragma once
 #include "mfma_common.h"
 
-size_t mfma_cmp_lds_bytes(int hs, int s_max);
+size_t mfma_fwd_lds_bytes(int D, int hs, int s_max, int T, int Ns);
 int mfma_forward_kernels(const MfmaView &v, int D, const void *q, const void *gates, void *out, float *lse,
                          int32_t *idx, void *out_branch, hipStream_t s);
 

@@ -144,7 +144,7 @@ bool mfma_supported(const ssa_ctx &c) {
   if (c.dtype != SSA_BF16) return false;
   if (c.d != 32 && c.d != 64 && c.d != 128) return false;
   if (c.hs != 1 && c.hs != 2 && c.hs != 4 && c.hs != 8 && c.hs != 16) return false;
-  if (mfma_cmp_lds_bytes(c.hs, c.blk->s_max) > 64 * 1024) return false;
+  if (mfma_fwd_lds_bytes(c.d, c.hs, c.blk->s_max, c.T, c.blk->Ns) > 150 * 1024) return false;
   return true;
 }
 
