@@ -12,6 +12,7 @@
 //     that the contractions over query rows get 16-byte operands.
 #include "mfma_common.h"
 #include "mfma_launch.h"
+#include "mfma_qc.h"
 #include "profile.h"
 
 namespace {
@@ -91,125 +92,190 @@ struct DqArgs {
   bf16_t *dQ;
 };
 
-template <int D>
-struct DqState {
-  f32x4 acc[D / 16];  // dQ^T: dim 16*dt + 4*quad + i of query column n
-};
-
-// One 32-key tile: transposed scores and dP, then dQ^T += K^T dS^T.
-template <int D, bool MASK>
-__device__ inline void dq_tile(DqState<D> &st, const bf16x8 (&qop)[D / 32], const bf16x8 (&dop)[D / 32],
-                               const bf16_t *__restrict__ Kg, const bf16_t *__restrict__ Vg, size_t kstride,
-                               const bf16_t *__restrict__ Ktg, size_t kchunk, int kb, int lo, int hi, float sl2,
-                               float scale, float lse2, float delta, float gw) {
-  const int n = threadIdx.x & 15, quad = threadIdx.x >> 4 & 3;
-  const size_t r0 = (size_t)tile_key_row(kb, 0) * kstride + 8 * quad, r1 = r0 + 4 * kstride;
-  f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0, p0 = s0, p1 = s0;
+// One staged 32-key tile: transposed scores (K rows) and dP (V rows), then dQ^T += K^T dS^T (transposed K tile).
+// lse2 is +inf for a column whose token did not select the current block, which makes its P exactly zero.
+template <int D, int CB, bool MASK>
+__device__ inline void dq_tile(f32x4 (&acc)[CB][D / 16], const QRows<D, CB> &q, const bf16x8 (&dop)[CB][D / 32],
+                               const bf16_t *ktile, const bf16_t *vtile, const bf16_t *kttile, int kb, const int (&lo)[CB],
+                               const int (&hi)[CB], const bool (&act)[CB], float sl2, float scale, const float (&lse2)[CB],
+                               const float (&delta)[CB], const float (&gw)[CB]) {
+  const int quad = threadIdx.x >> 4 & 3;
+  f32x4 s0[CB], s1[CB], p0[CB], p1[CB];
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb) s0[cb] = s1[cb] = p0[cb] = p1[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int ks = 0; ks < D / 32; ++ks) {
-    s0 = mfma16(ld8(Kg + r0 + 32 * ks), qop[ks], s0);
-    s1 = mfma16(ld8(Kg + r1 + 32 * ks), qop[ks], s1);
-    p0 = mfma16(ld8(Vg + r0 + 32 * ks), dop[ks], p0);
-    p1 = mfma16(ld8(Vg + r1 + 32 * ks), dop[ks], p1);
-  }
-  bf16x8 dsb;
+    const bf16x8 k0 = lds_row_operand<D>(ktile, 0, ks), k1 = lds_row_operand<D>(ktile, 1, ks);
+    const bf16x8 v0 = lds_row_operand<D>(vtile, 0, ks), v1 = lds_row_operand<D>(vtile, 1, ks);
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const float s = (j < 4 ? s0[j & 3] : s1[j & 3]) * sl2;
-    const float dp = j < 4 ? p0[j & 3] : p1[j & 3];
-    float p = fast_exp2(s - lse2);
-    if (MASK) {
-      const int key = kb + 8 * quad + j;
-      if (key < lo || key >= hi) p = 0.f;
+    for (int cb = 0; cb < CB; ++cb)
+      if (act[cb]) {
+        s0[cb] = mfma16(k0, q.qop[cb][ks], s0[cb]);
+        s1[cb] = mfma16(k1, q.qop[cb][ks], s1[cb]);
+        p0[cb] = mfma16(v0, dop[cb][ks], p0[cb]);
+        p1[cb] = mfma16(v1, dop[cb][ks], p1[cb]);
+      }
+  }
+  bf16x8 dsb[CB];
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb) {
+    if (!act[cb]) continue;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float sv = j < 4 ? s0[cb][j & 3] : s1[cb][j & 3];
+      const float dp = j < 4 ? p0[cb][j & 3] : p1[cb][j & 3];
+      float p = fast_exp2(__builtin_fmaf(sv, sl2, -lse2[cb]));
+      if (MASK) {
+        const int key = kb + 8 * quad + j;
+        if (key < lo[cb] || key >= hi[cb]) p = 0.f;
+      }
+      dsb[cb][j] = (__bf16)(p * __builtin_fmaf(gw[cb], dp, -delta[cb]) * scale);
     }
-    dsb[j] = (__bf16)(p * (gw * dp - delta) * scale);
   }
-  const bf16_t *kt = Ktg + (size_t)((kb >> 3) + quad) * kchunk + (size_t)n * 8;
 #pragma unroll
-  for (int dt = 0; dt < D / 16; ++dt) st.acc[dt] = mfma16(ld8(kt + dt * 128), dsb, st.acc[dt]);
-}
-
-template <int D>
-__device__ inline void dq_range(DqState<D> &st, const bf16x8 (&qop)[D / 32], const bf16x8 (&dop)[D / 32],
-                                const bf16_t *Kg, const bf16_t *Vg, size_t kstride, const bf16_t *Ktg, size_t kchunk,
-                                int wlo, int whi, int lo, int hi, bool uniform, float sl2, float scale, float lse2,
-                                float delta, float gw) {
-  for (int kb = wlo & ~7; kb < whi; kb += 32) {
-    if (uniform && kb >= wlo && kb + 32 <= whi)
-      dq_tile<D, false>(st, qop, dop, Kg, Vg, kstride, Ktg, kchunk, kb, lo, hi, sl2, scale, lse2, delta, gw);
-    else
-      dq_tile<D, true>(st, qop, dop, Kg, Vg, kstride, Ktg, kchunk, kb, lo, hi, sl2, scale, lse2, delta, gw);
+  for (int dt = 0; dt < D / 16; ++dt) {
+    const bf16x8 kt = lds_t_operand<D>(kttile, dt);
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+      if (act[cb]) acc[cb][dt] = mfma16(kt, dsb[cb], acc[cb][dt]);
   }
 }
 
+// LDS plan of the dQ kernel (bytes): two stages (K rows, V rows, K transposed) | 8 ints | selection lists as in the
+// forward selection kernel.
 template <int D>
+__host__ __device__ inline size_t dq_lds_bytes(int tw, int T, int Ns) {
+  return (size_t)2 * StageLayout<D, 2, 1>::ELEMS * sizeof(bf16_t) + 32 + ((size_t)tw * T * 4 + (size_t)(Ns + 31) / 32 + 4) * 4;
+}
+
+template <int D, int CB>
 __global__ __launch_bounds__(256) void m_bwd_dq(DqArgs a) {
-  const int wid = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 15, quad = lane >> 4;
-  const int hs = a.v.hs, tpw = 16 / hs, g = blockIdx.y, T = a.v.T, N = a.v.N;
-  const int pos0 = (blockIdx.x * 4 + wid) * tpw;
-  if (pos0 >= N) return;
-  const int pos = pos0 + n / hs;
-  const bool valid = pos < N;
-  const int tok = valid ? a.v.perm[pos] : 0;
-  const int h = g * hs + n % hs;
-  bf16x8 qop[D / 32], dop[D / 32];
-  {
-    const size_t off = ((size_t)tok * a.v.Hq + h) * D + 8 * quad;
+  extern __shared__ __align__(16) unsigned char smem[];
+  using L = StageLayout<D, 2, 1>;
+  bf16_t *stage0 = (bf16_t *)smem;
+  int *ints = (int *)(stage0 + 2 * L::ELEMS);
+  const int quad = threadIdx.x >> 4 & 3;
+  const int hs = a.v.hs, g = blockIdx.y, T = a.v.T, N = a.v.N, Ns = a.v.Ns;
+  const int TW = 4 * CB * 16 / hs, wg_pos0 = blockIdx.x * TW;
+  int *Irows = ints + 8;
+  int *ub = Irows + TW * T, *us = ub + TW * T, *ue = us + TW * T;
+  uint32_t *bits = (uint32_t *)(ue + TW * T);
+  QRows<D, CB> q;
+  load_rows<D, CB>(a.Q, a.v, wg_pos0, g, q);
+  bf16x8 dop[CB][D / 32];
+  size_t rs_[CB];
 #pragma unroll
-    for (int ks = 0; ks < D / 32; ++ks) {
-      qop[ks] = valid ? ld8(a.Q + off + 32 * ks) : zero8();
-      dop[ks] = valid ? ld8(a.dO + off + 32 * ks) : zero8();
-    }
+  for (int cb = 0; cb < CB; ++cb) {
+    const bf16_t *src = a.dO + ((size_t)q.tok[cb] * a.v.Hq + q.h[cb]) * D + 8 * quad;
+#pragma unroll
+    for (int ks = 0; ks < D / 32; ++ks) dop[cb][ks] = q.valid[cb] ? ld8(src + 32 * ks) : zero8();
+    rs_[cb] = (size_t)(q.valid[cb] ? q.pos[cb] : 0) * a.v.Hq + q.h[cb];
   }
-  const size_t kstride = (size_t)a.v.Hkv * D, kchunk = kstride * 8;
-  const size_t NH = (size_t)N * a.v.Hq, rs = (size_t)(valid ? pos : 0) * a.v.Hq + h;
-  DqState<D> st;
+  const size_t NH = (size_t)N * a.v.Hq;
+  f32x4 acc[CB][D / 16];
 #pragma unroll
-  for (int dt = 0; dt < D / 16; ++dt) st.acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) acc[cb][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
   const float sl2 = a.v.sl2, scale = a.v.scale;
-  // compression branch
-  {
-    const int item = valid ? a.v.tok_item[pos] : 0;
-    const int lo = valid ? a.v.cmp_batch[item] : 0, hi = valid ? a.v.cmp_batch[item + 1] : 0;
-    const int wlo = wave_min_i(valid ? lo : 0x7fffffff), whi = wave_max_i(hi);
-    const bool uniform = __all(valid && lo == wlo && hi == whi);
-    dq_range<D>(st, qop, dop, a.v.Kc + (size_t)g * D, a.v.Vc + (size_t)g * D, kstride, a.v.Kct + (size_t)g * D * 8, kchunk,
-                wlo, whi, lo, hi, uniform, sl2, scale, a.lse2s[rs], a.deltas[rs], a.gws[rs]);
-  }
-  const bf16_t *Kg = a.v.Ks + (size_t)g * D, *Vg = a.v.Vs + (size_t)g * D, *Ktg = a.v.Kt + (size_t)g * D * 8;
-  // selection branch
-  {
-    const float lse2 = a.lse2s[NH + rs], delta = a.deltas[NH + rs], gw = a.gws[NH + rs];
-    const int32_t *row = a.idx + ((size_t)tok * a.v.Hkv + g) * T;
-    int j = 0;
-    for (;;) {
-      const int cur = (valid && j < T) ? row[j] : -1;
-      const int key = cur < 0 ? 0x7fffffff : cur;
-      const int b = wave_min_i(key);
-      if (b == 0x7fffffff) break;
-      const bool sel = key == b;
-      if (sel) ++j;
-      const int bs = a.v.slc_start[b], be = a.v.slc_start[b + 1];
-      dq_range<D>(st, qop, dop, Kg, Vg, kstride, Ktg, kchunk, bs, be, sel ? bs : 0, sel ? be : 0, __all(sel), sl2, scale,
-                  lse2, delta, gw);
+  const size_t kstride = (size_t)a.v.Hkv * D;
+  int lo[CB], hi[CB];
+  bool act[CB];
+  float lse2[CB], delta[CB], gw[CB];
+
+  // ---- compression and window branches: one key range, per-lane [lo, hi)
+  for (int branch = 0; branch < 3; branch += 2) {
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+      if (branch == 0) {
+        const int item = q.valid[cb] ? a.v.tok_item[q.pos[cb]] : 0;
+        lo[cb] = q.valid[cb] ? a.v.cmp_batch[item] : 0;
+        hi[cb] = q.valid[cb] ? a.v.cmp_batch[item + 1] : 0;
+      } else {
+        const int w = q.valid[cb] ? a.v.tok_win[q.pos[cb]] : 0;
+        lo[cb] = q.valid[cb] ? a.v.win_start[w] : 0;
+        hi[cb] = q.valid[cb] ? a.v.win_start[w + 1] : 0;
+      }
+      act[cb] = true;
+      lse2[cb] = a.lse2s[branch * NH + rs_[cb]];
+      delta[cb] = a.deltas[branch * NH + rs_[cb]];
+      gw[cb] = a.gws[branch * NH + rs_[cb]];
     }
+    int rs, re;
+    bool uniform;
+    wg_range<CB>(ints, lo, hi, q.valid, rs, re, uniform);
+    if (threadIdx.x == 0) { ints[4] = rs; ints[5] = re; }
+    __syncthreads();
+    TileSrc<2, 1> src = branch == 0
+        ? TileSrc<2, 1>{{a.v.Kc + (size_t)g * D, a.v.Vc + (size_t)g * D}, {a.v.Kct + (size_t)g * D * 8}, kstride}
+        : TileSrc<2, 1>{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, {a.v.Kt + (size_t)g * D * 8}, kstride};
+    run_pipeline<D, 2, 1>(
+        src, stage0, ints + 4, ints + 5, re > rs ? 1 : 0, [](int) {},
+        [&](const bf16_t *stg, int kb, int) {
+          bf16_t *st = (bf16_t *)stg;
+          if (uniform && kb >= rs && kb + 32 <= re)
+            dq_tile<D, CB, false>(acc, q, dop, L::row_tile(st, 0), L::row_tile(st, 1), L::t_tile(st, 0), kb, lo, hi, act, sl2,
+                                  scale, lse2, delta, gw);
+          else
+            dq_tile<D, CB, true>(acc, q, dop, L::row_tile(st, 0), L::row_tile(st, 1), L::t_tile(st, 0), kb, lo, hi, act, sl2,
+                                 scale, lse2, delta, gw);
+        });
   }
-  // window branch
+  // ---- selection branch: union of the selected blocks of the workgroup's tokens
   {
-    const int w = valid ? a.v.tok_win[pos] : 0;
-    const int lo = valid ? a.v.win_start[w] : 0, hi = valid ? a.v.win_start[w + 1] : 0;
-    const int wlo = wave_min_i(valid ? lo : 0x7fffffff), whi = wave_max_i(hi);
-    const bool uniform = __all(valid && lo == wlo && hi == whi);
-    dq_range<D>(st, qop, dop, Kg, Vg, kstride, Ktg, kchunk, wlo, whi, lo, hi, uniform, sl2, scale, a.lse2s[2 * NH + rs],
-                a.deltas[2 * NH + rs], a.gws[2 * NH + rs]);
+    build_union(a.v, a.idx, wg_pos0, g, TW, Irows, ub, us, ue, bits, &ints[0]);
+    const int nr = lds_uniform(&ints[0]);
+    int jc[CB];
+    float lse_own[CB];
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+      jc[cb] = 0; lo[cb] = hi[cb] = 0; act[cb] = false;
+      lse_own[cb] = a.lse2s[NH + rs_[cb]];
+      delta[cb] = a.deltas[NH + rs_[cb]];
+      gw[cb] = a.gws[NH + rs_[cb]];
+    }
+    int rs = 0, re = 0;
+    TileSrc<2, 1> src{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, {a.v.Kt + (size_t)g * D * 8}, kstride};
+    run_pipeline<D, 2, 1>(
+        src, stage0, us, ue, nr,
+        [&](int r) {
+          const int b = lds_uniform(&ub[r]);
+          rs = lds_uniform(&us[r]);
+          re = lds_uniform(&ue[r]);
+#pragma unroll
+          for (int cb = 0; cb < CB; ++cb) {
+            const int cur = (q.valid[cb] && jc[cb] < T) ? Irows[q.slot[cb] * T + jc[cb]] : -1;
+            const bool sel = cur == b;
+            if (sel) ++jc[cb];
+            lo[cb] = sel ? rs : 0;
+            hi[cb] = sel ? re : 0;
+            lse2[cb] = sel ? lse_own[cb] : INFINITY;
+            act[cb] = __any(sel);
+          }
+        },
+        [&](const bf16_t *stg, int kb, int) {
+          bool any = false;
+#pragma unroll
+          for (int cb = 0; cb < CB; ++cb) any = any || act[cb];
+          if (!any) return;
+          bf16_t *st = (bf16_t *)stg;
+          if (kb >= rs && kb + 32 <= re)
+            dq_tile<D, CB, false>(acc, q, dop, L::row_tile(st, 0), L::row_tile(st, 1), L::t_tile(st, 0), kb, lo, hi, act, sl2,
+                                  scale, lse2, delta, gw);
+          else
+            dq_tile<D, CB, true>(acc, q, dop, L::row_tile(st, 0), L::row_tile(st, 1), L::t_tile(st, 0), kb, lo, hi, act, sl2,
+                                 scale, lse2, delta, gw);
+        });
   }
-  if (valid) {
-    bf16_t *o = a.dQ + ((size_t)tok * a.v.Hq + h) * D + 4 * quad;
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb) {
+    if (!q.valid[cb]) continue;
+    bf16_t *o = a.dQ + ((size_t)q.tok[cb] * a.v.Hq + q.h[cb]) * D + 4 * quad;
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt) {
       bf16x4 w;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) w[i] = (__bf16)st.acc[dt][i];
+      for (int i = 0; i < 4; ++i) w[i] = (__bf16)acc[cb][dt][i];
       *reinterpret_cast<bf16x4 *>(o + 16 * dt) = w;
     }
   }
@@ -546,8 +612,14 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
   {
     ProfScope ps(PROF_BWD_DQ, s);
     DqArgs a{v, (const bf16_t *)q, (const bf16_t *)dout, idx, w.lse2s, w.deltas, w.gws, (bf16_t *)dq};
-    const int tpw = 16 / v.hs;
-    m_bwd_dq<D><<<dim3((N + 4 * tpw - 1) / (4 * tpw), Hkv), 256, 0, s>>>(a);
+    constexpr int CB = 1;
+    const int tw = 4 * CB * 16 / v.hs;
+    static bool attr_done = false;
+    if (!attr_done) {
+      (void)hipFuncSetAttribute((const void *)m_bwd_dq<D, CB>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      attr_done = true;
+    }
+    m_bwd_dq<D, CB><<<dim3((N + tw - 1) / tw, Hkv), 256, dq_lds_bytes<D>(tw, v.T, v.Ns), s>>>(a);
   }
   constexpr int WG_KEYS = 64 * KB_KEYS;
   DkvArgs base{v, (const bf16_t *)q, (const bf16_t *)dout, w.QT, w.dOT, nullptr, nullptr, nullptr, w.sel_start, w.sel_list,

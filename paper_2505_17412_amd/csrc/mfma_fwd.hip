@@ -23,32 +23,6 @@ struct FwdArgs {
   int32_t *idx;  // [N,Hkv,T]
 };
 
-// The query rows of one wavefront: CB blocks of 16 columns; column n of block cb is workgroup row
-// (wave*CB + cb)*16 + n = (token slot) * h_s + (head inside the group).
-template <int D, int CB>
-struct QRows {
-  bf16x8 qop[CB][D / 32];
-  int slot[CB], pos[CB], tok[CB], h[CB];
-  bool valid[CB];
-};
-
-template <int D, int CB>
-__device__ inline void load_rows(const bf16_t *Q, const MfmaView &v, int wg_pos0, int g, QRows<D, CB> &q) {
-  const int wid = threadIdx.x >> 6, n = threadIdx.x & 15, quad = threadIdx.x >> 4 & 3;
-#pragma unroll
-  for (int cb = 0; cb < CB; ++cb) {
-    const int row = (wid * CB + cb) * 16 + n;
-    q.slot[cb] = row / v.hs;
-    q.pos[cb] = wg_pos0 + q.slot[cb];
-    q.valid[cb] = q.pos[cb] < v.N;
-    q.tok[cb] = q.valid[cb] ? v.perm[q.pos[cb]] : 0;
-    q.h[cb] = g * v.hs + row % v.hs;
-    const bf16_t *src = Q + ((size_t)q.tok[cb] * v.Hq + q.h[cb]) * D + 8 * quad;
-#pragma unroll
-    for (int ks = 0; ks < D / 32; ++ks) q.qop[cb][ks] = q.valid[cb] ? ld8(src + 32 * ks) : zero8();
-  }
-}
-
 template <int D, int CB>
 struct FwdState {
   f32x4 o[CB][D / 16];  // o[cb][dt][i]: output dim 16*dt + 4*quad + i of query column n
@@ -163,93 +137,6 @@ __device__ inline void finish(const FwdArgs &a, FwdState<D, CB> &st, int branch,
       if (quad == 0) a.lse[((size_t)branch * a.v.N + q.tok[cb]) * a.v.Hq + q.h[cb]] = lse2[cb] * LN2;
     }
   }
-}
-
-// Walk the tiles of the key ranges rng_s/rng_e[0..nr) (LDS, workgroup-uniform): stage tile i+1 while tile i is
-// consumed.  enter(r) runs when the walk reaches range r, tile(stage, kb, r) consumes one staged tile.
-template <int D, int NROW, int NT, class Enter, class Tile>
-__device__ inline void run_pipeline(const TileSrc<NROW, NT> &src, bf16_t *stage0, const int *rng_s, const int *rng_e, int nr,
-                                    Enter enter, Tile tile) {
-  using L = StageLayout<D, NROW, NT>;
-  if (nr > 0) {
-    TileRegs<D, NROW, NT> regs;
-    TileIter it = iter_begin(rng_s, nr);
-    tile_load<D, NROW, NT>(regs, src, it.kb);
-    int buf = 0, cur_r = -1;
-    while (it.r < nr) {
-      bf16_t *st = stage0 + buf * L::ELEMS;
-      tile_store<D, NROW, NT>(regs, st);
-      __syncthreads();
-      const TileIter nx = iter_next(it, rng_s, rng_e, nr);
-      if (nx.r < nr) tile_load<D, NROW, NT>(regs, src, nx.kb);
-      if (it.r != cur_r) {
-        cur_r = it.r;
-        enter(cur_r);
-      }
-      tile(st, it.kb, cur_r);
-      it = nx;
-      buf ^= 1;
-    }
-  }
-  __syncthreads();
-}
-
-// Workgroup-wide [min lo, max hi) of the per-lane key ranges, and whether every row has exactly that range.
-// scratch: 3 ints of LDS.  Returns through rs, re, uniform (all workgroup-uniform).
-template <int CB>
-__device__ inline void wg_range(int *scratch, const int (&lo)[CB], const int (&hi)[CB], const bool (&valid)[CB], int &rs,
-                                int &re, bool &uniform) {
-  if (threadIdx.x == 0) { scratch[0] = 0x7fffffff; scratch[1] = 0; scratch[2] = 1; }
-  __syncthreads();
-  int wlo = 0x7fffffff, whi = 0;
-#pragma unroll
-  for (int cb = 0; cb < CB; ++cb)
-    if (valid[cb]) { wlo = min(wlo, lo[cb]); whi = max(whi, hi[cb]); }
-  wlo = wave_min_i(wlo);
-  whi = wave_max_i(whi);
-  if ((threadIdx.x & 63) == 0) { atomicMin(&scratch[0], wlo); atomicMax(&scratch[1], whi); }
-  __syncthreads();
-  rs = lds_uniform(&scratch[0]);
-  re = lds_uniform(&scratch[1]);
-  bool u = true;
-#pragma unroll
-  for (int cb = 0; cb < CB; ++cb) u = u && valid[cb] && lo[cb] == rs && hi[cb] == re;
-  if (!__all(u) && (threadIdx.x & 63) == 0) scratch[2] = 0;
-  __syncthreads();
-  uniform = lds_uniform(&scratch[2]) != 0;
-  if (re <= rs) { rs = 0; re = 0; }
-}
-
-// ---- top-k over unsigned fixed-point scores held in LDS by one wavefront (ties -> lowest id) ----
-__device__ inline void topk_wave_u32(const uint32_t *S, int n, int T, int base, int32_t *out, uint32_t *sel) {
-  const int lane = threadIdx.x & 63;
-  const int words = (n + 31) >> 5;
-  for (int i = lane; i < words; i += 64) sel[i] = 0u;
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  const int rounds = T < n ? T : n;
-  for (int r = 0; r < rounds; ++r) {
-    uint64_t best = 0ull;
-    for (int j = lane; j < n; j += 64) {
-      if ((sel[j >> 5] >> (j & 31)) & 1u) continue;
-      const uint64_t key = ((uint64_t)S[j] << 32) | (uint64_t)(0xFFFFFFFFu - (uint32_t)j);
-      best = key > best ? key : best;
-    }
-    best = wave_max_u64(best);
-    const uint32_t j = 0xFFFFFFFFu - (uint32_t)(best & 0xFFFFFFFFull);
-    if (lane == 0) sel[j >> 5] |= 1u << (j & 31);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-  }
-  int written = 0;
-  for (int j0 = 0; j0 < n; j0 += 64) {
-    const int j = j0 + lane;
-    const bool s = j < n && ((sel[j >> 5] >> (j & 31)) & 1u);
-    const uint64_t m = __ballot(s);
-    if (s) out[written + __popcll(m & ((1ull << lane) - 1ull))] = base + j;
-    written += __popcll(m);
-  }
-  for (int w = written + lane; w < T; w += 64) out[w] = -1;
 }
 
 constexpr float SCORE_FIX = 134217728.0f;  // 2^27: a row's scores sum to h_s <= 16 < 2^5
@@ -376,40 +263,7 @@ __global__ __launch_bounds__(256) void m_slc_fwd(FwdArgs a) {
   const int words = (Ns + 31) >> 5;
   QRows<D, CB> q;
   load_rows<D, CB>(a.Q, a.v, wg_pos0, g, q);
-  for (int i = threadIdx.x; i < TW * T; i += 256) {
-    const int pos = wg_pos0 + i / T;
-    Irows[i] = pos < a.v.N ? a.idx[((size_t)a.v.perm[pos] * a.v.Hkv + g) * T + i % T] : -1;
-  }
-  for (int i = threadIdx.x; i < words; i += 256) bits[i] = 0u;
-  __syncthreads();
-  for (int i = threadIdx.x; i < TW * T; i += 256) {
-    const int b = Irows[i];
-    if (b >= 0 && b < Ns) atomicOr(&bits[b >> 5], 1u << (b & 31));
-  }
-  __syncthreads();
-  if (threadIdx.x < 64) {  // ordered compaction of the union into (id, start, end) lists
-    int base = 0;
-    for (int w0 = 0; w0 < words; w0 += 64) {
-      uint32_t w = (w0 + lane) < words ? bits[w0 + lane] : 0u;
-      const int c = __popc(w);
-      int incl = c;
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const int o = __shfl_up(incl, off);
-        if (lane >= off) incl += o;
-      }
-      int at = base + incl - c;
-      while (w) {
-        const int b = (w0 + lane) * 32 + __ffs(w) - 1;
-        ub[at] = b; us[at] = a.v.slc_start[b]; ue[at] = a.v.slc_start[b + 1];
-        ++at;
-        w &= w - 1;
-      }
-      base += __shfl(incl, 63);
-    }
-    if (lane == 0) ints[0] = base;
-  }
-  __syncthreads();
+  build_union(a.v, a.idx, wg_pos0, g, TW, Irows, ub, us, ue, bits, &ints[0]);
   const int nr = lds_uniform(&ints[0]);
   int jc[CB], lo[CB], hi[CB];
   bool act[CB];
