@@ -35,6 +35,7 @@ struct PreArgs {
   bf16_t *dgates;               // [N,Hq,3] caller order
   float *lse2s, *deltas, *gws;  // [3][N(pos)][Hq]
   bf16_t *QT, *dOT;             // [N(pos)][Hkv][D][hs]
+  bf16_t *Qs, *dOs;             // [N(pos)][Hq][D] sorted row-major copies
 };
 
 __global__ __launch_bounds__(256) void m_bwd_pre(PreArgs a) {
@@ -44,8 +45,11 @@ __global__ __launch_bounds__(256) void m_bwd_pre(PreArgs a) {
   const size_t base = (size_t)tok * HD;
   bf16_t *tq = tile, *td = tile + HD;
   for (int e = threadIdx.x * 8; e < HD; e += blockDim.x * 8) {
-    *reinterpret_cast<bf16x8 *>(tq + e) = ld8(a.Q + base + e);
-    *reinterpret_cast<bf16x8 *>(td + e) = ld8(a.dO + base + e);
+    const bf16x8 xq = ld8(a.Q + base + e), xd = ld8(a.dO + base + e);
+    *reinterpret_cast<bf16x8 *>(tq + e) = xq;
+    *reinterpret_cast<bf16x8 *>(td + e) = xd;
+    *reinterpret_cast<bf16x8 *>(a.Qs + (size_t)pos * HD + e) = xq;
+    *reinterpret_cast<bf16x8 *>(a.dOs + (size_t)pos * HD + e) = xd;
   }
   __syncthreads();
   // transposed copies: out[(g*D + dim)*hs + hl] = in[(g*hs + hl)*D + dim]
@@ -288,7 +292,7 @@ enum { DKV_WIN = 0, DKV_SLC = 1, DKV_CMP = 2 };
 
 struct DkvArgs {
   MfmaView v;
-  const bf16_t *Q, *dO, *QT, *dOT;
+  const bf16_t *Qs, *dOs, *QT, *dOT;  // sorted copies: [N(pos)][Hq][D] and [N(pos)][Hkv][D][hs]
   const float *lse2s, *deltas, *gws;  // already offset to the branch: [N(pos)][Hq]
   const int32_t *sel_start, *sel_list;  // selection branch: query positions per (g, block)
   float *dK, *dV;                       // [rows][Hkv][D] fp32 (rows: sorted tokens, or compression blocks)
@@ -299,7 +303,18 @@ struct DkvArgs {
   int q_splits;                         // compression branch: query range split into this many parts
 };
 
-// 32 query rows = 32/hs token slots.  slot_pos(s) gives the sorted position of slot s of the current tile, or -1.
+// LDS stage of the dK/dV kernels: 32 query rows as row-major tiles of Q and dO, the same rows as transposed tiles
+// (dims x rows) of Q and dO, and the rows' scalars (lse in log2 units, delta, gate).
+template <int D>
+struct DkvStage {
+  using G = TileGeom<D>;
+  static constexpr int ELEMS = 2 * G::ROW_ELEMS + 2 * G::T_ELEMS;
+  static constexpr int BYTES = ELEMS * 2 + 3 * 32 * 4;
+};
+
+// A workgroup owns 64*KB keys of one block (16*KB per wavefront, held in registers as MFMA B operands) and
+// streams the query rows that attend to them in tiles of 32 rows = 32/h_s token slots, staged through LDS once per
+// workgroup and double buffered.
 template <int D, int KB, int MODE>
 __global__ __launch_bounds__(256) void m_bwd_dkv(DkvArgs a) {
   const int wid = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 15, quad = lane >> 4;
@@ -339,14 +354,15 @@ __global__ __launch_bounds__(256) void m_bwd_dkv(DkvArgs a) {
     qbeg = min(q1, q0 + (int)blockIdx.z * per); qend = min(q1, qbeg + per);
     Kr = a.v.Kc; Vr = a.v.Vc;
   }
+  if (kbeg + tile * WG_KEYS >= kend) return;             // whole workgroup beyond the block (uniform)
   const int k0 = kbeg + tile * WG_KEYS + wid * 16 * KB;  // this wave's first key
-  if (k0 >= kend) return;  // nothing for this wavefront (no workgroup barrier is used below)
+  const bool wave_on = k0 < kend;                        // idle wavefronts still help staging and keep the barriers
   const size_t kstride = (size_t)a.v.Hkv * D;
-  // B operands: this wave's keys (column n of key block kbk), all of D
+  // B operands: this wave's keys (column n of key block kbk), all of D (rows past the block are padded: in bounds)
   bf16x8 kop[KB][D / 32], vop[KB][D / 32];
 #pragma unroll
   for (int kbk = 0; kbk < KB; ++kbk) {
-    const size_t off = (size_t)(k0 + 16 * kbk + n) * kstride + (size_t)g * D + 8 * quad;  // padded rows: in bounds
+    const size_t off = (size_t)(k0 + 16 * kbk + n) * kstride + (size_t)g * D + 8 * quad;
 #pragma unroll
     for (int ks = 0; ks < D / 32; ++ks) {
       kop[kbk][ks] = ld8(Kr + off + 32 * ks);
@@ -359,61 +375,136 @@ __global__ __launch_bounds__(256) void m_bwd_dkv(DkvArgs a) {
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt) dk[kbk][dt] = dv[kbk][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+  extern __shared__ __align__(16) unsigned char smem[];
+  using G = TileGeom<D>;
+  using SG = DkvStage<D>;
   const int slots = 32 / hs;  // token slots per 32-row tile (hs is 8 or 16)
   const float sl2 = a.v.sl2, scale = a.v.scale;
+  // sorted positions of the token slots of the tile that starts at list index qb (-1: past the end)
+  auto positions = [&](int qb, int (&p)[4]) {
+#pragma unroll
+    for (int sidx = 0; sidx < 4; ++sidx) {
+      const int sl = qb + sidx;
+      p[sidx] = (sidx < slots && sl < qend) ? (MODE == DKV_SLC ? a.sel_list[sl] : sl) : -1;
+    }
+  };
+  bf16x8 rq[G::ROW_PER_THREAD], rd[G::ROW_PER_THREAD], tq[G::T_PER_THREAD], td[G::T_PER_THREAD];
+  float sc = 0.f;
+  auto pick = [](const int (&p)[4], int i) { return i == 0 ? p[0] : (i == 1 ? p[1] : (i == 2 ? p[2] : p[3])); };
+  auto load_tile = [&](const int (&p)[4]) {
+#pragma unroll
+    for (int i = 0; i < G::ROW_PER_THREAD; ++i) {
+      const int it = threadIdx.x + 256 * i;
+      if (G::ROW_ITEMS % 256 == 0 || it < G::ROW_ITEMS) {
+        const int row = it / (D / 8), seg = it % (D / 8);
+        const int pos = max(pick(p, row / hs), 0);
+        const size_t off = ((size_t)pos * Hq + g * hs + row % hs) * D + seg * 8;
+        rq[i] = ld8(a.Qs + off);
+        rd[i] = ld8(a.dOs + off);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < G::T_PER_THREAD; ++i) {
+      const int it = threadIdx.x + 256 * i;
+      if (G::T_ITEMS % 256 == 0 || it < G::T_ITEMS) {
+        const int chunk = it / D, dim = it % D;
+        const int pos = max(pick(p, chunk * 8 / hs), 0);
+        const size_t off = (((size_t)pos * a.v.Hkv + g) * D + dim) * hs + (chunk * 8) % hs;
+        tq[i] = ld8(a.QT + off);
+        td[i] = ld8(a.dOT + off);
+      }
+    }
+    if (threadIdx.x < 96) {
+      const int arr = threadIdx.x >> 5, row = threadIdx.x & 31;
+      const int pos = pick(p, row / hs);
+      const size_t rsx = (size_t)max(pos, 0) * Hq + g * hs + row % hs;
+      const float *srcp = arr == 0 ? a.lse2s : (arr == 1 ? a.deltas : a.gws);
+      sc = srcp[rsx];
+      if (arr == 0 && pos < 0) sc = INFINITY;  // a missing row contributes exp2(-inf) = 0
+    }
+  };
+  auto store_tile = [&](unsigned char *stage) {
+    bf16_t *e = (bf16_t *)stage;
+#pragma unroll
+    for (int i = 0; i < G::ROW_PER_THREAD; ++i) {
+      const int it = threadIdx.x + 256 * i;
+      if (G::ROW_ITEMS % 256 == 0 || it < G::ROW_ITEMS) {
+        const int off = G::row_off(it / (D / 8), it % (D / 8));
+        *reinterpret_cast<bf16x8 *>(e + off) = rq[i];
+        *reinterpret_cast<bf16x8 *>(e + G::ROW_ELEMS + off) = rd[i];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < G::T_PER_THREAD; ++i) {
+      const int it = threadIdx.x + 256 * i;
+      if (G::T_ITEMS % 256 == 0 || it < G::T_ITEMS) {
+        const int off = 2 * G::ROW_ELEMS + G::t_off(it % D, it / D);
+        *reinterpret_cast<bf16x8 *>(e + off) = tq[i];
+        *reinterpret_cast<bf16x8 *>(e + G::T_ELEMS + off) = td[i];
+      }
+    }
+    if (threadIdx.x < 96) ((float *)(stage + SG::ELEMS * 2))[threadIdx.x] = sc;
+  };
+
+  int pcur[4], pnxt[4];
+  positions(qbeg, pcur);
+  if (qbeg < qend) load_tile(pcur);
+  positions(qbeg + slots, pnxt);
+  int buf = 0;
   for (int qb = qbeg; qb < qend; qb += slots) {
-    // --- rows this lane feeds as A operand (sub-tile a): q-row 8*(n>>2) + 4a + (n&3)
+    unsigned char *stage = smem + (size_t)buf * SG::BYTES;
+    store_tile(stage);
+    __syncthreads();
+    if (qb + slots < qend) {
+      load_tile(pnxt);
+      positions(qb + 2 * slots, pnxt);
+    }
+    buf ^= 1;
+    if (!wave_on) continue;
+    const bf16_t *Qr = (const bf16_t *)stage, *Dr = Qr + G::ROW_ELEMS, *Qt = Qr + 2 * G::ROW_ELEMS, *Dt = Qt + G::T_ELEMS;
+    const float *scal = (const float *)(stage + SG::ELEMS * 2);
     f32x4 s[KB][2], dp[KB][2];
 #pragma unroll
     for (int kbk = 0; kbk < KB; ++kbk)
 #pragma unroll
       for (int sa = 0; sa < 2; ++sa) s[kbk][sa] = dp[kbk][sa] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int sa = 0; sa < 2; ++sa) {
-      const int qr = 8 * (n >> 2) + 4 * sa + (n & 3);
-      const int sl = qb + qr / hs;
-      const int pos = sl < qend ? (MODE == DKV_SLC ? a.sel_list[sl] : sl) : -1;
-      const int tok = a.v.perm[pos < 0 ? 0 : pos];
-      const size_t off = ((size_t)tok * Hq + g * hs + qr % hs) * D + 8 * quad;
+    for (int sa = 0; sa < 2; ++sa)
 #pragma unroll
       for (int ks = 0; ks < D / 32; ++ks) {
-        const bf16x8 qa = ld8(a.Q + off + 32 * ks), da = ld8(a.dO + off + 32 * ks);
+        const bf16x8 qa = lds_row_operand<D>(Qr, sa, ks), da = lds_row_operand<D>(Dr, sa, ks);
 #pragma unroll
         for (int kbk = 0; kbk < KB; ++kbk) {
           s[kbk][sa] = mfma16(qa, kop[kbk][ks], s[kbk][sa]);
           dp[kbk][sa] = mfma16(da, vop[kbk][ks], dp[kbk][sa]);
         }
       }
-    }
-    // --- this lane's eight consecutive q-rows 8*quad .. +7: one token slot, heads h0 .. h0+7
-    const int sl = qb + (8 * quad) / hs, h0 = (8 * quad) % hs;
-    const int pos = sl < qend ? (MODE == DKV_SLC ? a.sel_list[sl] : sl) : -1;
-    const int psafe = pos < 0 ? 0 : pos;
-    const size_t rs = (size_t)psafe * Hq + g * hs + h0;
+    // this lane's eight consecutive query rows 8*quad .. +7
     float lse2[8], delta[8], gw[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      lse2[j] = pos < 0 ? INFINITY : a.lse2s[rs + j];  // a missing row contributes exp2(-inf) = 0
-      delta[j] = a.deltas[rs + j];
-      gw[j] = a.gws[rs + j];
+    {
+      const float4 l0 = *reinterpret_cast<const float4 *>(scal + 8 * quad), l1 = *reinterpret_cast<const float4 *>(scal + 8 * quad + 4);
+      const float4 d0 = *reinterpret_cast<const float4 *>(scal + 32 + 8 * quad), d1 = *reinterpret_cast<const float4 *>(scal + 36 + 8 * quad);
+      const float4 g0 = *reinterpret_cast<const float4 *>(scal + 64 + 8 * quad), g1 = *reinterpret_cast<const float4 *>(scal + 68 + 8 * quad);
+      lse2[0] = l0.x; lse2[1] = l0.y; lse2[2] = l0.z; lse2[3] = l0.w; lse2[4] = l1.x; lse2[5] = l1.y; lse2[6] = l1.z; lse2[7] = l1.w;
+      delta[0] = d0.x; delta[1] = d0.y; delta[2] = d0.z; delta[3] = d0.w; delta[4] = d1.x; delta[5] = d1.y; delta[6] = d1.z; delta[7] = d1.w;
+      gw[0] = g0.x; gw[1] = g0.y; gw[2] = g0.z; gw[3] = g0.w; gw[4] = g1.x; gw[5] = g1.y; gw[6] = g1.z; gw[7] = g1.w;
     }
-    const size_t toff = (((size_t)psafe * a.v.Hkv + g) * D + n) * hs + h0;  // [pos][g][dim][hs]
     bf16x8 qt[D / 16], dot[D / 16];
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt) {
-      qt[dt] = ld8(a.QT + toff + (size_t)dt * 16 * hs);
-      dot[dt] = ld8(a.dOT + toff + (size_t)dt * 16 * hs);
+      qt[dt] = lds_t_operand<D>(Qt, dt);
+      dot[dt] = lds_t_operand<D>(Dt, dt);
     }
 #pragma unroll
     for (int kbk = 0; kbk < KB; ++kbk) {
       bf16x8 pw, ds;
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        const float sv = (j < 4 ? s[kbk][0][j & 3] : s[kbk][1][j & 3]) * sl2;
+        const float sv = j < 4 ? s[kbk][0][j & 3] : s[kbk][1][j & 3];
         const float dpv = j < 4 ? dp[kbk][0][j & 3] : dp[kbk][1][j & 3];
-        const float p = fast_exp2(sv - lse2[j]);
+        const float p = fast_exp2(__builtin_fmaf(sv, sl2, -lse2[j]));
         pw[j] = (__bf16)(p * gw[j]);
-        ds[j] = (__bf16)(p * (gw[j] * dpv - delta[j]) * scale);
+        ds[j] = (__bf16)(p * __builtin_fmaf(gw[j], dpv, -delta[j]) * scale);
       }
 #pragma unroll
       for (int dt = 0; dt < D / 16; ++dt) {
@@ -422,6 +513,7 @@ __global__ __launch_bounds__(256) void m_bwd_dkv(DkvArgs a) {
       }
     }
   }
+  if (!wave_on) return;
   // --- store: lane holds dims 16*dt + 4*quad + i of key column n
 #pragma unroll
   for (int kbk = 0; kbk < KB; ++kbk) {
@@ -595,7 +687,7 @@ __global__ void m_bwd_finish(const int32_t *__restrict__ perm, const int32_t *__
   }
 }
 
-constexpr int KB_KEYS = 2;  // key blocks of 16 per wavefront in the dK/dV kernels
+constexpr int KB_KEYS = 2;  // key blocks of 16 per wavefront in the dK/dV kernels (keep 64*KB_KEYS <= SSA_KEY_PAD)
 
 template <int D>
 int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const void *gates, const void *out_branch,
@@ -606,7 +698,7 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
   {
     ProfScope ps(PROF_BWD_PRE, s);
     PreArgs a{(const bf16_t *)q, (const bf16_t *)dout, (const bf16_t *)out_branch, (const bf16_t *)gates, lse, v.perm,
-              N, Hq, Hkv, v.hs, D, (bf16_t *)dgates, w.lse2s, w.deltas, w.gws, w.QT, w.dOT};
+              N, Hq, Hkv, v.hs, D, (bf16_t *)dgates, w.lse2s, w.deltas, w.gws, w.QT, w.dOT, w.Qs, w.dOs};
     m_bwd_pre<<<N, 256, (size_t)2 * Hq * D * sizeof(bf16_t), s>>>(a);
   }
   {
@@ -622,14 +714,22 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
     m_bwd_dq<D, CB><<<dim3((N + tw - 1) / tw, Hkv), 256, dq_lds_bytes<D>(tw, v.T, v.Ns), s>>>(a);
   }
   constexpr int WG_KEYS = 64 * KB_KEYS;
-  DkvArgs base{v, (const bf16_t *)q, (const bf16_t *)dout, w.QT, w.dOT, nullptr, nullptr, nullptr, w.sel_start, w.sel_list,
+  const size_t dkv_lds = (size_t)2 * DkvStage<D>::BYTES;
+  static bool dkv_attr = false;
+  if (!dkv_attr) {
+    (void)hipFuncSetAttribute((const void *)m_bwd_dkv<D, KB_KEYS, DKV_WIN>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    (void)hipFuncSetAttribute((const void *)m_bwd_dkv<D, KB_KEYS, DKV_SLC>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    (void)hipFuncSetAttribute((const void *)m_bwd_dkv<D, KB_KEYS, DKV_CMP>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    dkv_attr = true;
+  }
+  DkvArgs base{v, w.Qs, w.dOs, w.QT, w.dOT, nullptr, nullptr, nullptr, w.sel_start, w.sel_list,
                w.dKs, w.dVs, w.chunk_start, w.part_row_start, w.chunk_len, 1, 1};
   {
     ProfScope ps(PROF_BWD_DKV_WIN, s);
     DkvArgs a = base;
     a.lse2s = w.lse2s + 2 * NH; a.deltas = w.deltas + 2 * NH; a.gws = w.gws + 2 * NH;
     a.tiles_per_block = (blk->win_tok_max + WG_KEYS - 1) / WG_KEYS;
-    m_bwd_dkv<D, KB_KEYS, DKV_WIN><<<dim3(blk->Nw * a.tiles_per_block, Hkv), 256, 0, s>>>(a);
+    m_bwd_dkv<D, KB_KEYS, DKV_WIN><<<dim3(blk->Nw * a.tiles_per_block, Hkv), 256, dkv_lds, s>>>(a);
   }
   {
     ProfScope ps(PROF_BWD_INVERT, s);
@@ -648,7 +748,7 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
     a.lse2s = w.lse2s + NH; a.deltas = w.deltas + NH; a.gws = w.gws + NH;
     a.dK = w.pK; a.dV = w.pV;
     a.tiles_per_block = (blk->slc_tok_max + WG_KEYS - 1) / WG_KEYS;
-    m_bwd_dkv<D, KB_KEYS, DKV_SLC><<<dim3(w.max_chunks, a.tiles_per_block), 256, 0, s>>>(a);
+    m_bwd_dkv<D, KB_KEYS, DKV_SLC><<<dim3(w.max_chunks, a.tiles_per_block), 256, dkv_lds, s>>>(a);
     const size_t items = (size_t)N * Hkv * (D / 4);
     m_slc_reduce<<<(unsigned)((items + 255) / 256), 256, 0, s>>>(blk->tok_slc, v.slc_start, w.chunk_start, w.part_row_start, N,
                                                                  Hkv, v.Ns, D, w.pK, w.pV, w.dKs, w.dVs);
@@ -660,7 +760,7 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
     a.dK = w.dKc; a.dV = w.dVc;
     a.tiles_per_block = (blk->c_max + WG_KEYS - 1) / WG_KEYS;
     a.q_splits = w.q_splits;
-    m_bwd_dkv<D, KB_KEYS, DKV_CMP><<<dim3(B * a.tiles_per_block, Hkv, w.q_splits), 256, 0, s>>>(a);
+    m_bwd_dkv<D, KB_KEYS, DKV_CMP><<<dim3(B * a.tiles_per_block, Hkv, w.q_splits), 256, dkv_lds, s>>>(a);
   }
   {
     ProfScope ps(PROF_BWD_FINISH, s);

@@ -10,6 +10,7 @@ int mfma_forward_kernels(const MfmaView &v, int D, const void *q, const void *ga
 struct BwdBuffers {
   float *lse2s, *deltas, *gws;  // [3][N(pos)][Hq]: lse*log2(e), gate*<dO,O_b>, gate
   bf16_t *QT, *dOT;             // [N(pos)][Hkv][D][hs]: per-token transposed Q and dO
+  bf16_t *Qs, *dOs;             // [N(pos)][Hq][D]: Q and dO in sorted token order
   float *dKs, *dVs;             // [N(pos)][Hkv][D] token-level gradients in sorted order
   float *dKc, *dVc;             // [q_splits][Nc][Hkv][D] partial gradients of the pooled keys/values
   uint32_t *sel_bits;           // [Hkv*Ns][ceil(N/32)] bit (key, pos): token at pos selected the block
