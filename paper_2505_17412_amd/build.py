@@ -16,6 +16,7 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-result",
+    "-fno-honor-nans", "-mno-amdgpu-ieee",  # no NaN is ever produced on purpose; saves the canonicalising v_max
     "-mllvm", "-amdgpu-mfma-vgpr-form",  # keep MFMA accumulators in VGPRs: the softmax rescales them every tile
 ]
 

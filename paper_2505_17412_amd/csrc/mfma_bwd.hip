@@ -153,14 +153,16 @@ __host__ __device__ inline size_t dq_lds_bytes(int tw, int T, int Ns) {
 }
 
 template <int D, int CB>
-__global__ __launch_bounds__(256) void m_bwd_dq(DqArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4 : 2))) void m_bwd_dq(DqArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   using L = StageLayout<D, 2, 1>;
   bf16_t *stage0 = (bf16_t *)smem;
   int *ints = (int *)(stage0 + 2 * L::ELEMS);
   const int quad = threadIdx.x >> 4 & 3;
-  const int hs = a.v.hs, g = blockIdx.y, T = a.v.T, N = a.v.N, Ns = a.v.Ns;
-  const int TW = 4 * CB * 16 / hs, wg_pos0 = blockIdx.x * TW;
+  const int hs = a.v.hs, T = a.v.T, N = a.v.N, Ns = a.v.Ns, TW = 4 * CB * 16 / hs;
+  const TileMap tm = xcd_tile_map((N + TW - 1) / TW, a.v.Hkv);
+  if (!tm.valid) return;
+  const int g = tm.g, wg_pos0 = tm.tile * TW;
   int *Irows = ints + 8;
   int *ub = Irows + TW * T, *us = ub + TW * T, *ue = us + TW * T;
   uint32_t *bits = (uint32_t *)(ue + TW * T);
@@ -711,7 +713,7 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
       (void)hipFuncSetAttribute((const void *)m_bwd_dq<D, CB>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
       attr_done = true;
     }
-    m_bwd_dq<D, CB><<<dim3((N + tw - 1) / tw, Hkv), 256, dq_lds_bytes<D>(tw, v.T, v.Ns), s>>>(a);
+    m_bwd_dq<D, CB><<<dim3(xcd_grid_size((N + tw - 1) / tw, Hkv)), 256, dq_lds_bytes<D>(tw, v.T, v.Ns), s>>>(a);
   }
   constexpr int WG_KEYS = 64 * KB_KEYS;
   const size_t dkv_lds = (size_t)2 * DkvStage<D>::BYTES;

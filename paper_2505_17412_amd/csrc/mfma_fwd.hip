@@ -157,8 +157,10 @@ __global__ __launch_bounds__(256) void m_cmp_fwd(FwdArgs a) {
   bf16_t *stage0 = (bf16_t *)smem;
   int *ints = (int *)(stage0 + 2 * L::ELEMS);
   const int wid = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 15, quad = lane >> 4;
-  const int hs = a.v.hs, g = blockIdx.y, s_max = a.v.s_max;
-  const int TW = 4 * CB * 16 / hs, wg_pos0 = blockIdx.x * TW;
+  const int hs = a.v.hs, s_max = a.v.s_max, TW = 4 * CB * 16 / hs;
+  const TileMap tm = xcd_tile_map((a.v.N + TW - 1) / TW, a.v.Hkv);
+  if (!tm.valid) return;
+  const int g = tm.g, wg_pos0 = tm.tile * TW;
   uint32_t *S = (uint32_t *)(ints + 8);
   uint32_t *sel = S + (size_t)TW * s_max + (size_t)wid * ((s_max + 31) >> 5);
   QRows<D, CB> q;
@@ -254,8 +256,10 @@ __global__ __launch_bounds__(256) void m_slc_fwd(FwdArgs a) {
   bf16_t *stage0 = (bf16_t *)smem;
   int *ints = (int *)(stage0 + 2 * L::ELEMS);
   const int lane = threadIdx.x & 63;
-  const int hs = a.v.hs, g = blockIdx.y, T = a.v.T, Ns = a.v.Ns;
-  const int TW = 4 * CB * 16 / hs, wg_pos0 = blockIdx.x * TW;
+  const int hs = a.v.hs, T = a.v.T, Ns = a.v.Ns, TW = 4 * CB * 16 / hs;
+  const TileMap tm = xcd_tile_map((a.v.N + TW - 1) / TW, a.v.Hkv);
+  if (!tm.valid) return;
+  const int g = tm.g, wg_pos0 = tm.tile * TW;
   int *Irows = ints + 8;                 // [TW][T]
   int *ub = Irows + TW * T;              // union list: block ids
   int *us = ub + TW * T, *ue = us + TW * T;
@@ -315,8 +319,10 @@ __global__ __launch_bounds__(256) void m_win_fwd(FwdArgs a) {
   using L = StageLayout<D, 1, 1>;
   bf16_t *stage0 = (bf16_t *)smem;
   int *ints = (int *)(stage0 + 2 * L::ELEMS);
-  const int hs = a.v.hs, g = blockIdx.y;
-  const int TW = 4 * CB * 16 / hs, wg_pos0 = blockIdx.x * TW;
+  const int hs = a.v.hs, TW = 4 * CB * 16 / hs;
+  const TileMap tm = xcd_tile_map((a.v.N + TW - 1) / TW, a.v.Hkv);
+  if (!tm.valid) return;
+  const int g = tm.g, wg_pos0 = tm.tile * TW;
   QRows<D, CB> q;
   load_rows<D, CB>(a.Q, a.v, wg_pos0, g, q);
   int lo[CB], hi[CB];
@@ -376,7 +382,7 @@ constexpr int FWD_CB = 1;  // blocks of 16 query columns per wavefront
 template <int D>
 int launch_forward(const FwdArgs &a, const bf16_t *gates, bf16_t *out, hipStream_t s) {
   const int tw = 4 * FWD_CB * 16 / a.v.hs;
-  const dim3 grid((a.v.N + tw - 1) / tw, a.v.Hkv);
+  const dim3 grid(xcd_grid_size((a.v.N + tw - 1) / tw, a.v.Hkv));
   const size_t lds_cmp = cmp_lds_bytes<D>(tw, a.v.s_max), lds_slc = slc_lds_bytes<D>(tw, a.v.T, a.v.Ns);
   const size_t lds_win = (size_t)2 * StageLayout<D, 1, 1>::ELEMS * sizeof(bf16_t) + 32;
   static bool attr_done = false;  // raise the dynamic LDS limit once per process for these instantiations

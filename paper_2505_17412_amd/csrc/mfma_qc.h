@@ -140,6 +140,28 @@ __device__ inline TileIter iter_next(TileIter it, const int *rng_s, const int *r
   return it;
 }
 
+// Workgroup -> (token tile, KV group).  Workgroups of a 1-D launch are dealt round-robin to the 8 XCDs, each with
+// its own L2; this map keeps every XCD on ONE KV group and one contiguous run of token tiles, so the K/V rows it
+// touches (one group's pooled keys, the windows and selected blocks of neighbouring tokens) stay L2 resident.
+struct TileMap {
+  int tile, g;
+  bool valid;
+};
+__host__ __device__ inline int xcd_grid_size(int n_tiles, int Hkv) {
+  if (Hkv > 8 || 8 % Hkv != 0) return n_tiles * Hkv;
+  const int parts = 8 / Hkv;
+  return 8 * ((n_tiles + parts - 1) / parts);
+}
+__device__ inline TileMap xcd_tile_map(int n_tiles, int Hkv) {
+  const int L = blockIdx.x;
+  if (Hkv > 8 || 8 % Hkv != 0) return TileMap{L % n_tiles, L / n_tiles, L < n_tiles * Hkv};
+  const int xcd = L & 7, idx = L >> 3, parts = 8 / Hkv;
+  const int g = xcd % Hkv, part = xcd / Hkv;
+  const int tpp = (n_tiles + parts - 1) / parts;
+  const int tile = part * tpp + idx;
+  return TileMap{tile, g, idx < tpp && tile < n_tiles};
+}
+
 // The query rows of one wavefront: CB blocks of 16 columns; column n of block cb is workgroup row
 // (wave*CB + cb)*16 + n = (token slot) * h_s + (head inside the group).
 template <int D, int CB>
