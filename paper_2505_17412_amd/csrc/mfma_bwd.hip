@@ -94,6 +94,7 @@ struct DqArgs {
   const int32_t *idx;
   const float *lse2s, *deltas, *gws;  // [3][N(pos)][Hq]
   bf16_t *dQ;
+  float *dQp;  // [N(pos)][Hq][D] fp32: compression-branch part of dQ, handed from the first dQ kernel to the second
 };
 
 // One staged 32-key tile: transposed scores (K rows) and dP (V rows), then dQ^T += K^T dS^T (transposed K tile).
@@ -152,7 +153,9 @@ __host__ __device__ inline size_t dq_lds_bytes(int tw, int T, int Ns) {
   return (size_t)2 * StageLayout<D, 2, 1>::ELEMS * sizeof(bf16_t) + 32 + ((size_t)tw * T * 4 + (size_t)(Ns + 31) / 32 + 4) * 4;
 }
 
-template <int D, int CB>
+// PART 0: compression branch only (its pooled keys stay L2 resident when nothing else streams through), result
+// kept in fp32; PART 1: window and selection branches on top of it, final bf16 dQ.
+template <int D, int CB, int PART>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4 : 2))) void m_bwd_dq(DqArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   using L = StageLayout<D, 2, 1>;
@@ -182,7 +185,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-    for (int dt = 0; dt < D / 16; ++dt) acc[cb][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int dt = 0; dt < D / 16; ++dt) {
+      acc[cb][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (PART == 1 && q.valid[cb])
+        acc[cb][dt] = *reinterpret_cast<const f32x4 *>(a.dQp + rs_[cb] * D + 16 * dt + 4 * quad);
+    }
   const float sl2 = a.v.sl2, scale = a.v.scale;
   const size_t kstride = (size_t)a.v.Hkv * D;
   int lo[CB], hi[CB];
@@ -190,7 +197,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
   float lse2[CB], delta[CB], gw[CB];
 
   // ---- compression and window branches: one key range, per-lane [lo, hi)
-  for (int branch = 0; branch < 3; branch += 2) {
+  {
+    constexpr int branch = PART == 0 ? 0 : 2;
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) {
       if (branch == 0) {
@@ -228,7 +236,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
         });
   }
   // ---- selection branch: union of the selected blocks of the workgroup's tokens
-  {
+  if (PART == 1) {
     build_union(a.v, a.idx, wg_pos0, g, TW, Irows, ub, us, ue, bits, &ints[0]);
     const int nr = lds_uniform(&ints[0]);
     int jc[CB];
@@ -276,6 +284,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) {
     if (!q.valid[cb]) continue;
+    if (PART == 0) {
+#pragma unroll
+      for (int dt = 0; dt < D / 16; ++dt) *reinterpret_cast<f32x4 *>(a.dQp + rs_[cb] * D + 16 * dt + 4 * quad) = acc[cb][dt];
+      continue;
+    }
     bf16_t *o = a.dQ + ((size_t)q.tok[cb] * a.v.Hq + q.h[cb]) * D + 4 * quad;
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt) {
@@ -705,15 +718,18 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
   }
   {
     ProfScope ps(PROF_BWD_DQ, s);
-    DqArgs a{v, (const bf16_t *)q, (const bf16_t *)dout, idx, w.lse2s, w.deltas, w.gws, (bf16_t *)dq};
+    DqArgs a{v, (const bf16_t *)q, (const bf16_t *)dout, idx, w.lse2s, w.deltas, w.gws, (bf16_t *)dq, w.dQp};
     constexpr int CB = 1;
     const int tw = 4 * CB * 16 / v.hs;
     static bool attr_done = false;
     if (!attr_done) {
-      (void)hipFuncSetAttribute((const void *)m_bwd_dq<D, CB>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      (void)hipFuncSetAttribute((const void *)m_bwd_dq<D, CB, 0>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      (void)hipFuncSetAttribute((const void *)m_bwd_dq<D, CB, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
       attr_done = true;
     }
-    m_bwd_dq<D, CB><<<dim3(xcd_grid_size((N + tw - 1) / tw, Hkv)), 256, dq_lds_bytes<D>(tw, v.T, v.Ns), s>>>(a);
+    const dim3 grid(xcd_grid_size((N + tw - 1) / tw, Hkv));
+    m_bwd_dq<D, CB, 0><<<grid, 256, dq_lds_bytes<D>(tw, v.T, v.Ns), s>>>(a);
+    m_bwd_dq<D, CB, 1><<<grid, 256, dq_lds_bytes<D>(tw, v.T, v.Ns), s>>>(a);
   }
   constexpr int WG_KEYS = 64 * KB_KEYS;
   const size_t dkv_lds = (size_t)2 * DkvStage<D>::BYTES;

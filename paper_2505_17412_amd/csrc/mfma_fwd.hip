@@ -65,11 +65,17 @@ __device__ inline void score_tile(const bf16_t *ktile, const QRows<D, CB> &q, co
     }
 }
 
-// One online-softmax step (Algorithm 1, inner loop body) over the staged tile.  lo/hi: the keys each lane may
-// see; act: wave-uniform "this column block has keys in the current range".
+// One online-softmax step (Algorithm 1, inner loop body) over the staged tile.
+//   lo/hi: the keys each lane may see (used only when MASK);  on: this lane's column takes part in the tile at all
+//   (a token that did not select the current block is off);  act: wave-uniform "some lane of the block is on".
+// The reference maximum m of a column is raised lazily: only when some score exceeds it by more than 8 in log2
+// units (so every exp2 argument stays below 8 and nothing overflows) does the wavefront take the update path
+// with its cross-lane maximum and rescale of o and l; otherwise the tile needs no cross-lane traffic at all.
+// The log-sum-exp reported at the end does not depend on which reference was used.
 template <int D, int CB, bool MASK>
 __device__ inline void fwd_tile(FwdState<D, CB> &st, const QRows<D, CB> &q, const bf16_t *ktile, const bf16_t *vtile, int kb,
-                                const int (&lo)[CB], const int (&hi)[CB], const bool (&act)[CB], float sl2) {
+                                const int (&lo)[CB], const int (&hi)[CB], const bool (&on)[CB], const bool (&act)[CB],
+                                float sl2, float slack) {
   const int quad = threadIdx.x >> 4 & 3;
   float s[CB][8];
   score_tile<D, CB>(ktile, q, act, s);
@@ -85,12 +91,20 @@ __device__ inline void fwd_tile(FwdState<D, CB> &st, const QRows<D, CB> &q, cons
         if (key < lo[cb] || key >= hi[cb]) v[j] = -INFINITY;
       }
     }
-    float tmax = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-    const float mn = fmaxf(st.m[cb], tmax);
-    const float neg = mn == -INFINITY ? 0.f : -mn * sl2;  // nothing seen yet: keep exp2 arguments finite or -inf
-    const float alpha = fast_exp2(__builtin_fmaf(st.m[cb], sl2, neg));
+    float pm = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
+    if (!on[cb]) pm = -INFINITY;
+    if (__any(pm > st.m[cb] + slack)) {
+      float tmax = fmaxf(pm, __shfl_xor(pm, 16));
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+      const float mn = fmaxf(st.m[cb], tmax);
+      const float alpha = mn == -INFINITY ? 1.0f : fast_exp2((st.m[cb] - mn) * sl2);
+      st.l[cb] *= alpha;
+      st.m[cb] = mn;
+#pragma unroll
+      for (int dt = 0; dt < D / 16; ++dt) st.o[cb][dt] *= alpha;
+    }
+    // exp2 arguments: finite or -inf; a column that is off (or has seen nothing yet and sees nothing now) gets p = 0
+    const float neg = (on[cb] && st.m[cb] != -INFINITY) ? -st.m[cb] * sl2 : -INFINITY;
     float psum = 0.f;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -98,12 +112,7 @@ __device__ inline void fwd_tile(FwdState<D, CB> &st, const QRows<D, CB> &q, cons
       psum += p;
       pb[cb][j] = (__bf16)p;
     }
-    st.l[cb] = st.l[cb] * alpha + psum;
-    st.m[cb] = mn;
-    if (!__all(alpha == 1.0f)) {
-#pragma unroll
-      for (int dt = 0; dt < D / 16; ++dt) st.o[cb][dt] *= alpha;
-    }
+    st.l[cb] += psum;
   }
 #pragma unroll
   for (int dt = 0; dt < D / 16; ++dt) {
@@ -151,7 +160,7 @@ __host__ __device__ inline size_t cmp_lds_bytes(int tw, int s_max) {
 // eq. (6) accumulated per selection block in LDS as fixed-point integers (integer adds commute, so the result
 // does not depend on scheduling), then the top-k.
 template <int D, int CB>
-__global__ __launch_bounds__(256) void m_cmp_fwd(FwdArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4 : 2))) void m_cmp_fwd(FwdArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   using L = StageLayout<D, 1, 1>;
   bf16_t *stage0 = (bf16_t *)smem;
@@ -179,9 +188,10 @@ __global__ __launch_bounds__(256) void m_cmp_fwd(FwdArgs a) {
   if (threadIdx.x == 0) { ints[4] = rs; ints[5] = re; }
   __syncthreads();
   const int nr = re > rs ? 1 : 0;
-  bool act[CB];
+  bool act[CB], on[CB];
 #pragma unroll
-  for (int cb = 0; cb < CB; ++cb) act[cb] = true;
+  for (int cb = 0; cb < CB; ++cb) { act[cb] = true; on[cb] = q.valid[cb]; }
+  const float slack = 8.0f / a.v.sl2;
   TileSrc<1, 1> src{{a.v.Kc + (size_t)g * D}, {a.v.Vct + (size_t)g * D * 8}, (size_t)a.v.Hkv * D};
   FwdState<D, CB> st;
   init_state(st);
@@ -190,9 +200,9 @@ __global__ __launch_bounds__(256) void m_cmp_fwd(FwdArgs a) {
       src, stage0, ints + 4, ints + 5, nr, [](int) {},
       [&](const bf16_t *stg, int kb, int) {
         if (uniform && kb >= rs && kb + 32 <= re)
-          fwd_tile<D, CB, false>(st, q, L::row_tile((bf16_t *)stg, 0), L::t_tile((bf16_t *)stg, 0), kb, lo, hi, act, sl2);
+          fwd_tile<D, CB, false>(st, q, L::row_tile((bf16_t *)stg, 0), L::t_tile((bf16_t *)stg, 0), kb, lo, hi, on, act, sl2, slack);
         else
-          fwd_tile<D, CB, true>(st, q, L::row_tile((bf16_t *)stg, 0), L::t_tile((bf16_t *)stg, 0), kb, lo, hi, act, sl2);
+          fwd_tile<D, CB, true>(st, q, L::row_tile((bf16_t *)stg, 0), L::t_tile((bf16_t *)stg, 0), kb, lo, hi, on, act, sl2, slack);
       });
   float lse2[CB];
   finish<D, CB>(a, st, 0, q, lse2);
@@ -250,7 +260,7 @@ __host__ __device__ inline size_t slc_lds_bytes(int tw, int T, int Ns) {
 // id; a token that did not select the current block sees it fully masked, a wavefront none of whose tokens
 // selected it skips the arithmetic.
 template <int D, int CB>
-__global__ __launch_bounds__(256) void m_slc_fwd(FwdArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4 : 2))) void m_slc_fwd(FwdArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   using L = StageLayout<D, 1, 1>;
   bf16_t *stage0 = (bf16_t *)smem;
@@ -270,14 +280,14 @@ __global__ __launch_bounds__(256) void m_slc_fwd(FwdArgs a) {
   build_union(a.v, a.idx, wg_pos0, g, TW, Irows, ub, us, ue, bits, &ints[0]);
   const int nr = lds_uniform(&ints[0]);
   int jc[CB], lo[CB], hi[CB];
-  bool act[CB];
+  bool act[CB], on[CB];
+  const float slack = 8.0f / a.v.sl2;
 #pragma unroll
-  for (int cb = 0; cb < CB; ++cb) { jc[cb] = 0; lo[cb] = hi[cb] = 0; act[cb] = false; }
+  for (int cb = 0; cb < CB; ++cb) { jc[cb] = 0; lo[cb] = hi[cb] = 0; act[cb] = false; on[cb] = false; }
   TileSrc<1, 1> src{{a.v.Ks + (size_t)g * D}, {a.v.Vt + (size_t)g * D * 8}, (size_t)a.v.Hkv * D};
   FwdState<D, CB> st;
   init_state(st);
   const float sl2 = a.v.sl2;
-  bool full = false;
   int rs = 0, re = 0;
   run_pipeline<D, 1, 1>(
       src, stage0, us, ue, nr,
@@ -285,7 +295,6 @@ __global__ __launch_bounds__(256) void m_slc_fwd(FwdArgs a) {
         const int b = lds_uniform(&ub[r]);
         rs = lds_uniform(&us[r]);
         re = lds_uniform(&ue[r]);
-        bool all_sel = true;
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
           const int cur = (q.valid[cb] && jc[cb] < T) ? Irows[q.slot[cb] * T + jc[cb]] : -1;
@@ -293,20 +302,19 @@ __global__ __launch_bounds__(256) void m_slc_fwd(FwdArgs a) {
           if (sel) ++jc[cb];
           lo[cb] = sel ? rs : 0;
           hi[cb] = sel ? re : 0;
+          on[cb] = sel;
           act[cb] = __any(sel);
-          all_sel = all_sel && __all(sel);
         }
-        full = all_sel;
       },
       [&](const bf16_t *stg, int kb, int) {
         bool any = false;
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) any = any || act[cb];
         if (!any) return;
-        if (full && kb >= rs && kb + 32 <= re)
-          fwd_tile<D, CB, false>(st, q, L::row_tile((bf16_t *)stg, 0), L::t_tile((bf16_t *)stg, 0), kb, lo, hi, act, sl2);
+        if (kb >= rs && kb + 32 <= re)
+          fwd_tile<D, CB, false>(st, q, L::row_tile((bf16_t *)stg, 0), L::t_tile((bf16_t *)stg, 0), kb, lo, hi, on, act, sl2, slack);
         else
-          fwd_tile<D, CB, true>(st, q, L::row_tile((bf16_t *)stg, 0), L::t_tile((bf16_t *)stg, 0), kb, lo, hi, act, sl2);
+          fwd_tile<D, CB, true>(st, q, L::row_tile((bf16_t *)stg, 0), L::t_tile((bf16_t *)stg, 0), kb, lo, hi, on, act, sl2, slack);
       });
   float lse2[CB];
   finish<D, CB>(a, st, 1, q, lse2);
@@ -314,7 +322,7 @@ __global__ __launch_bounds__(256) void m_slc_fwd(FwdArgs a) {
 
 // Window branch: keys are the tokens of the query's own window.
 template <int D, int CB>
-__global__ __launch_bounds__(256) void m_win_fwd(FwdArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4 : 2))) void m_win_fwd(FwdArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   using L = StageLayout<D, 1, 1>;
   bf16_t *stage0 = (bf16_t *)smem;
@@ -326,13 +334,15 @@ __global__ __launch_bounds__(256) void m_win_fwd(FwdArgs a) {
   QRows<D, CB> q;
   load_rows<D, CB>(a.Q, a.v, wg_pos0, g, q);
   int lo[CB], hi[CB];
-  bool act[CB];
+  bool act[CB], on[CB];
+  const float slack = 8.0f / a.v.sl2;
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) {
     const int w = q.valid[cb] ? a.v.tok_win[q.pos[cb]] : 0;
     lo[cb] = q.valid[cb] ? a.v.win_start[w] : 0;
     hi[cb] = q.valid[cb] ? a.v.win_start[w + 1] : 0;
     act[cb] = true;
+    on[cb] = q.valid[cb];
   }
   int rs, re;
   bool uniform;
@@ -347,9 +357,9 @@ __global__ __launch_bounds__(256) void m_win_fwd(FwdArgs a) {
       src, stage0, ints + 4, ints + 5, re > rs ? 1 : 0, [](int) {},
       [&](const bf16_t *stg, int kb, int) {
         if (uniform && kb >= rs && kb + 32 <= re)
-          fwd_tile<D, CB, false>(st, q, L::row_tile((bf16_t *)stg, 0), L::t_tile((bf16_t *)stg, 0), kb, lo, hi, act, sl2);
+          fwd_tile<D, CB, false>(st, q, L::row_tile((bf16_t *)stg, 0), L::t_tile((bf16_t *)stg, 0), kb, lo, hi, on, act, sl2, slack);
         else
-          fwd_tile<D, CB, true>(st, q, L::row_tile((bf16_t *)stg, 0), L::t_tile((bf16_t *)stg, 0), kb, lo, hi, act, sl2);
+          fwd_tile<D, CB, true>(st, q, L::row_tile((bf16_t *)stg, 0), L::t_tile((bf16_t *)stg, 0), kb, lo, hi, on, act, sl2, slack);
       });
   float lse2[CB];
   finish<D, CB>(a, st, 2, q, lse2);

@@ -12,6 +12,7 @@ struct BwdBuffers {
   bf16_t *QT, *dOT;             // [N(pos)][Hkv][D][hs]: per-token transposed Q and dO
   bf16_t *Qs, *dOs;             // [N(pos)][Hq][D]: Q and dO in sorted token order
   float *dKs, *dVs;             // [N(pos)][Hkv][D] token-level gradients in sorted order
+  float *dQp;                   // [N(pos)][Hq][D] compression-branch part of dQ (fp32)
   float *dKc, *dVc;             // [q_splits][Nc][Hkv][D] partial gradients of the pooled keys/values
   uint32_t *sel_bits;           // [Hkv*Ns][ceil(N/32)] bit (key, pos): token at pos selected the block
   uint32_t *sel_counts;         // [Hkv*Ns]

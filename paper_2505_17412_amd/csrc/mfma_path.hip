@@ -91,7 +91,7 @@ int run_prep(const ssa_ctx &c, const void *k, const void *v, const PrepOut &o) {
 }
 
 struct BwdPlan {
-  size_t ks, vs, kt, kc, vc, kct, lse2s, deltas, gws, qt, dot, qs, dos, dks, dvs, dkc, dvc, bits, counts, start, list, cstart, prow,
+  size_t ks, vs, kt, kc, vc, kct, lse2s, deltas, gws, qt, dot, qs, dos, dqp, dks, dvs, dkc, dvc, bits, counts, start, list, cstart, prow,
       pk, pv, total;
   int q_splits, chunk_len, max_chunks;
 };
@@ -114,6 +114,7 @@ BwdPlan bwd_plan(const ssa_ctx &c) {
   p.lse2s = take(nh); p.deltas = take(nh); p.gws = take(nh);
   p.qt = take((size_t)c.N * c.Hq * c.d * 2); p.dot = take((size_t)c.N * c.Hq * c.d * 2);
   p.qs = take((size_t)c.N * c.Hq * c.d * 2); p.dos = take((size_t)c.N * c.Hq * c.d * 2);
+  p.dqp = take((size_t)c.N * c.Hq * c.d * 4);
   p.dks = take((size_t)c.N * row * 4); p.dvs = take((size_t)c.N * row * 4);
   p.dkc = take((size_t)p.q_splits * b->Nc * row * 4); p.dvc = take((size_t)p.q_splits * b->Nc * row * 4);
   const size_t keys = (size_t)c.Hkv * b->Ns, words = ((size_t)c.N + 31) / 32;
@@ -174,7 +175,7 @@ int mfma_backward(const ssa_ctx &c, const void *q, const void *k, const void *v,
   BwdBuffers w{};
   w.lse2s = (float *)(ws + p.lse2s); w.deltas = (float *)(ws + p.deltas); w.gws = (float *)(ws + p.gws);
   w.QT = (bf16_t *)(ws + p.qt); w.dOT = (bf16_t *)(ws + p.dot);
-  w.Qs = (bf16_t *)(ws + p.qs); w.dOs = (bf16_t *)(ws + p.dos);
+  w.Qs = (bf16_t *)(ws + p.qs); w.dOs = (bf16_t *)(ws + p.dos); w.dQp = (float *)(ws + p.dqp);
   w.dKs = (float *)(ws + p.dks); w.dVs = (float *)(ws + p.dvs); w.dKc = (float *)(ws + p.dkc); w.dVc = (float *)(ws + p.dvc);
   w.sel_bits = (uint32_t *)(ws + p.bits); w.sel_counts = (uint32_t *)(ws + p.counts);
   w.sel_start = (int32_t *)(ws + p.start); w.sel_list = (int32_t *)(ws + p.list);
