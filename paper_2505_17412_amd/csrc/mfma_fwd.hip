@@ -150,10 +150,11 @@ __device__ inline void finish(const FwdArgs &a, FwdState<D, CB> &st, int branch,
 
 constexpr float SCORE_FIX = 134217728.0f;  // 2^27: a row's scores sum to h_s <= 16 < 2^5
 
-// LDS plan of the compression kernel (bytes): two tile stages | 8 ints | scores [TW][s_max] | top-k marks [4][words]
+// LDS plan of the compression kernel (bytes): two tile stages | 8 ints | scores [TW][s_max] | top-k marks [4][words] |
+// lse per query row [4 waves][CB <= 4][16]
 template <int D>
 __host__ __device__ inline size_t cmp_lds_bytes(int tw, int s_max) {
-  return (size_t)2 * StageLayout<D, 1, 1>::ELEMS * sizeof(bf16_t) + 32 + ((size_t)tw * s_max + 4 * ((s_max + 31) / 32)) * 4;
+  return (size_t)2 * StageLayout<D, 1, 1>::ELEMS * sizeof(bf16_t) + 32 + ((size_t)tw * s_max + 4 * ((s_max + 31) / 32) + 4 * 4 * 16) * 4;
 }
 
 // Compression branch (eq. (4) first term over the mean-pooled keys of eq. (5)), then the selection scores of
@@ -171,7 +172,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
   if (!tm.valid) return;
   const int g = tm.g, wg_pos0 = tm.tile * TW;
   uint32_t *S = (uint32_t *)(ints + 8);
-  uint32_t *sel = S + (size_t)TW * s_max + (size_t)wid * ((s_max + 31) >> 5);
+  uint32_t *sel_base = S + (size_t)TW * s_max;
+  uint32_t *sel = sel_base + (size_t)wid * ((s_max + 31) >> 5);
   QRows<D, CB> q;
   load_rows<D, CB>(a.Q, a.v, wg_pos0, g, q);
   int lo[CB], hi[CB], s0[CB];
@@ -209,36 +211,88 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
 
   // ---- selection scores, eq. (6): second walk over the pooled keys with the normaliser known
   for (int i = threadIdx.x; i < TW * s_max; i += 256) S[i] = 0u;
-  __syncthreads();
   TileSrc<1, 0> ksrc{{a.v.Kc + (size_t)g * D}, {}, (size_t)a.v.Hkv * D};
-  run_pipeline<D, 1, 0>(
-      ksrc, stage0, ints + 4, ints + 5, nr, [](int) {},
-      [&](const bf16_t *stg, int kb, int) {
-        float s[CB][8];
-        score_tile<D, CB>(stg, q, act, s);
-        const bool inner = uniform && kb >= rs && kb + 32 <= re;
-        const int hl = n % hs;
+  if (hs >= 4) {
+    // Scores NOT transposed here (S = Q K^T: query rows x keys), so that a lane holds four heads of ONE token for
+    // one key: the sum over the group's heads (eq. (6), inner sum) is three in-lane adds plus at most two lane
+    // exchanges, and one integer LDS atomic per (token, key) adds it onto the key's selection block (outer sum).
+    float *lse_l = (float *)(sel_base + 4 * ((s_max + 31) >> 5));  // [4 waves][CB][16] lse2 per query row
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb) {
-          float p[8];
+    for (int cb = 0; cb < CB; ++cb)
+      if (quad == 0) lse_l[(wid * CB + cb) * 16 + n] = lse2[cb];
+    __syncthreads();
+    float l4[CB][4];
+    int klo[CB], khi[CB], ks0[CB], kslot[CB];
+    bool owner[CB];
 #pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            const int key = kb + 8 * quad + j;
-            const float e = fast_exp2(__builtin_fmaf(s[cb][j], sl2, -lse2[cb]));
-            p[j] = (inner || (key >= lo[cb] && key < hi[cb])) ? e : 0.f;
-            p[j] = group_sum(p[j], hs);  // sum over the group's heads (eq. (6), inner sum)
+    for (int cb = 0; cb < CB; ++cb) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) l4[cb][i] = lse_l[(wid * CB + cb) * 16 + 4 * quad + i];
+      kslot[cb] = (wid * CB + cb) * (16 / hs) + (4 * quad) / hs;  // the token of this lane's four rows
+      const int pos = wg_pos0 + kslot[cb];
+      const bool ok = pos < a.v.N;
+      const int item = ok ? a.v.tok_item[pos] : 0;
+      klo[cb] = ok ? a.v.cmp_batch[item] : 0;
+      khi[cb] = ok ? a.v.cmp_batch[item + 1] : 0;
+      ks0[cb] = ok ? a.v.slc_batch[item] : 0;
+      owner[cb] = (4 * quad) % hs == 0;
+    }
+    run_pipeline<D, 1, 0>(
+        ksrc, stage0, ints + 4, ints + 5, nr, [](int) {},
+        [&](const bf16_t *stg, int kb, int) {
+#pragma unroll
+          for (int sub = 0; sub < 2; ++sub) {
+            f32x4 c[CB];
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) c[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < D / 32; ++ks) {
+              const bf16x8 kop =
+                  *reinterpret_cast<const bf16x8 *>(stg + TileGeom<D>::row_off(16 * sub + n, 4 * ks + quad));
+#pragma unroll
+              for (int cb = 0; cb < CB; ++cb) c[cb] = mfma16(q.qop[cb][ks], kop, c[cb]);
+            }
+            const int key = kb + 16 * sub + n;
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+              float t = 0.f;
+#pragma unroll
+              for (int i = 0; i < 4; ++i) t += fast_exp2(__builtin_fmaf(c[cb][i], sl2, -l4[cb][i]));
+              if (hs >= 8) t += __shfl_xor(t, 16);
+              if (hs >= 16) t += __shfl_xor(t, 32);
+              if (owner[cb] && key >= klo[cb] && key < khi[cb])
+                atomicAdd(&S[(size_t)kslot[cb] * s_max + a.v.cmp_slc[key] - ks0[cb]], (uint32_t)(t * SCORE_FIX));
+            }
           }
-          // every lane of a head group now holds the same 8 sums; lane hl adds the sums of keys j = hl (mod hs)
-          // onto their selection blocks (eq. (6), outer sum over the child blocks)
-          uint32_t *Srow = S + (size_t)q.slot[cb] * s_max;
+        });
+  } else {
+    __syncthreads();
+    run_pipeline<D, 1, 0>(
+        ksrc, stage0, ints + 4, ints + 5, nr, [](int) {},
+        [&](const bf16_t *stg, int kb, int) {
+          float s[CB][8];
+          score_tile<D, CB>(stg, q, act, s);
+          const int hl = n % hs;
 #pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            const int key = kb + 8 * quad + j;
-            if (q.valid[cb] && (j % hs) == hl && hl < 8 && key >= lo[cb] && key < hi[cb])
-              atomicAdd(&Srow[a.v.cmp_slc[key] - s0[cb]], (uint32_t)(p[j] * SCORE_FIX));
+          for (int cb = 0; cb < CB; ++cb) {
+            float p[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+              p[j] = fast_exp2(__builtin_fmaf(s[cb][j], sl2, -lse2[cb]));
+              p[j] = group_sum(p[j], hs);  // sum over the group's heads (eq. (6), inner sum)
+            }
+            // every lane of a head group now holds the same 8 sums; lane hl adds the sums of keys j = hl (mod hs)
+            // onto their selection blocks (eq. (6), outer sum over the child blocks)
+            uint32_t *Srow = S + (size_t)q.slot[cb] * s_max;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+              const int key = kb + 8 * quad + j;
+              if (q.valid[cb] && (j % hs) == hl && key >= lo[cb] && key < hi[cb])
+                atomicAdd(&Srow[a.v.cmp_slc[key] - s0[cb]], (uint32_t)(p[j] * SCORE_FIX));
+            }
           }
-        }
-      });
+        });
+  }
   // ---- top-k: each wavefront serves its own token slots, one after the other
   const int spw = CB * 16 / hs;  // token slots per wavefront
   for (int tl = 0; tl < spw; ++tl) {
