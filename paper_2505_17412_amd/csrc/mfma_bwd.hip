@@ -155,14 +155,14 @@ __host__ __device__ inline size_t dq_lds_bytes(int tw, int T, int Ns) {
 
 // PART 0: compression branch only (its pooled keys stay L2 resident when nothing else streams through), result
 // kept in fp32; PART 1: window and selection branches on top of it, final bf16 dQ.
-template <int D, int CB, int PART>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4 : 2))) void m_bwd_dq(DqArgs a) {
+template <int D, int CB, int PART, int NW>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4 : 2))) void m_bwd_dq(DqArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   using L = StageLayout<D, 2, 1>;
   bf16_t *stage0 = (bf16_t *)smem;
   int *ints = (int *)(stage0 + 2 * L::ELEMS);
   const int quad = threadIdx.x >> 4 & 3;
-  const int hs = a.v.hs, T = a.v.T, N = a.v.N, Ns = a.v.Ns, TW = 4 * CB * 16 / hs;
+  const int hs = a.v.hs, T = a.v.T, N = a.v.N, Ns = a.v.Ns, TW = NW * CB * 16 / hs;
   const TileMap tm = xcd_tile_map((N + TW - 1) / TW, a.v.Hkv);
   if (!tm.valid) return;
   const int g = tm.g, wg_pos0 = tm.tile * TW;
@@ -223,7 +223,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
     TileSrc<2, 1> src = branch == 0
         ? TileSrc<2, 1>{{a.v.Kc + (size_t)g * D, a.v.Vc + (size_t)g * D}, {a.v.Kct + (size_t)g * D * 8}, kstride}
         : TileSrc<2, 1>{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, {a.v.Kt + (size_t)g * D * 8}, kstride};
-    run_pipeline<D, 2, 1>(
+    run_pipeline<D, 2, 1, 64 * NW>(
         src, stage0, ints + 4, ints + 5, re > rs ? 1 : 0, [](int) {},
         [&](const bf16_t *stg, int kb, int) {
           bf16_t *st = (bf16_t *)stg;
@@ -250,7 +250,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
     }
     int rs = 0, re = 0;
     TileSrc<2, 1> src{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, {a.v.Kt + (size_t)g * D * 8}, kstride};
-    run_pipeline<D, 2, 1>(
+    run_pipeline<D, 2, 1, 64 * NW>(
         src, stage0, us, ue, nr,
         [&](int r) {
           const int b = lds_uniform(&ub[r]);
@@ -403,12 +403,12 @@ __global__ __launch_bounds__(256) void m_bwd_dkv(DkvArgs a) {
       p[sidx] = (sidx < slots && sl < qend) ? (MODE == DKV_SLC ? a.sel_list[sl] : sl) : -1;
     }
   };
-  bf16x8 rq[G::ROW_PER_THREAD], rd[G::ROW_PER_THREAD], tq[G::T_PER_THREAD], td[G::T_PER_THREAD];
+  bf16x8 rq[G::row_per_thread(256)], rd[G::row_per_thread(256)], tq[G::t_per_thread(256)], td[G::t_per_thread(256)];
   float sc = 0.f;
   auto pick = [](const int (&p)[4], int i) { return i == 0 ? p[0] : (i == 1 ? p[1] : (i == 2 ? p[2] : p[3])); };
   auto load_tile = [&](const int (&p)[4]) {
 #pragma unroll
-    for (int i = 0; i < G::ROW_PER_THREAD; ++i) {
+    for (int i = 0; i < G::row_per_thread(256); ++i) {
       const int it = threadIdx.x + 256 * i;
       if (G::ROW_ITEMS % 256 == 0 || it < G::ROW_ITEMS) {
         const int row = it / (D / 8), seg = it % (D / 8);
@@ -419,7 +419,7 @@ __global__ __launch_bounds__(256) void m_bwd_dkv(DkvArgs a) {
       }
     }
 #pragma unroll
-    for (int i = 0; i < G::T_PER_THREAD; ++i) {
+    for (int i = 0; i < G::t_per_thread(256); ++i) {
       const int it = threadIdx.x + 256 * i;
       if (G::T_ITEMS % 256 == 0 || it < G::T_ITEMS) {
         const int chunk = it / D, dim = it % D;
@@ -441,7 +441,7 @@ __global__ __launch_bounds__(256) void m_bwd_dkv(DkvArgs a) {
   auto store_tile = [&](unsigned char *stage) {
     bf16_t *e = (bf16_t *)stage;
 #pragma unroll
-    for (int i = 0; i < G::ROW_PER_THREAD; ++i) {
+    for (int i = 0; i < G::row_per_thread(256); ++i) {
       const int it = threadIdx.x + 256 * i;
       if (G::ROW_ITEMS % 256 == 0 || it < G::ROW_ITEMS) {
         const int off = G::row_off(it / (D / 8), it % (D / 8));
@@ -450,7 +450,7 @@ __global__ __launch_bounds__(256) void m_bwd_dkv(DkvArgs a) {
       }
     }
 #pragma unroll
-    for (int i = 0; i < G::T_PER_THREAD; ++i) {
+    for (int i = 0; i < G::t_per_thread(256); ++i) {
       const int it = threadIdx.x + 256 * i;
       if (G::T_ITEMS % 256 == 0 || it < G::T_ITEMS) {
         const int off = 2 * G::ROW_ELEMS + G::t_off(it % D, it / D);
@@ -702,6 +702,7 @@ __global__ void m_bwd_finish(const int32_t *__restrict__ perm, const int32_t *__
   }
 }
 
+constexpr int DQ_SLC_WAVES = 4;  // wavefronts per workgroup of the selection/window dQ kernel (16 tokens at h_s = 8)
 constexpr int KB_KEYS = 2;  // key blocks of 16 per wavefront in the dK/dV kernels (keep 64*KB_KEYS <= SSA_KEY_PAD)
 
 template <int D>
@@ -719,17 +720,16 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
   {
     ProfScope ps(PROF_BWD_DQ, s);
     DqArgs a{v, (const bf16_t *)q, (const bf16_t *)dout, idx, w.lse2s, w.deltas, w.gws, (bf16_t *)dq, w.dQp};
-    constexpr int CB = 1;
-    const int tw = 4 * CB * 16 / v.hs;
+    constexpr int CB = 1, NW0 = 4, NW1 = DQ_SLC_WAVES;
+    const int tw0 = NW0 * CB * 16 / v.hs, tw1 = NW1 * CB * 16 / v.hs;
     static bool attr_done = false;
     if (!attr_done) {
-      (void)hipFuncSetAttribute((const void *)m_bwd_dq<D, CB, 0>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-      (void)hipFuncSetAttribute((const void *)m_bwd_dq<D, CB, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      (void)hipFuncSetAttribute((const void *)m_bwd_dq<D, CB, 0, NW0>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      (void)hipFuncSetAttribute((const void *)m_bwd_dq<D, CB, 1, NW1>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
       attr_done = true;
     }
-    const dim3 grid(xcd_grid_size((N + tw - 1) / tw, Hkv));
-    m_bwd_dq<D, CB, 0><<<grid, 256, dq_lds_bytes<D>(tw, v.T, v.Ns), s>>>(a);
-    m_bwd_dq<D, CB, 1><<<grid, 256, dq_lds_bytes<D>(tw, v.T, v.Ns), s>>>(a);
+    m_bwd_dq<D, CB, 0, NW0><<<dim3(xcd_grid_size((N + tw0 - 1) / tw0, Hkv)), 64 * NW0, dq_lds_bytes<D>(tw0, v.T, v.Ns), s>>>(a);
+    m_bwd_dq<D, CB, 1, NW1><<<dim3(xcd_grid_size((N + tw1 - 1) / tw1, Hkv)), 64 * NW1, dq_lds_bytes<D>(tw1, v.T, v.Ns), s>>>(a);
   }
   constexpr int WG_KEYS = 64 * KB_KEYS;
   const size_t dkv_lds = (size_t)2 * DkvStage<D>::BYTES;

@@ -248,11 +248,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
 #pragma unroll
             for (int ks = 0; ks < D / 32; ++ks) {
               const bf16x8 kop =
-                  *reinterpret_cast<const bf16x8 *>(stg + TileGeom<D>::row_off(16 * sub + n, 4 * ks + quad));
+                  *reinterpret_cast<const bf16x8 *>(stg + TileGeom<D>::slot_off(16 * sub + n, 4 * ks + quad));
 #pragma unroll
               for (int cb = 0; cb < CB; ++cb) c[cb] = mfma16(q.qop[cb][ks], kop, c[cb]);
             }
-            const int key = kb + 16 * sub + n;
+            const int key = tile_key_row(kb, sub);  // column n of sub-tile `sub` sits in row slot 16*sub + n
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb) {
               float t = 0.f;
@@ -313,14 +313,14 @@ __host__ __device__ inline size_t slc_lds_bytes(int tw, int T, int Ns) {
 // Selection branch: Algorithm 1.  The workgroup walks the union of the blocks its tokens selected, in ascending
 // id; a token that did not select the current block sees it fully masked, a wavefront none of whose tokens
 // selected it skips the arithmetic.
-template <int D, int CB>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4 : 2))) void m_slc_fwd(FwdArgs a) {
+template <int D, int CB, int NW>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4 : 2))) void m_slc_fwd(FwdArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   using L = StageLayout<D, 1, 1>;
   bf16_t *stage0 = (bf16_t *)smem;
   int *ints = (int *)(stage0 + 2 * L::ELEMS);
   const int lane = threadIdx.x & 63;
-  const int hs = a.v.hs, T = a.v.T, Ns = a.v.Ns, TW = 4 * CB * 16 / hs;
+  const int hs = a.v.hs, T = a.v.T, Ns = a.v.Ns, TW = NW * CB * 16 / hs;
   const TileMap tm = xcd_tile_map((a.v.N + TW - 1) / TW, a.v.Hkv);
   if (!tm.valid) return;
   const int g = tm.g, wg_pos0 = tm.tile * TW;
@@ -343,7 +343,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
   init_state(st);
   const float sl2 = a.v.sl2;
   int rs = 0, re = 0;
-  run_pipeline<D, 1, 1>(
+  run_pipeline<D, 1, 1, 64 * NW>(
       src, stage0, us, ue, nr,
       [&](int r) {
         const int b = lds_uniform(&ub[r]);
@@ -441,18 +441,20 @@ __global__ void m_combine(const bf16_t *__restrict__ Ob, const bf16_t *__restric
   *reinterpret_cast<bf16x8 *>(out + off) = o;
 }
 
-constexpr int FWD_CB = 1;  // blocks of 16 query columns per wavefront
+constexpr int FWD_CB = 1;
+constexpr int SLC_WAVES = 4;  // wavefronts per workgroup of the selection kernel  // blocks of 16 query columns per wavefront
 
 template <int D>
 int launch_forward(const FwdArgs &a, const bf16_t *gates, bf16_t *out, hipStream_t s) {
   const int tw = 4 * FWD_CB * 16 / a.v.hs;
   const dim3 grid(xcd_grid_size((a.v.N + tw - 1) / tw, a.v.Hkv));
-  const size_t lds_cmp = cmp_lds_bytes<D>(tw, a.v.s_max), lds_slc = slc_lds_bytes<D>(tw, a.v.T, a.v.Ns);
+  const int tw_slc = SLC_WAVES * FWD_CB * 16 / a.v.hs;
+  const size_t lds_cmp = cmp_lds_bytes<D>(tw, a.v.s_max), lds_slc = slc_lds_bytes<D>(tw_slc, a.v.T, a.v.Ns);
   const size_t lds_win = (size_t)2 * StageLayout<D, 1, 1>::ELEMS * sizeof(bf16_t) + 32;
   static bool attr_done = false;  // raise the dynamic LDS limit once per process for these instantiations
   if (!attr_done) {
     (void)hipFuncSetAttribute((const void *)m_cmp_fwd<D, FWD_CB>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    (void)hipFuncSetAttribute((const void *)m_slc_fwd<D, FWD_CB>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    (void)hipFuncSetAttribute((const void *)m_slc_fwd<D, FWD_CB, SLC_WAVES>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     attr_done = true;
   }
   {
@@ -461,7 +463,7 @@ int launch_forward(const FwdArgs &a, const bf16_t *gates, bf16_t *out, hipStream
   }
   {
     ProfScope ps(PROF_SLC_FWD, s);
-    m_slc_fwd<D, FWD_CB><<<grid, 256, lds_slc, s>>>(a);
+    m_slc_fwd<D, FWD_CB, SLC_WAVES><<<dim3(xcd_grid_size((a.v.N + tw_slc - 1) / tw_slc, a.v.Hkv)), 64 * SLC_WAVES, lds_slc, s>>>(a);
   }
   {
     ProfScope ps(PROF_WIN_FWD, s);
@@ -479,12 +481,12 @@ int launch_forward(const FwdArgs &a, const bf16_t *gates, bf16_t *out, hipStream
 
 // Largest dynamic LDS request of the forward kernels for this problem (bytes).
 size_t mfma_fwd_lds_bytes(int D, int hs, int s_max, int T, int Ns) {
-  const int tw = 4 * FWD_CB * 16 / hs;
+  const int tw = 4 * FWD_CB * 16 / hs, tws = SLC_WAVES * FWD_CB * 16 / hs;
   size_t a = 0, b = 0;
   switch (D) {
-    case 32: a = cmp_lds_bytes<32>(tw, s_max); b = slc_lds_bytes<32>(tw, T, Ns); break;
-    case 64: a = cmp_lds_bytes<64>(tw, s_max); b = slc_lds_bytes<64>(tw, T, Ns); break;
-    default: a = cmp_lds_bytes<128>(tw, s_max); b = slc_lds_bytes<128>(tw, T, Ns); break;
+    case 32: a = cmp_lds_bytes<32>(tw, s_max); b = slc_lds_bytes<32>(tws, T, Ns); break;
+    case 64: a = cmp_lds_bytes<64>(tw, s_max); b = slc_lds_bytes<64>(tws, T, Ns); break;
+    default: a = cmp_lds_bytes<128>(tw, s_max); b = slc_lds_bytes<128>(tws, T, Ns); break;
   }
   return a > b ? a : b;
 }

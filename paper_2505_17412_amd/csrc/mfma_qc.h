@@ -10,31 +10,37 @@
 #include "mfma_common.h"
 #include "topk_device.h"
 
-// LDS geometry of one staged tile set.  Row-major tiles: 32 key rows of D (+8 pad) bf16, 16-byte segments XOR
-// swizzled by bit 3 of the row so that the rows {0-3, 8-11} (and {4-7, 12-15}, ...) an operand read touches in
-// one 8-lane phase fall into different 16-byte bank groups.  Transposed tiles: D rows (dims) of 32 keys (+8 pad).
+// LDS geometry of one staged tile set.
+// Row-major tiles (32 rows of D bf16, no padding) are stored as [16-byte segment][row slot][8 elements]: the slot of
+// row k is sigma(k) = 16*((k>>2)&1) + 4*(k>>3) + (k&3), i.e. the 16 rows lane n = 0..15 of sub-tile a reads (see
+// tile_key_row) occupy the consecutive slots 16a .. 16a+15, so one operand read of a 16-lane quad covers 256
+// contiguous bytes.  The slot is XORed with (segment & 7): reads stay a permutation of the same 16 slots, and the
+// 8 threads that stage one row (8 segments, 512 bytes apart) land in 8 different 16-byte bank groups.
+// Transposed tiles: D rows (dims) of 32 keys (+8 pad) = 80-byte rows, conflict free for reads and writes.
 template <int D>
 struct TileGeom {
-  static constexpr int KROW = D + 8;
-  static constexpr int ROW_ELEMS = 32 * KROW;
+  static constexpr int ROW_ELEMS = 32 * D;
   static constexpr int TROW = 40;
   static constexpr int T_ELEMS = D * TROW;
   static constexpr int ROW_ITEMS = 32 * D / 8;                  // 16-byte items of a row-major tile
   static constexpr int T_ITEMS = 4 * D;                         // 16-byte items of a transposed tile
-  static constexpr int ROW_PER_THREAD = (ROW_ITEMS + 255) / 256;
-  static constexpr int T_PER_THREAD = (T_ITEMS + 255) / 256;
-  __device__ static inline int swz(int row) { return D >= 64 ? ((row >> 3) & 1) * 4 : 0; }
-  // element offset of (row, 16-byte segment) inside a row-major tile
-  __device__ static inline int row_off(int row, int seg) { return row * KROW + ((seg ^ swz(row)) << 3); }
+  // 16-byte items per thread when NTHR threads stage a tile
+  static constexpr int row_per_thread(int nthr) { return (ROW_ITEMS + nthr - 1) / nthr; }
+  static constexpr int t_per_thread(int nthr) { return (T_ITEMS + nthr - 1) / nthr; }
+  __device__ static inline int sigma(int row) { return 16 * ((row >> 2) & 1) + 4 * (row >> 3) + (row & 3); }
+  // element offset of (row slot, 16-byte segment) inside a row-major tile
+  __device__ static inline int slot_off(int slot, int seg) { return ((seg << 5) + (slot ^ (seg & 7))) << 3; }
+  // element offset of (row, 16-byte segment)
+  __device__ static inline int row_off(int row, int seg) { return slot_off(sigma(row), seg); }
   // element offset of (dim, chunk of 8 keys) inside a transposed tile
   __device__ static inline int t_off(int dim, int chunk) { return dim * TROW + (chunk << 3); }
 };
 
 // Registers holding one tile set on its way from global memory to LDS.
-template <int D, int NROW, int NT>
+template <int D, int NROW, int NT, int NTHR = 256>
 struct TileRegs {
-  bf16x8 r[NROW][TileGeom<D>::ROW_PER_THREAD];
-  bf16x8 t[NT][TileGeom<D>::T_PER_THREAD];
+  bf16x8 r[NROW][TileGeom<D>::row_per_thread(NTHR)];
+  bf16x8 t[NT][TileGeom<D>::t_per_thread(NTHR)];
 };
 
 // Global sources of a tile set: row-major arrays [rows][Hkv][D] and chunk-transposed arrays [rows/8][Hkv][D][8],
@@ -46,15 +52,15 @@ struct TileSrc {
   size_t kstride;  // elements between consecutive rows of a row-major array (Hkv*D)
 };
 
-template <int D, int NROW, int NT>
-__device__ inline void tile_load(TileRegs<D, NROW, NT> &regs, const TileSrc<NROW, NT> &src, int kb) {
+template <int D, int NROW, int NT, int NTHR>
+__device__ inline void tile_load(TileRegs<D, NROW, NT, NTHR> &regs, const TileSrc<NROW, NT> &src, int kb) {
   using G = TileGeom<D>;
 #pragma unroll
   for (int x = 0; x < NROW; ++x)
 #pragma unroll
-    for (int i = 0; i < G::ROW_PER_THREAD; ++i) {
-      const int it = threadIdx.x + 256 * i;
-      if (G::ROW_ITEMS % 256 == 0 || it < G::ROW_ITEMS) {
+    for (int i = 0; i < G::row_per_thread(NTHR); ++i) {
+      const int it = threadIdx.x + NTHR * i;
+      if (G::ROW_ITEMS % NTHR == 0 || it < G::ROW_ITEMS) {
         const int row = it / (D / 8), seg = it % (D / 8);
         regs.r[x][i] = ld8(src.row[x] + (size_t)(kb + row) * src.kstride + seg * 8);
       }
@@ -62,9 +68,9 @@ __device__ inline void tile_load(TileRegs<D, NROW, NT> &regs, const TileSrc<NROW
 #pragma unroll
   for (int x = 0; x < NT; ++x)
 #pragma unroll
-    for (int i = 0; i < G::T_PER_THREAD; ++i) {
-      const int it = threadIdx.x + 256 * i;
-      if (G::T_ITEMS % 256 == 0 || it < G::T_ITEMS) {
+    for (int i = 0; i < G::t_per_thread(NTHR); ++i) {
+      const int it = threadIdx.x + NTHR * i;
+      if (G::T_ITEMS % NTHR == 0 || it < G::T_ITEMS) {
         const int chunk = it / D, dim = it % D;
         regs.t[x][i] = ld8(src.tr[x] + (size_t)((kb >> 3) + chunk) * src.kstride * 8 + (size_t)dim * 8);
       }
@@ -81,16 +87,16 @@ struct StageLayout {
   }
 };
 
-template <int D, int NROW, int NT>
-__device__ inline void tile_store(const TileRegs<D, NROW, NT> &regs, bf16_t *stage) {
+template <int D, int NROW, int NT, int NTHR>
+__device__ inline void tile_store(const TileRegs<D, NROW, NT, NTHR> &regs, bf16_t *stage) {
   using G = TileGeom<D>;
   using L = StageLayout<D, NROW, NT>;
 #pragma unroll
   for (int x = 0; x < NROW; ++x)
 #pragma unroll
-    for (int i = 0; i < G::ROW_PER_THREAD; ++i) {
-      const int it = threadIdx.x + 256 * i;
-      if (G::ROW_ITEMS % 256 == 0 || it < G::ROW_ITEMS) {
+    for (int i = 0; i < G::row_per_thread(NTHR); ++i) {
+      const int it = threadIdx.x + NTHR * i;
+      if (G::ROW_ITEMS % NTHR == 0 || it < G::ROW_ITEMS) {
         const int row = it / (D / 8), seg = it % (D / 8);
         *reinterpret_cast<bf16x8 *>(L::row_tile(stage, x) + G::row_off(row, seg)) = regs.r[x][i];
       }
@@ -98,9 +104,9 @@ __device__ inline void tile_store(const TileRegs<D, NROW, NT> &regs, bf16_t *sta
 #pragma unroll
   for (int x = 0; x < NT; ++x)
 #pragma unroll
-    for (int i = 0; i < G::T_PER_THREAD; ++i) {
-      const int it = threadIdx.x + 256 * i;
-      if (G::T_ITEMS % 256 == 0 || it < G::T_ITEMS) {
+    for (int i = 0; i < G::t_per_thread(NTHR); ++i) {
+      const int it = threadIdx.x + NTHR * i;
+      if (G::T_ITEMS % NTHR == 0 || it < G::T_ITEMS) {
         const int chunk = it / D, dim = it % D;
         *reinterpret_cast<bf16x8 *>(L::t_tile(stage, x) + G::t_off(dim, chunk)) = regs.t[x][i];
       }
@@ -111,8 +117,7 @@ __device__ inline void tile_store(const TileRegs<D, NROW, NT> &regs, bf16_t *sta
 template <int D>
 __device__ inline bf16x8 lds_row_operand(const bf16_t *tile, int a, int ks) {
   const int n = threadIdx.x & 15, quad = threadIdx.x >> 4 & 3;
-  const int row = 8 * (n >> 2) + 4 * a + (n & 3);
-  return *reinterpret_cast<const bf16x8 *>(tile + TileGeom<D>::row_off(row, 4 * ks + quad));
+  return *reinterpret_cast<const bf16x8 *>(tile + TileGeom<D>::slot_off(16 * a + n, 4 * ks + quad));
 }
 // A operand of dim block dt from a transposed LDS tile (row = dim 16*dt + n, keys 8*quad .. +7).
 template <int D>
@@ -190,21 +195,21 @@ __device__ inline void load_rows(const bf16_t *Q, const MfmaView &v, int wg_pos0
 
 // Walk the tiles of the key ranges rng_s/rng_e[0..nr) (LDS, workgroup-uniform): stage tile i+1 while tile i is
 // consumed.  enter(r) runs when the walk reaches range r, tile(stage, kb, r) consumes one staged tile.
-template <int D, int NROW, int NT, class Enter, class Tile>
+template <int D, int NROW, int NT, int NTHR = 256, class Enter, class Tile>
 __device__ inline void run_pipeline(const TileSrc<NROW, NT> &src, bf16_t *stage0, const int *rng_s, const int *rng_e, int nr,
                                     Enter enter, Tile tile) {
   using L = StageLayout<D, NROW, NT>;
   if (nr > 0) {
-    TileRegs<D, NROW, NT> regs;
+    TileRegs<D, NROW, NT, NTHR> regs;
     TileIter it = iter_begin(rng_s, nr);
-    tile_load<D, NROW, NT>(regs, src, it.kb);
+    tile_load<D, NROW, NT, NTHR>(regs, src, it.kb);
     int buf = 0, cur_r = -1;
     while (it.r < nr) {
       bf16_t *st = stage0 + buf * L::ELEMS;
-      tile_store<D, NROW, NT>(regs, st);
+      tile_store<D, NROW, NT, NTHR>(regs, st);
       __syncthreads();
       const TileIter nx = iter_next(it, rng_s, rng_e, nr);
-      if (nx.r < nr) tile_load<D, NROW, NT>(regs, src, nx.kb);
+      if (nx.r < nr) tile_load<D, NROW, NT, NTHR>(regs, src, nx.kb);
       if (it.r != cur_r) {
         cur_r = it.r;
         enter(cur_r);
@@ -282,13 +287,13 @@ __device__ inline void build_union(const MfmaView &v, const int32_t *idx, int wg
                                    int *us, int *ue, uint32_t *bits, int *count) {
   const int T = v.T, Ns = v.Ns, lane = threadIdx.x & 63;
   const int words = (Ns + 31) >> 5;
-  for (int i = threadIdx.x; i < TW * T; i += 256) {
+  for (int i = threadIdx.x; i < TW * T; i += blockDim.x) {
     const int pos = wg_pos0 + i / T;
     Irows[i] = pos < v.N ? idx[((size_t)v.perm[pos] * v.Hkv + g) * T + i % T] : -1;
   }
-  for (int i = threadIdx.x; i < words; i += 256) bits[i] = 0u;
+  for (int i = threadIdx.x; i < words; i += blockDim.x) bits[i] = 0u;
   __syncthreads();
-  for (int i = threadIdx.x; i < TW * T; i += 256) {
+  for (int i = threadIdx.x; i < TW * T; i += blockDim.x) {
     const int b = Irows[i];
     if (b >= 0 && b < Ns) atomicOr(&bits[b >> 5], 1u << (b & 31));
   }
