@@ -330,11 +330,11 @@ struct DkvStage {
 // A workgroup owns 64*KB keys of one block (16*KB per wavefront, held in registers as MFMA B operands) and
 // streams the query rows that attend to them in tiles of 32 rows = 32/h_s token slots, staged through LDS once per
 // workgroup and double buffered.
-template <int D, int KB, int MODE>
-__global__ __launch_bounds__(256) void m_bwd_dkv(DkvArgs a) {
+template <int D, int KB, int MODE, int NW>
+__global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
   const int wid = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 15, quad = lane >> 4;
   const int hs = a.v.hs, Hq = a.v.Hq;
-  constexpr int WG_KEYS = 64 * KB;
+  constexpr int WG_KEYS = 16 * KB * NW, NTHR = 64 * NW;
   int g = blockIdx.y, blk, tile;
   // key range of the block and query source
   int kbeg, kend, qbeg = 0, qend = 0;
@@ -403,14 +403,14 @@ __global__ __launch_bounds__(256) void m_bwd_dkv(DkvArgs a) {
       p[sidx] = (sidx < slots && sl < qend) ? (MODE == DKV_SLC ? a.sel_list[sl] : sl) : -1;
     }
   };
-  bf16x8 rq[G::row_per_thread(256)], rd[G::row_per_thread(256)], tq[G::t_per_thread(256)], td[G::t_per_thread(256)];
+  bf16x8 rq[G::row_per_thread(NTHR)], rd[G::row_per_thread(NTHR)], tq[G::t_per_thread(NTHR)], td[G::t_per_thread(NTHR)];
   float sc = 0.f;
   auto pick = [](const int (&p)[4], int i) { return i == 0 ? p[0] : (i == 1 ? p[1] : (i == 2 ? p[2] : p[3])); };
   auto load_tile = [&](const int (&p)[4]) {
 #pragma unroll
-    for (int i = 0; i < G::row_per_thread(256); ++i) {
-      const int it = threadIdx.x + 256 * i;
-      if (G::ROW_ITEMS % 256 == 0 || it < G::ROW_ITEMS) {
+    for (int i = 0; i < G::row_per_thread(NTHR); ++i) {
+      const int it = threadIdx.x + NTHR * i;
+      if (G::ROW_ITEMS % NTHR == 0 || it < G::ROW_ITEMS) {
         const int row = it / (D / 8), seg = it % (D / 8);
         const int pos = max(pick(p, row / hs), 0);
         const size_t off = ((size_t)pos * Hq + g * hs + row % hs) * D + seg * 8;
@@ -419,9 +419,9 @@ __global__ __launch_bounds__(256) void m_bwd_dkv(DkvArgs a) {
       }
     }
 #pragma unroll
-    for (int i = 0; i < G::t_per_thread(256); ++i) {
-      const int it = threadIdx.x + 256 * i;
-      if (G::T_ITEMS % 256 == 0 || it < G::T_ITEMS) {
+    for (int i = 0; i < G::t_per_thread(NTHR); ++i) {
+      const int it = threadIdx.x + NTHR * i;
+      if (G::T_ITEMS % NTHR == 0 || it < G::T_ITEMS) {
         const int chunk = it / D, dim = it % D;
         const int pos = max(pick(p, chunk * 8 / hs), 0);
         const size_t off = (((size_t)pos * a.v.Hkv + g) * D + dim) * hs + (chunk * 8) % hs;
@@ -441,18 +441,18 @@ __global__ __launch_bounds__(256) void m_bwd_dkv(DkvArgs a) {
   auto store_tile = [&](unsigned char *stage) {
     bf16_t *e = (bf16_t *)stage;
 #pragma unroll
-    for (int i = 0; i < G::row_per_thread(256); ++i) {
-      const int it = threadIdx.x + 256 * i;
-      if (G::ROW_ITEMS % 256 == 0 || it < G::ROW_ITEMS) {
+    for (int i = 0; i < G::row_per_thread(NTHR); ++i) {
+      const int it = threadIdx.x + NTHR * i;
+      if (G::ROW_ITEMS % NTHR == 0 || it < G::ROW_ITEMS) {
         const int off = G::row_off(it / (D / 8), it % (D / 8));
         *reinterpret_cast<bf16x8 *>(e + off) = rq[i];
         *reinterpret_cast<bf16x8 *>(e + G::ROW_ELEMS + off) = rd[i];
       }
     }
 #pragma unroll
-    for (int i = 0; i < G::t_per_thread(256); ++i) {
-      const int it = threadIdx.x + 256 * i;
-      if (G::T_ITEMS % 256 == 0 || it < G::T_ITEMS) {
+    for (int i = 0; i < G::t_per_thread(NTHR); ++i) {
+      const int it = threadIdx.x + NTHR * i;
+      if (G::T_ITEMS % NTHR == 0 || it < G::T_ITEMS) {
         const int off = 2 * G::ROW_ELEMS + G::t_off(it % D, it / D);
         *reinterpret_cast<bf16x8 *>(e + off) = tq[i];
         *reinterpret_cast<bf16x8 *>(e + G::T_ELEMS + off) = td[i];
@@ -703,7 +703,10 @@ __global__ void m_bwd_finish(const int32_t *__restrict__ perm, const int32_t *__
 }
 
 constexpr int DQ_SLC_WAVES = 4;  // wavefronts per workgroup of the selection/window dQ kernel (16 tokens at h_s = 8)
-constexpr int KB_KEYS = 2;  // key blocks of 16 per wavefront in the dK/dV kernels (keep 64*KB_KEYS <= SSA_KEY_PAD)
+constexpr int KB_KEYS = 2;    // key blocks of 16 per wavefront in the dK/dV kernels
+// wavefronts per workgroup there (16*KB_KEYS keys each): blocks and windows hold ~130 tokens, an item's pooled keys
+// thousands, so the compression branch takes wider workgroups (fewer passes over the query rows)
+constexpr int DKV_WAVES = 4, DKV_WAVES_CMP = 8;
 
 template <int D>
 int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const void *gates, const void *out_branch,
@@ -731,13 +734,14 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
     m_bwd_dq<D, CB, 0, NW0><<<dim3(xcd_grid_size((N + tw0 - 1) / tw0, Hkv)), 64 * NW0, dq_lds_bytes<D>(tw0, v.T, v.Ns), s>>>(a);
     m_bwd_dq<D, CB, 1, NW1><<<dim3(xcd_grid_size((N + tw1 - 1) / tw1, Hkv)), 64 * NW1, dq_lds_bytes<D>(tw1, v.T, v.Ns), s>>>(a);
   }
-  constexpr int WG_KEYS = 64 * KB_KEYS;
+  constexpr int WG_KEYS = 16 * KB_KEYS * DKV_WAVES, WG_KEYS_CMP = 16 * KB_KEYS * DKV_WAVES_CMP;
+  static_assert(WG_KEYS <= SSA_KEY_PAD && WG_KEYS_CMP <= SSA_KEY_PAD, "key tiles may read up to WG_KEYS rows past a block");
   const size_t dkv_lds = (size_t)2 * DkvStage<D>::BYTES;
   static bool dkv_attr = false;
   if (!dkv_attr) {
-    (void)hipFuncSetAttribute((const void *)m_bwd_dkv<D, KB_KEYS, DKV_WIN>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    (void)hipFuncSetAttribute((const void *)m_bwd_dkv<D, KB_KEYS, DKV_SLC>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    (void)hipFuncSetAttribute((const void *)m_bwd_dkv<D, KB_KEYS, DKV_CMP>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    (void)hipFuncSetAttribute((const void *)m_bwd_dkv<D, KB_KEYS, DKV_WIN, DKV_WAVES>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    (void)hipFuncSetAttribute((const void *)m_bwd_dkv<D, KB_KEYS, DKV_SLC, DKV_WAVES>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    (void)hipFuncSetAttribute((const void *)m_bwd_dkv<D, KB_KEYS, DKV_CMP, DKV_WAVES_CMP>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     dkv_attr = true;
   }
   DkvArgs base{v, w.Qs, w.dOs, w.QT, w.dOT, nullptr, nullptr, nullptr, w.sel_start, w.sel_list,
@@ -747,7 +751,7 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
     DkvArgs a = base;
     a.lse2s = w.lse2s + 2 * NH; a.deltas = w.deltas + 2 * NH; a.gws = w.gws + 2 * NH;
     a.tiles_per_block = (blk->win_tok_max + WG_KEYS - 1) / WG_KEYS;
-    m_bwd_dkv<D, KB_KEYS, DKV_WIN><<<dim3(blk->Nw * a.tiles_per_block, Hkv), 256, dkv_lds, s>>>(a);
+    m_bwd_dkv<D, KB_KEYS, DKV_WIN, DKV_WAVES><<<dim3(blk->Nw * a.tiles_per_block, Hkv), 64 * DKV_WAVES, dkv_lds, s>>>(a);
   }
   {
     ProfScope ps(PROF_BWD_INVERT, s);
@@ -766,7 +770,7 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
     a.lse2s = w.lse2s + NH; a.deltas = w.deltas + NH; a.gws = w.gws + NH;
     a.dK = w.pK; a.dV = w.pV;
     a.tiles_per_block = (blk->slc_tok_max + WG_KEYS - 1) / WG_KEYS;
-    m_bwd_dkv<D, KB_KEYS, DKV_SLC><<<dim3(w.max_chunks, a.tiles_per_block), 256, dkv_lds, s>>>(a);
+    m_bwd_dkv<D, KB_KEYS, DKV_SLC, DKV_WAVES><<<dim3(w.max_chunks, a.tiles_per_block), 64 * DKV_WAVES, dkv_lds, s>>>(a);
     const size_t items = (size_t)N * Hkv * (D / 4);
     m_slc_reduce<<<(unsigned)((items + 255) / 256), 256, 0, s>>>(blk->tok_slc, v.slc_start, w.chunk_start, w.part_row_start, N,
                                                                  Hkv, v.Ns, D, w.pK, w.pV, w.dKs, w.dVs);
@@ -776,9 +780,9 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
     DkvArgs a = base;
     a.lse2s = w.lse2s; a.deltas = w.deltas; a.gws = w.gws;
     a.dK = w.dKc; a.dV = w.dVc;
-    a.tiles_per_block = (blk->c_max + WG_KEYS - 1) / WG_KEYS;
+    a.tiles_per_block = (blk->c_max + WG_KEYS_CMP - 1) / WG_KEYS_CMP;
     a.q_splits = w.q_splits;
-    m_bwd_dkv<D, KB_KEYS, DKV_CMP><<<dim3(B * a.tiles_per_block, Hkv, w.q_splits), 256, dkv_lds, s>>>(a);
+    m_bwd_dkv<D, KB_KEYS, DKV_CMP, DKV_WAVES_CMP><<<dim3(B * a.tiles_per_block, Hkv, w.q_splits), 64 * DKV_WAVES_CMP, dkv_lds, s>>>(a);
   }
   {
     ProfScope ps(PROF_BWD_FINISH, s);

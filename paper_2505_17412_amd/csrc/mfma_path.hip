@@ -96,7 +96,7 @@ struct BwdPlan {
   int q_splits, chunk_len, max_chunks;
 };
 
-constexpr int DKV_WG_KEYS = 128;  // keys per workgroup of the dK/dV kernels (4 waves x 2 blocks of 16)
+constexpr int DKV_WG_KEYS = 256;  // keys per workgroup of the dK/dV kernels (8 waves x 2 blocks of 16)
 
 BwdPlan bwd_plan(const ssa_ctx &c) {
   BwdPlan p{};

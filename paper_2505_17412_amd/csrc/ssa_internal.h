@@ -15,7 +15,7 @@
 
 // Rows of zero padding kept after the last token / compressed block of the sorted K,V copies, so that a
 // key tile that starts inside the data may read past its end.
-constexpr int SSA_KEY_PAD = 128;
+constexpr int SSA_KEY_PAD = 256;
 
 struct ssa_blocks {
   int32_t N, B, G, m_cmp, m_slc, m_win, bits;
