@@ -147,3 +147,26 @@ def test_g128_bf16_forward_backward_sampled():
     The oracle visits every 97th query; dO is zero elsewhere (backward is linear in dO), so dK/dV compare in full."""
     wl = inputs.make_workload("g128")
     full_parity(wl, backward=True, queries=np.arange(5, wl.n_tokens, 97, dtype=np.int32))
+
+
+def test_batch_of_four_shapes_sampled():
+    """Variable-length batch: four 128^3 shapes (20k-70k tokens each) with batch offsets, bf16, 16 heads, d=64, T=16.
+    Every key set must stay inside the query's own item."""
+    wl = inputs.make_batch_workload()
+    full_parity(wl, backward=True, queries=np.arange(11, wl.n_tokens, 389, dtype=np.int32))
+
+
+@pytest.mark.parametrize("topk,m_win", [(16, 8), (32, 4)])
+def test_g128_thick_d128_sampled(topk, m_win):
+    """Stress config: thick shell (~150k tokens), head_dim 128, top-k and window size varied."""
+    wl = inputs.make_workload("g128_thick", topk=topk, m=(4, 8, m_win))
+    full_parity(wl, backward=True, queries=np.arange(3, wl.n_tokens, 613, dtype=np.int32))
+
+
+def test_forward_backward_are_deterministic():
+    """Two runs on the same inputs give bit-identical outputs (no order-dependent float atomics in the bf16 path)."""
+    wl = inputs.make_workload("g64")
+    a = util.run_gpu(wl, backward=True)
+    b = util.run_gpu(wl, backward=True)
+    for name in ("out", "lse", "topk_idx", "dq", "dk", "dv", "dgates"):
+        assert np.array_equal(getattr(a, name), getattr(b, name)), name
