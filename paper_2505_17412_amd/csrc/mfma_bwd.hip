@@ -703,7 +703,7 @@ __global__ void m_bwd_finish(const int32_t *__restrict__ perm, const int32_t *__
 }
 
 constexpr int DQ_SLC_WAVES = 4;  // wavefronts per workgroup of the selection/window dQ kernel (16 tokens at h_s = 8)
-constexpr int KB_KEYS = 2;    // key blocks of 16 per wavefront in the dK/dV kernels
+constexpr int KB_KEYS_MAX = 2;  // key blocks of 16 per wavefront in the dK/dV kernels (1 at head_dim 128: registers)
 // wavefronts per workgroup there (16*KB_KEYS keys each): blocks and windows hold ~130 tokens, an item's pooled keys
 // thousands, so the compression branch takes wider workgroups (fewer passes over the query rows)
 constexpr int DKV_WAVES = 4, DKV_WAVES_CMP = 8;
@@ -734,6 +734,7 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
     m_bwd_dq<D, CB, 0, NW0><<<dim3(xcd_grid_size((N + tw0 - 1) / tw0, Hkv)), 64 * NW0, dq_lds_bytes<D>(tw0, v.T, v.Ns), s>>>(a);
     m_bwd_dq<D, CB, 1, NW1><<<dim3(xcd_grid_size((N + tw1 - 1) / tw1, Hkv)), 64 * NW1, dq_lds_bytes<D>(tw1, v.T, v.Ns), s>>>(a);
   }
+  constexpr int KB_KEYS = D >= 128 ? 1 : KB_KEYS_MAX;
   constexpr int WG_KEYS = 16 * KB_KEYS * DKV_WAVES, WG_KEYS_CMP = 16 * KB_KEYS * DKV_WAVES_CMP;
   static_assert(WG_KEYS <= SSA_KEY_PAD && WG_KEYS_CMP <= SSA_KEY_PAD, "key tiles may read up to WG_KEYS rows past a block");
   const size_t dkv_lds = (size_t)2 * DkvStage<D>::BYTES;
