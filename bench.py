@@ -122,7 +122,7 @@ def main():
     # dQ kernel (6d), dV, dK on the dK/dV kernels (4d)
     kflops = {
         "cmp_fwd_scores_topk": 4 * d * pairs["cmp"], "slc_fwd": 4 * d * pairs["slc"], "win_fwd": 4 * d * pairs["win"],
-        "bwd_dq": 6 * d * all_pairs, "bwd_dkv_cmp": 4 * d * pairs["cmp"], "bwd_dkv_slc": 4 * d * pairs["slc"],
+        "bwd_dq_cmp": 6 * d * pairs["cmp"], "bwd_dq_slc_win": 6 * d * (pairs["slc"] + pairs["win"]), "bwd_dkv_cmp": 4 * d * pairs["cmp"], "bwd_dkv_slc": 4 * d * pairs["slc"],
         "bwd_dkv_win": 4 * d * pairs["win"], "generic_path": 10 * d * all_pairs,
     }
     dom = max(kern_ms, key=kern_ms.get) if kern_ms else None

@@ -721,7 +721,6 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
     m_bwd_pre<<<N, 256, (size_t)2 * Hq * D * sizeof(bf16_t), s>>>(a);
   }
   {
-    ProfScope ps(PROF_BWD_DQ, s);
     DqArgs a{v, (const bf16_t *)q, (const bf16_t *)dout, idx, w.lse2s, w.deltas, w.gws, (bf16_t *)dq, w.dQp};
     constexpr int CB = 1, NW0 = 4, NW1 = DQ_SLC_WAVES;
     const int tw0 = NW0 * CB * 16 / v.hs, tw1 = NW1 * CB * 16 / v.hs;
@@ -731,8 +730,14 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
       (void)hipFuncSetAttribute((const void *)m_bwd_dq<D, CB, 1, NW1>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
       attr_done = true;
     }
-    m_bwd_dq<D, CB, 0, NW0><<<dim3(xcd_grid_size((N + tw0 - 1) / tw0, Hkv)), 64 * NW0, dq_lds_bytes<D>(tw0, v.T, v.Ns), s>>>(a);
-    m_bwd_dq<D, CB, 1, NW1><<<dim3(xcd_grid_size((N + tw1 - 1) / tw1, Hkv)), 64 * NW1, dq_lds_bytes<D>(tw1, v.T, v.Ns), s>>>(a);
+    {
+      ProfScope ps0(PROF_BWD_DQ_CMP, s);
+      m_bwd_dq<D, CB, 0, NW0><<<dim3(xcd_grid_size((N + tw0 - 1) / tw0, Hkv)), 64 * NW0, dq_lds_bytes<D>(tw0, v.T, v.Ns), s>>>(a);
+    }
+    {
+      ProfScope ps1(PROF_BWD_DQ, s);
+      m_bwd_dq<D, CB, 1, NW1><<<dim3(xcd_grid_size((N + tw1 - 1) / tw1, Hkv)), 64 * NW1, dq_lds_bytes<D>(tw1, v.T, v.Ns), s>>>(a);
+    }
   }
   constexpr int KB_KEYS = D >= 128 ? 1 : KB_KEYS_MAX;
   constexpr int WG_KEYS = 16 * KB_KEYS * DKV_WAVES, WG_KEYS_CMP = 16 * KB_KEYS * DKV_WAVES_CMP;

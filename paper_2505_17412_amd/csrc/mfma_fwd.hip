@@ -442,24 +442,25 @@ __global__ void m_combine(const bf16_t *__restrict__ Ob, const bf16_t *__restric
 }
 
 constexpr int FWD_CB = 1;
+constexpr int CMP_CB = 1;  // the compression kernel shares every key tile between all rows: two column blocks per wave
 constexpr int SLC_WAVES = 4;  // wavefronts per workgroup of the selection kernel  // blocks of 16 query columns per wavefront
 
 template <int D>
 int launch_forward(const FwdArgs &a, const bf16_t *gates, bf16_t *out, hipStream_t s) {
-  const int tw = 4 * FWD_CB * 16 / a.v.hs;
+  const int tw = 4 * FWD_CB * 16 / a.v.hs, tw_cmp = 4 * CMP_CB * 16 / a.v.hs;
   const dim3 grid(xcd_grid_size((a.v.N + tw - 1) / tw, a.v.Hkv));
   const int tw_slc = SLC_WAVES * FWD_CB * 16 / a.v.hs;
-  const size_t lds_cmp = cmp_lds_bytes<D>(tw, a.v.s_max), lds_slc = slc_lds_bytes<D>(tw_slc, a.v.T, a.v.Ns);
+  const size_t lds_cmp = cmp_lds_bytes<D>(tw_cmp, a.v.s_max), lds_slc = slc_lds_bytes<D>(tw_slc, a.v.T, a.v.Ns);
   const size_t lds_win = (size_t)2 * StageLayout<D, 1, 1>::ELEMS * sizeof(bf16_t) + 32;
   static bool attr_done = false;  // raise the dynamic LDS limit once per process for these instantiations
   if (!attr_done) {
-    (void)hipFuncSetAttribute((const void *)m_cmp_fwd<D, FWD_CB>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    (void)hipFuncSetAttribute((const void *)m_cmp_fwd<D, CMP_CB>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     (void)hipFuncSetAttribute((const void *)m_slc_fwd<D, FWD_CB, SLC_WAVES>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     attr_done = true;
   }
   {
     ProfScope ps(PROF_CMP_FWD, s);
-    m_cmp_fwd<D, FWD_CB><<<grid, 256, lds_cmp, s>>>(a);
+    m_cmp_fwd<D, CMP_CB><<<dim3(xcd_grid_size((a.v.N + tw_cmp - 1) / tw_cmp, a.v.Hkv)), 256, lds_cmp, s>>>(a);
   }
   {
     ProfScope ps(PROF_SLC_FWD, s);
@@ -481,7 +482,7 @@ int launch_forward(const FwdArgs &a, const bf16_t *gates, bf16_t *out, hipStream
 
 // Largest dynamic LDS request of the forward kernels for this problem (bytes).
 size_t mfma_fwd_lds_bytes(int D, int hs, int s_max, int T, int Ns) {
-  const int tw = 4 * FWD_CB * 16 / hs, tws = SLC_WAVES * FWD_CB * 16 / hs;
+  const int tw = 4 * CMP_CB * 16 / hs, tws = SLC_WAVES * FWD_CB * 16 / hs;
   size_t a = 0, b = 0;
   switch (D) {
     case 32: a = cmp_lds_bytes<32>(tw, s_max); b = slc_lds_bytes<32>(tws, T, Ns); break;
