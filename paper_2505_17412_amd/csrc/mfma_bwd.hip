@@ -105,6 +105,9 @@ __device__ inline void dq_tile(f32x4 (&acc)[CB][D / 16], const QRows<D, CB> &q, 
                                const int (&hi)[CB], const bool (&act)[CB], float sl2, float scale, const float (&lse2)[CB],
                                const float (&delta)[CB], const float (&gw)[CB]) {
   const int quad = threadIdx.x >> 4 & 3;
+  float gws[CB], dls[CB];  // gate and delta with the softmax scale folded in: dS = P (gate dP - delta) scale
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb) { gws[cb] = gw[cb] * scale; dls[cb] = delta[cb] * scale; }
   f32x4 s0[CB], s1[CB], p0[CB], p1[CB];
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) s0[cb] = s1[cb] = p0[cb] = p1[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -134,7 +137,7 @@ __device__ inline void dq_tile(f32x4 (&acc)[CB][D / 16], const QRows<D, CB> &q, 
         const int key = kb + 8 * quad + j;
         if (key < lo[cb] || key >= hi[cb]) p = 0.f;
       }
-      dsb[cb][j] = (__bf16)(p * __builtin_fmaf(gw[cb], dp, -delta[cb]) * scale);
+      dsb[cb][j] = (__bf16)(p * __builtin_fmaf(gws[cb], dp, -dls[cb]));
     }
   }
 #pragma unroll
@@ -221,8 +224,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
     if (threadIdx.x == 0) { ints[4] = rs; ints[5] = re; }
     __syncthreads();
     TileSrc<2, 1> src = branch == 0
-        ? TileSrc<2, 1>{{a.v.Kc + (size_t)g * D, a.v.Vc + (size_t)g * D}, {a.v.Kct + (size_t)g * D * 8}, kstride}
-        : TileSrc<2, 1>{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, {a.v.Kt + (size_t)g * D * 8}, kstride};
+        ? TileSrc<2, 1>{{a.v.Kc + (size_t)g * D, a.v.Vc + (size_t)g * D}, {a.v.Kct + (size_t)g * D * 8}, (uint32_t)kstride}
+        : TileSrc<2, 1>{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, {a.v.Kt + (size_t)g * D * 8}, (uint32_t)kstride};
     run_pipeline<D, 2, 1, 64 * NW>(
         src, stage0, ints + 4, ints + 5, re > rs ? 1 : 0, [](int) {},
         [&](const bf16_t *stg, int kb, int) {
@@ -249,7 +252,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
       gw[cb] = a.gws[NH + rs_[cb]];
     }
     int rs = 0, re = 0;
-    TileSrc<2, 1> src{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, {a.v.Kt + (size_t)g * D * 8}, kstride};
+    TileSrc<2, 1> src{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, {a.v.Kt + (size_t)g * D * 8}, (uint32_t)kstride};
     run_pipeline<D, 2, 1, 64 * NW>(
         src, stage0, us, ue, nr,
         [&](int r) {
@@ -413,7 +416,7 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
       if (G::ROW_ITEMS % NTHR == 0 || it < G::ROW_ITEMS) {
         const int row = it / (D / 8), seg = it % (D / 8);
         const int pos = max(pick(p, row / hs), 0);
-        const size_t off = ((size_t)pos * Hq + g * hs + row % hs) * D + seg * 8;
+        const uint32_t off = ((uint32_t)pos * Hq + g * hs + row % hs) * D + seg * 8;
         rq[i] = ld8(a.Qs + off);
         rd[i] = ld8(a.dOs + off);
       }
@@ -424,7 +427,7 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
       if (G::T_ITEMS % NTHR == 0 || it < G::T_ITEMS) {
         const int chunk = it / D, dim = it % D;
         const int pos = max(pick(p, chunk * 8 / hs), 0);
-        const size_t off = (((size_t)pos * a.v.Hkv + g) * D + dim) * hs + (chunk * 8) % hs;
+        const uint32_t off = (((uint32_t)pos * a.v.Hkv + g) * D + dim) * hs + (chunk * 8) % hs;
         tq[i] = ld8(a.QT + off);
         td[i] = ld8(a.dOT + off);
       }
@@ -432,7 +435,7 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
     if (threadIdx.x < 96) {
       const int arr = threadIdx.x >> 5, row = threadIdx.x & 31;
       const int pos = pick(p, row / hs);
-      const size_t rsx = (size_t)max(pos, 0) * Hq + g * hs + row % hs;
+      const uint32_t rsx = (uint32_t)max(pos, 0) * Hq + g * hs + row % hs;
       const float *srcp = arr == 0 ? a.lse2s : (arr == 1 ? a.deltas : a.gws);
       sc = srcp[rsx];
       if (arr == 0 && pos < 0) sc = INFINITY;  // a missing row contributes exp2(-inf) = 0
@@ -519,7 +522,7 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
         const float dpv = j < 4 ? dp[kbk][0][j & 3] : dp[kbk][1][j & 3];
         const float p = fast_exp2(__builtin_fmaf(sv, sl2, -lse2[j]));
         pw[j] = (__bf16)(p * gw[j]);
-        ds[j] = (__bf16)(p * __builtin_fmaf(gw[j], dpv, -delta[j]) * scale);
+        ds[j] = (__bf16)(p * __builtin_fmaf(gw[j] * scale, dpv, -delta[j] * scale));
       }
 #pragma unroll
       for (int dt = 0; dt < D / 16; ++dt) {

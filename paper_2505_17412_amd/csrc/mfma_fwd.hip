@@ -194,7 +194,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) { act[cb] = true; on[cb] = q.valid[cb]; }
   const float slack = 8.0f / a.v.sl2;
-  TileSrc<1, 1> src{{a.v.Kc + (size_t)g * D}, {a.v.Vct + (size_t)g * D * 8}, (size_t)a.v.Hkv * D};
+  TileSrc<1, 1> src{{a.v.Kc + (size_t)g * D}, {a.v.Vct + (size_t)g * D * 8}, (uint32_t)(a.v.Hkv * D)};
   FwdState<D, CB> st;
   init_state(st);
   const float sl2 = a.v.sl2;
@@ -211,7 +211,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
 
   // ---- selection scores, eq. (6): second walk over the pooled keys with the normaliser known
   for (int i = threadIdx.x; i < TW * s_max; i += 256) S[i] = 0u;
-  TileSrc<1, 0> ksrc{{a.v.Kc + (size_t)g * D}, {}, (size_t)a.v.Hkv * D};
+  TileSrc<1, 0> ksrc{{a.v.Kc + (size_t)g * D}, {}, (uint32_t)(a.v.Hkv * D)};
   if (hs >= 4) {
     // Scores NOT transposed here (S = Q K^T: query rows x keys), so that a lane holds four heads of ONE token for
     // one key: the sum over the group's heads (eq. (6), inner sum) is three in-lane adds plus at most two lane
@@ -338,7 +338,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
   const float slack = 8.0f / a.v.sl2;
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) { jc[cb] = 0; lo[cb] = hi[cb] = 0; act[cb] = false; on[cb] = false; }
-  TileSrc<1, 1> src{{a.v.Ks + (size_t)g * D}, {a.v.Vt + (size_t)g * D * 8}, (size_t)a.v.Hkv * D};
+  TileSrc<1, 1> src{{a.v.Ks + (size_t)g * D}, {a.v.Vt + (size_t)g * D * 8}, (uint32_t)(a.v.Hkv * D)};
   FwdState<D, CB> st;
   init_state(st);
   const float sl2 = a.v.sl2;
@@ -403,7 +403,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
   wg_range<CB>(ints, lo, hi, q.valid, rs, re, uniform);
   if (threadIdx.x == 0) { ints[4] = rs; ints[5] = re; }
   __syncthreads();
-  TileSrc<1, 1> src{{a.v.Ks + (size_t)g * D}, {a.v.Vt + (size_t)g * D * 8}, (size_t)a.v.Hkv * D};
+  TileSrc<1, 1> src{{a.v.Ks + (size_t)g * D}, {a.v.Vt + (size_t)g * D * 8}, (uint32_t)(a.v.Hkv * D)};
   FwdState<D, CB> st;
   init_state(st);
   const float sl2 = a.v.sl2;

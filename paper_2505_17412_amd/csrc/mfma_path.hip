@@ -146,6 +146,8 @@ bool mfma_supported(const ssa_ctx &c) {
   if (c.dtype != SSA_BF16) return false;
   if (c.d != 32 && c.d != 64 && c.d != 128) return false;
   if (c.hs != 1 && c.hs != 2 && c.hs != 4 && c.hs != 8 && c.hs != 16) return false;
+  // the kernels index their staged arrays with 32-bit element offsets
+  if ((unsigned long long)(c.N + 2 * SSA_KEY_PAD) * c.Hq * c.d >= (1ull << 31)) return false;
   if (mfma_fwd_lds_bytes(c.d, c.hs, c.blk->s_max, c.T, c.blk->Ns) > 150 * 1024) return false;
   return true;
 }

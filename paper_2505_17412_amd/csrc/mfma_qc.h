@@ -49,7 +49,7 @@ template <int NROW, int NT>
 struct TileSrc {
   const bf16_t *row[NROW];
   const bf16_t *tr[NT];
-  size_t kstride;  // elements between consecutive rows of a row-major array (Hkv*D)
+  uint32_t kstride;  // elements between consecutive rows of a row-major array (Hkv*D); whole arrays stay below 2^31 elements
 };
 
 template <int D, int NROW, int NT, int NTHR>
@@ -62,7 +62,7 @@ __device__ inline void tile_load(TileRegs<D, NROW, NT, NTHR> &regs, const TileSr
       const int it = threadIdx.x + NTHR * i;
       if (G::ROW_ITEMS % NTHR == 0 || it < G::ROW_ITEMS) {
         const int row = it / (D / 8), seg = it % (D / 8);
-        regs.r[x][i] = ld8(src.row[x] + (size_t)(kb + row) * src.kstride + seg * 8);
+        regs.r[x][i] = ld8(src.row[x] + ((uint32_t)(kb + row) * (uint32_t)src.kstride + (uint32_t)(seg * 8)));
       }
     }
 #pragma unroll
@@ -72,7 +72,7 @@ __device__ inline void tile_load(TileRegs<D, NROW, NT, NTHR> &regs, const TileSr
       const int it = threadIdx.x + NTHR * i;
       if (G::T_ITEMS % NTHR == 0 || it < G::T_ITEMS) {
         const int chunk = it / D, dim = it % D;
-        regs.t[x][i] = ld8(src.tr[x] + (size_t)((kb >> 3) + chunk) * src.kstride * 8 + (size_t)dim * 8);
+        regs.t[x][i] = ld8(src.tr[x] + ((uint32_t)((kb >> 3) + chunk) * (uint32_t)(src.kstride * 8) + (uint32_t)(dim * 8)));
       }
     }
 }
