@@ -226,7 +226,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
     TileSrc<2, 1> src = branch == 0
         ? TileSrc<2, 1>{{a.v.Kc + (size_t)g * D, a.v.Vc + (size_t)g * D}, {a.v.Kct + (size_t)g * D * 8}, (uint32_t)kstride}
         : TileSrc<2, 1>{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, {a.v.Kt + (size_t)g * D * 8}, (uint32_t)kstride};
-    run_pipeline<D, 2, 1, 64 * NW>(
+    run_pipeline<D, 2, 1, 64 * NW, 1>(
         src, stage0, ints + 4, ints + 5, re > rs ? 1 : 0, [](int) {},
         [&](const bf16_t *stg, int kb, int) {
           bf16_t *st = (bf16_t *)stg;
@@ -253,7 +253,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
     }
     int rs = 0, re = 0;
     TileSrc<2, 1> src{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, {a.v.Kt + (size_t)g * D * 8}, (uint32_t)kstride};
-    run_pipeline<D, 2, 1, 64 * NW>(
+    run_pipeline<D, 2, 1, 64 * NW, 1>(
         src, stage0, us, ue, nr,
         [&](int r) {
           const int b = lds_uniform(&ub[r]);

@@ -193,30 +193,44 @@ __device__ inline void load_rows(const bf16_t *Q, const MfmaView &v, int wg_pos0
   }
 }
 
-// Walk the tiles of the key ranges rng_s/rng_e[0..nr) (LDS, workgroup-uniform): stage tile i+1 while tile i is
-// consumed.  enter(r) runs when the walk reaches range r, tile(stage, kb, r) consumes one staged tile.
-template <int D, int NROW, int NT, int NTHR = 256, class Enter, class Tile>
+// Walk the tiles of the key ranges rng_s/rng_e[0..nr) (LDS, workgroup-uniform).  Global loads run PF tiles (1 or 2)
+// ahead of the tile being consumed, through PF register sets used alternately; LDS holds two stages: the stage
+// written at step i is read at step i and overwritten at step i+2, with one barrier per step in between.
+// enter(r) runs when the walk reaches range r, tile(stage, kb, r) consumes one staged tile.
+template <int D, int NROW, int NT, int NTHR = 256, int PF = 2, class Enter, class Tile>
 __device__ inline void run_pipeline(const TileSrc<NROW, NT> &src, bf16_t *stage0, const int *rng_s, const int *rng_e, int nr,
                                     Enter enter, Tile tile) {
   using L = StageLayout<D, NROW, NT>;
   if (nr > 0) {
-    TileRegs<D, NROW, NT, NTHR> regs;
-    TileIter it = iter_begin(rng_s, nr);
-    tile_load<D, NROW, NT, NTHR>(regs, src, it.kb);
+    TileRegs<D, NROW, NT, NTHR> regs[PF];
+    TileIter cur = iter_begin(rng_s, nr);
+    TileIter ahead = cur;  // the last tile whose loads are in flight
+    tile_load<D, NROW, NT, NTHR>(regs[0], src, cur.kb);
+    if (PF == 2) {
+      ahead = iter_next(cur, rng_s, rng_e, nr);
+      if (ahead.r < nr) tile_load<D, NROW, NT, NTHR>(regs[PF - 1], src, ahead.kb);
+    }
     int buf = 0, cur_r = -1;
-    while (it.r < nr) {
+    auto step = [&](TileRegs<D, NROW, NT, NTHR> &r) {
       bf16_t *st = stage0 + buf * L::ELEMS;
-      tile_store<D, NROW, NT, NTHR>(regs, st);
+      tile_store<D, NROW, NT, NTHR>(r, st);
       __syncthreads();
-      const TileIter nx = iter_next(it, rng_s, rng_e, nr);
-      if (nx.r < nr) tile_load<D, NROW, NT, NTHR>(regs, src, nx.kb);
-      if (it.r != cur_r) {
-        cur_r = it.r;
+      if (ahead.r < nr) ahead = iter_next(ahead, rng_s, rng_e, nr);
+      if (ahead.r < nr) tile_load<D, NROW, NT, NTHR>(r, src, ahead.kb);
+      if (cur.r != cur_r) {
+        cur_r = cur.r;
         enter(cur_r);
       }
-      tile(st, it.kb, cur_r);
-      it = nx;
+      tile(st, cur.kb, cur_r);
+      cur = iter_next(cur, rng_s, rng_e, nr);
       buf ^= 1;
+    };
+    while (cur.r < nr) {
+      step(regs[0]);
+      if (PF == 2) {
+        if (!(cur.r < nr)) break;
+        step(regs[PF - 1]);
+      }
     }
   }
   __syncthreads();
