@@ -33,6 +33,29 @@ def algorithmic_flops(wl, blk_arrays, idx):
     return dict(cmp=pairs_cmp, slc=pairs_slc, win=pairs_win, d=d)
 
 
+# bench.py kernel name -> kernel name prefix in the rocprofv3 summaries
+ROCPROF_NAME = {
+    "cmp_fwd_scores_topk": "m_cmp_fwd<", "slc_fwd": "m_slc_fwd<", "win_fwd": "m_win_fwd<",
+    "bwd_dq_cmp": "m_bwd_dq<{d}, 1, 0,", "bwd_dq_slc_win": "m_bwd_dq<{d}, 1, 1,",
+    "bwd_dkv_win": "m_bwd_dkv<{d}, {kb}, 0,", "bwd_dkv_slc": "m_bwd_dkv<{d}, {kb}, 1,", "bwd_dkv_cmp": "m_bwd_dkv<{d}, {kb}, 2,",
+}
+
+
+def recorded_traffic(kernel, workload, d):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 FETCH_SIZE/WRITE_SIZE summary of this workload
+    (scaled columns, MiB), or None when no summary covers it."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}_fwd_bwd.md")
+    pat = ROCPROF_NAME.get(kernel)
+    if pat is None or not os.path.exists(path):
+        return None
+    pat = pat.format(d=d, kb=1 if d >= 128 else 2)
+    for line in open(path):
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) == 5 and cells[0].startswith(pat):
+            return int((float(cells[3]) + float(cells[4])) * 1024 * 1024)
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -130,7 +153,8 @@ def main():
     if dom is not None and dom in kflops:
         ach = kflops[dom] / (kern_ms[dom] * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": dom, "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
-                    "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                    "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4),
+                    "traffic": recorded_traffic(dom, args.workload, d),
                     "kernel_ms": round(kern_ms[dom], 4)}
     total_flops = 14 * d * all_pairs
 
