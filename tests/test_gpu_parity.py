@@ -170,3 +170,41 @@ def test_forward_backward_are_deterministic():
     b = util.run_gpu(wl, backward=True)
     for name in ("out", "lse", "topk_idx", "dq", "dk", "dv", "dgates"):
         assert np.array_equal(getattr(a, name), getattr(b, name)), name
+
+
+def test_bf16_inference_call_without_optional_outputs():
+    """ssa_forward with lse / topk_idx / out_branch = NULL (inference) writes the same `out` as the training call."""
+    import torch
+    from paper_2505_17412_amd import ssa
+    wl = inputs.random_points_workload(21, 32, (900, 500), 16, 2, 64, (4, 8, 8), 6, "bf16")
+    full = util.run_gpu(wl, backward=False)
+    p, blk = util.build_blocks_gpu(wl)
+    q, k, v, g = (util.to_dev(a, "bf16") for a in (wl.q, wl.k, wl.v, wl.gates))
+    out = torch.zeros_like(q)
+    ssa.ssa_forward(p, blk, q, k, v, g, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(util.to_np(out), full.out)
+
+
+def test_whole_grid_window_is_dense_attention_on_gpu():
+    """A window covering the whole grid makes the window branch plain dense attention (window paragraph): the same
+    kernels then serve as a dense variable-length flash attention, forward and backward."""
+    wl = inputs.random_points_workload(22, 16, (1500, 700), 16, 2, 64, (4, 8, 16), 4, "bf16")
+    orc = oracle_for(wl)
+    assert orc.blocks.n_blocks["win"] == 2  # one window per batch item
+    gates = np.zeros_like(wl.gates)
+    gates[..., 2] = 1.0
+    wl.gates = gates
+    g = util.run_gpu(wl, backward=True)
+    qf, kf, vf = (a.astype(np.float64) for a in (wl.q, wl.k, wl.v))
+    for b in range(2):
+        sl = slice(int(wl.batch_offsets[b]), int(wl.batch_offsets[b + 1]))
+        for h in (0, 9, 15):
+            s = (qf[sl, h] @ kf[sl, h // 8].T) * orc.scale
+            p = np.exp(s - s.max(1, keepdims=True))
+            p /= p.sum(1, keepdims=True)
+            util.assert_close(g.out[sl, h], p @ vf[sl, h // 8], "bf16", f"dense out item {b} head {h}")
+    ref = orc.forward(wl.q, wl.k, wl.v, wl.gates, topk_idx=g.topk_idx)
+    rb = orc.backward(wl.q, wl.k, wl.v, wl.gates, wl.dout, g.topk_idx, out_branch=ref.out_branch)
+    for name, got, want in (("dq", g.dq, rb.dq), ("dk", g.dk, rb.dk), ("dv", g.dv, rb.dv)):
+        util.assert_close(got, want, "bf16", name)
