@@ -300,7 +300,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
     if (pos >= a.v.N) break;
     const int tok = a.v.perm[pos], it = a.v.tok_item[pos];
     const int b0 = a.v.slc_batch[it], nb = a.v.slc_batch[it + 1] - b0;
-    topk_wave_u32(S + (size_t)slot * s_max, nb, a.v.T, b0, a.idx + ((size_t)tok * a.v.Hkv + g) * a.v.T, sel);
+    int32_t *row = a.idx + ((size_t)tok * a.v.Hkv + g) * a.v.T;
+    if (s_max <= 512) topk_wave_bits<8>(S + (size_t)slot * s_max, nb, a.v.T, b0, row);
+    else if (s_max <= 1024) topk_wave_bits<16>(S + (size_t)slot * s_max, nb, a.v.T, b0, row);
+    else topk_wave_u32(S + (size_t)slot * s_max, nb, a.v.T, b0, row, sel);
   }
 }
 

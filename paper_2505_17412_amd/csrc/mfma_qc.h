@@ -236,6 +236,51 @@ __device__ inline void run_pipeline(const TileSrc<NROW, NT> &src, bf16_t *stage0
   __syncthreads();
 }
 
+// Top-k over unsigned fixed-point scores S[0..n) held in LDS by one wavefront, ties to the lowest index, entirely in
+// registers and wave ballots (no lane exchange, no LDS traffic inside the search).  Lane l keeps entries l, l+64, ...
+// (up to R per lane, n <= 64*R).  The T-th largest value is found by building it bit by bit from the top: a
+// candidate threshold is kept when at least T entries reach it (one compare + ballot + population count per
+// register and bit).  Entries above the threshold are selected, entries equal to it in ascending index order until
+// T are reached.  Writes T ids (base + index) in ascending order, padded with -1.
+template <int R>
+__device__ inline void topk_wave_bits(const uint32_t *S, int n, int T, int base, int32_t *out) {
+  const int lane = threadIdx.x & 63;
+  const uint64_t lt = (1ull << lane) - 1ull;
+  uint32_t val[R];  // score + 1 (so that every real entry is >= 1); 0 marks "no entry"
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int j = r * 64 + lane;
+    val[r] = j < n ? S[j] + 1u : 0u;
+  }
+  const int Tn = T < n ? T : n;
+  uint32_t thr = 0u;
+  if (Tn > 0) {
+    for (int b = 31; b >= 0; --b) {
+      const uint32_t cand = thr | (1u << b);
+      int cnt = 0;
+#pragma unroll
+      for (int r = 0; r < R; ++r) cnt += __popcll(__ballot(val[r] >= cand));
+      if (cnt >= Tn) thr = cand;
+    }
+  }
+  int greater = 0;
+#pragma unroll
+  for (int r = 0; r < R; ++r) greater += __popcll(__ballot(val[r] > thr));
+  const int need = Tn - greater;  // entries equal to the threshold still to take, lowest indices first
+  int written = 0, eq_before = 0;
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const bool eq = Tn > 0 && val[r] == thr;
+    const uint64_t em = __ballot(eq);
+    const bool sel = (Tn > 0 && val[r] > thr) || (eq && eq_before + __popcll(em & lt) < need);
+    eq_before += __popcll(em);
+    const uint64_t sm = __ballot(sel);
+    if (sel) out[written + __popcll(sm & lt)] = base + r * 64 + lane;
+    written += __popcll(sm);
+  }
+  for (int w = written + lane; w < T; w += 64) out[w] = -1;
+}
+
 // Workgroup-wide [min lo, max hi) of the per-lane key ranges, and whether every row has exactly that range.
 // scratch: 3 ints of LDS.  Returns through rs, re, uniform (all workgroup-uniform).
 template <int CB>
