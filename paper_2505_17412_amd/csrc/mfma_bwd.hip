@@ -128,15 +128,14 @@ __device__ inline void dq_tile(f32x4 (&acc)[CB][D / 16], const QRows<D, CB> &q, 
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) {
     if (!act[cb]) continue;
+    const int rel = kb + 8 * quad - lo[cb];
+    const unsigned len = (unsigned)(hi[cb] - lo[cb]);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const float sv = j < 4 ? s0[cb][j & 3] : s1[cb][j & 3];
       const float dp = j < 4 ? p0[cb][j & 3] : p1[cb][j & 3];
       float p = fast_exp2(__builtin_fmaf(sv, sl2, -lse2[cb]));
-      if (MASK) {
-        const int key = kb + 8 * quad + j;
-        if (key < lo[cb] || key >= hi[cb]) p = 0.f;
-      }
+      if (MASK && (unsigned)(rel + j) >= len) p = 0.f;  // lo <= key < hi as one unsigned comparison
       dsb[cb][j] = (__bf16)(p * __builtin_fmaf(gws[cb], dp, -dls[cb]));
     }
   }

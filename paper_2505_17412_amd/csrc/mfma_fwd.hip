@@ -26,7 +26,8 @@ struct FwdArgs {
 template <int D, int CB>
 struct FwdState {
   f32x4 o[CB][D / 16];  // o[cb][dt][i]: output dim 16*dt + 4*quad + i of query column n
-  float m[CB], l[CB];   // running max (raw score units) and this lane's share of the running sum
+  f32x4 l[CB];          // l[cb][0]: running sum of column n over all keys seen (the other three elements are unused)
+  float m[CB];          // running max (raw score units)
 };
 
 template <int D, int CB>
@@ -36,7 +37,7 @@ __device__ inline void init_state(FwdState<D, CB> &st) {
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt) st.o[cb][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     st.m[cb] = -INFINITY;
-    st.l[cb] = 0.f;
+    st.l[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 }
 
@@ -79,17 +80,20 @@ __device__ inline void fwd_tile(FwdState<D, CB> &st, const QRows<D, CB> &q, cons
   const int quad = threadIdx.x >> 4 & 3;
   float s[CB][8];
   score_tile<D, CB>(ktile, q, act, s);
-  bf16x8 pb[CB];
+  bf16x8 pb[CB], ones;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) ones[j] = (__bf16)1.0f;
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) {
     if (!act[cb]) continue;
     float(&v)[8] = s[cb];
     if (MASK) {
+      // lo <= key < hi as one unsigned comparison of (key - lo) against the range length
+      const int rel = kb + 8 * quad - lo[cb];
+      const unsigned len = (unsigned)(hi[cb] - lo[cb]);
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int key = kb + 8 * quad + j;
-        if (key < lo[cb] || key >= hi[cb]) v[j] = -INFINITY;
-      }
+      for (int j = 0; j < 8; ++j)
+        if ((unsigned)(rel + j) >= len) v[j] = -INFINITY;
     }
     float pm = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
     if (!on[cb]) pm = -INFINITY;
@@ -98,21 +102,18 @@ __device__ inline void fwd_tile(FwdState<D, CB> &st, const QRows<D, CB> &q, cons
       tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
       const float mn = fmaxf(st.m[cb], tmax);
       const float alpha = mn == -INFINITY ? 1.0f : fast_exp2((st.m[cb] - mn) * sl2);
-      st.l[cb] *= alpha;
+      st.l[cb][0] *= alpha;
       st.m[cb] = mn;
 #pragma unroll
       for (int dt = 0; dt < D / 16; ++dt) st.o[cb][dt] *= alpha;
     }
     // exp2 arguments: finite or -inf; a column that is off (or has seen nothing yet and sees nothing now) gets p = 0
     const float neg = (on[cb] && st.m[cb] != -INFINITY) ? -st.m[cb] * sl2 : -INFINITY;
-    float psum = 0.f;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const float p = fast_exp2(__builtin_fmaf(v[j], sl2, neg));
-      psum += p;
-      pb[cb][j] = (__bf16)p;
-    }
-    st.l[cb] += psum;
+    for (int j = 0; j < 8; ++j) pb[cb][j] = (__bf16)fast_exp2(__builtin_fmaf(v[j], sl2, neg));
+    // the normaliser on the matrix pipe: an all-ones A operand sums the 32 probabilities of every column, in the
+    // same bf16 rounding the numerator uses, and leaves the total in every lane of the column
+    st.l[cb] = mfma16(ones, pb[cb], st.l[cb]);
   }
 #pragma unroll
   for (int dt = 0; dt < D / 16; ++dt) {
@@ -129,9 +130,7 @@ __device__ inline void finish(const FwdArgs &a, FwdState<D, CB> &st, int branch,
   const int quad = threadIdx.x >> 4 & 3;
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) {
-    float l = st.l[cb];
-    l += __shfl_xor(l, 16);
-    l += __shfl_xor(l, 32);
+    const float l = st.l[cb][0];
     const float inv = l > 0.f ? 1.0f / l : 0.f;
     lse2[cb] = l > 0.f ? st.m[cb] * a.v.sl2 + __log2f(l) : -INFINITY;
     if (q.valid[cb]) {
@@ -445,20 +444,21 @@ __global__ void m_combine(const bf16_t *__restrict__ Ob, const bf16_t *__restric
 }
 
 constexpr int FWD_CB = 1;
-constexpr int CMP_CB = 1;  // the compression kernel shares every key tile between all rows: two column blocks per wave
-constexpr int SLC_WAVES = 4;  // wavefronts per workgroup of the selection kernel  // blocks of 16 query columns per wavefront
+constexpr int CMP_CB = 1;     // 16-column blocks per wavefront of the compression kernel
+constexpr int SLC_CB = 1;     // 16-column blocks per wavefront of the selection kernel
+constexpr int SLC_WAVES = 4;  // wavefronts per workgroup of the selection kernel
 
 template <int D>
 int launch_forward(const FwdArgs &a, const bf16_t *gates, bf16_t *out, hipStream_t s) {
   const int tw = 4 * FWD_CB * 16 / a.v.hs, tw_cmp = 4 * CMP_CB * 16 / a.v.hs;
   const dim3 grid(xcd_grid_size((a.v.N + tw - 1) / tw, a.v.Hkv));
-  const int tw_slc = SLC_WAVES * FWD_CB * 16 / a.v.hs;
+  const int tw_slc = SLC_WAVES * SLC_CB * 16 / a.v.hs;
   const size_t lds_cmp = cmp_lds_bytes<D>(tw_cmp, a.v.s_max), lds_slc = slc_lds_bytes<D>(tw_slc, a.v.T, a.v.Ns);
   const size_t lds_win = (size_t)2 * StageLayout<D, 1, 1>::ELEMS * sizeof(bf16_t) + 32;
   static bool attr_done = false;  // raise the dynamic LDS limit once per process for these instantiations
   if (!attr_done) {
     (void)hipFuncSetAttribute((const void *)m_cmp_fwd<D, CMP_CB>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    (void)hipFuncSetAttribute((const void *)m_slc_fwd<D, FWD_CB, SLC_WAVES>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    (void)hipFuncSetAttribute((const void *)m_slc_fwd<D, SLC_CB, SLC_WAVES>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     attr_done = true;
   }
   {
@@ -467,7 +467,7 @@ int launch_forward(const FwdArgs &a, const bf16_t *gates, bf16_t *out, hipStream
   }
   {
     ProfScope ps(PROF_SLC_FWD, s);
-    m_slc_fwd<D, FWD_CB, SLC_WAVES><<<dim3(xcd_grid_size((a.v.N + tw_slc - 1) / tw_slc, a.v.Hkv)), 64 * SLC_WAVES, lds_slc, s>>>(a);
+    m_slc_fwd<D, SLC_CB, SLC_WAVES><<<dim3(xcd_grid_size((a.v.N + tw_slc - 1) / tw_slc, a.v.Hkv)), 64 * SLC_WAVES, lds_slc, s>>>(a);
   }
   {
     ProfScope ps(PROF_WIN_FWD, s);
@@ -485,7 +485,7 @@ int launch_forward(const FwdArgs &a, const bf16_t *gates, bf16_t *out, hipStream
 
 // Largest dynamic LDS request of the forward kernels for this problem (bytes).
 size_t mfma_fwd_lds_bytes(int D, int hs, int s_max, int T, int Ns) {
-  const int tw = 4 * CMP_CB * 16 / hs, tws = SLC_WAVES * FWD_CB * 16 / hs;
+  const int tw = 4 * CMP_CB * 16 / hs, tws = SLC_WAVES * SLC_CB * 16 / hs;
   size_t a = 0, b = 0;
   switch (D) {
     case 32: a = cmp_lds_bytes<32>(tw, s_max); b = slc_lds_bytes<32>(tws, T, Ns); break;
