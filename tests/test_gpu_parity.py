@@ -208,3 +208,39 @@ def test_whole_grid_window_is_dense_attention_on_gpu():
     rb = orc.backward(wl.q, wl.k, wl.v, wl.gates, wl.dout, g.topk_idx, out_branch=ref.out_branch)
     for name, got, want in (("dq", g.dq, rb.dq), ("dk", g.dk, rb.dk), ("dv", g.dv, rb.dv)):
         util.assert_close(got, want, "bf16", name)
+
+
+@pytest.mark.parametrize("seed,n,expect_blocks", [
+    (31, (900,), (513, 1024)),     # selection blocks per item in (512, 1024]
+    (32, (3000,), (1025, 4096)),   # more than 1024 selection blocks per item
+])
+def test_many_selection_blocks(seed, n, expect_blocks):
+    """Sparse random points on a 64^3 grid with 4^3 selection blocks: the top-k search runs over hundreds to
+    thousands of candidate blocks per item (every size class of the search routine is visited)."""
+    wl = inputs.random_points_workload(seed, 64, n, 16, 2, 64, (2, 4, 4), 8, "bf16")
+    ns = oracle_for(wl).blocks.n_blocks["slc"]
+    assert expect_blocks[0] <= ns <= expect_blocks[1], ns
+    full_parity(wl)
+
+
+@pytest.mark.parametrize("hq,hkv,d", [(8, 4, 64), (8, 2, 32), (2, 2, 128)])
+def test_bf16_small_head_groups(hq, hkv, d):
+    """bf16 with h_s = 2, 4 and 1 queries per KV head (8 or more token slots share one 16-column matrix tile)."""
+    wl = inputs.random_points_workload(40 + hq + hkv, 32, (800, 333), hq, hkv, d, (4, 8, 8), 5, "bf16")
+    full_parity(wl)
+
+
+def test_empty_call_and_empty_batch_item():
+    """N = 0 returns success without touching the outputs; a batch whose middle item is empty matches the oracle."""
+    import torch
+    from paper_2505_17412_amd import ssa
+    wl0 = inputs.random_points_workload(1, 8, (0, 0), 4, 2, 16, (2, 4, 4), 2)
+    p, blk = util.build_blocks_gpu(wl0)
+    e = torch.empty((0, 4, 16), dtype=torch.float32, device="cuda")
+    ekv = torch.empty((0, 2, 16), dtype=torch.float32, device="cuda")
+    eg = torch.empty((0, 4, 3), dtype=torch.float32, device="cuda")
+    ssa.ssa_forward(p, blk, e, ekv, ekv, eg, e)
+    torch.cuda.synchronize()
+    blk.destroy()
+    wl = inputs.random_points_workload(33, 16, (300, 0, 211), 4, 2, 32, (2, 4, 4), 3, "f32")
+    full_parity(wl)
