@@ -157,6 +157,11 @@ def main():
                     "traffic": recorded_traffic(dom, args.workload, d),
                     "kernel_ms": round(kern_ms[dom], 4)}
     total_flops = 14 * d * all_pairs
+    # HBM-bound helper: gather + mean pool of K and V, priced at its algorithmic bytes (K, V read once, pooled rows
+    # written once); the sorted and transposed copies the kernel also writes are this design's own extra traffic
+    n_cmp = blk.counts()[0]
+    prep_bytes = 2 * (n + n_cmp) * hkv * d * 2
+    prep_gbps = round(prep_bytes / (kern_ms["prep_sort_pool"] * 1e-3) / 1e9, 1) if kern_ms.get("prep_sort_pool") else None
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -191,6 +196,8 @@ def main():
                                f"Hkv={hkv}, d={d}, m_cmp/m_slc/m_win={wl.m_cmp}/{wl.m_slc}/{wl.m_win}, top-k={T}, fwd+bwd",
                    "n_tokens": n, "blocks_cmp_slc_win": list(blk.counts())},
         "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4), "build_blocks_ms": round(build_ms, 3),
+        "tokens_per_s_incl_build_blocks": round(n / ((ms + build_ms) * 1e-3), 1),
+        "prep_sort_pool_algorithmic_gbps": prep_gbps,
         "algorithmic_tflop_per_step": round(total_flops / 1e12, 4),
         "mfma_frac_whole_step": round(total_flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
         "kernel_ms": {k_: round(v_, 4) for k_, v_ in kern_ms.items()},
