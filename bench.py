@@ -56,6 +56,69 @@ def recorded_traffic(kernel, workload, d):
     return None
 
 
+# Token sweep of the sparse path against dense attention computed by the same library (the window branch with one
+# window over the whole grid is plain dense variable-length attention).  Shells of the bench workload's recipe at
+# three grid sizes: (grid, size factor f, half-width w).
+SWEEP_POINTS = [(32, 0.55, 1.0), (64, 0.45, 1.0), (64, 0.55, 1.5), (128, 0.55, 0.75), (128, 0.55, 1.5), (128, 0.55, 3.0)]
+
+
+def dense_sweep(args):
+    """One JSON line per sweep point: per-kernel HIP-event times of the sparse configuration (m = 4/8/8, top-k 16)
+    and of the dense stand-in (m_win = grid, top-k 1: the window kernels then visit every (query, key) pair)."""
+    import torch
+    from paper_2505_17412_amd import inputs, ssa
+    from tests import util
+
+    torch.cuda.set_device(0)
+
+    def kernel_times(wl, steps):
+        n, hq, hkv, T = wl.n_tokens, wl.n_heads_q, wl.n_heads_kv, wl.topk
+        p, blk = util.build_blocks_gpu(wl)
+        q, k, v, g, do = (util.to_dev(a, wl.dtype) for a in (wl.q, wl.k, wl.v, wl.gates, wl.dout))
+        out = torch.empty_like(q)
+        ob = torch.empty((3,) + tuple(q.shape), dtype=q.dtype, device="cuda")
+        lse = torch.empty((3, n, hq), dtype=torch.float32, device="cuda")
+        idx = torch.empty((n, hkv, T), dtype=torch.int32, device="cuda")
+        dq, dk, dv, dg = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v), torch.empty_like(g)
+        wsf = torch.empty(ssa.ssa_workspace_bytes(p, blk, False), dtype=torch.uint8, device="cuda")
+        wsb = torch.empty(ssa.ssa_workspace_bytes(p, blk, True), dtype=torch.uint8, device="cuda")
+
+        def step():
+            ssa.ssa_forward(p, blk, q, k, v, g, out, lse, idx, ob, wsf)
+            ssa.ssa_backward(p, blk, q, k, v, g, ob, lse, idx, do, dq, dk, dv, dg, wsb)
+
+        step()
+        torch.cuda.synchronize()
+        ssa.ssa_profile_enable(True)
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        prof = ssa.ssa_profile_get()
+        ssa.ssa_profile_enable(False)
+        blk.destroy()
+        return {nm: tot / cnt for nm, (tot, cnt) in prof.items()}
+
+    fwd_names = ("prep_sort_pool", "cmp_fwd_scores_topk", "slc_fwd", "win_fwd", "combine")
+    for grid, f, w in SWEEP_POINTS:
+        sparse = inputs.make_workload("g128", grid=grid, f=f, w=w)
+        dense = inputs.make_workload("g128", grid=grid, f=f, w=w, m=(4, 8, grid), topk=1)
+        n = sparse.n_tokens
+        ks = kernel_times(sparse, 3)
+        kd = kernel_times(dense, 2 if n > 50000 else 3)
+        # prep_sort_pool runs once in forward and once in backward; its average is booked on both sides
+        s_fwd = sum(ks[nm] for nm in fwd_names)
+        s_bwd = sum(v_ for nm, v_ in ks.items() if nm not in fwd_names) + ks["prep_sort_pool"]
+        d_fwd = kd["win_fwd"]
+        d_bwd = kd["bwd_dq_slc_win"] + kd["bwd_dkv_win"] + kd["bwd_pre_delta"]
+        line = {"sweep": "ssa_vs_dense", "grid": grid, "n_tokens": n, "heads": [sparse.n_heads_q, sparse.n_heads_kv],
+                "head_dim": sparse.head_dim, "ssa_fwd_ms": round(s_fwd, 3), "ssa_bwd_ms": round(s_bwd, 3),
+                "dense_fwd_ms": round(d_fwd, 3), "dense_bwd_ms": round(d_bwd, 3),
+                "speedup_fwd": round(d_fwd / s_fwd, 2), "speedup_bwd": round(d_bwd / s_bwd, 2),
+                "speedup_fwd_bwd": round((d_fwd + d_bwd) / (s_fwd + s_bwd), 2),
+                "dense_fwd_tflops": round(4 * sparse.head_dim * n * n * sparse.n_heads_q / (d_fwd * 1e-3) / 1e12, 1)}
+        print(json.dumps(line), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -66,10 +129,15 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, to scale rocprofv3 byte counters)")
+    ap.add_argument("--dense-sweep", action="store_true",
+                    help="instead of the benchmark line: sparse path against dense attention over 2.6k-124k tokens")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding or collectives); use --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.dense_sweep:
+        dense_sweep(args)
+        return
 
     import numpy as np
     import torch
