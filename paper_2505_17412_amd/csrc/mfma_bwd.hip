@@ -348,8 +348,11 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
     qbeg = kbeg; qend = kend;
     Kr = a.v.Ks; Vr = a.v.Vs;
   } else if (MODE == DKV_SLC) {
-    // blockIdx.x is a work chunk; find its (g, block) by bisection over the chunk prefix sums
-    const int nkeys = a.v.Hkv * a.v.Ns, w = blockIdx.x;
+    // 1-D launch: the key tiles of one work chunk get workgroup ids 8 apart, i.e. they run on the same XCD close in
+    // time, so the chunk's query rows are fetched into that L2 once.  Find the chunk's (g, block) by bisection over
+    // the chunk prefix sums.
+    const int per8 = 8 * a.tiles_per_block;
+    const int nkeys = a.v.Hkv * a.v.Ns, w = (int)(blockIdx.x / per8) * 8 + (int)(blockIdx.x % 8);
     if (w >= a.chunk_start[nkeys]) return;
     int lo = 0, hi = nkeys;  // chunk_start[lo] <= w < chunk_start[hi]
     while (hi - lo > 1) {
@@ -357,7 +360,7 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
       if (a.chunk_start[mid] <= w) lo = mid; else hi = mid;
     }
     const int key = lo, chunk = w - a.chunk_start[key];
-    g = key / a.v.Ns; blk = key % a.v.Ns; tile = blockIdx.y;
+    g = key / a.v.Ns; blk = key % a.v.Ns; tile = (int)(blockIdx.x % per8) / 8;
     kbeg = a.v.slc_start[blk]; kend = a.v.slc_start[blk + 1];
     qbeg = a.sel_start[key] + chunk * a.chunk_len;
     qend = min(a.sel_start[key + 1], qbeg + a.chunk_len);
@@ -778,7 +781,7 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
     a.lse2s = w.lse2s + NH; a.deltas = w.deltas + NH; a.gws = w.gws + NH;
     a.dK = w.pK; a.dV = w.pV;
     a.tiles_per_block = (blk->slc_tok_max + WG_KEYS - 1) / WG_KEYS;
-    m_bwd_dkv<D, KB_KEYS, DKV_SLC, DKV_WAVES><<<dim3(w.max_chunks, a.tiles_per_block), 64 * DKV_WAVES, dkv_lds, s>>>(a);
+    m_bwd_dkv<D, KB_KEYS, DKV_SLC, DKV_WAVES><<<dim3((w.max_chunks + 7) / 8 * 8 * a.tiles_per_block), 64 * DKV_WAVES, dkv_lds, s>>>(a);
     const size_t items = (size_t)N * Hkv * (D / 4);
     m_slc_reduce<<<(unsigned)((items + 255) / 256), 256, 0, s>>>(blk->tok_slc, v.slc_start, w.chunk_start, w.part_row_start, N,
                                                                  Hkv, v.Ns, D, w.pK, w.pV, w.dKs, w.dVs);
