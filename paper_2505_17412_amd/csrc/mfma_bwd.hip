@@ -97,11 +97,12 @@ struct DqArgs {
   float *dQp;  // [N(pos)][Hq][D] fp32: compression-branch part of dQ, handed from the first dQ kernel to the second
 };
 
-// One staged 32-key tile: transposed scores (K rows) and dP (V rows), then dQ^T += K^T dS^T (transposed K tile).
+// One staged 32-key tile: transposed scores (K rows) and dP (V rows), then dQ^T += K^T dS^T (the K rows again, read
+// through the transposing LDS load).
 // lse2 is +inf for a column whose token did not select the current block, which makes its P exactly zero.
 template <int D, int CB, bool MASK>
 __device__ inline void dq_tile(f32x4 (&acc)[CB][D / 16], const QRows<D, CB> &q, const bf16x8 (&dop)[CB][D / 32],
-                               const bf16_t *ktile, const bf16_t *vtile, const bf16_t *kttile, int kb, const int (&lo)[CB],
+                               const bf16_t *ktile, const bf16_t *vtile, int kb, const int (&lo)[CB],
                                const int (&hi)[CB], const bool (&act)[CB], float sl2, float scale, const float (&lse2)[CB],
                                const float (&delta)[CB], const float (&gw)[CB]) {
   const int quad = threadIdx.x >> 4 & 3;
@@ -141,18 +142,18 @@ __device__ inline void dq_tile(f32x4 (&acc)[CB][D / 16], const QRows<D, CB> &q, 
   }
 #pragma unroll
   for (int dt = 0; dt < D / 16; ++dt) {
-    const bf16x8 kt = lds_t_operand<D>(kttile, dt);
+    const bf16x8 kt = lds_tr_operand<D>(ktile, dt);
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
       if (act[cb]) acc[cb][dt] = mfma16(kt, dsb[cb], acc[cb][dt]);
   }
 }
 
-// LDS plan of the dQ kernel (bytes): two stages (K rows, V rows, K transposed) | 8 ints | selection lists as in the
+// LDS plan of the dQ kernel (bytes): two stages (K rows, V rows) | 8 ints | selection lists as in the
 // forward selection kernel.
 template <int D>
 __host__ __device__ inline size_t dq_lds_bytes(int tw, int T, int Ns) {
-  return (size_t)2 * StageLayout<D, 2, 1>::ELEMS * sizeof(bf16_t) + 32 + ((size_t)tw * T * 4 + (size_t)(Ns + 31) / 32 + 4) * 4;
+  return (size_t)2 * StageLayout<D, 2, 0>::ELEMS * sizeof(bf16_t) + 32 + ((size_t)tw * T * 4 + (size_t)(Ns + 31) / 32 + 4) * 4;
 }
 
 // PART 0: compression branch only (its pooled keys stay L2 resident when nothing else streams through), result
@@ -160,7 +161,7 @@ __host__ __device__ inline size_t dq_lds_bytes(int tw, int T, int Ns) {
 template <int D, int CB, int PART, int NW>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4 : 2))) void m_bwd_dq(DqArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
-  using L = StageLayout<D, 2, 1>;
+  using L = StageLayout<D, 2, 0>;
   bf16_t *stage0 = (bf16_t *)smem;
   int *ints = (int *)(stage0 + 2 * L::ELEMS);
   const int quad = threadIdx.x >> 4 & 3;
@@ -222,18 +223,18 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
     wg_range<CB>(ints, lo, hi, q.valid, rs, re, uniform);
     if (threadIdx.x == 0) { ints[4] = rs; ints[5] = re; }
     __syncthreads();
-    TileSrc<2, 1> src = branch == 0
-        ? TileSrc<2, 1>{{a.v.Kc + (size_t)g * D, a.v.Vc + (size_t)g * D}, {a.v.Kct + (size_t)g * D * 8}, (uint32_t)kstride}
-        : TileSrc<2, 1>{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, {a.v.Kt + (size_t)g * D * 8}, (uint32_t)kstride};
-    run_pipeline<D, 2, 1, 64 * NW, 1>(
+    TileSrc<2, 0> src = branch == 0
+        ? TileSrc<2, 0>{{a.v.Kc + (size_t)g * D, a.v.Vc + (size_t)g * D}, {}, (uint32_t)kstride}
+        : TileSrc<2, 0>{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, {}, (uint32_t)kstride};
+    run_pipeline<D, 2, 0, 64 * NW, 1>(
         src, stage0, ints + 4, ints + 5, re > rs ? 1 : 0, [](int) {},
         [&](const bf16_t *stg, int kb, int) {
           bf16_t *st = (bf16_t *)stg;
           if (uniform && kb >= rs && kb + 32 <= re)
-            dq_tile<D, CB, false>(acc, q, dop, L::row_tile(st, 0), L::row_tile(st, 1), L::t_tile(st, 0), kb, lo, hi, act, sl2,
+            dq_tile<D, CB, false>(acc, q, dop, L::row_tile(st, 0), L::row_tile(st, 1), kb, lo, hi, act, sl2,
                                   scale, lse2, delta, gw);
           else
-            dq_tile<D, CB, true>(acc, q, dop, L::row_tile(st, 0), L::row_tile(st, 1), L::t_tile(st, 0), kb, lo, hi, act, sl2,
+            dq_tile<D, CB, true>(acc, q, dop, L::row_tile(st, 0), L::row_tile(st, 1), kb, lo, hi, act, sl2,
                                  scale, lse2, delta, gw);
         });
   }
@@ -251,8 +252,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
       gw[cb] = a.gws[NH + rs_[cb]];
     }
     int rs = 0, re = 0;
-    TileSrc<2, 1> src{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, {a.v.Kt + (size_t)g * D * 8}, (uint32_t)kstride};
-    run_pipeline<D, 2, 1, 64 * NW, 1>(
+    TileSrc<2, 0> src{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, {}, (uint32_t)kstride};
+    run_pipeline<D, 2, 0, 64 * NW, 1>(
         src, stage0, us, ue, nr,
         [&](int r) {
           const int b = lds_uniform(&ub[r]);
@@ -276,10 +277,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
           if (!any) return;
           bf16_t *st = (bf16_t *)stg;
           if (kb >= rs && kb + 32 <= re)
-            dq_tile<D, CB, false>(acc, q, dop, L::row_tile(st, 0), L::row_tile(st, 1), L::t_tile(st, 0), kb, lo, hi, act, sl2,
+            dq_tile<D, CB, false>(acc, q, dop, L::row_tile(st, 0), L::row_tile(st, 1), kb, lo, hi, act, sl2,
                                   scale, lse2, delta, gw);
           else
-            dq_tile<D, CB, true>(acc, q, dop, L::row_tile(st, 0), L::row_tile(st, 1), L::t_tile(st, 0), kb, lo, hi, act, sl2,
+            dq_tile<D, CB, true>(acc, q, dop, L::row_tile(st, 0), L::row_tile(st, 1), kb, lo, hi, act, sl2,
                                  scale, lse2, delta, gw);
         });
   }
@@ -320,12 +321,12 @@ struct DkvArgs {
   int q_splits;                         // compression branch: query range split into this many parts
 };
 
-// LDS stage of the dK/dV kernels: 32 query rows as row-major tiles of Q and dO, the same rows as transposed tiles
-// (dims x rows) of Q and dO, and the rows' scalars (lse in log2 units, delta, gate).
+// LDS stage of the dK/dV kernels: 32 query rows as row-major tiles of Q and dO (read both as they are and through
+// the transposing LDS load), and the rows' scalars (lse in log2 units, delta, gate).
 template <int D>
 struct DkvStage {
   using G = TileGeom<D>;
-  static constexpr int ELEMS = 2 * G::ROW_ELEMS + 2 * G::T_ELEMS;
+  static constexpr int ELEMS = 2 * G::ROW_ELEMS;
   static constexpr int BYTES = ELEMS * 2 + 3 * 32 * 4;
 };
 
@@ -408,7 +409,7 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
       p[sidx] = (sidx < slots && sl < qend) ? (MODE == DKV_SLC ? a.sel_list[sl] : sl) : -1;
     }
   };
-  bf16x8 rq[G::row_per_thread(NTHR)], rd[G::row_per_thread(NTHR)], tq[G::t_per_thread(NTHR)], td[G::t_per_thread(NTHR)];
+  bf16x8 rq[G::row_per_thread(NTHR)], rd[G::row_per_thread(NTHR)];
   float sc = 0.f;
   auto pick = [](const int (&p)[4], int i) { return i == 0 ? p[0] : (i == 1 ? p[1] : (i == 2 ? p[2] : p[3])); };
   auto load_tile = [&](const int (&p)[4]) {
@@ -421,17 +422,6 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
         const uint32_t off = ((uint32_t)pos * Hq + g * hs + row % hs) * D + seg * 8;
         rq[i] = ld8(a.Qs + off);
         rd[i] = ld8(a.dOs + off);
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < G::t_per_thread(NTHR); ++i) {
-      const int it = threadIdx.x + NTHR * i;
-      if (G::T_ITEMS % NTHR == 0 || it < G::T_ITEMS) {
-        const int chunk = it / D, dim = it % D;
-        const int pos = max(pick(p, chunk * 8 / hs), 0);
-        const uint32_t off = (((uint32_t)pos * a.v.Hkv + g) * D + dim) * hs + (chunk * 8) % hs;
-        tq[i] = ld8(a.QT + off);
-        td[i] = ld8(a.dOT + off);
       }
     }
     if (threadIdx.x < 96) {
@@ -454,15 +444,6 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
         *reinterpret_cast<bf16x8 *>(e + G::ROW_ELEMS + off) = rd[i];
       }
     }
-#pragma unroll
-    for (int i = 0; i < G::t_per_thread(NTHR); ++i) {
-      const int it = threadIdx.x + NTHR * i;
-      if (G::T_ITEMS % NTHR == 0 || it < G::T_ITEMS) {
-        const int off = 2 * G::ROW_ELEMS + G::t_off(it % D, it / D);
-        *reinterpret_cast<bf16x8 *>(e + off) = tq[i];
-        *reinterpret_cast<bf16x8 *>(e + G::T_ELEMS + off) = td[i];
-      }
-    }
     if (threadIdx.x < 96) ((float *)(stage + SG::ELEMS * 2))[threadIdx.x] = sc;
   };
 
@@ -481,7 +462,7 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
     }
     buf ^= 1;
     if (!wave_on) continue;
-    const bf16_t *Qr = (const bf16_t *)stage, *Dr = Qr + G::ROW_ELEMS, *Qt = Qr + 2 * G::ROW_ELEMS, *Dt = Qt + G::T_ELEMS;
+    const bf16_t *Qr = (const bf16_t *)stage, *Dr = Qr + G::ROW_ELEMS;
     const float *scal = (const float *)(stage + SG::ELEMS * 2);
     f32x4 s[KB][2], dp[KB][2];
 #pragma unroll
@@ -512,8 +493,8 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
     bf16x8 qt[D / 16], dot[D / 16];
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt) {
-      qt[dt] = lds_t_operand<D>(Qt, dt);
-      dot[dt] = lds_t_operand<D>(Dt, dt);
+      qt[dt] = lds_tr_operand<D>(Qr, dt);
+      dot[dt] = lds_tr_operand<D>(Dr, dt);
     }
 #pragma unroll
     for (int kbk = 0; kbk < KB; ++kbk) {

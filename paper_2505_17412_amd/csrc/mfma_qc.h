@@ -126,6 +126,27 @@ __device__ inline bf16x8 lds_t_operand(const bf16_t *tile, int dt) {
   return *reinterpret_cast<const bf16x8 *>(tile + TileGeom<D>::t_off(16 * dt + n, quad));
 }
 
+// The same A operand as lds_t_operand (row = dim 16*dt + n, contraction rows 8*quad .. +7 of the tile), but taken from
+// a ROW-major LDS tile with the transposing LDS read of gfx950 (ds_read_b64_tr_b16): inside a 16-lane group lane p
+// hands in the address of 4 consecutive elements and lane i receives element (i & 3) of lanes (i >> 2), 4 + (i >> 2),
+// 8 + (i >> 2), 12 + (i >> 2).  With lane p pointing at row 8*quad + (p >> 2), dims 16*dt + 4*(p & 3) .. +3, lane i
+// ends up with dim 16*dt + i of rows 8*quad .. +3; a second read covers rows +4 .. +7.  No transposed copy of the
+// tile is needed, in LDS or in memory.
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+template <int D>
+__device__ inline bf16x8 lds_tr_operand(const bf16_t *tile, int dt) {
+  const int p = threadIdx.x & 15, quad = threadIdx.x >> 4 & 3;
+  const int d0 = 16 * dt + 4 * (p & 3), seg = d0 >> 3, within = d0 & 7;
+  const int row = 8 * quad + (p >> 2);
+  const bf16_t *a0 = tile + TileGeom<D>::row_off(row, seg) + within;
+  const bf16_t *a1 = tile + TileGeom<D>::row_off(row + 4, seg) + within;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)a0);
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)a1);
+  typedef __attribute__((ext_vector_type(8))) short s16x8;
+  const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, both);
+}
+
 // Cursor over the tiles of a list of key ranges held in LDS (rng_s/rng_e), uniform across the workgroup.
 struct TileIter {
   int r, kb;
