@@ -24,7 +24,7 @@ __device__ inline float wave_sum_f(float v) {
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// Pre-pass: dgates, per-row scalars in sorted order, per-token transposed copies of Q and dO.
+// Pre-pass: dgates, per-row scalars in sorted order, sorted copies of Q and dO.
 // One workgroup per sorted token position.
 // ---------------------------------------------------------------------------------------------------------
 struct PreArgs {
@@ -34,31 +34,22 @@ struct PreArgs {
   int N, Hq, Hkv, hs, D;
   bf16_t *dgates;               // [N,Hq,3] caller order
   float *lse2s, *deltas, *gws;  // [3][N(pos)][Hq]
-  bf16_t *QT, *dOT;             // [N(pos)][Hkv][D][hs]
   bf16_t *Qs, *dOs;             // [N(pos)][Hq][D] sorted row-major copies
 };
 
 __global__ __launch_bounds__(256) void m_bwd_pre(PreArgs a) {
-  extern __shared__ bf16_t tile[];  // [2][Hq*D]
+  extern __shared__ bf16_t tile[];  // [Hq*D]: the token's dO rows
   const int pos = blockIdx.x, tok = a.perm[pos];
   const int HD = a.Hq * a.D;
   const size_t base = (size_t)tok * HD;
-  bf16_t *tq = tile, *td = tile + HD;
+  bf16_t *td = tile;
   for (int e = threadIdx.x * 8; e < HD; e += blockDim.x * 8) {
     const bf16x8 xq = ld8(a.Q + base + e), xd = ld8(a.dO + base + e);
-    *reinterpret_cast<bf16x8 *>(tq + e) = xq;
     *reinterpret_cast<bf16x8 *>(td + e) = xd;
     *reinterpret_cast<bf16x8 *>(a.Qs + (size_t)pos * HD + e) = xq;
     *reinterpret_cast<bf16x8 *>(a.dOs + (size_t)pos * HD + e) = xd;
   }
   __syncthreads();
-  // transposed copies: out[(g*D + dim)*hs + hl] = in[(g*hs + hl)*D + dim]
-  for (int o = threadIdx.x; o < HD; o += blockDim.x) {
-    const int hl = o % a.hs, gd = o / a.hs, dim = gd % a.D, g = gd / a.D;
-    const int e = (g * a.hs + hl) * a.D + dim;
-    a.QT[(size_t)pos * HD + o] = tq[e];
-    a.dOT[(size_t)pos * HD + o] = td[e];
-  }
   // dgates and the row scalars: one wavefront per head, lanes over the head dimension
   const int wid = threadIdx.x >> 6, lane = threadIdx.x & 63;
   for (int h = wid; h < a.Hq; h += 4) {
@@ -310,7 +301,7 @@ enum { DKV_WIN = 0, DKV_SLC = 1, DKV_CMP = 2 };
 
 struct DkvArgs {
   MfmaView v;
-  const bf16_t *Qs, *dOs, *QT, *dOT;  // sorted copies: [N(pos)][Hq][D] and [N(pos)][Hkv][D][hs]
+  const bf16_t *Qs, *dOs;             // sorted copies: [N(pos)][Hq][D]
   const float *lse2s, *deltas, *gws;  // already offset to the branch: [N(pos)][Hq]
   const int32_t *sel_start, *sel_list;  // selection branch: query positions per (g, block)
   float *dK, *dV;                       // [rows][Hkv][D] fp32 (rows: sorted tokens, or compression blocks)
@@ -703,8 +694,8 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
   {
     ProfScope ps(PROF_BWD_PRE, s);
     PreArgs a{(const bf16_t *)q, (const bf16_t *)dout, (const bf16_t *)out_branch, (const bf16_t *)gates, lse, v.perm,
-              N, Hq, Hkv, v.hs, D, (bf16_t *)dgates, w.lse2s, w.deltas, w.gws, w.QT, w.dOT, w.Qs, w.dOs};
-    m_bwd_pre<<<N, 256, (size_t)2 * Hq * D * sizeof(bf16_t), s>>>(a);
+              N, Hq, Hkv, v.hs, D, (bf16_t *)dgates, w.lse2s, w.deltas, w.gws, w.Qs, w.dOs};
+    m_bwd_pre<<<N, 256, (size_t)Hq * D * sizeof(bf16_t), s>>>(a);
   }
   {
     DqArgs a{v, (const bf16_t *)q, (const bf16_t *)dout, idx, w.lse2s, w.deltas, w.gws, (bf16_t *)dq, w.dQp};
@@ -736,7 +727,7 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
     (void)hipFuncSetAttribute((const void *)m_bwd_dkv<D, KB_KEYS, DKV_CMP, DKV_WAVES_CMP>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     dkv_attr = true;
   }
-  DkvArgs base{v, w.Qs, w.dOs, w.QT, w.dOT, nullptr, nullptr, nullptr, w.sel_start, w.sel_list,
+  DkvArgs base{v, w.Qs, w.dOs, nullptr, nullptr, nullptr, w.sel_start, w.sel_list,
                w.dKs, w.dVs, w.chunk_start, w.part_row_start, w.chunk_len, 1, 1};
   {
     ProfScope ps(PROF_BWD_DKV_WIN, s);

@@ -72,6 +72,6 @@ struct MfmaView {
       *cmp_batch, *slc_batch, *item_start;
   int N, Nc, Ns, Hq, Hkv, hs, T, s_max;
   float scale, sl2;  // softmax scale, scale * log2(e)
-  // sorted copies (bf16): row-major [rows][Hkv][D] and chunk-transposed [rows/8][Hkv][D][8]
-  const bf16_t *Ks, *Vs, *Kt, *Vt, *Kc, *Vc, *Kct, *Vct;
+  // sorted copies (bf16), row-major [rows][Hkv][D]: token K, V and pooled K, V
+  const bf16_t *Ks, *Vs, *Kc, *Vc;
 };

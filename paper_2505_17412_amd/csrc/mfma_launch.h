@@ -9,7 +9,6 @@ int mfma_forward_kernels(const MfmaView &v, int D, const void *q, const void *ga
 // Device buffers of the backward pass (carved from the caller's workspace).
 struct BwdBuffers {
   float *lse2s, *deltas, *gws;  // [3][N(pos)][Hq]: lse*log2(e), gate*<dO,O_b>, gate
-  bf16_t *QT, *dOT;             // [N(pos)][Hkv][D][hs]: per-token transposed Q and dO
   bf16_t *Qs, *dOs;             // [N(pos)][Hq][D]: Q and dO in sorted token order
   float *dKs, *dVs;             // [N(pos)][Hkv][D] token-level gradients in sorted order
   float *dQp;                   // [N(pos)][Hq][D] compression-branch part of dQ (fp32)

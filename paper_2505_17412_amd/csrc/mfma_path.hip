@@ -6,7 +6,7 @@
 namespace {
 
 struct Tail { bf16_t *p; size_t begin, end; };  // element range to clear
-struct Tails { Tail t[8]; };
+struct Tails { Tail t[4]; };
 
 __global__ void m_zero_tails(Tails ts) {
   const Tail t = ts.t[blockIdx.y];
@@ -15,11 +15,10 @@ __global__ void m_zero_tails(Tails ts) {
     t.p[i] = 0;
 }
 
-struct PrepOut { bf16_t *Ks, *Vs, *Kt, *Vt, *Kc, *Vc, *Kct, *Vct; };
+struct PrepOut { bf16_t *Ks, *Vs, *Kc, *Vc; };
 
-// One workgroup per compression block: gathers its tokens' K,V rows into sorted order (row-major copy and the
-// 8-token chunk-transposed copy) and writes the block mean (eq. (5), mean pool over the active tokens).
-// Any output pointer may be NULL.
+// One workgroup per compression block: gathers its tokens' K,V rows into sorted order and writes the block mean
+// (eq. (5), mean pool over the active tokens).
 __global__ void m_prep(const bf16_t *__restrict__ K, const bf16_t *__restrict__ V, const int32_t *__restrict__ perm,
                        const int32_t *__restrict__ cmp_start, int Hkv, int D, PrepOut o) {
   const int c = blockIdx.x, row = Hkv * D;
@@ -31,34 +30,28 @@ __global__ void m_prep(const bf16_t *__restrict__ K, const bf16_t *__restrict__ 
     for (int pos = b; pos < e; ++pos) {
       const size_t src = (size_t)perm[pos] * row + f;
       const bf16_t kk = K[src], vv = V[src];
-      const size_t tr = (((size_t)(pos >> 3) * Hkv + g) * D + dim) * 8 + (pos & 7);
-      if (o.Ks) o.Ks[(size_t)pos * row + f] = kk;
-      if (o.Vs) o.Vs[(size_t)pos * row + f] = vv;
-      if (o.Kt) o.Kt[tr] = kk;
-      if (o.Vt) o.Vt[tr] = vv;
+      o.Ks[(size_t)pos * row + f] = kk;
+      o.Vs[(size_t)pos * row + f] = vv;
       sk += bf16_to_f32(kk);
       sv += bf16_to_f32(vv);
     }
     const bf16_t kc = f32_to_bf16(sk * inv), vc = f32_to_bf16(sv * inv);
-    const size_t tr = (((size_t)(c >> 3) * Hkv + g) * D + dim) * 8 + (c & 7);
-    if (o.Kc) o.Kc[(size_t)c * row + f] = kc;
-    if (o.Vc) o.Vc[(size_t)c * row + f] = vc;
-    if (o.Kct) o.Kct[tr] = kc;
-    if (o.Vct) o.Vct[tr] = vc;
+    o.Kc[(size_t)c * row + f] = kc;
+    o.Vc[(size_t)c * row + f] = vc;
   }
 }
 
 size_t padded_rows(int n) { return align_up((size_t)n, 8) + SSA_KEY_PAD; }
 
-struct FwdPlan { size_t ks, vt, kc, vct, ob, lse, idx, total; };
+struct FwdPlan { size_t ks, vs, kc, vc, ob, lse, idx, total; };
 
 FwdPlan fwd_plan(const ssa_ctx &c) {
   FwdPlan p{};
   const size_t row = (size_t)c.Hkv * c.d * 2;
   size_t off = 0;
   auto take = [&](size_t n) { size_t r = off; off += align_up(n, 256); return r; };
-  p.ks = take(padded_rows(c.N) * row); p.vt = take(padded_rows(c.N) * row);
-  p.kc = take(padded_rows(c.blk->Nc) * row); p.vct = take(padded_rows(c.blk->Nc) * row);
+  p.ks = take(padded_rows(c.N) * row); p.vs = take(padded_rows(c.N) * row);
+  p.kc = take(padded_rows(c.blk->Nc) * row); p.vc = take(padded_rows(c.blk->Nc) * row);
   p.ob = take((size_t)3 * c.N * c.Hq * c.d * 2);
   p.lse = take((size_t)3 * c.N * c.Hq * 4);
   p.idx = take((size_t)c.N * c.Hkv * c.T * 4);
@@ -83,15 +76,14 @@ int run_prep(const ssa_ctx &c, const void *k, const void *v, const PrepOut &o) {
   const size_t row = (size_t)c.Hkv * c.d;
   const size_t nt = padded_rows(c.N) * row, nc = padded_rows(c.blk->Nc) * row;
   const size_t t0 = (size_t)(c.N / 8) * 8 * row, c0 = (size_t)(c.blk->Nc / 8) * 8 * row;
-  Tails ts{{{o.Ks, t0, nt}, {o.Vs, t0, nt}, {o.Kt, t0, nt}, {o.Vt, t0, nt},
-            {o.Kc, c0, nc}, {o.Vc, c0, nc}, {o.Kct, c0, nc}, {o.Vct, c0, nc}}};
-  m_zero_tails<<<dim3(8, 8), 256, 0, c.stream>>>(ts);
+  Tails ts{{{o.Ks, t0, nt}, {o.Vs, t0, nt}, {o.Kc, c0, nc}, {o.Vc, c0, nc}}};
+  m_zero_tails<<<dim3(8, 4), 256, 0, c.stream>>>(ts);
   m_prep<<<c.blk->Nc, 128, 0, c.stream>>>((const bf16_t *)k, (const bf16_t *)v, c.blk->perm, c.blk->cmp_start, c.Hkv, c.d, o);
   return hipGetLastError() == hipSuccess ? SSA_OK : SSA_ERR_HIP;
 }
 
 struct BwdPlan {
-  size_t ks, vs, kt, kc, vc, kct, lse2s, deltas, gws, qt, dot, qs, dos, dqp, dks, dvs, dkc, dvc, bits, counts, start, list, cstart, prow,
+  size_t ks, vs, kc, vc, lse2s, deltas, gws, qs, dos, dqp, dks, dvs, dkc, dvc, bits, counts, start, list, cstart, prow,
       pk, pv, total;
   int q_splits, chunk_len, max_chunks;
 };
@@ -108,11 +100,10 @@ BwdPlan bwd_plan(const ssa_ctx &c) {
   p.q_splits = (int)(sp < 1 ? 1 : (sp > 64 ? 64 : sp));
   size_t off = 0;
   auto take = [&](size_t n) { size_t r = off; off += align_up(n, 256); return r; };
-  p.ks = take(padded_rows(c.N) * row * 2); p.vs = take(padded_rows(c.N) * row * 2); p.kt = take(padded_rows(c.N) * row * 2);
-  p.kc = take(padded_rows(b->Nc) * row * 2); p.vc = take(padded_rows(b->Nc) * row * 2); p.kct = take(padded_rows(b->Nc) * row * 2);
+  p.ks = take(padded_rows(c.N) * row * 2); p.vs = take(padded_rows(c.N) * row * 2);
+  p.kc = take(padded_rows(b->Nc) * row * 2); p.vc = take(padded_rows(b->Nc) * row * 2);
   const size_t nh = (size_t)3 * c.N * c.Hq * 4;
   p.lse2s = take(nh); p.deltas = take(nh); p.gws = take(nh);
-  p.qt = take((size_t)c.N * c.Hq * c.d * 2); p.dot = take((size_t)c.N * c.Hq * c.d * 2);
   p.qs = take((size_t)c.N * c.Hq * c.d * 2); p.dos = take((size_t)c.N * c.Hq * c.d * 2);
   p.dqp = take((size_t)c.N * c.Hq * c.d * 4);
   p.dks = take((size_t)c.N * row * 4); p.dvs = take((size_t)c.N * row * 4);
@@ -168,15 +159,14 @@ int mfma_backward(const ssa_ctx &c, const void *q, const void *k, const void *v,
   if (ws_bytes < p.total) return SSA_ERR_WORKSPACE;
   char *ws = (char *)ws_;
   PrepOut o{};
-  o.Ks = (bf16_t *)(ws + p.ks); o.Vs = (bf16_t *)(ws + p.vs); o.Kt = (bf16_t *)(ws + p.kt);
-  o.Kc = (bf16_t *)(ws + p.kc); o.Vc = (bf16_t *)(ws + p.vc); o.Kct = (bf16_t *)(ws + p.kct);
+  o.Ks = (bf16_t *)(ws + p.ks); o.Vs = (bf16_t *)(ws + p.vs);
+  o.Kc = (bf16_t *)(ws + p.kc); o.Vc = (bf16_t *)(ws + p.vc);
   int rc = run_prep(c, k, v, o);
   if (rc != SSA_OK) return rc;
   MfmaView view = make_view(c);
-  view.Ks = o.Ks; view.Vs = o.Vs; view.Kt = o.Kt; view.Kc = o.Kc; view.Vc = o.Vc; view.Kct = o.Kct;
+  view.Ks = o.Ks; view.Vs = o.Vs; view.Kc = o.Kc; view.Vc = o.Vc;
   BwdBuffers w{};
   w.lse2s = (float *)(ws + p.lse2s); w.deltas = (float *)(ws + p.deltas); w.gws = (float *)(ws + p.gws);
-  w.QT = (bf16_t *)(ws + p.qt); w.dOT = (bf16_t *)(ws + p.dot);
   w.Qs = (bf16_t *)(ws + p.qs); w.dOs = (bf16_t *)(ws + p.dos); w.dQp = (float *)(ws + p.dqp);
   w.dKs = (float *)(ws + p.dks); w.dVs = (float *)(ws + p.dvs); w.dKc = (float *)(ws + p.dkc); w.dVc = (float *)(ws + p.dvc);
   w.sel_bits = (uint32_t *)(ws + p.bits); w.sel_counts = (uint32_t *)(ws + p.counts);
@@ -194,11 +184,11 @@ int mfma_forward(const ssa_ctx &c, const void *q, const void *k, const void *v, 
   if (ws_bytes < p.total) return SSA_ERR_WORKSPACE;
   char *ws = (char *)ws_;
   PrepOut o{};
-  o.Ks = (bf16_t *)(ws + p.ks); o.Vt = (bf16_t *)(ws + p.vt); o.Kc = (bf16_t *)(ws + p.kc); o.Vct = (bf16_t *)(ws + p.vct);
+  o.Ks = (bf16_t *)(ws + p.ks); o.Vs = (bf16_t *)(ws + p.vs); o.Kc = (bf16_t *)(ws + p.kc); o.Vc = (bf16_t *)(ws + p.vc);
   int rc = run_prep(c, k, v, o);
   if (rc != SSA_OK) return rc;
   MfmaView view = make_view(c);
-  view.Ks = o.Ks; view.Vt = o.Vt; view.Kc = o.Kc; view.Vct = o.Vct;
+  view.Ks = o.Ks; view.Vs = o.Vs; view.Kc = o.Kc; view.Vc = o.Vc;
   return mfma_forward_kernels(view, c.d, q, gates, out, lse ? lse : (float *)(ws + p.lse),
                               topk_idx ? topk_idx : (int32_t *)(ws + p.idx), out_branch ? out_branch : (void *)(ws + p.ob),
                               c.stream);
