@@ -8,8 +8,8 @@
 // Two kernel families, both free of floating-point atomics (results do not depend on scheduling):
 //   * m_bwd_dq: query-centric, same walk as the forward kernels (transposed scores, keys in the lanes);
 //   * m_bwd_dkv: key-centric; a wavefront owns 16*KB keys and streams the query rows that attend to them
-//     (scores with the query rows in the lanes), reading Q and dO also from per-token transposed copies so
-//     that the contractions over query rows get 16-byte operands.
+//     (scores with the query rows in the lanes); the contractions over query rows take Q^T and dO^T from the
+//     staged row-major tiles through the transposing LDS read.
 #include "mfma_common.h"
 #include "mfma_launch.h"
 #include "mfma_qc.h"
@@ -144,7 +144,7 @@ __device__ inline void dq_tile(f32x4 (&acc)[CB][D / 16], const QRows<D, CB> &q, 
 // forward selection kernel.
 template <int D>
 __host__ __device__ inline size_t dq_lds_bytes(int tw, int T, int Ns) {
-  return (size_t)2 * StageLayout<D, 2, 0>::ELEMS * sizeof(bf16_t) + 32 + ((size_t)tw * T * 4 + (size_t)(Ns + 31) / 32 + 4) * 4;
+  return (size_t)2 * StageLayout<D, 2>::ELEMS * sizeof(bf16_t) + 32 + ((size_t)tw * T * 4 + (size_t)(Ns + 31) / 32 + 4) * 4;
 }
 
 // PART 0: compression branch only (its pooled keys stay L2 resident when nothing else streams through), result
@@ -152,7 +152,7 @@ __host__ __device__ inline size_t dq_lds_bytes(int tw, int T, int Ns) {
 template <int D, int CB, int PART, int NW>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4 : 2))) void m_bwd_dq(DqArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
-  using L = StageLayout<D, 2, 0>;
+  using L = StageLayout<D, 2>;
   bf16_t *stage0 = (bf16_t *)smem;
   int *ints = (int *)(stage0 + 2 * L::ELEMS);
   const int quad = threadIdx.x >> 4 & 3;
@@ -214,10 +214,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
     wg_range<CB>(ints, lo, hi, q.valid, rs, re, uniform);
     if (threadIdx.x == 0) { ints[4] = rs; ints[5] = re; }
     __syncthreads();
-    TileSrc<2, 0> src = branch == 0
-        ? TileSrc<2, 0>{{a.v.Kc + (size_t)g * D, a.v.Vc + (size_t)g * D}, {}, (uint32_t)kstride}
-        : TileSrc<2, 0>{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, {}, (uint32_t)kstride};
-    run_pipeline<D, 2, 0, 64 * NW, 1>(
+    TileSrc<2> src = branch == 0
+        ? TileSrc<2>{{a.v.Kc + (size_t)g * D, a.v.Vc + (size_t)g * D}, (uint32_t)kstride}
+        : TileSrc<2>{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, (uint32_t)kstride};
+    run_pipeline<D, 2, 64 * NW, 1>(
         src, stage0, ints + 4, ints + 5, re > rs ? 1 : 0, [](int) {},
         [&](const bf16_t *stg, int kb, int) {
           bf16_t *st = (bf16_t *)stg;
@@ -243,8 +243,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
       gw[cb] = a.gws[NH + rs_[cb]];
     }
     int rs = 0, re = 0;
-    TileSrc<2, 0> src{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, {}, (uint32_t)kstride};
-    run_pipeline<D, 2, 0, 64 * NW, 1>(
+    TileSrc<2> src{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, (uint32_t)kstride};
+    run_pipeline<D, 2, 64 * NW, 1>(
         src, stage0, us, ue, nr,
         [&](int r) {
           const int b = lds_uniform(&ub[r]);

@@ -66,7 +66,7 @@ __device__ inline int tile_key_row(int kb, int a) {
   return kb + 8 * (r >> 2) + 4 * a + (r & 3);
 }
 
-// Device arrays of the block structure and the sorted / transposed K,V copies the kernels read.
+// Device arrays of the block structure and the sorted K,V copies the kernels read.
 struct MfmaView {
   const int32_t *perm, *tok_item, *tok_cmp, *tok_win, *cmp_start, *slc_start, *win_start, *slc_child_start, *cmp_slc,
       *cmp_batch, *slc_batch, *item_start;

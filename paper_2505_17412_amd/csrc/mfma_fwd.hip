@@ -3,10 +3,10 @@
 // A workgroup of 4 wavefronts owns 4*CB*16 query rows = consecutive sorted tokens x the h_s heads of one KV
 // group; each wavefront keeps CB blocks of 16 query columns and their running softmax state (Algorithm 1's
 // m, l, o) in registers.  Scores are produced TRANSPOSED (S^T = K Q^T, keys x queries) so that the
-// probabilities land in the lanes exactly as the B operand of the second contraction O^T = V^T P^T needs them;
-// V comes from a copy stored in chunks of 8 tokens, transposed inside each chunk.  Key tiles are staged through
-// LDS once per workgroup (see mfma_qc.h) and every MFMA A operand is one 16-byte LDS read shared by the CB
-// column blocks.
+// probabilities land in the lanes exactly as the B operand of the second contraction O^T = V^T P^T needs them.
+// Key tiles (K rows and V rows, both row-major) are staged through LDS once per workgroup (see mfma_qc.h); the K
+// operand is one 16-byte LDS read, the V^T operand comes from the same row-major V tile through the transposing
+// LDS read of gfx950, so no transposed copy of V exists anywhere.
 #include "mfma_common.h"
 #include "topk_device.h"
 #include "mfma_launch.h"
@@ -153,7 +153,7 @@ constexpr float SCORE_FIX = 134217728.0f;  // 2^27: a row's scores sum to h_s <=
 // lse per query row [4 waves][CB <= 4][16]
 template <int D>
 __host__ __device__ inline size_t cmp_lds_bytes(int tw, int s_max) {
-  return (size_t)2 * StageLayout<D, 2, 0>::ELEMS * sizeof(bf16_t) + 32 + ((size_t)tw * s_max + 4 * ((s_max + 31) / 32) + 4 * 4 * 16) * 4;
+  return (size_t)2 * StageLayout<D, 2>::ELEMS * sizeof(bf16_t) + 32 + ((size_t)tw * s_max + 4 * ((s_max + 31) / 32) + 4 * 4 * 16) * 4;
 }
 
 // Compression branch (eq. (4) first term over the mean-pooled keys of eq. (5)), then the selection scores of
@@ -162,7 +162,7 @@ __host__ __device__ inline size_t cmp_lds_bytes(int tw, int s_max) {
 template <int D, int CB>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4 : 2))) void m_cmp_fwd(FwdArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
-  using L = StageLayout<D, 2, 0>;
+  using L = StageLayout<D, 2>;
   bf16_t *stage0 = (bf16_t *)smem;
   int *ints = (int *)(stage0 + 2 * L::ELEMS);
   const int wid = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 15, quad = lane >> 4;
@@ -193,11 +193,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) { act[cb] = true; on[cb] = q.valid[cb]; }
   const float slack = 8.0f / a.v.sl2;
-  TileSrc<2, 0> src{{a.v.Kc + (size_t)g * D, a.v.Vc + (size_t)g * D}, {}, (uint32_t)(a.v.Hkv * D)};
+  TileSrc<2> src{{a.v.Kc + (size_t)g * D, a.v.Vc + (size_t)g * D}, (uint32_t)(a.v.Hkv * D)};
   FwdState<D, CB> st;
   init_state(st);
   const float sl2 = a.v.sl2;
-  run_pipeline<D, 2, 0>(
+  run_pipeline<D, 2>(
       src, stage0, ints + 4, ints + 5, nr, [](int) {},
       [&](const bf16_t *stg, int kb, int) {
         if (uniform && kb >= rs && kb + 32 <= re)
@@ -210,7 +210,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
 
   // ---- selection scores, eq. (6): second walk over the pooled keys with the normaliser known
   for (int i = threadIdx.x; i < TW * s_max; i += 256) S[i] = 0u;
-  TileSrc<1, 0> ksrc{{a.v.Kc + (size_t)g * D}, {}, (uint32_t)(a.v.Hkv * D)};
+  TileSrc<1> ksrc{{a.v.Kc + (size_t)g * D}, (uint32_t)(a.v.Hkv * D)};
   if (hs >= 4) {
     // Scores NOT transposed here (S = Q K^T: query rows x keys), so that a lane holds four heads of ONE token for
     // one key: the sum over the group's heads (eq. (6), inner sum) is three in-lane adds plus at most two lane
@@ -236,7 +236,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
       ks0[cb] = ok ? a.v.slc_batch[item] : 0;
       owner[cb] = (4 * quad) % hs == 0;
     }
-    run_pipeline<D, 1, 0>(
+    run_pipeline<D, 1>(
         ksrc, stage0, ints + 4, ints + 5, nr, [](int) {},
         [&](const bf16_t *stg, int kb, int) {
 #pragma unroll
@@ -266,7 +266,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
         });
   } else {
     __syncthreads();
-    run_pipeline<D, 1, 0>(
+    run_pipeline<D, 1>(
         ksrc, stage0, ints + 4, ints + 5, nr, [](int) {},
         [&](const bf16_t *stg, int kb, int) {
           float s[CB][8];
@@ -309,7 +309,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
 // LDS plan of the selection kernel (bytes): two stages | 8 ints | I rows [TW][T] | union bits | range lists 3 x [TW*T]
 template <int D>
 __host__ __device__ inline size_t slc_lds_bytes(int tw, int T, int Ns) {
-  return (size_t)2 * StageLayout<D, 2, 0>::ELEMS * sizeof(bf16_t) + 32 + ((size_t)tw * T * 4 + (size_t)(Ns + 31) / 32 + 4) * 4;
+  return (size_t)2 * StageLayout<D, 2>::ELEMS * sizeof(bf16_t) + 32 + ((size_t)tw * T * 4 + (size_t)(Ns + 31) / 32 + 4) * 4;
 }
 
 // Selection branch: Algorithm 1.  The workgroup walks the union of the blocks its tokens selected, in ascending
@@ -318,7 +318,7 @@ __host__ __device__ inline size_t slc_lds_bytes(int tw, int T, int Ns) {
 template <int D, int CB, int NW>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4 : 2))) void m_slc_fwd(FwdArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
-  using L = StageLayout<D, 2, 0>;
+  using L = StageLayout<D, 2>;
   bf16_t *stage0 = (bf16_t *)smem;
   int *ints = (int *)(stage0 + 2 * L::ELEMS);
   const int lane = threadIdx.x & 63;
@@ -340,12 +340,12 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
   const float slack = 8.0f / a.v.sl2;
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) { jc[cb] = 0; lo[cb] = hi[cb] = 0; act[cb] = false; on[cb] = false; }
-  TileSrc<2, 0> src{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, {}, (uint32_t)(a.v.Hkv * D)};
+  TileSrc<2> src{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, (uint32_t)(a.v.Hkv * D)};
   FwdState<D, CB> st;
   init_state(st);
   const float sl2 = a.v.sl2;
   int rs = 0, re = 0;
-  run_pipeline<D, 2, 0, 64 * NW>(
+  run_pipeline<D, 2, 64 * NW>(
       src, stage0, us, ue, nr,
       [&](int r) {
         const int b = lds_uniform(&ub[r]);
@@ -380,7 +380,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
 template <int D, int CB>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4 : 2))) void m_win_fwd(FwdArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
-  using L = StageLayout<D, 2, 0>;
+  using L = StageLayout<D, 2>;
   bf16_t *stage0 = (bf16_t *)smem;
   int *ints = (int *)(stage0 + 2 * L::ELEMS);
   const int hs = a.v.hs, TW = 4 * CB * 16 / hs;
@@ -405,11 +405,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
   wg_range<CB>(ints, lo, hi, q.valid, rs, re, uniform);
   if (threadIdx.x == 0) { ints[4] = rs; ints[5] = re; }
   __syncthreads();
-  TileSrc<2, 0> src{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, {}, (uint32_t)(a.v.Hkv * D)};
+  TileSrc<2> src{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, (uint32_t)(a.v.Hkv * D)};
   FwdState<D, CB> st;
   init_state(st);
   const float sl2 = a.v.sl2;
-  run_pipeline<D, 2, 0>(
+  run_pipeline<D, 2>(
       src, stage0, ints + 4, ints + 5, re > rs ? 1 : 0, [](int) {},
       [&](const bf16_t *stg, int kb, int) {
         if (uniform && kb >= rs && kb + 32 <= re)
@@ -454,7 +454,7 @@ int launch_forward(const FwdArgs &a, const bf16_t *gates, bf16_t *out, hipStream
   const dim3 grid(xcd_grid_size((a.v.N + tw - 1) / tw, a.v.Hkv));
   const int tw_slc = SLC_WAVES * SLC_CB * 16 / a.v.hs;
   const size_t lds_cmp = cmp_lds_bytes<D>(tw_cmp, a.v.s_max), lds_slc = slc_lds_bytes<D>(tw_slc, a.v.T, a.v.Ns);
-  const size_t lds_win = (size_t)2 * StageLayout<D, 2, 0>::ELEMS * sizeof(bf16_t) + 32;
+  const size_t lds_win = (size_t)2 * StageLayout<D, 2>::ELEMS * sizeof(bf16_t) + 32;
   static bool attr_done = false;  // raise the dynamic LDS limit once per process for these instantiations
   if (!attr_done) {
     (void)hipFuncSetAttribute((const void *)m_cmp_fwd<D, CMP_CB>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);

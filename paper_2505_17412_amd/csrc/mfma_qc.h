@@ -16,44 +16,34 @@
 // tile_key_row) occupy the consecutive slots 16a .. 16a+15, so one operand read of a 16-lane quad covers 256
 // contiguous bytes.  The slot is XORed with (segment & 7): reads stay a permutation of the same 16 slots, and the
 // 8 threads that stage one row (8 segments, 512 bytes apart) land in 8 different 16-byte bank groups.
-// Transposed tiles: D rows (dims) of 32 keys (+8 pad) = 80-byte rows, conflict free for reads and writes.
 template <int D>
 struct TileGeom {
   static constexpr int ROW_ELEMS = 32 * D;
-  static constexpr int TROW = 40;
-  static constexpr int T_ELEMS = D * TROW;
   static constexpr int ROW_ITEMS = 32 * D / 8;                  // 16-byte items of a row-major tile
-  static constexpr int T_ITEMS = 4 * D;                         // 16-byte items of a transposed tile
   // 16-byte items per thread when NTHR threads stage a tile
   static constexpr int row_per_thread(int nthr) { return (ROW_ITEMS + nthr - 1) / nthr; }
-  static constexpr int t_per_thread(int nthr) { return (T_ITEMS + nthr - 1) / nthr; }
   __device__ static inline int sigma(int row) { return 16 * ((row >> 2) & 1) + 4 * (row >> 3) + (row & 3); }
   // element offset of (row slot, 16-byte segment) inside a row-major tile
   __device__ static inline int slot_off(int slot, int seg) { return ((seg << 5) + (slot ^ (seg & 7))) << 3; }
   // element offset of (row, 16-byte segment)
   __device__ static inline int row_off(int row, int seg) { return slot_off(sigma(row), seg); }
-  // element offset of (dim, chunk of 8 keys) inside a transposed tile
-  __device__ static inline int t_off(int dim, int chunk) { return dim * TROW + (chunk << 3); }
 };
 
 // Registers holding one tile set on its way from global memory to LDS.
-template <int D, int NROW, int NT, int NTHR = 256>
+template <int D, int NROW, int NTHR = 256>
 struct TileRegs {
   bf16x8 r[NROW][TileGeom<D>::row_per_thread(NTHR)];
-  bf16x8 t[NT][TileGeom<D>::t_per_thread(NTHR)];
 };
 
-// Global sources of a tile set: row-major arrays [rows][Hkv][D] and chunk-transposed arrays [rows/8][Hkv][D][8],
-// already offset to the KV group.
-template <int NROW, int NT>
+// Global sources of a tile set: row-major arrays [rows][Hkv][D], already offset to the KV group.
+template <int NROW>
 struct TileSrc {
   const bf16_t *row[NROW];
-  const bf16_t *tr[NT];
   uint32_t kstride;  // elements between consecutive rows of a row-major array (Hkv*D); whole arrays stay below 2^31 elements
 };
 
-template <int D, int NROW, int NT, int NTHR>
-__device__ inline void tile_load(TileRegs<D, NROW, NT, NTHR> &regs, const TileSrc<NROW, NT> &src, int kb) {
+template <int D, int NROW, int NTHR>
+__device__ inline void tile_load(TileRegs<D, NROW, NTHR> &regs, const TileSrc<NROW> &src, int kb) {
   using G = TileGeom<D>;
 #pragma unroll
   for (int x = 0; x < NROW; ++x)
@@ -65,32 +55,19 @@ __device__ inline void tile_load(TileRegs<D, NROW, NT, NTHR> &regs, const TileSr
         regs.r[x][i] = ld8(src.row[x] + ((uint32_t)(kb + row) * (uint32_t)src.kstride + (uint32_t)(seg * 8)));
       }
     }
-#pragma unroll
-  for (int x = 0; x < NT; ++x)
-#pragma unroll
-    for (int i = 0; i < G::t_per_thread(NTHR); ++i) {
-      const int it = threadIdx.x + NTHR * i;
-      if (G::T_ITEMS % NTHR == 0 || it < G::T_ITEMS) {
-        const int chunk = it / D, dim = it % D;
-        regs.t[x][i] = ld8(src.tr[x] + ((uint32_t)((kb >> 3) + chunk) * (uint32_t)(src.kstride * 8) + (uint32_t)(dim * 8)));
-      }
-    }
 }
 
-// LDS buffer layout of one stage: NROW row-major tiles, then NT transposed tiles.
-template <int D, int NROW, int NT>
+// LDS buffer layout of one stage: NROW row-major tiles.
+template <int D, int NROW>
 struct StageLayout {
-  static constexpr int ELEMS = NROW * TileGeom<D>::ROW_ELEMS + NT * TileGeom<D>::T_ELEMS;
+  static constexpr int ELEMS = NROW * TileGeom<D>::ROW_ELEMS;
   __device__ static inline bf16_t *row_tile(bf16_t *stage, int x) { return stage + x * TileGeom<D>::ROW_ELEMS; }
-  __device__ static inline bf16_t *t_tile(bf16_t *stage, int x) {
-    return stage + NROW * TileGeom<D>::ROW_ELEMS + x * TileGeom<D>::T_ELEMS;
-  }
 };
 
-template <int D, int NROW, int NT, int NTHR>
-__device__ inline void tile_store(const TileRegs<D, NROW, NT, NTHR> &regs, bf16_t *stage) {
+template <int D, int NROW, int NTHR>
+__device__ inline void tile_store(const TileRegs<D, NROW, NTHR> &regs, bf16_t *stage) {
   using G = TileGeom<D>;
-  using L = StageLayout<D, NROW, NT>;
+  using L = StageLayout<D, NROW>;
 #pragma unroll
   for (int x = 0; x < NROW; ++x)
 #pragma unroll
@@ -101,16 +78,6 @@ __device__ inline void tile_store(const TileRegs<D, NROW, NT, NTHR> &regs, bf16_
         *reinterpret_cast<bf16x8 *>(L::row_tile(stage, x) + G::row_off(row, seg)) = regs.r[x][i];
       }
     }
-#pragma unroll
-  for (int x = 0; x < NT; ++x)
-#pragma unroll
-    for (int i = 0; i < G::t_per_thread(NTHR); ++i) {
-      const int it = threadIdx.x + NTHR * i;
-      if (G::T_ITEMS % NTHR == 0 || it < G::T_ITEMS) {
-        const int chunk = it / D, dim = it % D;
-        *reinterpret_cast<bf16x8 *>(L::t_tile(stage, x) + G::t_off(dim, chunk)) = regs.t[x][i];
-      }
-    }
 }
 
 // A operand of sub-tile a, contraction step ks, from a row-major LDS tile (row = key, see tile_key_row).
@@ -119,15 +86,9 @@ __device__ inline bf16x8 lds_row_operand(const bf16_t *tile, int a, int ks) {
   const int n = threadIdx.x & 15, quad = threadIdx.x >> 4 & 3;
   return *reinterpret_cast<const bf16x8 *>(tile + TileGeom<D>::slot_off(16 * a + n, 4 * ks + quad));
 }
-// A operand of dim block dt from a transposed LDS tile (row = dim 16*dt + n, keys 8*quad .. +7).
-template <int D>
-__device__ inline bf16x8 lds_t_operand(const bf16_t *tile, int dt) {
-  const int n = threadIdx.x & 15, quad = threadIdx.x >> 4 & 3;
-  return *reinterpret_cast<const bf16x8 *>(tile + TileGeom<D>::t_off(16 * dt + n, quad));
-}
 
-// The same A operand as lds_t_operand (row = dim 16*dt + n, contraction rows 8*quad .. +7 of the tile), but taken from
-// a ROW-major LDS tile with the transposing LDS read of gfx950 (ds_read_b64_tr_b16): inside a 16-lane group lane p
+// Transposed A operand (row = dim 16*dt + n, contraction over the tile's rows 8*quad .. +7), taken from the same
+// ROW-major LDS tile with the transposing LDS read of gfx950 (ds_read_b64_tr_b16): inside a 16-lane group lane p
 // hands in the address of 4 consecutive elements and lane i receives element (i & 3) of lanes (i >> 2), 4 + (i >> 2),
 // 8 + (i >> 2), 12 + (i >> 2).  With lane p pointing at row 8*quad + (p >> 2), dims 16*dt + 4*(p & 3) .. +3, lane i
 // ends up with dim 16*dt + i of rows 8*quad .. +3; a second read covers rows +4 .. +7.  No transposed copy of the
@@ -218,26 +179,26 @@ __device__ inline void load_rows(const bf16_t *Q, const MfmaView &v, int wg_pos0
 // ahead of the tile being consumed, through PF register sets used alternately; LDS holds two stages: the stage
 // written at step i is read at step i and overwritten at step i+2, with one barrier per step in between.
 // enter(r) runs when the walk reaches range r, tile(stage, kb, r) consumes one staged tile.
-template <int D, int NROW, int NT, int NTHR = 256, int PF = 2, class Enter, class Tile>
-__device__ inline void run_pipeline(const TileSrc<NROW, NT> &src, bf16_t *stage0, const int *rng_s, const int *rng_e, int nr,
+template <int D, int NROW, int NTHR = 256, int PF = 2, class Enter, class Tile>
+__device__ inline void run_pipeline(const TileSrc<NROW> &src, bf16_t *stage0, const int *rng_s, const int *rng_e, int nr,
                                     Enter enter, Tile tile) {
-  using L = StageLayout<D, NROW, NT>;
+  using L = StageLayout<D, NROW>;
   if (nr > 0) {
-    TileRegs<D, NROW, NT, NTHR> regs[PF];
+    TileRegs<D, NROW, NTHR> regs[PF];
     TileIter cur = iter_begin(rng_s, nr);
     TileIter ahead = cur;  // the last tile whose loads are in flight
-    tile_load<D, NROW, NT, NTHR>(regs[0], src, cur.kb);
+    tile_load<D, NROW, NTHR>(regs[0], src, cur.kb);
     if (PF == 2) {
       ahead = iter_next(cur, rng_s, rng_e, nr);
-      if (ahead.r < nr) tile_load<D, NROW, NT, NTHR>(regs[PF - 1], src, ahead.kb);
+      if (ahead.r < nr) tile_load<D, NROW, NTHR>(regs[PF - 1], src, ahead.kb);
     }
     int buf = 0, cur_r = -1;
-    auto step = [&](TileRegs<D, NROW, NT, NTHR> &r) {
+    auto step = [&](TileRegs<D, NROW, NTHR> &r) {
       bf16_t *st = stage0 + buf * L::ELEMS;
-      tile_store<D, NROW, NT, NTHR>(r, st);
+      tile_store<D, NROW, NTHR>(r, st);
       __syncthreads();
       if (ahead.r < nr) ahead = iter_next(ahead, rng_s, rng_e, nr);
-      if (ahead.r < nr) tile_load<D, NROW, NT, NTHR>(r, src, ahead.kb);
+      if (ahead.r < nr) tile_load<D, NROW, NTHR>(r, src, ahead.kb);
       if (cur.r != cur_r) {
         cur_r = cur.r;
         enter(cur_r);
