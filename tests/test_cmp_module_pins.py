@@ -1,0 +1,102 @@
+"""CPU pins of the learned-compression oracle (eq. (5): positional encoding + sparse 3D convolution + mean pool).
+
+The oracle is checked against things that are not itself: a dense `conv3d` of a library (zeros at inactive sites
+make the dense and the submanifold convolution agree at active sites) with the library's own reverse-mode
+differentiation for every gradient, and the special case in which the module reduces to the plain mean pool.
+"""
+import numpy as np
+import pytest
+
+from oracle.blocks import build_blocks
+from oracle.cmp_module import OFFSETS, CompressionModule, neighbor_table, pe_index
+from oracle.ssa_oracle import Oracle
+from paper_2505_17412_amd import inputs
+
+
+def problem(seed=5, grid=8, n=(60, 45), m=(2, 4, 4), c=6):
+    wl = inputs.random_points_workload(seed, grid, n, 2, 1, c, m, 2)
+    rng = np.random.default_rng(seed + 1)
+    b = build_blocks(wl.coords, wl.batch_offsets, grid, *m)
+    mod = CompressionModule(wl.coords, wl.batch_offsets, m[0], b.ids["cmp"], b.n_blocks["cmp"])
+    x = rng.standard_normal((wl.n_tokens, c))
+    pe = rng.standard_normal((m[0] ** 3, c))
+    w = rng.standard_normal((27, c, c)) * 0.3
+    bias = rng.standard_normal(c)
+    return wl, b, mod, x, pe, w, bias, rng
+
+
+def test_neighbor_table_and_pe_index_by_brute_force():
+    wl, b, mod, *_ = problem()
+    nb = neighbor_table(wl.coords, wl.batch_offsets)
+    item = np.searchsorted(wl.batch_offsets, np.arange(wl.n_tokens), side="right") - 1
+    for t in range(wl.n_tokens):
+        for o, off in enumerate(OFFSETS):
+            hit = [u for u in range(wl.n_tokens)
+                   if item[u] == item[t] and tuple(wl.coords[u] - wl.coords[t]) == off]
+            assert nb[t, o] == (hit[0] if hit else -1)
+    assert OFFSETS[13] == (0, 0, 0) and np.array_equal(nb[:, 13], np.arange(wl.n_tokens))
+    m = 2
+    assert np.array_equal(pe_index(wl.coords, m), [(int(x) % m * m + int(y) % m) * m + int(z) % m for x, y, z in wl.coords])
+
+
+def test_module_matches_dense_conv3d_and_its_autograd():
+    torch = pytest.importorskip("torch")
+    wl, b, mod, x, pe, w, bias, rng = problem()
+    grid, c, m = 8, x.shape[1], 2
+    dxc = rng.standard_normal((b.n_blocks["cmp"], c))
+    item = np.searchsorted(wl.batch_offsets, np.arange(wl.n_tokens), side="right") - 1
+    tx = torch.tensor(x, dtype=torch.float64, requires_grad=True)
+    tpe = torch.tensor(pe, dtype=torch.float64, requires_grad=True)
+    tw = torch.tensor(w, dtype=torch.float64, requires_grad=True)
+    tb = torch.tensor(bias, dtype=torch.float64, requires_grad=True)
+    cx, cy, cz = (torch.tensor(wl.coords[:, i].astype(np.int64)) for i in range(3))
+    ti = torch.tensor(item.astype(np.int64))
+    u = tx + tpe[torch.tensor(pe_index(wl.coords, m).astype(np.int64))]
+    vol = torch.zeros((2, grid, grid, grid, c), dtype=torch.float64)
+    vol = vol.index_put((ti, cx, cy, cz), u).permute(0, 4, 1, 2, 3)  # [item, :, x, y, z] = u, zero elsewhere
+    # conv3d is a cross-correlation: out[co, p] = sum_{ci,k} weight[co, ci, k] * in[ci, p + k - 1]
+    weight = tw.reshape(3, 3, 3, c, c).permute(4, 3, 0, 1, 2)
+    dense = torch.nn.functional.conv3d(vol, weight, bias=tb, padding=1)
+    y = dense[ti, :, cx, cy, cz]
+    cid = torch.tensor(b.ids["cmp"].astype(np.int64))
+    cnt = torch.bincount(cid, minlength=b.n_blocks["cmp"]).to(torch.float64)
+    xc = torch.zeros((b.n_blocks["cmp"], c), dtype=torch.float64).index_add(0, cid, y) / cnt[:, None]
+    f = mod.forward(x, pe, w, bias)
+    assert np.allclose(f.y, y.detach().numpy(), rtol=1e-12, atol=1e-12)
+    assert np.allclose(f.x_cmp, xc.detach().numpy(), rtol=1e-12, atol=1e-12)
+    (xc * torch.tensor(dxc)).sum().backward()
+    g = mod.backward(x, pe, w, bias, dxc)
+    for name, got, want in (("dx", g.dx, tx.grad), ("dpe", g.dpe, tpe.grad), ("dw", g.dw, tw.grad), ("dbias", g.dbias, tb.grad)):
+        assert np.allclose(got, want.numpy(), rtol=1e-10, atol=1e-10), name
+
+
+def test_identity_centre_weight_reduces_to_mean_pool():
+    wl, b, mod, x, pe, w, bias, rng = problem(seed=9, c=4)
+    c = x.shape[1]
+    w0 = np.zeros((27, c, c))
+    w0[13] = np.eye(c)
+    f = mod.forward(x, np.zeros_like(pe), w0, np.zeros(c))
+    orc = Oracle(wl.coords, wl.batch_offsets, 8, 2, 4, 4, 2, 2, 1, c)
+    assert np.allclose(f.x_cmp.reshape(-1, 1, c), orc.pool(x.reshape(-1, 1, c)), rtol=1e-13, atol=1e-13)
+    # gradient of the plain mean pool: every member receives dXc / count, nothing else moves
+    dxc = rng.standard_normal(f.x_cmp.shape)
+    g = mod.backward(x, np.zeros_like(pe), w0, np.zeros(c), dxc)
+    cnt = np.bincount(b.ids["cmp"])
+    assert np.allclose(g.dx, dxc[b.ids["cmp"]] / cnt[b.ids["cmp"]][:, None])
+
+
+def test_translation_by_one_block_keeps_the_module_output():
+    """Shifting every coordinate by m_cmp moves no token inside its block and changes no neighbourhood."""
+    wl, b, mod, x, pe, w, bias, rng = problem(seed=11, grid=8, n=(50,), m=(2, 4, 4))
+    keep = np.all(wl.coords < 6, axis=1)
+    coords = wl.coords[keep]
+    offs = np.array([0, coords.shape[0]], dtype=np.int32)
+    outs = []
+    for shift in (0, 2):
+        cs = coords + shift
+        bb = build_blocks(cs, offs, 8, 2, 4, 4)
+        mm = CompressionModule(cs, offs, 2, bb.ids["cmp"], bb.n_blocks["cmp"])
+        f = mm.forward(x[keep], pe, w, bias)
+        outs.append((f.y, np.sort(np.round(f.x_cmp, 9), axis=0)))
+    assert np.allclose(outs[0][0], outs[1][0])
+    assert np.allclose(outs[0][1], outs[1][1])
