@@ -149,6 +149,62 @@ int ssa_topk_from_scores(const ssa_params_t *params, const ssa_blocks_t *blocks,
                          int32_t *topk_idx, void *stream);
 
 /*
+ * Learned sparse 3D compression module (Sec. "Sparse 3D Compression", eq. (5)): block-level tokens
+ * x_cmp = delta(x + PE(x)), delta = sparse 3D convolution followed by sparse 3D mean pooling, for one tensor x
+ * (the keys or the values).  The paper names the three operations only; this library fixes: PE is a table with one
+ * row per place inside an m_cmp^3 block, row ((x mod m)*m + (y mod m))*m + (z mod m); the convolution is a
+ * submanifold 3x3x3 one over the sparse volume of the token's batch item (outputs at active sites, inactive
+ * neighbours contribute nothing) with C = Hkv*d input and output channels and a bias; the mean is over the active
+ * tokens of the compression block.  Coordinates must be distinct inside a batch item (otherwise the neighbourhood
+ * of a site is not defined; no error is raised).  bf16 only; C in {32, 64, 128, 256}; m_cmp^3 * C <= 16384.
+ */
+typedef struct {
+  const void *pe;   /* dev [m_cmp^3, C]  positional table, dtype of params                                   */
+  const void *w;    /* dev [27, C, C]    w[o][c_in][c_out]; o = ((dx+1)*3 + (dy+1))*3 + (dz+1) multiplies the
+                                          token at coords + (dx,dy,dz)                                        */
+  const void *bias; /* dev [C]                                                                                */
+} ssa_cmp_weights_t;
+
+/* Bytes of device workspace of ssa_compress_forward (for_backward == 0) / ssa_compress_backward; 0 on bad input. */
+size_t ssa_compress_workspace_bytes(const ssa_params_t *params, const ssa_blocks_t *blocks, int for_backward);
+
+/*
+ * Forward of the module.  x dev [N,Hkv,d] (caller token order); x_cmp dev [N_c,Hkv,d], written, row c = compression
+ * block c of the handle (ascending (item, Morton) order, the order of ssa_blocks_export(CMP_START)).
+ * Asynchronous on `stream`; allocates nothing.  Errors: NULL, MISMATCH, BAD_HEADS, UNSUPPORTED, WORKSPACE, HIP.
+ */
+int ssa_compress_forward(const ssa_params_t *params, const ssa_blocks_t *blocks, const void *x,
+                         const ssa_cmp_weights_t *weights, void *x_cmp, void *workspace, size_t workspace_bytes,
+                         void *stream);
+
+/*
+ * Backward of the module (chain rule of the three operations; the paper states none).
+ *   dx_cmp   dev float [N_c,Hkv,d]  gradient w.r.t. x_cmp (what ssa_backward_pooled writes)
+ *   dx_accum dev [N,Hkv,d]          in/out: the gradient w.r.t. x is ADDED to it (it usually already holds the
+ *                                   attention's own dk or dv)
+ *   dpe dev float [m_cmp^3, C], dw dev float [27, C, C], dbias dev float [C]: overwritten
+ */
+int ssa_compress_backward(const ssa_params_t *params, const ssa_blocks_t *blocks, const void *x,
+                          const ssa_cmp_weights_t *weights, const float *dx_cmp, void *dx_accum, float *dpe,
+                          float *dw, float *dbias, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * ssa_forward / ssa_backward with the block-level keys and values supplied by the caller (k_cmp, v_cmp dev
+ * [N_c,Hkv,d], e.g. from ssa_compress_forward) instead of the plain mean pool.  ssa_backward_pooled writes the
+ * gradients w.r.t. them (dk_cmp, dv_cmp dev float [N_c,Hkv,d]); its dk, dv then hold the selection and window
+ * branches only.  Workspace as ssa_workspace_bytes.  bf16 problems the matrix-core kernels cover only
+ * (head_dim 32/64/128; backward: 8 or 16 query heads per KV head), otherwise UNSUPPORTED.
+ */
+int ssa_forward_pooled(const ssa_params_t *params, const ssa_blocks_t *blocks, const void *q, const void *k,
+                       const void *v, const void *gates, const void *k_cmp, const void *v_cmp, void *out, float *lse,
+                       int32_t *topk_idx, void *out_branch, void *workspace, size_t workspace_bytes, void *stream);
+int ssa_backward_pooled(const ssa_params_t *params, const ssa_blocks_t *blocks, const void *q, const void *k,
+                        const void *v, const void *gates, const void *k_cmp, const void *v_cmp,
+                        const void *out_branch, const float *lse, const int32_t *topk_idx, const void *dout, void *dq,
+                        void *dk, void *dv, void *dgates, float *dk_cmp, float *dv_cmp, void *workspace,
+                        size_t workspace_bytes, void *stream);
+
+/*
  * Measurement hook (not an operation of the paper; for benchmarks that need the duration of single kernels).
  * While enabled, every kernel the library launches is bracketed by a HIP event pair recorded on the launch
  * stream.  ssa_profile_enable(on) clears the totals; ssa_profile_get(i, ...) waits for the recorded events and

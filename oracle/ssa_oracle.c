@@ -257,7 +257,7 @@ static void attend_bwd(const ssa_oracle_problem *p, const double *q, const doubl
 void ssa_oracle_backward(const ssa_oracle_problem *p, const double *Q, const double *K, const double *V,
                          const double *gates, const double *Kc, const double *Vc, const double *Ob,
                          const double *dO, int64_t nq, const int32_t *qidx, const int32_t *I, double *dQ,
-                         double *dK, double *dV, double *dgates) {
+                         double *dK, double *dV, double *dgates, double *dKc_out, double *dVc_out) {
   const int d = p->d, Hq = p->Hq, Hkv = p->Hkv, hs = Hq / Hkv, T = p->T;
   const int64_t N = p->N;
   const int64_t kvsz = N * Hkv * d, csz = (int64_t)p->Nc * Hkv * d;
@@ -314,6 +314,14 @@ void ssa_oracle_backward(const ssa_oracle_problem *p, const double *Q, const dou
       for (int64_t i = 0; i < csz; ++i) { dKc[i] += tKc[i]; dVc[i] += tVc[i]; }
     }
     free(prob); free(keys); free(gb); free(tK); free(tV); free(tKc); free(tVc);
+  }
+  /* block-level keys/values supplied from outside (Kc, Vc are then not the mean pool of K, V): hand their
+   * gradients out and leave dK, dV with the selection and window branches only */
+  if (dKc_out != NULL && dVc_out != NULL) {
+    memcpy(dKc_out, dKc, sizeof(double) * (size_t)csz);
+    memcpy(dVc_out, dVc, sizeof(double) * (size_t)csz);
+    free(dKc); free(dVc);
+    return;
   }
   /* gradient of the mean pool: every member token receives dXc / count */
   const int64_t row = (int64_t)Hkv * d;

@@ -87,6 +87,8 @@ class BackwardResult:
     dk: np.ndarray
     dv: np.ndarray
     dgates: np.ndarray
+    dk_cmp: Optional[np.ndarray] = None  # only when block-level keys/values were supplied from outside
+    dv_cmp: Optional[np.ndarray] = None
 
 
 class Oracle:
@@ -125,13 +127,16 @@ class Oracle:
     def _qidx(self, queries) -> np.ndarray:
         return np.arange(self.N, dtype=np.int32) if queries is None else _i32(queries)
 
-    def forward(self, q, k, v, gates, queries=None, topk_idx=None, want_scores: bool = False) -> ForwardResult:
+    def forward(self, q, k, v, gates, queries=None, topk_idx=None, want_scores: bool = False, k_cmp=None,
+                v_cmp=None) -> ForwardResult:
         """Forward for ``queries`` (caller-order token indices; default all).  ``topk_idx`` given: use those
-        selection sets instead of computing them."""
+        selection sets instead of computing them.  ``k_cmp``/``v_cmp`` given: block-level keys/values from outside
+        (e.g. the learned compression module) instead of the mean pool."""
         q, k, v, gates = _f64(q), _f64(k), _f64(v), _f64(gates)
         assert q.shape == (self.N, self.Hq, self.d) and k.shape == (self.N, self.Hkv, self.d)
         assert v.shape == k.shape and gates.shape == (self.N, self.Hq, 3)
-        kc, vc = self.pool(k), self.pool(v)
+        kc, vc = (self.pool(k), self.pool(v)) if k_cmp is None else (_f64(k_cmp), _f64(v_cmp))
+        assert kc.shape == (self.blocks.n_blocks["cmp"], self.Hkv, self.d) and vc.shape == kc.shape
         qi = self._qidx(queries)
         out = np.zeros((self.N, self.Hq, self.d))
         ob = np.zeros((3, self.N, self.Hq, self.d))
@@ -143,22 +148,30 @@ class Oracle:
                                    C.c_int64(qi.shape[0]), _p(qi), _p(iin), _p(out), _p(ob), _p(lse), _p(sc), _p(idx))
         return ForwardResult(out, ob, lse, idx, sc, kc, vc)
 
-    def backward(self, q, k, v, gates, dout, topk_idx, out_branch=None, queries=None) -> BackwardResult:
-        """Gradients of sum(dout * out) with the selection sets ``topk_idx`` held constant."""
+    def backward(self, q, k, v, gates, dout, topk_idx, out_branch=None, queries=None, k_cmp=None, v_cmp=None):
+        """Gradients of sum(dout * out) with the selection sets ``topk_idx`` held constant.  With ``k_cmp``/``v_cmp``
+        (block-level keys/values from outside) the result also carries their gradients and dk, dv hold the selection
+        and window branches only."""
         q, k, v, gates, dout = _f64(q), _f64(k), _f64(v), _f64(gates), _f64(dout)
         qi = self._qidx(queries)
         idx = _i32(topk_idx)
         if out_branch is None:
-            out_branch = self.forward(q, k, v, gates, queries=qi, topk_idx=idx).out_branch
+            out_branch = self.forward(q, k, v, gates, queries=qi, topk_idx=idx, k_cmp=k_cmp, v_cmp=v_cmp).out_branch
         ob = _f64(out_branch)
-        kc, vc = self.pool(k), self.pool(v)
+        given = k_cmp is not None
+        kc, vc = (_f64(k_cmp), _f64(v_cmp)) if given else (self.pool(k), self.pool(v))
+        dkc = np.zeros_like(kc) if given else None
+        dvc = np.zeros_like(vc) if given else None
         dq = np.zeros((self.N, self.Hq, self.d))
         dk = np.zeros((self.N, self.Hkv, self.d))
         dv = np.zeros((self.N, self.Hkv, self.d))
         dg = np.zeros((self.N, self.Hq, 3))
         _load().ssa_oracle_backward(C.byref(self._prob), _p(q), _p(k), _p(v), _p(gates), _p(kc), _p(vc), _p(ob),
-                                    _p(dout), C.c_int64(qi.shape[0]), _p(qi), _p(idx), _p(dq), _p(dk), _p(dv), _p(dg))
-        return BackwardResult(dq, dk, dv, dg)
+                                    _p(dout), C.c_int64(qi.shape[0]), _p(qi), _p(idx), _p(dq), _p(dk), _p(dv), _p(dg),
+                                    _p(dkc), _p(dvc))
+        res = BackwardResult(dq, dk, dv, dg)
+        res.dk_cmp, res.dv_cmp = dkc, dvc
+        return res
 
     def topk_from_scores(self, scores32: np.ndarray) -> np.ndarray:
         """Top-k decision alone on fp32 scores [N,Hkv,Smax] (column j = j-th selection block of the item)."""

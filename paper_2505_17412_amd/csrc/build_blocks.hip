@@ -212,10 +212,11 @@ extern "C" int ssa_build_blocks(const ssa_params_t *p, const int32_t *coords, co
   h->N = N; h->B = B; h->G = p->grid; h->m_cmp = p->m_cmp; h->m_slc = p->m_slc; h->m_win = p->m_win; h->bits = bits;
   if (hipGetDevice(&h->device) != hipSuccess) { delete h; return SSA_ERR_HIP; }
   const size_t n1 = (size_t)N + 1;
-  const size_t ints = 6 * (size_t)N + 4 * n1 + (size_t)N + 3 * ((size_t)B + 1) + 64;
+  const size_t ints = 2 * (size_t)N + 6 * (size_t)N + 4 * n1 + (size_t)N + 3 * ((size_t)B + 1) + 64;
   if (hipMalloc(&h->base, ints * sizeof(int32_t)) != hipSuccess) { delete h; return SSA_ERR_HIP; }
   int32_t *w = (int32_t *)h->base;
   auto take = [&](size_t n) { int32_t *r = w; w += n; return r; };
+  h->sorted_keys = (uint64_t *)take(2 * (size_t)N);  // first: the allocation's alignment serves the 8-byte keys
   h->perm = take(N); h->inv_perm = take(N); h->tok_item = take(N); h->tok_cmp = take(N); h->tok_slc = take(N);
   h->tok_win = take(N); h->cmp_start = take(n1); h->slc_start = take(n1); h->win_start = take(n1);
   h->slc_child_start = take(n1); h->cmp_slc = take(N); h->cmp_batch = take(B + 1); h->slc_batch = take(B + 1);
@@ -258,6 +259,8 @@ extern "C" int ssa_build_blocks(const ssa_params_t *p, const int32_t *coords, co
                                   3 * ilog2_exact(p->m_win), o, meta);
     const int span = (N > B ? N : B);
     k_maxima<<<(span + 255) / 256, 256, 0, stream>>>(o, B, meta);
+    if (hipMemcpyAsync(h->sorted_keys, k0, (size_t)N * sizeof(uint64_t), hipMemcpyDeviceToDevice, stream) != hipSuccess)
+      return fail(SSA_ERR_HIP);
   } else {
     // no tokens: every start array is a single zero; the offsets are still validated (all must be zero)
     if (hipMemsetAsync(h->base, 0, ints * sizeof(int32_t), stream) != hipSuccess) return fail(SSA_ERR_HIP);

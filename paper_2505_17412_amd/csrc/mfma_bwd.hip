@@ -654,12 +654,13 @@ __global__ __launch_bounds__(256) void m_sel_fill(const uint32_t *__restrict__ b
 
 // ---------------------------------------------------------------------------------------------------------
 // Finish: dK[tok] = dKs[pos] + (sum over query splits of dKc[c]) / count(c)  (gradient of the mean pool),
-// scattered back to caller order.  One workgroup per compression block.
+// scattered back to caller order.  One workgroup per compression block.  With dKc_out/dVc_out given (the pooled
+// rows were the caller's), the summed block gradients go there instead and dK, dV keep the token-level part only.
 // ---------------------------------------------------------------------------------------------------------
 __global__ void m_bwd_finish(const int32_t *__restrict__ perm, const int32_t *__restrict__ cmp_start, int Nc, int row,
                              int splits, const float *__restrict__ dKs, const float *__restrict__ dVs,
                              const float *__restrict__ dKc, const float *__restrict__ dVc, bf16_t *__restrict__ dK,
-                             bf16_t *__restrict__ dV) {
+                             bf16_t *__restrict__ dV, float *__restrict__ dKc_out, float *__restrict__ dVc_out) {
   const int c = blockIdx.x;
   const int b = cmp_start[c], e = cmp_start[c + 1];
   const float inv = 1.0f / (float)(e - b);
@@ -668,6 +669,11 @@ __global__ void m_bwd_finish(const int32_t *__restrict__ perm, const int32_t *__
     for (int s = 0; s < splits; ++s) {
       ck += dKc[((size_t)s * Nc + c) * row + f];
       cv += dVc[((size_t)s * Nc + c) * row + f];
+    }
+    if (dKc_out) {
+      dKc_out[(size_t)c * row + f] = ck;
+      dVc_out[(size_t)c * row + f] = cv;
+      ck = cv = 0.f;
     }
     ck *= inv;
     cv *= inv;
@@ -770,7 +776,7 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
   {
     ProfScope ps(PROF_BWD_FINISH, s);
     m_bwd_finish<<<v.Nc, 128, 0, s>>>(v.perm, v.cmp_start, v.Nc, row, w.q_splits, w.dKs, w.dVs, w.dKc, w.dVc, (bf16_t *)dk,
-                                      (bf16_t *)dv);
+                                      (bf16_t *)dv, w.dKc_out, w.dVc_out);
   }
   return hipGetLastError() == hipSuccess ? SSA_OK : SSA_ERR_HIP;
 }

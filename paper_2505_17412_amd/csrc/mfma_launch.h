@@ -20,6 +20,7 @@ struct BwdBuffers {
   float *pK, *pV;               // [max_part_rows][D] per-chunk partial dK/dV of the selection branch
   int chunk_len, max_chunks;    // query tokens per chunk; upper bound of the number of chunks
   int q_splits;
+  float *dKc_out, *dVc_out;     // [Nc][Hkv][D] or NULL: where the pooled-key/value gradients go instead of being un-pooled
 };
 int mfma_backward_kernels(const MfmaView &v, int D, const BwdBuffers &w, const void *q, const void *gates,
                           const void *out_branch, const float *lse, const int32_t *idx, const void *dout, void *dq,

@@ -82,6 +82,15 @@ int run_prep(const ssa_ctx &c, const void *k, const void *v, const PrepOut &o) {
   return hipGetLastError() == hipSuccess ? SSA_OK : SSA_ERR_HIP;
 }
 
+// Caller-supplied block-level keys/values take the place of the mean-pooled rows (the zero padding behind them stays).
+int override_pooled(const ssa_ctx &c, const PrepOut &o) {
+  if (!c.kc_in) return SSA_OK;
+  const size_t bytes = (size_t)c.blk->Nc * c.Hkv * c.d * sizeof(bf16_t);
+  SSA_HIP_TRY(hipMemcpyAsync(o.Kc, c.kc_in, bytes, hipMemcpyDeviceToDevice, c.stream));
+  SSA_HIP_TRY(hipMemcpyAsync(o.Vc, c.vc_in, bytes, hipMemcpyDeviceToDevice, c.stream));
+  return SSA_OK;
+}
+
 struct BwdPlan {
   size_t ks, vs, kc, vc, lse2s, deltas, gws, qs, dos, dqp, dks, dvs, dkc, dvc, bits, counts, start, list, cstart, prow,
       pk, pv, total;
@@ -133,6 +142,8 @@ bool mfma_bwd_supported(const ssa_ctx &c) { return c.hs == 8 || c.hs == 16; }
 
 }  // namespace
 
+bool mfma_backward_covers(const ssa_ctx &c) { return mfma_bwd_supported(c); }
+
 bool mfma_supported(const ssa_ctx &c) {
   if (c.dtype != SSA_BF16) return false;
   if (c.d != 32 && c.d != 64 && c.d != 128) return false;
@@ -163,9 +174,12 @@ int mfma_backward(const ssa_ctx &c, const void *q, const void *k, const void *v,
   o.Kc = (bf16_t *)(ws + p.kc); o.Vc = (bf16_t *)(ws + p.vc);
   int rc = run_prep(c, k, v, o);
   if (rc != SSA_OK) return rc;
+  rc = override_pooled(c, o);
+  if (rc != SSA_OK) return rc;
   MfmaView view = make_view(c);
   view.Ks = o.Ks; view.Vs = o.Vs; view.Kc = o.Kc; view.Vc = o.Vc;
   BwdBuffers w{};
+  w.dKc_out = c.dkc_out; w.dVc_out = c.dvc_out;
   w.lse2s = (float *)(ws + p.lse2s); w.deltas = (float *)(ws + p.deltas); w.gws = (float *)(ws + p.gws);
   w.Qs = (bf16_t *)(ws + p.qs); w.dOs = (bf16_t *)(ws + p.dos); w.dQp = (float *)(ws + p.dqp);
   w.dKs = (float *)(ws + p.dks); w.dVs = (float *)(ws + p.dvs); w.dKc = (float *)(ws + p.dkc); w.dVc = (float *)(ws + p.dvc);
@@ -186,6 +200,8 @@ int mfma_forward(const ssa_ctx &c, const void *q, const void *k, const void *v, 
   PrepOut o{};
   o.Ks = (bf16_t *)(ws + p.ks); o.Vs = (bf16_t *)(ws + p.vs); o.Kc = (bf16_t *)(ws + p.kc); o.Vc = (bf16_t *)(ws + p.vc);
   int rc = run_prep(c, k, v, o);
+  if (rc != SSA_OK) return rc;
+  rc = override_pooled(c, o);
   if (rc != SSA_OK) return rc;
   MfmaView view = make_view(c);
   view.Ks = o.Ks; view.Vs = o.Vs; view.Kc = o.Kc; view.Vc = o.Vc;

@@ -82,6 +82,43 @@ extern "C" int ssa_backward(const ssa_params_t *p, const ssa_blocks_t *b, const 
   return generic_backward(c, q, k, v, gates, out_branch, lse, topk_idx, dout, dq, dk, dv, dgates, w, wb);
 }
 
+extern "C" int ssa_forward_pooled(const ssa_params_t *p, const ssa_blocks_t *b, const void *q, const void *k,
+                                  const void *v, const void *gates, const void *k_cmp, const void *v_cmp, void *out,
+                                  float *lse, int32_t *topk_idx, void *out_branch, void *ws, size_t ws_bytes,
+                                  void *stream) {
+  ssa_ctx c;
+  const int rc = make_ctx(p, b, stream, &c);
+  if (rc != SSA_OK) return rc;
+  if (!use_mfma(c)) return SSA_ERR_UNSUPPORTED;
+  if (c.N == 0) return SSA_OK;
+  if (!q || !k || !v || !gates || !k_cmp || !v_cmp || !out) return SSA_ERR_NULL;
+  if (!ws || ws_bytes < ssa_workspace_bytes(p, b, 0)) return SSA_ERR_WORKSPACE;
+  void *w = (void *)align_up((size_t)ws, 256);
+  const size_t wb = ws_bytes - ((size_t)w - (size_t)ws);
+  c.kc_in = k_cmp; c.vc_in = v_cmp;
+  return mfma_forward(c, q, k, v, gates, out, lse, topk_idx, out_branch, w, wb);
+}
+
+extern "C" int ssa_backward_pooled(const ssa_params_t *p, const ssa_blocks_t *b, const void *q, const void *k,
+                                   const void *v, const void *gates, const void *k_cmp, const void *v_cmp,
+                                   const void *out_branch, const float *lse, const int32_t *topk_idx, const void *dout,
+                                   void *dq, void *dk, void *dv, void *dgates, float *dk_cmp, float *dv_cmp, void *ws,
+                                   size_t ws_bytes, void *stream) {
+  ssa_ctx c;
+  const int rc = make_ctx(p, b, stream, &c);
+  if (rc != SSA_OK) return rc;
+  if (!use_mfma(c) || !mfma_backward_covers(c)) return SSA_ERR_UNSUPPORTED;
+  if (c.N == 0) return SSA_OK;
+  if (!q || !k || !v || !gates || !k_cmp || !v_cmp || !out_branch || !lse || !topk_idx || !dout || !dq || !dk || !dv ||
+      !dgates || !dk_cmp || !dv_cmp)
+    return SSA_ERR_NULL;
+  if (!ws || ws_bytes < ssa_workspace_bytes(p, b, 1)) return SSA_ERR_WORKSPACE;
+  void *w = (void *)align_up((size_t)ws, 256);
+  const size_t wb = ws_bytes - ((size_t)w - (size_t)ws);
+  c.kc_in = k_cmp; c.vc_in = v_cmp; c.dkc_out = dk_cmp; c.dvc_out = dv_cmp;
+  return mfma_backward(c, q, k, v, gates, out_branch, lse, topk_idx, dout, dq, dk, dv, dgates, w, wb);
+}
+
 extern "C" int ssa_topk_from_scores(const ssa_params_t *p, const ssa_blocks_t *b, const float *scores, int32_t *topk_idx,
                                     void *stream) {
   if (!p || !b) return SSA_ERR_NULL;

@@ -30,6 +30,7 @@ struct ssa_blocks {
   int32_t *perm, *inv_perm, *tok_item, *tok_cmp, *tok_slc, *tok_win;
   int32_t *cmp_start, *slc_start, *win_start, *slc_child_start, *cmp_slc, *cmp_batch, *slc_batch;
   int32_t *item_start;  // [B+1] sorted-position range of each batch item (a copy of the batch offsets)
+  uint64_t *sorted_keys;  // [N] (batch item << 3*bits) | Morton code, ascending: the token order itself
 };
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -70,6 +71,10 @@ struct ssa_ctx {
   float scale;
   const ssa_blocks *blk;
   hipStream_t stream;
+  // caller-supplied block-level keys/values [Nc][Hkv][d] replacing the mean pool, and where the gradients w.r.t.
+  // them go (fp32 [Nc][Hkv][d]); all NULL in the plain entry points
+  const void *kc_in = nullptr, *vc_in = nullptr;
+  float *dkc_out = nullptr, *dvc_out = nullptr;
 };
 
 // ---- generic (any head_dim / head grouping, fp32 arithmetic) path: generic_kernels.hip
@@ -84,6 +89,7 @@ int launch_topk_from_scores(const ssa_ctx &c, const float *scores, int32_t *topk
 
 // ---- bf16 MFMA path: mfma_*.hip
 bool mfma_supported(const ssa_ctx &c);
+bool mfma_backward_covers(const ssa_ctx &c);  // the key-centric backward kernels cover this head grouping
 size_t mfma_forward_workspace(const ssa_ctx &c);
 size_t mfma_backward_workspace(const ssa_ctx &c);
 int mfma_forward(const ssa_ctx &c, const void *q, const void *k, const void *v, const void *gates, void *out,

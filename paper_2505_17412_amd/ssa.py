@@ -21,12 +21,18 @@ EXPORTED_SYMBOLS = (
     "ssa_build_blocks", "ssa_blocks_counts", "ssa_blocks_max_slc_per_item", "ssa_blocks_export",
     "ssa_blocks_destroy", "ssa_workspace_bytes", "ssa_forward", "ssa_backward", "ssa_topk_from_scores",
     "ssa_error_string", "ssa_profile_enable", "ssa_profile_num_kernels", "ssa_profile_get",
+    "ssa_compress_workspace_bytes", "ssa_compress_forward", "ssa_compress_backward", "ssa_forward_pooled",
+    "ssa_backward_pooled",
 )
 
 
 class ssa_params_t(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_tokens", "n_batch", "grid", "m_cmp", "m_slc", "m_win", "topk",
                                          "n_heads_q", "n_heads_kv", "head_dim", "dtype")] + [("scale", C.c_float)]
+
+
+class ssa_cmp_weights_t(C.Structure):
+    _fields_ = [("pe", C.c_void_p), ("w", C.c_void_p), ("bias", C.c_void_p)]
 
 
 class SSAError(RuntimeError):
@@ -56,6 +62,13 @@ def lib() -> C.CDLL:
         L.ssa_forward.argtypes = [C.POINTER(ssa_params_t), vp] + [vp] * 8 + [vp, C.c_size_t, vp]
         L.ssa_backward.argtypes = [C.POINTER(ssa_params_t), vp] + [vp] * 12 + [vp, C.c_size_t, vp]
         L.ssa_topk_from_scores.argtypes = [C.POINTER(ssa_params_t), vp, vp, vp, vp]
+        L.ssa_compress_workspace_bytes.argtypes = [C.POINTER(ssa_params_t), vp, C.c_int]
+        L.ssa_compress_workspace_bytes.restype = C.c_size_t
+        L.ssa_compress_forward.argtypes = [C.POINTER(ssa_params_t), vp, vp, C.POINTER(ssa_cmp_weights_t), vp, vp, C.c_size_t, vp]
+        L.ssa_compress_backward.argtypes = [C.POINTER(ssa_params_t), vp, vp, C.POINTER(ssa_cmp_weights_t)] + [vp] * 5 + \
+            [vp, C.c_size_t, vp]
+        L.ssa_forward_pooled.argtypes = [C.POINTER(ssa_params_t), vp] + [vp] * 10 + [vp, C.c_size_t, vp]
+        L.ssa_backward_pooled.argtypes = [C.POINTER(ssa_params_t), vp] + [vp] * 16 + [vp, C.c_size_t, vp]
         L.ssa_profile_enable.argtypes = [C.c_int]
         L.ssa_profile_get.argtypes = [C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         L.ssa_error_string.argtypes = [C.c_int]
@@ -159,6 +172,51 @@ def ssa_backward(params, blocks: Blocks, q, k, v, gates, out_branch, lse, topk_i
     _check(lib().ssa_backward(C.byref(params), blocks.handle, _ptr(q), _ptr(k), _ptr(v), _ptr(gates),
                               _ptr(out_branch), _ptr(lse), _ptr(topk_idx), _ptr(dout), _ptr(dq), _ptr(dk), _ptr(dv),
                               _ptr(dgates), _ptr(workspace), workspace.numel(), _stream()), "ssa_backward")
+
+
+def ssa_compress_workspace_bytes(params: ssa_params_t, blocks: Blocks, for_backward: bool) -> int:
+    return int(lib().ssa_compress_workspace_bytes(C.byref(params), blocks.handle, int(for_backward)))
+
+
+def _weights(pe, w, bias) -> ssa_cmp_weights_t:
+    return ssa_cmp_weights_t(_ptr(pe), _ptr(w), _ptr(bias))
+
+
+def ssa_compress_forward(params, blocks: Blocks, x, pe, w, bias, x_cmp, workspace: Optional[torch.Tensor] = None) -> None:
+    if workspace is None:
+        workspace = torch.empty(ssa_compress_workspace_bytes(params, blocks, False), dtype=torch.uint8, device="cuda")
+    wt = _weights(pe, w, bias)
+    _check(lib().ssa_compress_forward(C.byref(params), blocks.handle, _ptr(x), C.byref(wt), _ptr(x_cmp), _ptr(workspace),
+                                      workspace.numel(), _stream()), "ssa_compress_forward")
+
+
+def ssa_compress_backward(params, blocks: Blocks, x, pe, w, bias, dx_cmp, dx_accum, dpe, dw, dbias,
+                          workspace: Optional[torch.Tensor] = None) -> None:
+    if workspace is None:
+        workspace = torch.empty(ssa_compress_workspace_bytes(params, blocks, True), dtype=torch.uint8, device="cuda")
+    wt = _weights(pe, w, bias)
+    _check(lib().ssa_compress_backward(C.byref(params), blocks.handle, _ptr(x), C.byref(wt), _ptr(dx_cmp), _ptr(dx_accum),
+                                       _ptr(dpe), _ptr(dw), _ptr(dbias), _ptr(workspace), workspace.numel(), _stream()),
+           "ssa_compress_backward")
+
+
+def ssa_forward_pooled(params, blocks: Blocks, q, k, v, gates, k_cmp, v_cmp, out, lse=None, topk_idx=None, out_branch=None,
+                       workspace: Optional[torch.Tensor] = None) -> None:
+    if workspace is None:
+        workspace = torch.empty(ssa_workspace_bytes(params, blocks, False), dtype=torch.uint8, device="cuda")
+    _check(lib().ssa_forward_pooled(C.byref(params), blocks.handle, _ptr(q), _ptr(k), _ptr(v), _ptr(gates), _ptr(k_cmp),
+                                    _ptr(v_cmp), _ptr(out), _ptr(lse), _ptr(topk_idx), _ptr(out_branch), _ptr(workspace),
+                                    workspace.numel(), _stream()), "ssa_forward_pooled")
+
+
+def ssa_backward_pooled(params, blocks: Blocks, q, k, v, gates, k_cmp, v_cmp, out_branch, lse, topk_idx, dout, dq, dk, dv,
+                        dgates, dk_cmp, dv_cmp, workspace: Optional[torch.Tensor] = None) -> None:
+    if workspace is None:
+        workspace = torch.empty(ssa_workspace_bytes(params, blocks, True), dtype=torch.uint8, device="cuda")
+    _check(lib().ssa_backward_pooled(C.byref(params), blocks.handle, _ptr(q), _ptr(k), _ptr(v), _ptr(gates), _ptr(k_cmp),
+                                     _ptr(v_cmp), _ptr(out_branch), _ptr(lse), _ptr(topk_idx), _ptr(dout), _ptr(dq),
+                                     _ptr(dk), _ptr(dv), _ptr(dgates), _ptr(dk_cmp), _ptr(dv_cmp), _ptr(workspace),
+                                     workspace.numel(), _stream()), "ssa_backward_pooled")
 
 
 def ssa_topk_from_scores(params, blocks: Blocks, scores: torch.Tensor, topk_idx: torch.Tensor) -> None:

@@ -100,3 +100,26 @@ def test_translation_by_one_block_keeps_the_module_output():
         outs.append((f.y, np.sort(np.round(f.x_cmp, 9), axis=0)))
     assert np.allclose(outs[0][0], outs[1][0])
     assert np.allclose(outs[0][1], outs[1][1])
+
+
+def test_attention_oracle_with_external_block_tokens_is_consistent_with_its_own_pooling():
+    """Handing the oracle its own mean-pooled keys/values from outside changes nothing in the forward pass, and the
+    block-level gradients it then returns, pushed through the mean pool by hand, complete dk and dv."""
+    wl = inputs.random_points_workload(21, 8, (70, 40), 4, 2, 8, (2, 4, 4), 2)
+    orc = Oracle(wl.coords, wl.batch_offsets, 8, 2, 4, 4, 2, 4, 2, 8)
+    kc, vc = orc.pool(wl.k), orc.pool(wl.v)
+    f0 = orc.forward(wl.q, wl.k, wl.v, wl.gates)
+    f1 = orc.forward(wl.q, wl.k, wl.v, wl.gates, k_cmp=kc, v_cmp=vc)
+    assert np.array_equal(f0.out, f1.out) and np.array_equal(f0.topk_idx, f1.topk_idx)
+    b0 = orc.backward(wl.q, wl.k, wl.v, wl.gates, wl.dout, f0.topk_idx)
+    b1 = orc.backward(wl.q, wl.k, wl.v, wl.gates, wl.dout, f0.topk_idx, k_cmp=kc, v_cmp=vc)
+    assert b0.dk_cmp is None and b1.dk_cmp.shape == kc.shape
+    cid = orc.blocks.ids["cmp"]
+    cnt = np.bincount(cid).astype(np.float64)
+    assert np.allclose(b1.dk + b1.dk_cmp[cid] / cnt[cid][:, None, None], b0.dk, rtol=1e-12, atol=1e-12)
+    assert np.allclose(b1.dv + b1.dv_cmp[cid] / cnt[cid][:, None, None], b0.dv, rtol=1e-12, atol=1e-12)
+    assert np.array_equal(b1.dq, b0.dq)
+    # different block tokens do change the compression branch
+    f2 = orc.forward(wl.q, wl.k, wl.v, wl.gates, k_cmp=kc * 1.5, v_cmp=vc)
+    assert not np.allclose(f2.out_branch[0], f0.out_branch[0])
+    assert np.array_equal(f2.out_branch[2], f0.out_branch[2])
