@@ -10,7 +10,7 @@
 //
 // Layout: everything is done in the sorted (Morton) token order of the block structure.  The neighbour of a
 // token is found by binary search of its Morton key among the sorted keys the handle keeps.  The convolution is a
-// gather-GEMM on the matrix cores: a wavefront owns 32 tokens (two 16-row MFMA tiles) and all C output channels,
+// gather-GEMM on the matrix cores: a wavefront owns 64 tokens (four 16-row MFMA tiles) and 32 output channels,
 // and for each of the 27 offsets multiplies the gathered neighbour rows (A operand, 16 bytes per lane straight
 // from memory) with the offset's C x C weights (B operand, contraction index contiguous).  The data gradient is
 // the same kernel on mirrored offsets with the weights read the other way round; the weight gradient contracts
@@ -44,31 +44,29 @@ __device__ inline Site decode(uint64_t key, int bits) {
   return Site{(int)(key >> (3 * bits)), (int)compact3(code >> 2), (int)compact3(code >> 1), (int)compact3(code)};
 }
 
-// nbr[pos][o] = sorted position of the token at coords(pos) + offset o in the same item, or -1.
+// nbr[pos][o] = sorted position of the token at coords(pos) + offset o in the same item, or -1.  One thread per
+// (pos, o): a binary search of the neighbour's key inside the item's range of the sorted keys.
 __global__ void c_neighbors(const uint64_t *__restrict__ keys, const int32_t *__restrict__ item_start, int N, int G,
                             int bits, int32_t *__restrict__ nbr) {
-  const int pos = blockIdx.x * blockDim.x + threadIdx.x;
-  if (pos >= N) return;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)N * 27) return;
+  const int pos = (int)(i / 27), o = (int)(i % 27);
   const Site s = decode(keys[pos], bits);
-  const int b = item_start[s.item], e = item_start[s.item + 1];
-  int o = 0;
-  for (int dx = -1; dx <= 1; ++dx)
-    for (int dy = -1; dy <= 1; ++dy)
-      for (int dz = -1; dz <= 1; ++dz, ++o) {
-        const int x = s.x + dx, y = s.y + dy, z = s.z + dz;
-        int found = -1;
-        if ((unsigned)x < (unsigned)G && (unsigned)y < (unsigned)G && (unsigned)z < (unsigned)G) {
-          const uint64_t want = ((uint64_t)s.item << (3 * bits)) |
-                                (uint64_t)((spread3m((uint32_t)x) << 2) | (spread3m((uint32_t)y) << 1) | spread3m((uint32_t)z));
-          int lo = b, hi = e;  // first position in [b, e) whose key is >= want
-          while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (keys[mid] < want) lo = mid + 1; else hi = mid;
-          }
-          if (lo < e && keys[lo] == want) found = lo;
-        }
-        nbr[(size_t)pos * 27 + o] = found;
-      }
+  const int x = s.x + o / 9 - 1, y = s.y + o / 3 % 3 - 1, z = s.z + o % 3 - 1;
+  int found = -1;
+  if ((unsigned)x < (unsigned)G && (unsigned)y < (unsigned)G && (unsigned)z < (unsigned)G) {
+    const uint64_t want = ((uint64_t)s.item << (3 * bits)) |
+                          (uint64_t)((spread3m((uint32_t)x) << 2) | (spread3m((uint32_t)y) << 1) | spread3m((uint32_t)z));
+    int lo = item_start[s.item];
+    const int e = item_start[s.item + 1];
+    int hi = e;  // first position in [lo, e) whose key is >= want
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (keys[mid] < want) lo = mid + 1; else hi = mid;
+    }
+    if (lo < e && keys[lo] == want) found = lo;
+  }
+  nbr[i] = found;
 }
 
 // U[pos] = x[perm[pos]] + PE[place of the token inside its block]   (bf16, sorted order)
@@ -98,51 +96,62 @@ __global__ void c_transpose_w(const bf16_t *__restrict__ w, int C, bf16_t *__res
 // Gather-GEMM: out[pos][n] = bias[n] + sum_o sum_k in[nbr[pos][o']][k] * Bw[o][n][k], o' = o (forward) or 26 - o
 // (data gradient: the token that took `pos` as its neighbour o sits at the mirrored offset).  Bw holds, per offset,
 // a [C][C] matrix with the contraction index contiguous.
-template <int C, bool MIRROR>
+template <int C, bool MIRROR, int MT, int NBW>
 __global__ __launch_bounds__(256) void c_conv(const bf16_t *__restrict__ in, const int32_t *__restrict__ nbr,
                                               const bf16_t *__restrict__ Bw, const bf16_t *__restrict__ bias, int N,
                                               float *__restrict__ out) {
   const int wid = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 15, quad = lane >> 4;
-  const int pos0 = (blockIdx.x * 4 + wid) * 32;
-  if (pos0 >= N) return;
-  f32x4 acc[2][C / 16];
+  const int pos0 = (blockIdx.x * 4 + wid) * 16 * MT;  // a wavefront owns MT tiles of 16 tokens: every weight operand
+  if (pos0 >= N) return;                               // it loads feeds MT matrix instructions
+  const int nb0 = blockIdx.y * NBW;                    // blockIdx.y: which NBW blocks of 16 output channels
+  f32x4 acc[MT][NBW];
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < MT; ++a)
 #pragma unroll
-    for (int nb = 0; nb < C / 16; ++nb) acc[a][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
-  int tok[2];
+    for (int nb = 0; nb < NBW; ++nb) acc[a][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  int tok[MT], nxt[MT];
 #pragma unroll
-  for (int a = 0; a < 2; ++a) tok[a] = pos0 + 16 * a + n;
+  for (int a = 0; a < MT; ++a) {
+    tok[a] = pos0 + 16 * a + n;
+    nxt[a] = tok[a] < N ? nbr[(size_t)tok[a] * 27 + (MIRROR ? 26 : 0)] : -1;
+  }
   for (int o = 0; o < 27; ++o) {
-    const int oo = MIRROR ? 26 - o : o;
-    int src[2];
+    // the neighbour indices of the next offset are requested before this offset's rows are used: the two dependent
+    // loads (index, then row) of consecutive offsets overlap
+    int src[MT];
+    bool some = false;
 #pragma unroll
-    for (int a = 0; a < 2; ++a) src[a] = tok[a] < N ? nbr[(size_t)tok[a] * 27 + oo] : -1;
-    if (!__any(src[0] >= 0 || src[1] >= 0)) continue;
+    for (int a = 0; a < MT; ++a) {
+      src[a] = nxt[a];
+      some = some || src[a] >= 0;
+      if (o + 1 < 27) nxt[a] = tok[a] < N ? nbr[(size_t)tok[a] * 27 + (MIRROR ? 25 - o : o + 1)] : -1;
+    }
+    if (!__any(some)) continue;
     const bf16_t *Bo = Bw + (size_t)o * C * C;
 #pragma unroll
     for (int ks = 0; ks < C / 32; ++ks) {
-      bf16x8 av[2];
+      bf16x8 av[MT];
 #pragma unroll
-      for (int a = 0; a < 2; ++a) av[a] = src[a] >= 0 ? ld8(in + (size_t)src[a] * C + 32 * ks + 8 * quad) : zero8();
+      for (int a = 0; a < MT; ++a) av[a] = src[a] >= 0 ? ld8(in + (size_t)src[a] * C + 32 * ks + 8 * quad) : zero8();
 #pragma unroll
-      for (int nb = 0; nb < C / 16; ++nb) {
-        const bf16x8 bv = ld8(Bo + (size_t)(16 * nb + n) * C + 32 * ks + 8 * quad);
-        acc[0][nb] = mfma16(av[0], bv, acc[0][nb]);
-        acc[1][nb] = mfma16(av[1], bv, acc[1][nb]);
+      for (int nb = 0; nb < NBW; ++nb) {
+        const bf16x8 bv = ld8(Bo + (size_t)(16 * (nb0 + nb) + n) * C + 32 * ks + 8 * quad);
+#pragma unroll
+        for (int a = 0; a < MT; ++a) acc[a][nb] = mfma16(av[a], bv, acc[a][nb]);
       }
     }
   }
-  // C layout: lane holds output channel 16*nb + n of tokens pos0 + 16*a + 4*quad + i
+  // C layout: lane holds output channel 16*(nb0 + nb) + n of tokens pos0 + 16*a + 4*quad + i
 #pragma unroll
-  for (int nb = 0; nb < C / 16; ++nb) {
-    const float bs = bias ? bf16_to_f32(bias[16 * nb + n]) : 0.f;
+  for (int nb = 0; nb < NBW; ++nb) {
+    const int ch = 16 * (nb0 + nb) + n;
+    const float bs = bias ? bf16_to_f32(bias[ch]) : 0.f;
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < MT; ++a)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int t = pos0 + 16 * a + 4 * quad + i;
-        if (t < N) out[(size_t)t * C + 16 * nb + n] = acc[a][nb][i] + bs;
+        if (t < N) out[(size_t)t * C + ch] = acc[a][nb][i] + bs;
       }
   }
 }
@@ -173,13 +182,17 @@ __global__ void c_expand(const float *__restrict__ dxc, const int32_t *__restric
   *reinterpret_cast<bf16x8 *>(dY + (size_t)pos * C + c0) = r;
 }
 
-// dbias[f] = sum over blocks of dXc[c][f]  (the pool's 1/count and the block's count cancel); rows added in order.
-__global__ void c_dbias(const float *__restrict__ dxc, int Nc, int C, float *__restrict__ dbias) {
+// dbias[f] = sum over blocks of dXc[c][f]  (the pool's 1/count and the block's count cancel): partial sums over
+// DBIAS_PARTS row ranges, added in order by c_sum_parts.
+constexpr int DBIAS_PARTS = 32;
+__global__ void c_dbias_partial(const float *__restrict__ dxc, int Nc, int C, float *__restrict__ part) {
   const int f = blockIdx.x * blockDim.x + threadIdx.x;
   if (f >= C) return;
+  const int per = (Nc + DBIAS_PARTS - 1) / DBIAS_PARTS;
+  const int b = min(Nc, (int)blockIdx.y * per), e = min(Nc, b + per);
   float s = 0.f;
-  for (int c = 0; c < Nc; ++c) s += dxc[(size_t)c * C + f];
-  dbias[f] = s;
+  for (int c = b; c < e; ++c) s += dxc[(size_t)c * C + f];
+  part[(size_t)blockIdx.y * C + f] = s;
 }
 
 // dx[perm[pos]] += dU[pos]   (caller order, parameter dtype)
@@ -214,13 +227,17 @@ __global__ void c_dpe_partial(const float *__restrict__ dU, const uint64_t *__re
   for (int i = threadIdx.x; i < rows * C; i += blockDim.x) part[(size_t)blockIdx.x * rows * C + i] = tbl[i];
 }
 
-// out[i] = sum over parts s = 0 .. n_parts-1 of part[s][i], in order
-__global__ void c_sum_parts(const float *__restrict__ part, int n_parts, size_t len, float *__restrict__ out) {
+// Ordered sum of partial results: out[g][i] = sum of part[g*group + j][i], j = 0 .. group-1 (parts past n_parts are
+// skipped).  One launch with group = n_parts gives the total; two launches (group, then the group results) keep
+// the work parallel when there are many parts.  The order of the additions is fixed either way.
+__global__ void c_sum_parts(const float *__restrict__ part, int n_parts, int n_groups, size_t len, float *__restrict__ out) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= len) return;
+  const int group = (n_parts + n_groups - 1) / n_groups;
+  const int g = blockIdx.y, b = g * group, e = min(n_parts, b + group);
   float s = 0.f;
-  for (int k = 0; k < n_parts; ++k) s += part[(size_t)k * len + i];
-  out[i] = s;
+  for (int k = b; k < e; ++k) s += part[(size_t)k * len + i];
+  out[(size_t)g * len + i] = s;
 }
 
 // Weight gradient: dW[o][ci][co] = sum_pos U[nbr[pos][o]][ci] * dY[pos][co], a contraction over tokens.  A workgroup
@@ -281,8 +298,10 @@ __global__ __launch_bounds__(256) void c_dw(const bf16_t *__restrict__ U, const 
         dst[(size_t)(ci0 + 16 * (wid + 4 * a) + 4 * quad + i) * C + co0 + 16 * nb + n] = acc[a][nb][i];
 }
 
+constexpr int PE_GROUPS = 32;  // first-level groups of the ordered dPE sum
+
 struct ModPlan {
-  size_t nbr, u, wt, y, dy, du, pw, ppe, total;
+  size_t nbr, u, wt, y, dy, du, pw, ppe, ppe2, pb, total;
   int dw_chunks, dw_chunk, pe_chunks, pe_chunk;
 };
 
@@ -303,11 +322,13 @@ ModPlan mod_plan(int N, int C, int m, bool backward) {
     p.dw_chunk = ((N + p.dw_chunks - 1) / p.dw_chunks + 31) / 32 * 32;
     if (p.dw_chunk < 32) p.dw_chunk = 32;
     p.pw = take((size_t)p.dw_chunks * 27 * C * C * 4);
-    p.pe_chunks = N > 0 ? (N + 255) / 256 : 1;
-    if (p.pe_chunks > 256) p.pe_chunks = 256;
+    p.pe_chunks = N > 0 ? (N + 63) / 64 : 1;
+    if (p.pe_chunks > 1024) p.pe_chunks = 1024;
     p.pe_chunk = (N + p.pe_chunks - 1) / p.pe_chunks;
     if (p.pe_chunk < 1) p.pe_chunk = 1;
     p.ppe = take((size_t)p.pe_chunks * m * m * m * C * 4);
+    p.ppe2 = take((size_t)PE_GROUPS * m * m * m * C * 4);
+    p.pb = take((size_t)DBIAS_PARTS * C * 4);
   }
   p.total = off;
   return p;
@@ -329,12 +350,13 @@ int check(const ssa_params_t *p, const ssa_blocks_t *b, int *C) {
 template <bool MIRROR>
 void launch_conv(int C, const bf16_t *in, const int32_t *nbr, const bf16_t *Bw, const bf16_t *bias, int N, float *out,
                  hipStream_t s) {
-  const unsigned grid = (unsigned)((N + 127) / 128);
+  // 64 tokens per wavefront and up to 128 output channels per workgroup row (blockIdx.y picks the channel range)
+  const dim3 grid((unsigned)((N + 255) / 256), (unsigned)(C > 128 ? C / 128 : 1));
   switch (C) {
-    case 32: c_conv<32, MIRROR><<<grid, 256, 0, s>>>(in, nbr, Bw, bias, N, out); break;
-    case 64: c_conv<64, MIRROR><<<grid, 256, 0, s>>>(in, nbr, Bw, bias, N, out); break;
-    case 128: c_conv<128, MIRROR><<<grid, 256, 0, s>>>(in, nbr, Bw, bias, N, out); break;
-    default: c_conv<256, MIRROR><<<grid, 256, 0, s>>>(in, nbr, Bw, bias, N, out); break;
+    case 32: c_conv<32, MIRROR, 4, 2><<<grid, 256, 0, s>>>(in, nbr, Bw, bias, N, out); break;
+    case 64: c_conv<64, MIRROR, 4, 4><<<grid, 256, 0, s>>>(in, nbr, Bw, bias, N, out); break;
+    case 128: c_conv<128, MIRROR, 4, 8><<<grid, 256, 0, s>>>(in, nbr, Bw, bias, N, out); break;
+    default: c_conv<256, MIRROR, 4, 8><<<grid, 256, 0, s>>>(in, nbr, Bw, bias, N, out); break;
   }
 }
 
@@ -362,7 +384,7 @@ extern "C" int ssa_compress_forward(const ssa_params_t *p, const ssa_blocks_t *b
   bf16_t *U = (bf16_t *)(ws + pl.u), *Wt = (bf16_t *)(ws + pl.wt);
   float *Y = (float *)(ws + pl.y);
   ProfScope ps(PROF_CMP_MODULE, s);
-  c_neighbors<<<(N + 255) / 256, 256, 0, s>>>(b->sorted_keys, b->item_start, N, b->G, b->bits, nbr);
+  c_neighbors<<<(unsigned)(((size_t)N * 27 + 255) / 256), 256, 0, s>>>(b->sorted_keys, b->item_start, N, b->G, b->bits, nbr);
   const size_t items = (size_t)N * (C / 8);
   c_add_pe<<<(unsigned)((items + 255) / 256), 256, 0, s>>>((const bf16_t *)x, (const bf16_t *)wts->pe, b->perm, b->sorted_keys, N,
                                                              C, b->bits, b->m_cmp, U);
@@ -388,19 +410,23 @@ extern "C" int ssa_compress_backward(const ssa_params_t *p, const ssa_blocks_t *
   int32_t *nbr = (int32_t *)(ws + pl.nbr);
   bf16_t *U = (bf16_t *)(ws + pl.u), *dY = (bf16_t *)(ws + pl.dy);
   float *dU = (float *)(ws + pl.du), *pw = (float *)(ws + pl.pw), *ppe = (float *)(ws + pl.ppe);
+  float *ppe2 = (float *)(ws + pl.ppe2), *pb = (float *)(ws + pl.pb);
   ProfScope ps(PROF_CMP_MODULE_BWD, s);
-  c_neighbors<<<(N + 255) / 256, 256, 0, s>>>(b->sorted_keys, b->item_start, N, b->G, b->bits, nbr);
+  c_neighbors<<<(unsigned)(((size_t)N * 27 + 255) / 256), 256, 0, s>>>(b->sorted_keys, b->item_start, N, b->G, b->bits, nbr);
   const size_t items = (size_t)N * (C / 8);
   const unsigned igrid = (unsigned)((items + 255) / 256);
   c_add_pe<<<igrid, 256, 0, s>>>((const bf16_t *)x, (const bf16_t *)wts->pe, b->perm, b->sorted_keys, N, C, b->bits, m, U);
   c_expand<<<igrid, 256, 0, s>>>(dx_cmp, b->tok_cmp, b->cmp_start, N, C, dY);
-  c_dbias<<<(C + 63) / 64, 64, 0, s>>>(dx_cmp, b->Nc, C, dbias);
+  c_dbias_partial<<<dim3((C + 63) / 64, DBIAS_PARTS), 64, 0, s>>>(dx_cmp, b->Nc, C, pb);
+  c_sum_parts<<<(C + 255) / 256, 256, 0, s>>>(pb, DBIAS_PARTS, 1, (size_t)C, dbias);
   // data gradient: dU[pos] = sum_o dY[token that took pos as neighbour o] * w[o]^T; w as given has c_out contiguous
   launch_conv<true>(C, dY, nbr, (const bf16_t *)wts->w, nullptr, N, dU, s);
   c_dx_accum<<<igrid, 256, 0, s>>>(dU, b->perm, N, C, (bf16_t *)dx_accum);
   const int rows = m * m * m;
-  c_dpe_partial<<<pl.pe_chunks, 256, (size_t)rows * C * 4, s>>>(dU, b->sorted_keys, N, C, b->bits, m, pl.pe_chunk, ppe);
-  c_sum_parts<<<(unsigned)(((size_t)rows * C + 255) / 256), 256, 0, s>>>(ppe, pl.pe_chunks, (size_t)rows * C, dpe);
+  const size_t plen = (size_t)rows * C;
+  c_dpe_partial<<<pl.pe_chunks, 128, plen * 4, s>>>(dU, b->sorted_keys, N, C, b->bits, m, pl.pe_chunk, ppe);
+  c_sum_parts<<<dim3((unsigned)((plen + 255) / 256), PE_GROUPS), 256, 0, s>>>(ppe, pl.pe_chunks, PE_GROUPS, plen, ppe2);
+  c_sum_parts<<<(unsigned)((plen + 255) / 256), 256, 0, s>>>(ppe2, PE_GROUPS, 1, plen, dpe);
   const int CT = C < 128 ? C : 128;
   const dim3 g(27, pl.dw_chunks, (C / CT) * (C / CT));
   switch (CT) {
@@ -409,6 +435,6 @@ extern "C" int ssa_compress_backward(const ssa_params_t *p, const ssa_blocks_t *
     default: c_dw<128><<<g, 256, 0, s>>>(U, dY, nbr, N, C, pl.dw_chunk, pw); break;
   }
   const size_t wlen = (size_t)27 * C * C;
-  c_sum_parts<<<(unsigned)((wlen + 255) / 256), 256, 0, s>>>(pw, pl.dw_chunks, wlen, dw);
+  c_sum_parts<<<(unsigned)((wlen + 255) / 256), 256, 0, s>>>(pw, pl.dw_chunks, 1, wlen, dw);
   return hipGetLastError() == hipSuccess ? SSA_OK : SSA_ERR_HIP;
 }
