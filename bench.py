@@ -119,6 +119,85 @@ def dense_sweep(args):
         print(json.dumps(line), flush=True)
 
 
+def cmp_module_bench(args):
+    """One JSON line: the learned compression module (eq. (5)) at the benchmark workload, alone and inside a full
+    training step (two modules forward, attention with their block-level tokens, everything backward)."""
+    import numpy as np
+    import torch
+    from paper_2505_17412_amd import inputs, ssa
+    from tests import util
+
+    torch.cuda.set_device(0)
+    wl = inputs.make_workload(args.workload)
+    n, hq, hkv, d, T = wl.n_tokens, wl.n_heads_q, wl.n_heads_kv, wl.head_dim, wl.topk
+    c, m3 = hkv * d, wl.m_cmp ** 3
+    p, blk = util.build_blocks_gpu(wl)
+    nc = blk.counts()[0]
+    q, k, v, g, do = (util.to_dev(a, wl.dtype) for a in (wl.q, wl.k, wl.v, wl.gates, wl.dout))
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    rand = lambda *shape: torch.randn(shape, generator=gen, device="cuda")
+    wts = [((0.5 * rand(m3, c)).bfloat16(), (rand(27, c, c) / (9.0 * c) ** 0.5).bfloat16(), (0.1 * rand(c)).bfloat16())
+           for _ in range(2)]
+    kc, vc = (torch.empty((nc, hkv, d), dtype=torch.bfloat16, device="cuda") for _ in range(2))
+    out = torch.empty_like(q)
+    ob = torch.empty((3,) + tuple(q.shape), dtype=q.dtype, device="cuda")
+    lse = torch.empty((3, n, hq), dtype=torch.float32, device="cuda")
+    idx = torch.empty((n, hkv, T), dtype=torch.int32, device="cuda")
+    dq, dk, dv, dg = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v), torch.empty_like(g)
+    dkc, dvc = (torch.empty((nc, hkv, d), dtype=torch.float32, device="cuda") for _ in range(2))
+    grads = [(torch.empty((m3, c), device="cuda"), torch.empty((27, c, c), device="cuda"), torch.empty((c,), device="cuda"))
+             for _ in range(2)]
+    wsf = torch.empty(ssa.ssa_workspace_bytes(p, blk, False), dtype=torch.uint8, device="cuda")
+    wsb = torch.empty(ssa.ssa_workspace_bytes(p, blk, True), dtype=torch.uint8, device="cuda")
+    wmf = torch.empty(ssa.ssa_compress_workspace_bytes(p, blk, False), dtype=torch.uint8, device="cuda")
+    wmb = torch.empty(ssa.ssa_compress_workspace_bytes(p, blk, True), dtype=torch.uint8, device="cuda")
+
+    def step():
+        ssa.ssa_compress_forward(p, blk, k, *wts[0], kc, wmf)
+        ssa.ssa_compress_forward(p, blk, v, *wts[1], vc, wmf)
+        ssa.ssa_forward_pooled(p, blk, q, k, v, g, kc, vc, out, lse, idx, ob, wsf)
+        ssa.ssa_backward_pooled(p, blk, q, k, v, g, kc, vc, ob, lse, idx, do, dq, dk, dv, dg, dkc, dvc, wsb)
+        ssa.ssa_compress_backward(p, blk, k, *wts[0], dkc, dk, *grads[0], wmb)
+        ssa.ssa_compress_backward(p, blk, v, *wts[1], dvc, dv, *grads[1], wmb)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    ssa.ssa_profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = {nm: tot / cnt for nm, (tot, cnt) in ssa.ssa_profile_get().items()}
+    ssa.ssa_profile_enable(False)
+    # (token, offset) pairs with an active neighbour, counted from the coordinates (single item)
+    co = wl.coords.astype(np.int64)
+    code = (co[:, 0] * 4096 + co[:, 1]) * 4096 + co[:, 2]
+    srt = np.sort(code)
+    pairs = 0
+    for dx in (-1, 0, 1):
+        for dy in (-1, 0, 1):
+            for dz in (-1, 0, 1):
+                cc = co + np.array([dx, dy, dz])
+                ok = np.all((cc >= 0) & (cc < wl.grid), axis=1)
+                want = (cc[:, 0] * 4096 + cc[:, 1]) * 4096 + cc[:, 2]
+                j = np.clip(np.searchsorted(srt, want), 0, n - 1)
+                pairs += int(np.sum(ok & (srt[j] == want)))
+    flop_fwd = 2.0 * c * c * pairs
+    line = {"bench": "learned_compression_module", "workload": args.workload, "n_tokens": n, "channels": c,
+            "neighbour_pairs": pairs, "module_fwd_ms_per_tensor": round(prof["cmp_module_fwd"], 4),
+            "module_bwd_ms_per_tensor": round(prof["cmp_module_bwd"], 4),
+            "module_fwd_algorithmic_tflops": round(flop_fwd / (prof["cmp_module_fwd"] * 1e-3) / 1e12, 2),
+            "module_bwd_algorithmic_tflops": round(2 * flop_fwd / (prof["cmp_module_bwd"] * 1e-3) / 1e12, 2),
+            "step_with_modules_ms": round(ms, 4), "tokens_per_s_with_modules": round(n / (ms * 1e-3), 1),
+            "steps": args.steps, "warmup": args.warmup}
+    print(json.dumps(line), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -129,6 +208,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, to scale rocprofv3 byte counters)")
+    ap.add_argument("--cmp-module", action="store_true",
+                    help="instead of the benchmark line: the learned compression module alone and inside a training step")
     ap.add_argument("--dense-sweep", action="store_true",
                     help="instead of the benchmark line: sparse path against dense attention over 2.6k-124k tokens")
     args = ap.parse_args()
@@ -137,6 +218,9 @@ def main():
         sys.exit(2)
     if args.dense_sweep:
         dense_sweep(args)
+        return
+    if args.cmp_module:
+        cmp_module_bench(args)
         return
 
     import numpy as np
