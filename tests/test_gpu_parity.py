@@ -244,3 +244,50 @@ def test_empty_call_and_empty_batch_item():
     blk.destroy()
     wl = inputs.random_points_workload(33, 16, (300, 0, 211), 4, 2, 32, (2, 4, 4), 3, "f32")
     full_parity(wl)
+
+
+def test_forward_backward_replay_from_a_hip_graph():
+    """The training step records into a HIP graph (no allocation, no synchronisation, no memset nodes inside the
+    library calls) and every replay, with eager work and synchronisations in between, reproduces the eager result
+    bit for bit."""
+    import torch
+    from paper_2505_17412_amd import ssa
+    wl = inputs.random_points_workload(23, 32, (1300, 800), 16, 2, 64, (4, 8, 8), 6, "bf16")
+    n, hq, hkv, d, T = wl.n_tokens, wl.n_heads_q, wl.n_heads_kv, wl.head_dim, wl.topk
+    p, blk = util.build_blocks_gpu(wl)
+    q, k, v, g, do = (util.to_dev(a, "bf16") for a in (wl.q, wl.k, wl.v, wl.gates, wl.dout))
+    out = torch.empty_like(q)
+    ob = torch.empty((3,) + tuple(q.shape), dtype=q.dtype, device="cuda")
+    lse = torch.empty((3, n, hq), dtype=torch.float32, device="cuda")
+    idx = torch.empty((n, hkv, T), dtype=torch.int32, device="cuda")
+    dq, dk, dv, dg = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v), torch.empty_like(g)
+    wsf = torch.empty(ssa.ssa_workspace_bytes(p, blk, False), dtype=torch.uint8, device="cuda")
+    wsb = torch.empty(ssa.ssa_workspace_bytes(p, blk, True), dtype=torch.uint8, device="cuda")
+
+    def step():
+        ssa.ssa_forward(p, blk, q, k, v, g, out, lse, idx, ob, wsf)
+        ssa.ssa_backward(p, blk, q, k, v, g, ob, lse, idx, do, dq, dk, dv, dg, wsb)
+
+    step()
+    torch.cuda.synchronize()
+    eager = [t.clone() for t in (out, lse, idx, dq, dk, dv, dg)]
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                      # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    for r in range(3):
+        for t in (out, lse, dq, dk, dv, dg):
+            t.fill_(float("nan"))   # eager work between the replays: the graph must rewrite every output
+        idx.fill_(-5)
+        wsf.random_(0, 255)
+        wsb.random_(0, 255)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, got, want in zip(("out", "lse", "idx", "dq", "dk", "dv", "dgates"), (out, lse, idx, dq, dk, dv, dg), eager):
+            assert torch.equal(got, want), (r, name)
