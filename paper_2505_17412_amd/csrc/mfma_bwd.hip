@@ -156,7 +156,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
   bf16_t *stage0 = (bf16_t *)smem;
   int *ints = (int *)(stage0 + 2 * L::ELEMS);
   const int quad = threadIdx.x >> 4 & 3;
-  const int hs = a.v.hs, T = a.v.T, N = a.v.N, Ns = a.v.Ns, TW = NW * CB * 16 / hs;
+  const int hs = a.v.hs, T = a.v.T, N = a.v.N, TW = NW * CB * 16 / hs;
   const TileMap tm = xcd_tile_map((N + TW - 1) / TW, a.v.Hkv);
   if (!tm.valid) return;
   const int g = tm.g, wg_pos0 = tm.tile * TW;

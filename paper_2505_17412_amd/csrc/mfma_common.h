@@ -68,8 +68,8 @@ __device__ inline int tile_key_row(int kb, int a) {
 
 // Device arrays of the block structure and the sorted K,V copies the kernels read.
 struct MfmaView {
-  const int32_t *perm, *tok_item, *tok_cmp, *tok_win, *cmp_start, *slc_start, *win_start, *slc_child_start, *cmp_slc,
-      *cmp_batch, *slc_batch, *item_start;
+  const int32_t *perm, *tok_item, *tok_win, *cmp_start, *slc_start, *win_start, *cmp_slc, *cmp_batch, *slc_batch,
+      *item_start;
   int N, Nc, Ns, Hq, Hkv, hs, T, s_max;
   float scale, sl2;  // softmax scale, scale * log2(e)
   // sorted copies (bf16), row-major [rows][Hkv][D]: token K, V and pooled K, V

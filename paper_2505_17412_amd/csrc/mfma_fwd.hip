@@ -321,8 +321,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
   using L = StageLayout<D, 2>;
   bf16_t *stage0 = (bf16_t *)smem;
   int *ints = (int *)(stage0 + 2 * L::ELEMS);
-  const int lane = threadIdx.x & 63;
-  const int hs = a.v.hs, T = a.v.T, Ns = a.v.Ns, TW = NW * CB * 16 / hs;
+  const int hs = a.v.hs, T = a.v.T, TW = NW * CB * 16 / hs;
   const TileMap tm = xcd_tile_map((a.v.N + TW - 1) / TW, a.v.Hkv);
   if (!tm.valid) return;
   const int g = tm.g, wg_pos0 = tm.tile * TW;
@@ -330,7 +329,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
   int *ub = Irows + TW * T;              // union list: block ids
   int *us = ub + TW * T, *ue = us + TW * T;
   uint32_t *bits = (uint32_t *)(ue + TW * T);
-  const int words = (Ns + 31) >> 5;
   QRows<D, CB> q;
   load_rows<D, CB>(a.Q, a.v, wg_pos0, g, q);
   build_union(a.v, a.idx, wg_pos0, g, TW, Irows, ub, us, ue, bits, &ints[0]);

@@ -25,7 +25,6 @@ __global__ void m_prep(const bf16_t *__restrict__ K, const bf16_t *__restrict__ 
   const int b = cmp_start[c], e = cmp_start[c + 1];
   const float inv = 1.0f / (float)(e - b);
   for (int f = threadIdx.x; f < row; f += blockDim.x) {
-    const int g = f / D, dim = f % D;
     float sk = 0.f, sv = 0.f;
     for (int pos = b; pos < e; ++pos) {
       const size_t src = (size_t)perm[pos] * row + f;
@@ -62,9 +61,9 @@ FwdPlan fwd_plan(const ssa_ctx &c) {
 MfmaView make_view(const ssa_ctx &c) {
   const ssa_blocks *b = c.blk;
   MfmaView v{};
-  v.perm = b->perm; v.tok_item = b->tok_item; v.tok_cmp = b->tok_cmp; v.tok_win = b->tok_win;
+  v.perm = b->perm; v.tok_item = b->tok_item; v.tok_win = b->tok_win;
   v.cmp_start = b->cmp_start; v.slc_start = b->slc_start; v.win_start = b->win_start;
-  v.slc_child_start = b->slc_child_start; v.cmp_slc = b->cmp_slc; v.cmp_batch = b->cmp_batch;
+  v.cmp_slc = b->cmp_slc; v.cmp_batch = b->cmp_batch;
   v.slc_batch = b->slc_batch; v.item_start = b->item_start;
   v.N = c.N; v.Nc = b->Nc; v.Ns = b->Ns; v.Hq = c.Hq; v.Hkv = c.Hkv; v.hs = c.hs; v.T = c.T; v.s_max = b->s_max;
   v.scale = c.scale; v.sl2 = c.scale * LOG2E;
