@@ -205,6 +205,23 @@ int ssa_backward_pooled(const ssa_params_t *params, const ssa_blocks_t *blocks, 
                         size_t workspace_bytes, void *stream);
 
 /*
+ * Gate predictor (text after eq. (4): the gating score of each module is a linear layer followed by a sigmoid on the
+ * input features): gates = sigmoid(x w + bias), one linear layer d_model -> 3*Hq.
+ *   x dev [N,d_model]; w dev [d_model, 3*Hq]; bias dev [3*Hq]; gates dev [N,Hq,3] (order cmp, slc, win), the
+ *   tensor ssa_forward takes.  Backward: dgates dev [N,Hq,3] (what ssa_backward writes); the gradient w.r.t. x is
+ *   ADDED to dx_accum dev [N,d_model] (in/out); dw dev float [d_model, 3*Hq] and dbias dev float [3*Hq] are
+ *   overwritten.  Only n_tokens, n_heads_q and dtype of params are read.
+ * bf16 only; 3*Hq <= 64; d_model a multiple of 128, at most 16384; otherwise UNSUPPORTED.  Asynchronous on `stream`,
+ * allocates nothing.  Errors: NULL, BAD_SHAPE, BAD_HEADS, UNSUPPORTED, WORKSPACE, HIP.
+ */
+size_t ssa_gate_workspace_bytes(const ssa_params_t *params, int32_t d_model, int for_backward);
+int ssa_gate_forward(const ssa_params_t *params, int32_t d_model, const void *x, const void *w, const void *bias,
+                     void *gates, void *workspace, size_t workspace_bytes, void *stream);
+int ssa_gate_backward(const ssa_params_t *params, int32_t d_model, const void *x, const void *w, const void *gates,
+                      const void *dgates, void *dx_accum, float *dw, float *dbias, void *workspace,
+                      size_t workspace_bytes, void *stream);
+
+/*
  * Measurement hook (not an operation of the paper; for benchmarks that need the duration of single kernels).
  * While enabled, every kernel the library launches is bracketed by a HIP event pair recorded on the launch
  * stream.  ssa_profile_enable(on) clears the totals; ssa_profile_get(i, ...) waits for the recorded events and

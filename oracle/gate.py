@@ -16,10 +16,11 @@ def gate_forward(x, w, b):
     return 1.0 / (1.0 + np.exp(-z))
 
 
-def gate_backward(x, w, b, dgates):
-    """Gradients of sum(dgates * gates): (dx [N, Dm], dw [Dm, J], db [J])."""
+def gate_backward(x, w, gates, dgates):
+    """Gradients of sum(dgates * gates) given the forward result ``gates`` (the backward entry point takes the
+    gates tensor, it does not recompute it): (dx [N, Dm], dw [Dm, J], db [J])."""
     x = np.asarray(x, np.float64)
     w = np.asarray(w, np.float64)
-    g = gate_forward(x, w, b)
+    g = np.asarray(gates, np.float64)
     dz = np.asarray(dgates, np.float64) * g * (1.0 - g)
     return dz @ w.T, x.T @ dz, dz.sum(axis=0)

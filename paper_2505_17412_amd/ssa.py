@@ -22,7 +22,7 @@ EXPORTED_SYMBOLS = (
     "ssa_blocks_destroy", "ssa_workspace_bytes", "ssa_forward", "ssa_backward", "ssa_topk_from_scores",
     "ssa_error_string", "ssa_profile_enable", "ssa_profile_num_kernels", "ssa_profile_get",
     "ssa_compress_workspace_bytes", "ssa_compress_forward", "ssa_compress_backward", "ssa_forward_pooled",
-    "ssa_backward_pooled",
+    "ssa_backward_pooled", "ssa_gate_workspace_bytes", "ssa_gate_forward", "ssa_gate_backward",
 )
 
 
@@ -67,6 +67,10 @@ def lib() -> C.CDLL:
         L.ssa_compress_forward.argtypes = [C.POINTER(ssa_params_t), vp, vp, C.POINTER(ssa_cmp_weights_t), vp, vp, C.c_size_t, vp]
         L.ssa_compress_backward.argtypes = [C.POINTER(ssa_params_t), vp, vp, C.POINTER(ssa_cmp_weights_t)] + [vp] * 5 + \
             [vp, C.c_size_t, vp]
+        L.ssa_gate_workspace_bytes.argtypes = [C.POINTER(ssa_params_t), C.c_int32, C.c_int]
+        L.ssa_gate_workspace_bytes.restype = C.c_size_t
+        L.ssa_gate_forward.argtypes = [C.POINTER(ssa_params_t), C.c_int32] + [vp] * 4 + [vp, C.c_size_t, vp]
+        L.ssa_gate_backward.argtypes = [C.POINTER(ssa_params_t), C.c_int32] + [vp] * 7 + [vp, C.c_size_t, vp]
         L.ssa_forward_pooled.argtypes = [C.POINTER(ssa_params_t), vp] + [vp] * 10 + [vp, C.c_size_t, vp]
         L.ssa_backward_pooled.argtypes = [C.POINTER(ssa_params_t), vp] + [vp] * 16 + [vp, C.c_size_t, vp]
         L.ssa_profile_enable.argtypes = [C.c_int]
@@ -217,6 +221,25 @@ def ssa_backward_pooled(params, blocks: Blocks, q, k, v, gates, k_cmp, v_cmp, ou
                                      _ptr(v_cmp), _ptr(out_branch), _ptr(lse), _ptr(topk_idx), _ptr(dout), _ptr(dq),
                                      _ptr(dk), _ptr(dv), _ptr(dgates), _ptr(dk_cmp), _ptr(dv_cmp), _ptr(workspace),
                                      workspace.numel(), _stream()), "ssa_backward_pooled")
+
+
+def ssa_gate_workspace_bytes(params: ssa_params_t, d_model: int, for_backward: bool) -> int:
+    return int(lib().ssa_gate_workspace_bytes(C.byref(params), int(d_model), int(for_backward)))
+
+
+def ssa_gate_forward(params, d_model: int, x, w, bias, gates, workspace: Optional[torch.Tensor] = None) -> None:
+    if workspace is None:
+        workspace = torch.empty(ssa_gate_workspace_bytes(params, d_model, False), dtype=torch.uint8, device="cuda")
+    _check(lib().ssa_gate_forward(C.byref(params), int(d_model), _ptr(x), _ptr(w), _ptr(bias), _ptr(gates), _ptr(workspace),
+                                  workspace.numel(), _stream()), "ssa_gate_forward")
+
+
+def ssa_gate_backward(params, d_model: int, x, w, gates, dgates, dx_accum, dw, dbias,
+                      workspace: Optional[torch.Tensor] = None) -> None:
+    if workspace is None:
+        workspace = torch.empty(ssa_gate_workspace_bytes(params, d_model, True), dtype=torch.uint8, device="cuda")
+    _check(lib().ssa_gate_backward(C.byref(params), int(d_model), _ptr(x), _ptr(w), _ptr(gates), _ptr(dgates), _ptr(dx_accum),
+                                   _ptr(dw), _ptr(dbias), _ptr(workspace), workspace.numel(), _stream()), "ssa_gate_backward")
 
 
 def ssa_topk_from_scores(params, blocks: Blocks, scores: torch.Tensor, topk_idx: torch.Tensor) -> None:
