@@ -198,6 +198,52 @@ def cmp_module_bench(args):
     print(json.dumps(line), flush=True)
 
 
+def gate_bench(args):
+    """One JSON line: the gate predictor (sigmoid of a linear layer d_model -> 3*Hq) at the benchmark workload's token
+    count, against the HBM roofline (it streams x once forward; x once and dx twice backward)."""
+    import torch
+    from paper_2505_17412_amd import inputs, ssa
+
+    torch.cuda.set_device(0)
+    wl = inputs.make_workload(args.workload, with_tensors=False)
+    n, hq = wl.n_tokens, wl.n_heads_q
+    dm, j = hq * wl.head_dim, 3 * hq
+    p = ssa.make_params(n, 1, wl.grid, wl.m_cmp, wl.m_slc, wl.m_win, wl.topk, hq, wl.n_heads_kv, wl.head_dim, "bf16")
+    gen = torch.Generator(device="cuda").manual_seed(11)
+    x = torch.randn((n, dm), generator=gen, device="cuda").bfloat16()
+    w = (torch.randn((dm, j), generator=gen, device="cuda") / dm ** 0.5).bfloat16()
+    b = torch.randn((j,), generator=gen, device="cuda").bfloat16()
+    dg = torch.randn((n, hq, 3), generator=gen, device="cuda").bfloat16()
+    gates = torch.empty((n, hq, 3), dtype=torch.bfloat16, device="cuda")
+    dx = torch.zeros_like(x)
+    dw = torch.empty((dm, j), device="cuda")
+    db = torch.empty((j,), device="cuda")
+    wsf = torch.empty(ssa.ssa_gate_workspace_bytes(p, dm, False), dtype=torch.uint8, device="cuda")
+    wsb = torch.empty(ssa.ssa_gate_workspace_bytes(p, dm, True), dtype=torch.uint8, device="cuda")
+
+    def step():
+        ssa.ssa_gate_forward(p, dm, x, w, b, gates, wsf)
+        ssa.ssa_gate_backward(p, dm, x, w, gates, dg, dx, dw, db, wsb)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ssa.ssa_profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = {nm: tot / cnt for nm, (tot, cnt) in ssa.ssa_profile_get().items()}
+    ssa.ssa_profile_enable(False)
+    fwd_bytes = n * dm * 2 + n * j * 2
+    bwd_bytes = n * dm * 2 + 2 * n * dm * 2 + 2 * n * j * 2
+    line = {"bench": "gate_predictor", "workload": args.workload, "n_tokens": n, "d_model": dm, "gates_per_token": j,
+            "fwd_ms": round(prof["gate_fwd"], 4), "bwd_ms": round(prof["gate_bwd"], 4),
+            "fwd_algorithmic_gbps": round(fwd_bytes / (prof["gate_fwd"] * 1e-3) / 1e9, 1),
+            "bwd_algorithmic_gbps": round(bwd_bytes / (prof["gate_bwd"] * 1e-3) / 1e9, 1),
+            "hbm_peak_gbps": HBM_PEAK_GBS, "steps": args.steps, "warmup": args.warmup}
+    print(json.dumps(line), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -208,6 +254,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, to scale rocprofv3 byte counters)")
+    ap.add_argument("--gate", action="store_true", help="instead of the benchmark line: the gate predictor against the HBM roofline")
     ap.add_argument("--cmp-module", action="store_true",
                     help="instead of the benchmark line: the learned compression module alone and inside a training step")
     ap.add_argument("--dense-sweep", action="store_true",
@@ -221,6 +268,9 @@ def main():
         return
     if args.cmp_module:
         cmp_module_bench(args)
+        return
+    if args.gate:
+        gate_bench(args)
         return
 
     import numpy as np

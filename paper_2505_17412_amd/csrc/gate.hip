@@ -8,7 +8,8 @@
 //             small transposed copy), sigmoid in the epilogue;
 //   backward  dz = dgates * g * (1 - g) (bf16, padded to 64 columns);  dx += dz W^T with dims as MFMA rows, so a
 //             lane holds 4 consecutive dims of one token;  dW = x^T dz contracts over tokens: 32-token tiles of x and
-//             dz go through LDS row-major and both operands are transposing LDS reads;  db = column sums of dz.
+//             dz go through LDS row-major and both operands are transposing LDS reads;  db = column sums of dz
+//             (one more matrix instruction with an all-ones operand in the same kernel).
 // No floating point atomics: per-chunk partial sums are added in a fixed order.
 #include "mfma_common.h"
 #include "mfma_qc.h"
@@ -31,110 +32,158 @@ __global__ void g_prep_w(const bf16_t *__restrict__ w, int Dm, int J, int JR, bf
   }
 }
 
-// gates[tok][j] = sigmoid(sum_k x[tok][k] w[k][j] + b[j]); NB = blocks of 16 gate columns
+// gates[tok][j] = sigmoid(sum_k x[tok][k] w[k][j] + b[j]); NB = blocks of 16 gate columns.  A wave owns two tiles of
+// 16 tokens (every weight operand feeds two matrix instructions); four contraction steps are issued per loop trip, so
+// eight 1 KB row loads per wave are in flight.
 template <int NB>
 __global__ __launch_bounds__(256) void g_fwd(const bf16_t *__restrict__ x, const bf16_t *__restrict__ wt,
                                              const bf16_t *__restrict__ bias, int N, int Dm, int J, bf16_t *__restrict__ gates) {
   const int wid = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 15, quad = lane >> 4;
-  const int t0 = (blockIdx.x * 4 + wid) * 16;
+  const int t0 = (blockIdx.x * 4 + wid) * 32;
   if (t0 >= N) return;
-  const int tok = min(t0 + n, N - 1);  // rows past the end repeat the last token and are not stored
-  const bf16_t *xr = x + (size_t)tok * Dm + 8 * quad;
-  f32x4 acc[NB];
+  const bf16_t *xr[2];
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
-  for (int ks = 0; ks < Dm / 32; ++ks) {
-    const bf16x8 av = ld8(xr + 32 * ks);
+  for (int a = 0; a < 2; ++a) xr[a] = x + (size_t)min(t0 + 16 * a + n, N - 1) * Dm + 8 * quad;  // rows past the end
+  f32x4 acc[2][NB];                                                                       // repeat the last token
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) acc[nb] = mfma16(av, ld8(wt + (size_t)(16 * nb + n) * Dm + 32 * ks + 8 * quad), acc[nb]);
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc[a][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int k4 = 0; k4 < Dm / 128; ++k4) {  // d_model is a multiple of 128: four contraction steps per trip
+    bf16x8 av[2][4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      av[0][u] = ld8(xr[0] + 128 * k4 + 32 * u);
+      av[1][u] = ld8(xr[1] + 128 * k4 + 32 * u);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        const bf16x8 bv = ld8(wt + (size_t)(16 * nb + n) * Dm + 128 * k4 + 32 * u + 8 * quad);
+        acc[0][nb] = mfma16(av[0][u], bv, acc[0][nb]);
+        acc[1][nb] = mfma16(av[1][u], bv, acc[1][nb]);
+      }
   }
-  // C layout: lane holds gate column 16*nb + n of tokens t0 + 4*quad + i
+  // C layout: lane holds gate column 16*nb + n of tokens t0 + 16*a + 4*quad + i
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
     const int j = 16 * nb + n;
     if (j >= J) continue;
     const float b = bf16_to_f32(bias[j]);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int t = t0 + 4 * quad + i;
-      if (t < N) gates[(size_t)t * J + j] = f32_to_bf16(1.0f / (1.0f + __expf(-(acc[nb][i] + b))));
-    }
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int t = t0 + 16 * a + 4 * quad + i;
+        if (t < N) gates[(size_t)t * J + j] = f32_to_bf16(1.0f / (1.0f + __expf(-(acc[a][nb][i] + b))));
+      }
   }
 }
 
-// dz[tok][j] = dgates * g * (1 - g) for j < J, zero up to column 63 (bf16); per-chunk column sums for db
-__global__ __launch_bounds__(256) void g_dz(const bf16_t *__restrict__ gates, const bf16_t *__restrict__ dgates, int N, int J,
-                                            int chunk, bf16_t *__restrict__ dz, float *__restrict__ pb) {
-  __shared__ float col[4][JP];
-  const int j = threadIdx.x & 63, r = threadIdx.x >> 6;
-  const int b = blockIdx.x * chunk, e = min(N, b + chunk);
-  float s = 0.f;
-  for (int t = b + r; t < e; t += 4) {  // row lane r visits tokens b+r, b+r+4, ..: a fixed order per (r, j)
-    float v = 0.f;
-    if (j < J) {
-      const float g = bf16_to_f32(gates[(size_t)t * J + j]);
-      v = bf16_to_f32(dgates[(size_t)t * J + j]) * g * (1.0f - g);
-    }
-    dz[(size_t)t * JP + j] = f32_to_bf16(v);
-    s += v;
+// dz[tok][j] = dgates * g * (1 - g) for j < J, zero up to column 63 (bf16)
+__global__ void g_dz(const bf16_t *__restrict__ gates, const bf16_t *__restrict__ dgates, int N, int J, bf16_t *__restrict__ dz) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)N * JP) return;
+  const size_t t = i / JP;
+  const int j = (int)(i % JP);
+  float v = 0.f;
+  if (j < J) {
+    const float g = bf16_to_f32(gates[t * J + j]);
+    v = bf16_to_f32(dgates[t * J + j]) * g * (1.0f - g);
   }
-  col[r][j] = s;
-  __syncthreads();
-  if (r == 0) pb[(size_t)blockIdx.x * JP + j] = (col[0][j] + col[1][j]) + (col[2][j] + col[3][j]);
+  dz[i] = f32_to_bf16(v);
 }
 
-// dx[tok][dim] += sum_j dz[tok][j] w[dim][j]: MFMA rows = dims (A = padded weights), columns = tokens (B = dz rows)
+// dx[tok][dim] += sum_j dz[tok][j] w[dim][j]: MFMA rows = dims (A = padded weights), columns = tokens (B = dz rows).
+// 64 dims per step as four matrix instructions whose row r stands for dim 16*(r >> 2) + 4*k + (r & 3) (k = instruction):
+// lane (token n, quad) then holds the 16 consecutive dims 16*quad .. +15 of the step, and the four quads of a token
+// cover 128 contiguous bytes of its dx row.
 __global__ __launch_bounds__(256) void g_dx(const bf16_t *__restrict__ dz, const bf16_t *__restrict__ wp, int N, int Dm,
                                             bf16_t *dx) {
   const int wid = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 15, quad = lane >> 4;
-  const int t0 = (blockIdx.x * 4 + wid) * 16;
+  const int t0 = (blockIdx.x * 4 + wid) * 32;  // two tiles of 16 tokens per wave: every weight operand is used twice
   if (t0 >= N) return;
-  const int tok = t0 + n;
-  const bool ok = tok < N;
-  bf16x8 bz[2];
+  int tok[2];
+  bf16x8 bz[2][2];
 #pragma unroll
-  for (int ks = 0; ks < 2; ++ks) bz[ks] = ok ? ld8(dz + (size_t)tok * JP + 32 * ks + 8 * quad) : zero8();
-  for (int mb = 0; mb < Dm / 16; ++mb) {
-    const bf16_t *wr = wp + (size_t)(16 * mb + n) * JP + 8 * quad;
-    f32x4 acc = mfma16(ld8(wr), bz[0], f32x4{0.f, 0.f, 0.f, 0.f});
-    acc = mfma16(ld8(wr + 32), bz[1], acc);
-    // C layout: lane holds dims 16*mb + 4*quad .. +3 of token column n: 8 contiguous bytes of dx
-    if (ok) {
-      bf16_t *d = dx + (size_t)tok * Dm + 16 * mb + 4 * quad;
-      const bf16x4 cur = *reinterpret_cast<const bf16x4 *>(d);
-      bf16x4 r;
+  for (int a = 0; a < 2; ++a) {
+    tok[a] = t0 + 16 * a + n;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) r[i] = (__bf16)((float)cur[i] + acc[i]);
-      *reinterpret_cast<bf16x4 *>(d) = r;
+    for (int ks = 0; ks < 2; ++ks) bz[a][ks] = tok[a] < N ? ld8(dz + (size_t)tok[a] * JP + 32 * ks + 8 * quad) : zero8();
+  }
+  const int rdim = 16 * (n >> 2) + (n & 3);  // dim (inside the step) of A row n, before the + 4*k of instruction k
+  for (int d0 = 0; d0 < Dm; d0 += 64) {
+    f32x4 acc[2][4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const bf16_t *wr = wp + (size_t)(d0 + rdim + 4 * k) * JP + 8 * quad;
+      const bf16x8 w0 = ld8(wr), w1 = ld8(wr + 32);
+#pragma unroll
+      for (int a = 0; a < 2; ++a) {
+        acc[a][k] = mfma16(w0, bz[a][0], f32x4{0.f, 0.f, 0.f, 0.f});
+        acc[a][k] = mfma16(w1, bz[a][1], acc[a][k]);
+      }
+    }
+    // C layout: lane holds rows 4*quad + i of every instruction = dims d0 + 16*quad + 4*k + i of token column n
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+      if (tok[a] >= N) continue;
+      bf16_t *d = dx + (size_t)tok[a] * Dm + d0 + 16 * quad;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const bf16x8 cur = ld8(d + 8 * h);
+        bf16x8 r;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) r[e] = (__bf16)((float)cur[e] + acc[a][2 * h + (e >> 2)][e & 3]);
+        *reinterpret_cast<bf16x8 *>(d + 8 * h) = r;
+      }
     }
   }
 }
 
 // dW partial: part[chunk][dim][j] = sum over the chunk's tokens of x[tok][dim] dz[tok][j]; a workgroup owns 128 dims
-// (wave w the 16-row blocks w and w+4) and all 64 (padded) gate columns.
+// (wave w the 16-row blocks w and w+4) and all 64 (padded) gate columns.  The next 32-token tile is fetched into
+// registers while the current one is consumed.  The workgroups of the first dim tile also produce the chunk's column
+// sums of dz (db) with an all-ones A operand.
 __global__ __launch_bounds__(256) void g_dw(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dz, int N, int Dm,
-                                            int chunk, float *__restrict__ part) {
+                                            int chunk, float *__restrict__ part, float *__restrict__ pb) {
   using GX = TileGeom<128>;
   using GZ = TileGeom<JP>;
   __shared__ __align__(16) bf16_t sx[GX::ROW_ELEMS], sz[GZ::ROW_ELEMS];
   const int d0 = blockIdx.x * 128, s = blockIdx.y;
   const int wid = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 15, quad = lane >> 4;
-  f32x4 acc[2][JP / 16];
+  const bool sums = blockIdx.x == 0 && wid == 0;
+  f32x4 acc[2][JP / 16], csum[JP / 16];
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int nb = 0; nb < JP / 16; ++nb) {
+    acc[0][nb] = acc[1][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    csum[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  bf16x8 ones;
 #pragma unroll
-    for (int nb = 0; nb < JP / 16; ++nb) acc[a][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int jj = 0; jj < 8; ++jj) ones[jj] = (__bf16)1.0f;
   const int b = s * chunk, e = min(N, b + chunk);
+  const int zrow = threadIdx.x / 8, zseg = threadIdx.x % 8;  // dz tile: 32 rows x 8 segments = 256 items
+  bf16x8 rx[2], rz;
+  auto fetch = [&](int t0) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int it = threadIdx.x + 256 * i, t = t0 + it / 16;
+      rx[i] = t < e ? ld8(x + (size_t)t * Dm + d0 + 8 * (it % 16)) : zero8();
+    }
+    rz = t0 + zrow < e ? ld8(dz + (size_t)(t0 + zrow) * JP + 8 * zseg) : zero8();
+  };
+  if (b < e) fetch(b);
   for (int t0 = b; t0 < e; t0 += 32) {
-    for (int it = threadIdx.x; it < GX::ROW_ITEMS; it += 256) {
-      const int row = it / 16, seg = it % 16, t = t0 + row;
-      *reinterpret_cast<bf16x8 *>(sx + GX::row_off(row, seg)) = t < e ? ld8(x + (size_t)t * Dm + d0 + 8 * seg) : zero8();
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int it = threadIdx.x + 256 * i;
+      *reinterpret_cast<bf16x8 *>(sx + GX::row_off(it / 16, it % 16)) = rx[i];
     }
-    {
-      const int row = threadIdx.x / 8, seg = threadIdx.x % 8, t = t0 + row;  // 32 rows x 8 segments = 256 items
-      *reinterpret_cast<bf16x8 *>(sz + GZ::row_off(row, seg)) = t < e ? ld8(dz + (size_t)t * JP + 8 * seg) : zero8();
-    }
+    *reinterpret_cast<bf16x8 *>(sz + GZ::row_off(zrow, zseg)) = rz;
     __syncthreads();
+    if (t0 + 32 < e) fetch(t0 + 32);
     bf16x8 av[2];
 #pragma unroll
     for (int a = 0; a < 2; ++a) av[a] = lds_tr_operand<128>(sx, wid + 4 * a);
@@ -143,6 +192,7 @@ __global__ __launch_bounds__(256) void g_dw(const bf16_t *__restrict__ x, const 
       const bf16x8 bv = lds_tr_operand<JP>(sz, nb);
 #pragma unroll
       for (int a = 0; a < 2; ++a) acc[a][nb] = mfma16(av[a], bv, acc[a][nb]);
+      if (sums) csum[nb] = mfma16(ones, bv, csum[nb]);
     }
     __syncthreads();
   }
@@ -153,6 +203,10 @@ __global__ __launch_bounds__(256) void g_dw(const bf16_t *__restrict__ x, const 
     for (int nb = 0; nb < JP / 16; ++nb)
 #pragma unroll
       for (int i = 0; i < 4; ++i) dst[(size_t)(d0 + 16 * (wid + 4 * a) + 4 * quad + i) * JP + 16 * nb + n] = acc[a][nb][i];
+  if (sums && quad == 0) {  // every row of csum holds the column sums; row 0 lives in quad 0
+#pragma unroll
+    for (int nb = 0; nb < JP / 16; ++nb) pb[(size_t)s * JP + 16 * nb + n] = csum[nb][0];
+  }
 }
 
 // out[r][j] (row stride J, j < J) = sum over parts p = 0 .. n_parts-1 of part[p][r][j] (row stride 64), in order
@@ -225,7 +279,7 @@ extern "C" int ssa_gate_forward(const ssa_params_t *p, int32_t d_model, const vo
   const int NB = (J + 15) / 16, JR = 16 * NB;
   ProfScope ps(PROF_GATE_FWD, s);
   g_prep_w<<<(unsigned)(((size_t)JR * d_model + 255) / 256), 256, 0, s>>>((const bf16_t *)w, d_model, J, JR, wt, nullptr);
-  const unsigned grid = (unsigned)((N + 63) / 64);
+  const unsigned grid = (unsigned)((N + 127) / 128);
   switch (NB) {
     case 1: g_fwd<1><<<grid, 256, 0, s>>>((const bf16_t *)x, wt, (const bf16_t *)bias, N, d_model, J, (bf16_t *)gates); break;
     case 2: g_fwd<2><<<grid, 256, 0, s>>>((const bf16_t *)x, wt, (const bf16_t *)bias, N, d_model, J, (bf16_t *)gates); break;
@@ -252,10 +306,10 @@ extern "C" int ssa_gate_backward(const ssa_params_t *p, int32_t d_model, const v
   float *pw = (float *)(ws + pl.pw), *pb = (float *)(ws + pl.pb);
   ProfScope ps(PROF_GATE_BWD, s);
   g_prep_w<<<(unsigned)(((size_t)d_model * JP + 255) / 256), 256, 0, s>>>((const bf16_t *)w, d_model, J, 0, nullptr, wp);
-  g_dz<<<pl.chunks, 256, 0, s>>>((const bf16_t *)gates, (const bf16_t *)dgates, N, J, pl.chunk, dz, pb);
+  g_dz<<<(unsigned)(((size_t)N * JP + 255) / 256), 256, 0, s>>>((const bf16_t *)gates, (const bf16_t *)dgates, N, J, dz);
+  g_dx<<<(unsigned)((N + 127) / 128), 256, 0, s>>>(dz, wp, N, d_model, (bf16_t *)dx_accum);
+  g_dw<<<dim3(d_model / 128, pl.chunks), 256, 0, s>>>((const bf16_t *)x, dz, N, d_model, pl.chunk, pw, pb);
   g_sum_parts<<<1, 64, 0, s>>>(pb, pl.chunks, 1, J, dbias);
-  g_dx<<<(unsigned)((N + 63) / 64), 256, 0, s>>>(dz, wp, N, d_model, (bf16_t *)dx_accum);
-  g_dw<<<dim3(d_model / 128, pl.chunks), 256, 0, s>>>((const bf16_t *)x, dz, N, d_model, pl.chunk, pw);
   g_sum_parts<<<(unsigned)(((size_t)d_model * J + 255) / 256), 256, 0, s>>>(pw, pl.chunks, d_model, J, dw);
   return hipGetLastError() == hipSuccess ? SSA_OK : SSA_ERR_HIP;
 }
