@@ -108,21 +108,28 @@ __device__ inline bf16x8 lds_tr_operand(const bf16_t *tile, int dt) {
   return __builtin_bit_cast(bf16x8, both);
 }
 
-// Cursor over the tiles of a list of key ranges held in LDS (rng_s/rng_e), uniform across the workgroup.
+// Cursor over the tiles of a list of key ranges held in LDS (rng_s/rng_e), uniform across the workgroup.  The end of
+// the current range is kept in the cursor: LDS is read only when the walk moves to another range.
 struct TileIter {
-  int r, kb;
+  int r, kb, end;
 };
 __device__ inline int lds_uniform(const int *p) { return __builtin_amdgcn_readfirstlane(*p); }
-__device__ inline TileIter iter_begin(const int *rng_s, int nr) {
-  TileIter it{0, 0};
-  if (nr > 0) it.kb = lds_uniform(rng_s) & ~7;
+__device__ inline TileIter iter_begin(const int *rng_s, const int *rng_e, int nr) {
+  TileIter it{0, 0, 0};
+  if (nr > 0) {
+    it.kb = lds_uniform(rng_s) & ~7;
+    it.end = lds_uniform(rng_e);
+  }
   return it;
 }
 __device__ inline TileIter iter_next(TileIter it, const int *rng_s, const int *rng_e, int nr) {
   it.kb += 32;
-  if (it.kb >= lds_uniform(rng_e + it.r)) {
+  if (it.kb >= it.end) {
     ++it.r;
-    if (it.r < nr) it.kb = lds_uniform(rng_s + it.r) & ~7;
+    if (it.r < nr) {
+      it.kb = lds_uniform(rng_s + it.r) & ~7;
+      it.end = lds_uniform(rng_e + it.r);
+    }
   }
   return it;
 }
@@ -185,7 +192,7 @@ __device__ inline void run_pipeline(const TileSrc<NROW> &src, bf16_t *stage0, co
   using L = StageLayout<D, NROW>;
   if (nr > 0) {
     TileRegs<D, NROW, NTHR> regs[PF];
-    TileIter cur = iter_begin(rng_s, nr);
+    TileIter cur = iter_begin(rng_s, rng_e, nr);
     TileIter ahead = cur;  // the last tile whose loads are in flight
     tile_load<D, NROW, NTHR>(regs[0], src, cur.kb);
     if (PF == 2) {
