@@ -60,3 +60,13 @@ def test_null_arguments():
     assert L.ssa_workspace_bytes(C.byref(p), None, 0) == 0
     assert L.ssa_blocks_counts(None, None, None, None) == -1
     L.ssa_blocks_destroy(None)  # allowed
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: `bench.py --gpus N` with N > 1 exits with a message, before touching the GPU."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
