@@ -203,9 +203,10 @@ __device__ inline void run_pipeline(const TileSrc<NROW> &src, bf16_t *stage0, co
     auto step = [&](TileRegs<D, NROW, NTHR> &r) {
       bf16_t *st = stage0 + buf * L::ELEMS;
       tile_store<D, NROW, NTHR>(r, st);
-      __syncthreads();
+      // the request for the tile PF steps ahead goes out while the LDS writes drain, before the barrier waits for them
       if (ahead.r < nr) ahead = iter_next(ahead, rng_s, rng_e, nr);
       if (ahead.r < nr) tile_load<D, NROW, NTHR>(r, src, ahead.kb);
+      __syncthreads();
       if (cur.r != cur_r) {
         cur_r = cur.r;
         enter(cur_r);
