@@ -59,34 +59,57 @@ __global__ void k_sort_hist(const uint64_t *__restrict__ keys, int N, int shift,
   hist[threadIdx.x * nTiles + blockIdx.x] = h[threadIdx.x];
 }
 
-// In-place exclusive scan of n values by one workgroup of 1024 threads.
-__global__ void k_scan_u32(uint32_t *data, int n) {
-  __shared__ uint32_t part[1024];
-  const int tid = threadIdx.x;
-  const int per = (n + 1023) / 1024;
-  const int b = min(n, tid * per), e = min(n, b + per);
-  uint32_t s = 0;
-  for (int i = b; i < e; ++i) s += data[i];
-  part[tid] = s;
+// Exclusive prefix sum over the `n` threads of a workgroup (n <= 1024 a multiple of 64): returns the sum of v over the
+// threads before this one; *total (optional) receives the sum over all threads.  `part` holds n/64 + 1 words of LDS.
+__device__ inline uint32_t block_exclusive_scan(uint32_t v, uint32_t *part, uint32_t *total) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  uint32_t inc = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t t = __shfl_up(inc, off);
+    if (lane >= off) inc += t;
+  }
+  __syncthreads();  // part may still be read from a previous call
+  if (lane == 63) part[w] = inc;
   __syncthreads();
-  for (int off = 1; off < 1024; off <<= 1) {
-    const uint32_t v = tid >= off ? part[tid - off] : 0u;
-    __syncthreads();
-    part[tid] += v;
-    __syncthreads();
+  uint32_t base = 0, all = 0;
+  for (int i = 0; i < nw; ++i) {
+    const uint32_t p = part[i];
+    if (i < w) base += p;
+    all += p;
   }
-  uint32_t run = part[tid] - s;
-  for (int i = b; i < e; ++i) {
-    const uint32_t v = data[i];
-    data[i] = run;
-    run += v;
+  if (total) *total = all;
+  return base + inc - v;
+}
+
+// Scatter offsets of one radix pass from the digit-major tile histogram hist[digit][tile]: workgroup d turns row d
+// into its exclusive prefix over the tiles (in place) and leaves the row total in totals[d] ...
+__global__ __launch_bounds__(256) void k_scan_rows(uint32_t *hist, int nTiles, uint32_t *totals) {
+  __shared__ uint32_t part[5];
+  uint32_t *row = hist + (size_t)blockIdx.x * nTiles;
+  uint32_t carry = 0;
+  for (int t0 = 0; t0 < nTiles; t0 += 256) {
+    const int t = t0 + threadIdx.x;
+    const uint32_t v = t < nTiles ? row[t] : 0u;
+    uint32_t all;
+    const uint32_t ex = block_exclusive_scan(v, part, &all);
+    if (t < nTiles) row[t] = carry + ex;
+    carry += all;
   }
+  if (threadIdx.x == 0) totals[blockIdx.x] = carry;
+}
+// ... and one workgroup turns the 256 digit totals into the digits' base offsets.
+__global__ __launch_bounds__(256) void k_scan_totals(uint32_t *totals) {
+  __shared__ uint32_t part[5];
+  const uint32_t v = totals[threadIdx.x];
+  const uint32_t ex = block_exclusive_scan(v, part, nullptr);
+  totals[threadIdx.x] = ex;
 }
 
 // Stable scatter of one 8-bit digit: rank inside the wavefront by ballot matching, wavefronts in order.
 __global__ void k_sort_scatter(const uint64_t *__restrict__ kin, const uint32_t *__restrict__ vin,
                                uint64_t *__restrict__ kout, uint32_t *__restrict__ vout, int N, int shift, int nTiles,
-                               const uint32_t *__restrict__ offs) {
+                               const uint32_t *__restrict__ offs, const uint32_t *__restrict__ digit_base) {
   __shared__ uint32_t wcnt[SORT_TILE / 64][256];
   for (int w = 0; w < SORT_TILE / 64; ++w) wcnt[w][threadIdx.x] = 0;
   __syncthreads();
@@ -106,7 +129,7 @@ __global__ void k_sort_scatter(const uint64_t *__restrict__ kin, const uint32_t 
   if (valid && rank == 0) wcnt[w][digit] = (uint32_t)__popcll(peers);
   __syncthreads();
   if (valid) {
-    uint32_t pos = offs[digit * nTiles + blockIdx.x] + rank;
+    uint32_t pos = digit_base[digit] + offs[digit * nTiles + blockIdx.x] + rank;
     for (int ww = 0; ww < w; ++ww) pos += wcnt[ww][digit];
     kout[pos] = key;
     vout[pos] = vin[i];
@@ -118,61 +141,83 @@ struct CsrOut {
   int32_t *cmp_start, *slc_start, *win_start, *slc_child_start, *cmp_slc, *cmp_batch, *slc_batch;
 };
 
-// One workgroup: block ids (= running count of block heads) at the three granularities and every start array.
-__global__ void k_csr(const uint64_t *__restrict__ ks, const uint32_t *__restrict__ vals, int N, int B, int bits, int sc,
-                      int ss, int sw, CsrOut o, int32_t *meta) {
-  __shared__ int part[3][1024];
-  const int tid = threadIdx.x;
-  const int per = (N + 1023) / 1024;
-  const int b = min(N, tid * per), e = min(N, b + per);
-  int c[3] = {0, 0, 0};
-  for (int i = b; i < e; ++i) {
-    const uint64_t k = ks[i];
-    const bool first = i == 0;
-    const uint64_t p = first ? 0ull : ks[i - 1];
-    c[0] += first || (k >> sc) != (p >> sc);
-    c[1] += first || (k >> ss) != (p >> ss);
-    c[2] += first || (k >> sw) != (p >> sw);
-  }
-  for (int x = 0; x < 3; ++x) part[x][tid] = c[x];
+// Block ids are running counts of block heads (a token whose key prefix differs from its predecessor's) at the three
+// granularities.  Three launches: per-tile head counts, their prefix over the tiles (one small workgroup), then every
+// tile numbers its own tokens and writes all per-token and per-block arrays.
+constexpr int CSR_TILE = 256;
+struct Heads { bool c, s, w; };
+__device__ inline Heads heads_of(const uint64_t *ks, int i, int sc, int ss, int sw) {
+  const uint64_t k = ks[i], p = i == 0 ? 0ull : ks[i - 1];
+  const bool first = i == 0;
+  return Heads{first || (k >> sc) != (p >> sc), first || (k >> ss) != (p >> ss), first || (k >> sw) != (p >> sw)};
+}
+
+__global__ __launch_bounds__(CSR_TILE) void k_csr_count(const uint64_t *__restrict__ ks, int N, int sc, int ss, int sw,
+                                                        int nTiles, uint32_t *__restrict__ tile_cnt) {
+  __shared__ uint32_t cnt[3];
+  if (threadIdx.x < 3) cnt[threadIdx.x] = 0;
   __syncthreads();
-  for (int off = 1; off < 1024; off <<= 1) {
-    int v[3];
-    for (int x = 0; x < 3; ++x) v[x] = tid >= off ? part[x][tid - off] : 0;
-    __syncthreads();
-    for (int x = 0; x < 3; ++x) part[x][tid] += v[x];
-    __syncthreads();
+  const int i = blockIdx.x * CSR_TILE + threadIdx.x;
+  Heads h{false, false, false};
+  if (i < N) h = heads_of(ks, i, sc, ss, sw);
+  const uint64_t bc = __ballot(h.c), bs = __ballot(h.s), bw = __ballot(h.w);
+  if ((threadIdx.x & 63) == 0) {
+    atomicAdd(&cnt[0], (uint32_t)__popcll(bc));
+    atomicAdd(&cnt[1], (uint32_t)__popcll(bs));
+    atomicAdd(&cnt[2], (uint32_t)__popcll(bw));
   }
-  int run[3];
-  for (int x = 0; x < 3; ++x) run[x] = part[x][tid] - c[x];
-  for (int i = b; i < e; ++i) {
-    const uint64_t k = ks[i];
-    const bool first = i == 0;
-    const uint64_t p = first ? 0ull : ks[i - 1];
-    const bool hc = first || (k >> sc) != (p >> sc);
-    const bool hs = first || (k >> ss) != (p >> ss);
-    const bool hw = first || (k >> sw) != (p >> sw);
-    run[0] += hc; run[1] += hs; run[2] += hw;
-    const int idc = run[0] - 1, ids = run[1] - 1, idw = run[2] - 1;
-    const int item = (int)(k >> (3 * bits));
-    const int pitem = first ? -1 : (int)(p >> (3 * bits));
-    const uint32_t src = vals[i];
-    o.perm[i] = (int32_t)src;
-    o.inv_perm[src] = i;
-    o.tok_item[i] = item;
-    o.tok_cmp[i] = idc;
-    o.tok_slc[i] = ids;
-    o.tok_win[i] = idw;
-    if (hc) { o.cmp_start[idc] = i; o.cmp_slc[idc] = ids; }
-    if (hs) { o.slc_start[ids] = i; o.slc_child_start[ids] = idc; }
-    if (hw) o.win_start[idw] = i;
-    for (int it = pitem + 1; it <= item; ++it) { o.cmp_batch[it] = idc; o.slc_batch[it] = ids; }
-    if (i == N - 1) {
-      const int Nc = idc + 1, Ns = ids + 1, Nw = idw + 1;
-      o.cmp_start[Nc] = N; o.slc_start[Ns] = N; o.win_start[Nw] = N; o.slc_child_start[Ns] = Nc;
-      for (int it = item + 1; it <= B; ++it) { o.cmp_batch[it] = Nc; o.slc_batch[it] = Ns; }
-      meta[META_NC] = Nc; meta[META_NS] = Ns; meta[META_NW] = Nw;
+  __syncthreads();
+  if (threadIdx.x < 3) tile_cnt[threadIdx.x * nTiles + blockIdx.x] = cnt[threadIdx.x];
+}
+
+// Exclusive prefix of the three count rows over the tiles (in place); one workgroup.
+__global__ __launch_bounds__(256) void k_csr_scan(uint32_t *tile_cnt, int nTiles) {
+  __shared__ uint32_t part[5];
+  for (int x = 0; x < 3; ++x) {
+    uint32_t *row = tile_cnt + (size_t)x * nTiles;
+    uint32_t carry = 0;
+    for (int t0 = 0; t0 < nTiles; t0 += 256) {
+      const int t = t0 + threadIdx.x;
+      const uint32_t v = t < nTiles ? row[t] : 0u;
+      uint32_t all;
+      const uint32_t ex = block_exclusive_scan(v, part, &all);
+      if (t < nTiles) row[t] = carry + ex;
+      carry += all;
     }
+  }
+}
+
+__global__ __launch_bounds__(CSR_TILE) void k_csr_write(const uint64_t *__restrict__ ks, const uint32_t *__restrict__ vals, int N,
+                                                        int B, int bits, int sc, int ss, int sw, int nTiles,
+                                                        const uint32_t *__restrict__ tile_base, CsrOut o, int32_t *meta) {
+  __shared__ uint32_t part[5];
+  const int i = blockIdx.x * CSR_TILE + threadIdx.x;
+  Heads h{false, false, false};
+  if (i < N) h = heads_of(ks, i, sc, ss, sw);
+  // inclusive head counts up to and including token i
+  const int idc = (int)(tile_base[blockIdx.x] + block_exclusive_scan(h.c, part, nullptr) + h.c) - 1;
+  const int ids = (int)(tile_base[nTiles + blockIdx.x] + block_exclusive_scan(h.s, part, nullptr) + h.s) - 1;
+  const int idw = (int)(tile_base[2 * nTiles + blockIdx.x] + block_exclusive_scan(h.w, part, nullptr) + h.w) - 1;
+  if (i >= N) return;
+  const uint64_t k = ks[i];
+  const int item = (int)(k >> (3 * bits));
+  const int pitem = i == 0 ? -1 : (int)(ks[i - 1] >> (3 * bits));
+  const uint32_t src = vals[i];
+  o.perm[i] = (int32_t)src;
+  o.inv_perm[src] = i;
+  o.tok_item[i] = item;
+  o.tok_cmp[i] = idc;
+  o.tok_slc[i] = ids;
+  o.tok_win[i] = idw;
+  if (h.c) { o.cmp_start[idc] = i; o.cmp_slc[idc] = ids; }
+  if (h.s) { o.slc_start[ids] = i; o.slc_child_start[ids] = idc; }
+  if (h.w) o.win_start[idw] = i;
+  for (int it = pitem + 1; it <= item; ++it) { o.cmp_batch[it] = idc; o.slc_batch[it] = ids; }
+  if (i == N - 1) {
+    const int Nc = idc + 1, Ns = ids + 1, Nw = idw + 1;
+    o.cmp_start[Nc] = N; o.slc_start[Ns] = N; o.win_start[Nw] = N; o.slc_child_start[Ns] = Nc;
+    for (int it = item + 1; it <= B; ++it) { o.cmp_batch[it] = Nc; o.slc_batch[it] = Ns; }
+    meta[META_NC] = Nc; meta[META_NS] = Ns; meta[META_NW] = Nw;
   }
 }
 
@@ -227,7 +272,9 @@ extern "C" int ssa_build_blocks(const ssa_params_t *p, const int32_t *coords, co
   void *tmp = nullptr;
   const size_t key_b = align_up((size_t)N * 8, 256), val_b = align_up((size_t)N * 4, 256);
   const size_t hist_b = align_up((size_t)256 * (nTiles > 0 ? nTiles : 1) * 4, 256);
-  const size_t tmp_bytes = 2 * key_b + 2 * val_b + hist_b + 256;
+  const int csrTiles = (N + CSR_TILE - 1) / CSR_TILE;
+  const size_t aux_b = align_up((size_t)(256 + 3 * (csrTiles > 0 ? csrTiles : 1)) * 4, 256);  // digit bases | CSR tile counts
+  const size_t tmp_bytes = 2 * key_b + 2 * val_b + hist_b + aux_b + 256;
   auto fail = [&](int code) {
     if (tmp) (void)hipFree(tmp);
     (void)hipFree(h->base);
@@ -241,6 +288,7 @@ extern "C" int ssa_build_blocks(const ssa_params_t *p, const int32_t *coords, co
   uint32_t *v0 = (uint32_t *)tp; tp += val_b;
   uint32_t *v1 = (uint32_t *)tp; tp += val_b;
   uint32_t *hist = (uint32_t *)tp; tp += hist_b;
+  uint32_t *digit_base = (uint32_t *)tp, *tile_cnt = digit_base + 256; tp += aux_b;
   int32_t *meta = (int32_t *)tp;
   if (hipMemsetAsync(meta, 0, 256, stream) != hipSuccess) return fail(SSA_ERR_HIP);
   CsrOut o{h->perm, h->inv_perm, h->tok_item, h->tok_cmp, h->tok_slc, h->tok_win, h->cmp_start, h->slc_start,
@@ -250,13 +298,16 @@ extern "C" int ssa_build_blocks(const ssa_params_t *p, const int32_t *coords, co
     const int total_bits = 3 * bits + item_bits;
     for (int shift = 0; shift < total_bits; shift += 8) {
       k_sort_hist<<<nTiles, SORT_TILE, 0, stream>>>(k0, N, shift, nTiles, hist);
-      k_scan_u32<<<1, 1024, 0, stream>>>(hist, 256 * nTiles);
-      k_sort_scatter<<<nTiles, SORT_TILE, 0, stream>>>(k0, v0, k1, v1, N, shift, nTiles, hist);
+      k_scan_rows<<<256, 256, 0, stream>>>(hist, nTiles, digit_base);
+      k_scan_totals<<<1, 256, 0, stream>>>(digit_base);
+      k_sort_scatter<<<nTiles, SORT_TILE, 0, stream>>>(k0, v0, k1, v1, N, shift, nTiles, hist, digit_base);
       uint64_t *tk = k0; k0 = k1; k1 = tk;
       uint32_t *tv = v0; v0 = v1; v1 = tv;
     }
-    k_csr<<<1, 1024, 0, stream>>>(k0, v0, N, B, bits, 3 * ilog2_exact(p->m_cmp), 3 * ilog2_exact(p->m_slc),
-                                  3 * ilog2_exact(p->m_win), o, meta);
+    const int sc = 3 * ilog2_exact(p->m_cmp), ss = 3 * ilog2_exact(p->m_slc), sw = 3 * ilog2_exact(p->m_win);
+    k_csr_count<<<csrTiles, CSR_TILE, 0, stream>>>(k0, N, sc, ss, sw, csrTiles, tile_cnt);
+    k_csr_scan<<<1, 256, 0, stream>>>(tile_cnt, csrTiles);
+    k_csr_write<<<csrTiles, CSR_TILE, 0, stream>>>(k0, v0, N, B, bits, sc, ss, sw, csrTiles, tile_cnt, o, meta);
     const int span = (N > B ? N : B);
     k_maxima<<<(span + 255) / 256, 256, 0, stream>>>(o, B, meta);
     if (hipMemcpyAsync(h->sorted_keys, k0, (size_t)N * sizeof(uint64_t), hipMemcpyDeviceToDevice, stream) != hipSuccess)
