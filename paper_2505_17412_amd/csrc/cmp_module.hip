@@ -156,6 +156,101 @@ __global__ __launch_bounds__(256) void c_conv(const bf16_t *__restrict__ in, con
   }
 }
 
+// The same gather-GEMM for C = 128 with both operands staged through LDS: a workgroup owns TOK tokens, wavefront w the
+// output channels 32w .. 32w+31.  Per offset the 128 x 128 weights (32 KB) and the TOK gathered rows are written to LDS
+// once and read by all four wavefronts as conflict-free row-operand reads; the data of the next offset is in flight in
+// registers meanwhile, its row indices taken from a copy of the tile's neighbour table in LDS.  Row r of a 16-row MFMA
+// tile stands for LDS row 8*(r >> 2) + 4*a + (r & 3) of its 32-row tile (a = which half), for tokens and for channels
+// alike; the store at the end undoes that numbering.
+constexpr int CONV_TOK = 128;  // tokens per workgroup of the staged convolution
+template <bool MIRROR, int TOK>
+__global__ __launch_bounds__(256) void c_conv128(const bf16_t *__restrict__ in, const int32_t *__restrict__ nbr,
+                                                 const bf16_t *__restrict__ Bw, const bf16_t *__restrict__ bias, int N,
+                                                 float *__restrict__ out) {
+  constexpr int C = 128, MT = TOK / 16, AI = TOK / 16;  // AI: gathered 16-byte items per thread (TOK x 16 / 256)
+  using G = TileGeom<C>;
+  __shared__ __align__(16) bf16_t sw[4 * G::ROW_ELEMS], sa[(TOK / 32) * G::ROW_ELEMS];
+  __shared__ int any_flag[27];
+  __shared__ int32_t snbr[TOK * 27];
+  const int wid = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 15, quad = lane >> 4;
+  const int pos0 = blockIdx.x * TOK;
+  // which offsets have a neighbour for any of the tokens (workgroup-uniform skip)
+  if (threadIdx.x < 27) any_flag[threadIdx.x] = 0;
+  __syncthreads();
+  for (int i = threadIdx.x; i < TOK * 27; i += 256) {
+    const int t = pos0 + i / 27, o = i % 27;
+    const int32_t v = t < N ? nbr[(size_t)t * 27 + o] : -1;
+    snbr[i] = v;
+    if (v >= 0) any_flag[MIRROR ? 26 - o : o] = 1;
+  }
+  __syncthreads();
+  f32x4 acc[MT][2];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) acc[mt][0] = acc[mt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+  // staging roles: the weights are 128 rows x 16 segments = 2048 items (8 per thread), the gathered rows TOK x 16
+  bf16x8 rw[8], ra[AI];
+  auto fetch = [&](int o) {
+    const bf16_t *Bo = Bw + (size_t)o * C * C;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int it = threadIdx.x + 256 * i;
+      rw[i] = ld8(Bo + (size_t)(it / 16) * C + 8 * (it % 16));
+    }
+    const int oo = MIRROR ? 26 - o : o;
+#pragma unroll
+    for (int i = 0; i < AI; ++i) {
+      const int it = threadIdx.x + 256 * i;
+      const int src = snbr[(it / 16) * 27 + oo];
+      ra[i] = src >= 0 ? ld8(in + (size_t)src * C + 8 * (it % 16)) : zero8();
+    }
+  };
+  int o = 0;
+  while (o < 27 && !any_flag[o]) ++o;
+  if (o < 27) fetch(o);
+  while (o < 27) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int it = threadIdx.x + 256 * i, row = it / 16;
+      *reinterpret_cast<bf16x8 *>(sw + (row >> 5) * G::ROW_ELEMS + G::row_off(row & 31, it % 16)) = rw[i];
+    }
+#pragma unroll
+    for (int i = 0; i < AI; ++i) {
+      const int it = threadIdx.x + 256 * i, row = it / 16;
+      *reinterpret_cast<bf16x8 *>(sa + (row >> 5) * G::ROW_ELEMS + G::row_off(row & 31, it % 16)) = ra[i];
+    }
+    __syncthreads();
+    int nxt = o + 1;
+    while (nxt < 27 && !any_flag[nxt]) ++nxt;
+    if (nxt < 27) fetch(nxt);
+#pragma unroll
+    for (int ks = 0; ks < C / 32; ++ks) {
+      const bf16x8 b0 = lds_row_operand<C>(sw + wid * G::ROW_ELEMS, 0, ks), b1 = lds_row_operand<C>(sw + wid * G::ROW_ELEMS, 1, ks);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const bf16x8 av = lds_row_operand<C>(sa + (mt >> 1) * G::ROW_ELEMS, mt & 1, ks);
+        acc[mt][0] = mfma16(av, b0, acc[mt][0]);
+        acc[mt][1] = mfma16(av, b1, acc[mt][1]);
+      }
+    }
+    __syncthreads();
+    o = nxt;
+  }
+  // lane: column n of half a -> channel 32*wid + 8*(n >> 2) + 4*a + (n & 3); rows 4*quad + i of tile mt -> token
+  // pos0 + 32*(mt >> 1) + 8*quad + 4*(mt & 1) + i
+#pragma unroll
+  for (int a = 0; a < 2; ++a) {
+    const int ch = 32 * wid + 8 * (n >> 2) + 4 * a + (n & 3);
+    const float bs = bias ? bf16_to_f32(bias[ch]) : 0.f;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int t = pos0 + 32 * (mt >> 1) + 8 * quad + 4 * (mt & 1) + i;
+        if (t < N) out[(size_t)t * C + ch] = acc[mt][a][i] + bs;
+      }
+  }
+}
+
 // Mean over the tokens of each compression block (contiguous in sorted order); one workgroup per block.
 __global__ void c_pool(const float *__restrict__ Y, const int32_t *__restrict__ cmp_start, int C, bf16_t *__restrict__ xc) {
   const int c = blockIdx.x, b = cmp_start[c], e = cmp_start[c + 1];
@@ -355,7 +450,7 @@ void launch_conv(int C, const bf16_t *in, const int32_t *nbr, const bf16_t *Bw, 
   switch (C) {
     case 32: c_conv<32, MIRROR, 4, 2><<<grid, 256, 0, s>>>(in, nbr, Bw, bias, N, out); break;
     case 64: c_conv<64, MIRROR, 4, 4><<<grid, 256, 0, s>>>(in, nbr, Bw, bias, N, out); break;
-    case 128: c_conv<128, MIRROR, 4, 8><<<grid, 256, 0, s>>>(in, nbr, Bw, bias, N, out); break;
+    case 128: c_conv128<MIRROR, CONV_TOK><<<(unsigned)((N + CONV_TOK - 1) / CONV_TOK), 256, 0, s>>>(in, nbr, Bw, bias, N, out); break;
     default: c_conv<256, MIRROR, 4, 8><<<grid, 256, 0, s>>>(in, nbr, Bw, bias, N, out); break;
   }
 }
