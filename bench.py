@@ -56,6 +56,46 @@ def recorded_traffic(kernel, workload, d):
     return None
 
 
+def _imports():
+    import torch
+    from paper_2505_17412_amd import inputs, ssa
+    from tests import util
+    return torch, inputs, ssa, util
+
+
+def kernel_times(wl, steps):
+    """Average HIP-event time per kernel (ms) over `steps` forward+backward passes; also returns what the work count
+    needs: the handle's arrays and the selected sets."""
+    torch, _, ssa, util = _imports()
+    n, hq, hkv, T = wl.n_tokens, wl.n_heads_q, wl.n_heads_kv, wl.topk
+    p, blk = util.build_blocks_gpu(wl)
+    q, k, v, g, do = (util.to_dev(a, wl.dtype) for a in (wl.q, wl.k, wl.v, wl.gates, wl.dout))
+    out = torch.empty_like(q)
+    ob = torch.empty((3,) + tuple(q.shape), dtype=q.dtype, device="cuda")
+    lse = torch.empty((3, n, hq), dtype=torch.float32, device="cuda")
+    idx = torch.empty((n, hkv, T), dtype=torch.int32, device="cuda")
+    dq, dk, dv, dg = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v), torch.empty_like(g)
+    wsf = torch.empty(ssa.ssa_workspace_bytes(p, blk, False), dtype=torch.uint8, device="cuda")
+    wsb = torch.empty(ssa.ssa_workspace_bytes(p, blk, True), dtype=torch.uint8, device="cuda")
+
+    def step():
+        ssa.ssa_forward(p, blk, q, k, v, g, out, lse, idx, ob, wsf)
+        ssa.ssa_backward(p, blk, q, k, v, g, ob, lse, idx, do, dq, dk, dv, dg, wsb)
+
+    step()
+    torch.cuda.synchronize()
+    ssa.ssa_profile_enable(True)
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    prof = ssa.ssa_profile_get()
+    ssa.ssa_profile_enable(False)
+    arrays = {nm: blk.export(nm).cpu().numpy() for nm in ("perm", "tok_win", "win_start", "cmp_batch", "slc_start")}
+    sel = idx.cpu().numpy()
+    blk.destroy()
+    return {nm: tot / cnt for nm, (tot, cnt) in prof.items()}, arrays, sel
+
+
 # Token sweep of the sparse path against dense attention computed by the same library (the window branch with one
 # window over the whole grid is plain dense variable-length attention).  Shells of the bench workload's recipe at
 # three grid sizes: (grid, size factor f, half-width w).
@@ -71,40 +111,13 @@ def dense_sweep(args):
 
     torch.cuda.set_device(0)
 
-    def kernel_times(wl, steps):
-        n, hq, hkv, T = wl.n_tokens, wl.n_heads_q, wl.n_heads_kv, wl.topk
-        p, blk = util.build_blocks_gpu(wl)
-        q, k, v, g, do = (util.to_dev(a, wl.dtype) for a in (wl.q, wl.k, wl.v, wl.gates, wl.dout))
-        out = torch.empty_like(q)
-        ob = torch.empty((3,) + tuple(q.shape), dtype=q.dtype, device="cuda")
-        lse = torch.empty((3, n, hq), dtype=torch.float32, device="cuda")
-        idx = torch.empty((n, hkv, T), dtype=torch.int32, device="cuda")
-        dq, dk, dv, dg = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v), torch.empty_like(g)
-        wsf = torch.empty(ssa.ssa_workspace_bytes(p, blk, False), dtype=torch.uint8, device="cuda")
-        wsb = torch.empty(ssa.ssa_workspace_bytes(p, blk, True), dtype=torch.uint8, device="cuda")
-
-        def step():
-            ssa.ssa_forward(p, blk, q, k, v, g, out, lse, idx, ob, wsf)
-            ssa.ssa_backward(p, blk, q, k, v, g, ob, lse, idx, do, dq, dk, dv, dg, wsb)
-
-        step()
-        torch.cuda.synchronize()
-        ssa.ssa_profile_enable(True)
-        for _ in range(steps):
-            step()
-        torch.cuda.synchronize()
-        prof = ssa.ssa_profile_get()
-        ssa.ssa_profile_enable(False)
-        blk.destroy()
-        return {nm: tot / cnt for nm, (tot, cnt) in prof.items()}
-
     fwd_names = ("prep_sort_pool", "cmp_fwd_scores_topk", "slc_fwd", "win_fwd", "combine")
     for grid, f, w in SWEEP_POINTS:
         sparse = inputs.make_workload("g128", grid=grid, f=f, w=w)
         dense = inputs.make_workload("g128", grid=grid, f=f, w=w, m=(4, 8, grid), topk=1)
         n = sparse.n_tokens
-        ks = kernel_times(sparse, 3)
-        kd = kernel_times(dense, 2 if n > 50000 else 3)
+        ks = kernel_times(sparse, 3)[0]
+        kd = kernel_times(dense, 2 if n > 50000 else 3)[0]
         # prep_sort_pool runs once in forward and once in backward; its average is booked on both sides
         s_fwd = sum(ks[nm] for nm in fwd_names)
         s_bwd = sum(v_ for nm, v_ in ks.items() if nm not in fwd_names) + ks["prep_sort_pool"]
@@ -116,6 +129,41 @@ def dense_sweep(args):
                 "speedup_fwd": round(d_fwd / s_fwd, 2), "speedup_bwd": round(d_bwd / s_bwd, 2),
                 "speedup_fwd_bwd": round((d_fwd + d_bwd) / (s_fwd + s_bwd), 2),
                 "dense_fwd_tflops": round(4 * sparse.head_dim * n * n * sparse.n_heads_q / (d_fwd * 1e-3) / 1e12, 1)}
+        print(json.dumps(line), flush=True)
+
+
+FWD_KERNELS = ("prep_sort_pool", "cmp_fwd_scores_topk", "slc_fwd", "win_fwd", "combine")
+
+
+def seq1d_bench(args):
+    """One JSON line per sequence workload: the same kernels on the one-dimensional partition of sequence models
+    (compression blocks of 32 tokens, selection blocks of 64, windows of 512, top-16), against dense attention over
+    the same sequences (one window per sequence)."""
+    torch, inputs, ssa, util = _imports()
+    torch.cuda.set_device(0)
+    for lens in ((65536,), (16384,) * 4):
+        n = sum(lens)
+        sparse = inputs.make_sequence_workload(2001, lens)
+        dense = inputs.make_sequence_workload(2001, lens, l=(32, 64, max(lens)), topk=1)
+        ks, arrays, sel = kernel_times(sparse, 3)
+        kd = kernel_times(dense, 2)[0]
+        pairs = algorithmic_flops(sparse, arrays, sel)
+        total_pairs = pairs["cmp"] + pairs["slc"] + pairs["win"]
+        s_fwd = sum(ks[nm] for nm in FWD_KERNELS)
+        s_bwd = sum(v_ for nm, v_ in ks.items() if nm not in FWD_KERNELS) + ks["prep_sort_pool"]
+        d_fwd = kd["win_fwd"]
+        d_bwd = kd["bwd_dq_slc_win"] + kd["bwd_dkv_win"] + kd["bwd_pre_delta"]
+        flops = 14 * sparse.head_dim * total_pairs
+        line = {"bench": "sequence_partition", "lens": list(lens), "n_tokens": n, "blocks": [32, 64, 512], "topk": 16,
+                "heads": [sparse.n_heads_q, sparse.n_heads_kv], "head_dim": sparse.head_dim,
+                "ssa_fwd_ms": round(s_fwd, 3), "ssa_bwd_ms": round(s_bwd, 3),
+                "tokens_per_s": round(n / ((s_fwd + s_bwd) * 1e-3)),
+                "pairs_cmp_slc_win": [pairs["cmp"], pairs["slc"], pairs["win"]],
+                "algorithmic_tflops": round(flops / ((s_fwd + s_bwd) * 1e-3) / 1e12, 1),
+                "frac_of_mfma_peak": round(flops / ((s_fwd + s_bwd) * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                "dense_fwd_ms": round(d_fwd, 3), "dense_bwd_ms": round(d_bwd, 3),
+                "speedup_fwd_bwd": round((d_fwd + d_bwd) / (s_fwd + s_bwd), 2),
+                "kernel_ms": {k_: round(v_, 3) for k_, v_ in ks.items()}}
         print(json.dumps(line), flush=True)
 
 
@@ -257,6 +305,7 @@ def main():
     ap.add_argument("--gate", action="store_true", help="instead of the benchmark line: the gate predictor against the HBM roofline")
     ap.add_argument("--cmp-module", action="store_true",
                     help="instead of the benchmark line: the learned compression module alone and inside a training step")
+    ap.add_argument("--seq1d", action="store_true", help="instead of the benchmark line: the kernels on a one-dimensional (sequence) partition")
     ap.add_argument("--dense-sweep", action="store_true",
                     help="instead of the benchmark line: sparse path against dense attention over 2.6k-124k tokens")
     args = ap.parse_args()
@@ -265,6 +314,9 @@ def main():
         sys.exit(2)
     if args.dense_sweep:
         dense_sweep(args)
+        return
+    if args.seq1d:
+        seq1d_bench(args)
         return
     if args.cmp_module:
         cmp_module_bench(args)

@@ -93,6 +93,21 @@ typedef enum {
 int ssa_build_blocks(const ssa_params_t *params, const int32_t *coords, const int32_t *batch_offsets,
                      void *stream, ssa_blocks_t **out);
 
+/*
+ * The same handle for a one-dimensional partition (the paper's remark that its 3D partition takes the place of the
+ * 1D blocks of sequence models): batch item i is a sequence of batch_offsets[i+1]-batch_offsets[i] tokens in the
+ * caller's order, and a block is a run of m_cmp / m_slc / m_win consecutive tokens counted from the start of the
+ * sequence (the last block of a sequence may be shorter).  m_cmp, m_slc, m_win are token counts here, any values
+ * with m_slc a proper multiple of m_cmp; params->grid is not read (but must be passed unchanged to the other calls).
+ * The token order is the caller's (PERM is the identity).  Every attention entry point accepts the handle;
+ * the learned compression module (a convolution on the voxel grid) returns SSA_ERR_UNSUPPORTED for it.
+ *
+ *   params, batch_offsets, stream, out: as for ssa_build_blocks
+ * Errors: NULL, BAD_SHAPE, BAD_BLOCK_SIZES (before any launch); BAD_OFFSETS (found on the device before the
+ * partition is built; no handle is returned); HIP.
+ */
+int ssa_build_blocks_1d(const ssa_params_t *params, const int32_t *batch_offsets, void *stream, ssa_blocks_t **out);
+
 /* Number of non-empty compression / selection / window blocks (host ints; any may be NULL). */
 int ssa_blocks_counts(const ssa_blocks_t *blocks, int32_t *n_cmp, int32_t *n_slc, int32_t *n_win);
 

@@ -111,3 +111,46 @@ def build_blocks(coords: np.ndarray, batch_offsets: np.ndarray, grid: int, m_cmp
         n_blocks=nblk, start=start, cmp_parent=cmp_parent, slc_child_start=slc_child_start,
         cmp_batch=cmp_batch, slc_batch=slc_batch, tok_win=ids["win"][perm].astype(np.int32),
     )
+
+
+def build_blocks_1d(batch_offsets: np.ndarray, l_cmp: int, l_slc: int, l_win: int) -> Blocks:
+    """One-dimensional partition (the sequence-model blocks the paper's 3D partition takes the place of): item i is
+    a sequence in the caller's order; a block is a run of l consecutive tokens counted from the start of its
+    sequence, the last one possibly shorter.  Block ids count the blocks of all items in order."""
+    offs = np.asarray(batch_offsets, dtype=np.int64)
+    n = int(offs[-1])
+    nb = offs.shape[0] - 1
+    assert offs[0] == 0 and np.all(np.diff(offs) >= 0)
+    assert l_slc > l_cmp and l_slc % l_cmp == 0 and l_win >= 1
+    item = (np.searchsorted(offs, np.arange(n), side="right") - 1).astype(np.int64)
+    pos = np.arange(n, dtype=np.int64) - offs[item]
+    lens = np.diff(offs)
+    ids: Dict[str, np.ndarray] = {}
+    nblk: Dict[str, int] = {}
+    start: Dict[str, np.ndarray] = {}
+    per_item: Dict[str, np.ndarray] = {}
+    for level, l in (("cmp", l_cmp), ("slc", l_slc), ("win", l_win)):
+        cnt = -(-lens // l)  # blocks per item: ceil(len / l)
+        first = np.concatenate([[0], np.cumsum(cnt)])
+        per_item[level] = first
+        ids[level] = (first[item] + pos // l).astype(np.int32)
+        nblk[level] = int(first[-1])
+        st = np.empty(nblk[level] + 1, dtype=np.int32)
+        for it in range(nb):
+            for j in range(int(cnt[it])):
+                st[first[it] + j] = offs[it] + j * l
+        st[-1] = n
+        start[level] = st
+    ratio = l_slc // l_cmp
+    cmp_parent = np.empty(nblk["cmp"], dtype=np.int32)
+    for it in range(nb):
+        for j in range(int(per_item["cmp"][it + 1] - per_item["cmp"][it])):
+            cmp_parent[per_item["cmp"][it] + j] = per_item["slc"][it] + j // ratio
+    slc_child_start = np.searchsorted(cmp_parent, np.arange(nblk["slc"] + 1), side="left").astype(np.int32)
+    ident = np.arange(n, dtype=np.int32)
+    return Blocks(
+        n_tokens=n, n_batch=nb, perm=ident, inv_perm=ident.copy(), tok_item=item.astype(np.int32), ids=ids,
+        n_blocks=nblk, start=start, cmp_parent=cmp_parent, slc_child_start=slc_child_start,
+        cmp_batch=per_item["cmp"].astype(np.int32), slc_batch=per_item["slc"].astype(np.int32),
+        tok_win=ids["win"].astype(np.int32),
+    )

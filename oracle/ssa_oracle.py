@@ -14,7 +14,7 @@ from typing import Optional
 
 import numpy as np
 
-from .blocks import Blocks, build_blocks
+from .blocks import Blocks, build_blocks, build_blocks_1d
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ssa_oracle.c")
@@ -187,6 +187,8 @@ class Oracle:
 
 
 def oracle_for(wl, **kw) -> Oracle:
-    """Oracle for a ``paper_2505_17412_amd.inputs.Workload``."""
+    """Oracle for a ``paper_2505_17412_amd.inputs.Workload`` (voxel grid, or sequences when ``wl.dims == 1``)."""
+    if getattr(wl, "dims", 3) == 1:
+        kw = dict(kw, blocks=build_blocks_1d(wl.batch_offsets, wl.m_cmp, wl.m_slc, wl.m_win))
     return Oracle(wl.coords, wl.batch_offsets, wl.grid, wl.m_cmp, wl.m_slc, wl.m_win, wl.topk,
                   wl.n_heads_q, wl.n_heads_kv, wl.head_dim, **kw)

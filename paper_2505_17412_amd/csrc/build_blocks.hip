@@ -146,20 +146,49 @@ struct CsrOut {
 // tile numbers its own tokens and writes all per-token and per-block arrays.
 constexpr int CSR_TILE = 256;
 struct Heads { bool c, s, w; };
-__device__ inline Heads heads_of(const uint64_t *ks, int i, int sc, int ss, int sw) {
-  const uint64_t k = ks[i], p = i == 0 ? 0ull : ks[i - 1];
-  const bool first = i == 0;
-  return Heads{first || (k >> sc) != (p >> sc), first || (k >> ss) != (p >> ss), first || (k >> sw) != (p >> sw)};
-}
 
-__global__ __launch_bounds__(CSR_TILE) void k_csr_count(const uint64_t *__restrict__ ks, int N, int sc, int ss, int sw,
-                                                        int nTiles, uint32_t *__restrict__ tile_cnt) {
+// Where the blocks begin and which item a sorted position belongs to, for the two kinds of partition.
+// Voxel grid: sorted (item << item_shift | Morton) keys; a block of side m is a change of the key above 3*log2(m) bits.
+struct GridSrc {
+  const uint64_t *ks;
+  const uint32_t *vals;  // sorted position -> caller index
+  int sc, ss, sw, item_shift;
+  __device__ Heads heads(int i) const {
+    const uint64_t k = ks[i], p = i == 0 ? 0ull : ks[i - 1];
+    const bool first = i == 0;
+    return Heads{first || (k >> sc) != (p >> sc), first || (k >> ss) != (p >> ss), first || (k >> sw) != (p >> sw)};
+  }
+  __device__ int item(int i) const { return (int)(ks[i] >> item_shift); }
+  __device__ int32_t source(int i) const { return (int32_t)vals[i]; }
+};
+// Sequences: the caller's order is the token order; blocks are runs of lc / ls / lw tokens counted from the start of
+// each sequence (the last one of a sequence may be shorter).
+struct SeqSrc {
+  const int32_t *offs;
+  int B, lc, ls, lw;
+  __device__ int item(int i) const {
+    int lo = 0, hi = B;  // offs[lo] <= i < offs[hi]
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (offs[mid] <= i) lo = mid; else hi = mid;
+    }
+    return lo;
+  }
+  __device__ Heads heads(int i) const {
+    const int pos = i - offs[item(i)];
+    return Heads{pos % lc == 0, pos % ls == 0, pos % lw == 0};
+  }
+  __device__ int32_t source(int i) const { return i; }
+};
+
+template <class Src>
+__global__ __launch_bounds__(CSR_TILE) void k_csr_count(Src src, int N, int nTiles, uint32_t *__restrict__ tile_cnt) {
   __shared__ uint32_t cnt[3];
   if (threadIdx.x < 3) cnt[threadIdx.x] = 0;
   __syncthreads();
   const int i = blockIdx.x * CSR_TILE + threadIdx.x;
   Heads h{false, false, false};
-  if (i < N) h = heads_of(ks, i, sc, ss, sw);
+  if (i < N) h = src.heads(i);
   const uint64_t bc = __ballot(h.c), bs = __ballot(h.s), bw = __ballot(h.w);
   if ((threadIdx.x & 63) == 0) {
     atomicAdd(&cnt[0], (uint32_t)__popcll(bc));
@@ -187,24 +216,23 @@ __global__ __launch_bounds__(256) void k_csr_scan(uint32_t *tile_cnt, int nTiles
   }
 }
 
-__global__ __launch_bounds__(CSR_TILE) void k_csr_write(const uint64_t *__restrict__ ks, const uint32_t *__restrict__ vals, int N,
-                                                        int B, int bits, int sc, int ss, int sw, int nTiles,
+template <class Src>
+__global__ __launch_bounds__(CSR_TILE) void k_csr_write(Src src, int N, int B, int nTiles,
                                                         const uint32_t *__restrict__ tile_base, CsrOut o, int32_t *meta) {
   __shared__ uint32_t part[5];
   const int i = blockIdx.x * CSR_TILE + threadIdx.x;
   Heads h{false, false, false};
-  if (i < N) h = heads_of(ks, i, sc, ss, sw);
+  if (i < N) h = src.heads(i);
   // inclusive head counts up to and including token i
   const int idc = (int)(tile_base[blockIdx.x] + block_exclusive_scan(h.c, part, nullptr) + h.c) - 1;
   const int ids = (int)(tile_base[nTiles + blockIdx.x] + block_exclusive_scan(h.s, part, nullptr) + h.s) - 1;
   const int idw = (int)(tile_base[2 * nTiles + blockIdx.x] + block_exclusive_scan(h.w, part, nullptr) + h.w) - 1;
   if (i >= N) return;
-  const uint64_t k = ks[i];
-  const int item = (int)(k >> (3 * bits));
-  const int pitem = i == 0 ? -1 : (int)(ks[i - 1] >> (3 * bits));
-  const uint32_t src = vals[i];
-  o.perm[i] = (int32_t)src;
-  o.inv_perm[src] = i;
+  const int item = src.item(i);
+  const int pitem = i == 0 ? -1 : src.item(i - 1);
+  const int32_t from = src.source(i);
+  o.perm[i] = from;
+  o.inv_perm[from] = i;
   o.tok_item[i] = item;
   o.tok_cmp[i] = idc;
   o.tok_slc[i] = ids;
@@ -218,6 +246,15 @@ __global__ __launch_bounds__(CSR_TILE) void k_csr_write(const uint64_t *__restri
     o.cmp_start[Nc] = N; o.slc_start[Ns] = N; o.win_start[Nw] = N; o.slc_child_start[Ns] = Nc;
     for (int it = item + 1; it <= B; ++it) { o.cmp_batch[it] = Nc; o.slc_batch[it] = Ns; }
     meta[META_NC] = Nc; meta[META_NS] = Ns; meta[META_NW] = Nw;
+  }
+}
+
+// Validation of the batch offsets alone (the sequence builder has no coordinates to read).
+__global__ void k_check_offsets(const int32_t *__restrict__ offs, int N, int B, int32_t *meta) {
+  for (int j = blockIdx.x * blockDim.x + threadIdx.x; j <= B; j += gridDim.x * blockDim.x) {
+    const int o = offs[j];
+    const bool bad = (j == 0 && o != 0) || (j == B && o != N) || (j > 0 && o < offs[j - 1]) || o < 0 || o > N;
+    if (bad) atomicOr(&meta[META_ERR], 1);
   }
 }
 
@@ -236,17 +273,9 @@ __global__ void k_maxima(CsrOut o, int B, int32_t *meta) {
 
 }  // namespace
 
-extern "C" int ssa_build_blocks(const ssa_params_t *p, const int32_t *coords, const int32_t *batch_offsets,
-                                void *stream_, ssa_blocks_t **out) {
-  if (!p || !out) return SSA_ERR_NULL;
-  *out = nullptr;
-  if (p->n_tokens < 0 || p->n_batch < 1 || p->grid < 1 || p->grid > 1024) return SSA_ERR_BAD_SHAPE;
-  if (p->m_cmp < 1 || p->m_slc < 1 || p->m_win < 1 || p->m_slc <= p->m_cmp || p->m_slc % p->m_cmp != 0)
-    return SSA_ERR_BAD_BLOCK_SIZES;
-  auto pow2 = [](int m) { return (m & (m - 1)) == 0; };
-  if (!pow2(p->m_cmp) || !pow2(p->m_slc) || !pow2(p->m_win)) return SSA_ERR_UNSUPPORTED;
-  if (!batch_offsets || (p->n_tokens > 0 && !coords)) return SSA_ERR_NULL;
-  hipStream_t stream = (hipStream_t)stream_;
+// Common part of the two builders: grid_mode = voxel partition (sort by Morton key), else sequences in caller order.
+static int build_handle(const ssa_params_t *p, const int32_t *coords, const int32_t *batch_offsets, bool grid_mode,
+                        hipStream_t stream, ssa_blocks_t **out) {
   const int N = p->n_tokens, B = p->n_batch;
   int bits = 1;
   while ((1 << bits) < p->grid) ++bits;
@@ -254,7 +283,9 @@ extern "C" int ssa_build_blocks(const ssa_params_t *p, const int32_t *coords, co
   while ((1ll << item_bits) < (long long)B) ++item_bits;
 
   ssa_blocks *h = new ssa_blocks();
-  h->N = N; h->B = B; h->G = p->grid; h->m_cmp = p->m_cmp; h->m_slc = p->m_slc; h->m_win = p->m_win; h->bits = bits;
+  h->N = N; h->B = B; h->G = p->grid; h->m_cmp = p->m_cmp; h->m_slc = p->m_slc; h->m_win = p->m_win;
+  h->bits = grid_mode ? bits : 0;
+  h->dims = grid_mode ? 3 : 1;
   if (hipGetDevice(&h->device) != hipSuccess) { delete h; return SSA_ERR_HIP; }
   const size_t n1 = (size_t)N + 1;
   const size_t ints = 2 * (size_t)N + 6 * (size_t)N + 4 * n1 + (size_t)N + 3 * ((size_t)B + 1) + 64;
@@ -274,7 +305,7 @@ extern "C" int ssa_build_blocks(const ssa_params_t *p, const int32_t *coords, co
   const size_t hist_b = align_up((size_t)256 * (nTiles > 0 ? nTiles : 1) * 4, 256);
   const int csrTiles = (N + CSR_TILE - 1) / CSR_TILE;
   const size_t aux_b = align_up((size_t)(256 + 3 * (csrTiles > 0 ? csrTiles : 1)) * 4, 256);  // digit bases | CSR tile counts
-  const size_t tmp_bytes = 2 * key_b + 2 * val_b + hist_b + aux_b + 256;
+  const size_t tmp_bytes = (grid_mode ? 2 * key_b + 2 * val_b + hist_b : 0) + aux_b + 256;
   auto fail = [&](int code) {
     if (tmp) (void)hipFree(tmp);
     (void)hipFree(h->base);
@@ -283,17 +314,25 @@ extern "C" int ssa_build_blocks(const ssa_params_t *p, const int32_t *coords, co
   };
   if (hipMalloc(&tmp, tmp_bytes) != hipSuccess) return fail(SSA_ERR_HIP);
   char *tp = (char *)tmp;
-  uint64_t *k0 = (uint64_t *)tp; tp += key_b;
-  uint64_t *k1 = (uint64_t *)tp; tp += key_b;
-  uint32_t *v0 = (uint32_t *)tp; tp += val_b;
-  uint32_t *v1 = (uint32_t *)tp; tp += val_b;
-  uint32_t *hist = (uint32_t *)tp; tp += hist_b;
+  uint64_t *k0 = nullptr, *k1 = nullptr;
+  uint32_t *v0 = nullptr, *v1 = nullptr, *hist = nullptr;
+  if (grid_mode) {
+    k0 = (uint64_t *)tp; tp += key_b;
+    k1 = (uint64_t *)tp; tp += key_b;
+    v0 = (uint32_t *)tp; tp += val_b;
+    v1 = (uint32_t *)tp; tp += val_b;
+    hist = (uint32_t *)tp; tp += hist_b;
+  }
   uint32_t *digit_base = (uint32_t *)tp, *tile_cnt = digit_base + 256; tp += aux_b;
   int32_t *meta = (int32_t *)tp;
   if (hipMemsetAsync(meta, 0, 256, stream) != hipSuccess) return fail(SSA_ERR_HIP);
   CsrOut o{h->perm, h->inv_perm, h->tok_item, h->tok_cmp, h->tok_slc, h->tok_win, h->cmp_start, h->slc_start,
            h->win_start, h->slc_child_start, h->cmp_slc, h->cmp_batch, h->slc_batch};
-  if (N > 0) {
+  if (N == 0) {
+    // no tokens: every start array is a single zero; the offsets are still validated (all must be zero)
+    if (hipMemsetAsync(h->base, 0, ints * sizeof(int32_t), stream) != hipSuccess) return fail(SSA_ERR_HIP);
+    k_check_offsets<<<1, 256, 0, stream>>>(batch_offsets, 0, B, meta);
+  } else if (grid_mode) {
     k_make_keys<<<(N + 255) / 256, 256, 0, stream>>>(coords, batch_offsets, N, B, p->grid, bits, k0, v0, meta);
     const int total_bits = 3 * bits + item_bits;
     for (int shift = 0; shift < total_bits; shift += 8) {
@@ -304,18 +343,28 @@ extern "C" int ssa_build_blocks(const ssa_params_t *p, const int32_t *coords, co
       uint64_t *tk = k0; k0 = k1; k1 = tk;
       uint32_t *tv = v0; v0 = v1; v1 = tv;
     }
-    const int sc = 3 * ilog2_exact(p->m_cmp), ss = 3 * ilog2_exact(p->m_slc), sw = 3 * ilog2_exact(p->m_win);
-    k_csr_count<<<csrTiles, CSR_TILE, 0, stream>>>(k0, N, sc, ss, sw, csrTiles, tile_cnt);
+    const GridSrc src{k0, v0, 3 * ilog2_exact(p->m_cmp), 3 * ilog2_exact(p->m_slc), 3 * ilog2_exact(p->m_win), 3 * bits};
+    k_csr_count<<<csrTiles, CSR_TILE, 0, stream>>>(src, N, csrTiles, tile_cnt);
     k_csr_scan<<<1, 256, 0, stream>>>(tile_cnt, csrTiles);
-    k_csr_write<<<csrTiles, CSR_TILE, 0, stream>>>(k0, v0, N, B, bits, sc, ss, sw, csrTiles, tile_cnt, o, meta);
-    const int span = (N > B ? N : B);
-    k_maxima<<<(span + 255) / 256, 256, 0, stream>>>(o, B, meta);
+    k_csr_write<<<csrTiles, CSR_TILE, 0, stream>>>(src, N, B, csrTiles, tile_cnt, o, meta);
     if (hipMemcpyAsync(h->sorted_keys, k0, (size_t)N * sizeof(uint64_t), hipMemcpyDeviceToDevice, stream) != hipSuccess)
       return fail(SSA_ERR_HIP);
   } else {
-    // no tokens: every start array is a single zero; the offsets are still validated (all must be zero)
-    if (hipMemsetAsync(h->base, 0, ints * sizeof(int32_t), stream) != hipSuccess) return fail(SSA_ERR_HIP);
-    k_make_keys<<<1, 256, 0, stream>>>(coords, batch_offsets, 0, B, p->grid, bits, k0, v0, meta);
+    // The offsets are checked first and the result is read back before any kernel searches them: SeqSrc::item assumes
+    // ascending offsets that start at 0 and end at N.
+    k_check_offsets<<<1, 256, 0, stream>>>(batch_offsets, N, B, meta);
+    if (hipMemcpyAsync(meta_h, meta, sizeof(meta_h), hipMemcpyDeviceToHost, stream) != hipSuccess) return fail(SSA_ERR_HIP);
+    if (hipStreamSynchronize(stream) != hipSuccess) return fail(SSA_ERR_HIP);
+    if (meta_h[META_ERR] & 1) return fail(SSA_ERR_BAD_OFFSETS);
+    const SeqSrc src{batch_offsets, B, p->m_cmp, p->m_slc, p->m_win};
+    k_csr_count<<<csrTiles, CSR_TILE, 0, stream>>>(src, N, csrTiles, tile_cnt);
+    k_csr_scan<<<1, 256, 0, stream>>>(tile_cnt, csrTiles);
+    k_csr_write<<<csrTiles, CSR_TILE, 0, stream>>>(src, N, B, csrTiles, tile_cnt, o, meta);
+    if (hipMemsetAsync(h->sorted_keys, 0, (size_t)N * sizeof(uint64_t), stream) != hipSuccess) return fail(SSA_ERR_HIP);
+  }
+  if (N > 0) {
+    const int span = (N > B ? N : B);
+    k_maxima<<<(span + 255) / 256, 256, 0, stream>>>(o, B, meta);
   }
   if (hipMemcpyAsync(h->item_start, batch_offsets, ((size_t)B + 1) * sizeof(int32_t), hipMemcpyDeviceToDevice, stream) !=
       hipSuccess)
@@ -332,6 +381,30 @@ extern "C" int ssa_build_blocks(const ssa_params_t *p, const int32_t *coords, co
   h->win_tok_max = meta_h[META_WIN_TOK]; h->cmp_tok_max = meta_h[META_CMP_TOK];
   *out = h;
   return SSA_OK;
+}
+
+extern "C" int ssa_build_blocks(const ssa_params_t *p, const int32_t *coords, const int32_t *batch_offsets,
+                                void *stream_, ssa_blocks_t **out) {
+  if (!p || !out) return SSA_ERR_NULL;
+  *out = nullptr;
+  if (p->n_tokens < 0 || p->n_batch < 1 || p->grid < 1 || p->grid > 1024) return SSA_ERR_BAD_SHAPE;
+  if (p->m_cmp < 1 || p->m_slc < 1 || p->m_win < 1 || p->m_slc <= p->m_cmp || p->m_slc % p->m_cmp != 0)
+    return SSA_ERR_BAD_BLOCK_SIZES;
+  auto pow2 = [](int m) { return (m & (m - 1)) == 0; };
+  if (!pow2(p->m_cmp) || !pow2(p->m_slc) || !pow2(p->m_win)) return SSA_ERR_UNSUPPORTED;
+  if (!batch_offsets || (p->n_tokens > 0 && !coords)) return SSA_ERR_NULL;
+  return build_handle(p, coords, batch_offsets, true, (hipStream_t)stream_, out);
+}
+
+extern "C" int ssa_build_blocks_1d(const ssa_params_t *p, const int32_t *batch_offsets, void *stream_,
+                                   ssa_blocks_t **out) {
+  if (!p || !out) return SSA_ERR_NULL;
+  *out = nullptr;
+  if (p->n_tokens < 0 || p->n_batch < 1) return SSA_ERR_BAD_SHAPE;
+  if (p->m_cmp < 1 || p->m_slc < 1 || p->m_win < 1 || p->m_slc <= p->m_cmp || p->m_slc % p->m_cmp != 0)
+    return SSA_ERR_BAD_BLOCK_SIZES;
+  if (!batch_offsets) return SSA_ERR_NULL;
+  return build_handle(p, nullptr, batch_offsets, false, (hipStream_t)stream_, out);
 }
 
 extern "C" int ssa_blocks_counts(const ssa_blocks_t *b, int32_t *n_cmp, int32_t *n_slc, int32_t *n_win) {

@@ -433,7 +433,7 @@ int check(const ssa_params_t *p, const ssa_blocks_t *b, int *C) {
   if (!p || !b) return SSA_ERR_NULL;
   if (p->n_tokens != b->N || p->n_batch != b->B || p->grid != b->G || p->m_cmp != b->m_cmp) return SSA_ERR_MISMATCH;
   if (p->n_heads_kv < 1 || p->head_dim < 1) return SSA_ERR_BAD_HEADS;
-  if (p->dtype != SSA_BF16) return SSA_ERR_UNSUPPORTED;
+  if (p->dtype != SSA_BF16 || b->dims != 3) return SSA_ERR_UNSUPPORTED;  // the convolution is defined on the voxel grid
   const long long c = (long long)p->n_heads_kv * p->head_dim;
   if (c != 32 && c != 64 && c != 128 && c != 256) return SSA_ERR_UNSUPPORTED;
   if ((size_t)p->m_cmp * p->m_cmp * p->m_cmp * (size_t)c * 4 > 64 * 1024) return SSA_ERR_UNSUPPORTED;

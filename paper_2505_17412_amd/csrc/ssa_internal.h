@@ -26,6 +26,7 @@ struct ssa_blocks {
   int32_t win_tok_max;  // max tokens in one window
   int32_t cmp_tok_max;  // max tokens in one compression block
   int device;
+  int dims;  // 3: voxel-grid partition (Morton order); 1: sequences in caller order (block sizes are token counts)
   void *base;  // single device allocation holding every array below
   int32_t *perm, *inv_perm, *tok_item, *tok_cmp, *tok_slc, *tok_win;
   int32_t *cmp_start, *slc_start, *win_start, *slc_child_start, *cmp_slc, *cmp_batch, *slc_batch;

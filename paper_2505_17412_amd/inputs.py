@@ -131,6 +131,7 @@ class Workload:
     gates: np.ndarray = field(repr=False, default=None)  # float32 [N,Hq,3], order (cmp, slc, win)
     dout: np.ndarray = field(repr=False, default=None)  # float32 [N,Hq,d]
     seeds: Tuple[int, ...] = ()
+    dims: int = 3  # 3: voxel grid; 1: sequences (coords then hold (0,0,position) and m_* are block lengths in tokens)
 
     @property
     def n_tokens(self) -> int:
@@ -255,4 +256,24 @@ def random_points_workload(
         topk=topk, dtype=dtype, seeds=(seed,),
     )
     wl.q, wl.k, wl.v, wl.gates, wl.dout = draw_tensors(seed, n, hq, hkv, d, dtype)
+    return wl
+
+
+def make_sequence_workload(
+    seed: int, lens: Sequence[int], hq: int = 16, hkv: int = 2, d: int = 64,
+    l: Tuple[int, int, int] = (32, 64, 512), topk: int = 16, dtype: str = "bf16", with_tensors: bool = True,
+) -> Workload:
+    """Sequences of the given lengths with a one-dimensional partition: compression blocks of l[0] tokens, selection
+    blocks of l[1], windows of l[2] (the block sizes of the sequence models whose partition the paper replaces)."""
+    offs = np.concatenate([[0], np.cumsum(np.asarray(lens, dtype=np.int64))]).astype(np.int32)
+    n = int(offs[-1])
+    coords = np.zeros((n, 3), dtype=np.int32)
+    for i in range(len(lens)):
+        coords[offs[i]:offs[i + 1], 2] = np.arange(int(lens[i]), dtype=np.int32)
+    wl = Workload(
+        name="seq1d", grid=0, coords=coords, batch_offsets=offs, n_heads_q=hq, n_heads_kv=hkv, head_dim=d,
+        m_cmp=l[0], m_slc=l[1], m_win=l[2], topk=topk, dtype=dtype, seeds=(seed,), dims=1,
+    )
+    if with_tensors:
+        wl.q, wl.k, wl.v, wl.gates, wl.dout = draw_tensors(seed, n, hq, hkv, d, dtype)
     return wl

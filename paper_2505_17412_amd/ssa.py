@@ -18,7 +18,7 @@ SSA_BF16, SSA_F32 = 0, 1
 ARRAYS = dict(perm=0, inv_perm=1, cmp_start=2, slc_start=3, win_start=4, slc_child_start=5, cmp_batch=6,
               slc_batch=7, tok_win=8)
 EXPORTED_SYMBOLS = (
-    "ssa_build_blocks", "ssa_blocks_counts", "ssa_blocks_max_slc_per_item", "ssa_blocks_export",
+    "ssa_build_blocks", "ssa_build_blocks_1d", "ssa_blocks_counts", "ssa_blocks_max_slc_per_item", "ssa_blocks_export",
     "ssa_blocks_destroy", "ssa_workspace_bytes", "ssa_forward", "ssa_backward", "ssa_topk_from_scores",
     "ssa_error_string", "ssa_profile_enable", "ssa_profile_num_kernels", "ssa_profile_get",
     "ssa_compress_workspace_bytes", "ssa_compress_forward", "ssa_compress_backward", "ssa_forward_pooled",
@@ -52,6 +52,7 @@ def lib() -> C.CDLL:
         L = C.CDLL(_LIB_PATH)
         vp, i32p = C.c_void_p, C.POINTER(C.c_int32)
         L.ssa_build_blocks.argtypes = [C.POINTER(ssa_params_t), vp, vp, vp, C.POINTER(vp)]
+        L.ssa_build_blocks_1d.argtypes = [C.POINTER(ssa_params_t), vp, vp, C.POINTER(vp)]
         L.ssa_blocks_counts.argtypes = [vp, i32p, i32p, i32p]
         L.ssa_blocks_max_slc_per_item.argtypes = [vp, i32p]
         L.ssa_blocks_export.argtypes = [vp, C.c_int, vp, C.c_size_t, vp]
@@ -153,6 +154,14 @@ def ssa_build_blocks(params: ssa_params_t, coords: torch.Tensor, batch_offsets: 
     h = C.c_void_p()
     _check(lib().ssa_build_blocks(C.byref(params), _ptr(coords), _ptr(batch_offsets), _stream(), C.byref(h)),
            "ssa_build_blocks")
+    return Blocks(h.value, params)
+
+
+def ssa_build_blocks_1d(params: ssa_params_t, batch_offsets: torch.Tensor) -> Blocks:
+    """Sequence partition: m_cmp / m_slc / m_win of ``params`` are block lengths in tokens; batch_offsets: cuda int32 [B+1]."""
+    assert batch_offsets.dtype == torch.int32
+    h = C.c_void_p()
+    _check(lib().ssa_build_blocks_1d(C.byref(params), _ptr(batch_offsets), _stream(), C.byref(h)), "ssa_build_blocks_1d")
     return Blocks(h.value, params)
 
 

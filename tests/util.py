@@ -62,6 +62,8 @@ def build_blocks_gpu(wl: inputs.Workload):
     import torch
     from paper_2505_17412_amd import ssa
     p = params_of(wl)
+    if wl.dims == 1:
+        return p, ssa.ssa_build_blocks_1d(p, torch.from_numpy(wl.batch_offsets).cuda())
     coords = torch.from_numpy(wl.coords.reshape(-1, 3)).cuda() if wl.n_tokens else torch.zeros((1, 3), dtype=torch.int32, device="cuda")
     offs = torch.from_numpy(wl.batch_offsets).cuda()
     return p, ssa.ssa_build_blocks(p, coords, offs)
