@@ -292,6 +292,52 @@ def gate_bench(args):
     print(json.dumps(line), flush=True)
 
 
+def linear_bench(args):
+    """One JSON line per projection shape of the layer (hidden -> Hq*d and hidden -> Hkv*d) at the benchmark workload's
+    token count, against the bf16 MFMA roofline: 2*N*d_in*d_out FLOPs forward, twice that backward (dx and dW)."""
+    import torch
+    from paper_2505_17412_amd import inputs, ssa
+
+    torch.cuda.set_device(0)
+    wl = inputs.make_workload(args.workload, with_tensors=False)
+    n = wl.n_tokens
+    dm = wl.n_heads_q * wl.head_dim
+    gen = torch.Generator(device="cuda").manual_seed(13)
+    for d_in, d_out in ((dm, dm), (dm, wl.n_heads_kv * wl.head_dim)):
+        x = torch.randn((n, d_in), generator=gen, device="cuda").bfloat16()
+        w = (torch.randn((d_out, d_in), generator=gen, device="cuda") / d_in ** 0.5).bfloat16()
+        b = torch.randn((d_out,), generator=gen, device="cuda").bfloat16()
+        dy = torch.randn((n, d_out), generator=gen, device="cuda").bfloat16()
+        y = torch.empty((n, d_out), dtype=torch.bfloat16, device="cuda")
+        dx = torch.empty_like(x)
+        dw = torch.empty((d_out, d_in), device="cuda")
+        db = torch.empty((d_out,), device="cuda")
+        ws = torch.empty(ssa.ssa_linear_workspace_bytes(n, d_in, d_out, True), dtype=torch.uint8, device="cuda")
+
+        def step():
+            ssa.ssa_linear_forward(x, w, b, y)
+            ssa.ssa_linear_backward(x, w, dy, dx, dw, db, ws)
+
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        ssa.ssa_profile_enable(True)
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        prof = {nm: tot / cnt for nm, (tot, cnt) in ssa.ssa_profile_get().items()}
+        ssa.ssa_profile_enable(False)
+        flops = 2.0 * n * d_in * d_out
+        line = {"bench": "linear_projection", "workload": args.workload, "n_tokens": n, "d_in": d_in, "d_out": d_out,
+                "fwd_ms": round(prof["linear_fwd"], 4), "bwd_ms": round(prof["linear_bwd"], 4),
+                "fwd_tflops": round(flops / (prof["linear_fwd"] * 1e-3) / 1e12, 1),
+                "bwd_tflops": round(2 * flops / (prof["linear_bwd"] * 1e-3) / 1e12, 1),
+                "fwd_frac_of_mfma_peak": round(flops / (prof["linear_fwd"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                "bwd_frac_of_mfma_peak": round(2 * flops / (prof["linear_bwd"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                "steps": args.steps, "warmup": args.warmup}
+        print(json.dumps(line), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -305,6 +351,7 @@ def main():
     ap.add_argument("--gate", action="store_true", help="instead of the benchmark line: the gate predictor against the HBM roofline")
     ap.add_argument("--cmp-module", action="store_true",
                     help="instead of the benchmark line: the learned compression module alone and inside a training step")
+    ap.add_argument("--linear", action="store_true", help="instead of the benchmark line: the layer's linear projections against the MFMA roofline")
     ap.add_argument("--seq1d", action="store_true", help="instead of the benchmark line: the kernels on a one-dimensional (sequence) partition")
     ap.add_argument("--dense-sweep", action="store_true",
                     help="instead of the benchmark line: sparse path against dense attention over 2.6k-124k tokens")
@@ -317,6 +364,9 @@ def main():
         return
     if args.seq1d:
         seq1d_bench(args)
+        return
+    if args.linear:
+        linear_bench(args)
         return
     if args.cmp_module:
         cmp_module_bench(args)

@@ -220,6 +220,22 @@ int ssa_backward_pooled(const ssa_params_t *params, const ssa_blocks_t *blocks, 
                         size_t workspace_bytes, void *stream);
 
 /*
+ * Linear projections of the attention layer around SSA (the query / key / value / output projections of a DiT block
+ * with hidden dimension 1024, paper Sec. "Implementation Details"; the paper prints no formula): y = x w^T + bias.
+ *   x dev bf16 [N,d_in]; w dev bf16 [d_out,d_in] (one row per output feature); bias dev bf16 [d_out] or NULL;
+ *   y dev bf16 [N,d_out].  Backward: dy dev bf16 [N,d_out]; dx dev bf16 [N,d_in] is overwritten (NULL: not computed);
+ *   dw dev float [d_out,d_in] and dbias dev float [d_out] (NULL: not computed) are overwritten.
+ * bf16 only, fp32 accumulation; d_in and d_out multiples of 128, at most 16384; otherwise UNSUPPORTED.  Forward needs
+ * no workspace; backward needs ssa_linear_workspace_bytes(..., 1) bytes.  Asynchronous on `stream`, allocates nothing.
+ * Errors: NULL, BAD_SHAPE, UNSUPPORTED, WORKSPACE, HIP.
+ */
+size_t ssa_linear_workspace_bytes(int32_t n_tokens, int32_t d_in, int32_t d_out, int for_backward);
+int ssa_linear_forward(int32_t n_tokens, int32_t d_in, int32_t d_out, const void *x, const void *w, const void *bias,
+                       void *y, void *stream);
+int ssa_linear_backward(int32_t n_tokens, int32_t d_in, int32_t d_out, const void *x, const void *w, const void *dy,
+                        void *dx, float *dw, float *dbias, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Gate predictor (text after eq. (4): the gating score of each module is a linear layer followed by a sigmoid on the
  * input features): gates = sigmoid(x w + bias), one linear layer d_model -> 3*Hq.
  *   x dev [N,d_model]; w dev [d_model, 3*Hq]; bias dev [3*Hq]; gates dev [N,Hq,3] (order cmp, slc, win), the

@@ -23,6 +23,7 @@ EXPORTED_SYMBOLS = (
     "ssa_error_string", "ssa_profile_enable", "ssa_profile_num_kernels", "ssa_profile_get",
     "ssa_compress_workspace_bytes", "ssa_compress_forward", "ssa_compress_backward", "ssa_forward_pooled",
     "ssa_backward_pooled", "ssa_gate_workspace_bytes", "ssa_gate_forward", "ssa_gate_backward",
+    "ssa_linear_workspace_bytes", "ssa_linear_forward", "ssa_linear_backward",
 )
 
 
@@ -68,6 +69,10 @@ def lib() -> C.CDLL:
         L.ssa_compress_forward.argtypes = [C.POINTER(ssa_params_t), vp, vp, C.POINTER(ssa_cmp_weights_t), vp, vp, C.c_size_t, vp]
         L.ssa_compress_backward.argtypes = [C.POINTER(ssa_params_t), vp, vp, C.POINTER(ssa_cmp_weights_t)] + [vp] * 5 + \
             [vp, C.c_size_t, vp]
+        L.ssa_linear_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int]
+        L.ssa_linear_workspace_bytes.restype = C.c_size_t
+        L.ssa_linear_forward.argtypes = [C.c_int32] * 3 + [vp] * 5
+        L.ssa_linear_backward.argtypes = [C.c_int32] * 3 + [vp] * 6 + [vp, C.c_size_t, vp]
         L.ssa_gate_workspace_bytes.argtypes = [C.POINTER(ssa_params_t), C.c_int32, C.c_int]
         L.ssa_gate_workspace_bytes.restype = C.c_size_t
         L.ssa_gate_forward.argtypes = [C.POINTER(ssa_params_t), C.c_int32] + [vp] * 4 + [vp, C.c_size_t, vp]
@@ -270,3 +275,23 @@ def ssa_profile_get() -> dict:
         if cnt.value:
             res[name.value.decode()] = (ms.value, cnt.value)
     return res
+
+
+def ssa_linear_workspace_bytes(n_tokens: int, d_in: int, d_out: int, for_backward: bool) -> int:
+    return int(lib().ssa_linear_workspace_bytes(n_tokens, d_in, d_out, int(for_backward)))
+
+
+def ssa_linear_forward(x, w, bias, y) -> None:
+    """y [N,d_out] = x [N,d_in] w[d_out,d_in]^T + bias (bf16 cuda tensors; bias may be None)."""
+    n, d_in = x.shape
+    _check(lib().ssa_linear_forward(n, d_in, w.shape[0], _ptr(x), _ptr(w), _ptr(bias), _ptr(y), _stream()),
+           "ssa_linear_forward")
+
+
+def ssa_linear_backward(x, w, dy, dx, dw, dbias=None, workspace: Optional[torch.Tensor] = None) -> None:
+    n, d_in = x.shape
+    d_out = w.shape[0]
+    if workspace is None:
+        workspace = torch.empty(max(ssa_linear_workspace_bytes(n, d_in, d_out, True), 1), dtype=torch.uint8, device="cuda")
+    _check(lib().ssa_linear_backward(n, d_in, d_out, _ptr(x), _ptr(w), _ptr(dy), _ptr(dx), _ptr(dw), _ptr(dbias),
+                                     _ptr(workspace), workspace.numel(), _stream()), "ssa_linear_backward")
