@@ -338,6 +338,62 @@ def linear_bench(args):
         print(json.dumps(line), flush=True)
 
 
+def layer_bench(args):
+    """One JSON line: a full SSA attention layer (q/k/v projections, gate predictor, attention, output projection;
+    hidden dimension = Hq * d) forward + backward at the benchmark workload, timed as a whole with events on the
+    stream, plus the per-part totals from the library's profiling hook."""
+    import torch
+    from paper_2505_17412_amd import inputs, ssa
+    from tests import util
+
+    torch.cuda.set_device(0)
+    wl = inputs.make_workload(args.workload, with_tensors=False)
+    n, hq, hkv, d = wl.n_tokens, wl.n_heads_q, wl.n_heads_kv, wl.head_dim
+    dm, cq, ckv = hq * d, hq * d, hkv * d
+    p, blk = util.build_blocks_gpu(wl)
+    gen = torch.Generator(device="cuda").manual_seed(17)
+    rnd = lambda *s_, scale=1.0: (torch.randn(s_, generator=gen, device="cuda") * scale).bfloat16()
+    x, dy = rnd(n, dm), rnd(n, dm)
+    w = dict(wq=rnd(cq, dm, scale=dm ** -0.5), wk=rnd(ckv, dm, scale=dm ** -0.5), wv=rnd(ckv, dm, scale=dm ** -0.5),
+             wg=rnd(dm, 3 * hq, scale=dm ** -0.5), bg=rnd(3 * hq), wo=rnd(dm, cq, scale=cq ** -0.5))
+    grads = {"d" + k_: torch.empty(v_.shape, device="cuda") for k_, v_ in w.items()}
+    y, dx = torch.empty_like(x), torch.empty_like(x)
+    saved = torch.empty(ssa.ssa_layer_saved_bytes(p)[0], dtype=torch.uint8, device="cuda")
+    wsf = torch.empty(ssa.ssa_layer_workspace_bytes(p, blk, dm, False), dtype=torch.uint8, device="cuda")
+    wsb = torch.empty(ssa.ssa_layer_workspace_bytes(p, blk, dm, True), dtype=torch.uint8, device="cuda")
+
+    def step():
+        ssa.ssa_layer_forward(p, blk, x, w, y, saved, wsf)
+        ssa.ssa_layer_backward(p, blk, x, w, saved, dy, dx, grads, wsb)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    ssa.ssa_profile_enable(True)
+    for _ in range(3):
+        step()
+    torch.cuda.synchronize()
+    prof = {nm: tot / 3 for nm, (tot, cnt) in ssa.ssa_profile_get().items()}
+    ssa.ssa_profile_enable(False)
+    lin = prof.get("linear_fwd", 0.0) + prof.get("linear_bwd", 0.0)
+    gate = prof.get("gate_fwd", 0.0) + prof.get("gate_bwd", 0.0)
+    attn = sum(v_ for k_, v_ in prof.items() if not k_.startswith(("linear", "gate")))
+    gemm_flops = 6.0 * n * dm * (2 * cq + 2 * ckv)  # forward 2 + backward 4 FLOPs per (token, weight)
+    line = {"bench": "ssa_layer", "workload": args.workload, "n_tokens": n, "d_model": dm, "heads": [hq, hkv], "head_dim": d,
+            "ms_per_layer_step": round(ms, 3), "tokens_per_s": round(n / (ms * 1e-3)),
+            "part_ms": {"projections": round(lin, 3), "gate_predictor": round(gate, 3), "attention": round(attn, 3)},
+            "projection_tflops": round(gemm_flops / (lin * 1e-3) / 1e12, 1) if lin > 0 else None,
+            "saved_activation_mib": round(saved.numel() / 2 ** 20, 1), "steps": args.steps, "warmup": args.warmup}
+    print(json.dumps(line), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -351,6 +407,7 @@ def main():
     ap.add_argument("--gate", action="store_true", help="instead of the benchmark line: the gate predictor against the HBM roofline")
     ap.add_argument("--cmp-module", action="store_true",
                     help="instead of the benchmark line: the learned compression module alone and inside a training step")
+    ap.add_argument("--layer", action="store_true", help="instead of the benchmark line: a full SSA attention layer, forward + backward")
     ap.add_argument("--linear", action="store_true", help="instead of the benchmark line: the layer's linear projections against the MFMA roofline")
     ap.add_argument("--seq1d", action="store_true", help="instead of the benchmark line: the kernels on a one-dimensional (sequence) partition")
     ap.add_argument("--dense-sweep", action="store_true",
@@ -367,6 +424,9 @@ def main():
         return
     if args.linear:
         linear_bench(args)
+        return
+    if args.layer:
+        layer_bench(args)
         return
     if args.cmp_module:
         cmp_module_bench(args)

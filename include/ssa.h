@@ -241,7 +241,7 @@ int ssa_linear_backward(int32_t n_tokens, int32_t d_in, int32_t d_out, const voi
  *   x dev [N,d_model]; w dev [d_model, 3*Hq]; bias dev [3*Hq]; gates dev [N,Hq,3] (order cmp, slc, win), the
  *   tensor ssa_forward takes.  Backward: dgates dev [N,Hq,3] (what ssa_backward writes); the gradient w.r.t. x is
  *   ADDED to dx_accum dev [N,d_model] (in/out); dw dev float [d_model, 3*Hq] and dbias dev float [3*Hq] are
- *   overwritten.  Only n_tokens, n_heads_q and dtype of params are read.
+ *   overwritten (with zeros when there are no tokens).  Only n_tokens, n_heads_q and dtype of params are read.
  * bf16 only; 3*Hq <= 64; d_model a multiple of 128, at most 16384; otherwise UNSUPPORTED.  Asynchronous on `stream`,
  * allocates nothing.  Errors: NULL, BAD_SHAPE, BAD_HEADS, UNSUPPORTED, WORKSPACE, HIP.
  */
@@ -251,6 +251,40 @@ int ssa_gate_forward(const ssa_params_t *params, int32_t d_model, const void *x,
 int ssa_gate_backward(const ssa_params_t *params, int32_t d_model, const void *x, const void *w, const void *gates,
                       const void *dgates, void *dx_accum, float *dw, float *dbias, void *workspace,
                       size_t workspace_bytes, void *stream);
+
+/*
+ * One full SSA attention layer, composed from the entry points above (the paper gives the parts: projections of the
+ * input features to queries, keys and values, gates = sigmoid of a linear layer on the same features, eq. (4), and an
+ * output projection; hidden dimension 1024 in its DiT):
+ *     q = x wq^T (+bq), k = x wk^T (+bk), v = x wv^T (+bv), gates = sigmoid(x wg + bg),
+ *     o = ssa_forward(q, k, v, gates), y = o wo^T (+bo).
+ *   x, y, dy, dx  dev bf16 [N, d_model]
+ *   weights       host struct of dev bf16 pointers: wq [Hq*d, d_model]; wk, wv [Hkv*d, d_model]; wg [d_model, 3*Hq] and
+ *                 bg [3*Hq] (the layout of ssa_gate_forward); wo [d_model, Hq*d]; bq, bk, bv, bo optional (NULL: none)
+ *   saved         dev, ssa_layer_saved_bytes() bytes: the activations forward keeps for backward (q, k, v, gates, o,
+ *                 out_branch, lse, topk_idx: their byte offsets from the 256-byte aligned start of the buffer are
+ *                 returned in `offsets`, 8 entries in that order, when it is not NULL)
+ *   grads         host struct of dev float pointers with the shapes of the weights; dbq, dbk, dbv, dbo optional; all
+ *                 overwritten
+ * bf16 only; d_model, Hq*d and Hkv*d multiples of 128; 3*Hq <= 64.  Asynchronous on `stream`, allocates nothing.
+ * Errors: those of the parts (NULL, BAD_SHAPE, BAD_HEADS, UNSUPPORTED, MISMATCH, WORKSPACE, HIP).
+ */
+typedef struct {
+  const void *wq, *wk, *wv, *wg, *bg, *wo;
+  const void *bq, *bk, *bv, *bo;
+} ssa_layer_weights_t;
+typedef struct {
+  float *dwq, *dwk, *dwv, *dwg, *dbg, *dwo;
+  float *dbq, *dbk, *dbv, *dbo;
+} ssa_layer_grads_t;
+size_t ssa_layer_saved_bytes(const ssa_params_t *params, size_t *offsets);
+size_t ssa_layer_workspace_bytes(const ssa_params_t *params, const ssa_blocks_t *blocks, int32_t d_model, int for_backward);
+int ssa_layer_forward(const ssa_params_t *params, const ssa_blocks_t *blocks, int32_t d_model, const void *x,
+                      const ssa_layer_weights_t *weights, void *y, void *saved, size_t saved_bytes, void *workspace,
+                      size_t workspace_bytes, void *stream);
+int ssa_layer_backward(const ssa_params_t *params, const ssa_blocks_t *blocks, int32_t d_model, const void *x,
+                       const ssa_layer_weights_t *weights, const void *saved, const void *dy, void *dx,
+                       const ssa_layer_grads_t *grads, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Measurement hook (not an operation of the paper; for benchmarks that need the duration of single kernels).

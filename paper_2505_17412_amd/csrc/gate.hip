@@ -296,10 +296,15 @@ extern "C" int ssa_gate_backward(const ssa_params_t *p, int32_t d_model, const v
   const int rc = gate_check(p, d_model, &J);
   if (rc != SSA_OK) return rc;
   const int N = p->n_tokens;
-  if (N == 0) return SSA_OK;
+  hipStream_t s = (hipStream_t)stream;
+  if (N == 0) {  // no tokens: the parameter gradients are zero (a sum over zero partials)
+    if (!dw || !dbias) return SSA_ERR_NULL;
+    g_sum_parts<<<1, 64, 0, s>>>(nullptr, 0, 1, J, dbias);
+    g_sum_parts<<<(unsigned)(((size_t)d_model * J + 255) / 256), 256, 0, s>>>(nullptr, 0, d_model, J, dw);
+    return hipGetLastError() == hipSuccess ? SSA_OK : SSA_ERR_HIP;
+  }
   if (!x || !w || !gates || !dgates || !dx_accum || !dw || !dbias) return SSA_ERR_NULL;
   if (!ws_ || ws_bytes < ssa_gate_workspace_bytes(p, d_model, 1)) return SSA_ERR_WORKSPACE;
-  hipStream_t s = (hipStream_t)stream;
   const GatePlan pl = gate_plan(N, d_model, J, true);
   char *ws = (char *)align_up((size_t)ws_, 256);
   bf16_t *wp = (bf16_t *)(ws + pl.wp), *dz = (bf16_t *)(ws + pl.dz);

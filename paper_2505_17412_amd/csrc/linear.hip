@@ -10,7 +10,7 @@
 //   dx        the same kernel on a transposed copy of the weights (dx = dy W).
 //   dW        dy^T x contracts over tokens: 32-token tiles of dy and x go through LDS row-major and both operands are
 //             transposing LDS reads; the token range is split over workgroups and the fp32 partial tiles are added in a
-//             fixed order.  db = column sums of dy: an all-ones operand in the same kernel, partials added the same way.
+//             fixed order.  db = column sums of dy in two steps (per 64-token chunk, then over the chunks), fixed order.
 // No floating point atomics anywhere.
 #include "mfma_common.h"
 #include "linear_internal.h"
@@ -153,11 +153,8 @@ __global__ __launch_bounds__(256) void lin_transpose(const bf16_t *__restrict__ 
 }
 
 // part[split][o][k] = sum over the split's tokens of dY[t][o] X[t][k]: workgroup = 128 x 128 output tile, one split.
-// bpart (optional) [split][o] = column sums of dY over the split's tokens: one more matrix instruction per feature tile
-// with an all-ones operand, in the wavefronts of the first input-feature tile.
 __global__ __launch_bounds__(256) void lin_tn(const bf16_t *__restrict__ dY, const bf16_t *__restrict__ X, int M, int O,
-                                              int K, int tok_per_split, float *__restrict__ part,
-                                              float *__restrict__ bpart) {
+                                              int K, int tok_per_split, float *__restrict__ part) {
   using G = TileGeom<128>;
   __shared__ __align__(16) bf16_t sy[2][G::ROW_ELEMS], sx[2][G::ROW_ELEMS];
   const int n_kt = K / 128;
@@ -171,13 +168,6 @@ __global__ __launch_bounds__(256) void lin_tn(const bf16_t *__restrict__ dY, con
   for (int oi = 0; oi < 4; ++oi)
 #pragma unroll
     for (int ki = 0; ki < 4; ++ki) acc[oi][ki] = f32x4{0.f, 0.f, 0.f, 0.f};
-  const bool do_bias = bpart != nullptr && kt == 0 && wk == 0;
-  f32x4 accb[4];
-  bf16x8 ones;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) ones[j] = (__bf16)1.0f;
-#pragma unroll
-  for (int oi = 0; oi < 4; ++oi) accb[oi] = f32x4{0.f, 0.f, 0.f, 0.f};
   bf16x8 ry[2], rx[2];
   auto fetch = [&](int t0) {
 #pragma unroll
@@ -212,17 +202,9 @@ __global__ __launch_bounds__(256) void lin_tn(const bf16_t *__restrict__ dY, con
     for (int oi = 0; oi < 4; ++oi)
 #pragma unroll
       for (int ki = 0; ki < 4; ++ki) acc[oi][ki] = mfma16(a[oi], b[ki], acc[oi][ki]);
-    if (do_bias)
-#pragma unroll
-      for (int oi = 0; oi < 4; ++oi) accb[oi] = mfma16(a[oi], ones, accb[oi]);
     if (more) stash(buf ^ 1);
     __syncthreads();
   }
-  if (do_bias && n == 0)  // every column of accb holds the same sums
-#pragma unroll
-    for (int oi = 0; oi < 4; ++oi)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) bpart[(size_t)split * O + o0 + 64 * wo + 16 * oi + 4 * quad + i] = accb[oi][i];
   float *dst = part + (size_t)split * O * K;
 #pragma unroll
   for (int oi = 0; oi < 4; ++oi)
@@ -242,15 +224,69 @@ __global__ void lin_sum_parts(const float *__restrict__ part, int n_parts, size_
   out[j] = s;
 }
 
+// Column sums of dY (the bias gradient) in two steps, both with a fixed order of additions.
+// Step 1: part[chunk][o] = sum of dY[t][o] over the chunk's COLSUM_CHUNK tokens; a thread owns 8 columns and every
+// `phases`-th token, the phases are added in order through LDS.  O % 8 == 0, O / 8 <= 256 or a multiple of 256.
+constexpr int COLSUM_CHUNK = 64;
+__global__ __launch_bounds__(256) void lin_colsum(const bf16_t *__restrict__ dY, int M, int O, float *__restrict__ part) {
+  __shared__ float red[2048];
+  const int cols8 = O / 8;
+  const int phases = cols8 >= 256 ? 1 : 256 / cols8;
+  const int t_begin = blockIdx.x * COLSUM_CHUNK, t_end = min(M, t_begin + COLSUM_CHUNK);
+  for (int cg0 = 0; cg0 < cols8; cg0 += 256) {
+    const int ph = threadIdx.x / cols8, cg = cg0 + threadIdx.x % cols8;
+    const bool active = ph < phases && cg < cols8;
+    float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (active) {
+#pragma unroll 4
+      for (int t = t_begin + ph; t < t_end; t += phases) {
+        const bf16x8 v = ld8(dY + (size_t)t * O + 8 * cg);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s[j] += (float)v[j];
+      }
+    }
+    for (int g = 0; g < phases; ++g) {
+      __syncthreads();
+      if (active && ph == g)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int c = 8 * (cg - cg0) + j;
+          red[c] = g == 0 ? s[j] : red[c] + s[j];
+        }
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < 8 * min(256, cols8 - cg0); c += 256) part[(size_t)blockIdx.x * O + 8 * cg0 + c] = red[c];
+    __syncthreads();
+  }
+}
+// Step 2: out[o] = sum over the parts; a workgroup owns 8 columns, 32 thread rows each add every 32nd part, then the
+// rows are added in order.
+__global__ __launch_bounds__(256) void lin_colsum_finish(const float *__restrict__ part, int n_parts, int O, float *__restrict__ out) {
+  __shared__ float red[32][8];
+  const int col = blockIdx.x * 8 + (threadIdx.x & 7), row = threadIdx.x >> 3;
+  float s = 0.f;
+  if (col < O)
+    for (int p = row; p < n_parts; p += 32) s += part[(size_t)p * O + col];
+  red[row][threadIdx.x & 7] = s;
+  __syncthreads();
+  if (row == 0 && col < O) {
+    float t = 0.f;
+#pragma unroll
+    for (int r = 0; r < 32; ++r) t += red[r][threadIdx.x & 7];
+    out[col] = t;
+  }
+}
+
 struct LinPlan {
-  int splits, tok_per_split;
+  int splits, tok_per_split, bias_parts;
   size_t wt, part, bpart, total;
 };
 
 LinPlan lin_plan(int M, int d_in, int d_out) {
   LinPlan p{};
   const int tiles = (d_out / 128) * (d_in / 128);
-  int s = (512 + tiles - 1) / tiles;  // about two workgroups per compute unit
+  // three workgroups per compute unit; two for skinny outputs, where the traffic of the partial tiles weighs more
+  int s = ((tiles >= 16 ? 768 : 512) + tiles - 1) / tiles;
   const int max_s = (M + 255) / 256;   // at least 256 tokens per split
   if (s > max_s) s = max_s;
   if (s < 1) s = 1;
@@ -260,7 +296,8 @@ LinPlan lin_plan(int M, int d_in, int d_out) {
   size_t off = 0;
   p.wt = off; off += align_up((size_t)d_in * d_out * sizeof(bf16_t), 256);
   p.part = off; off += align_up((size_t)p.splits * d_in * d_out * sizeof(float), 256);
-  p.bpart = off; off += align_up((size_t)p.splits * d_out * sizeof(float), 256);
+  p.bias_parts = M > 0 ? (M + COLSUM_CHUNK - 1) / COLSUM_CHUNK : 1;
+  p.bpart = off; off += align_up((size_t)p.bias_parts * d_out * sizeof(float), 256);
   p.total = off;
   return p;
 }
@@ -299,12 +336,15 @@ size_t lin_dw_workspace(int M, int d_in, int d_out) {
 // dw [d_out][d_in] = dy^T x, dbias (optional) = column sums of dy; ws holds lin_dw_workspace() bytes, 256-byte aligned
 int lin_dw(int M, int d_in, int d_out, const void *x, const void *dy, float *dw, float *dbias, void *ws, hipStream_t s) {
   const LinPlan pl = lin_plan(M, d_in, d_out);
-  float *part = (float *)ws, *bpart = dbias ? (float *)((char *)ws + (pl.bpart - pl.part)) : nullptr;
+  float *part = (float *)ws, *bpart = (float *)((char *)ws + (pl.bpart - pl.part));
   lin_tn<<<dim3((d_out / 128) * (d_in / 128), pl.splits), 256, 0, s>>>((const bf16_t *)dy, (const bf16_t *)x, M, d_out, d_in,
-                                                                     pl.tok_per_split, part, bpart);
+                                                                     pl.tok_per_split, part);
   const size_t len = (size_t)d_in * d_out;
   lin_sum_parts<<<(unsigned)((len + 255) / 256), 256, 0, s>>>(part, pl.splits, len, dw);
-  if (dbias) lin_sum_parts<<<(d_out + 255) / 256, 256, 0, s>>>(bpart, pl.splits, (size_t)d_out, dbias);
+  if (dbias) {
+    lin_colsum<<<pl.bias_parts, 256, 0, s>>>((const bf16_t *)dy, M, d_out, bpart);
+    lin_colsum_finish<<<(d_out + 7) / 8, 256, 0, s>>>(bpart, pl.bias_parts, d_out, dbias);
+  }
   return SSA_OK;
 }
 

@@ -24,7 +24,16 @@ EXPORTED_SYMBOLS = (
     "ssa_compress_workspace_bytes", "ssa_compress_forward", "ssa_compress_backward", "ssa_forward_pooled",
     "ssa_backward_pooled", "ssa_gate_workspace_bytes", "ssa_gate_forward", "ssa_gate_backward",
     "ssa_linear_workspace_bytes", "ssa_linear_forward", "ssa_linear_backward",
+    "ssa_layer_saved_bytes", "ssa_layer_workspace_bytes", "ssa_layer_forward", "ssa_layer_backward",
 )
+
+
+class ssa_layer_weights_t(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("wq", "wk", "wv", "wg", "bg", "wo", "bq", "bk", "bv", "bo")]
+
+
+class ssa_layer_grads_t(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("dwq", "dwk", "dwv", "dwg", "dbg", "dwo", "dbq", "dbk", "dbv", "dbo")]
 
 
 class ssa_params_t(C.Structure):
@@ -73,6 +82,12 @@ def lib() -> C.CDLL:
         L.ssa_linear_workspace_bytes.restype = C.c_size_t
         L.ssa_linear_forward.argtypes = [C.c_int32] * 3 + [vp] * 5
         L.ssa_linear_backward.argtypes = [C.c_int32] * 3 + [vp] * 6 + [vp, C.c_size_t, vp]
+        L.ssa_layer_saved_bytes.argtypes = [C.POINTER(ssa_params_t), C.POINTER(C.c_size_t)]
+        L.ssa_layer_saved_bytes.restype = C.c_size_t
+        L.ssa_layer_workspace_bytes.argtypes = [C.POINTER(ssa_params_t), vp, C.c_int32, C.c_int]
+        L.ssa_layer_workspace_bytes.restype = C.c_size_t
+        L.ssa_layer_forward.argtypes = [C.POINTER(ssa_params_t), vp, C.c_int32, vp, C.POINTER(ssa_layer_weights_t), vp, vp, C.c_size_t, vp, C.c_size_t, vp]
+        L.ssa_layer_backward.argtypes = [C.POINTER(ssa_params_t), vp, C.c_int32, vp, C.POINTER(ssa_layer_weights_t), vp, vp, vp, C.POINTER(ssa_layer_grads_t), vp, C.c_size_t, vp]
         L.ssa_gate_workspace_bytes.argtypes = [C.POINTER(ssa_params_t), C.c_int32, C.c_int]
         L.ssa_gate_workspace_bytes.restype = C.c_size_t
         L.ssa_gate_forward.argtypes = [C.POINTER(ssa_params_t), C.c_int32] + [vp] * 4 + [vp, C.c_size_t, vp]
@@ -295,3 +310,43 @@ def ssa_linear_backward(x, w, dy, dx, dw, dbias=None, workspace: Optional[torch.
         workspace = torch.empty(max(ssa_linear_workspace_bytes(n, d_in, d_out, True), 1), dtype=torch.uint8, device="cuda")
     _check(lib().ssa_linear_backward(n, d_in, d_out, _ptr(x), _ptr(w), _ptr(dy), _ptr(dx), _ptr(dw), _ptr(dbias),
                                      _ptr(workspace), workspace.numel(), _stream()), "ssa_linear_backward")
+
+
+LAYER_SAVED = ("q", "k", "v", "gates", "o", "out_branch", "lse", "topk_idx")
+
+
+def ssa_layer_saved_bytes(params: ssa_params_t):
+    """(bytes, {name: byte offset from the 256-byte aligned start}) of the activations the layer keeps for backward."""
+    offs = (C.c_size_t * 8)()
+    n = int(lib().ssa_layer_saved_bytes(C.byref(params), offs))
+    return n, dict(zip(LAYER_SAVED, (int(o) for o in offs)))
+
+
+def ssa_layer_workspace_bytes(params: ssa_params_t, blocks: Blocks, d_model: int, for_backward: bool) -> int:
+    return int(lib().ssa_layer_workspace_bytes(C.byref(params), blocks.handle, d_model, int(for_backward)))
+
+
+def _layer_struct(cls, tensors: dict):
+    return cls(**{k: _ptr(tensors.get(k)) for k, _ in cls._fields_})
+
+
+def ssa_layer_forward(params, blocks: Blocks, x, weights: dict, y, saved, workspace: Optional[torch.Tensor] = None) -> None:
+    """weights: dict of cuda bf16 tensors wq, wk, wv, wg, bg, wo (+ optional bq, bk, bv, bo)."""
+    d_model = x.shape[1]
+    if workspace is None:
+        workspace = torch.empty(max(ssa_layer_workspace_bytes(params, blocks, d_model, False), 1), dtype=torch.uint8, device="cuda")
+    w = _layer_struct(ssa_layer_weights_t, weights)
+    _check(lib().ssa_layer_forward(C.byref(params), blocks.handle, d_model, _ptr(x), C.byref(w), _ptr(y), _ptr(saved),
+                                   saved.numel(), _ptr(workspace), workspace.numel(), _stream()), "ssa_layer_forward")
+
+
+def ssa_layer_backward(params, blocks: Blocks, x, weights: dict, saved, dy, dx, grads: dict,
+                       workspace: Optional[torch.Tensor] = None) -> None:
+    """grads: dict of cuda float tensors dwq, dwk, dwv, dwg, dbg, dwo (+ optional dbq, dbk, dbv, dbo), overwritten."""
+    d_model = x.shape[1]
+    if workspace is None:
+        workspace = torch.empty(max(ssa_layer_workspace_bytes(params, blocks, d_model, True), 1), dtype=torch.uint8, device="cuda")
+    w = _layer_struct(ssa_layer_weights_t, weights)
+    g = _layer_struct(ssa_layer_grads_t, grads)
+    _check(lib().ssa_layer_backward(C.byref(params), blocks.handle, d_model, _ptr(x), C.byref(w), _ptr(saved), _ptr(dy),
+                                    _ptr(dx), C.byref(g), _ptr(workspace), workspace.numel(), _stream()), "ssa_layer_backward")

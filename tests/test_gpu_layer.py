@@ -1,0 +1,119 @@
+"""GPU: the full SSA attention layer (projections, gate predictor, attention, output projection) against the chained
+fp64 oracle.  Forward is checked stage by stage: every stage of the oracle is fed the bf16 tensor the HIP path saved for
+the stage before, so each comparison sees one stage's arithmetic (tolerances of the attention path).  Backward is
+checked end to end against the oracle chain started from the saved activations (the intermediate gradients dO, dq, dk,
+dv, dgates are bf16 on the HIP side; the same tolerances still hold for every result)."""
+import numpy as np
+import pytest
+
+from oracle.gate import gate_forward
+from oracle.layer import LayerForward, LayerWeights, layer_backward
+from oracle.linear import linear_forward
+from oracle.ssa_oracle import oracle_for
+from paper_2505_17412_amd import inputs
+from tests import util
+
+pytestmark = pytest.mark.gpu
+
+W_NAMES = ("wq", "wk", "wv", "wg", "bg", "wo", "bq", "bk", "bv", "bo")
+
+
+def make_weights(rng, dm, cq, ckv, hq, biases):
+    r = inputs.round_to_bf16
+    g = lambda *s: rng.standard_normal(s).astype(np.float32)
+    w = dict(wq=r(g(cq, dm) / np.sqrt(dm)), wk=r(g(ckv, dm) / np.sqrt(dm)), wv=r(g(ckv, dm) / np.sqrt(dm)),
+             wg=r(g(dm, 3 * hq) / np.sqrt(dm)), bg=r(g(3 * hq)), wo=r(g(dm, cq) / np.sqrt(cq)))
+    if biases:
+        w.update(bq=r(g(cq) * 0.1), bk=r(g(ckv) * 0.1), bv=r(g(ckv) * 0.1), bo=r(g(dm) * 0.1))
+    return w
+
+
+@pytest.mark.parametrize("seed,grid,n,hq,hkv,d,dm,topk,biases", [
+    (81, 16, (700, 450), 16, 2, 64, 256, 4, True),
+    (82, 32, (1500,), 16, 2, 64, 1024, 6, False),     # the paper's layer shape: hidden 1024, 16 heads of 64, 2 KV heads
+    (83, 16, (300, 0, 333), 8, 1, 128, 128, 3, True),
+])
+def test_layer_forward_backward(seed, grid, n, hq, hkv, d, dm, topk, biases):
+    import torch
+    from paper_2505_17412_amd import ssa
+    print("layer", seed, n, hq, hkv, d, dm, flush=True)
+    wl = inputs.random_points_workload(seed, grid, n, hq, hkv, d, (4, 8, 8), topk, "bf16")
+    N, cq, ckv = wl.n_tokens, hq * d, hkv * d
+    rng = np.random.default_rng(seed)
+    r = inputs.round_to_bf16
+    x = r(rng.standard_normal((N, dm)).astype(np.float32))
+    dy = r(rng.standard_normal((N, dm)).astype(np.float32))
+    w = make_weights(rng, dm, cq, ckv, hq, biases)
+    p, blk = util.build_blocks_gpu(wl)
+    tw = {k: util.to_dev(v, "bf16") for k, v in w.items()}
+    tx, tdy = util.to_dev(x, "bf16"), util.to_dev(dy, "bf16")
+    nbytes, offs = ssa.ssa_layer_saved_bytes(p)
+    saved = torch.zeros(nbytes + 256, dtype=torch.uint8, device="cuda")
+    y = torch.full((N, dm), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ssa.ssa_layer_forward(p, blk, tx, tw, y, saved)
+    torch.cuda.synchronize()
+    base = (-saved.data_ptr()) % 256
+
+    def view(name, shape, dtype):
+        nb = int(np.prod(shape)) * torch.empty((), dtype=dtype).element_size()
+        return saved[base + offs[name]: base + offs[name] + nb].view(dtype).view(*shape)
+
+    q = util.to_np(view("q", (N, hq, d), torch.bfloat16))
+    k = util.to_np(view("k", (N, hkv, d), torch.bfloat16))
+    v = util.to_np(view("v", (N, hkv, d), torch.bfloat16))
+    gates = util.to_np(view("gates", (N, hq, 3), torch.bfloat16))
+    o = util.to_np(view("o", (N, hq, d), torch.bfloat16))
+    ob = util.to_np(view("out_branch", (3, N, hq, d), torch.bfloat16))
+    lse = util.to_np(view("lse", (3, N, hq), torch.float32))
+    idx = util.to_np(view("topk_idx", (N, hkv, topk), torch.int32))
+    # ---- forward, stage by stage
+    util.assert_close(q.reshape(N, cq), linear_forward(x, w["wq"], w.get("bq")), "bf16", "q")
+    util.assert_close(k.reshape(N, ckv), linear_forward(x, w["wk"], w.get("bk")), "bf16", "k")
+    util.assert_close(v.reshape(N, ckv), linear_forward(x, w["wv"], w.get("bv")), "bf16", "v")
+    util.assert_close(gates.reshape(N, 3 * hq), gate_forward(x, w["wg"], w["bg"]), "bf16", "gates")
+    orc = oracle_for(wl)
+    own = orc.forward(q, k, v, gates, want_scores=True)
+    util.check_topk(idx, own, orc, "bf16")
+    ref = orc.forward(q, k, v, gates, topk_idx=idx)
+    util.assert_close(o, ref.out, "bf16", "attention out")
+    for b in range(3):
+        util.assert_close(ob[b], ref.out_branch[b], "bf16", f"out_branch {b}")
+        util.assert_close(lse[b], ref.lse[b], "bf16", f"lse {b}")
+    util.assert_close(util.to_np(y), linear_forward(o.reshape(N, cq), w["wo"], w.get("bo")), "bf16", "y")
+    # ---- backward, end to end from the saved activations
+    g_names = ["dwq", "dwk", "dwv", "dwg", "dbg", "dwo"] + (["dbq", "dbk", "dbv", "dbo"] if biases else [])
+    grads = {nm: torch.full(w[nm[1:]].shape, float("nan"), dtype=torch.float32, device="cuda") for nm in g_names}
+    dx = torch.full((N, dm), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ssa.ssa_layer_backward(p, blk, tx, tw, saved, tdy, dx, grads)
+    torch.cuda.synchronize()
+    lw = LayerWeights(**{nm: w.get(nm) for nm in W_NAMES})
+    ref.out = o  # the oracle chain starts from what the HIP path saved (and rounded)
+    ref.out_branch = ob
+    rb = layer_backward(orc, x, lw, LayerForward(q, k, v, gates, ref, None), dy)
+    errs = {"dx": util.assert_close(util.to_np(dx), rb["dx"], "bf16", "dx")}
+    for nm in g_names:
+        if nm == "dbk":
+            # Adding one vector to every key shifts all scores of a query alike and leaves every softmax unchanged: the
+            # exact gradient is zero, and both sides hold only rounding noise of the column sums of dk.
+            bound = 2e-3 * np.abs(rb["dk"]).reshape(N, ckv).sum(axis=0)
+            assert np.all(np.abs(util.to_np(grads[nm])) <= bound), nm
+            continue
+        errs[nm] = util.assert_close(util.to_np(grads[nm]), rb[nm], "bf16", nm)
+    print("  errors:", {k_: f"{v_[0]:.1e}/{v_[1]:.1e}" for k_, v_ in errs.items()}, flush=True)
+
+
+def test_layer_validation():
+    import torch
+    from paper_2505_17412_amd import ssa
+    wl = inputs.random_points_workload(5, 8, (64,), 4, 2, 32, (2, 4, 4), 2, "bf16")   # Hkv*d = 64: not a multiple of 128
+    p, blk = util.build_blocks_gpu(wl)
+    assert ssa.ssa_layer_workspace_bytes(p, blk, 128, False) == 0
+    wl = inputs.random_points_workload(5, 8, (64,), 4, 2, 64, (2, 4, 4), 2, "bf16")
+    p, blk = util.build_blocks_gpu(wl)
+    assert ssa.ssa_layer_workspace_bytes(p, blk, 100, False) == 0                     # d_model not a multiple of 128
+    assert ssa.ssa_layer_workspace_bytes(p, blk, 128, True) > 0
+    x = torch.zeros((64, 128), dtype=torch.bfloat16, device="cuda")
+    w = {k: x for k in ("wq", "wk", "wv", "wg", "bg", "wo")}
+    with pytest.raises(ssa.SSAError) as e:
+        ssa.ssa_layer_forward(p, blk, x, w, x, torch.empty(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == -7
