@@ -400,6 +400,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="g128")
+    ap.add_argument("--heads", default=None, help="HQ,HKV,D: another head shape on the same tokens (context figures; the default is the benchmark configuration)")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="target CPU time of the oracle baseline leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -440,7 +441,11 @@ def main():
     from paper_2505_17412_amd import inputs, ssa
     from tests import util
 
-    wl = inputs.make_workload(args.workload)
+    over = {}
+    if args.heads:
+        h = [int(t) for t in args.heads.split(",")]
+        over = dict(hq=h[0], hkv=h[1], d=h[2])
+    wl = inputs.make_workload(args.workload, **over)
     n, hq, hkv, d, T = wl.n_tokens, wl.n_heads_q, wl.n_heads_kv, wl.head_dim, wl.topk
     torch.cuda.set_device(0)
     p, blk = util.build_blocks_gpu(wl)

@@ -357,6 +357,11 @@ int forward_t(const ssa_ctx &c, const void *q, const void *k, const void *v, con
   return hipGetLastError() == hipSuccess ? SSA_OK : SSA_ERR_HIP;
 }
 
+__global__ void g_zero_f32(float *p, size_t n) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0.f;
+}
+
 template <typename T>
 int backward_t(const ssa_ctx &c, const void *q, const void *k, const void *v, const void *gates, const void *out_branch,
                const float *lse, const int32_t *topk_idx, const void *dout, void *dq, void *dk, void *dv, void *dgates,
@@ -367,8 +372,9 @@ int backward_t(const ssa_ctx &c, const void *q, const void *k, const void *v, co
   float *delta = (float *)(ws + p.delta);
   float *dKs = (float *)(ws + p.dks), *dVs = (float *)(ws + p.dvs), *dKc = (float *)(ws + p.dkc), *dVc = (float *)(ws + p.dvc);
   const int N = c.N, row = c.Hkv * c.d;
-  // the four accumulators are contiguous in the plan
-  SSA_HIP_TRY(hipMemsetAsync(dKs, 0, (p.total - p.dks), c.stream));
+  // the four accumulators are contiguous in the plan; cleared by a kernel, so that a caller may capture the call in a graph
+  const size_t n_acc = (p.total - p.dks) / sizeof(float);
+  g_zero_f32<<<(unsigned)((n_acc + 255) / 256), 256, 0, c.stream>>>(dKs, n_acc);
   g_sort_pool<T><<<c.blk->Nc, 256, 0, c.stream>>>((const T *)k, (const T *)v, bv, row, Ks, Vs, Kc, Vc);
   g_bwd_pre<T><<<N * c.Hq, WAVE, 0, c.stream>>>((const T *)dout, (const T *)out_branch, (const T *)gates, (size_t)N, c.Hq, c.d,
                                                 (T *)dgates, delta);
