@@ -394,6 +394,39 @@ def layer_bench(args):
     print(json.dumps(line), flush=True)
 
 
+def ablation_sweep(args):
+    """Stress workload (thick shell, ~150k tokens, head_dim 128): top-k in {8, 16, 32} x window side in {4, 8}, one
+    JSON line each with every branch's forward+backward time and its algorithmic TFLOP/s against the MFMA peak."""
+    torch, inputs, ssa, util = _imports()
+    torch.cuda.set_device(0)
+    for topk in (8, 16, 32):
+        for m_win in (4, 8):
+            wl = inputs.make_workload("g128_thick", topk=topk, m=(4, 8, m_win))
+            n, d = wl.n_tokens, wl.head_dim
+            ks, arrays, sel = kernel_times(wl, 2)
+            pairs = algorithmic_flops(wl, arrays, sel)
+            # the window and selection branches share the dQ launch: its time is split by their pair counts
+            dq_sw = ks["bwd_dq_slc_win"]
+            f_s = pairs["slc"] / max(pairs["slc"] + pairs["win"], 1)
+            branch_ms = {
+                "cmp": ks["cmp_fwd_scores_topk"] + ks["bwd_dq_cmp"] + ks["bwd_dkv_cmp"],
+                "slc": ks["slc_fwd"] + dq_sw * f_s + ks["bwd_dkv_slc"] + ks["bwd_invert_selection"],
+                "win": ks["win_fwd"] + dq_sw * (1 - f_s) + ks["bwd_dkv_win"],
+            }
+            other = sum(ks.values()) + ks["prep_sort_pool"] - sum(branch_ms.values())
+            total = sum(branch_ms.values()) + other
+            tf = {b: 14 * d * pairs[b] / (branch_ms[b] * 1e-3) / 1e12 for b in branch_ms}
+            line = {"bench": "stress_ablation", "workload": "g128_thick", "n_tokens": n, "head_dim": d,
+                    "heads": [wl.n_heads_q, wl.n_heads_kv], "topk": topk, "m_win": m_win,
+                    "fwd_bwd_ms": round(total, 3), "tokens_per_s": round(n / (total * 1e-3)),
+                    "branch_ms": {b: round(v_, 3) for b, v_ in branch_ms.items()}, "other_ms": round(other, 3),
+                    "branch_tflops": {b: round(v_, 1) for b, v_ in tf.items()},
+                    "branch_frac_of_mfma_peak": {b: round(v_ / MFMA_BF16_PEAK_TFLOPS, 4) for b, v_ in tf.items()},
+                    "whole_step_frac_of_mfma_peak": round(14 * d * sum(pairs[b] for b in branch_ms) / (total * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                    "kernel_ms": {k_: round(v_, 3) for k_, v_ in ks.items()}}
+            print(json.dumps(line), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -408,6 +441,7 @@ def main():
     ap.add_argument("--gate", action="store_true", help="instead of the benchmark line: the gate predictor against the HBM roofline")
     ap.add_argument("--cmp-module", action="store_true",
                     help="instead of the benchmark line: the learned compression module alone and inside a training step")
+    ap.add_argument("--ablation", action="store_true", help="instead of the benchmark line: the stress workload, top-k x window sweep with per-branch figures")
     ap.add_argument("--layer", action="store_true", help="instead of the benchmark line: a full SSA attention layer, forward + backward")
     ap.add_argument("--linear", action="store_true", help="instead of the benchmark line: the layer's linear projections against the MFMA roofline")
     ap.add_argument("--seq1d", action="store_true", help="instead of the benchmark line: the kernels on a one-dimensional (sequence) partition")
@@ -428,6 +462,9 @@ def main():
         return
     if args.layer:
         layer_bench(args)
+        return
+    if args.ablation:
+        ablation_sweep(args)
         return
     if args.cmp_module:
         cmp_module_bench(args)
