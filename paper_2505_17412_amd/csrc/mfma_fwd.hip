@@ -236,31 +236,42 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
       ks0[cb] = ok ? a.v.slc_batch[item] : 0;
       owner[cb] = (4 * quad) % hs == 0;
     }
-    run_pipeline<D, 1>(
-        ksrc, stage0, ints + 4, ints + 5, nr, [](int) {},
-        [&](const bf16_t *stg, int kb, int) {
+    // two consecutive 32-key tiles per step: half the barriers and staging rounds of a walk that has little work per key
+    TileSrc<2> ksrc2{{a.v.Kc + (size_t)g * D, a.v.Kc + (size_t)g * D + (size_t)32 * a.v.Hkv * D}, (uint32_t)(a.v.Hkv * D)};
+    run_pipeline<D, 2, 256, 2, 64>(
+        ksrc2, stage0, ints + 4, ints + 5, nr, [](int) {},
+        [&](const bf16_t *stg2, int kb2, int) {
 #pragma unroll
-          for (int sub = 0; sub < 2; ++sub) {
-            f32x4 c[CB];
+          for (int half = 0; half < 2; ++half) {
+            const bf16_t *stg = L::row_tile((bf16_t *)stg2, half);
+            const int kb = kb2 + 32 * half;
+            // the selection block of this lane's key in either sub-tile, requested before the matrix instructions
+            int sblk[2];
 #pragma unroll
-            for (int cb = 0; cb < CB; ++cb) c[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int sub = 0; sub < 2; ++sub) sblk[sub] = a.v.cmp_slc[min(tile_key_row(kb, sub), a.v.Nc - 1)];
 #pragma unroll
-            for (int ks = 0; ks < D / 32; ++ks) {
-              const bf16x8 kop =
-                  *reinterpret_cast<const bf16x8 *>(stg + TileGeom<D>::slot_off(16 * sub + n, 4 * ks + quad));
+            for (int sub = 0; sub < 2; ++sub) {
+              f32x4 c[CB];
 #pragma unroll
-              for (int cb = 0; cb < CB; ++cb) c[cb] = mfma16(q.qop[cb][ks], kop, c[cb]);
-            }
-            const int key = tile_key_row(kb, sub);  // column n of sub-tile `sub` sits in row slot 16*sub + n
+              for (int cb = 0; cb < CB; ++cb) c[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int cb = 0; cb < CB; ++cb) {
-              float t = 0.f;
+              for (int ks = 0; ks < D / 32; ++ks) {
+                const bf16x8 kop =
+                    *reinterpret_cast<const bf16x8 *>(stg + TileGeom<D>::slot_off(16 * sub + n, 4 * ks + quad));
 #pragma unroll
-              for (int i = 0; i < 4; ++i) t += fast_exp2(__builtin_fmaf(c[cb][i], sl2, -l4[cb][i]));
-              if (hs >= 8) t += __shfl_xor(t, 16);
-              if (hs >= 16) t += __shfl_xor(t, 32);
-              if (owner[cb] && key >= klo[cb] && key < khi[cb])
-                atomicAdd(&S[(size_t)kslot[cb] * s_max + a.v.cmp_slc[key] - ks0[cb]], (uint32_t)(t * SCORE_FIX));
+                for (int cb = 0; cb < CB; ++cb) c[cb] = mfma16(q.qop[cb][ks], kop, c[cb]);
+              }
+              const int key = tile_key_row(kb, sub);  // column n of sub-tile `sub` sits in row slot 16*sub + n
+#pragma unroll
+              for (int cb = 0; cb < CB; ++cb) {
+                float t = 0.f;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) t += fast_exp2(__builtin_fmaf(c[cb][i], sl2, -l4[cb][i]));
+                if (hs >= 8) t += __shfl_xor(t, 16);
+                if (hs >= 16) t += __shfl_xor(t, 32);
+                if (owner[cb] && key >= klo[cb] && key < khi[cb])
+                  atomicAdd(&S[(size_t)kslot[cb] * s_max + sblk[sub] - ks0[cb]], (uint32_t)(t * SCORE_FIX));
+              }
             }
           }
         });

@@ -122,8 +122,8 @@ __device__ inline TileIter iter_begin(const int *rng_s, const int *rng_e, int nr
   }
   return it;
 }
-__device__ inline TileIter iter_next(TileIter it, const int *rng_s, const int *rng_e, int nr) {
-  it.kb += 32;
+__device__ inline TileIter iter_next(TileIter it, const int *rng_s, const int *rng_e, int nr, int step = 32) {
+  it.kb += step;
   if (it.kb >= it.end) {
     ++it.r;
     if (it.r < nr) {
@@ -186,7 +186,8 @@ __device__ inline void load_rows(const bf16_t *Q, const MfmaView &v, int wg_pos0
 // ahead of the tile being consumed, through PF register sets used alternately; LDS holds two stages: the stage
 // written at step i is read at step i and overwritten at step i+2, with one barrier per step in between.
 // enter(r) runs when the walk reaches range r, tile(stage, kb, r) consumes one staged tile.
-template <int D, int NROW, int NTHR = 256, int PF = 2, class Enter, class Tile>
+// STEP: key rows consumed per step (32, or 64 when the tile set holds two consecutive 32-row tiles of one array).
+template <int D, int NROW, int NTHR = 256, int PF = 2, int STEP = 32, class Enter, class Tile>
 __device__ inline void run_pipeline(const TileSrc<NROW> &src, bf16_t *stage0, const int *rng_s, const int *rng_e, int nr,
                                     Enter enter, Tile tile) {
   using L = StageLayout<D, NROW>;
@@ -196,7 +197,7 @@ __device__ inline void run_pipeline(const TileSrc<NROW> &src, bf16_t *stage0, co
     TileIter ahead = cur;  // the last tile whose loads are in flight
     tile_load<D, NROW, NTHR>(regs[0], src, cur.kb);
     if (PF == 2) {
-      ahead = iter_next(cur, rng_s, rng_e, nr);
+      ahead = iter_next(cur, rng_s, rng_e, nr, STEP);
       if (ahead.r < nr) tile_load<D, NROW, NTHR>(regs[PF - 1], src, ahead.kb);
     }
     int buf = 0, cur_r = -1;
@@ -204,7 +205,7 @@ __device__ inline void run_pipeline(const TileSrc<NROW> &src, bf16_t *stage0, co
       bf16_t *st = stage0 + buf * L::ELEMS;
       tile_store<D, NROW, NTHR>(r, st);
       // the request for the tile PF steps ahead goes out while the LDS writes drain, before the barrier waits for them
-      if (ahead.r < nr) ahead = iter_next(ahead, rng_s, rng_e, nr);
+      if (ahead.r < nr) ahead = iter_next(ahead, rng_s, rng_e, nr, STEP);
       if (ahead.r < nr) tile_load<D, NROW, NTHR>(r, src, ahead.kb);
       __syncthreads();
       if (cur.r != cur_r) {
@@ -212,7 +213,7 @@ __device__ inline void run_pipeline(const TileSrc<NROW> &src, bf16_t *stage0, co
         enter(cur_r);
       }
       tile(st, cur.kb, cur_r);
-      cur = iter_next(cur, rng_s, rng_e, nr);
+      cur = iter_next(cur, rng_s, rng_e, nr, STEP);
       buf ^= 1;
     };
     while (cur.r < nr) {
