@@ -217,7 +217,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
     TileSrc<2> src = branch == 0
         ? TileSrc<2>{{a.v.Kc + (size_t)g * D, a.v.Vc + (size_t)g * D}, (uint32_t)kstride}
         : TileSrc<2>{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, (uint32_t)kstride};
-    run_pipeline<D, 2, 64 * NW, 1>(
+    run_pipeline<D, 2, 64 * NW, (PART == 0 ? 2 : 1)>(
         src, stage0, ints + 4, ints + 5, re > rs ? 1 : 0, [](int) {},
         [&](const bf16_t *stg, int kb, int) {
           bf16_t *st = (bf16_t *)stg;
