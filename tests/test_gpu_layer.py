@@ -117,3 +117,23 @@ def test_layer_validation():
     with pytest.raises(ssa.SSAError) as e:
         ssa.ssa_layer_forward(p, blk, x, w, x, torch.empty(16, dtype=torch.uint8, device="cuda"))
     assert e.value.status == -7
+
+
+def test_layer_without_tokens():
+    """No tokens: forward writes nothing, backward leaves zero parameter gradients."""
+    import torch
+    from paper_2505_17412_amd import ssa
+    p = ssa.make_params(0, 2, 8, 2, 4, 4, 2, 4, 2, 64, "bf16")
+    blk = ssa.ssa_build_blocks(p, torch.zeros((1, 3), dtype=torch.int32, device="cuda"),
+                               torch.zeros(3, dtype=torch.int32, device="cuda"))
+    dm, cq, ckv, hq = 128, 256, 128, 4
+    z = lambda *s_: torch.zeros(s_, dtype=torch.bfloat16, device="cuda")
+    w = dict(wq=z(cq, dm), wk=z(ckv, dm), wv=z(ckv, dm), wg=z(dm, 3 * hq), bg=z(3 * hq), wo=z(dm, cq))
+    x = z(0, dm)
+    saved = torch.empty(max(ssa.ssa_layer_saved_bytes(p)[0], 1), dtype=torch.uint8, device="cuda")
+    ssa.ssa_layer_forward(p, blk, x, w, x, saved)
+    grads = {"d" + k_: torch.full(v_.shape, float("nan"), dtype=torch.float32, device="cuda") for k_, v_ in w.items()}
+    ssa.ssa_layer_backward(p, blk, x, w, saved, x, x, grads)
+    torch.cuda.synchronize()
+    for nm, t in grads.items():
+        assert float(t.abs().max()) == 0.0, nm
