@@ -80,6 +80,28 @@ def test_module_forward_backward(seed, grid, n, hkv, d, m):
     util.assert_close(got["dbias"], g.dbias, "bf16", "dbias")
 
 
+def test_module_full_size_g128():
+    """The benchmark workload itself (62 229 tokens, C = 128), in the launch configuration ``bench.py --cmp-module``
+    times; the fp64 oracle covers every output at this size in seconds."""
+    wl = inputs.make_workload("g128")
+    orc, mod = module_oracle(wl)
+    c = wl.n_heads_kv * wl.head_dim
+    pe, w, bias = draw_weights(59, wl.m_cmp, c)
+    x = wl.k.reshape(wl.n_tokens, c)
+    rng = np.random.default_rng(66)
+    dxc = rng.standard_normal((orc.blocks.n_blocks["cmp"], c)).astype(np.float32)
+    dx0 = inputs.round_to_bf16(rng.standard_normal((wl.n_tokens, c)).astype(np.float32))
+    p, blk = util.build_blocks_gpu(wl)
+    got = gpu_module(wl, p, blk, wl.k, pe, w, bias, dxc, dx0.reshape(wl.k.shape))
+    f = mod.forward(x, pe, w, bias)
+    g = mod.backward(x, pe, w, bias, dxc)
+    util.assert_close(got["x_cmp"].reshape(-1, c), f.x_cmp, "bf16", "x_cmp")
+    util.assert_close(got["dx"].reshape(-1, c), dx0 + g.dx, "bf16", "dx")
+    util.assert_close(got["dpe"], g.dpe, "bf16", "dpe")
+    util.assert_close(got["dw"], g.dw, "bf16", "dw")
+    util.assert_close(got["dbias"], g.dbias, "bf16", "dbias")
+
+
 def test_identity_module_equals_plain_pool_bitwise():
     """Centre weight = identity, PE = bias = 0: the module's output is the mean pool; fed to ssa_forward_pooled it
     must give the same result as ssa_forward does with its own pooling (same rounding: fp32 mean -> bf16)."""

@@ -15,6 +15,7 @@ pytestmark = pytest.mark.gpu
     (62, 77, 4, 128),         # J = 12: one partly filled block of 16 gate columns; ragged token tail
     (63, 2049, 20, 256),      # J = 60
     (64, 1, 8, 128),          # a single token
+    (65, 62229, 16, 1024),    # the token count and layer shape bench.py --gate times
 ])
 def test_gate_forward_backward(seed, n, hq, dm):
     import torch

@@ -17,6 +17,8 @@ pytestmark = pytest.mark.gpu
     (74, 4100, 1024, 1024, True),    # the layer's square projection; several token splits in the weight gradient
     (75, 2500, 1024, 128, False),    # the key / value projection of 2 KV heads of 64
     (76, 128, 384, 256, True),       # exactly one token tile
+    (77, 62229, 1024, 1024, True),   # the shapes bench.py --linear times
+    (78, 62229, 1024, 128, True),
 ])
 def test_linear_forward_backward(seed, n, d_in, d_out, bias):
     import torch
