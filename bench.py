@@ -36,7 +36,7 @@ def algorithmic_flops(wl, blk_arrays, idx):
 # bench.py kernel name -> kernel name prefix in the rocprofv3 summaries
 ROCPROF_NAME = {
     "cmp_fwd_scores_topk": "m_cmp_fwd<", "slc_fwd": "m_slc_fwd<", "win_fwd": "m_win_fwd<",
-    "bwd_dq_cmp": "m_bwd_dq<{d}, 1, 0,", "bwd_dq_slc_win": "m_bwd_dq<{d}, 1, 1,",
+    "bwd_dq_cmp_win": "m_bwd_dq<{d}, 1, 0,", "bwd_dq_slc": "m_bwd_dq<{d}, 1, 1,",
     "bwd_dkv_win": "m_bwd_dkv<{d}, {kb}, 0,", "bwd_dkv_slc": "m_bwd_dkv<{d}, {kb}, 1,", "bwd_dkv_cmp": "m_bwd_dkv<{d}, {kb}, 2,",
 }
 
@@ -96,6 +96,12 @@ def kernel_times(wl, steps):
     return {nm: tot / cnt for nm, (tot, cnt) in prof.items()}, arrays, sel
 
 
+def dense_dq_ms(kd, pairs):
+    """Window share of the dQ kernel that handles the compression and window branches (split by their pair counts): in the
+    dense stand-in the window is the whole item, the compression branch a few per cent of it."""
+    return kd["bwd_dq_cmp_win"] * pairs["win"] / max(pairs["win"] + pairs["cmp"], 1)
+
+
 # Token sweep of the sparse path against dense attention computed by the same library (the window branch with one
 # window over the whole grid is plain dense variable-length attention).  Shells of the bench workload's recipe at
 # three grid sizes: (grid, size factor f, half-width w).
@@ -117,12 +123,13 @@ def dense_sweep(args):
         dense = inputs.make_workload("g128", grid=grid, f=f, w=w, m=(4, 8, grid), topk=1)
         n = sparse.n_tokens
         ks = kernel_times(sparse, 3)[0]
-        kd = kernel_times(dense, 2 if n > 50000 else 3)[0]
+        kd, d_arrays, d_sel = kernel_times(dense, 2 if n > 50000 else 3)
+        dense_pairs = algorithmic_flops(dense, d_arrays, d_sel)
         # prep_sort_pool runs once in forward and once in backward; its average is booked on both sides
-        s_fwd = sum(ks[nm] for nm in fwd_names)
+        s_fwd = sum(ks[nm] for nm in fwd_names) + ks.get("slc_token_order", 0.0)  # runs in forward and in backward
         s_bwd = sum(v_ for nm, v_ in ks.items() if nm not in fwd_names) + ks["prep_sort_pool"]
         d_fwd = kd["win_fwd"]
-        d_bwd = kd["bwd_dq_slc_win"] + kd["bwd_dkv_win"] + kd["bwd_pre_delta"]
+        d_bwd = dense_dq_ms(kd, dense_pairs) + kd["bwd_dkv_win"] + kd["bwd_pre_delta"]
         line = {"sweep": "ssa_vs_dense", "grid": grid, "n_tokens": n, "heads": [sparse.n_heads_q, sparse.n_heads_kv],
                 "head_dim": sparse.head_dim, "ssa_fwd_ms": round(s_fwd, 3), "ssa_bwd_ms": round(s_bwd, 3),
                 "dense_fwd_ms": round(d_fwd, 3), "dense_bwd_ms": round(d_bwd, 3),
@@ -146,13 +153,14 @@ def seq1d_bench(args):
         sparse = inputs.make_sequence_workload(2001, lens)
         dense = inputs.make_sequence_workload(2001, lens, l=(32, 64, max(lens)), topk=1)
         ks, arrays, sel = kernel_times(sparse, 3)
-        kd = kernel_times(dense, 2)[0]
+        kd, d_arrays, d_sel = kernel_times(dense, 2)
+        dense_pairs = algorithmic_flops(dense, d_arrays, d_sel)
         pairs = algorithmic_flops(sparse, arrays, sel)
         total_pairs = pairs["cmp"] + pairs["slc"] + pairs["win"]
-        s_fwd = sum(ks[nm] for nm in FWD_KERNELS)
+        s_fwd = sum(ks[nm] for nm in FWD_KERNELS) + ks.get("slc_token_order", 0.0)  # runs in forward and in backward
         s_bwd = sum(v_ for nm, v_ in ks.items() if nm not in FWD_KERNELS) + ks["prep_sort_pool"]
         d_fwd = kd["win_fwd"]
-        d_bwd = kd["bwd_dq_slc_win"] + kd["bwd_dkv_win"] + kd["bwd_pre_delta"]
+        d_bwd = dense_dq_ms(kd, dense_pairs) + kd["bwd_dkv_win"] + kd["bwd_pre_delta"]
         flops = 14 * sparse.head_dim * total_pairs
         line = {"bench": "sequence_partition", "lens": list(lens), "n_tokens": n, "blocks": [32, 64, 512], "topk": 16,
                 "heads": [sparse.n_heads_q, sparse.n_heads_kv], "head_dim": sparse.head_dim,
@@ -405,15 +413,15 @@ def ablation_sweep(args):
             n, d = wl.n_tokens, wl.head_dim
             ks, arrays, sel = kernel_times(wl, 2)
             pairs = algorithmic_flops(wl, arrays, sel)
-            # the window and selection branches share the dQ launch: its time is split by their pair counts
-            dq_sw = ks["bwd_dq_slc_win"]
-            f_s = pairs["slc"] / max(pairs["slc"] + pairs["win"], 1)
+            # the compression and window branches share a dQ launch: its time is split by their pair counts
+            dq_cw = ks["bwd_dq_cmp_win"]
+            f_c = pairs["cmp"] / max(pairs["cmp"] + pairs["win"], 1)
             branch_ms = {
-                "cmp": ks["cmp_fwd_scores_topk"] + ks["bwd_dq_cmp"] + ks["bwd_dkv_cmp"],
-                "slc": ks["slc_fwd"] + dq_sw * f_s + ks["bwd_dkv_slc"] + ks["bwd_invert_selection"],
-                "win": ks["win_fwd"] + dq_sw * (1 - f_s) + ks["bwd_dkv_win"],
+                "cmp": ks["cmp_fwd_scores_topk"] + dq_cw * f_c + ks["bwd_dkv_cmp"],
+                "slc": ks["slc_fwd"] + ks["bwd_dq_slc"] + ks["bwd_dkv_slc"] + ks["bwd_invert_selection"] + 2 * ks.get("slc_token_order", 0.0),
+                "win": ks["win_fwd"] + dq_cw * (1 - f_c) + ks["bwd_dkv_win"],
             }
-            other = sum(ks.values()) + ks["prep_sort_pool"] - sum(branch_ms.values())
+            other = sum(ks.values()) + ks["prep_sort_pool"] + ks.get("slc_token_order", 0.0) - sum(branch_ms.values())
             total = sum(branch_ms.values()) + other
             tf = {b: 14 * d * pairs[b] / (branch_ms[b] * 1e-3) / 1e12 for b in branch_ms}
             line = {"bench": "stress_ablation", "workload": "g128_thick", "n_tokens": n, "head_dim": d,
@@ -551,7 +559,7 @@ def main():
     # dQ kernel (6d), dV, dK on the dK/dV kernels (4d)
     kflops = {
         "cmp_fwd_scores_topk": 4 * d * pairs["cmp"], "slc_fwd": 4 * d * pairs["slc"], "win_fwd": 4 * d * pairs["win"],
-        "bwd_dq_cmp": 6 * d * pairs["cmp"], "bwd_dq_slc_win": 6 * d * (pairs["slc"] + pairs["win"]), "bwd_dkv_cmp": 4 * d * pairs["cmp"], "bwd_dkv_slc": 4 * d * pairs["slc"],
+        "bwd_dq_cmp_win": 6 * d * (pairs["cmp"] + pairs["win"]), "bwd_dq_slc": 6 * d * pairs["slc"], "bwd_dkv_cmp": 4 * d * pairs["cmp"], "bwd_dkv_slc": 4 * d * pairs["slc"],
         "bwd_dkv_win": 4 * d * pairs["win"], "generic_path": 10 * d * all_pairs,
     }
     dom = max(kern_ms, key=kern_ms.get) if kern_ms else None

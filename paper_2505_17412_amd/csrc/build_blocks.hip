@@ -273,6 +273,31 @@ __global__ void k_maxima(CsrOut o, int B, int32_t *meta) {
 
 }  // namespace
 
+// Stable LSD radix sort of n (key, value) pairs by the low `bits` bits of the keys, 8 bits per pass, ping-ponging between
+// (k0, v0) and (k1, v1); `aux` holds sort_pairs_aux_bytes(n) bytes.  Returns 0 when the sorted pairs end in (k0, v0),
+// 1 when they end in (k1, v1).  Four launches per pass on `stream`, no allocation, no synchronisation.
+size_t sort_pairs_aux_bytes(int n) {
+  const int nTiles = (n + SORT_TILE - 1) / SORT_TILE;
+  return align_up((size_t)256 * (nTiles > 0 ? nTiles : 1) * 4, 256) + 256 * 4;
+}
+int sort_pairs(uint64_t *k0, uint32_t *v0, uint64_t *k1, uint32_t *v1, void *aux, int n, int bits, hipStream_t stream) {
+  const int nTiles = (n + SORT_TILE - 1) / SORT_TILE;
+  uint32_t *hist = (uint32_t *)aux;
+  uint32_t *digit_base = (uint32_t *)((char *)aux + align_up((size_t)256 * (nTiles > 0 ? nTiles : 1) * 4, 256));
+  int where = 0;
+  if (n <= 0) return where;
+  for (int shift = 0; shift < bits; shift += 8) {
+    k_sort_hist<<<nTiles, SORT_TILE, 0, stream>>>(k0, n, shift, nTiles, hist);
+    k_scan_rows<<<256, 256, 0, stream>>>(hist, nTiles, digit_base);
+    k_scan_totals<<<1, 256, 0, stream>>>(digit_base);
+    k_sort_scatter<<<nTiles, SORT_TILE, 0, stream>>>(k0, v0, k1, v1, n, shift, nTiles, hist, digit_base);
+    uint64_t *tk = k0; k0 = k1; k1 = tk;
+    uint32_t *tv = v0; v0 = v1; v1 = tv;
+    where ^= 1;
+  }
+  return where;
+}
+
 // Common part of the two builders: grid_mode = voxel partition (sort by Morton key), else sequences in caller order.
 static int build_handle(const ssa_params_t *p, const int32_t *coords, const int32_t *batch_offsets, bool grid_mode,
                         hipStream_t stream, ssa_blocks_t **out) {

@@ -85,7 +85,9 @@ struct DqArgs {
   const int32_t *idx;
   const float *lse2s, *deltas, *gws;  // [3][N(pos)][Hq]
   bf16_t *dQ;
-  float *dQp;  // [N(pos)][Hq][D] fp32: compression-branch part of dQ, handed from the first dQ kernel to the second
+  float *dQp;  // [N(pos)][Hq][D] fp32: compression + window part of dQ, handed from the first dQ kernel to the second
+  const int32_t *slc_order;  // [Hkv][N] token order of the selection part (caller indices), or NULL: sorted order
+  const int32_t *inv_perm;   // [N] caller index -> sorted position
 };
 
 // One staged 32-key tile: transposed scores (K rows) and dP (V rows), then dQ^T += K^T dS^T (the K rows again, read
@@ -147,8 +149,9 @@ __host__ __device__ inline size_t dq_lds_bytes(int tw, int T, int Ns) {
   return (size_t)2 * StageLayout<D, 2>::ELEMS * sizeof(bf16_t) + 32 + ((size_t)tw * T * 4 + (size_t)(Ns + 31) / 32 + 4) * 4;
 }
 
-// PART 0: compression branch only (its pooled keys stay L2 resident when nothing else streams through), result
-// kept in fp32; PART 1: window and selection branches on top of it, final bf16 dQ.
+// PART 0: compression branch, then the (small) window branch, in the sorted token order; result kept in fp32.
+// PART 1: selection branch on top of it, in the selection order of the KV head (tokens with similar selected sets
+// next to each other), final bf16 dQ.
 template <int D, int CB, int PART, int NW>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4 : 2))) void m_bwd_dq(DqArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -164,15 +167,19 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
   int *ub = Irows + TW * T, *us = ub + TW * T, *ue = us + TW * T;
   uint32_t *bits = (uint32_t *)(ue + TW * T);
   QRows<D, CB> q;
-  load_rows<D, CB>(a.Q, a.v, wg_pos0, g, q);
+  MfmaView vo = a.v;  // position -> token: the sorted order, or the selection order of this KV head
+  const bool reordered = PART == 1 && a.slc_order != nullptr;
+  if (reordered) vo.perm = a.slc_order + (size_t)g * N;
+  load_rows<D, CB>(a.Q, vo, wg_pos0, g, q);
   bf16x8 dop[CB][D / 32];
-  size_t rs_[CB];
+  size_t rs_[CB];  // row of the per-row arrays, which are laid out by sorted position
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) {
     const bf16_t *src = a.dO + ((size_t)q.tok[cb] * a.v.Hq + q.h[cb]) * D + 8 * quad;
 #pragma unroll
     for (int ks = 0; ks < D / 32; ++ks) dop[cb][ks] = q.valid[cb] ? ld8(src + 32 * ks) : zero8();
-    rs_[cb] = (size_t)(q.valid[cb] ? q.pos[cb] : 0) * a.v.Hq + q.h[cb];
+    const int spos = !q.valid[cb] ? 0 : (reordered ? a.inv_perm[q.tok[cb]] : q.pos[cb]);
+    rs_[cb] = (size_t)spos * a.v.Hq + q.h[cb];
   }
   const size_t NH = (size_t)N * a.v.Hq;
   f32x4 acc[CB][D / 16];
@@ -190,9 +197,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
   bool act[CB];
   float lse2[CB], delta[CB], gw[CB];
 
-  // ---- compression and window branches: one key range, per-lane [lo, hi)
-  {
-    constexpr int branch = PART == 0 ? 0 : 2;
+  // ---- compression and window branches: one key range each, per-lane [lo, hi)
+  for (int branch = 0; PART == 0 && branch <= 2; branch += 2) {
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) {
       if (branch == 0) {
@@ -217,7 +223,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
     TileSrc<2> src = branch == 0
         ? TileSrc<2>{{a.v.Kc + (size_t)g * D, a.v.Vc + (size_t)g * D}, (uint32_t)kstride}
         : TileSrc<2>{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, (uint32_t)kstride};
-    run_pipeline<D, 2, 64 * NW, (PART == 0 ? 2 : 1)>(
+    run_pipeline<D, 2, 64 * NW, 2>(
         src, stage0, ints + 4, ints + 5, re > rs ? 1 : 0, [](int) {},
         [&](const bf16_t *stg, int kb, int) {
           bf16_t *st = (bf16_t *)stg;
@@ -231,7 +237,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
   }
   // ---- selection branch: union of the selected blocks of the workgroup's tokens
   if (PART == 1) {
-    build_union(a.v, a.idx, wg_pos0, g, TW, Irows, ub, us, ue, bits, &ints[0]);
+    build_union(vo, a.idx, wg_pos0, g, TW, Irows, ub, us, ue, bits, &ints[0]);
     const int nr = lds_uniform(&ints[0]);
     int jc[CB];
     float lse_own[CB];
@@ -704,7 +710,7 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
     m_bwd_pre<<<N, 256, (size_t)Hq * D * sizeof(bf16_t), s>>>(a);
   }
   {
-    DqArgs a{v, (const bf16_t *)q, (const bf16_t *)dout, idx, w.lse2s, w.deltas, w.gws, (bf16_t *)dq, w.dQp};
+    DqArgs a{v, (const bf16_t *)q, (const bf16_t *)dout, idx, w.lse2s, w.deltas, w.gws, (bf16_t *)dq, w.dQp, nullptr, blk->inv_perm};
     constexpr int CB = 1, NW0 = 4, NW1 = DQ_SLC_WAVES;
     const int tw0 = NW0 * CB * 16 / v.hs, tw1 = NW1 * CB * 16 / v.hs;
     static bool attr_done = false;
@@ -716,6 +722,10 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
     {
       ProfScope ps0(PROF_BWD_DQ_CMP, s);
       m_bwd_dq<D, CB, 0, NW0><<<dim3(xcd_grid_size((N + tw0 - 1) / tw0, Hkv)), 64 * NW0, dq_lds_bytes<D>(tw0, v.T, v.Ns), s>>>(a);
+    }
+    {
+      const int rc = slc_order_build(idx, v.perm, N, Hkv, v.T, v.Ns, w.order_ws, s, &a.slc_order);
+      if (rc != SSA_OK) return rc;
     }
     {
       ProfScope ps1(PROF_BWD_DQ, s);

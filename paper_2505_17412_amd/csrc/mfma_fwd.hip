@@ -21,6 +21,7 @@ struct FwdArgs {
   bf16_t *Ob;    // [3,N,Hq,D]
   float *lse;    // [3,N,Hq]
   int32_t *idx;  // [N,Hkv,T]
+  const int32_t *slc_order;  // [Hkv,N] token order of the selection kernel, or NULL: the sorted order
 };
 
 template <int D, int CB>
@@ -341,8 +342,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
   int *us = ub + TW * T, *ue = us + TW * T;
   uint32_t *bits = (uint32_t *)(ue + TW * T);
   QRows<D, CB> q;
-  load_rows<D, CB>(a.Q, a.v, wg_pos0, g, q);
-  build_union(a.v, a.idx, wg_pos0, g, TW, Irows, ub, us, ue, bits, &ints[0]);
+  MfmaView vo = a.v;  // position -> token through the selection order of this KV head
+  if (a.slc_order) vo.perm = a.slc_order + (size_t)g * a.v.N;
+  load_rows<D, CB>(a.Q, vo, wg_pos0, g, q);
+  build_union(vo, a.idx, wg_pos0, g, TW, Irows, ub, us, ue, bits, &ints[0]);
   const int nr = lds_uniform(&ints[0]);
   int jc[CB], lo[CB], hi[CB];
   bool act[CB], on[CB];
@@ -458,7 +461,7 @@ constexpr int SLC_CB = 1;     // 16-column blocks per wavefront of the selection
 constexpr int SLC_WAVES = 4;  // wavefronts per workgroup of the selection kernel
 
 template <int D>
-int launch_forward(const FwdArgs &a, const bf16_t *gates, bf16_t *out, hipStream_t s) {
+int launch_forward(FwdArgs a, const bf16_t *gates, bf16_t *out, void *order_ws, hipStream_t s) {
   const int tw = 4 * FWD_CB * 16 / a.v.hs, tw_cmp = 4 * CMP_CB * 16 / a.v.hs;
   const dim3 grid(xcd_grid_size((a.v.N + tw - 1) / tw, a.v.Hkv));
   const int tw_slc = SLC_WAVES * SLC_CB * 16 / a.v.hs;
@@ -473,6 +476,10 @@ int launch_forward(const FwdArgs &a, const bf16_t *gates, bf16_t *out, hipStream
   {
     ProfScope ps(PROF_CMP_FWD, s);
     m_cmp_fwd<D, CMP_CB><<<dim3(xcd_grid_size((a.v.N + tw_cmp - 1) / tw_cmp, a.v.Hkv)), 256, lds_cmp, s>>>(a);
+  }
+  {
+    const int rc = slc_order_build(a.idx, a.v.perm, a.v.N, a.v.Hkv, a.v.T, a.v.Ns, order_ws, s, &a.slc_order);
+    if (rc != SSA_OK) return rc;
   }
   {
     ProfScope ps(PROF_SLC_FWD, s);
@@ -505,12 +512,12 @@ size_t mfma_fwd_lds_bytes(int D, int hs, int s_max, int T, int Ns) {
 }
 
 int mfma_forward_kernels(const MfmaView &v, int D, const void *q, const void *gates, void *out, float *lse,
-                         int32_t *idx, void *out_branch, hipStream_t s) {
-  FwdArgs a{v, (const bf16_t *)q, (bf16_t *)out_branch, lse, idx};
+                         int32_t *idx, void *out_branch, void *order_ws, hipStream_t s) {
+  FwdArgs a{v, (const bf16_t *)q, (bf16_t *)out_branch, lse, idx, nullptr};
   switch (D) {
-    case 32: return launch_forward<32>(a, (const bf16_t *)gates, (bf16_t *)out, s);
-    case 64: return launch_forward<64>(a, (const bf16_t *)gates, (bf16_t *)out, s);
-    case 128: return launch_forward<128>(a, (const bf16_t *)gates, (bf16_t *)out, s);
+    case 32: return launch_forward<32>(a, (const bf16_t *)gates, (bf16_t *)out, order_ws, s);
+    case 64: return launch_forward<64>(a, (const bf16_t *)gates, (bf16_t *)out, order_ws, s);
+    case 128: return launch_forward<128>(a, (const bf16_t *)gates, (bf16_t *)out, order_ws, s);
     default: return SSA_ERR_UNSUPPORTED;
   }
 }

@@ -4,7 +4,15 @@
 
 size_t mfma_fwd_lds_bytes(int D, int hs, int s_max, int T, int Ns);
 int mfma_forward_kernels(const MfmaView &v, int D, const void *q, const void *gates, void *out, float *lse,
-                         int32_t *idx, void *out_branch, hipStream_t s);
+                         int32_t *idx, void *out_branch, void *order_ws, hipStream_t s);
+
+// Token order of the selection-branch kernels (slc_order.hip): per KV head, the tokens' caller indices ordered so that
+// tokens with similar selected sets are neighbours; *order = [Hkv][N] inside `ws`, or NULL when the problem is too
+// small to bother (the kernels then walk the sorted order).
+constexpr int SLC_ORDER_MIN_TOKENS = 4096;
+size_t slc_order_workspace(int N, int Hkv, int Ns);
+int slc_order_build(const int32_t *idx, const int32_t *perm, int N, int Hkv, int T, int Ns, void *ws, hipStream_t s,
+                    const int32_t **order);
 
 // Device buffers of the backward pass (carved from the caller's workspace).
 struct BwdBuffers {
@@ -21,6 +29,7 @@ struct BwdBuffers {
   int chunk_len, max_chunks;    // query tokens per chunk; upper bound of the number of chunks
   int q_splits;
   float *dKc_out, *dVc_out;     // [Nc][Hkv][D] or NULL: where the pooled-key/value gradients go instead of being un-pooled
+  void *order_ws;               // slc_order_workspace() bytes
 };
 int mfma_backward_kernels(const MfmaView &v, int D, const BwdBuffers &w, const void *q, const void *gates,
                           const void *out_branch, const float *lse, const int32_t *idx, const void *dout, void *dq,

@@ -42,7 +42,7 @@ __global__ void m_prep(const bf16_t *__restrict__ K, const bf16_t *__restrict__ 
 
 size_t padded_rows(int n) { return align_up((size_t)n, 8) + SSA_KEY_PAD; }
 
-struct FwdPlan { size_t ks, vs, kc, vc, ob, lse, idx, total; };
+struct FwdPlan { size_t ks, vs, kc, vc, ob, lse, idx, order, total; };
 
 FwdPlan fwd_plan(const ssa_ctx &c) {
   FwdPlan p{};
@@ -54,6 +54,7 @@ FwdPlan fwd_plan(const ssa_ctx &c) {
   p.ob = take((size_t)3 * c.N * c.Hq * c.d * 2);
   p.lse = take((size_t)3 * c.N * c.Hq * 4);
   p.idx = take((size_t)c.N * c.Hkv * c.T * 4);
+  p.order = take(slc_order_workspace(c.N, c.Hkv, c.blk->Ns));
   p.total = off;
   return p;
 }
@@ -92,7 +93,7 @@ int override_pooled(const ssa_ctx &c, const PrepOut &o) {
 
 struct BwdPlan {
   size_t ks, vs, kc, vc, lse2s, deltas, gws, qs, dos, dqp, dks, dvs, dkc, dvc, bits, counts, start, list, cstart, prow,
-      pk, pv, total;
+      pk, pv, order, total;
   int q_splits, chunk_len, max_chunks;
 };
 
@@ -133,6 +134,7 @@ BwdPlan bwd_plan(const ssa_ctx &c) {
   p.max_chunks = (int)(entries / p.chunk_len + keys + 1);
   p.cstart = take((keys + 1) * 4); p.prow = take((keys + 1) * 4);
   p.pk = take(rows * c.d * 4); p.pv = take(rows * c.d * 4);
+  p.order = take(slc_order_workspace(c.N, c.Hkv, b->Ns));
   p.total = off;
   return p;
 }
@@ -187,6 +189,7 @@ int mfma_backward(const ssa_ctx &c, const void *q, const void *k, const void *v,
   w.q_splits = p.q_splits;
   w.chunk_start = (int32_t *)(ws + p.cstart); w.part_row_start = (int32_t *)(ws + p.prow);
   w.pK = (float *)(ws + p.pk); w.pV = (float *)(ws + p.pv); w.chunk_len = p.chunk_len; w.max_chunks = p.max_chunks;
+  w.order_ws = ws + p.order;
   return mfma_backward_kernels(view, c.d, w, q, gates, out_branch, lse, topk_idx, dout, dq, dk, dv, dgates, c.blk, c.B,
                                c.stream);
 }
@@ -206,5 +209,5 @@ int mfma_forward(const ssa_ctx &c, const void *q, const void *k, const void *v, 
   view.Ks = o.Ks; view.Vs = o.Vs; view.Kc = o.Kc; view.Vc = o.Vc;
   return mfma_forward_kernels(view, c.d, q, gates, out, lse ? lse : (float *)(ws + p.lse),
                               topk_idx ? topk_idx : (int32_t *)(ws + p.idx), out_branch ? out_branch : (void *)(ws + p.ob),
-                              c.stream);
+                              ws + p.order, c.stream);
 }

@@ -98,3 +98,7 @@ int mfma_forward(const ssa_ctx &c, const void *q, const void *k, const void *v, 
 int mfma_backward(const ssa_ctx &c, const void *q, const void *k, const void *v, const void *gates,
                   const void *out_branch, const float *lse, const int32_t *topk_idx, const void *dout, void *dq,
                   void *dk, void *dv, void *dgates, void *ws, size_t ws_bytes);
+
+// ---- stable radix sort of (uint64 key, uint32 value) pairs: build_blocks.hip
+size_t sort_pairs_aux_bytes(int n);
+int sort_pairs(uint64_t *k0, uint32_t *v0, uint64_t *k1, uint32_t *v1, void *aux, int n, int bits, hipStream_t stream);

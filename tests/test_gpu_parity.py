@@ -252,7 +252,8 @@ def test_forward_backward_replay_from_a_hip_graph():
     bit for bit."""
     import torch
     from paper_2505_17412_amd import ssa
-    wl = inputs.random_points_workload(23, 32, (1300, 800), 16, 2, 64, (4, 8, 8), 6, "bf16")
+    # 4 800 tokens: large enough for the selection kernels to run in their own token order (built by kernels alone)
+    wl = inputs.random_points_workload(23, 32, (3000, 1800), 16, 2, 64, (4, 8, 8), 6, "bf16")
     n, hq, hkv, d, T = wl.n_tokens, wl.n_heads_q, wl.n_heads_kv, wl.head_dim, wl.topk
     p, blk = util.build_blocks_gpu(wl)
     q, k, v, g, do = (util.to_dev(a, "bf16") for a in (wl.q, wl.k, wl.v, wl.gates, wl.dout))
