@@ -22,7 +22,7 @@ __global__ void o_fill(uint32_t *p, size_t n, uint32_t v) {
 
 // counts[g][b] = how many (token, g) rows selected block b.  A workgroup histograms its share of the index tensor in
 // LDS (bins <= LDS_BINS) and adds the non-zero bins to memory; integer adds commute, so the result is exact.
-constexpr int LDS_BINS = 16384;
+constexpr int LDS_BINS = 8192;
 __global__ __launch_bounds__(256) void o_count(const int32_t *__restrict__ idx, size_t entries, int Hkv, int T, int Ns,
                                                uint32_t *__restrict__ counts) {
   extern __shared__ uint32_t hist[];
