@@ -50,20 +50,25 @@ __global__ __launch_bounds__(256) void m_bwd_pre(PreArgs a) {
     *reinterpret_cast<bf16x8 *>(a.dOs + (size_t)pos * HD + e) = xd;
   }
   __syncthreads();
-  // dgates and the row scalars: one wavefront per head, lanes over the head dimension
-  const int wid = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  for (int h = wid; h < a.Hq; h += 4) {
+  // dgates and the row scalars: D/8 lanes per head (8 elements each), 256 / (D/8) heads per pass
+  const int per = a.D / 8;  // 4, 8 or 16 lanes per head
+  for (int h0 = 0; h0 < a.Hq; h0 += 256 / per) {
+    const int h = h0 + threadIdx.x / per, part = threadIdx.x % per;
     float acc[3] = {0.f, 0.f, 0.f};
-    for (int i = lane; i < a.D; i += 64) {
-      const float go = bf16_to_f32(td[h * a.D + i]);
+    if (h < a.Hq) {
+      const bf16x8 go = *reinterpret_cast<const bf16x8 *>(td + h * a.D + 8 * part);
 #pragma unroll
-      for (int b = 0; b < 3; ++b)
-        acc[b] += go * bf16_to_f32(a.Ob[(((size_t)b * a.N + tok) * a.Hq + h) * a.D + i]);
+      for (int b = 0; b < 3; ++b) {
+        const bf16x8 ob = ld8(a.Ob + (((size_t)b * a.N + tok) * a.Hq + h) * a.D + 8 * part);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[b] += (float)go[j] * (float)ob[j];
+      }
     }
+    for (int off = 1; off < per; off <<= 1)
 #pragma unroll
-    for (int b = 0; b < 3; ++b) acc[b] = wave_sum_f(acc[b]);
-    if (lane < 3) {
-      const int b = lane;
+      for (int b = 0; b < 3; ++b) acc[b] += __shfl_xor(acc[b], off);
+    if (h < a.Hq && part < 3) {
+      const int b = part;
       const float dot = b == 0 ? acc[0] : (b == 1 ? acc[1] : acc[2]);
       const size_t th = (size_t)tok * a.Hq + h;
       const float w = bf16_to_f32(a.gates[th * 3 + b]);
