@@ -581,6 +581,30 @@ __global__ void m_sel_bits(const int32_t *__restrict__ idx, const int32_t *__res
   atomicOr(&bits[((size_t)g * Ns + b) * words + (pos >> 5)], 1u << (pos & 31));
 }
 
+// The same bit matrix built tile by tile in LDS: workgroup (chunk, g) owns `cw` words = 32*cw sorted positions of all
+// Ns blocks of KV head g, sets the bits with LDS atomics and writes every word of its tile (so the matrix needs no
+// clearing beforehand).  Needs Ns * cw * 4 bytes of LDS.
+__global__ __launch_bounds__(256) void m_sel_bits_tile(const int32_t *__restrict__ idx, const int32_t *__restrict__ perm, int N,
+                                                       int Hkv, int T, int Ns, int words, int cw, uint32_t *__restrict__ bits) {
+  extern __shared__ __align__(16) unsigned char sel_smem[];
+  uint32_t *tile = (uint32_t *)sel_smem;  // [Ns][cw]
+  const int g = blockIdx.y, w0 = blockIdx.x * cw, p0 = w0 * 32;
+  for (int i = threadIdx.x; i < Ns * cw; i += 256) tile[i] = 0u;
+  __syncthreads();
+  const int npos = min(32 * cw, N - p0);
+  for (int e = threadIdx.x; e < npos * T; e += 256) {
+    const int pl = e / T, j = e % T;
+    const int b = idx[((size_t)perm[p0 + pl] * Hkv + g) * T + j];
+    if (b >= 0 && b < Ns) atomicOr(&tile[b * cw + (pl >> 5)], 1u << (pl & 31));
+  }
+  __syncthreads();
+  const int wn = min(cw, words - w0);
+  for (int i = threadIdx.x; i < Ns * cw; i += 256) {
+    const int b = i / cw, w = i % cw;
+    if (w < wn) bits[((size_t)g * Ns + b) * words + w0 + w] = tile[i];
+  }
+}
+
 __global__ __launch_bounds__(256) void m_sel_count(const uint32_t *__restrict__ bits, int words, uint32_t *counts) {
   __shared__ uint32_t part[4];
   const uint32_t *row = bits + (size_t)blockIdx.x * words;
@@ -760,9 +784,18 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
   {
     ProfScope ps(PROF_BWD_INVERT, s);
     const int words = (N + 31) / 32, keys = Hkv * v.Ns;
-    m_fill_u32<<<1024, 256, 0, s>>>(w.sel_bits, (size_t)keys * words, 0u);
-    const size_t entries = (size_t)N * Hkv * v.T;
-    m_sel_bits<<<(unsigned)((entries + 255) / 256), 256, 0, s>>>(idx, v.perm, N, Hkv, v.T, v.Ns, words, w.sel_bits);
+    // bit matrix: tiles of up to 32 words per block row held in LDS (64 KB), or global atomics when a KV head has more
+    // than 16 384 blocks
+    int cw = v.Ns > 0 ? 16384 / v.Ns : 0;
+    if (cw > 32) cw = 32;
+    if (cw >= 1) {
+      m_sel_bits_tile<<<dim3((words + cw - 1) / cw, Hkv), 256, (size_t)v.Ns * cw * 4, s>>>(idx, v.perm, N, Hkv, v.T, v.Ns, words,
+                                                                                            cw, w.sel_bits);
+    } else {
+      m_fill_u32<<<1024, 256, 0, s>>>(w.sel_bits, (size_t)keys * words, 0u);
+      const size_t entries = (size_t)N * Hkv * v.T;
+      m_sel_bits<<<(unsigned)((entries + 255) / 256), 256, 0, s>>>(idx, v.perm, N, Hkv, v.T, v.Ns, words, w.sel_bits);
+    }
     m_sel_count<<<keys, 256, 0, s>>>(w.sel_bits, words, w.sel_counts);
     m_scan_counts<<<1, 1024, 0, s>>>(w.sel_counts, keys, v.Ns, w.chunk_len, v.slc_start, w.sel_start, w.chunk_start,
                                      w.part_row_start);
