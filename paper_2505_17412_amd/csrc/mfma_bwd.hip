@@ -720,7 +720,7 @@ __global__ void m_bwd_finish(const int32_t *__restrict__ perm, const int32_t *__
   }
 }
 
-constexpr int DQ_SLC_WAVES = 4;  // wavefronts per workgroup of the selection/window dQ kernel (16 tokens at h_s = 8)
+constexpr int DQ_SLC_WAVES = 4;  // wavefronts per workgroup of the selection dQ kernel (8 tokens at h_s = 8)
 constexpr int KB_KEYS_MAX = 2;  // key blocks of 16 per wavefront in the dK/dV kernels (1 at head_dim 128: registers)
 // wavefronts per workgroup there (16*KB_KEYS keys each): blocks and windows hold ~130 tokens, an item's pooled keys
 // thousands, so the compression branch takes wider workgroups (fewer passes over the query rows)
