@@ -210,6 +210,35 @@ def test_whole_grid_window_is_dense_attention_on_gpu():
         util.assert_close(got, want, "bf16", name)
 
 
+def test_shifted_windows_are_the_window_kernels_on_shifted_coordinates():
+    """Shifted 3D windows (the VAE's window attention alternates plain and half-window-shifted partitions, section 3.1)
+    need no kernel of their own: a second block handle built on coordinates moved by half a window partitions the
+    tokens into the shifted windows.  The window branch is checked against dense attention inside windows whose ids
+    are computed here from floor((c + m/2) / m), not by the oracle's block builder."""
+    import dataclasses
+    base = inputs.random_points_workload(23, 16, (1300, 900), 16, 2, 64, (4, 8, 8), 4, "bf16")
+    shift = base.m_win // 2
+    wl = dataclasses.replace(base, coords=base.coords + shift, grid=base.grid + base.m_win)
+    gates = np.zeros_like(wl.gates)
+    gates[..., 2] = 1.0
+    wl.gates = gates
+    g = util.run_gpu(wl, backward=False)
+    item = np.searchsorted(wl.batch_offsets, np.arange(wl.n_tokens), side="right") - 1
+    w = (base.coords + shift) // base.m_win
+    wid = ((item * 4 + w[:, 0]) * 4 + w[:, 1]) * 4 + w[:, 2]
+    plain = base.coords // base.m_win
+    assert len(np.unique(wid)) != len(np.unique(((item * 4 + plain[:, 0]) * 4 + plain[:, 1]) * 4 + plain[:, 2]))
+    qf, kf, vf = (a.astype(np.float64) for a in (wl.q, wl.k, wl.v))
+    scale = 1.0 / np.sqrt(wl.head_dim)
+    for win in np.unique(wid)[::7]:
+        rows = np.nonzero(wid == win)[0]
+        for h in (0, 11):
+            s = (qf[rows, h] @ kf[rows, h // 8].T) * scale
+            p = np.exp(s - s.max(1, keepdims=True))
+            p /= p.sum(1, keepdims=True)
+            util.assert_close(g.out[rows, h], p @ vf[rows, h // 8], "bf16", f"shifted window {win} head {h}")
+
+
 @pytest.mark.parametrize("seed,n,expect_blocks", [
     (31, (900,), (513, 1024)),     # selection blocks per item in (512, 1024]
     (32, (3000,), (1025, 4096)),   # more than 1024 selection blocks per item
