@@ -364,6 +364,11 @@ def layer_bench(args):
     x, dy = rnd(n, dm), rnd(n, dm)
     w = dict(wq=rnd(cq, dm, scale=dm ** -0.5), wk=rnd(ckv, dm, scale=dm ** -0.5), wv=rnd(ckv, dm, scale=dm ** -0.5),
              wg=rnd(dm, 3 * hq, scale=dm ** -0.5), bg=rnd(3 * hq), wo=rnd(dm, cq, scale=cq ** -0.5))
+    if args.learned_cmp:  # the learned compression module on keys and values instead of the mean pool
+        for t in ("k", "v"):
+            w["pe_" + t] = rnd(wl.m_cmp ** 3, ckv, scale=0.5)
+            w["wc_" + t] = rnd(27, ckv, ckv, scale=(9.0 * ckv) ** -0.5)
+            w["bc_" + t] = rnd(ckv, scale=0.1)
     grads = {"d" + k_: torch.empty(v_.shape, device="cuda") for k_, v_ in w.items()}
     y, dx = torch.empty_like(x), torch.empty_like(x)
     saved = torch.empty(ssa.ssa_layer_saved_bytes(p)[0], dtype=torch.uint8, device="cuda")
@@ -392,11 +397,14 @@ def layer_bench(args):
     ssa.ssa_profile_enable(False)
     lin = prof.get("linear_fwd", 0.0) + prof.get("linear_bwd", 0.0)
     gate = prof.get("gate_fwd", 0.0) + prof.get("gate_bwd", 0.0)
-    attn = sum(v_ for k_, v_ in prof.items() if not k_.startswith(("linear", "gate")))
+    module = sum(v_ for k_, v_ in prof.items() if k_.startswith("cmp_module"))
+    attn = sum(v_ for k_, v_ in prof.items() if not k_.startswith(("linear", "gate", "cmp_module")))
     gemm_flops = 6.0 * n * dm * (2 * cq + 2 * ckv)  # forward 2 + backward 4 FLOPs per (token, weight)
     line = {"bench": "ssa_layer", "workload": args.workload, "n_tokens": n, "d_model": dm, "heads": [hq, hkv], "head_dim": d,
             "ms_per_layer_step": round(ms, 3), "tokens_per_s": round(n / (ms * 1e-3)),
-            "part_ms": {"projections": round(lin, 3), "gate_predictor": round(gate, 3), "attention": round(attn, 3)},
+            "compression": "learned module" if args.learned_cmp else "mean pool",
+            "part_ms": {"projections": round(lin, 3), "gate_predictor": round(gate, 3), "attention": round(attn, 3),
+                        "compression_module": round(module, 3)},
             "projection_tflops": round(gemm_flops / (lin * 1e-3) / 1e12, 1) if lin > 0 else None,
             "saved_activation_mib": round(saved.numel() / 2 ** 20, 1), "steps": args.steps, "warmup": args.warmup}
     print(json.dumps(line), flush=True)
@@ -451,6 +459,7 @@ def main():
                     help="instead of the benchmark line: the learned compression module alone and inside a training step")
     ap.add_argument("--ablation", action="store_true", help="instead of the benchmark line: the stress workload, top-k x window sweep with per-branch figures")
     ap.add_argument("--layer", action="store_true", help="instead of the benchmark line: a full SSA attention layer, forward + backward")
+    ap.add_argument("--learned-cmp", action="store_true", help="with --layer: the learned compression module instead of the mean pool")
     ap.add_argument("--linear", action="store_true", help="instead of the benchmark line: the layer's linear projections against the MFMA roofline")
     ap.add_argument("--seq1d", action="store_true", help="instead of the benchmark line: the kernels on a one-dimensional (sequence) partition")
     ap.add_argument("--dense-sweep", action="store_true",

@@ -197,7 +197,7 @@ int ssa_compress_forward(const ssa_params_t *params, const ssa_blocks_t *blocks,
  *   dx_cmp   dev float [N_c,Hkv,d]  gradient w.r.t. x_cmp (what ssa_backward_pooled writes)
  *   dx_accum dev [N,Hkv,d]          in/out: the gradient w.r.t. x is ADDED to it (it usually already holds the
  *                                   attention's own dk or dv)
- *   dpe dev float [m_cmp^3, C], dw dev float [27, C, C], dbias dev float [C]: overwritten
+ *   dpe dev float [m_cmp^3, C], dw dev float [27, C, C], dbias dev float [C]: overwritten (zeros when N = 0)
  */
 int ssa_compress_backward(const ssa_params_t *params, const ssa_blocks_t *blocks, const void *x,
                           const ssa_cmp_weights_t *weights, const float *dx_cmp, void *dx_accum, float *dpe,
@@ -260,22 +260,29 @@ int ssa_gate_backward(const ssa_params_t *params, int32_t d_model, const void *x
  *     o = ssa_forward(q, k, v, gates), y = o wo^T (+bo).
  *   x, y, dy, dx  dev bf16 [N, d_model]
  *   weights       host struct of dev bf16 pointers: wq [Hq*d, d_model]; wk, wv [Hkv*d, d_model]; wg [d_model, 3*Hq] and
- *                 bg [3*Hq] (the layout of ssa_gate_forward); wo [d_model, Hq*d]; bq, bk, bv, bo optional (NULL: none)
+ *                 bg [3*Hq] (the layout of ssa_gate_forward); wo [d_model, Hq*d]; bq, bk, bv, bo optional (NULL: none).
+ *                 pe_k, wc_k, bc_k and pe_v, wc_v, bc_v (the pe, w, bias of ssa_cmp_weights_t for the keys and for the
+ *                 values): all six NULL, and the compression branch attends to mean-pooled keys and values; all six
+ *                 given, and to the learned module's block tokens (ssa_compress_forward on k and on v, then
+ *                 ssa_forward_pooled; backward recomputes them); anything else is SSA_ERR_NULL
  *   saved         dev, ssa_layer_saved_bytes() bytes: the activations forward keeps for backward (q, k, v, gates, o,
  *                 out_branch, lse, topk_idx: their byte offsets from the 256-byte aligned start of the buffer are
  *                 returned in `offsets`, 8 entries in that order, when it is not NULL)
- *   grads         host struct of dev float pointers with the shapes of the weights; dbq, dbk, dbv, dbo optional; all
- *                 overwritten
- * bf16 only; d_model, Hq*d and Hkv*d multiples of 128; 3*Hq <= 64.  Asynchronous on `stream`, allocates nothing.
+ *   grads         host struct of dev float pointers with the shapes of the weights; dbq, dbk, dbv, dbo optional; the
+ *                 six of the compression module required exactly when its weights are given; all overwritten
+ * bf16 only; d_model, Hq*d and Hkv*d multiples of 128; 3*Hq <= 64; with the module also its own limits.  Asynchronous on
+ * `stream`, allocates nothing.
  * Errors: those of the parts (NULL, BAD_SHAPE, BAD_HEADS, UNSUPPORTED, MISMATCH, WORKSPACE, HIP).
  */
 typedef struct {
   const void *wq, *wk, *wv, *wg, *bg, *wo;
   const void *bq, *bk, *bv, *bo;
+  const void *pe_k, *wc_k, *bc_k, *pe_v, *wc_v, *bc_v;
 } ssa_layer_weights_t;
 typedef struct {
   float *dwq, *dwk, *dwv, *dwg, *dbg, *dwo;
   float *dbq, *dbk, *dbv, *dbo;
+  float *dpe_k, *dwc_k, *dbc_k, *dpe_v, *dwc_v, *dbc_v;
 } ssa_layer_grads_t;
 size_t ssa_layer_saved_bytes(const ssa_params_t *params, size_t *offsets);
 size_t ssa_layer_workspace_bytes(const ssa_params_t *params, const ssa_blocks_t *blocks, int32_t d_model, int for_backward);

@@ -495,10 +495,17 @@ extern "C" int ssa_compress_backward(const ssa_params_t *p, const ssa_blocks_t *
   int C;
   const int rc = check(p, b, &C);
   if (rc != SSA_OK) return rc;
-  if (b->N == 0) return SSA_OK;
+  hipStream_t s = (hipStream_t)stream;
+  if (b->N == 0) {  // no tokens: the parameter gradients are zero
+    if (!dpe || !dw || !dbias) return SSA_ERR_NULL;
+    const size_t plen0 = (size_t)b->m_cmp * b->m_cmp * b->m_cmp * C, wlen0 = (size_t)27 * C * C;
+    c_sum_parts<<<(unsigned)((plen0 + 255) / 256), 256, 0, s>>>(nullptr, 0, 1, plen0, dpe);
+    c_sum_parts<<<(unsigned)((wlen0 + 255) / 256), 256, 0, s>>>(nullptr, 0, 1, wlen0, dw);
+    c_sum_parts<<<(C + 255) / 256, 256, 0, s>>>(nullptr, 0, 1, (size_t)C, dbias);
+    return hipGetLastError() == hipSuccess ? SSA_OK : SSA_ERR_HIP;
+  }
   if (!x || !wts || !wts->pe || !wts->w || !wts->bias || !dx_cmp || !dx_accum || !dpe || !dw || !dbias) return SSA_ERR_NULL;
   if (!ws_ || ws_bytes < ssa_compress_workspace_bytes(p, b, 1)) return SSA_ERR_WORKSPACE;
-  hipStream_t s = (hipStream_t)stream;
   const int N = b->N, m = b->m_cmp;
   const ModPlan pl = mod_plan(N, C, m, true);
   char *ws = (char *)align_up((size_t)ws_, 256);

@@ -35,10 +35,35 @@ SavedPlan saved_plan(const ssa_params_t *p) {
 }
 
 struct BwdPlan {
-  size_t d_o, dq, dk, dv, dg, scratch, scratch_bytes, total;
+  size_t d_o, dq, dk, dv, dg, kc, vc, dkc, dvc, scratch, scratch_bytes, total;
 };
 
+// Forward workspace: the learned module's block tokens in front of a scratch region shared by the parts.
+struct FwdPlan {
+  size_t kc, vc, scratch, scratch_bytes, total;
+};
+
+// 0: mean pool; 1: learned compression module on keys and values; -1: some but not all of its pointers given
+int module_mode(const ssa_layer_weights_t *w) {
+  const int n = (w->pe_k != nullptr) + (w->wc_k != nullptr) + (w->bc_k != nullptr) + (w->pe_v != nullptr) +
+                (w->wc_v != nullptr) + (w->bc_v != nullptr);
+  return n == 0 ? 0 : n == 6 ? 1 : -1;
+}
+
 size_t max3(size_t a, size_t b, size_t c) { return a > b ? (a > c ? a : c) : (b > c ? b : c); }
+
+FwdPlan fwd_plan(const ssa_params_t *p, const ssa_blocks_t *b, int Dm) {
+  const size_t ckv = (size_t)p->n_heads_kv * p->head_dim;
+  FwdPlan w{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) { const size_t r = off; off += align_up(bytes, 256); return r; };
+  w.kc = take((size_t)b->Nc * ckv * 2);
+  w.vc = take((size_t)b->Nc * ckv * 2);
+  w.scratch_bytes = max3(ssa_workspace_bytes(p, b, 0), ssa_gate_workspace_bytes(p, Dm, 0), ssa_compress_workspace_bytes(p, b, 0)) + 256;
+  w.scratch = take(w.scratch_bytes);
+  w.total = off;
+  return w;
+}
 
 BwdPlan bwd_plan(const ssa_params_t *p, const ssa_blocks_t *b, int Dm) {
   const size_t N = (size_t)p->n_tokens, cq = (size_t)p->n_heads_q * p->head_dim, ckv = (size_t)p->n_heads_kv * p->head_dim;
@@ -50,10 +75,15 @@ BwdPlan bwd_plan(const ssa_params_t *p, const ssa_blocks_t *b, int Dm) {
   w.dk = take(N * ckv * 2);
   w.dv = take(N * ckv * 2);
   w.dg = take(N * p->n_heads_q * 3 * 2);
+  w.kc = take((size_t)b->Nc * ckv * 2);  // the learned module's block tokens (recomputed) and their gradients
+  w.vc = take((size_t)b->Nc * ckv * 2);
+  w.dkc = take((size_t)b->Nc * ckv * 4);
+  w.dvc = take((size_t)b->Nc * ckv * 4);
   const size_t wt = align_up(cq * Dm * 2, 256) + 2 * align_up(ckv * Dm * 2, 256);  // transposed Wq, Wk, Wv
   const size_t lin = max3(ssa_linear_workspace_bytes(p->n_tokens, (int)cq, Dm, 1), lin_dw_workspace(p->n_tokens, Dm, (int)cq),
                           lin_dw_workspace(p->n_tokens, Dm, (int)ckv));
-  w.scratch_bytes = max3(max3(wt, lin, 0), ssa_workspace_bytes(p, b, 1), ssa_gate_workspace_bytes(p, Dm, 1)) + 256;
+  const size_t mod = max3(ssa_compress_workspace_bytes(p, b, 0), ssa_compress_workspace_bytes(p, b, 1), 0);
+  w.scratch_bytes = max3(max3(wt, lin, mod), ssa_workspace_bytes(p, b, 1), ssa_gate_workspace_bytes(p, Dm, 1)) + 256;
   w.scratch = take(w.scratch_bytes);
   w.total = off;
   return w;
@@ -88,8 +118,7 @@ extern "C" size_t ssa_layer_saved_bytes(const ssa_params_t *p, size_t *offsets) 
 extern "C" size_t ssa_layer_workspace_bytes(const ssa_params_t *p, const ssa_blocks_t *b, int32_t d_model, int for_backward) {
   if (layer_check(p, b, d_model) != SSA_OK) return 0;
   if (for_backward) return bwd_plan(p, b, d_model).total + 256;
-  const size_t a = ssa_workspace_bytes(p, b, 0), g = ssa_gate_workspace_bytes(p, d_model, 0);
-  return (a > g ? a : g) + 256;
+  return fwd_plan(p, b, d_model).total + 256;
 }
 
 extern "C" int ssa_layer_forward(const ssa_params_t *p, const ssa_blocks_t *b, int32_t d_model, const void *x,
@@ -102,16 +131,30 @@ extern "C" int ssa_layer_forward(const ssa_params_t *p, const ssa_blocks_t *b, i
   if (!w->wq || !w->wk || !w->wv || !w->wg || !w->bg || !w->wo) return SSA_ERR_NULL;
   if (saved_bytes < ssa_layer_saved_bytes(p, nullptr)) return SSA_ERR_WORKSPACE;
   if (!ws || ws_bytes < ssa_layer_workspace_bytes(p, b, d_model, 0)) return SSA_ERR_WORKSPACE;
+  const int mode = module_mode(w);
+  if (mode < 0) return SSA_ERR_NULL;
+  if (mode == 1 && ssa_compress_workspace_bytes(p, b, 0) == 0) return SSA_ERR_UNSUPPORTED;
   const SavedPlan s = saved_plan(p);
+  const FwdPlan pl = fwd_plan(p, b, d_model);
   char *sv = (char *)align_up((size_t)saved_, 256);
+  char *wsb = (char *)align_up((size_t)ws, 256);
+  char *scratch = wsb + pl.scratch;
   const int N = p->n_tokens, cq = p->n_heads_q * p->head_dim, ckv = p->n_heads_kv * p->head_dim;
   int rc = ssa_linear_forward(N, d_model, cq, x, w->wq, w->bq, sv + s.q, stream);
   if (rc == SSA_OK) rc = ssa_linear_forward(N, d_model, ckv, x, w->wk, w->bk, sv + s.k, stream);
   if (rc == SSA_OK) rc = ssa_linear_forward(N, d_model, ckv, x, w->wv, w->bv, sv + s.v, stream);
-  if (rc == SSA_OK) rc = ssa_gate_forward(p, d_model, x, w->wg, w->bg, sv + s.gates, ws, ws_bytes, stream);
-  if (rc == SSA_OK)
+  if (rc == SSA_OK) rc = ssa_gate_forward(p, d_model, x, w->wg, w->bg, sv + s.gates, scratch, pl.scratch_bytes, stream);
+  if (rc == SSA_OK && mode == 1) {
+    const ssa_cmp_weights_t ck{w->pe_k, w->wc_k, w->bc_k}, cv{w->pe_v, w->wc_v, w->bc_v};
+    rc = ssa_compress_forward(p, b, sv + s.k, &ck, wsb + pl.kc, scratch, pl.scratch_bytes, stream);
+    if (rc == SSA_OK) rc = ssa_compress_forward(p, b, sv + s.v, &cv, wsb + pl.vc, scratch, pl.scratch_bytes, stream);
+    if (rc == SSA_OK)
+      rc = ssa_forward_pooled(p, b, sv + s.q, sv + s.k, sv + s.v, sv + s.gates, wsb + pl.kc, wsb + pl.vc, sv + s.o,
+                              (float *)(sv + s.lse), (int32_t *)(sv + s.idx), sv + s.ob, scratch, pl.scratch_bytes, stream);
+  } else if (rc == SSA_OK) {
     rc = ssa_forward(p, b, sv + s.q, sv + s.k, sv + s.v, sv + s.gates, sv + s.o, (float *)(sv + s.lse), (int32_t *)(sv + s.idx),
-                     sv + s.ob, ws, ws_bytes, stream);
+                     sv + s.ob, scratch, pl.scratch_bytes, stream);
+  }
   if (rc == SSA_OK) rc = ssa_linear_forward(N, cq, d_model, sv + s.o, w->wo, w->bo, y, stream);
   return rc;
 }
@@ -123,6 +166,11 @@ extern "C" int ssa_layer_backward(const ssa_params_t *p, const ssa_blocks_t *b, 
   if (rc0 != SSA_OK) return rc0;
   if (!w || !g) return SSA_ERR_NULL;
   if (!g->dwq || !g->dwk || !g->dwv || !g->dwg || !g->dbg || !g->dwo) return SSA_ERR_NULL;
+  const int mode = module_mode(w);
+  if (mode < 0) return SSA_ERR_NULL;
+  if (mode == 1 && (!g->dpe_k || !g->dwc_k || !g->dbc_k || !g->dpe_v || !g->dwc_v || !g->dbc_v)) return SSA_ERR_NULL;
+  if (mode == 1 && ssa_compress_workspace_bytes(p, b, 1) == 0) return SSA_ERR_UNSUPPORTED;
+  const ssa_cmp_weights_t ck{w->pe_k, w->wc_k, w->bc_k}, cv{w->pe_v, w->wc_v, w->bc_v};
   hipStream_t st = (hipStream_t)stream;
   const int N = p->n_tokens, cq = p->n_heads_q * p->head_dim, ckv = p->n_heads_kv * p->head_dim;
   if (N == 0) {  // no tokens: every parameter gradient is zero (the parts write the zeros)
@@ -131,6 +179,10 @@ extern "C" int ssa_layer_backward(const ssa_params_t *p, const ssa_blocks_t *b, 
     if (rc == SSA_OK) rc = ssa_linear_backward(0, d_model, ckv, nullptr, nullptr, nullptr, nullptr, g->dwk, g->dbk, nullptr, 0, stream);
     if (rc == SSA_OK) rc = ssa_linear_backward(0, d_model, ckv, nullptr, nullptr, nullptr, nullptr, g->dwv, g->dbv, nullptr, 0, stream);
     if (rc == SSA_OK) rc = ssa_gate_backward(p, d_model, nullptr, nullptr, nullptr, nullptr, nullptr, g->dwg, g->dbg, nullptr, 0, stream);
+    if (rc == SSA_OK && mode == 1)
+      rc = ssa_compress_backward(p, b, nullptr, &ck, nullptr, nullptr, g->dpe_k, g->dwc_k, g->dbc_k, nullptr, 0, stream);
+    if (rc == SSA_OK && mode == 1)
+      rc = ssa_compress_backward(p, b, nullptr, &cv, nullptr, nullptr, g->dpe_v, g->dwc_v, g->dbc_v, nullptr, 0, stream);
     return rc;
   }
   if (!x || !saved_ || !dy || !dx) return SSA_ERR_NULL;
@@ -145,8 +197,24 @@ extern "C" int ssa_layer_backward(const ssa_params_t *p, const ssa_blocks_t *b, 
   // output projection: dO and its parameter gradients
   int rc = ssa_linear_backward(N, cq, d_model, sv + s.o, w->wo, dy, d_o, g->dwo, g->dbo, scratch, pl.scratch_bytes, stream);
   if (rc != SSA_OK) return rc;
-  rc = ssa_backward(p, b, sv + s.q, sv + s.k, sv + s.v, sv + s.gates, sv + s.ob, (const float *)(sv + s.lse),
-                    (const int32_t *)(sv + s.idx), d_o, dq, dk, dv, dg, scratch, pl.scratch_bytes, stream);
+  if (mode == 1) {
+    // the block tokens are recomputed rather than saved (two small launches); their gradients flow back through
+    // the module onto dk and dv
+    void *kc = ws + pl.kc, *vc = ws + pl.vc;
+    float *dkc = (float *)(ws + pl.dkc), *dvc = (float *)(ws + pl.dvc);
+    rc = ssa_compress_forward(p, b, sv + s.k, &ck, kc, scratch, pl.scratch_bytes, stream);
+    if (rc == SSA_OK) rc = ssa_compress_forward(p, b, sv + s.v, &cv, vc, scratch, pl.scratch_bytes, stream);
+    if (rc == SSA_OK)
+      rc = ssa_backward_pooled(p, b, sv + s.q, sv + s.k, sv + s.v, sv + s.gates, kc, vc, sv + s.ob, (const float *)(sv + s.lse),
+                               (const int32_t *)(sv + s.idx), d_o, dq, dk, dv, dg, dkc, dvc, scratch, pl.scratch_bytes, stream);
+    if (rc == SSA_OK)
+      rc = ssa_compress_backward(p, b, sv + s.k, &ck, dkc, dk, g->dpe_k, g->dwc_k, g->dbc_k, scratch, pl.scratch_bytes, stream);
+    if (rc == SSA_OK)
+      rc = ssa_compress_backward(p, b, sv + s.v, &cv, dvc, dv, g->dpe_v, g->dwc_v, g->dbc_v, scratch, pl.scratch_bytes, stream);
+  } else {
+    rc = ssa_backward(p, b, sv + s.q, sv + s.k, sv + s.v, sv + s.gates, sv + s.ob, (const float *)(sv + s.lse),
+                      (const int32_t *)(sv + s.idx), d_o, dq, dk, dv, dg, scratch, pl.scratch_bytes, stream);
+  }
   if (rc != SSA_OK) return rc;
   {
     ProfScope ps(PROF_LINEAR_BWD, st);

@@ -29,11 +29,13 @@ EXPORTED_SYMBOLS = (
 
 
 class ssa_layer_weights_t(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("wq", "wk", "wv", "wg", "bg", "wo", "bq", "bk", "bv", "bo")]
+    _fields_ = [(n, C.c_void_p) for n in ("wq", "wk", "wv", "wg", "bg", "wo", "bq", "bk", "bv", "bo",
+                                                 "pe_k", "wc_k", "bc_k", "pe_v", "wc_v", "bc_v")]
 
 
 class ssa_layer_grads_t(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("dwq", "dwk", "dwv", "dwg", "dbg", "dwo", "dbq", "dbk", "dbv", "dbo")]
+    _fields_ = [(n, C.c_void_p) for n in ("dwq", "dwk", "dwv", "dwg", "dbg", "dwo", "dbq", "dbk", "dbv", "dbo",
+                                                 "dpe_k", "dwc_k", "dbc_k", "dpe_v", "dwc_v", "dbc_v")]
 
 
 class ssa_params_t(C.Structure):
@@ -331,7 +333,8 @@ def _layer_struct(cls, tensors: dict):
 
 
 def ssa_layer_forward(params, blocks: Blocks, x, weights: dict, y, saved, workspace: Optional[torch.Tensor] = None) -> None:
-    """weights: dict of cuda bf16 tensors wq, wk, wv, wg, bg, wo (+ optional bq, bk, bv, bo)."""
+    """weights: dict of cuda bf16 tensors wq, wk, wv, wg, bg, wo (+ optional bq, bk, bv, bo; + pe_k, wc_k, bc_k, pe_v,
+    wc_v, bc_v for the learned compression module on keys and values, all six or none)."""
     d_model = x.shape[1]
     if workspace is None:
         workspace = torch.empty(max(ssa_layer_workspace_bytes(params, blocks, d_model, False), 1), dtype=torch.uint8, device="cuda")
@@ -342,7 +345,8 @@ def ssa_layer_forward(params, blocks: Blocks, x, weights: dict, y, saved, worksp
 
 def ssa_layer_backward(params, blocks: Blocks, x, weights: dict, saved, dy, dx, grads: dict,
                        workspace: Optional[torch.Tensor] = None) -> None:
-    """grads: dict of cuda float tensors dwq, dwk, dwv, dwg, dbg, dwo (+ optional dbq, dbk, dbv, dbo), overwritten."""
+    """grads: dict of cuda float tensors dwq, dwk, dwv, dwg, dbg, dwo (+ optional dbq, dbk, dbv, dbo; + dpe_k, dwc_k,
+    dbc_k, dpe_v, dwc_v, dbc_v when the module's weights are given), overwritten."""
     d_model = x.shape[1]
     if workspace is None:
         workspace = torch.empty(max(ssa_layer_workspace_bytes(params, blocks, d_model, True), 1), dtype=torch.uint8, device="cuda")

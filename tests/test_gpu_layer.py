@@ -102,6 +102,88 @@ def test_layer_forward_backward(seed, grid, n, hq, hkv, d, dm, topk, biases):
     print("  errors:", {k_: f"{v_[0]:.1e}/{v_[1]:.1e}" for k_, v_ in errs.items()}, flush=True)
 
 
+def test_layer_with_learned_compression_module():
+    """The layer with the learned compression module on keys and values (Sparse 3D Compression, eq. (5)) in place of
+    the mean pool: forward against the oracle chain fed the saved q, k, v, gates; backward end to end, including the
+    six parameter gradients of the two modules."""
+    import torch
+    from oracle.cmp_module import CompressionModule
+    from oracle.layer import block_tokens
+    from paper_2505_17412_amd import ssa
+    seed, hq, hkv, d, dm, topk = 84, 16, 2, 64, 256, 5
+    wl = inputs.random_points_workload(seed, 32, (1300, 800), hq, hkv, d, (4, 8, 8), topk, "bf16")
+    N, cq, ckv = wl.n_tokens, hq * d, hkv * d
+    rng = np.random.default_rng(seed)
+    r = inputs.round_to_bf16
+    gn = lambda *s: rng.standard_normal(s).astype(np.float32)
+    x, dy = r(gn(N, dm)), r(gn(N, dm))
+    w = make_weights(rng, dm, cq, ckv, hq, True)
+    for t in ("k", "v"):
+        w["pe_" + t] = r(0.5 * gn(64, ckv))
+        w["wc_" + t] = r(gn(27, ckv, ckv) / np.sqrt(9.0 * ckv))
+        w["bc_" + t] = r(0.1 * gn(ckv))
+    p, blk = util.build_blocks_gpu(wl)
+    tw = {k: util.to_dev(v, "bf16") for k, v in w.items()}
+    tx, tdy = util.to_dev(x, "bf16"), util.to_dev(dy, "bf16")
+    nbytes, offs = ssa.ssa_layer_saved_bytes(p)
+    saved = torch.zeros(nbytes + 256, dtype=torch.uint8, device="cuda")
+    y = torch.full((N, dm), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ssa.ssa_layer_forward(p, blk, tx, tw, y, saved)
+    torch.cuda.synchronize()
+    base = (-saved.data_ptr()) % 256
+
+    def view(name, shape, dtype):
+        nb = int(np.prod(shape)) * torch.empty((), dtype=dtype).element_size()
+        return util.to_np(saved[base + offs[name]: base + offs[name] + nb].view(dtype).view(*shape))
+
+    q, k, v = view("q", (N, hq, d), torch.bfloat16), view("k", (N, hkv, d), torch.bfloat16), view("v", (N, hkv, d), torch.bfloat16)
+    gates, o = view("gates", (N, hq, 3), torch.bfloat16), view("o", (N, hq, d), torch.bfloat16)
+    ob, idx = view("out_branch", (3, N, hq, d), torch.bfloat16), view("topk_idx", (N, hkv, topk), torch.int32)
+    orc = oracle_for(wl)
+    module = CompressionModule(wl.coords, wl.batch_offsets, wl.m_cmp, orc.blocks.ids["cmp"], orc.blocks.n_blocks["cmp"])
+    lw = LayerWeights(**w)
+    kc, vc = block_tokens(orc, module, k, v, lw)
+    kc, vc = r(kc.astype(np.float32)), r(vc.astype(np.float32))  # the block tokens cross the boundary in bf16
+    own = orc.forward(q, k, v, gates, want_scores=True, k_cmp=kc, v_cmp=vc)
+    util.check_topk(idx, own, orc, "bf16")
+    ref = orc.forward(q, k, v, gates, topk_idx=idx, k_cmp=kc, v_cmp=vc)
+    util.assert_close(o, ref.out, "bf16", "attention out")
+    pooled = orc.forward(q, k, v, gates, topk_idx=idx)
+    assert np.abs(pooled.out_branch[0] - ref.out_branch[0]).max() > 0.05  # not the mean pool
+    util.assert_close(util.to_np(y), linear_forward(o.reshape(N, cq), w["wo"], w["bo"]), "bf16", "y")
+    # ---- backward
+    g_names = ["d" + nm for nm in w]
+    grads = {nm: torch.full(w[nm[1:]].shape, float("nan"), dtype=torch.float32, device="cuda") for nm in g_names}
+    dx = torch.full((N, dm), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ssa.ssa_layer_backward(p, blk, tx, tw, saved, tdy, dx, grads)
+    torch.cuda.synchronize()
+    ref.out, ref.out_branch = o, ob
+    rb = layer_backward(orc, x, lw, LayerForward(q, k, v, gates, ref, None, kc, vc), dy, module=module)
+    errs = {"dx": util.assert_close(util.to_np(dx), rb["dx"], "bf16", "dx")}
+    for nm in g_names:
+        if nm == "dbc_k":
+            # one vector added to every block-level key shifts all compression scores of a query alike: the exact
+            # gradient is zero (the oracle's is not quite, it starts from the rounded out_branch the HIP path saved);
+            # what is left on both sides is rounding of the column sums of dk_cmp
+            bound = 2e-3 * np.abs(rb["dk_cmp"]).reshape(-1, ckv).sum(axis=0)
+            assert np.all(np.abs(util.to_np(grads[nm]) - rb[nm]) <= bound), nm
+            continue
+        if nm == "dbk":
+            # the selection and window parts of the column sums of dk cancel exactly (a vector added to every key
+            # leaves those softmaxes unchanged); only the module's part survives, far below the terms' absolute sum,
+            # which is what the rounding of dk scales with
+            bound = 2e-3 * np.abs(rb["dk"]).reshape(N, ckv).sum(axis=0)
+            assert np.all(np.abs(util.to_np(grads[nm]) - rb[nm]) <= bound), nm
+            continue
+        errs[nm] = util.assert_close(util.to_np(grads[nm]), rb[nm], "bf16", nm)
+    print("  errors:", {k_: f"{v_[0]:.1e}/{v_[1]:.1e}" for k_, v_ in errs.items()}, flush=True)
+    # some but not all of the module's pointers: refused
+    bad = dict(tw)
+    del bad["bc_v"]
+    with pytest.raises(ssa.SSAError):
+        ssa.ssa_layer_forward(p, blk, tx, bad, y, saved)
+
+
 def test_layer_validation():
     import torch
     from paper_2505_17412_amd import ssa
@@ -131,9 +213,11 @@ def test_layer_without_tokens():
     w = dict(wq=z(cq, dm), wk=z(ckv, dm), wv=z(ckv, dm), wg=z(dm, 3 * hq), bg=z(3 * hq), wo=z(dm, cq))
     x = z(0, dm)
     saved = torch.empty(max(ssa.ssa_layer_saved_bytes(p)[0], 1), dtype=torch.uint8, device="cuda")
-    ssa.ssa_layer_forward(p, blk, x, w, x, saved)
-    grads = {"d" + k_: torch.full(v_.shape, float("nan"), dtype=torch.float32, device="cuda") for k_, v_ in w.items()}
-    ssa.ssa_layer_backward(p, blk, x, w, saved, x, x, grads)
-    torch.cuda.synchronize()
-    for nm, t in grads.items():
-        assert float(t.abs().max()) == 0.0, nm
+    module = dict(pe_k=z(8, ckv), wc_k=z(27, ckv, ckv), bc_k=z(ckv), pe_v=z(8, ckv), wc_v=z(27, ckv, ckv), bc_v=z(ckv))
+    for weights in (w, dict(w, **module)):   # mean pool, then the learned compression module
+        ssa.ssa_layer_forward(p, blk, x, weights, x, saved)
+        grads = {"d" + k_: torch.full(v_.shape, float("nan"), dtype=torch.float32, device="cuda") for k_, v_ in weights.items()}
+        ssa.ssa_layer_backward(p, blk, x, weights, saved, x, x, grads)
+        torch.cuda.synchronize()
+        for nm, t in grads.items():
+            assert float(t.abs().max()) == 0.0, nm
