@@ -9,10 +9,6 @@
 
 namespace {
 
-struct LayerDims {
-  int N, Dm, Cq, Ckv, Hq, T;
-};
-
 struct SavedPlan {
   size_t q, k, v, gates, o, ob, lse, idx, total;
 };

@@ -17,12 +17,6 @@
 
 namespace {
 
-__device__ inline float wave_sum_f(float v) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
-  return v;
-}
-
 // ---------------------------------------------------------------------------------------------------------
 // Pre-pass: dgates, per-row scalars in sorted order, sorted copies of Q and dO.
 // One workgroup per sorted token position.

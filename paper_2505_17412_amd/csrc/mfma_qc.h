@@ -263,7 +263,7 @@ __device__ inline void topk_wave_bits(const uint32_t *S, int n, int T, int base,
   for (int r = 0; r < R; ++r) {
     const bool eq = Tn > 0 && val[r] == thr;
     const uint64_t em = __ballot(eq);
-    const bool sel = (Tn > 0 && val[r] > thr) || (eq && eq_before + __popcll(em & lt) < need);
+    const bool sel = (Tn > 0 && val[r] > thr) || (eq && eq_before + (int)__popcll(em & lt) < need);
     eq_before += __popcll(em);
     const uint64_t sm = __ballot(sel);
     if (sel) out[written + __popcll(sm & lt)] = base + r * 64 + lane;
