@@ -221,3 +221,58 @@ def test_layer_without_tokens():
         torch.cuda.synchronize()
         for nm, t in grads.items():
             assert float(t.abs().max()) == 0.0, nm
+
+
+def test_layer_step_replays_from_a_hip_graph():
+    """The whole layer step, learned compression module included, records into a HIP graph (the library calls allocate
+    nothing, synchronise nothing and record no memset nodes) and every replay, with eager work and synchronisations
+    in between, reproduces the eager results bit for bit."""
+    import torch
+    from paper_2505_17412_amd import ssa
+    hq, hkv, d, dm, topk = 16, 2, 64, 256, 6
+    wl = inputs.random_points_workload(91, 32, (2900, 1700), hq, hkv, d, (4, 8, 8), topk, "bf16")
+    N, cq, ckv = wl.n_tokens, hq * d, hkv * d
+    p, blk = util.build_blocks_gpu(wl)
+    gen = torch.Generator(device="cuda").manual_seed(91)
+    rnd = lambda *s_, scale=1.0: (torch.randn(s_, generator=gen, device="cuda") * scale).bfloat16()
+    x, dy = rnd(N, dm), rnd(N, dm)
+    w = dict(wq=rnd(cq, dm, scale=dm ** -0.5), wk=rnd(ckv, dm, scale=dm ** -0.5), wv=rnd(ckv, dm, scale=dm ** -0.5),
+             wg=rnd(dm, 3 * hq, scale=dm ** -0.5), bg=rnd(3 * hq), wo=rnd(dm, cq, scale=cq ** -0.5), bq=rnd(cq, scale=0.1),
+             bk=rnd(ckv, scale=0.1), bv=rnd(ckv, scale=0.1), bo=rnd(dm, scale=0.1))
+    for t in ("k", "v"):
+        w.update({"pe_" + t: rnd(64, ckv, scale=0.5), "wc_" + t: rnd(27, ckv, ckv, scale=(9.0 * ckv) ** -0.5),
+                  "bc_" + t: rnd(ckv, scale=0.1)})
+    grads = {"d" + k_: torch.empty(v_.shape, device="cuda") for k_, v_ in w.items()}
+    y, dx = torch.empty_like(x), torch.empty_like(x)
+    saved = torch.empty(ssa.ssa_layer_saved_bytes(p)[0], dtype=torch.uint8, device="cuda")
+    wsf = torch.empty(ssa.ssa_layer_workspace_bytes(p, blk, dm, False), dtype=torch.uint8, device="cuda")
+    wsb = torch.empty(ssa.ssa_layer_workspace_bytes(p, blk, dm, True), dtype=torch.uint8, device="cuda")
+
+    def step():
+        ssa.ssa_layer_forward(p, blk, x, w, y, saved, wsf)
+        ssa.ssa_layer_backward(p, blk, x, w, saved, dy, dx, grads, wsb)
+
+    step()
+    torch.cuda.synchronize()
+    outputs = dict(y=y, dx=dx, **grads)
+    eager = {nm: t.clone() for nm, t in outputs.items()}
+    assert all(bool(torch.isfinite(t.float()).all()) for t in eager.values())
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                      # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    for r in range(3):
+        for t in outputs.values():
+            t.fill_(float("nan"))   # eager work between the replays: the graph must rewrite every output
+        for buf in (saved, wsf, wsb):
+            buf.random_(0, 255)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for nm, t in outputs.items():
+            assert torch.equal(t, eager[nm]), (r, nm)
