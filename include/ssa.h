@@ -18,6 +18,8 @@
  *   - dtype selects the element type of q,k,v,gates,out,out_branch,dout,dq,dk,dv,dgates: SSA_BF16 (2 bytes,
  *     bfloat16) or SSA_F32.  lse is always float, indices are int32.
  *   - The caller owns every tensor and the workspace.  The library owns only ssa_blocks_t.
+ *   - Every tensor pointer must sit on a 16-byte boundary (the kernels use 16-byte vector accesses); otherwise
+ *     SSA_ERR_ALIGNMENT.  Workspaces may start anywhere: the library aligns inside them.
  *   - ssa_forward / ssa_backward enqueue work on `stream` (a hipStream_t passed as void*) and return without
  *     synchronising; they never allocate.  ssa_build_blocks allocates the handle's arrays and synchronises
  *     the stream once to learn the block counts.
@@ -49,7 +51,8 @@ typedef enum {
   SSA_ERR_WORKSPACE = -7,       /* workspace NULL or smaller than ssa_workspace_bytes() */
   SSA_ERR_UNSUPPORTED = -8,     /* block side not a power of two; head_dim not a multiple of 8 or > 128 */
   SSA_ERR_HIP = -9,             /* a HIP runtime call failed */
-  SSA_ERR_MISMATCH = -10        /* params disagree with the ones the blocks handle was built with */
+  SSA_ERR_MISMATCH = -10,       /* params disagree with the ones the blocks handle was built with */
+  SSA_ERR_ALIGNMENT = -11       /* a tensor pointer is not 16-byte aligned */
 } ssa_status_t;
 
 typedef struct {

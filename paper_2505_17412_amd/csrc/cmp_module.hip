@@ -470,6 +470,7 @@ extern "C" int ssa_compress_forward(const ssa_params_t *p, const ssa_blocks_t *b
   if (rc != SSA_OK) return rc;
   if (b->N == 0) return SSA_OK;
   if (!x || !wts || !wts->pe || !wts->w || !wts->bias || !x_cmp) return SSA_ERR_NULL;
+  if (!aligned16(x, wts->pe, wts->w, wts->bias, x_cmp)) return SSA_ERR_ALIGNMENT;
   if (!ws_ || ws_bytes < ssa_compress_workspace_bytes(p, b, 0)) return SSA_ERR_WORKSPACE;
   hipStream_t s = (hipStream_t)stream;
   const int N = b->N;
@@ -505,6 +506,7 @@ extern "C" int ssa_compress_backward(const ssa_params_t *p, const ssa_blocks_t *
     return hipGetLastError() == hipSuccess ? SSA_OK : SSA_ERR_HIP;
   }
   if (!x || !wts || !wts->pe || !wts->w || !wts->bias || !dx_cmp || !dx_accum || !dpe || !dw || !dbias) return SSA_ERR_NULL;
+  if (!aligned16(x, wts->pe, wts->w, wts->bias, dx_cmp, dx_accum, dpe, dw, dbias)) return SSA_ERR_ALIGNMENT;
   if (!ws_ || ws_bytes < ssa_compress_workspace_bytes(p, b, 1)) return SSA_ERR_WORKSPACE;
   const int N = b->N, m = b->m_cmp;
   const ModPlan pl = mod_plan(N, C, m, true);

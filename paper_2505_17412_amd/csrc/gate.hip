@@ -271,6 +271,7 @@ extern "C" int ssa_gate_forward(const ssa_params_t *p, int32_t d_model, const vo
   const int N = p->n_tokens;
   if (N == 0) return SSA_OK;
   if (!x || !w || !bias || !gates) return SSA_ERR_NULL;
+  if (!aligned16(x, w, bias, gates)) return SSA_ERR_ALIGNMENT;
   if (!ws_ || ws_bytes < ssa_gate_workspace_bytes(p, d_model, 0)) return SSA_ERR_WORKSPACE;
   hipStream_t s = (hipStream_t)stream;
   const GatePlan pl = gate_plan(N, d_model, J, false);
@@ -304,6 +305,7 @@ extern "C" int ssa_gate_backward(const ssa_params_t *p, int32_t d_model, const v
     return hipGetLastError() == hipSuccess ? SSA_OK : SSA_ERR_HIP;
   }
   if (!x || !w || !gates || !dgates || !dx_accum || !dw || !dbias) return SSA_ERR_NULL;
+  if (!aligned16(x, w, gates, dgates, dx_accum, dw, dbias)) return SSA_ERR_ALIGNMENT;
   if (!ws_ || ws_bytes < ssa_gate_workspace_bytes(p, d_model, 1)) return SSA_ERR_WORKSPACE;
   const GatePlan pl = gate_plan(N, d_model, J, true);
   char *ws = (char *)align_up((size_t)ws_, 256);

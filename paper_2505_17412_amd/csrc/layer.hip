@@ -125,6 +125,7 @@ extern "C" int ssa_layer_forward(const ssa_params_t *p, const ssa_blocks_t *b, i
   if (p->n_tokens == 0) return SSA_OK;
   if (!x || !w || !y || !saved_) return SSA_ERR_NULL;
   if (!w->wq || !w->wk || !w->wv || !w->wg || !w->bg || !w->wo) return SSA_ERR_NULL;
+  if (!aligned16(x, y)) return SSA_ERR_ALIGNMENT;  // the weights are checked by the parts
   if (saved_bytes < ssa_layer_saved_bytes(p, nullptr)) return SSA_ERR_WORKSPACE;
   if (!ws || ws_bytes < ssa_layer_workspace_bytes(p, b, d_model, 0)) return SSA_ERR_WORKSPACE;
   const int mode = module_mode(w);
@@ -182,6 +183,7 @@ extern "C" int ssa_layer_backward(const ssa_params_t *p, const ssa_blocks_t *b, 
     return rc;
   }
   if (!x || !saved_ || !dy || !dx) return SSA_ERR_NULL;
+  if (!aligned16(x, dy, dx, w->wq, w->wk, w->wv, g->dwq, g->dwk, g->dwv, g->dbq, g->dbk, g->dbv)) return SSA_ERR_ALIGNMENT;
   if (!w->wq || !w->wk || !w->wv || !w->wg || !w->wo) return SSA_ERR_NULL;
   if (!ws_ || ws_bytes < ssa_layer_workspace_bytes(p, b, d_model, 1)) return SSA_ERR_WORKSPACE;
   const SavedPlan s = saved_plan(p);

@@ -366,6 +366,7 @@ extern "C" int ssa_linear_forward(int32_t n_tokens, int32_t d_in, int32_t d_out,
   if (rc != SSA_OK) return rc;
   if (n_tokens == 0) return SSA_OK;
   if (!x || !w || !y) return SSA_ERR_NULL;
+  if (!aligned16(x, w, bias, y)) return SSA_ERR_ALIGNMENT;
   hipStream_t s = (hipStream_t)stream;
   ProfScope ps(PROF_LINEAR_FWD, s);
   const int lrc = lin_nt_multi(1, &x, &w, &d_in, bias, n_tokens, d_out, y, s);
@@ -389,6 +390,7 @@ extern "C" int ssa_linear_backward(int32_t n_tokens, int32_t d_in, int32_t d_out
     return SSA_OK;
   }
   if (!x || !w || !dy) return SSA_ERR_NULL;
+  if (!aligned16(x, w, dy, dx, dw, dbias)) return SSA_ERR_ALIGNMENT;
   if (!ws_ || ws_bytes < ssa_linear_workspace_bytes(n_tokens, d_in, d_out, 1)) return SSA_ERR_WORKSPACE;
   const LinPlan pl = lin_plan(n_tokens, d_in, d_out);
   char *ws = (char *)align_up((size_t)ws_, 256);

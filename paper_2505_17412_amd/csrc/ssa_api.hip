@@ -57,6 +57,7 @@ extern "C" int ssa_forward(const ssa_params_t *p, const ssa_blocks_t *b, const v
   if (rc != SSA_OK) return rc;
   if (c.N == 0) return SSA_OK;
   if (!q || !k || !v || !gates || !out) return SSA_ERR_NULL;
+  if (!aligned16(q, k, v, gates, out, lse, topk_idx, out_branch)) return SSA_ERR_ALIGNMENT;
   if (!ws || ws_bytes < ssa_workspace_bytes(p, b, 0)) return SSA_ERR_WORKSPACE;
   void *w = (void *)align_up((size_t)ws, 256);
   const size_t wb = ws_bytes - ((size_t)w - (size_t)ws);
@@ -74,6 +75,7 @@ extern "C" int ssa_backward(const ssa_params_t *p, const ssa_blocks_t *b, const 
   if (c.N == 0) return SSA_OK;
   if (!q || !k || !v || !gates || !out_branch || !lse || !topk_idx || !dout || !dq || !dk || !dv || !dgates)
     return SSA_ERR_NULL;
+  if (!aligned16(q, k, v, gates, out_branch, lse, topk_idx, dout, dq, dk, dv, dgates)) return SSA_ERR_ALIGNMENT;
   if (!ws || ws_bytes < ssa_workspace_bytes(p, b, 1)) return SSA_ERR_WORKSPACE;
   void *w = (void *)align_up((size_t)ws, 256);
   const size_t wb = ws_bytes - ((size_t)w - (size_t)ws);
@@ -92,6 +94,7 @@ extern "C" int ssa_forward_pooled(const ssa_params_t *p, const ssa_blocks_t *b, 
   if (!use_mfma(c)) return SSA_ERR_UNSUPPORTED;
   if (c.N == 0) return SSA_OK;
   if (!q || !k || !v || !gates || !k_cmp || !v_cmp || !out) return SSA_ERR_NULL;
+  if (!aligned16(q, k, v, gates, k_cmp, v_cmp, out, lse, topk_idx, out_branch)) return SSA_ERR_ALIGNMENT;
   if (!ws || ws_bytes < ssa_workspace_bytes(p, b, 0)) return SSA_ERR_WORKSPACE;
   void *w = (void *)align_up((size_t)ws, 256);
   const size_t wb = ws_bytes - ((size_t)w - (size_t)ws);
@@ -112,6 +115,8 @@ extern "C" int ssa_backward_pooled(const ssa_params_t *p, const ssa_blocks_t *b,
   if (!q || !k || !v || !gates || !k_cmp || !v_cmp || !out_branch || !lse || !topk_idx || !dout || !dq || !dk || !dv ||
       !dgates || !dk_cmp || !dv_cmp)
     return SSA_ERR_NULL;
+  if (!aligned16(q, k, v, gates, k_cmp, v_cmp, out_branch, lse, topk_idx, dout, dq, dk, dv, dgates, dk_cmp, dv_cmp))
+    return SSA_ERR_ALIGNMENT;
   if (!ws || ws_bytes < ssa_workspace_bytes(p, b, 1)) return SSA_ERR_WORKSPACE;
   void *w = (void *)align_up((size_t)ws, 256);
   const size_t wb = ws_bytes - ((size_t)w - (size_t)ws);
@@ -145,6 +150,7 @@ extern "C" const char *ssa_error_string(int s) {
     case SSA_ERR_UNSUPPORTED: return "unsupported configuration (block side not a power of two, or head_dim)";
     case SSA_ERR_HIP: return "a HIP runtime call failed";
     case SSA_ERR_MISMATCH: return "parameters do not match the blocks handle";
+    case SSA_ERR_ALIGNMENT: return "a tensor pointer is not 16-byte aligned";
     default: return "unknown status";
   }
 }

@@ -36,6 +36,10 @@ struct ssa_blocks {
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// True when every pointer of the list (NULL included) sits on a 16-byte boundary: the kernels read and write tensors
+// through 16-byte vector accesses.
+template <typename... P> static inline bool aligned16(P... p) { return ((((size_t)p) | ...) & 15) == 0; }
+
 static inline int ilog2_exact(int m) {  // m is a power of two
   int l = 0;
   while ((1 << l) < m) ++l;

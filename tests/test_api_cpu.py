@@ -27,8 +27,8 @@ def test_library_exports_every_declared_symbol():
 
 def test_error_strings():
     assert ssa.error_string(0) == "ok"
-    seen = {ssa.error_string(-i) for i in range(1, 11)}
-    assert len(seen) == 10 and "unknown status" not in seen
+    seen = {ssa.error_string(-i) for i in range(1, 12)}
+    assert len(seen) == 11 and "unknown status" not in seen
     assert ssa.error_string(-99) == "unknown status"
 
 

@@ -119,6 +119,13 @@ def test_validation_on_gpu():
     with pytest.raises(ssa.SSAError) as e:
         ssa.ssa_forward(p2, blk, q, k, v, g, out)
     assert e.value.status == -10
+    # a tensor that does not start on a 16-byte boundary is refused before anything is launched
+    shifted = torch.zeros(q.numel() + 1, dtype=q.dtype, device="cuda")[1:].view(q.shape)
+    assert shifted.data_ptr() % 16 == 4
+    for args in ((shifted, k, v, g, out), (q, k, v, g, shifted)):
+        with pytest.raises(ssa.SSAError) as e:
+            ssa.ssa_forward(p, blk, *args)
+        assert e.value.status == -11
     p3 = util.params_of(wl)
     p3.n_heads_kv = 3
     with pytest.raises(ssa.SSAError) as e:
