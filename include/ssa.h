@@ -256,6 +256,19 @@ int ssa_gate_backward(const ssa_params_t *params, int32_t d_model, const void *x
                       size_t workspace_bytes, void *stream);
 
 /*
+ * ssa_gate_forward for callers that cannot allocate device memory and have no workspace to hand in: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same result as ssa_gate_forward, bit for bit;
+ * the transposed copy of w (the only scratch memory of the forward pass) lives in a 512 KiB array inside the library
+ * instead, one per GPU, held until the process ends.  Limit: d_model <= 4096 (larger: SSA_ERR_UNSUPPORTED; the other
+ * limits are those of ssa_gate_forward).  Calls no hipMalloc / hipFree and nothing else that allocates; the first call
+ * on a device looks up the array's address (make that call outside a graph capture).  All calls on one GPU share the
+ * array, which is rewritten by every call: calls that overlap in time on the same GPU (different streams or threads)
+ * race and must be serialised by the caller.  Errors: NULL, BAD_SHAPE, BAD_HEADS, UNSUPPORTED, ALIGNMENT, HIP.
+ */
+int ssa_gate_forward_static(const ssa_params_t *params, int32_t d_model, const void *x, const void *w, const void *bias,
+                            void *gates, void *stream);
+
+/*
  * One full SSA attention layer, composed from the entry points above (the paper gives the parts: projections of the
  * input features to queries, keys and values, gates = sigmoid of a linear layer on the same features, eq. (4), and an
  * output projection; hidden dimension 1024 in its DiT):

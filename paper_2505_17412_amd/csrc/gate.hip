@@ -15,6 +15,8 @@
 #include "mfma_qc.h"
 #include "profile.h"
 
+#include <mutex>
+
 namespace {
 
 constexpr int JP = 64;  // padded gate count (columns of dz and of the padded weights)
@@ -263,20 +265,9 @@ extern "C" size_t ssa_gate_workspace_bytes(const ssa_params_t *p, int32_t d_mode
   return gate_plan(p->n_tokens, d_model, J, for_backward != 0).total + 256;
 }
 
-extern "C" int ssa_gate_forward(const ssa_params_t *p, int32_t d_model, const void *x, const void *w, const void *bias,
-                                void *gates, void *ws_, size_t ws_bytes, void *stream) {
-  int J;
-  const int rc = gate_check(p, d_model, &J);
-  if (rc != SSA_OK) return rc;
-  const int N = p->n_tokens;
-  if (N == 0) return SSA_OK;
-  if (!x || !w || !bias || !gates) return SSA_ERR_NULL;
-  if (!aligned16(x, w, bias, gates)) return SSA_ERR_ALIGNMENT;
-  if (!ws_ || ws_bytes < ssa_gate_workspace_bytes(p, d_model, 0)) return SSA_ERR_WORKSPACE;
-  hipStream_t s = (hipStream_t)stream;
-  const GatePlan pl = gate_plan(N, d_model, J, false);
-  char *ws = (char *)align_up((size_t)ws_, 256);
-  bf16_t *wt = (bf16_t *)(ws + pl.wt);
+// Forward launches with the transposed weight copy in `wt` (device, ((J+15)/16*16) * d_model bf16).
+static int gate_forward_launch(int N, int d_model, int J, const void *x, const void *w, const void *bias, void *gates,
+                               bf16_t *wt, hipStream_t s) {
   const int NB = (J + 15) / 16, JR = 16 * NB;
   ProfScope ps(PROF_GATE_FWD, s);
   g_prep_w<<<(unsigned)(((size_t)JR * d_model + 255) / 256), 256, 0, s>>>((const bf16_t *)w, d_model, J, JR, wt, nullptr);
@@ -288,6 +279,61 @@ extern "C" int ssa_gate_forward(const ssa_params_t *p, int32_t d_model, const vo
     default: g_fwd<4><<<grid, 256, 0, s>>>((const bf16_t *)x, wt, (const bf16_t *)bias, N, d_model, J, (bf16_t *)gates); break;
   }
   return hipGetLastError() == hipSuccess ? SSA_OK : SSA_ERR_HIP;
+}
+
+extern "C" int ssa_gate_forward(const ssa_params_t *p, int32_t d_model, const void *x, const void *w, const void *bias,
+                                void *gates, void *ws_, size_t ws_bytes, void *stream) {
+  int J;
+  const int rc = gate_check(p, d_model, &J);
+  if (rc != SSA_OK) return rc;
+  const int N = p->n_tokens;
+  if (N == 0) return SSA_OK;
+  if (!x || !w || !bias || !gates) return SSA_ERR_NULL;
+  if (!aligned16(x, w, bias, gates)) return SSA_ERR_ALIGNMENT;
+  if (!ws_ || ws_bytes < ssa_gate_workspace_bytes(p, d_model, 0)) return SSA_ERR_WORKSPACE;
+  const GatePlan pl = gate_plan(N, d_model, J, false);
+  char *ws = (char *)align_up((size_t)ws_, 256);
+  return gate_forward_launch(N, d_model, J, x, w, bias, gates, (bf16_t *)(ws + pl.wt), (hipStream_t)stream);
+}
+
+// ---- the same forward for callers that cannot allocate: the transposed weight copy lives in a static device array.
+// Every device the library runs on holds its own copy of the array at its own address; the address is looked up once
+// per device (with that device current) and only that pointer is ever handed to a kernel.
+constexpr int GATE_STATIC_MAX_DMODEL = 4096;
+constexpr size_t GATE_STATIC_BYTES = (size_t)JP * GATE_STATIC_MAX_DMODEL * sizeof(bf16_t);  // 512 KiB
+static __device__ __align__(256) unsigned char scratch[GATE_STATIC_BYTES];
+
+constexpr int GATE_MAX_DEVICES = 64;
+static std::mutex scratch_mutex;
+static void *scratch_ptr[GATE_MAX_DEVICES];  // device address of `scratch` per HIP device, NULL until looked up
+
+static int gate_scratch(void **out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= GATE_MAX_DEVICES) return SSA_ERR_HIP;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (!scratch_ptr[dev]) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return SSA_ERR_HIP;
+    scratch_ptr[dev] = ptr;
+  }
+  *out = scratch_ptr[dev];
+  return SSA_OK;
+}
+
+extern "C" int ssa_gate_forward_static(const ssa_params_t *p, int32_t d_model, const void *x, const void *w,
+                                       const void *bias, void *gates, void *stream) {
+  int J;
+  const int rc = gate_check(p, d_model, &J);
+  if (rc != SSA_OK) return rc;
+  if (d_model > GATE_STATIC_MAX_DMODEL) return SSA_ERR_UNSUPPORTED;  // the static array holds 64 x 4096 weights
+  const int N = p->n_tokens;
+  if (N == 0) return SSA_OK;
+  if (!x || !w || !bias || !gates) return SSA_ERR_NULL;
+  if (!aligned16(x, w, bias, gates)) return SSA_ERR_ALIGNMENT;
+  void *wt = nullptr;
+  const int rs = gate_scratch(&wt);
+  if (rs != SSA_OK) return rs;
+  return gate_forward_launch(N, d_model, J, x, w, bias, gates, (bf16_t *)wt, (hipStream_t)stream);
 }
 
 extern "C" int ssa_gate_backward(const ssa_params_t *p, int32_t d_model, const void *x, const void *w, const void *gates,

@@ -22,7 +22,7 @@ EXPORTED_SYMBOLS = (
     "ssa_blocks_destroy", "ssa_workspace_bytes", "ssa_forward", "ssa_backward", "ssa_topk_from_scores",
     "ssa_error_string", "ssa_profile_enable", "ssa_profile_num_kernels", "ssa_profile_get",
     "ssa_compress_workspace_bytes", "ssa_compress_forward", "ssa_compress_backward", "ssa_forward_pooled",
-    "ssa_backward_pooled", "ssa_gate_workspace_bytes", "ssa_gate_forward", "ssa_gate_backward",
+    "ssa_backward_pooled", "ssa_gate_workspace_bytes", "ssa_gate_forward", "ssa_gate_backward", "ssa_gate_forward_static",
     "ssa_linear_workspace_bytes", "ssa_linear_forward", "ssa_linear_backward",
     "ssa_layer_saved_bytes", "ssa_layer_workspace_bytes", "ssa_layer_forward", "ssa_layer_backward",
 )
@@ -94,6 +94,7 @@ def lib() -> C.CDLL:
         L.ssa_gate_workspace_bytes.restype = C.c_size_t
         L.ssa_gate_forward.argtypes = [C.POINTER(ssa_params_t), C.c_int32] + [vp] * 4 + [vp, C.c_size_t, vp]
         L.ssa_gate_backward.argtypes = [C.POINTER(ssa_params_t), C.c_int32] + [vp] * 7 + [vp, C.c_size_t, vp]
+        L.ssa_gate_forward_static.argtypes = [C.POINTER(ssa_params_t), C.c_int32] + [vp] * 4 + [vp]
         L.ssa_forward_pooled.argtypes = [C.POINTER(ssa_params_t), vp] + [vp] * 10 + [vp, C.c_size_t, vp]
         L.ssa_backward_pooled.argtypes = [C.POINTER(ssa_params_t), vp] + [vp] * 16 + [vp, C.c_size_t, vp]
         L.ssa_profile_enable.argtypes = [C.c_int]
@@ -263,6 +264,11 @@ def ssa_gate_forward(params, d_model: int, x, w, bias, gates, workspace: Optiona
         workspace = torch.empty(ssa_gate_workspace_bytes(params, d_model, False), dtype=torch.uint8, device="cuda")
     _check(lib().ssa_gate_forward(C.byref(params), int(d_model), _ptr(x), _ptr(w), _ptr(bias), _ptr(gates), _ptr(workspace),
                                   workspace.numel(), _stream()), "ssa_gate_forward")
+
+
+def ssa_gate_forward_static(params, d_model: int, x, w, bias, gates) -> None:
+    _check(lib().ssa_gate_forward_static(C.byref(params), int(d_model), _ptr(x), _ptr(w), _ptr(bias), _ptr(gates), _stream()),
+           "ssa_gate_forward_static")
 
 
 def ssa_gate_backward(params, d_model: int, x, w, gates, dgates, dx_accum, dw, dbias,
