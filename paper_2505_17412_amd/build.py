@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "lib", "libssa_hip.so")
 
-SOURCES = ["ssa_api.hip", "build_blocks.hip", "generic_kernels.hip", "mfma_path.hip", "mfma_fwd.hip", "mfma_bwd.hip", "cmp_module.hip", "gate.hip", "linear.hip", "layer.hip", "slc_order.hip", "profile.hip"]
+SOURCES = ["ssa_api.hip", "build_blocks.hip", "generic_kernels.hip", "mfma_path.hip", "mfma_fwd.hip", "mfma_bwd.hip", "cmp_module.hip", "gate.hip", "linear.hip", "layer.hip", "sel_index.hip", "profile.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -13,7 +13,10 @@
 #include "mfma_common.h"
 #include "mfma_launch.h"
 #include "mfma_qc.h"
+#include "mfma_bc.h"
 #include "profile.h"
+
+#include <mutex>
 
 namespace {
 
@@ -81,12 +84,8 @@ __global__ __launch_bounds__(256) void m_bwd_pre(PreArgs a) {
 struct DqArgs {
   MfmaView v;
   const bf16_t *Q, *dO;
-  const int32_t *idx;
   const float *lse2s, *deltas, *gws;  // [3][N(pos)][Hq]
-  bf16_t *dQ;
-  float *dQp;  // [N(pos)][Hq][D] fp32: compression + window part of dQ, handed from the first dQ kernel to the second
-  const int32_t *slc_order;  // [Hkv][N] token order of the selection part (caller indices), or NULL: sorted order
-  const int32_t *inv_perm;   // [N] caller index -> sorted position
+  float *dQp;  // [N(pos)][Hq][D] fp32: compression + window part of dQ
 };
 
 // One staged 32-key tile: transposed scores (K rows) and dP (V rows), then dQ^T += K^T dS^T (the K rows again, read
@@ -141,35 +140,25 @@ __device__ inline void dq_tile(f32x4 (&acc)[CB][D / 16], const QRows<D, CB> &q, 
   }
 }
 
-// LDS plan of the dQ kernel (bytes): two stages (K rows, V rows) | 8 ints | selection lists as in the
-// forward selection kernel.
+// LDS plan of the dQ kernel (bytes): two stages (K rows, V rows) | 8 ints
 template <int D>
-__host__ __device__ inline size_t dq_lds_bytes(int tw, int T, int Ns) {
-  return (size_t)2 * StageLayout<D, 2>::ELEMS * sizeof(bf16_t) + 32 + ((size_t)tw * T * 4 + (size_t)(Ns + 31) / 32 + 4) * 4;
-}
+__host__ __device__ inline size_t dq_lds_bytes() { return (size_t)2 * StageLayout<D, 2>::ELEMS * sizeof(bf16_t) + 32; }
 
-// PART 0: compression branch, then the (small) window branch, in the sorted token order; result kept in fp32.
-// PART 1: selection branch on top of it, in the selection order of the KV head (tokens with similar selected sets
-// next to each other), final bf16 dQ.
-template <int D, int CB, int PART, int NW>
+// dQ of the compression branch, then of the (small) window branch, in the sorted token order; the sum is kept in fp32 by
+// sorted position (dQp) for the merge with the selection branch's partials.
+template <int D, int CB, int NW>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4 : 2))) void m_bwd_dq(DqArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   using L = StageLayout<D, 2>;
   bf16_t *stage0 = (bf16_t *)smem;
   int *ints = (int *)(stage0 + 2 * L::ELEMS);
   const int quad = threadIdx.x >> 4 & 3;
-  const int hs = a.v.hs, T = a.v.T, N = a.v.N, TW = NW * CB * 16 / hs;
+  const int hs = a.v.hs, N = a.v.N, TW = NW * CB * 16 / hs;
   const TileMap tm = xcd_tile_map((N + TW - 1) / TW, a.v.Hkv);
   if (!tm.valid) return;
   const int g = tm.g, wg_pos0 = tm.tile * TW;
-  int *Irows = ints + 8;
-  int *ub = Irows + TW * T, *us = ub + TW * T, *ue = us + TW * T;
-  uint32_t *bits = (uint32_t *)(ue + TW * T);
   QRows<D, CB> q;
-  MfmaView vo = a.v;  // position -> token: the sorted order, or the selection order of this KV head
-  const bool reordered = PART == 1 && a.slc_order != nullptr;
-  if (reordered) vo.perm = a.slc_order + (size_t)g * N;
-  load_rows<D, CB>(a.Q, vo, wg_pos0, g, q);
+  load_rows<D, CB>(a.Q, a.v, wg_pos0, g, q);
   bf16x8 dop[CB][D / 32];
   size_t rs_[CB];  // row of the per-row arrays, which are laid out by sorted position
 #pragma unroll
@@ -177,27 +166,21 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
     const bf16_t *src = a.dO + ((size_t)q.tok[cb] * a.v.Hq + q.h[cb]) * D + 8 * quad;
 #pragma unroll
     for (int ks = 0; ks < D / 32; ++ks) dop[cb][ks] = q.valid[cb] ? ld8(src + 32 * ks) : zero8();
-    const int spos = !q.valid[cb] ? 0 : (reordered ? a.inv_perm[q.tok[cb]] : q.pos[cb]);
-    rs_[cb] = (size_t)spos * a.v.Hq + q.h[cb];
+    rs_[cb] = (size_t)(q.valid[cb] ? q.pos[cb] : 0) * a.v.Hq + q.h[cb];
   }
   const size_t NH = (size_t)N * a.v.Hq;
   f32x4 acc[CB][D / 16];
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-    for (int dt = 0; dt < D / 16; ++dt) {
-      acc[cb][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-      if (PART == 1 && q.valid[cb])
-        acc[cb][dt] = *reinterpret_cast<const f32x4 *>(a.dQp + rs_[cb] * D + 16 * dt + 4 * quad);
-    }
+    for (int dt = 0; dt < D / 16; ++dt) acc[cb][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
   const float sl2 = a.v.sl2, scale = a.v.scale;
   const size_t kstride = (size_t)a.v.Hkv * D;
   int lo[CB], hi[CB];
   bool act[CB];
   float lse2[CB], delta[CB], gw[CB];
-
-  // ---- compression and window branches: one key range each, per-lane [lo, hi)
-  for (int branch = 0; PART == 0 && branch <= 2; branch += 2) {
+  // one key range per branch, per-lane [lo, hi)
+  for (int branch = 0; branch <= 2; branch += 2) {
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) {
       if (branch == 0) {
@@ -234,69 +217,192 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
                                  scale, lse2, delta, gw);
         });
   }
-  // ---- selection branch: union of the selected blocks of the workgroup's tokens
-  if (PART == 1) {
-    build_union(vo, a.idx, wg_pos0, g, TW, Irows, ub, us, ue, bits, &ints[0]);
-    const int nr = lds_uniform(&ints[0]);
-    int jc[CB];
-    float lse_own[CB];
-#pragma unroll
-    for (int cb = 0; cb < CB; ++cb) {
-      jc[cb] = 0; lo[cb] = hi[cb] = 0; act[cb] = false;
-      lse_own[cb] = a.lse2s[NH + rs_[cb]];
-      delta[cb] = a.deltas[NH + rs_[cb]];
-      gw[cb] = a.gws[NH + rs_[cb]];
-    }
-    int rs = 0, re = 0;
-    TileSrc<2> src{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, (uint32_t)kstride};
-    run_pipeline<D, 2, 64 * NW, 1>(
-        src, stage0, us, ue, nr,
-        [&](int r) {
-          const int b = lds_uniform(&ub[r]);
-          rs = lds_uniform(&us[r]);
-          re = lds_uniform(&ue[r]);
-#pragma unroll
-          for (int cb = 0; cb < CB; ++cb) {
-            const int cur = (q.valid[cb] && jc[cb] < T) ? Irows[q.slot[cb] * T + jc[cb]] : -1;
-            const bool sel = cur == b;
-            if (sel) ++jc[cb];
-            lo[cb] = sel ? rs : 0;
-            hi[cb] = sel ? re : 0;
-            lse2[cb] = sel ? lse_own[cb] : INFINITY;
-            act[cb] = __any(sel);
-          }
-        },
-        [&](const bf16_t *stg, int kb, int) {
-          bool any = false;
-#pragma unroll
-          for (int cb = 0; cb < CB; ++cb) any = any || act[cb];
-          if (!any) return;
-          bf16_t *st = (bf16_t *)stg;
-          if (kb >= rs && kb + 32 <= re)
-            dq_tile<D, CB, false>(acc, q, dop, L::row_tile(st, 0), L::row_tile(st, 1), kb, lo, hi, act, sl2,
-                                  scale, lse2, delta, gw);
-          else
-            dq_tile<D, CB, true>(acc, q, dop, L::row_tile(st, 0), L::row_tile(st, 1), kb, lo, hi, act, sl2,
-                                 scale, lse2, delta, gw);
-        });
-  }
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) {
     if (!q.valid[cb]) continue;
-    if (PART == 0) {
 #pragma unroll
-      for (int dt = 0; dt < D / 16; ++dt) *reinterpret_cast<f32x4 *>(a.dQp + rs_[cb] * D + 16 * dt + 4 * quad) = acc[cb][dt];
-      continue;
+    for (int dt = 0; dt < D / 16; ++dt) *reinterpret_cast<f32x4 *>(a.dQp + rs_[cb] * D + 16 * dt + 4 * quad) = acc[cb][dt];
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// dQ of the selection branch, block-centric: the same exchange of loops as the forward kernel m_slc_fwd_bc.  A workgroup
+// holds one selection block's K and V rows in LDS and runs through a chunk of the tokens that selected it; every
+// wavefront takes 16/h_s tokens per step on its own (query and dO rows in registers, no barrier, no column that did
+// not select the block).  One bf16 partial dQ per (token, KV head, selected block) goes to memory; m_dq_merge adds them
+// in rank order onto the fp32 compression + window part.
+// ---------------------------------------------------------------------------------------------------------
+struct BcDqArgs {
+  MfmaView v;
+  const bf16_t *Qs, *dOs;             // [N(pos)][Hq][D] sorted copies
+  const float *lse2s, *deltas, *gws;  // selection branch: [N(pos)][Hq]
+  const int32_t *idx;                 // [N,Hkv,T]
+  const int32_t *sel_start, *sel_list, *chunk_start;
+  bf16_t *pdq;                        // [N(pos)][Hkv][T][hs][D]
+};
+
+template <int D>
+struct BcDqRows {
+  bf16x8 qop[D / 32], dop[D / 32];
+  float lse2, gws, dls;  // lse in log2 units; gate and delta with the softmax scale folded in
+  uint32_t prow;         // ((pos*Hkv + g)*T + rank)*hs + head
+  bool valid;
+};
+
+template <int D>
+__device__ inline void bc_dq_load_rows(const BcDqArgs &a, const int *tl, const int *sl, int step, int cnt, int g, BcDqRows<D> &r) {
+  const int n = threadIdx.x & 15, quad = threadIdx.x >> 4 & 3;
+  const int hs = a.v.hs, hl = n % hs;
+  const int e = step * (16 / hs) + n / hs;
+  r.valid = e < cnt;
+  const int pos = r.valid ? tl[e] : 0, rank = r.valid ? sl[e] : 0;
+  const size_t th = (size_t)pos * a.v.Hq + g * hs + hl;
+#pragma unroll
+  for (int ks = 0; ks < D / 32; ++ks) {
+    r.qop[ks] = r.valid ? ld8(a.Qs + th * D + 8 * quad + 32 * ks) : zero8();
+    r.dop[ks] = r.valid ? ld8(a.dOs + th * D + 8 * quad + 32 * ks) : zero8();
+  }
+  r.lse2 = r.valid ? a.lse2s[th] : INFINITY;  // a missing column gets P = exp2(-inf) = 0
+  r.gws = a.gws[th] * a.v.scale;
+  r.dls = a.deltas[th] * a.v.scale;
+  r.prow = (uint32_t)((((size_t)pos * a.v.Hkv + g) * a.v.T + rank) * hs + hl);
+}
+
+// One 32-key LDS tile: transposed scores (K rows) and dP (V rows), dS^T = P (gate dP - delta) scale, then
+// dQ^T += K^T dS^T with K^T read from the same K tile through the transposing LDS load.
+template <int D, bool MASK>
+__device__ inline void bc_dq_tile(f32x4 (&acc)[D / 16], const BcDqRows<D> &r, lds_cptr kr, lds_cptr vr, lds_cptr ktr, int key0,
+                                  int nk, float sl2) {
+  f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0, p0 = s0, p1 = s0;
+#pragma unroll
+  for (int ks = 0; ks < D / 32; ++ks) {
+    s0 = mfma16(p_row_operand<D>(kr, 0, ks), r.qop[ks], s0);
+    s1 = mfma16(p_row_operand<D>(kr, 1, ks), r.qop[ks], s1);
+    p0 = mfma16(p_row_operand<D>(vr, 0, ks), r.dop[ks], p0);
+    p1 = mfma16(p_row_operand<D>(vr, 1, ks), r.dop[ks], p1);
+  }
+  bf16x8 ds;
+  const int first = key0 + 8 * (int)(threadIdx.x >> 4 & 3);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const float sv = j < 4 ? s0[j & 3] : s1[j & 3], dp = j < 4 ? p0[j & 3] : p1[j & 3];
+    float p = fast_exp2(__builtin_fmaf(sv, sl2, -r.lse2));
+    if (MASK && first + j >= nk) p = 0.f;
+    ds[j] = (__bf16)(p * __builtin_fmaf(r.gws, dp, -r.dls));
+  }
+#pragma unroll
+  for (int dt = 0; dt < D / 16; ++dt) acc[dt] = mfma16(p_tr_operand<D>(ktr, dt), ds, acc[dt]);
+}
+
+template <int D, int KSEG>
+constexpr size_t bc_dq_lds_bytes() { return (size_t)2 * (KSEG / 32) * PTile<D>::BYTES + (size_t)2 * BC_CHUNK * sizeof(int); }
+
+template <int D, int NW, int KSEG>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4 : 2))) void m_bwd_dq_bc(BcDqArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  using P = PTile<D>;
+  constexpr int MAXT = KSEG / 32;
+  unsigned char *Kt = smem, *Vt = Kt + MAXT * P::BYTES;
+  int *tl = (int *)(Vt + MAXT * P::BYTES), *sl = tl + BC_CHUNK;
+  const int wid = threadIdx.x >> 6, quad = threadIdx.x >> 4 & 3;
+  const int hs = a.v.hs, Hkv = a.v.Hkv, T = a.v.T, Ns = a.v.Ns;
+  const int w = bc_chunk_of_workgroup(a.chunk_start[Hkv * Ns]);
+  int key, chunk;
+  if (w < 0 || !bc_find_chunk(a.chunk_start, Hkv * Ns, w, key, chunk)) return;
+  const int g = key / Ns, blk = key % Ns;
+  const int kbeg = a.v.slc_start[blk], kend = a.v.slc_start[blk + 1];
+  const int qbeg = a.sel_start[key] + chunk * BC_CHUNK, cnt = min(a.sel_start[key + 1] - qbeg, BC_CHUNK);
+  // the chunk's tokens (sorted positions) and the rank of this block in each token's row of I
+  for (int i = threadIdx.x; i < cnt; i += 64 * NW) {
+    const int pos = a.sel_list[qbeg + i];
+    const int32_t *row = a.idx + ((size_t)a.v.perm[pos] * Hkv + g) * T;
+    int j = 0;
+    while (j < T - 1 && row[j] != blk) ++j;
+    tl[i] = pos;
+    sl[i] = j;
+  }
+  const int tpw = 16 / hs;
+  const int n_it = (cnt + tpw - 1) / tpw;
+  const uint32_t kstride = (uint32_t)(Hkv * D);
+  const float sl2 = a.v.sl2;
+  const lds_cptr kr = (lds_cptr)Kt + P::row_lane(), vr = (lds_cptr)Vt + P::row_lane(), ktr = (lds_cptr)Kt + P::tr_lane();
+  __syncthreads();
+  BcDqRows<D> cur;
+  if (wid < n_it) bc_dq_load_rows<D>(a, tl, sl, wid, cnt, g, cur);
+  for (int k0 = kbeg; k0 < kend; k0 += KSEG) {
+    const int nk = min(KSEG, kend - k0), nfull = nk >> 5;
+    if (k0 > kbeg) {
+      __syncthreads();
+      if (wid < n_it) bc_dq_load_rows<D>(a, tl, sl, wid, cnt, g, cur);
     }
-    bf16_t *o = a.dQ + ((size_t)q.tok[cb] * a.v.Hq + q.h[cb]) * D + 4 * quad;
+    p_stage2<D, 64 * NW>(a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D, kstride, k0, (nk + 31) >> 5, Kt, Vt);
+    __syncthreads();
+    for (int it = wid; it < n_it; it += NW) {
+      BcDqRows<D> nxt;
+      if (it + NW < n_it) bc_dq_load_rows<D>(a, tl, sl, it + NW, cnt, g, nxt);
+      f32x4 acc[D / 16];
 #pragma unroll
-    for (int dt = 0; dt < D / 16; ++dt) {
-      bf16x4 w;
+      for (int dt = 0; dt < D / 16; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (k0 > kbeg && cur.valid) {  // continue from the partial of the earlier segments
 #pragma unroll
-      for (int i = 0; i < 4; ++i) w[i] = (__bf16)acc[cb][dt][i];
-      *reinterpret_cast<bf16x4 *>(o + 16 * dt) = w;
+        for (int dt = 0; dt < D / 16; ++dt) {
+          const bf16x4 x = *reinterpret_cast<const bf16x4 *>(a.pdq + (size_t)cur.prow * D + 16 * dt + 4 * quad);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) acc[dt][i] = (float)x[i];
+        }
+      }
+#pragma unroll
+      for (int t = 0; t < MAXT; ++t)
+        if (t < nfull) bc_dq_tile<D, false>(acc, cur, kr + t * P::BYTES, vr + t * P::BYTES, ktr + t * P::BYTES, 32 * t, nk, sl2);
+      if (nk & 31)
+        bc_dq_tile<D, true>(acc, cur, kr + nfull * P::BYTES, vr + nfull * P::BYTES, ktr + nfull * P::BYTES, 32 * nfull, nk, sl2);
+      if (cur.valid) {
+#pragma unroll
+        for (int dt = 0; dt < D / 16; ++dt) {
+          bf16x4 x;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) x[i] = (__bf16)acc[dt][i];
+          *reinterpret_cast<bf16x4 *>(a.pdq + (size_t)cur.prow * D + 16 * dt + 4 * quad) = x;
+        }
+      }
+      cur = nxt;
     }
   }
+}
+
+// dQ[tok] = (compression + window part, fp32, by sorted position) + sum over the token's selected blocks, in rank
+// order, of the partial dQ.  One thread per (sorted position, query head, 8 dims).
+struct DqMergeArgs {
+  const bf16_t *pdq;
+  const float *dQp;
+  const int32_t *idx, *perm;
+  bf16_t *dQ;
+  int N, Hq, Hkv, hs, T, D;
+};
+
+__global__ __launch_bounds__(256) void m_dq_merge(DqMergeArgs a) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int per_row = a.D / 8;
+  if (i >= (size_t)a.N * a.Hq * per_row) return;
+  const int c8 = (int)(i % per_row), h = (int)(i / per_row % a.Hq), pos = (int)(i / ((size_t)per_row * a.Hq));
+  const int g = h / a.hs, hl = h % a.hs, tok = a.perm[pos];
+  const int32_t *row = a.idx + ((size_t)tok * a.Hkv + g) * a.T;
+  int nv = 0;  // rows are ascending with the -1 padding at the end
+  for (int j = 0; j < a.T; ++j) nv += row[j] >= 0 ? 1 : 0;
+  const float *base = a.dQp + ((size_t)pos * a.Hq + h) * a.D + 8 * c8;
+  const float4 b0 = *reinterpret_cast<const float4 *>(base), b1 = *reinterpret_cast<const float4 *>(base + 4);
+  float acc[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+  const size_t slot0 = ((size_t)pos * a.Hkv + g) * a.T;
+#pragma unroll 4
+  for (int j = 0; j < nv; ++j) {
+    const bf16x8 x = ld8(a.pdq + ((slot0 + j) * a.hs + hl) * a.D + 8 * c8);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] += (float)x[e];
+  }
+  bf16x8 o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = (__bf16)acc[e];
+  *reinterpret_cast<bf16x8 *>(a.dQ + ((size_t)tok * a.Hq + h) * a.D + 8 * c8) = o;
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -558,130 +664,6 @@ __global__ void m_slc_reduce(const int32_t *__restrict__ tok_slc, const int32_t 
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// Inverse of the selection: for every (KV head, selection block) the ascending list of query positions that
-// selected it.  Built from a bit matrix (integer OR: order independent), then compacted in order.
-// ---------------------------------------------------------------------------------------------------------
-__global__ void m_fill_u32(uint32_t *p, size_t n, uint32_t v) {
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
-}
-
-__global__ void m_sel_bits(const int32_t *__restrict__ idx, const int32_t *__restrict__ perm, int N, int Hkv, int T, int Ns,
-                           int words, uint32_t *bits) {
-  const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= (size_t)N * Hkv * T) return;
-  const int pos = (int)(e / ((size_t)Hkv * T)), g = (int)(e / T % Hkv), j = (int)(e % T);
-  const int b = idx[((size_t)perm[pos] * Hkv + g) * T + j];
-  if (b < 0 || b >= Ns) return;
-  atomicOr(&bits[((size_t)g * Ns + b) * words + (pos >> 5)], 1u << (pos & 31));
-}
-
-// The same bit matrix built tile by tile in LDS: workgroup (chunk, g) owns `cw` words = 32*cw sorted positions of all
-// Ns blocks of KV head g, sets the bits with LDS atomics and writes every word of its tile (so the matrix needs no
-// clearing beforehand).  Needs Ns * cw * 4 bytes of LDS.
-__global__ __launch_bounds__(256) void m_sel_bits_tile(const int32_t *__restrict__ idx, const int32_t *__restrict__ perm, int N,
-                                                       int Hkv, int T, int Ns, int words, int cw, uint32_t *__restrict__ bits) {
-  extern __shared__ __align__(16) unsigned char sel_smem[];
-  uint32_t *tile = (uint32_t *)sel_smem;  // [Ns][cw]
-  const int g = blockIdx.y, w0 = blockIdx.x * cw, p0 = w0 * 32;
-  for (int i = threadIdx.x; i < Ns * cw; i += 256) tile[i] = 0u;
-  __syncthreads();
-  const int npos = min(32 * cw, N - p0);
-  for (int e = threadIdx.x; e < npos * T; e += 256) {
-    const int pl = e / T, j = e % T;
-    const int b = idx[((size_t)perm[p0 + pl] * Hkv + g) * T + j];
-    if (b >= 0 && b < Ns) atomicOr(&tile[b * cw + (pl >> 5)], 1u << (pl & 31));
-  }
-  __syncthreads();
-  const int wn = min(cw, words - w0);
-  for (int i = threadIdx.x; i < Ns * cw; i += 256) {
-    const int b = i / cw, w = i % cw;
-    if (w < wn) bits[((size_t)g * Ns + b) * words + w0 + w] = tile[i];
-  }
-}
-
-__global__ __launch_bounds__(256) void m_sel_count(const uint32_t *__restrict__ bits, int words, uint32_t *counts) {
-  __shared__ uint32_t part[4];
-  const uint32_t *row = bits + (size_t)blockIdx.x * words;
-  uint32_t c = 0;
-  for (int i = threadIdx.x; i < words; i += 256) c += __popc(row[i]);
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) c += __shfl_xor(c, off);
-  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = c;
-  __syncthreads();
-  if (threadIdx.x == 0) counts[blockIdx.x] = part[0] + part[1] + part[2] + part[3];
-}
-
-// single workgroup: from the per-(g, block) selector counts, three exclusive prefix sums over the n keys:
-// start (list offsets), chunk_start (work chunks of chunk_len query tokens), part_row_start (rows of partial sums:
-// chunks x keys of the block).
-__global__ void m_scan_counts(const uint32_t *counts, int n, int Ns, int chunk_len, const int32_t *slc_start,
-                              int32_t *start, int32_t *chunk_start, int32_t *part_row_start) {
-  __shared__ uint32_t part[3][1024];
-  const int tid = threadIdx.x;
-  const int per = (n + 1023) / 1024;
-  const int b = min(n, tid * per), e = min(n, b + per);
-  uint32_t s[3] = {0u, 0u, 0u};
-  for (int i = b; i < e; ++i) {
-    const uint32_t c = counts[i], nch = (c + chunk_len - 1) / chunk_len;
-    const int blk = i % Ns;
-    s[0] += c; s[1] += nch; s[2] += nch * (uint32_t)(slc_start[blk + 1] - slc_start[blk]);
-  }
-  for (int x = 0; x < 3; ++x) part[x][tid] = s[x];
-  __syncthreads();
-  for (int off = 1; off < 1024; off <<= 1) {
-    uint32_t v[3];
-    for (int x = 0; x < 3; ++x) v[x] = tid >= off ? part[x][tid - off] : 0u;
-    __syncthreads();
-    for (int x = 0; x < 3; ++x) part[x][tid] += v[x];
-    __syncthreads();
-  }
-  uint32_t run[3];
-  for (int x = 0; x < 3; ++x) run[x] = part[x][tid] - s[x];
-  for (int i = b; i < e; ++i) {
-    const uint32_t c = counts[i], nch = (c + chunk_len - 1) / chunk_len;
-    const int blk = i % Ns;
-    start[i] = (int32_t)run[0]; chunk_start[i] = (int32_t)run[1]; part_row_start[i] = (int32_t)run[2];
-    run[0] += c; run[1] += nch; run[2] += nch * (uint32_t)(slc_start[blk + 1] - slc_start[blk]);
-  }
-  if (tid == 1023) {
-    start[n] = (int32_t)part[0][1023]; chunk_start[n] = (int32_t)part[1][1023]; part_row_start[n] = (int32_t)part[2][1023];
-  }
-}
-
-__global__ __launch_bounds__(256) void m_sel_fill(const uint32_t *__restrict__ bits, int words,
-                                                  const int32_t *__restrict__ start, int32_t *list) {
-  __shared__ uint32_t wsum[4];
-  __shared__ uint32_t base;
-  const uint32_t *row = bits + (size_t)blockIdx.x * words;
-  if (threadIdx.x == 0) base = (uint32_t)start[blockIdx.x];
-  __syncthreads();
-  const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
-  for (int i0 = 0; i0 < words; i0 += 256) {
-    const int i = i0 + threadIdx.x;
-    uint32_t w = i < words ? row[i] : 0u;
-    const uint32_t c = __popc(w);
-    uint32_t incl = c;  // inclusive scan inside the wavefront
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const uint32_t o = __shfl_up(incl, off);
-      if (lane >= off) incl += o;
-    }
-    if (lane == 63) wsum[wid] = incl;
-    __syncthreads();
-    uint32_t off = base + incl - c;
-    for (int ww = 0; ww < wid; ++ww) off += wsum[ww];
-    while (w) {
-      const int bit = __ffs(w) - 1;
-      list[off++] = i * 32 + bit;
-      w &= w - 1;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) base += wsum[0] + wsum[1] + wsum[2] + wsum[3];
-    __syncthreads();
-  }
-}
-
-// ---------------------------------------------------------------------------------------------------------
 // Finish: dK[tok] = dKs[pos] + (sum over query splits of dKc[c]) / count(c)  (gradient of the mean pool),
 // scattered back to caller order.  One workgroup per compression block.  With dKc_out/dVc_out given (the pooled
 // rows were the caller's), the summed block gradients go there instead and dK, dV keep the token-level part only.
@@ -714,7 +696,9 @@ __global__ void m_bwd_finish(const int32_t *__restrict__ perm, const int32_t *__
   }
 }
 
-constexpr int DQ_SLC_WAVES = 4;  // wavefronts per workgroup of the selection dQ kernel (8 tokens at h_s = 8)
+// Shape of the block-centric selection dQ kernel per head dimension: wavefronts per workgroup, keys held in LDS at a time.
+template <int D> struct BcDqShape { static constexpr int NW = 8, KSEG = 256; };
+template <> struct BcDqShape<128> { static constexpr int NW = 8, KSEG = 256; };
 constexpr int KB_KEYS_MAX = 2;  // key blocks of 16 per wavefront in the dK/dV kernels (1 at head_dim 128: registers)
 // wavefronts per workgroup there (16*KB_KEYS keys each): blocks and windows hold ~130 tokens, an item's pooled keys
 // thousands, so the compression branch takes wider workgroups (fewer passes over the query rows)
@@ -732,68 +716,57 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
               N, Hq, Hkv, v.hs, D, (bf16_t *)dgates, w.lse2s, w.deltas, w.gws, w.Qs, w.dOs};
     m_bwd_pre<<<N, 256, (size_t)Hq * D * sizeof(bf16_t), s>>>(a);
   }
+  using BS = BcDqShape<D>;
+  static std::once_flag dq_once;  // raise the dynamic LDS limit once per process for these instantiations
+  std::call_once(dq_once, [] {
+    (void)hipFuncSetAttribute((const void *)m_bwd_dq<D, 1, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    (void)hipFuncSetAttribute((const void *)m_bwd_dq_bc<D, BS::NW, BS::KSEG>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              160 * 1024);
+  });
   {
-    DqArgs a{v, (const bf16_t *)q, (const bf16_t *)dout, idx, w.lse2s, w.deltas, w.gws, (bf16_t *)dq, w.dQp, nullptr, blk->inv_perm};
-    constexpr int CB = 1, NW0 = 4, NW1 = DQ_SLC_WAVES;
-    const int tw0 = NW0 * CB * 16 / v.hs, tw1 = NW1 * CB * 16 / v.hs;
-    static bool attr_done = false;
-    if (!attr_done) {
-      (void)hipFuncSetAttribute((const void *)m_bwd_dq<D, CB, 0, NW0>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-      (void)hipFuncSetAttribute((const void *)m_bwd_dq<D, CB, 1, NW1>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-      attr_done = true;
-    }
-    {
-      ProfScope ps0(PROF_BWD_DQ_CMP, s);
-      m_bwd_dq<D, CB, 0, NW0><<<dim3(xcd_grid_size((N + tw0 - 1) / tw0, Hkv)), 64 * NW0, dq_lds_bytes<D>(tw0, v.T, v.Ns), s>>>(a);
-    }
-    {
-      const int rc = slc_order_build(idx, v.perm, N, Hkv, v.T, v.Ns, w.order_ws, s, &a.slc_order);
-      if (rc != SSA_OK) return rc;
-    }
-    {
-      ProfScope ps1(PROF_BWD_DQ, s);
-      m_bwd_dq<D, CB, 1, NW1><<<dim3(xcd_grid_size((N + tw1 - 1) / tw1, Hkv)), 64 * NW1, dq_lds_bytes<D>(tw1, v.T, v.Ns), s>>>(a);
-    }
+    ProfScope ps0(PROF_BWD_DQ_CMP, s);
+    DqArgs a{v, (const bf16_t *)q, (const bf16_t *)dout, w.lse2s, w.deltas, w.gws, w.dQp};
+    constexpr int CB = 1, NW0 = 4;
+    const int tw0 = NW0 * CB * 16 / v.hs;
+    m_bwd_dq<D, CB, NW0><<<dim3(xcd_grid_size((N + tw0 - 1) / tw0, Hkv)), 64 * NW0, dq_lds_bytes<D>(), s>>>(a);
+  }
+  {
+    ProfScope ps(PROF_BWD_INVERT, s);
+    const int rc = sel_index_build(idx, v.perm, v.slc_start, N, Hkv, v.T, v.Ns, w.sel, s);
+    if (rc != SSA_OK) return rc;
+  }
+  {
+    ProfScope ps1(PROF_BWD_DQ, s);
+    const size_t entries = (size_t)N * Hkv * v.T;
+    const unsigned chunks = (unsigned)(entries / BC_CHUNK + (size_t)Hkv * v.Ns);
+    BcDqArgs b{v, w.Qs, w.dOs, w.lse2s + NH, w.deltas + NH, w.gws + NH, idx, w.sel.start, w.sel.list, w.sel.bc_chunk_start,
+               w.part.o};
+    m_bwd_dq_bc<D, BS::NW, BS::KSEG><<<dim3((chunks + 7) / 8 * 8), 64 * BS::NW, bc_dq_lds_bytes<D, BS::KSEG>(), s>>>(b);
+  }
+  {
+    ProfScope ps2(PROF_BWD_DQ_MERGE, s);
+    DqMergeArgs m{w.part.o, w.dQp, idx, v.perm, (bf16_t *)dq, N, Hq, Hkv, v.hs, v.T, D};
+    const size_t threads = (size_t)N * Hq * (D / 8);
+    m_dq_merge<<<(unsigned)((threads + 255) / 256), 256, 0, s>>>(m);
   }
   constexpr int KB_KEYS = D >= 128 ? 1 : KB_KEYS_MAX;
   constexpr int WG_KEYS = 16 * KB_KEYS * DKV_WAVES, WG_KEYS_CMP = 16 * KB_KEYS * DKV_WAVES_CMP;
   static_assert(WG_KEYS <= SSA_KEY_PAD && WG_KEYS_CMP <= SSA_KEY_PAD, "key tiles may read up to WG_KEYS rows past a block");
   const size_t dkv_lds = (size_t)2 * DkvStage<D>::BYTES;
-  static bool dkv_attr = false;
-  if (!dkv_attr) {
+  static std::once_flag dkv_once;
+  std::call_once(dkv_once, [] {
     (void)hipFuncSetAttribute((const void *)m_bwd_dkv<D, KB_KEYS, DKV_WIN, DKV_WAVES>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     (void)hipFuncSetAttribute((const void *)m_bwd_dkv<D, KB_KEYS, DKV_SLC, DKV_WAVES>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     (void)hipFuncSetAttribute((const void *)m_bwd_dkv<D, KB_KEYS, DKV_CMP, DKV_WAVES_CMP>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    dkv_attr = true;
-  }
-  DkvArgs base{v, w.Qs, w.dOs, nullptr, nullptr, nullptr, w.sel_start, w.sel_list,
-               w.dKs, w.dVs, w.chunk_start, w.part_row_start, w.chunk_len, 1, 1};
+  });
+  DkvArgs base{v, w.Qs, w.dOs, nullptr, nullptr, nullptr, w.sel.start, w.sel.list,
+               w.dKs, w.dVs, w.sel.chunk_start, w.sel.part_row_start, w.sel.chunk_len, 1, 1};
   {
     ProfScope ps(PROF_BWD_DKV_WIN, s);
     DkvArgs a = base;
     a.lse2s = w.lse2s + 2 * NH; a.deltas = w.deltas + 2 * NH; a.gws = w.gws + 2 * NH;
     a.tiles_per_block = (blk->win_tok_max + WG_KEYS - 1) / WG_KEYS;
     m_bwd_dkv<D, KB_KEYS, DKV_WIN, DKV_WAVES><<<dim3(blk->Nw * a.tiles_per_block, Hkv), 64 * DKV_WAVES, dkv_lds, s>>>(a);
-  }
-  {
-    ProfScope ps(PROF_BWD_INVERT, s);
-    const int words = (N + 31) / 32, keys = Hkv * v.Ns;
-    // bit matrix: tiles of up to 32 words per block row held in LDS (64 KB), or global atomics when a KV head has more
-    // than 16 384 blocks
-    int cw = v.Ns > 0 ? 16384 / v.Ns : 0;
-    if (cw > 32) cw = 32;
-    if (cw >= 1) {
-      m_sel_bits_tile<<<dim3((words + cw - 1) / cw, Hkv), 256, (size_t)v.Ns * cw * 4, s>>>(idx, v.perm, N, Hkv, v.T, v.Ns, words,
-                                                                                            cw, w.sel_bits);
-    } else {
-      m_fill_u32<<<1024, 256, 0, s>>>(w.sel_bits, (size_t)keys * words, 0u);
-      const size_t entries = (size_t)N * Hkv * v.T;
-      m_sel_bits<<<(unsigned)((entries + 255) / 256), 256, 0, s>>>(idx, v.perm, N, Hkv, v.T, v.Ns, words, w.sel_bits);
-    }
-    m_sel_count<<<keys, 256, 0, s>>>(w.sel_bits, words, w.sel_counts);
-    m_scan_counts<<<1, 1024, 0, s>>>(w.sel_counts, keys, v.Ns, w.chunk_len, v.slc_start, w.sel_start, w.chunk_start,
-                                     w.part_row_start);
-    m_sel_fill<<<keys, 256, 0, s>>>(w.sel_bits, words, w.sel_start, w.sel_list);
   }
   {
     ProfScope ps(PROF_BWD_DKV_SLC, s);
@@ -803,7 +776,7 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
     a.tiles_per_block = (blk->slc_tok_max + WG_KEYS - 1) / WG_KEYS;
     m_bwd_dkv<D, KB_KEYS, DKV_SLC, DKV_WAVES><<<dim3((w.max_chunks + 7) / 8 * 8 * a.tiles_per_block), 64 * DKV_WAVES, dkv_lds, s>>>(a);
     const size_t items = (size_t)N * Hkv * (D / 4);
-    m_slc_reduce<<<(unsigned)((items + 255) / 256), 256, 0, s>>>(blk->tok_slc, v.slc_start, w.chunk_start, w.part_row_start, N,
+    m_slc_reduce<<<(unsigned)((items + 255) / 256), 256, 0, s>>>(blk->tok_slc, v.slc_start, w.sel.chunk_start, w.sel.part_row_start, N,
                                                                  Hkv, v.Ns, D, w.pK, w.pV, w.dKs, w.dVs);
   }
   {

@@ -11,7 +11,10 @@
 #include "topk_device.h"
 #include "mfma_launch.h"
 #include "mfma_qc.h"
+#include "mfma_bc.h"
 #include "profile.h"
+
+#include <mutex>
 
 namespace {
 
@@ -21,7 +24,6 @@ struct FwdArgs {
   bf16_t *Ob;    // [3,N,Hq,D]
   float *lse;    // [3,N,Hq]
   int32_t *idx;  // [N,Hkv,T]
-  const int32_t *slc_order;  // [Hkv,N] token order of the selection kernel, or NULL: the sorted order
 };
 
 template <int D, int CB>
@@ -318,74 +320,223 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
   }
 }
 
-// LDS plan of the selection kernel (bytes): two stages | 8 ints | I rows [TW][T] | union bits | range lists 3 x [TW*T]
+// ---------------------------------------------------------------------------------------------------------
+// Selection branch, block-centric (Algorithm 1 with the loops exchanged): the outer loop runs over the selected blocks,
+// the inner one over the query tokens that selected the block.  A workgroup takes one (KV head, selection block) and a
+// chunk of up to BC_CHUNK tokens of that block's selector list, puts the block's K and V rows into LDS ONCE (up to KSEG
+// keys; longer blocks in several segments) and lets every wavefront run, on its own and without any barrier, through
+// groups of CB*16/h_s tokens: all CB*16 query columns of a matrix tile then take part in every key tile (nothing is
+// computed for a token that did not select the block), the K and V^T operands read from LDS feed CB column blocks,
+// and no wavefront waits for another.  The price is one partial result per (token, KV head, selected block): the
+// unnormalised output in bf16 with its running maximum and sum (Algorithm 1's o, m, l for that block alone), merged per
+// token afterwards (m_slc_merge).  A wavefront that meets a block longer than KSEG picks its own partial up again for
+// the next segment.
+// ---------------------------------------------------------------------------------------------------------
+struct BcFwdArgs {
+  MfmaView v;
+  const bf16_t *Q;
+  const int32_t *idx;  // [N,Hkv,T]
+  const int32_t *sel_start, *sel_list, *chunk_start;
+  bf16_t *po;  // [N][Hkv][T][hs][D]
+  float *pml;  // [N][Hkv][T][hs][2]
+};
+
+// LDS plan (bytes): K tiles | V tiles (KSEG/32 tiles each, PTile layout) | token ids [BC_CHUNK] | ranks [BC_CHUNK]
+template <int D, int KSEG>
+constexpr size_t bc_lds_bytes() { return (size_t)2 * (KSEG / 32) * PTile<D>::BYTES + (size_t)2 * BC_CHUNK * sizeof(int); }
+
+// Query operands and partial-row index of one wavefront step: column n stands for chunk entry step*(16/h_s) + n/h_s,
+// head n % h_s of the KV group.
 template <int D>
-__host__ __device__ inline size_t slc_lds_bytes(int tw, int T, int Ns) {
-  return (size_t)2 * StageLayout<D, 2>::ELEMS * sizeof(bf16_t) + 32 + ((size_t)tw * T * 4 + (size_t)(Ns + 31) / 32 + 4) * 4;
+struct BcRows {
+  bf16x8 qop[D / 32];
+  uint32_t prow;  // ((tok*Hkv + g)*T + rank)*hs + head: row of the partial arrays (below 2^32: N*Hq*T is)
+  bool valid;
+};
+
+template <int D>
+__device__ inline void bc_load_rows(const BcFwdArgs &a, const int *tl, const int *sl, int step, int cnt, int g, BcRows<D> &r) {
+  const int n = threadIdx.x & 15, quad = threadIdx.x >> 4 & 3;
+  const int hs = a.v.hs, hl = n % hs;
+  const int e = step * (16 / hs) + n / hs;
+  r.valid = e < cnt;
+  const int tok = r.valid ? tl[e] : 0, rank = r.valid ? sl[e] : 0;
+  const bf16_t *src = a.Q + ((size_t)tok * a.v.Hq + g * hs + hl) * D + 8 * quad;
+#pragma unroll
+  for (int ks = 0; ks < D / 32; ++ks) r.qop[ks] = r.valid ? ld8(src + 32 * ks) : zero8();
+  r.prow = (uint32_t)((((size_t)tok * a.v.Hkv + g) * a.v.T + rank) * hs + hl);
 }
 
-// Selection branch: Algorithm 1.  The workgroup walks the union of the blocks its tokens selected, in ascending
-// id; a token that did not select the current block sees it fully masked, a wavefront none of whose tokens
-// selected it skips the arithmetic.
-template <int D, int CB, int NW>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4 : 2))) void m_slc_fwd(FwdArgs a) {
+// One online-softmax step (Algorithm 1, inner loop body) of 16 query columns over one 32-key LDS tile.  kl, vl: the
+// lane's operand addresses inside the tile (see PTile).  MASK: keys from index nk on (counted from the segment start;
+// this tile starts at key0) do not exist.  Lazy reference maximum as in fwd_tile.
+template <int D, bool MASK>
+__device__ inline void bc_fwd_tile(FwdState<D, 1> &st, const bf16x8 (&qop)[D / 32], lds_cptr kl, lds_cptr vl, int key0,
+                                   int nk, float sl2, float slack, const bf16x8 &ones) {
+  f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int ks = 0; ks < D / 32; ++ks) {
+    s0 = mfma16(p_row_operand<D>(kl, 0, ks), qop[ks], s0);
+    s1 = mfma16(p_row_operand<D>(kl, 1, ks), qop[ks], s1);
+  }
+  float v[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
+  if (MASK) {
+    const int first = key0 + 8 * (int)(threadIdx.x >> 4 & 3);
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (first + j >= nk) v[j] = -INFINITY;
+  }
+  const float pm = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
+  if (__any(pm > st.m[0] + slack)) {
+    float tmax = fmaxf(pm, __shfl_xor(pm, 16));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+    const float mn = fmaxf(st.m[0], tmax);
+    const float alpha = mn == -INFINITY ? 1.0f : fast_exp2((st.m[0] - mn) * sl2);
+    st.l[0][0] *= alpha;
+    st.m[0] = mn;
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) st.o[0][dt] *= alpha;
+  }
+  const float neg = st.m[0] != -INFINITY ? -st.m[0] * sl2 : -INFINITY;
+  bf16x8 pb;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) pb[j] = (__bf16)fast_exp2(__builtin_fmaf(v[j], sl2, neg));
+  st.l[0] = mfma16(ones, pb, st.l[0]);
+#pragma unroll
+  for (int dt = 0; dt < D / 16; ++dt) st.o[0][dt] = mfma16(p_tr_operand<D>(vl, dt), pb, st.o[0][dt]);
+}
+
+template <int D, int NW, int KSEG>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4 : 2))) void m_slc_fwd_bc(BcFwdArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
-  using L = StageLayout<D, 2>;
-  bf16_t *stage0 = (bf16_t *)smem;
-  int *ints = (int *)(stage0 + 2 * L::ELEMS);
-  const int hs = a.v.hs, T = a.v.T, TW = NW * CB * 16 / hs;
-  const TileMap tm = xcd_tile_map((a.v.N + TW - 1) / TW, a.v.Hkv);
-  if (!tm.valid) return;
-  const int g = tm.g, wg_pos0 = tm.tile * TW;
-  int *Irows = ints + 8;                 // [TW][T]
-  int *ub = Irows + TW * T;              // union list: block ids
-  int *us = ub + TW * T, *ue = us + TW * T;
-  uint32_t *bits = (uint32_t *)(ue + TW * T);
-  QRows<D, CB> q;
-  MfmaView vo = a.v;  // position -> token through the selection order of this KV head
-  if (a.slc_order) vo.perm = a.slc_order + (size_t)g * a.v.N;
-  load_rows<D, CB>(a.Q, vo, wg_pos0, g, q);
-  build_union(vo, a.idx, wg_pos0, g, TW, Irows, ub, us, ue, bits, &ints[0]);
-  const int nr = lds_uniform(&ints[0]);
-  int jc[CB], lo[CB], hi[CB];
-  bool act[CB], on[CB];
-  const float slack = 8.0f / a.v.sl2;
+  using P = PTile<D>;
+  constexpr int MAXT = KSEG / 32;
+  unsigned char *Kt = smem, *Vt = Kt + MAXT * P::BYTES;
+  int *tl = (int *)(Vt + MAXT * P::BYTES), *sl = tl + BC_CHUNK;
+  const int wid = threadIdx.x >> 6, quad = threadIdx.x >> 4 & 3;
+  const int hs = a.v.hs, Hkv = a.v.Hkv, T = a.v.T, Ns = a.v.Ns;
+  const int w = bc_chunk_of_workgroup(a.chunk_start[Hkv * Ns]);
+  int key, chunk;
+  if (w < 0 || !bc_find_chunk(a.chunk_start, Hkv * Ns, w, key, chunk)) return;
+  const int g = key / Ns, blk = key % Ns;
+  const int kbeg = a.v.slc_start[blk], kend = a.v.slc_start[blk + 1];
+  const int qbeg = a.sel_start[key] + chunk * BC_CHUNK, cnt = min(a.sel_start[key + 1] - qbeg, BC_CHUNK);
+  // the chunk's tokens (caller indices) and the rank of this block in each token's row of I
+  for (int i = threadIdx.x; i < cnt; i += 64 * NW) {
+    const int tok = a.v.perm[a.sel_list[qbeg + i]];
+    const int32_t *row = a.idx + ((size_t)tok * Hkv + g) * T;
+    int j = 0;
+    while (j < T - 1 && row[j] != blk) ++j;
+    tl[i] = tok;
+    sl[i] = j;
+  }
+  const int tpw = 16 / hs;  // tokens per wavefront step
+  const int n_it = (cnt + tpw - 1) / tpw;
+  const uint32_t kstride = (uint32_t)(Hkv * D);
+  const float sl2 = a.v.sl2, slack = 8.0f / sl2;
+  bf16x8 ones;
 #pragma unroll
-  for (int cb = 0; cb < CB; ++cb) { jc[cb] = 0; lo[cb] = hi[cb] = 0; act[cb] = false; on[cb] = false; }
-  TileSrc<2> src{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, (uint32_t)(a.v.Hkv * D)};
-  FwdState<D, CB> st;
-  init_state(st);
-  const float sl2 = a.v.sl2;
-  int rs = 0, re = 0;
-  run_pipeline<D, 2, 64 * NW>(
-      src, stage0, us, ue, nr,
-      [&](int r) {
-        const int b = lds_uniform(&ub[r]);
-        rs = lds_uniform(&us[r]);
-        re = lds_uniform(&ue[r]);
+  for (int j = 0; j < 8; ++j) ones[j] = (__bf16)1.0f;
+  const lds_cptr kl = (lds_cptr)Kt + P::row_lane(), vl = (lds_cptr)Vt + P::tr_lane();
+  __syncthreads();
+  BcRows<D> cur;
+  if (wid < n_it) bc_load_rows<D>(a, tl, sl, wid, cnt, g, cur);  // in flight while the block is staged
+  for (int k0 = kbeg; k0 < kend; k0 += KSEG) {
+    const int nk = min(KSEG, kend - k0), nfull = nk >> 5;
+    if (k0 > kbeg) {
+      __syncthreads();  // every wavefront is done with the previous segment
+      if (wid < n_it) bc_load_rows<D>(a, tl, sl, wid, cnt, g, cur);
+    }
+    p_stage2<D, 64 * NW>(a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D, kstride, k0, (nk + 31) >> 5, Kt, Vt);
+    __syncthreads();
+    for (int it = wid; it < n_it; it += NW) {
+      BcRows<D> nxt;  // the next step's operands are requested before this step's arithmetic
+      if (it + NW < n_it) bc_load_rows<D>(a, tl, sl, it + NW, cnt, g, nxt);
+      FwdState<D, 1> st;
+      init_state(st);
+      if (k0 > kbeg && cur.valid) {  // pick the partial of the earlier segments up again
+        const float2 ml = *reinterpret_cast<const float2 *>(a.pml + (size_t)cur.prow * 2);
+        st.m[0] = ml.x;
+        st.l[0][0] = ml.y;
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb) {
-          const int cur = (q.valid[cb] && jc[cb] < T) ? Irows[q.slot[cb] * T + jc[cb]] : -1;
-          const bool sel = cur == b;
-          if (sel) ++jc[cb];
-          lo[cb] = sel ? rs : 0;
-          hi[cb] = sel ? re : 0;
-          on[cb] = sel;
-          act[cb] = __any(sel);
+        for (int dt = 0; dt < D / 16; ++dt) {
+          const bf16x4 x = *reinterpret_cast<const bf16x4 *>(a.po + (size_t)cur.prow * D + 16 * dt + 4 * quad);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) st.o[0][dt][i] = (float)x[i];
         }
-      },
-      [&](const bf16_t *stg, int kb, int) {
-        bool any = false;
+      }
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb) any = any || act[cb];
-        if (!any) return;
-        if (kb >= rs && kb + 32 <= re)
-          fwd_tile<D, CB, false>(st, q, L::row_tile((bf16_t *)stg, 0), L::row_tile((bf16_t *)stg, 1), kb, lo, hi, on, act, sl2, slack);
-        else
-          fwd_tile<D, CB, true>(st, q, L::row_tile((bf16_t *)stg, 0), L::row_tile((bf16_t *)stg, 1), kb, lo, hi, on, act, sl2, slack);
-      });
-  float lse2[CB];
-  finish<D, CB>(a, st, 1, q, lse2);
+      for (int t = 0; t < MAXT; ++t)
+        if (t < nfull) bc_fwd_tile<D, false>(st, cur.qop, kl + t * P::BYTES, vl + t * P::BYTES, 32 * t, nk, sl2, slack, ones);
+      if (nk & 31)
+        bc_fwd_tile<D, true>(st, cur.qop, kl + nfull * P::BYTES, vl + nfull * P::BYTES, 32 * nfull, nk, sl2, slack, ones);
+      if (cur.valid) {
+#pragma unroll
+        for (int dt = 0; dt < D / 16; ++dt) {
+          bf16x4 x;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) x[i] = (__bf16)st.o[0][dt][i];
+          *reinterpret_cast<bf16x4 *>(a.po + (size_t)cur.prow * D + 16 * dt + 4 * quad) = x;
+        }
+        if (quad == 0) *reinterpret_cast<float2 *>(a.pml + (size_t)cur.prow * 2) = make_float2(st.m[0], st.l[0][0]);
+      }
+      cur = nxt;
+    }
+  }
+}
+
+// Merge of the per-block partials of the selection branch (the online-softmax recurrence of Algorithm 1 applied across
+// blocks instead of key tiles), and the gate-weighted sum of eq. (4) in the same pass: one thread per (token, query
+// head, 8 output dims).  Writes out_branch[1], lse[1] and out.
+struct MergeArgs {
+  const bf16_t *po;
+  const float *pml;
+  const int32_t *idx;
+  const bf16_t *gates;
+  bf16_t *Ob;  // [3,N,Hq,D]: branches 0 and 2 are read, 1 is written
+  float *lse;  // [3,N,Hq]
+  bf16_t *out;
+  int N, Hq, Hkv, hs, T, D;
+  float sl2;
+};
+
+__global__ __launch_bounds__(256) void m_slc_merge(MergeArgs a) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int per_row = a.D / 8;
+  if (i >= (size_t)a.N * a.Hq * per_row) return;
+  const int c8 = (int)(i % per_row), h = (int)(i / per_row % a.Hq), tok = (int)(i / ((size_t)per_row * a.Hq));
+  const int g = h / a.hs, hl = h % a.hs;
+  const size_t slot0 = ((size_t)tok * a.Hkv + g) * a.T;
+  const int32_t *row = a.idx + slot0;
+  int nv = 0;  // rows are ascending with the -1 padding at the end
+  for (int j = 0; j < a.T; ++j) nv += row[j] >= 0 ? 1 : 0;
+  float M = -INFINITY;
+  for (int j = 0; j < nv; ++j) M = fmaxf(M, a.pml[((slot0 + j) * a.hs + hl) * 2]);
+  float L = 0.f, acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+  for (int j = 0; j < nv; ++j) {
+    const size_t r = (slot0 + j) * a.hs + hl;
+    const float2 ml = *reinterpret_cast<const float2 *>(a.pml + r * 2);
+    const bf16x8 x = ld8(a.po + r * a.D + 8 * c8);
+    const float wj = ml.x == -INFINITY ? 0.f : fast_exp2((ml.x - M) * a.sl2);
+    L += wj * ml.y;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] += wj * (float)x[e];
+  }
+  const float inv = L > 0.f ? 1.0f / L : 0.f;
+  const size_t th = (size_t)tok * a.Hq + h, NH = (size_t)a.N * a.Hq;
+  const size_t off = th * a.D + 8 * c8;
+  bf16x8 os;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) os[e] = (__bf16)(acc[e] * inv);
+  *reinterpret_cast<bf16x8 *>(a.Ob + NH * a.D + off) = os;
+  if (c8 == 0) a.lse[NH + th] = L > 0.f ? (M * a.sl2 + __log2f(L)) * LN2 : -INFINITY;
+  const float w0 = bf16_to_f32(a.gates[th * 3]), w1 = bf16_to_f32(a.gates[th * 3 + 1]), w2 = bf16_to_f32(a.gates[th * 3 + 2]);
+  const bf16x8 x0 = ld8(a.Ob + off), x2 = ld8(a.Ob + 2 * NH * a.D + off);
+  bf16x8 o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = (__bf16)(w0 * (float)x0[e] + w1 * (float)os[e] + w2 * (float)x2[e]);
+  *reinterpret_cast<bf16x8 *>(a.out + off) = o;
 }
 
 // Window branch: keys are the tokens of the query's own window.
@@ -433,57 +584,43 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
   finish<D, CB>(a, st, 2, q, lse2);
 }
 
-// eq. (4): out = sum_b gate_b * out_b, 8 elements per thread.
-__global__ void m_combine(const bf16_t *__restrict__ Ob, const bf16_t *__restrict__ gates, size_t rows /*N*Hq*/, int D,
-                          bf16_t *__restrict__ out) {
-  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // one 8-element chunk
-  const int per_row = D / 8;
-  if (i >= rows * per_row) return;
-  const size_t row = i / per_row;
-  const size_t off = row * D + (i % per_row) * 8;
-  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int b = 0; b < 3; ++b) {
-    const float w = bf16_to_f32(gates[row * 3 + b]);
-    const bf16x8 x = ld8(Ob + (size_t)b * rows * D + off);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) acc[j] += w * (float)x[j];
-  }
-  bf16x8 o;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) o[j] = (__bf16)acc[j];
-  *reinterpret_cast<bf16x8 *>(out + off) = o;
-}
-
 constexpr int FWD_CB = 1;
 constexpr int CMP_CB = 1;     // 16-column blocks per wavefront of the compression kernel
-constexpr int SLC_CB = 1;     // 16-column blocks per wavefront of the selection kernel
-constexpr int SLC_WAVES = 4;  // wavefronts per workgroup of the selection kernel
+
+// Shape of the block-centric selection kernel per head dimension: wavefronts per workgroup, keys held in LDS at a time.
+template <int D> struct BcShape { static constexpr int NW = 8, KSEG = 256; };
+template <> struct BcShape<128> { static constexpr int NW = 8, KSEG = 256; };
 
 template <int D>
-int launch_forward(FwdArgs a, const bf16_t *gates, bf16_t *out, void *order_ws, hipStream_t s) {
+int launch_forward(FwdArgs a, const bf16_t *gates, bf16_t *out, const SelIndex &sel, const SlcPartials &part, hipStream_t s) {
+  using BS = BcShape<D>;
   const int tw = 4 * FWD_CB * 16 / a.v.hs, tw_cmp = 4 * CMP_CB * 16 / a.v.hs;
   const dim3 grid(xcd_grid_size((a.v.N + tw - 1) / tw, a.v.Hkv));
-  const int tw_slc = SLC_WAVES * SLC_CB * 16 / a.v.hs;
-  const size_t lds_cmp = cmp_lds_bytes<D>(tw_cmp, a.v.s_max), lds_slc = slc_lds_bytes<D>(tw_slc, a.v.T, a.v.Ns);
+  const size_t lds_cmp = cmp_lds_bytes<D>(tw_cmp, a.v.s_max);
   const size_t lds_win = (size_t)2 * StageLayout<D, 2>::ELEMS * sizeof(bf16_t) + 32;
-  static bool attr_done = false;  // raise the dynamic LDS limit once per process for these instantiations
-  if (!attr_done) {
+  const size_t lds_bc = bc_lds_bytes<D, BS::KSEG>();
+  static std::once_flag attr_once;  // raise the dynamic LDS limit once per process for these instantiations
+  std::call_once(attr_once, [] {
     (void)hipFuncSetAttribute((const void *)m_cmp_fwd<D, CMP_CB>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    (void)hipFuncSetAttribute((const void *)m_slc_fwd<D, SLC_CB, SLC_WAVES>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    attr_done = true;
-  }
+    (void)hipFuncSetAttribute((const void *)m_slc_fwd_bc<D, BS::NW, BS::KSEG>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              160 * 1024);
+  });
   {
     ProfScope ps(PROF_CMP_FWD, s);
     m_cmp_fwd<D, CMP_CB><<<dim3(xcd_grid_size((a.v.N + tw_cmp - 1) / tw_cmp, a.v.Hkv)), 256, lds_cmp, s>>>(a);
   }
   {
-    const int rc = slc_order_build(a.idx, a.v.perm, a.v.N, a.v.Hkv, a.v.T, a.v.Ns, order_ws, s, &a.slc_order);
+    ProfScope ps(PROF_FWD_INVERT, s);
+    const int rc = sel_index_build(a.idx, a.v.perm, a.v.slc_start, a.v.N, a.v.Hkv, a.v.T, a.v.Ns, sel, s);
     if (rc != SSA_OK) return rc;
   }
   {
     ProfScope ps(PROF_SLC_FWD, s);
-    m_slc_fwd<D, SLC_CB, SLC_WAVES><<<dim3(xcd_grid_size((a.v.N + tw_slc - 1) / tw_slc, a.v.Hkv)), 64 * SLC_WAVES, lds_slc, s>>>(a);
+    // upper bound of the number of chunks: every list adds at most one partly filled chunk
+    const size_t entries = (size_t)a.v.N * a.v.Hkv * a.v.T;
+    const unsigned chunks = (unsigned)(entries / BC_CHUNK + (size_t)a.v.Hkv * a.v.Ns);
+    BcFwdArgs b{a.v, a.Q, a.idx, sel.start, sel.list, sel.bc_chunk_start, part.o, part.ml};
+    m_slc_fwd_bc<D, BS::NW, BS::KSEG><<<dim3((chunks + 7) / 8 * 8), 64 * BS::NW, lds_bc, s>>>(b);
   }
   {
     ProfScope ps(PROF_WIN_FWD, s);
@@ -491,8 +628,9 @@ int launch_forward(FwdArgs a, const bf16_t *gates, bf16_t *out, void *order_ws, 
   }
   {
     ProfScope ps(PROF_COMBINE, s);
-    const size_t chunks = (size_t)a.v.N * a.v.Hq * (D / 8);
-    m_combine<<<(unsigned)((chunks + 255) / 256), 256, 0, s>>>(a.Ob, gates, (size_t)a.v.N * a.v.Hq, D, out);
+    MergeArgs m{part.o, part.ml, a.idx, gates, a.Ob, a.lse, out, a.v.N, a.v.Hq, a.v.Hkv, a.v.hs, a.v.T, D, a.v.sl2};
+    const size_t threads = (size_t)a.v.N * a.v.Hq * (D / 8);
+    m_slc_merge<<<(unsigned)((threads + 255) / 256), 256, 0, s>>>(m);
   }
   return hipGetLastError() == hipSuccess ? SSA_OK : SSA_ERR_HIP;
 }
@@ -500,24 +638,22 @@ int launch_forward(FwdArgs a, const bf16_t *gates, bf16_t *out, void *order_ws, 
 }  // namespace
 
 // Largest dynamic LDS request of the forward kernels for this problem (bytes).
-size_t mfma_fwd_lds_bytes(int D, int hs, int s_max, int T, int Ns) {
-  const int tw = 4 * CMP_CB * 16 / hs, tws = SLC_WAVES * SLC_CB * 16 / hs;
-  size_t a = 0, b = 0;
+size_t mfma_fwd_lds_bytes(int D, int hs, int s_max) {
+  const int tw = 4 * CMP_CB * 16 / hs;
   switch (D) {
-    case 32: a = cmp_lds_bytes<32>(tw, s_max); b = slc_lds_bytes<32>(tws, T, Ns); break;
-    case 64: a = cmp_lds_bytes<64>(tw, s_max); b = slc_lds_bytes<64>(tws, T, Ns); break;
-    default: a = cmp_lds_bytes<128>(tw, s_max); b = slc_lds_bytes<128>(tws, T, Ns); break;
+    case 32: return cmp_lds_bytes<32>(tw, s_max);
+    case 64: return cmp_lds_bytes<64>(tw, s_max);
+    default: return cmp_lds_bytes<128>(tw, s_max);
   }
-  return a > b ? a : b;
 }
 
 int mfma_forward_kernels(const MfmaView &v, int D, const void *q, const void *gates, void *out, float *lse,
-                         int32_t *idx, void *out_branch, void *order_ws, hipStream_t s) {
-  FwdArgs a{v, (const bf16_t *)q, (bf16_t *)out_branch, lse, idx, nullptr};
+                         int32_t *idx, void *out_branch, const SelIndex &sel, const SlcPartials &part, hipStream_t s) {
+  FwdArgs a{v, (const bf16_t *)q, (bf16_t *)out_branch, lse, idx};
   switch (D) {
-    case 32: return launch_forward<32>(a, (const bf16_t *)gates, (bf16_t *)out, order_ws, s);
-    case 64: return launch_forward<64>(a, (const bf16_t *)gates, (bf16_t *)out, order_ws, s);
-    case 128: return launch_forward<128>(a, (const bf16_t *)gates, (bf16_t *)out, order_ws, s);
+    case 32: return launch_forward<32>(a, (const bf16_t *)gates, (bf16_t *)out, sel, part, s);
+    case 64: return launch_forward<64>(a, (const bf16_t *)gates, (bf16_t *)out, sel, part, s);
+    case 128: return launch_forward<128>(a, (const bf16_t *)gates, (bf16_t *)out, sel, part, s);
     default: return SSA_ERR_UNSUPPORTED;
   }
 }

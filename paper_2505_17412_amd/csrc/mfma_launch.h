@@ -2,17 +2,33 @@
 #pragma once
 #include "mfma_common.h"
 
-size_t mfma_fwd_lds_bytes(int D, int hs, int s_max, int T, int Ns);
+size_t mfma_fwd_lds_bytes(int D, int hs, int s_max);
+struct SelIndex;
+struct SlcPartials;
 int mfma_forward_kernels(const MfmaView &v, int D, const void *q, const void *gates, void *out, float *lse,
-                         int32_t *idx, void *out_branch, void *order_ws, hipStream_t s);
+                         int32_t *idx, void *out_branch, const SelIndex &sel, const SlcPartials &part, hipStream_t s);
 
-// Token order of the selection-branch kernels (slc_order.hip): per KV head, the tokens' caller indices ordered so that
-// tokens with similar selected sets are neighbours; *order = [Hkv][N] inside `ws`, or NULL when the problem is too
-// small to bother (the kernels then walk the sorted order).
-constexpr int SLC_ORDER_MIN_TOKENS = 4096;
-size_t slc_order_workspace(int N, int Hkv, int Ns);
-int slc_order_build(const int32_t *idx, const int32_t *perm, int N, int Hkv, int T, int Ns, void *ws, hipStream_t s,
-                    const int32_t **order);
+// Inverse of the selection (sel_index.hip): per (KV head, selection block) key = g*Ns + b, the ascending list of sorted
+// positions of the tokens that selected it, and the cuts of the lists into work chunks.
+struct SelIndex {
+  uint32_t *bits;                 // [Hkv*Ns][ceil(N/32)] bit (key, pos): token at pos selected the block
+  uint32_t *counts;               // [Hkv*Ns]
+  int32_t *start, *list;          // [Hkv*Ns+1], [N*Hkv*T]
+  int32_t *chunk_start, *part_row_start;  // [Hkv*Ns+1] each: dK/dV work chunks and partial-sum rows per key
+  int32_t *bc_chunk_start;        // [Hkv*Ns+1]: work chunks of the block-centric forward / dQ kernels
+  int chunk_len, bc_chunk_len;    // query tokens per chunk of either kind
+};
+size_t sel_index_bytes(int N, int Hkv, int T, int Ns);
+SelIndex sel_index_carve(void *ws, int N, int Hkv, int T, int Ns, int chunk_len, int bc_chunk_len);
+int sel_index_build(const int32_t *idx, const int32_t *perm, const int32_t *slc_start, int N, int Hkv, int T, int Ns,
+                    const SelIndex &x, hipStream_t s);
+
+// Block-centric selection kernels: query tokens per work chunk, and the per-(token, KV head, rank) partial results.
+constexpr int BC_CHUNK = 256;
+struct SlcPartials {
+  bf16_t *o;    // [N][Hkv][T][hs][D]: unnormalised partial output (forward) / partial dQ (backward) per selected block
+  float *ml;    // [N][Hkv][T][hs][2]: running maximum (raw score units) and sum of the partial softmax (forward only)
+};
 
 // Device buffers of the backward pass (carved from the caller's workspace).
 struct BwdBuffers {
@@ -21,15 +37,12 @@ struct BwdBuffers {
   float *dKs, *dVs;             // [N(pos)][Hkv][D] token-level gradients in sorted order
   float *dQp;                   // [N(pos)][Hq][D] compression-branch part of dQ (fp32)
   float *dKc, *dVc;             // [q_splits][Nc][Hkv][D] partial gradients of the pooled keys/values
-  uint32_t *sel_bits;           // [Hkv*Ns][ceil(N/32)] bit (key, pos): token at pos selected the block
-  uint32_t *sel_counts;         // [Hkv*Ns]
-  int32_t *sel_start, *sel_list;  // [Hkv*Ns+1], [N*Hkv*T]
-  int32_t *chunk_start, *part_row_start;  // [Hkv*Ns+1] each: work chunks and partial-sum rows per (g, block)
+  SelIndex sel;
   float *pK, *pV;               // [max_part_rows][D] per-chunk partial dK/dV of the selection branch
-  int chunk_len, max_chunks;    // query tokens per chunk; upper bound of the number of chunks
+  int max_chunks;               // upper bound of the number of dK/dV chunks
   int q_splits;
   float *dKc_out, *dVc_out;     // [Nc][Hkv][D] or NULL: where the pooled-key/value gradients go instead of being un-pooled
-  void *order_ws;               // slc_order_workspace() bytes
+  SlcPartials part;             // partial dQ of the selection branch
 };
 int mfma_backward_kernels(const MfmaView &v, int D, const BwdBuffers &w, const void *q, const void *gates,
                           const void *out_branch, const float *lse, const int32_t *idx, const void *dout, void *dq,

@@ -42,7 +42,7 @@ __global__ void m_prep(const bf16_t *__restrict__ K, const bf16_t *__restrict__ 
 
 size_t padded_rows(int n) { return align_up((size_t)n, 8) + SSA_KEY_PAD; }
 
-struct FwdPlan { size_t ks, vs, kc, vc, ob, lse, idx, order, total; };
+struct FwdPlan { size_t ks, vs, kc, vc, ob, lse, idx, sel, po, pml, total; };
 
 FwdPlan fwd_plan(const ssa_ctx &c) {
   FwdPlan p{};
@@ -54,7 +54,10 @@ FwdPlan fwd_plan(const ssa_ctx &c) {
   p.ob = take((size_t)3 * c.N * c.Hq * c.d * 2);
   p.lse = take((size_t)3 * c.N * c.Hq * 4);
   p.idx = take((size_t)c.N * c.Hkv * c.T * 4);
-  p.order = take(slc_order_workspace(c.N, c.Hkv, c.blk->Ns));
+  p.sel = take(sel_index_bytes(c.N, c.Hkv, c.T, c.blk->Ns));
+  const size_t slots = (size_t)c.N * c.Hkv * c.T * c.hs;  // one partial row per (token, query head, selected block)
+  p.po = take(slots * c.d * 2);
+  p.pml = take(slots * 2 * 4);
   p.total = off;
   return p;
 }
@@ -92,8 +95,7 @@ int override_pooled(const ssa_ctx &c, const PrepOut &o) {
 }
 
 struct BwdPlan {
-  size_t ks, vs, kc, vc, lse2s, deltas, gws, qs, dos, dqp, dks, dvs, dkc, dvc, bits, counts, start, list, cstart, prow,
-      pk, pv, order, total;
+  size_t ks, vs, kc, vc, lse2s, deltas, gws, qs, dos, dqp, dks, dvs, dkc, dvc, sel, pk, pv, pdq, total;
   int q_splits, chunk_len, max_chunks;
 };
 
@@ -117,9 +119,8 @@ BwdPlan bwd_plan(const ssa_ctx &c) {
   p.dqp = take((size_t)c.N * c.Hq * c.d * 4);
   p.dks = take((size_t)c.N * row * 4); p.dvs = take((size_t)c.N * row * 4);
   p.dkc = take((size_t)p.q_splits * b->Nc * row * 4); p.dvc = take((size_t)p.q_splits * b->Nc * row * 4);
-  const size_t keys = (size_t)c.Hkv * b->Ns, words = ((size_t)c.N + 31) / 32;
-  p.bits = take(keys * words * 4); p.counts = take(keys * 4 + 4); p.start = take((keys + 1) * 4);
-  p.list = take((size_t)c.N * c.Hkv * c.T * 4);
+  const size_t keys = (size_t)c.Hkv * b->Ns;
+  p.sel = take(sel_index_bytes(c.N, c.Hkv, c.T, b->Ns));
   // selection-branch work chunks: every (g, block) list is cut into pieces of chunk_len query tokens whose partial
   // dK/dV are summed afterwards in a fixed order.  Bounds: chunks <= entries/chunk_len + keys; partial rows <=
   // slc_tok_max * entries/chunk_len + N*Hkv.  chunk_len grows until the partial sums fit in about 1 GiB.
@@ -132,9 +133,8 @@ BwdPlan bwd_plan(const ssa_ctx &c) {
     p.chunk_len *= 2;
   }
   p.max_chunks = (int)(entries / p.chunk_len + keys + 1);
-  p.cstart = take((keys + 1) * 4); p.prow = take((keys + 1) * 4);
   p.pk = take(rows * c.d * 4); p.pv = take(rows * c.d * 4);
-  p.order = take(slc_order_workspace(c.N, c.Hkv, b->Ns));
+  p.pdq = take((size_t)c.N * c.Hkv * c.T * c.hs * c.d * 2);  // one partial dQ row per (token, query head, selected block)
   p.total = off;
   return p;
 }
@@ -151,7 +151,7 @@ bool mfma_supported(const ssa_ctx &c) {
   if (c.hs != 1 && c.hs != 2 && c.hs != 4 && c.hs != 8 && c.hs != 16) return false;
   // the kernels index their staged arrays with 32-bit element offsets
   if ((unsigned long long)(c.N + 2 * SSA_KEY_PAD) * c.Hq * c.d >= (1ull << 31)) return false;
-  if (mfma_fwd_lds_bytes(c.d, c.hs, c.blk->s_max, c.T, c.blk->Ns) > 150 * 1024) return false;
+  if (mfma_fwd_lds_bytes(c.d, c.hs, c.blk->s_max) > 150 * 1024) return false;
   return true;
 }
 
@@ -184,12 +184,10 @@ int mfma_backward(const ssa_ctx &c, const void *q, const void *k, const void *v,
   w.lse2s = (float *)(ws + p.lse2s); w.deltas = (float *)(ws + p.deltas); w.gws = (float *)(ws + p.gws);
   w.Qs = (bf16_t *)(ws + p.qs); w.dOs = (bf16_t *)(ws + p.dos); w.dQp = (float *)(ws + p.dqp);
   w.dKs = (float *)(ws + p.dks); w.dVs = (float *)(ws + p.dvs); w.dKc = (float *)(ws + p.dkc); w.dVc = (float *)(ws + p.dvc);
-  w.sel_bits = (uint32_t *)(ws + p.bits); w.sel_counts = (uint32_t *)(ws + p.counts);
-  w.sel_start = (int32_t *)(ws + p.start); w.sel_list = (int32_t *)(ws + p.list);
+  w.sel = sel_index_carve(ws + p.sel, c.N, c.Hkv, c.T, c.blk->Ns, p.chunk_len, BC_CHUNK);
   w.q_splits = p.q_splits;
-  w.chunk_start = (int32_t *)(ws + p.cstart); w.part_row_start = (int32_t *)(ws + p.prow);
-  w.pK = (float *)(ws + p.pk); w.pV = (float *)(ws + p.pv); w.chunk_len = p.chunk_len; w.max_chunks = p.max_chunks;
-  w.order_ws = ws + p.order;
+  w.pK = (float *)(ws + p.pk); w.pV = (float *)(ws + p.pv); w.max_chunks = p.max_chunks;
+  w.part = SlcPartials{(bf16_t *)(ws + p.pdq), nullptr};
   return mfma_backward_kernels(view, c.d, w, q, gates, out_branch, lse, topk_idx, dout, dq, dk, dv, dgates, c.blk, c.B,
                                c.stream);
 }
@@ -207,7 +205,9 @@ int mfma_forward(const ssa_ctx &c, const void *q, const void *k, const void *v, 
   if (rc != SSA_OK) return rc;
   MfmaView view = make_view(c);
   view.Ks = o.Ks; view.Vs = o.Vs; view.Kc = o.Kc; view.Vc = o.Vc;
+  const SelIndex sel = sel_index_carve(ws + p.sel, c.N, c.Hkv, c.T, c.blk->Ns, 1024, BC_CHUNK);
+  const SlcPartials part{(bf16_t *)(ws + p.po), (float *)(ws + p.pml)};
   return mfma_forward_kernels(view, c.d, q, gates, out, lse ? lse : (float *)(ws + p.lse),
                               topk_idx ? topk_idx : (int32_t *)(ws + p.idx), out_branch ? out_branch : (void *)(ws + p.ob),
-                              ws + p.order, c.stream);
+                              sel, part, c.stream);
 }

@@ -8,10 +8,10 @@
 
 namespace {
 const char *const kNames[PROF_COUNT] = {
-    "prep_sort_pool", "cmp_fwd_scores_topk", "slc_fwd", "win_fwd", "combine",
+    "prep_sort_pool", "cmp_fwd_scores_topk", "slc_fwd", "win_fwd", "slc_merge_combine",
     "bwd_prep", "bwd_pre_delta", "bwd_dq_cmp_win", "bwd_dq_slc", "bwd_invert_selection", "bwd_dkv_win", "bwd_dkv_slc", "bwd_dkv_cmp",
     "bwd_finish_unpool", "generic_path", "cmp_module_fwd", "cmp_module_bwd", "gate_fwd", "gate_bwd",
-    "linear_fwd", "linear_bwd", "slc_token_order"};
+    "linear_fwd", "linear_bwd", "fwd_invert_selection", "bwd_dq_merge"};
 struct Rec { int id; hipEvent_t a, b; };
 bool g_on = false;
 std::vector<Rec> g_pending;
