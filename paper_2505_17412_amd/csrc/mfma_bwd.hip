@@ -423,23 +423,25 @@ struct DkvArgs {
   int q_splits;                         // compression branch: query range split into this many parts
 };
 
-// LDS stage of the dK/dV kernels: 32 query rows as row-major tiles of Q and dO (read both as they are and through
-// the transposing LDS load), and the rows' scalars (lse in log2 units, delta, gate).
-template <int D>
+// LDS stage of the dK/dV kernels: ST tiles of 32 query rows each, of Q and of dO (PTile layout: read both as they are
+// and through the transposing LDS load), and the rows' scalars (lse in log2 units, delta, gate).
+template <int D, int ST>
 struct DkvStage {
-  using G = TileGeom<D>;
-  static constexpr int ELEMS = 2 * G::ROW_ELEMS;
-  static constexpr int BYTES = ELEMS * 2 + 3 * 32 * 4;
+  static constexpr int TILES_B = 2 * ST * PTile<D>::BYTES;  // Q tiles, then dO tiles
+  static constexpr int BYTES = TILES_B + 3 * 32 * ST * 4;   // + [3][32*ST] floats
 };
 
-// A workgroup owns 64*KB keys of one block (16*KB per wavefront, held in registers as MFMA B operands) and
-// streams the query rows that attend to them in tiles of 32 rows = 32/h_s token slots, staged through LDS once per
-// workgroup and double buffered.
-template <int D, int KB, int MODE, int NW>
+// A workgroup owns 16*KB*NW keys of one block (16*KB per wavefront, held in registers as MFMA B operands with their
+// dK and dV accumulators) and streams the query rows that attend to them in stages of ST tiles of 32 rows (32/h_s
+// token slots each), staged through LDS once per workgroup, double buffered, ONE barrier per stage: the loads of
+// stage i+1 are in flight while stage i is consumed and land in the other buffer before the barrier.
+template <int D, int KB, int MODE, int NW, int ST>
 __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
   const int wid = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 15, quad = lane >> 4;
   const int hs = a.v.hs, Hq = a.v.Hq;
   constexpr int WG_KEYS = 16 * KB * NW, NTHR = 64 * NW;
+  using P = PTile<D>;
+  using SG = DkvStage<D, ST>;
   int g = blockIdx.y, blk, tile;
   // key range of the block and query source
   int kbeg, kend, qbeg = 0, qend = 0;
@@ -456,13 +458,8 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
     // the chunk prefix sums.
     const int per8 = 8 * a.tiles_per_block;
     const int nkeys = a.v.Hkv * a.v.Ns, w = (int)(blockIdx.x / per8) * 8 + (int)(blockIdx.x % 8);
-    if (w >= a.chunk_start[nkeys]) return;
-    int lo = 0, hi = nkeys;  // chunk_start[lo] <= w < chunk_start[hi]
-    while (hi - lo > 1) {
-      const int mid = (lo + hi) >> 1;
-      if (a.chunk_start[mid] <= w) lo = mid; else hi = mid;
-    }
-    const int key = lo, chunk = w - a.chunk_start[key];
+    int key, chunk;
+    if (!bc_find_chunk(a.chunk_start, nkeys, w, key, chunk)) return;
     g = key / a.v.Ns; blk = key % a.v.Ns; tile = (int)(blockIdx.x % per8) / 8;
     kbeg = a.v.slc_start[blk]; kend = a.v.slc_start[blk + 1];
     qbeg = a.sel_start[key] + chunk * a.chunk_len;
@@ -499,122 +496,141 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
     for (int dt = 0; dt < D / 16; ++dt) dk[kbk][dt] = dv[kbk][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   extern __shared__ __align__(16) unsigned char smem[];
-  using G = TileGeom<D>;
-  using SG = DkvStage<D>;
-  const int slots = 32 / hs;  // token slots per 32-row tile (hs is 8 or 16)
+  const int slots = 32 / hs;              // token slots per 32-row tile (hs is 8 or 16)
+  const int stage_slots = ST * slots;     // token slots per stage
   const float sl2 = a.v.sl2, scale = a.v.scale;
-  // sorted positions of the token slots of the tile that starts at list index qb (-1: past the end)
-  auto positions = [&](int qb, int (&p)[4]) {
+  // what this thread stages: NI 16-byte items of Q and of dO per stage, and (threads < 3*32*ST) one scalar
+  constexpr int NI = (ST * P::ITEMS + NTHR - 1) / NTHR;
+  int it_off[NI], it_slot[NI], it_col[NI];  // LDS byte offset, token slot inside the stage, element offset inside the token
 #pragma unroll
-    for (int sidx = 0; sidx < 4; ++sidx) {
-      const int sl = qb + sidx;
-      p[sidx] = (sidx < slots && sl < qend) ? (MODE == DKV_SLC ? a.sel_list[sl] : sl) : -1;
-    }
+  for (int i = 0; i < NI; ++i) {
+    // (when the stage has fewer items than the workgroup threads, the surplus threads repeat the last items)
+    const int it = min((int)threadIdx.x + NTHR * i, ST * P::ITEMS - 1);
+    const int rt = it / P::ITEMS, w = it % P::ITEMS, row = w / P::SEGS, seg = w % P::SEGS;
+    it_off[i] = rt * P::BYTES + P::off(row, seg);
+    it_slot[i] = rt * slots + row / hs;
+    it_col[i] = (g * hs + row % hs) * D + seg * 8;
+  }
+  static_assert(3 * 32 * ST <= NTHR, "one scalar per thread and stage");
+  const bool has_sc = threadIdx.x < 3 * 32 * ST;
+  const int sc_arr = threadIdx.x / (32 * ST), sc_r = threadIdx.x % (32 * ST);
+  const int sc_slot = (sc_r >> 5) * slots + (sc_r & 31) / hs, sc_head = g * hs + (sc_r & 31) % hs;
+  const float *sc_src = sc_arr == 0 ? a.lse2s : (sc_arr == 1 ? a.deltas : a.gws);
+  // sorted position of the token at list index li (-1: past the end)
+  auto position = [&](int li) { return li < qend ? (MODE == DKV_SLC ? a.sel_list[li] : li) : -1; };
+  // Two register sets and two position sets, used alternately: while stage i is consumed, the rows of stage i+2 are
+  // requested (two stages of loads in flight) with the positions read during stage i-1, and the positions of stage
+  // i+3 are read.  Inside a stage the positions are requested BEFORE the rows, so that waiting for them (the next
+  // stage needs them for its addresses) leaves the younger row loads in flight; nothing loaded is touched before the
+  // stage that stores it into LDS.
+  struct StageRegs { bf16x8 rq[NI], rd[NI]; float sc; bool missing; };
+  struct StagePos { int it[NI], sc; };
+  StageRegs regs[2];
+  StagePos pos[2];
+  auto load_positions = [&](int qb, StagePos &p) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i) p.it[i] = position(qb + it_slot[i]);
+    p.sc = has_sc ? position(qb + sc_slot) : -1;
   };
-  bf16x8 rq[G::row_per_thread(NTHR)], rd[G::row_per_thread(NTHR)];
-  float sc = 0.f;
-  auto pick = [](const int (&p)[4], int i) { return i == 0 ? p[0] : (i == 1 ? p[1] : (i == 2 ? p[2] : p[3])); };
-  auto load_tile = [&](const int (&p)[4]) {
+  auto load_stage = [&](StageRegs &r, const StagePos &p) {
 #pragma unroll
-    for (int i = 0; i < G::row_per_thread(NTHR); ++i) {
-      const int it = threadIdx.x + NTHR * i;
-      if (G::ROW_ITEMS % NTHR == 0 || it < G::ROW_ITEMS) {
-        const int row = it / (D / 8), seg = it % (D / 8);
-        const int pos = max(pick(p, row / hs), 0);
-        const uint32_t off = ((uint32_t)pos * Hq + g * hs + row % hs) * D + seg * 8;
-        rq[i] = ld8(a.Qs + off);
-        rd[i] = ld8(a.dOs + off);
-      }
+    for (int i = 0; i < NI; ++i) {
+      const uint32_t off = (uint32_t)max(p.it[i], 0) * (uint32_t)(Hq * D) + (uint32_t)it_col[i];
+      r.rq[i] = ld8(a.Qs + off);
+      r.rd[i] = ld8(a.dOs + off);
     }
-    if (threadIdx.x < 96) {
-      const int arr = threadIdx.x >> 5, row = threadIdx.x & 31;
-      const int pos = pick(p, row / hs);
-      const uint32_t rsx = (uint32_t)max(pos, 0) * Hq + g * hs + row % hs;
-      const float *srcp = arr == 0 ? a.lse2s : (arr == 1 ? a.deltas : a.gws);
-      sc = srcp[rsx];
-      if (arr == 0 && pos < 0) sc = INFINITY;  // a missing row contributes exp2(-inf) = 0
-    }
+    r.sc = has_sc ? sc_src[(uint32_t)max(p.sc, 0) * Hq + sc_head] : 0.f;
+    r.missing = sc_arr == 0 && p.sc < 0;  // a missing row gets lse = +inf: it contributes exp2(-inf) = 0
   };
-  auto store_tile = [&](unsigned char *stage) {
-    bf16_t *e = (bf16_t *)stage;
+  auto store_stage = [&](const StageRegs &r, unsigned char *stage) {
 #pragma unroll
-    for (int i = 0; i < G::row_per_thread(NTHR); ++i) {
-      const int it = threadIdx.x + NTHR * i;
-      if (G::ROW_ITEMS % NTHR == 0 || it < G::ROW_ITEMS) {
-        const int off = G::row_off(it / (D / 8), it % (D / 8));
-        *reinterpret_cast<bf16x8 *>(e + off) = rq[i];
-        *reinterpret_cast<bf16x8 *>(e + G::ROW_ELEMS + off) = rd[i];
-      }
+    for (int i = 0; i < NI; ++i) {
+      *reinterpret_cast<bf16x8 *>(stage + it_off[i]) = r.rq[i];
+      *reinterpret_cast<bf16x8 *>(stage + ST * P::BYTES + it_off[i]) = r.rd[i];
     }
-    if (threadIdx.x < 96) ((float *)(stage + SG::ELEMS * 2))[threadIdx.x] = sc;
+    if (has_sc) ((float *)(stage + SG::TILES_B))[threadIdx.x] = r.missing ? INFINITY : r.sc;
   };
 
-  int pcur[4], pnxt[4];
-  positions(qbeg, pcur);
-  if (qbeg < qend) load_tile(pcur);
-  positions(qbeg + slots, pnxt);
+  load_positions(qbeg, pos[0]);
+  load_positions(qbeg + stage_slots, pos[1]);
+  load_stage(regs[0], pos[0]);
+  load_stage(regs[1], pos[1]);
+  load_positions(qbeg + 2 * stage_slots, pos[0]);
   int buf = 0;
-  for (int qb = qbeg; qb < qend; qb += slots) {
+  // stage qb: `r` holds its rows; `p_rows` the positions of stage qb+2, `p_next` is refilled with those of stage qb+3
+  auto do_stage = [&](int qb, StageRegs &r, StagePos &p_rows, StagePos &p_next) {
     unsigned char *stage = smem + (size_t)buf * SG::BYTES;
-    store_tile(stage);
+    store_stage(r, stage);
     __syncthreads();
-    if (qb + slots < qend) {
-      load_tile(pnxt);
-      positions(qb + 2 * slots, pnxt);
+    if (qb + 2 * stage_slots < qend) {
+      load_positions(qb + 3 * stage_slots, p_next);
+      load_stage(r, p_rows);
     }
     buf ^= 1;
-    if (!wave_on) continue;
-    const bf16_t *Qr = (const bf16_t *)stage, *Dr = Qr + G::ROW_ELEMS;
-    const float *scal = (const float *)(stage + SG::ELEMS * 2);
-    f32x4 s[KB][2], dp[KB][2];
+    if (!wave_on) return;
+    const lds_cptr qrow = (lds_cptr)stage + P::row_lane(), qtr = (lds_cptr)stage + P::tr_lane();
+    const __attribute__((address_space(3))) float *scal =
+        (const __attribute__((address_space(3))) float *)((lds_cptr)stage + SG::TILES_B) + 8 * quad;
 #pragma unroll
-    for (int kbk = 0; kbk < KB; ++kbk)
+    for (int rt = 0; rt < ST; ++rt) {
+      if (qb + rt * slots >= qend) break;
+      const lds_cptr Qr = qrow + rt * P::BYTES, Dr = qrow + (ST + rt) * P::BYTES;
+      const lds_cptr Qt = qtr + rt * P::BYTES, Dt = qtr + (ST + rt) * P::BYTES;
+      f32x4 s[KB][2], dp[KB][2];
 #pragma unroll
-      for (int sa = 0; sa < 2; ++sa) s[kbk][sa] = dp[kbk][sa] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int kbk = 0; kbk < KB; ++kbk)
 #pragma unroll
-    for (int sa = 0; sa < 2; ++sa)
+        for (int sa = 0; sa < 2; ++sa) s[kbk][sa] = dp[kbk][sa] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int ks = 0; ks < D / 32; ++ks) {
-        const bf16x8 qa = lds_row_operand<D>(Qr, sa, ks), da = lds_row_operand<D>(Dr, sa, ks);
+      for (int sa = 0; sa < 2; ++sa)
 #pragma unroll
-        for (int kbk = 0; kbk < KB; ++kbk) {
-          s[kbk][sa] = mfma16(qa, kop[kbk][ks], s[kbk][sa]);
-          dp[kbk][sa] = mfma16(da, vop[kbk][ks], dp[kbk][sa]);
+        for (int ks = 0; ks < D / 32; ++ks) {
+          const bf16x8 qa = p_row_operand<D>(Qr, sa, ks), da = p_row_operand<D>(Dr, sa, ks);
+#pragma unroll
+          for (int kbk = 0; kbk < KB; ++kbk) {
+            s[kbk][sa] = mfma16(qa, kop[kbk][ks], s[kbk][sa]);
+            dp[kbk][sa] = mfma16(da, vop[kbk][ks], dp[kbk][sa]);
+          }
+        }
+      // this lane's eight consecutive query rows 8*quad .. +7 of the tile
+      float lse2[8], delta[8], gw[8];
+      {
+        typedef const __attribute__((address_space(3))) f32x4 *f4p;
+        const f32x4 l0 = *(f4p)(scal + 32 * rt), l1 = *(f4p)(scal + 32 * rt + 4);
+        const f32x4 d0 = *(f4p)(scal + 32 * (ST + rt)), d1 = *(f4p)(scal + 32 * (ST + rt) + 4);
+        const f32x4 g0 = *(f4p)(scal + 32 * (2 * ST + rt)), g1 = *(f4p)(scal + 32 * (2 * ST + rt) + 4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          lse2[j] = l0[j]; lse2[4 + j] = l1[j];
+          delta[j] = d0[j]; delta[4 + j] = d1[j];
+          gw[j] = g0[j]; gw[4 + j] = g1[j];
         }
       }
-    // this lane's eight consecutive query rows 8*quad .. +7
-    float lse2[8], delta[8], gw[8];
-    {
-      const float4 l0 = *reinterpret_cast<const float4 *>(scal + 8 * quad), l1 = *reinterpret_cast<const float4 *>(scal + 8 * quad + 4);
-      const float4 d0 = *reinterpret_cast<const float4 *>(scal + 32 + 8 * quad), d1 = *reinterpret_cast<const float4 *>(scal + 36 + 8 * quad);
-      const float4 g0 = *reinterpret_cast<const float4 *>(scal + 64 + 8 * quad), g1 = *reinterpret_cast<const float4 *>(scal + 68 + 8 * quad);
-      lse2[0] = l0.x; lse2[1] = l0.y; lse2[2] = l0.z; lse2[3] = l0.w; lse2[4] = l1.x; lse2[5] = l1.y; lse2[6] = l1.z; lse2[7] = l1.w;
-      delta[0] = d0.x; delta[1] = d0.y; delta[2] = d0.z; delta[3] = d0.w; delta[4] = d1.x; delta[5] = d1.y; delta[6] = d1.z; delta[7] = d1.w;
-      gw[0] = g0.x; gw[1] = g0.y; gw[2] = g0.z; gw[3] = g0.w; gw[4] = g1.x; gw[5] = g1.y; gw[6] = g1.z; gw[7] = g1.w;
-    }
-    bf16x8 qt[D / 16], dot[D / 16];
+      bf16x8 pw[KB], ds[KB];
 #pragma unroll
-    for (int dt = 0; dt < D / 16; ++dt) {
-      qt[dt] = lds_tr_operand<D>(Qr, dt);
-      dot[dt] = lds_tr_operand<D>(Dr, dt);
-    }
+      for (int kbk = 0; kbk < KB; ++kbk)
 #pragma unroll
-    for (int kbk = 0; kbk < KB; ++kbk) {
-      bf16x8 pw, ds;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const float sv = j < 4 ? s[kbk][0][j & 3] : s[kbk][1][j & 3];
-        const float dpv = j < 4 ? dp[kbk][0][j & 3] : dp[kbk][1][j & 3];
-        const float p = fast_exp2(__builtin_fmaf(sv, sl2, -lse2[j]));
-        pw[j] = (__bf16)(p * gw[j]);
-        ds[j] = (__bf16)(p * __builtin_fmaf(gw[j] * scale, dpv, -delta[j] * scale));
-      }
+        for (int j = 0; j < 8; ++j) {
+          const float sv = j < 4 ? s[kbk][0][j & 3] : s[kbk][1][j & 3];
+          const float dpv = j < 4 ? dp[kbk][0][j & 3] : dp[kbk][1][j & 3];
+          const float p = fast_exp2(__builtin_fmaf(sv, sl2, -lse2[j]));
+          pw[kbk][j] = (__bf16)(p * gw[j]);
+          ds[kbk][j] = (__bf16)(p * __builtin_fmaf(gw[j] * scale, dpv, -delta[j] * scale));
+        }
 #pragma unroll
       for (int dt = 0; dt < D / 16; ++dt) {
-        dv[kbk][dt] = mfma16(dot[dt], pw, dv[kbk][dt]);
-        dk[kbk][dt] = mfma16(qt[dt], ds, dk[kbk][dt]);
+        const bf16x8 qt = p_tr_operand<D>(Qt, dt), dot = p_tr_operand<D>(Dt, dt);
+#pragma unroll
+        for (int kbk = 0; kbk < KB; ++kbk) {
+          dv[kbk][dt] = mfma16(dot, pw[kbk], dv[kbk][dt]);
+          dk[kbk][dt] = mfma16(qt, ds[kbk], dk[kbk][dt]);
+        }
       }
     }
+  };
+  for (int qb = qbeg; qb < qend; qb += 2 * stage_slots) {
+    do_stage(qb, regs[0], pos[0], pos[1]);
+    if (qb + stage_slots < qend) do_stage(qb + stage_slots, regs[1], pos[1], pos[0]);
   }
   if (!wave_on) return;
   // --- store: lane holds dims 16*dt + 4*quad + i of key column n
@@ -702,7 +718,9 @@ template <> struct BcDqShape<128> { static constexpr int NW = 8, KSEG = 256; };
 constexpr int KB_KEYS_MAX = 2;  // key blocks of 16 per wavefront in the dK/dV kernels (1 at head_dim 128: registers)
 // wavefronts per workgroup there (16*KB_KEYS keys each): blocks and windows hold ~130 tokens, an item's pooled keys
 // thousands, so the compression branch takes wider workgroups (fewer passes over the query rows)
-constexpr int DKV_WAVES = 4, DKV_WAVES_CMP = 8;
+constexpr int DKV_WAVES = 4, DKV_WAVES_CMP = 4;
+// 32-row tiles of query rows per LDS stage (one barrier per stage)
+template <int D> struct DkvShape { static constexpr int ST = 2; };
 
 template <int D>
 int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const void *gates, const void *out_branch,
@@ -752,12 +770,13 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
   constexpr int KB_KEYS = D >= 128 ? 1 : KB_KEYS_MAX;
   constexpr int WG_KEYS = 16 * KB_KEYS * DKV_WAVES, WG_KEYS_CMP = 16 * KB_KEYS * DKV_WAVES_CMP;
   static_assert(WG_KEYS <= SSA_KEY_PAD && WG_KEYS_CMP <= SSA_KEY_PAD, "key tiles may read up to WG_KEYS rows past a block");
-  const size_t dkv_lds = (size_t)2 * DkvStage<D>::BYTES;
+  constexpr int ST = DkvShape<D>::ST;
+  const size_t dkv_lds = (size_t)2 * DkvStage<D, ST>::BYTES;
   static std::once_flag dkv_once;
   std::call_once(dkv_once, [] {
-    (void)hipFuncSetAttribute((const void *)m_bwd_dkv<D, KB_KEYS, DKV_WIN, DKV_WAVES>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    (void)hipFuncSetAttribute((const void *)m_bwd_dkv<D, KB_KEYS, DKV_SLC, DKV_WAVES>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    (void)hipFuncSetAttribute((const void *)m_bwd_dkv<D, KB_KEYS, DKV_CMP, DKV_WAVES_CMP>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    (void)hipFuncSetAttribute((const void *)m_bwd_dkv<D, KB_KEYS, DKV_WIN, DKV_WAVES, ST>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    (void)hipFuncSetAttribute((const void *)m_bwd_dkv<D, KB_KEYS, DKV_SLC, DKV_WAVES, ST>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    (void)hipFuncSetAttribute((const void *)m_bwd_dkv<D, KB_KEYS, DKV_CMP, DKV_WAVES_CMP, ST>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
   });
   DkvArgs base{v, w.Qs, w.dOs, nullptr, nullptr, nullptr, w.sel.start, w.sel.list,
                w.dKs, w.dVs, w.sel.chunk_start, w.sel.part_row_start, w.sel.chunk_len, 1, 1};
@@ -766,7 +785,7 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
     DkvArgs a = base;
     a.lse2s = w.lse2s + 2 * NH; a.deltas = w.deltas + 2 * NH; a.gws = w.gws + 2 * NH;
     a.tiles_per_block = (blk->win_tok_max + WG_KEYS - 1) / WG_KEYS;
-    m_bwd_dkv<D, KB_KEYS, DKV_WIN, DKV_WAVES><<<dim3(blk->Nw * a.tiles_per_block, Hkv), 64 * DKV_WAVES, dkv_lds, s>>>(a);
+    m_bwd_dkv<D, KB_KEYS, DKV_WIN, DKV_WAVES, ST><<<dim3(blk->Nw * a.tiles_per_block, Hkv), 64 * DKV_WAVES, dkv_lds, s>>>(a);
   }
   {
     ProfScope ps(PROF_BWD_DKV_SLC, s);
@@ -774,7 +793,7 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
     a.lse2s = w.lse2s + NH; a.deltas = w.deltas + NH; a.gws = w.gws + NH;
     a.dK = w.pK; a.dV = w.pV;
     a.tiles_per_block = (blk->slc_tok_max + WG_KEYS - 1) / WG_KEYS;
-    m_bwd_dkv<D, KB_KEYS, DKV_SLC, DKV_WAVES><<<dim3((w.max_chunks + 7) / 8 * 8 * a.tiles_per_block), 64 * DKV_WAVES, dkv_lds, s>>>(a);
+    m_bwd_dkv<D, KB_KEYS, DKV_SLC, DKV_WAVES, ST><<<dim3((w.max_chunks + 7) / 8 * 8 * a.tiles_per_block), 64 * DKV_WAVES, dkv_lds, s>>>(a);
     const size_t items = (size_t)N * Hkv * (D / 4);
     m_slc_reduce<<<(unsigned)((items + 255) / 256), 256, 0, s>>>(blk->tok_slc, v.slc_start, w.sel.chunk_start, w.sel.part_row_start, N,
                                                                  Hkv, v.Ns, D, w.pK, w.pV, w.dKs, w.dVs);
@@ -786,7 +805,7 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
     a.dK = w.dKc; a.dV = w.dVc;
     a.tiles_per_block = (blk->c_max + WG_KEYS_CMP - 1) / WG_KEYS_CMP;
     a.q_splits = w.q_splits;
-    m_bwd_dkv<D, KB_KEYS, DKV_CMP, DKV_WAVES_CMP><<<dim3(B * a.tiles_per_block, Hkv, w.q_splits), 64 * DKV_WAVES_CMP, dkv_lds, s>>>(a);
+    m_bwd_dkv<D, KB_KEYS, DKV_CMP, DKV_WAVES_CMP, ST><<<dim3(B * a.tiles_per_block, Hkv, w.q_splits), 64 * DKV_WAVES_CMP, dkv_lds, s>>>(a);
   }
   {
     ProfScope ps(PROF_BWD_FINISH, s);

@@ -99,7 +99,7 @@ struct BwdPlan {
   int q_splits, chunk_len, max_chunks;
 };
 
-constexpr int DKV_WG_KEYS = 256;  // keys per workgroup of the dK/dV kernels (8 waves x 2 blocks of 16)
+constexpr int DKV_WG_KEYS = 128;  // keys per workgroup of the dK/dV kernels (4 waves x 2 blocks of 16)
 
 BwdPlan bwd_plan(const ssa_ctx &c) {
   BwdPlan p{};
@@ -107,7 +107,7 @@ BwdPlan bwd_plan(const ssa_ctx &c) {
   const size_t row = (size_t)c.Hkv * c.d;
   const int tiles = (b->c_max + DKV_WG_KEYS - 1) / DKV_WG_KEYS;
   const long long wgs = (long long)c.B * (tiles > 0 ? tiles : 1) * c.Hkv;
-  long long sp = (1024 + wgs - 1) / wgs;
+  long long sp = (2048 + wgs - 1) / wgs;  // about 2048 workgroups: four rounds of two per compute unit
   p.q_splits = (int)(sp < 1 ? 1 : (sp > 64 ? 64 : sp));
   size_t off = 0;
   auto take = [&](size_t n) { size_t r = off; off += align_up(n, 256); return r; };
