@@ -1,57 +1,15 @@
-// LDS tile layout and work-chunk lookup of the block-centric selection kernels (gfx950, wave64).
-//
-// A 32-row tile of a row-major bf16 array is kept as D/8 planes, one per 16-byte segment of a row; a plane holds the
-// 32 rows' segments in the slot order sigma(row) (the order in which the lanes of the two 16-row matrix sub-tiles read
-// them, see TileGeom) and is followed by 64 bytes of padding.  Every operand address is then lane part + compile-time
-// constant: the sub-tile, the contraction step, the output-dim block and the tile index all move the address by
-// constants, which the LDS instructions take as immediate offsets, so a tile costs no address arithmetic at all.  The
-// padding shifts consecutive planes by 16 banks: the 16 lanes of a transposing read (two planes, four rows each) and
-// the 64 lanes of a staging write (eight planes) spread evenly over the banks.
+// Staging of whole key blocks into LDS and the work-chunk lookup of the block-centric selection kernels (gfx950,
+// wave64); the tile layout itself (PTile) is the one of mfma_qc.h.
 #pragma once
 
 #include "mfma_qc.h"
 
-template <int D>
-struct PTile {
-  static constexpr int SEGS = D / 8;
-  static constexpr int PLANE_B = 32 * 16 + 64;   // bytes per plane
-  static constexpr int BYTES = SEGS * PLANE_B;   // bytes per 32-row tile
-  static constexpr int ITEMS = 32 * SEGS;        // 16-byte items per tile
-  __device__ static inline int off(int row, int seg) { return seg * PLANE_B + TileGeom<D>::sigma(row) * 16; }
-  // lane part of the address of a row operand (A or B operand whose rows are the tile's rows): sub-tile a and
-  // contraction step ks add a*256 + ks*4*PLANE_B
-  __device__ static inline int row_lane() { return (int)(threadIdx.x >> 4 & 3) * PLANE_B + (int)(threadIdx.x & 15) * 16; }
-  // lane part of the address of a transposed operand (rows = dims 16*dt + n, contraction over the tile's rows
-  // 8*quad .. +7): dim block dt adds dt*2*PLANE_B, the second half (rows +4 .. +7) adds 256
-  __device__ static inline int tr_lane() {
-    const int p = threadIdx.x & 15, quad = threadIdx.x >> 4 & 3;
-    return ((p & 3) >> 1) * PLANE_B + (4 * quad + (p >> 2)) * 16 + (p & 1) * 8;
-  }
-};
-
-typedef const __attribute__((address_space(3))) unsigned char *lds_cptr;
-
-template <int D>
-__device__ inline bf16x8 p_row_operand(lds_cptr lane_base, int a, int ks) {
-  return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8 *>(lane_base + a * 256 + ks * 4 * PTile<D>::PLANE_B);
-}
-
-template <int D>
-__device__ inline bf16x8 p_tr_operand(lds_cptr lane_base, int dt) {
-  typedef __attribute__((address_space(3))) s16x4 *tr_ptr;
-  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tr_ptr)(lane_base + dt * 2 * PTile<D>::PLANE_B));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tr_ptr)(lane_base + dt * 2 * PTile<D>::PLANE_B + 256));
-  typedef __attribute__((ext_vector_type(8))) short s16x8;
-  const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8, both);
-}
-
 // Copy rows r0 .. r0 + 32*ntiles - 1 of two row-major arrays (already offset to the KV group or head group; `stride`
 // elements between rows) into LDS tiles of the layout above.
-template <int D, int NTHR>
+template <int D, bool SWZ, int NTHR>
 __device__ inline void p_stage2(const bf16_t *xa, const bf16_t *xb, uint32_t stride, int r0, int ntiles, unsigned char *ta,
                                 unsigned char *tb) {
-  using P = PTile<D>;
+  using P = PTile<D, SWZ>;
   const int total = ntiles * P::ITEMS;
   for (int i0 = 0; i0 < total; i0 += 4 * NTHR) {
     bf16x8 ra[4], rb[4];

@@ -89,11 +89,11 @@ struct DqArgs {
 };
 
 // One staged 32-key tile: transposed scores (K rows) and dP (V rows), then dQ^T += K^T dS^T (the K rows again, read
-// through the transposing LDS load).
+// through the transposing LDS load).  kt, vt: the staged K and V tiles, ln: the lane offsets of their operands (PTile).
 // lse2 is +inf for a column whose token did not select the current block, which makes its P exactly zero.
 template <int D, int CB, bool MASK>
 __device__ inline void dq_tile(f32x4 (&acc)[CB][D / 16], const QRows<D, CB> &q, const bf16x8 (&dop)[CB][D / 32],
-                               const bf16_t *ktile, const bf16_t *vtile, int kb, const int (&lo)[CB],
+                               lds_cptr kt, lds_cptr vt, const typename PTile<D>::Lanes &ln, int kb, const int (&lo)[CB],
                                const int (&hi)[CB], const bool (&act)[CB], float sl2, float scale, const float (&lse2)[CB],
                                const float (&delta)[CB], const float (&gw)[CB]) {
   const int quad = threadIdx.x >> 4 & 3;
@@ -105,8 +105,8 @@ __device__ inline void dq_tile(f32x4 (&acc)[CB][D / 16], const QRows<D, CB> &q, 
   for (int cb = 0; cb < CB; ++cb) s0[cb] = s1[cb] = p0[cb] = p1[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int ks = 0; ks < D / 32; ++ks) {
-    const bf16x8 k0 = lds_row_operand<D>(ktile, 0, ks), k1 = lds_row_operand<D>(ktile, 1, ks);
-    const bf16x8 v0 = lds_row_operand<D>(vtile, 0, ks), v1 = lds_row_operand<D>(vtile, 1, ks);
+    const bf16x8 k0 = p_row_operand<D, true>(kt, ln, 0, ks), k1 = p_row_operand<D, true>(kt, ln, 1, ks);
+    const bf16x8 v0 = p_row_operand<D, true>(vt, ln, 0, ks), v1 = p_row_operand<D, true>(vt, ln, 1, ks);
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
       if (act[cb]) {
@@ -133,10 +133,10 @@ __device__ inline void dq_tile(f32x4 (&acc)[CB][D / 16], const QRows<D, CB> &q, 
   }
 #pragma unroll
   for (int dt = 0; dt < D / 16; ++dt) {
-    const bf16x8 kt = lds_tr_operand<D>(ktile, dt);
+    const bf16x8 ktd = p_tr_operand<D, true>(kt, ln, dt);
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
-      if (act[cb]) acc[cb][dt] = mfma16(kt, dsb[cb], acc[cb][dt]);
+      if (act[cb]) acc[cb][dt] = mfma16(ktd, dsb[cb], acc[cb][dt]);
   }
 }
 
@@ -176,6 +176,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
     for (int dt = 0; dt < D / 16; ++dt) acc[cb][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
   const float sl2 = a.v.sl2, scale = a.v.scale;
   const size_t kstride = (size_t)a.v.Hkv * D;
+  const typename PTile<D>::Lanes ln = PTile<D>::lanes();
   int lo[CB], hi[CB];
   bool act[CB];
   float lse2[CB], delta[CB], gw[CB];
@@ -210,10 +211,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
         [&](const bf16_t *stg, int kb, int) {
           bf16_t *st = (bf16_t *)stg;
           if (uniform && kb >= rs && kb + 32 <= re)
-            dq_tile<D, CB, false>(acc, q, dop, L::row_tile(st, 0), L::row_tile(st, 1), kb, lo, hi, act, sl2,
+            dq_tile<D, CB, false>(acc, q, dop, (lds_cptr)L::row_tile(st, 0), (lds_cptr)L::row_tile(st, 1), ln, kb, lo, hi, act, sl2,
                                   scale, lse2, delta, gw);
           else
-            dq_tile<D, CB, true>(acc, q, dop, L::row_tile(st, 0), L::row_tile(st, 1), kb, lo, hi, act, sl2,
+            dq_tile<D, CB, true>(acc, q, dop, (lds_cptr)L::row_tile(st, 0), (lds_cptr)L::row_tile(st, 1), ln, kb, lo, hi, act, sl2,
                                  scale, lse2, delta, gw);
         });
   }
@@ -271,15 +272,15 @@ __device__ inline void bc_dq_load_rows(const BcDqArgs &a, const int *tl, const i
 // One 32-key LDS tile: transposed scores (K rows) and dP (V rows), dS^T = P (gate dP - delta) scale, then
 // dQ^T += K^T dS^T with K^T read from the same K tile through the transposing LDS load.
 template <int D, bool MASK>
-__device__ inline void bc_dq_tile(f32x4 (&acc)[D / 16], const BcDqRows<D> &r, lds_cptr kr, lds_cptr vr, lds_cptr ktr, int key0,
-                                  int nk, float sl2) {
+__device__ inline void bc_dq_tile(f32x4 (&acc)[D / 16], const BcDqRows<D> &r, lds_cptr kt, lds_cptr vt,
+                                  const typename PTile<D, false>::Lanes &ln, int key0, int nk, float sl2) {
   f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0, p0 = s0, p1 = s0;
 #pragma unroll
   for (int ks = 0; ks < D / 32; ++ks) {
-    s0 = mfma16(p_row_operand<D>(kr, 0, ks), r.qop[ks], s0);
-    s1 = mfma16(p_row_operand<D>(kr, 1, ks), r.qop[ks], s1);
-    p0 = mfma16(p_row_operand<D>(vr, 0, ks), r.dop[ks], p0);
-    p1 = mfma16(p_row_operand<D>(vr, 1, ks), r.dop[ks], p1);
+    s0 = mfma16(p_row_operand<D, false>(kt, ln, 0, ks), r.qop[ks], s0);
+    s1 = mfma16(p_row_operand<D, false>(kt, ln, 1, ks), r.qop[ks], s1);
+    p0 = mfma16(p_row_operand<D, false>(vt, ln, 0, ks), r.dop[ks], p0);
+    p1 = mfma16(p_row_operand<D, false>(vt, ln, 1, ks), r.dop[ks], p1);
   }
   bf16x8 ds;
   const int first = key0 + 8 * (int)(threadIdx.x >> 4 & 3);
@@ -291,16 +292,16 @@ __device__ inline void bc_dq_tile(f32x4 (&acc)[D / 16], const BcDqRows<D> &r, ld
     ds[j] = (__bf16)(p * __builtin_fmaf(r.gws, dp, -r.dls));
   }
 #pragma unroll
-  for (int dt = 0; dt < D / 16; ++dt) acc[dt] = mfma16(p_tr_operand<D>(ktr, dt), ds, acc[dt]);
+  for (int dt = 0; dt < D / 16; ++dt) acc[dt] = mfma16(p_tr_operand<D, false>(kt, ln, dt), ds, acc[dt]);
 }
 
 template <int D, int KSEG>
-constexpr size_t bc_dq_lds_bytes() { return (size_t)2 * (KSEG / 32) * PTile<D>::BYTES + (size_t)2 * BC_CHUNK * sizeof(int); }
+constexpr size_t bc_dq_lds_bytes() { return (size_t)2 * (KSEG / 32) * PTile<D, false>::BYTES + (size_t)2 * BC_CHUNK * sizeof(int); }
 
 template <int D, int NW, int KSEG>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4 : 2))) void m_bwd_dq_bc(BcDqArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
-  using P = PTile<D>;
+  using P = PTile<D, false>;
   constexpr int MAXT = KSEG / 32;
   unsigned char *Kt = smem, *Vt = Kt + MAXT * P::BYTES;
   int *tl = (int *)(Vt + MAXT * P::BYTES), *sl = tl + BC_CHUNK;
@@ -325,7 +326,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
   const int n_it = (cnt + tpw - 1) / tpw;
   const uint32_t kstride = (uint32_t)(Hkv * D);
   const float sl2 = a.v.sl2;
-  const lds_cptr kr = (lds_cptr)Kt + P::row_lane(), vr = (lds_cptr)Vt + P::row_lane(), ktr = (lds_cptr)Kt + P::tr_lane();
+  const typename P::Lanes ln = P::lanes();
+  const lds_cptr kt = (lds_cptr)Kt, vt = (lds_cptr)Vt;
   __syncthreads();
   BcDqRows<D> cur;
   if (wid < n_it) bc_dq_load_rows<D>(a, tl, sl, wid, cnt, g, cur);
@@ -335,7 +337,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
       __syncthreads();
       if (wid < n_it) bc_dq_load_rows<D>(a, tl, sl, wid, cnt, g, cur);
     }
-    p_stage2<D, 64 * NW>(a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D, kstride, k0, (nk + 31) >> 5, Kt, Vt);
+    p_stage2<D, false, 64 * NW>(a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D, kstride, k0, (nk + 31) >> 5, Kt, Vt);
     __syncthreads();
     for (int it = wid; it < n_it; it += NW) {
       BcDqRows<D> nxt;
@@ -353,9 +355,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
       }
 #pragma unroll
       for (int t = 0; t < MAXT; ++t)
-        if (t < nfull) bc_dq_tile<D, false>(acc, cur, kr + t * P::BYTES, vr + t * P::BYTES, ktr + t * P::BYTES, 32 * t, nk, sl2);
-      if (nk & 31)
-        bc_dq_tile<D, true>(acc, cur, kr + nfull * P::BYTES, vr + nfull * P::BYTES, ktr + nfull * P::BYTES, 32 * nfull, nk, sl2);
+        if (t < nfull) bc_dq_tile<D, false>(acc, cur, kt + t * P::BYTES, vt + t * P::BYTES, ln, 32 * t, nk, sl2);
+      if (nk & 31) bc_dq_tile<D, true>(acc, cur, kt + nfull * P::BYTES, vt + nfull * P::BYTES, ln, 32 * nfull, nk, sl2);
       if (cur.valid) {
 #pragma unroll
         for (int dt = 0; dt < D / 16; ++dt) {
@@ -499,6 +500,7 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
   const int slots = 32 / hs;              // token slots per 32-row tile (hs is 8 or 16)
   const int stage_slots = ST * slots;     // token slots per stage
   const float sl2 = a.v.sl2, scale = a.v.scale;
+  const typename P::Lanes ln = P::lanes();
   // what this thread stages: NI 16-byte items of Q and of dO per stage, and (threads < 3*32*ST) one scalar
   constexpr int NI = (ST * P::ITEMS + NTHR - 1) / NTHR;
   int it_off[NI], it_slot[NI], it_col[NI];  // LDS byte offset, token slot inside the stage, element offset inside the token
@@ -568,14 +570,13 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
     }
     buf ^= 1;
     if (!wave_on) return;
-    const lds_cptr qrow = (lds_cptr)stage + P::row_lane(), qtr = (lds_cptr)stage + P::tr_lane();
+    const lds_cptr st0 = (lds_cptr)stage;
     const __attribute__((address_space(3))) float *scal =
         (const __attribute__((address_space(3))) float *)((lds_cptr)stage + SG::TILES_B) + 8 * quad;
 #pragma unroll
     for (int rt = 0; rt < ST; ++rt) {
       if (qb + rt * slots >= qend) break;
-      const lds_cptr Qr = qrow + rt * P::BYTES, Dr = qrow + (ST + rt) * P::BYTES;
-      const lds_cptr Qt = qtr + rt * P::BYTES, Dt = qtr + (ST + rt) * P::BYTES;
+      const lds_cptr Qt = st0 + rt * P::BYTES, Dt = st0 + (ST + rt) * P::BYTES;
       f32x4 s[KB][2], dp[KB][2];
 #pragma unroll
       for (int kbk = 0; kbk < KB; ++kbk)
@@ -585,7 +586,7 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
       for (int sa = 0; sa < 2; ++sa)
 #pragma unroll
         for (int ks = 0; ks < D / 32; ++ks) {
-          const bf16x8 qa = p_row_operand<D>(Qr, sa, ks), da = p_row_operand<D>(Dr, sa, ks);
+          const bf16x8 qa = p_row_operand<D, true>(Qt, ln, sa, ks), da = p_row_operand<D, true>(Dt, ln, sa, ks);
 #pragma unroll
           for (int kbk = 0; kbk < KB; ++kbk) {
             s[kbk][sa] = mfma16(qa, kop[kbk][ks], s[kbk][sa]);
@@ -619,7 +620,7 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
         }
 #pragma unroll
       for (int dt = 0; dt < D / 16; ++dt) {
-        const bf16x8 qt = p_tr_operand<D>(Qt, dt), dot = p_tr_operand<D>(Dt, dt);
+        const bf16x8 qt = p_tr_operand<D, true>(Qt, ln, dt), dot = p_tr_operand<D, true>(Dt, ln, dt);
 #pragma unroll
         for (int kbk = 0; kbk < KB; ++kbk) {
           dv[kbk][dt] = mfma16(dot, pw[kbk], dv[kbk][dt]);

@@ -46,13 +46,14 @@ __device__ inline void init_state(FwdState<D, CB> &st) {
 
 // Raw transposed scores of the staged 32-key tile: s[cb][j] = <q column n of block cb, key kb + 8*quad + j>.
 template <int D, int CB>
-__device__ inline void score_tile(const bf16_t *ktile, const QRows<D, CB> &q, const bool (&act)[CB], float (&s)[CB][8]) {
+__device__ inline void score_tile(lds_cptr kt, const typename PTile<D>::Lanes &ln, const QRows<D, CB> &q, const bool (&act)[CB],
+                                  float (&s)[CB][8]) {
   f32x4 s0[CB], s1[CB];
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) s0[cb] = s1[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int ks = 0; ks < D / 32; ++ks) {
-    const bf16x8 a0 = lds_row_operand<D>(ktile, 0, ks), a1 = lds_row_operand<D>(ktile, 1, ks);
+    const bf16x8 a0 = p_row_operand<D, true>(kt, ln, 0, ks), a1 = p_row_operand<D, true>(kt, ln, 1, ks);
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
       if (act[cb]) {
@@ -70,6 +71,7 @@ __device__ inline void score_tile(const bf16_t *ktile, const QRows<D, CB> &q, co
 }
 
 // One online-softmax step (Algorithm 1, inner loop body) over the staged tile.
+//   kt/vt: the staged K and V tiles, ln: the lane offsets of their operands (see PTile);
 //   lo/hi: the keys each lane may see (used only when MASK);  on: this lane's column takes part in the tile at all
 //   (a token that did not select the current block is off);  act: wave-uniform "some lane of the block is on".
 // The reference maximum m of a column is raised lazily: only when some score exceeds it by more than 8 in log2
@@ -77,12 +79,13 @@ __device__ inline void score_tile(const bf16_t *ktile, const QRows<D, CB> &q, co
 // with its cross-lane maximum and rescale of o and l; otherwise the tile needs no cross-lane traffic at all.
 // The log-sum-exp reported at the end does not depend on which reference was used.
 template <int D, int CB, bool MASK>
-__device__ inline void fwd_tile(FwdState<D, CB> &st, const QRows<D, CB> &q, const bf16_t *ktile, const bf16_t *vtile, int kb,
+__device__ inline void fwd_tile(FwdState<D, CB> &st, const QRows<D, CB> &q, lds_cptr kt, lds_cptr vt,
+                                const typename PTile<D>::Lanes &ln, int kb,
                                 const int (&lo)[CB], const int (&hi)[CB], const bool (&on)[CB], const bool (&act)[CB],
                                 float sl2, float slack) {
   const int quad = threadIdx.x >> 4 & 3;
   float s[CB][8];
-  score_tile<D, CB>(ktile, q, act, s);
+  score_tile<D, CB>(kt, ln, q, act, s);
   bf16x8 pb[CB], ones;
 #pragma unroll
   for (int j = 0; j < 8; ++j) ones[j] = (__bf16)1.0f;
@@ -120,7 +123,7 @@ __device__ inline void fwd_tile(FwdState<D, CB> &st, const QRows<D, CB> &q, cons
   }
 #pragma unroll
   for (int dt = 0; dt < D / 16; ++dt) {
-    const bf16x8 av = lds_tr_operand<D>(vtile, dt);
+    const bf16x8 av = p_tr_operand<D, true>(vt, ln, dt);
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
       if (act[cb]) st.o[cb][dt] = mfma16(av, pb[cb], st.o[cb][dt]);
@@ -200,13 +203,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
   FwdState<D, CB> st;
   init_state(st);
   const float sl2 = a.v.sl2;
+  const typename PTile<D>::Lanes ln = PTile<D>::lanes();
   run_pipeline<D, 2>(
       src, stage0, ints + 4, ints + 5, nr, [](int) {},
       [&](const bf16_t *stg, int kb, int) {
         if (uniform && kb >= rs && kb + 32 <= re)
-          fwd_tile<D, CB, false>(st, q, L::row_tile((bf16_t *)stg, 0), L::row_tile((bf16_t *)stg, 1), kb, lo, hi, on, act, sl2, slack);
+          fwd_tile<D, CB, false>(st, q, (lds_cptr)L::row_tile((bf16_t *)stg, 0), (lds_cptr)L::row_tile((bf16_t *)stg, 1), ln, kb, lo, hi, on, act, sl2, slack);
         else
-          fwd_tile<D, CB, true>(st, q, L::row_tile((bf16_t *)stg, 0), L::row_tile((bf16_t *)stg, 1), kb, lo, hi, on, act, sl2, slack);
+          fwd_tile<D, CB, true>(st, q, (lds_cptr)L::row_tile((bf16_t *)stg, 0), (lds_cptr)L::row_tile((bf16_t *)stg, 1), ln, kb, lo, hi, on, act, sl2, slack);
       });
   float lse2[CB];
   finish<D, CB>(a, st, 0, q, lse2);
@@ -259,8 +263,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
               for (int cb = 0; cb < CB; ++cb) c[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
               for (int ks = 0; ks < D / 32; ++ks) {
-                const bf16x8 kop =
-                    *reinterpret_cast<const bf16x8 *>(stg + TileGeom<D>::slot_off(16 * sub + n, 4 * ks + quad));
+                const bf16x8 kop = p_row_operand<D, true>((lds_cptr)stg, ln, sub, ks);
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb) c[cb] = mfma16(q.qop[cb][ks], kop, c[cb]);
               }
@@ -284,7 +287,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
         ksrc, stage0, ints + 4, ints + 5, nr, [](int) {},
         [&](const bf16_t *stg, int kb, int) {
           float s[CB][8];
-          score_tile<D, CB>(stg, q, act, s);
+          score_tile<D, CB>((lds_cptr)stg, ln, q, act, s);
           const int hl = n % hs;
 #pragma unroll
           for (int cb = 0; cb < CB; ++cb) {
@@ -343,7 +346,7 @@ struct BcFwdArgs {
 
 // LDS plan (bytes): K tiles | V tiles (KSEG/32 tiles each, PTile layout) | token ids [BC_CHUNK] | ranks [BC_CHUNK]
 template <int D, int KSEG>
-constexpr size_t bc_lds_bytes() { return (size_t)2 * (KSEG / 32) * PTile<D>::BYTES + (size_t)2 * BC_CHUNK * sizeof(int); }
+constexpr size_t bc_lds_bytes() { return (size_t)2 * (KSEG / 32) * PTile<D, false>::BYTES + (size_t)2 * BC_CHUNK * sizeof(int); }
 
 // Query operands and partial-row index of one wavefront step: column n stands for chunk entry step*(16/h_s) + n/h_s,
 // head n % h_s of the KV group.
@@ -367,17 +370,18 @@ __device__ inline void bc_load_rows(const BcFwdArgs &a, const int *tl, const int
   r.prow = (uint32_t)((((size_t)tok * a.v.Hkv + g) * a.v.T + rank) * hs + hl);
 }
 
-// One online-softmax step (Algorithm 1, inner loop body) of 16 query columns over one 32-key LDS tile.  kl, vl: the
-// lane's operand addresses inside the tile (see PTile).  MASK: keys from index nk on (counted from the segment start;
+// One online-softmax step (Algorithm 1, inner loop body) of 16 query columns over one 32-key LDS tile.  kt, vt: the K
+// and V tile, ln: the lane offsets of their operands (see PTile).  MASK: keys from index nk on (counted from the segment start;
 // this tile starts at key0) do not exist.  Lazy reference maximum as in fwd_tile.
 template <int D, bool MASK>
-__device__ inline void bc_fwd_tile(FwdState<D, 1> &st, const bf16x8 (&qop)[D / 32], lds_cptr kl, lds_cptr vl, int key0,
-                                   int nk, float sl2, float slack, const bf16x8 &ones) {
+__device__ inline void bc_fwd_tile(FwdState<D, 1> &st, const bf16x8 (&qop)[D / 32], lds_cptr kt, lds_cptr vt,
+                                   const typename PTile<D, false>::Lanes &ln, int key0, int nk, float sl2, float slack,
+                                   const bf16x8 &ones) {
   f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int ks = 0; ks < D / 32; ++ks) {
-    s0 = mfma16(p_row_operand<D>(kl, 0, ks), qop[ks], s0);
-    s1 = mfma16(p_row_operand<D>(kl, 1, ks), qop[ks], s1);
+    s0 = mfma16(p_row_operand<D, false>(kt, ln, 0, ks), qop[ks], s0);
+    s1 = mfma16(p_row_operand<D, false>(kt, ln, 1, ks), qop[ks], s1);
   }
   float v[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
   if (MASK) {
@@ -403,13 +407,13 @@ __device__ inline void bc_fwd_tile(FwdState<D, 1> &st, const bf16x8 (&qop)[D / 3
   for (int j = 0; j < 8; ++j) pb[j] = (__bf16)fast_exp2(__builtin_fmaf(v[j], sl2, neg));
   st.l[0] = mfma16(ones, pb, st.l[0]);
 #pragma unroll
-  for (int dt = 0; dt < D / 16; ++dt) st.o[0][dt] = mfma16(p_tr_operand<D>(vl, dt), pb, st.o[0][dt]);
+  for (int dt = 0; dt < D / 16; ++dt) st.o[0][dt] = mfma16(p_tr_operand<D, false>(vt, ln, dt), pb, st.o[0][dt]);
 }
 
 template <int D, int NW, int KSEG>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4 : 2))) void m_slc_fwd_bc(BcFwdArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
-  using P = PTile<D>;
+  using P = PTile<D, false>;
   constexpr int MAXT = KSEG / 32;
   unsigned char *Kt = smem, *Vt = Kt + MAXT * P::BYTES;
   int *tl = (int *)(Vt + MAXT * P::BYTES), *sl = tl + BC_CHUNK;
@@ -437,7 +441,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
   bf16x8 ones;
 #pragma unroll
   for (int j = 0; j < 8; ++j) ones[j] = (__bf16)1.0f;
-  const lds_cptr kl = (lds_cptr)Kt + P::row_lane(), vl = (lds_cptr)Vt + P::tr_lane();
+  const typename P::Lanes ln = P::lanes();
+  const lds_cptr kl = (lds_cptr)Kt, vl = (lds_cptr)Vt;
   __syncthreads();
   BcRows<D> cur;
   if (wid < n_it) bc_load_rows<D>(a, tl, sl, wid, cnt, g, cur);  // in flight while the block is staged
@@ -447,7 +452,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
       __syncthreads();  // every wavefront is done with the previous segment
       if (wid < n_it) bc_load_rows<D>(a, tl, sl, wid, cnt, g, cur);
     }
-    p_stage2<D, 64 * NW>(a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D, kstride, k0, (nk + 31) >> 5, Kt, Vt);
+    p_stage2<D, false, 64 * NW>(a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D, kstride, k0, (nk + 31) >> 5, Kt, Vt);
     __syncthreads();
     for (int it = wid; it < n_it; it += NW) {
       BcRows<D> nxt;  // the next step's operands are requested before this step's arithmetic
@@ -467,9 +472,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
       }
 #pragma unroll
       for (int t = 0; t < MAXT; ++t)
-        if (t < nfull) bc_fwd_tile<D, false>(st, cur.qop, kl + t * P::BYTES, vl + t * P::BYTES, 32 * t, nk, sl2, slack, ones);
+        if (t < nfull) bc_fwd_tile<D, false>(st, cur.qop, kl + t * P::BYTES, vl + t * P::BYTES, ln, 32 * t, nk, sl2, slack, ones);
       if (nk & 31)
-        bc_fwd_tile<D, true>(st, cur.qop, kl + nfull * P::BYTES, vl + nfull * P::BYTES, 32 * nfull, nk, sl2, slack, ones);
+        bc_fwd_tile<D, true>(st, cur.qop, kl + nfull * P::BYTES, vl + nfull * P::BYTES, ln, 32 * nfull, nk, sl2, slack, ones);
       if (cur.valid) {
 #pragma unroll
         for (int dt = 0; dt < D / 16; ++dt) {
@@ -572,13 +577,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
   FwdState<D, CB> st;
   init_state(st);
   const float sl2 = a.v.sl2;
+  const typename PTile<D>::Lanes ln = PTile<D>::lanes();
   run_pipeline<D, 2>(
       src, stage0, ints + 4, ints + 5, re > rs ? 1 : 0, [](int) {},
       [&](const bf16_t *stg, int kb, int) {
         if (uniform && kb >= rs && kb + 32 <= re)
-          fwd_tile<D, CB, false>(st, q, L::row_tile((bf16_t *)stg, 0), L::row_tile((bf16_t *)stg, 1), kb, lo, hi, on, act, sl2, slack);
+          fwd_tile<D, CB, false>(st, q, (lds_cptr)L::row_tile((bf16_t *)stg, 0), (lds_cptr)L::row_tile((bf16_t *)stg, 1), ln, kb, lo, hi, on, act, sl2, slack);
         else
-          fwd_tile<D, CB, true>(st, q, L::row_tile((bf16_t *)stg, 0), L::row_tile((bf16_t *)stg, 1), kb, lo, hi, on, act, sl2, slack);
+          fwd_tile<D, CB, true>(st, q, (lds_cptr)L::row_tile((bf16_t *)stg, 0), (lds_cptr)L::row_tile((bf16_t *)stg, 1), ln, kb, lo, hi, on, act, sl2, slack);
       });
   float lse2[CB];
   finish<D, CB>(a, st, 2, q, lse2);

@@ -29,6 +29,66 @@ struct TileGeom {
   __device__ static inline int row_off(int row, int seg) { return slot_off(sigma(row), seg); }
 };
 
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+// Tile layout of the attention kernels in LDS.  A 32-row tile of a row-major bf16 array is kept as D/8 planes of 512
+// bytes, one per 16-byte segment of a row; a plane holds the 32 rows' segments in the slot order sigma(row) (the order
+// in which the lanes of the two 16-row matrix sub-tiles read them).  With SWZ the slot is XORed with (segment & 7):
+// the 8 threads that stage one row (8 planes, 512 bytes apart) then land in 8 different 16-byte bank groups, which
+// matters for kernels that restage tiles all the time; kernels that stage a block once and read it many times take
+// the plain form, whose transposing reads are a little faster.  (Measured per wave instruction on one CU with 8 waves:
+// row read 2.4 ns either way, transposing read 2.05 ns swizzled / 1.8 ns plain, staging write 6.1 ns swizzled /
+// 27 ns plain; padding the planes instead of swizzling slows the row reads to 3.5 ns.)
+// Operand addresses are lane part + compile-time constant: the lane part depends on the contraction step (row
+// operands) or the output-dim block (transposed operands) only through the swizzle, so a kernel keeps D/32 + D/16
+// lane offsets in registers (Lanes) and the sub-tile, the row half, the tile index and the LDS stage all move the
+// address by constants, which the LDS instructions take as immediate offsets: a tile costs no address arithmetic.
+template <int D, bool SWZ = true>
+struct PTile {
+  static constexpr int SEGS = D / 8;
+  static constexpr int PLANE_B = 512;            // bytes per plane: 32 row slots of 16 bytes
+  static constexpr int BYTES = SEGS * PLANE_B;   // bytes per 32-row tile
+  static constexpr int ITEMS = 32 * SEGS;        // 16-byte items per tile
+  __device__ static inline int slot_off(int slot, int seg) { return seg * PLANE_B + ((SWZ ? slot ^ (seg & 7) : slot) << 4); }
+  __device__ static inline int off(int row, int seg) { return slot_off(TileGeom<D>::sigma(row), seg); }
+  struct Lanes {
+    int row[D / 32];  // row operand (rows = the tile's rows), contraction step ks; sub-tile a adds a*256
+    int tr[D / 16];   // transposed operand (rows = dims 16*dt + n, contraction over rows 8*quad .. +7); rows +4 .. +7 add 256
+  };
+  __device__ static inline Lanes lanes() {
+    const int n = threadIdx.x & 15, quad = threadIdx.x >> 4 & 3;
+    Lanes l;
+#pragma unroll
+    for (int ks = 0; ks < D / 32; ++ks) l.row[ks] = slot_off(n, 4 * ks + quad);
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) l.tr[dt] = slot_off(4 * quad + (n >> 2), 2 * dt + ((n & 3) >> 1)) + (n & 1) * 8;
+    return l;
+  }
+};
+
+typedef const __attribute__((address_space(3))) unsigned char *lds_cptr;
+
+// A operand of sub-tile a, contraction step ks (row = key, see tile_key_row) from the tile at `tile` (uniform address).
+template <int D, bool SWZ>
+__device__ inline bf16x8 p_row_operand(lds_cptr tile, const typename PTile<D, SWZ>::Lanes &l, int a, int ks) {
+  return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8 *>(tile + l.row[ks] + a * 256);
+}
+
+// Transposed A operand (row = dim 16*dt + n, contraction over the tile's rows 8*quad .. +7), taken from the same
+// row-major tile with the transposing LDS read of gfx950 (ds_read_b64_tr_b16): inside a 16-lane group lane p hands in
+// the address of 4 consecutive elements and lane i receives element (i & 3) of lanes (i >> 2), 4 + (i >> 2),
+// 8 + (i >> 2), 12 + (i >> 2).  With lane p pointing at row 8*quad + (p >> 2), dims 16*dt + 4*(p & 3) .. +3, lane i
+// ends up with dim 16*dt + i of rows 8*quad .. +3; a second read covers rows +4 .. +7.
+template <int D, bool SWZ>
+__device__ inline bf16x8 p_tr_operand(lds_cptr tile, const typename PTile<D, SWZ>::Lanes &l, int dt) {
+  typedef __attribute__((address_space(3))) s16x4 *tr_ptr;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tr_ptr)(tile + l.tr[dt]));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tr_ptr)(tile + l.tr[dt] + 256));
+  typedef __attribute__((ext_vector_type(8))) short s16x8;
+  const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, both);
+}
+
 // Registers holding one tile set on its way from global memory to LDS.
 template <int D, int NROW, int NTHR = 256>
 struct TileRegs {
@@ -57,11 +117,12 @@ __device__ inline void tile_load(TileRegs<D, NROW, NTHR> &regs, const TileSrc<NR
     }
 }
 
-// LDS buffer layout of one stage: NROW row-major tiles.
+// LDS buffer layout of one stage: NROW tiles in the padded layout.
 template <int D, int NROW>
 struct StageLayout {
-  static constexpr int ELEMS = NROW * TileGeom<D>::ROW_ELEMS;
-  __device__ static inline bf16_t *row_tile(bf16_t *stage, int x) { return stage + x * TileGeom<D>::ROW_ELEMS; }
+  static constexpr int TILE_ELEMS = PTile<D>::BYTES / 2;
+  static constexpr int ELEMS = NROW * TILE_ELEMS;
+  __device__ static inline bf16_t *row_tile(bf16_t *stage, int x) { return stage + x * TILE_ELEMS; }
 };
 
 template <int D, int NROW, int NTHR>
@@ -75,7 +136,7 @@ __device__ inline void tile_store(const TileRegs<D, NROW, NTHR> &regs, bf16_t *s
       const int it = threadIdx.x + NTHR * i;
       if (G::ROW_ITEMS % NTHR == 0 || it < G::ROW_ITEMS) {
         const int row = it / (D / 8), seg = it % (D / 8);
-        *reinterpret_cast<bf16x8 *>(L::row_tile(stage, x) + G::row_off(row, seg)) = regs.r[x][i];
+        *reinterpret_cast<bf16x8 *>((unsigned char *)L::row_tile(stage, x) + PTile<D>::off(row, seg)) = regs.r[x][i];
       }
     }
 }
@@ -93,7 +154,6 @@ __device__ inline bf16x8 lds_row_operand(const bf16_t *tile, int a, int ks) {
 // 8 + (i >> 2), 12 + (i >> 2).  With lane p pointing at row 8*quad + (p >> 2), dims 16*dt + 4*(p & 3) .. +3, lane i
 // ends up with dim 16*dt + i of rows 8*quad .. +3; a second read covers rows +4 .. +7.  No transposed copy of the
 // tile is needed, in LDS or in memory.
-typedef __attribute__((ext_vector_type(4))) short s16x4;
 template <int D>
 __device__ inline bf16x8 lds_tr_operand(const bf16_t *tile, int dt) {
   const int p = threadIdx.x & 15, quad = threadIdx.x >> 4 & 3;
@@ -196,15 +256,15 @@ __device__ inline void run_pipeline(const TileSrc<NROW> &src, bf16_t *stage0, co
     TileIter cur = iter_begin(rng_s, rng_e, nr);
     TileIter ahead = cur;  // the last tile whose loads are in flight
     tile_load<D, NROW, NTHR>(regs[0], src, cur.kb);
-    if (PF == 2) {
-      ahead = iter_next(cur, rng_s, rng_e, nr, STEP);
-      if (ahead.r < nr) tile_load<D, NROW, NTHR>(regs[PF - 1], src, ahead.kb);
-    }
-    int buf = 0, cur_r = -1;
-    auto step = [&](TileRegs<D, NROW, NTHR> &r) {
+    ahead = iter_next(cur, rng_s, rng_e, nr, STEP);
+    if (ahead.r < nr) tile_load<D, NROW, NTHR>(regs[1], src, ahead.kb);
+    int cur_r = -1;
+    // register set 0 always feeds LDS stage 0 and set 1 stage 1 (the steps alternate), so the stage address is a
+    // constant at each call site
+    auto step = [&](TileRegs<D, NROW, NTHR> &r, int buf) {
       bf16_t *st = stage0 + buf * L::ELEMS;
       tile_store<D, NROW, NTHR>(r, st);
-      // the request for the tile PF steps ahead goes out while the LDS writes drain, before the barrier waits for them
+      // the request for the tile two steps ahead goes out while the LDS writes drain, before the barrier waits for them
       if (ahead.r < nr) ahead = iter_next(ahead, rng_s, rng_e, nr, STEP);
       if (ahead.r < nr) tile_load<D, NROW, NTHR>(r, src, ahead.kb);
       __syncthreads();
@@ -214,14 +274,12 @@ __device__ inline void run_pipeline(const TileSrc<NROW> &src, bf16_t *stage0, co
       }
       tile(st, cur.kb, cur_r);
       cur = iter_next(cur, rng_s, rng_e, nr, STEP);
-      buf ^= 1;
     };
+    static_assert(PF == 2, "two register sets, two LDS stages");
     while (cur.r < nr) {
-      step(regs[0]);
-      if (PF == 2) {
-        if (!(cur.r < nr)) break;
-        step(regs[PF - 1]);
-      }
+      step(regs[0], 0);
+      if (!(cur.r < nr)) break;
+      step(regs[1], 1);
     }
   }
   __syncthreads();
