@@ -14,6 +14,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+# kernels of ssa_forward as the profiling hook names them (prep_sort_pool also runs in ssa_backward)
+FWD_KERNELS = ("prep_sort_pool", "cmp_fwd_scores_topk", "fwd_invert_selection", "slc_fwd", "win_fwd", "slc_merge_combine")
 HBM_PEAK_GBS = 8000.0
 
 
@@ -35,31 +37,48 @@ def algorithmic_flops(wl, blk_arrays, idx):
 
 # bench.py kernel name -> kernel name prefix in the rocprofv3 summaries
 ROCPROF_NAME = {
-    "cmp_fwd_scores_topk": "m_cmp_fwd<", "slc_fwd": "m_slc_fwd<", "win_fwd": "m_win_fwd<",
-    "bwd_dq_cmp_win": "m_bwd_dq<{d}, 1, 0,", "bwd_dq_slc": "m_bwd_dq<{d}, 1, 1,",
+    "cmp_fwd_scores_topk": "m_cmp_fwd<", "slc_fwd": "m_slc_fwd_bc<", "win_fwd": "m_win_fwd<",
+    "bwd_dq_cmp_win": "m_bwd_dq<{d},", "bwd_dq_slc": "m_bwd_dq_bc<{d},",
     "bwd_dkv_win": "m_bwd_dkv<{d}, {kb}, 0,", "bwd_dkv_slc": "m_bwd_dkv<{d}, {kb}, 1,", "bwd_dkv_cmp": "m_bwd_dkv<{d}, {kb}, 2,",
 }
 
 
+def kernel_source_hash():
+    """sha256 over the library's sources (kernels and headers): a profile summary names the hash of the sources it was
+    measured on, so a figure read from it is only reported while the sources are still those."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2505_17412_amd", "csrc")
+    files = sorted(os.path.join(csrc, f) for f in os.listdir(csrc) if f.endswith((".hip", ".h")))
+    for f in files + [os.path.join(ROOT, "include", "ssa.h")]:
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
 def recorded_traffic(kernel, workload, d):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 FETCH_SIZE/WRITE_SIZE summary of this workload
-    (scaled columns, MiB), or None when no summary covers it."""
+    (scaled columns, MiB) with the summary it came from, or (None, None) when no summary covers the kernel or the
+    summary was measured on other sources than the ones in the tree."""
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}_fwd_bwd.md")
     pat = ROCPROF_NAME.get(kernel)
     if pat is None or not os.path.exists(path):
-        return None
+        return None, None
     pat = pat.format(d=d, kb=1 if d >= 128 else 2)
-    for line in open(path):
+    text = open(path).read()
+    src = kernel_source_hash()
+    if f"kernel sources sha256/16: {src}" not in text:
+        return None, None
+    for line in text.splitlines():
         cells = [c.strip() for c in line.strip().strip("|").split("|")]
         if len(cells) == 5 and cells[0].startswith(pat):
-            return int((float(cells[3]) + float(cells[4])) * 1024 * 1024)
-    return None
+            return int((float(cells[3]) + float(cells[4])) * 1024 * 1024), {"summary": os.path.relpath(path, ROOT), "kernel_sources": src}
+    return None, None
 
 
 def _imports():
     import torch
-    from paper_2505_17412_amd import inputs, ssa
-    from tests import util
+    from paper_2505_17412_amd import harness as util, inputs, ssa
     return torch, inputs, ssa, util
 
 
@@ -112,12 +131,11 @@ def dense_sweep(args):
     """One JSON line per sweep point: per-kernel HIP-event times of the sparse configuration (m = 4/8/8, top-k 16)
     and of the dense stand-in (m_win = grid, top-k 1: the window kernels then visit every (query, key) pair)."""
     import torch
-    from paper_2505_17412_amd import inputs, ssa
-    from tests import util
+    from paper_2505_17412_amd import harness as util, inputs, ssa
 
     torch.cuda.set_device(0)
 
-    fwd_names = ("prep_sort_pool", "cmp_fwd_scores_topk", "slc_fwd", "win_fwd", "combine")
+    fwd_names = FWD_KERNELS
     for grid, f, w in SWEEP_POINTS:
         sparse = inputs.make_workload("g128", grid=grid, f=f, w=w)
         dense = inputs.make_workload("g128", grid=grid, f=f, w=w, m=(4, 8, grid), topk=1)
@@ -126,7 +144,7 @@ def dense_sweep(args):
         kd, d_arrays, d_sel = kernel_times(dense, 2 if n > 50000 else 3)
         dense_pairs = algorithmic_flops(dense, d_arrays, d_sel)
         # prep_sort_pool runs once in forward and once in backward; its average is booked on both sides
-        s_fwd = sum(ks[nm] for nm in fwd_names) + ks.get("slc_token_order", 0.0)  # runs in forward and in backward
+        s_fwd = sum(ks.get(nm, 0.0) for nm in fwd_names)
         s_bwd = sum(v_ for nm, v_ in ks.items() if nm not in fwd_names) + ks["prep_sort_pool"]
         d_fwd = kd["win_fwd"]
         d_bwd = dense_dq_ms(kd, dense_pairs) + kd["bwd_dkv_win"] + kd["bwd_pre_delta"]
@@ -139,7 +157,7 @@ def dense_sweep(args):
         print(json.dumps(line), flush=True)
 
 
-FWD_KERNELS = ("prep_sort_pool", "cmp_fwd_scores_topk", "slc_fwd", "win_fwd", "combine")
+
 
 
 def seq1d_bench(args):
@@ -157,7 +175,7 @@ def seq1d_bench(args):
         dense_pairs = algorithmic_flops(dense, d_arrays, d_sel)
         pairs = algorithmic_flops(sparse, arrays, sel)
         total_pairs = pairs["cmp"] + pairs["slc"] + pairs["win"]
-        s_fwd = sum(ks[nm] for nm in FWD_KERNELS) + ks.get("slc_token_order", 0.0)  # runs in forward and in backward
+        s_fwd = sum(ks.get(nm, 0.0) for nm in FWD_KERNELS)
         s_bwd = sum(v_ for nm, v_ in ks.items() if nm not in FWD_KERNELS) + ks["prep_sort_pool"]
         d_fwd = kd["win_fwd"]
         d_bwd = dense_dq_ms(kd, dense_pairs) + kd["bwd_dkv_win"] + kd["bwd_pre_delta"]
@@ -180,8 +198,7 @@ def cmp_module_bench(args):
     training step (two modules forward, attention with their block-level tokens, everything backward)."""
     import numpy as np
     import torch
-    from paper_2505_17412_amd import inputs, ssa
-    from tests import util
+    from paper_2505_17412_amd import harness as util, inputs, ssa
 
     torch.cuda.set_device(0)
     wl = inputs.make_workload(args.workload)
@@ -351,8 +368,7 @@ def layer_bench(args):
     hidden dimension = Hq * d) forward + backward at the benchmark workload, timed as a whole with events on the
     stream, plus the per-part totals from the library's profiling hook."""
     import torch
-    from paper_2505_17412_amd import inputs, ssa
-    from tests import util
+    from paper_2505_17412_amd import harness as util, inputs, ssa
 
     torch.cuda.set_device(0)
     wl = inputs.make_workload(args.workload, with_tensors=False)
@@ -426,10 +442,11 @@ def ablation_sweep(args):
             f_c = pairs["cmp"] / max(pairs["cmp"] + pairs["win"], 1)
             branch_ms = {
                 "cmp": ks["cmp_fwd_scores_topk"] + dq_cw * f_c + ks["bwd_dkv_cmp"],
-                "slc": ks["slc_fwd"] + ks["bwd_dq_slc"] + ks["bwd_dkv_slc"] + ks["bwd_invert_selection"] + 2 * ks.get("slc_token_order", 0.0),
+                "slc": ks["slc_fwd"] + ks["fwd_invert_selection"] + ks["slc_merge_combine"] + ks["bwd_dq_slc"] + ks["bwd_dq_merge"]
+                       + ks["bwd_dkv_slc"] + ks["bwd_invert_selection"],
                 "win": ks["win_fwd"] + dq_cw * (1 - f_c) + ks["bwd_dkv_win"],
             }
-            other = sum(ks.values()) + ks["prep_sort_pool"] + ks.get("slc_token_order", 0.0) - sum(branch_ms.values())
+            other = sum(ks.values()) + ks["prep_sort_pool"] - sum(branch_ms.values())
             total = sum(branch_ms.values()) + other
             tf = {b: 14 * d * pairs[b] / (branch_ms[b] * 1e-3) / 1e12 for b in branch_ms}
             line = {"bench": "stress_ablation", "workload": "g128_thick", "n_tokens": n, "head_dim": d,
@@ -443,12 +460,178 @@ def ablation_sweep(args):
             print(json.dumps(line), flush=True)
 
 
+# workloads that run the forward pass only (the configuration says so)
+FORWARD_ONLY = ("g64",)
+
+
+def load_workload(name, heads=None):
+    from paper_2505_17412_amd import inputs
+    if name == "batch4":
+        return inputs.make_batch_workload()
+    over = {}
+    if heads:
+        h = [int(t) for t in heads.split(",")]
+        over = dict(hq=h[0], hkv=h[1], d=h[2])
+    return inputs.make_workload(name, **over)
+
+
+def bench_workload(name, args, steps, warmup, cpu_seconds):
+    """The benchmark line of one workload: whole-step time, per-kernel HIP-event times, roofline position of the
+    dominant kernel and the oracle timed on a bounded query sample."""
+    import numpy as np
+    import torch
+    from paper_2505_17412_amd import harness as util, ssa
+
+    wl = load_workload(name, args.heads)
+    bwd = name not in FORWARD_ONLY
+    n, hq, hkv, d, T = wl.n_tokens, wl.n_heads_q, wl.n_heads_kv, wl.head_dim, wl.topk
+    torch.cuda.set_device(0)
+    p, blk = util.build_blocks_gpu(wl)
+    t0 = time.perf_counter()
+    for _ in range(3):
+        util.build_blocks_gpu(wl)[1].destroy()
+    torch.cuda.synchronize()
+    build_ms = (time.perf_counter() - t0) / 3 * 1e3
+
+    q, k, v, g, do = (util.to_dev(a, wl.dtype) for a in (wl.q, wl.k, wl.v, wl.gates, wl.dout))
+    out = torch.empty_like(q)
+    ob = torch.empty((3,) + tuple(q.shape), dtype=q.dtype, device="cuda")
+    lse = torch.empty((3, n, hq), dtype=torch.float32, device="cuda")
+    idx = torch.empty((n, hkv, T), dtype=torch.int32, device="cuda")
+    dq, dk, dv, dg = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v), torch.empty_like(g)
+    wsf = torch.empty(ssa.ssa_workspace_bytes(p, blk, False), dtype=torch.uint8, device="cuda")
+    wsb = torch.empty(ssa.ssa_workspace_bytes(p, blk, True) if bwd else 16, dtype=torch.uint8, device="cuda")
+
+    def fwd():
+        ssa.ssa_forward(p, blk, q, k, v, g, out, lse, idx, ob, wsf)
+
+    def bwd_pass():
+        ssa.ssa_backward(p, blk, q, k, v, g, ob, lse, idx, do, dq, dk, dv, dg, wsb)
+
+    def step():
+        fwd()
+        if bwd:
+            bwd_pass()
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / steps * 1e3
+
+    # forward / backward split (separate loops, HIP events on the launch stream)
+    def timed(fn, reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    reps = max(3, steps // 2)
+    fwd_ms = timed(fwd, reps)
+    bwd_ms = timed(bwd_pass, reps) if bwd else None
+
+    # per-kernel durations over the same steps, HIP events recorded by the library on the launch stream
+    ssa.ssa_profile_enable(True)
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    prof = ssa.ssa_profile_get()
+    ssa.ssa_profile_enable(False)
+    kern_ms = {nm: tot / cnt for nm, (tot, cnt) in prof.items()}
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)  # 1 GiB read + 1 GiB written
+        torch.cuda.synchronize()
+        del src, dst
+
+    arrays = {nm: blk.export(nm).cpu().numpy() for nm in ("perm", "tok_win", "win_start", "cmp_batch", "slc_start")}
+    pairs = algorithmic_flops(wl, arrays, idx.cpu().numpy())
+    all_pairs = pairs["cmp"] + pairs["slc"] + pairs["win"]
+    # algorithmic FLOPs per kernel: forward 2 contractions (4d per pair); backward 5 (10d): S, dP, dQ booked on the
+    # dQ kernel (6d), dV, dK on the dK/dV kernels (4d); recomputed scores are not counted
+    kflops = {
+        "cmp_fwd_scores_topk": 4 * d * pairs["cmp"], "slc_fwd": 4 * d * pairs["slc"], "win_fwd": 4 * d * pairs["win"],
+        "bwd_dq_cmp_win": 6 * d * (pairs["cmp"] + pairs["win"]), "bwd_dq_slc": 6 * d * pairs["slc"], "bwd_dkv_cmp": 4 * d * pairs["cmp"], "bwd_dkv_slc": 4 * d * pairs["slc"],
+        "bwd_dkv_win": 4 * d * pairs["win"], "generic_path": (14 if bwd else 4) * d * all_pairs,
+    }
+    dom = max(kern_ms, key=kern_ms.get) if kern_ms else None
+    roofline = None
+    if dom is not None and dom in kflops:
+        ach = kflops[dom] / (kern_ms[dom] * 1e-3) / 1e12
+        traffic, source = recorded_traffic(dom, name, d)
+        roofline = {"bound": "mfma", "kernel": dom, "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4),
+                    "traffic": traffic, "traffic_source": source, "kernel_ms": round(kern_ms[dom], 4)}
+    total_flops = (14 if bwd else 4) * d * all_pairs
+    # HBM-bound helper: gather + mean pool of K and V, priced at its algorithmic bytes (K, V read once, pooled rows
+    # written once); the sorted copies the kernel also writes are this design's own extra traffic
+    n_cmp = blk.counts()[0]
+    prep_bytes = 2 * (n + n_cmp) * hkv * d * 2
+    prep_gbps = round(prep_bytes / (kern_ms["prep_sort_pool"] * 1e-3) / 1e9, 1) if kern_ms.get("prep_sort_pool") else None
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import ssa_oracle
+        from oracle.ssa_oracle import oracle_for
+        orc = oracle_for(wl)
+
+        def oracle_step(sub):
+            f = orc.forward(wl.q, wl.k, wl.v, wl.gates, queries=sub)
+            if bwd:
+                orc.backward(wl.q, wl.k, wl.v, wl.gates, wl.dout, f.topk_idx, out_branch=f.out_branch, queries=sub)
+
+        probe = np.arange(0, n, max(1, n // 256), dtype=np.int32)[:256]
+        oracle_step(probe[:32])  # first call pays library load and thread start-up
+        t0 = time.perf_counter()
+        oracle_step(probe)
+        per_q = (time.perf_counter() - t0) / len(probe)
+        ns = int(min(n, max(64, cpu_seconds / max(per_q, 1e-9))))
+        sub = np.arange(0, n, max(1, n // ns), dtype=np.int32)[:ns]
+        t0 = time.perf_counter()
+        oracle_step(sub)
+        dt = time.perf_counter() - t0
+        what = "fwd+bwd" if bwd else "fwd"
+        cpu = {"value": round(len(sub) / dt, 2), "unit": "tokens/s", "cores": ssa_oracle.n_threads(), "kind": "oracle",
+               "sample": f"{what} of {len(sub)} evenly spaced query tokens of the same {n}-token workload, {dt:.1f} s wall",
+               "seconds": round(dt, 2)}
+
+    passes = "fwd+bwd" if bwd else "fwd"
+    shape = (f"{wl.n_batch} union-of-primitives shells" if wl.n_batch > 1 else "union-of-primitives shell")
+    line = {
+        "metric": f"SSA {passes} tokens/sec", "value": round(n / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {shape} on a {wl.grid}^3 grid, N={n} tokens, Hq={hq}, "
+                               f"Hkv={hkv}, d={d}, m_cmp/m_slc/m_win={wl.m_cmp}/{wl.m_slc}/{wl.m_win}, top-k={T}, {passes}",
+                   "n_tokens": n, "n_batch": wl.n_batch, "blocks_cmp_slc_win": list(blk.counts())},
+        "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4) if bwd else None, "build_blocks_ms": round(build_ms, 3),
+        "tokens_per_s_incl_build_blocks": round(n / ((ms + build_ms) * 1e-3), 1),
+        "prep_sort_pool_algorithmic_gbps": prep_gbps,
+        "algorithmic_tflop_per_step": round(total_flops / 1e12, 4),
+        "pairs_cmp_slc_win": [pairs["cmp"], pairs["slc"], pairs["win"]],
+        "mfma_frac_whole_step": round(total_flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+        "kernel_ms": {k_: round(v_, 4) for k_, v_ in kern_ms.items()},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    blk.destroy()
+    return line
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="g128")
+    ap.add_argument("--workload", default="g128", help="tiny | g64 (forward only) | g128 | batch4 | g128_thick")
+    ap.add_argument("--all-configs", action="store_true", help="one benchmark line for each of the five workload configurations")
     ap.add_argument("--heads", default=None, help="HQ,HKV,D: another head shape on the same tokens (context figures; the default is the benchmark configuration)")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="target CPU time of the oracle baseline leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -490,143 +673,14 @@ def main():
         gate_bench(args)
         return
 
-    import numpy as np
-    import torch
-    from paper_2505_17412_amd import inputs, ssa
-    from tests import util
-
-    over = {}
-    if args.heads:
-        h = [int(t) for t in args.heads.split(",")]
-        over = dict(hq=h[0], hkv=h[1], d=h[2])
-    wl = inputs.make_workload(args.workload, **over)
-    n, hq, hkv, d, T = wl.n_tokens, wl.n_heads_q, wl.n_heads_kv, wl.head_dim, wl.topk
-    torch.cuda.set_device(0)
-    p, blk = util.build_blocks_gpu(wl)
-    t0 = time.perf_counter()
-    for _ in range(3):
-        util.build_blocks_gpu(wl)[1].destroy()
-    torch.cuda.synchronize()
-    build_ms = (time.perf_counter() - t0) / 3 * 1e3
-
-    q, k, v, g, do = (util.to_dev(a, wl.dtype) for a in (wl.q, wl.k, wl.v, wl.gates, wl.dout))
-    out = torch.empty_like(q)
-    ob = torch.empty((3,) + tuple(q.shape), dtype=q.dtype, device="cuda")
-    lse = torch.empty((3, n, hq), dtype=torch.float32, device="cuda")
-    idx = torch.empty((n, hkv, T), dtype=torch.int32, device="cuda")
-    dq, dk, dv, dg = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v), torch.empty_like(g)
-    wsf = torch.empty(ssa.ssa_workspace_bytes(p, blk, False), dtype=torch.uint8, device="cuda")
-    wsb = torch.empty(ssa.ssa_workspace_bytes(p, blk, True), dtype=torch.uint8, device="cuda")
-
-    def step():
-        ssa.ssa_forward(p, blk, q, k, v, g, out, lse, idx, ob, wsf)
-        ssa.ssa_backward(p, blk, q, k, v, g, ob, lse, idx, do, dq, dk, dv, dg, wsb)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) / args.steps * 1e3
-
-    # forward / backward split (separate loops, HIP events on the launch stream)
-    def timed(fn, reps):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / reps
-
-    reps = max(3, args.steps // 2)
-    fwd_ms = timed(lambda: ssa.ssa_forward(p, blk, q, k, v, g, out, lse, idx, ob, wsf), reps)
-    bwd_ms = timed(lambda: ssa.ssa_backward(p, blk, q, k, v, g, ob, lse, idx, do, dq, dk, dv, dg, wsb), reps)
-
-    # per-kernel durations over the same steps, HIP events recorded by the library on the launch stream
-    ssa.ssa_profile_enable(True)
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    prof = ssa.ssa_profile_get()
-    ssa.ssa_profile_enable(False)
-    kern_ms = {nm: tot / cnt for nm, (tot, cnt) in prof.items()}
-
-    if args.calibrate_copy:
-        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
-        dst = torch.empty_like(src)
-        dst.copy_(src)  # 1 GiB read + 1 GiB written
-        torch.cuda.synchronize()
-        del src, dst
-
-    arrays = {nm: blk.export(nm).cpu().numpy() for nm in ("perm", "tok_win", "win_start", "cmp_batch", "slc_start")}
-    pairs = algorithmic_flops(wl, arrays, idx.cpu().numpy())
-    all_pairs = pairs["cmp"] + pairs["slc"] + pairs["win"]
-    # algorithmic FLOPs per kernel: forward 2 contractions (4d per pair); backward 5 (10d): S, dP, dQ booked on the
-    # dQ kernel (6d), dV, dK on the dK/dV kernels (4d)
-    kflops = {
-        "cmp_fwd_scores_topk": 4 * d * pairs["cmp"], "slc_fwd": 4 * d * pairs["slc"], "win_fwd": 4 * d * pairs["win"],
-        "bwd_dq_cmp_win": 6 * d * (pairs["cmp"] + pairs["win"]), "bwd_dq_slc": 6 * d * pairs["slc"], "bwd_dkv_cmp": 4 * d * pairs["cmp"], "bwd_dkv_slc": 4 * d * pairs["slc"],
-        "bwd_dkv_win": 4 * d * pairs["win"], "generic_path": 10 * d * all_pairs,
-    }
-    dom = max(kern_ms, key=kern_ms.get) if kern_ms else None
-    roofline = None
-    if dom is not None and dom in kflops:
-        ach = kflops[dom] / (kern_ms[dom] * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "kernel": dom, "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
-                    "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4),
-                    "traffic": recorded_traffic(dom, args.workload, d),
-                    "kernel_ms": round(kern_ms[dom], 4)}
-    total_flops = 14 * d * all_pairs
-    # HBM-bound helper: gather + mean pool of K and V, priced at its algorithmic bytes (K, V read once, pooled rows
-    # written once); the sorted and transposed copies the kernel also writes are this design's own extra traffic
-    n_cmp = blk.counts()[0]
-    prep_bytes = 2 * (n + n_cmp) * hkv * d * 2
-    prep_gbps = round(prep_bytes / (kern_ms["prep_sort_pool"] * 1e-3) / 1e9, 1) if kern_ms.get("prep_sort_pool") else None
-
-    cpu = None
-    if not args.no_cpu_baseline:
-        from oracle import ssa_oracle
-        from oracle.ssa_oracle import oracle_for
-        orc = oracle_for(wl)
-        I = idx.cpu().numpy()
-
-        def oracle_step(sub):
-            f = orc.forward(wl.q, wl.k, wl.v, wl.gates, queries=sub)
-            orc.backward(wl.q, wl.k, wl.v, wl.gates, wl.dout, f.topk_idx, out_branch=f.out_branch, queries=sub)
-
-        probe = np.arange(0, n, max(1, n // 256), dtype=np.int32)[:256]
-        oracle_step(probe[:32])  # first call pays library load and thread start-up
-        t0 = time.perf_counter()
-        oracle_step(probe)
-        per_q = (time.perf_counter() - t0) / len(probe)
-        ns = int(min(n, max(64, args.cpu_seconds / max(per_q, 1e-9))))
-        sub = np.arange(0, n, max(1, n // ns), dtype=np.int32)[:ns]
-        t0 = time.perf_counter()
-        oracle_step(sub)
-        dt = time.perf_counter() - t0
-        cpu = {"value": round(len(sub) / dt, 2), "unit": "tokens/s", "cores": ssa_oracle.n_threads(), "kind": "oracle",
-               "sample": f"fwd+bwd of {len(sub)} evenly spaced query tokens of the same {n}-token workload, {dt:.1f} s wall",
-               "seconds": round(dt, 2)}
-
-    line = {
-        "metric": "SSA fwd+bwd tokens/sec", "value": round(n / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
-        "config": {"workload": f"{wl.name}: union-of-primitives shell on a {wl.grid}^3 grid, N={n} tokens, Hq={hq}, "
-                               f"Hkv={hkv}, d={d}, m_cmp/m_slc/m_win={wl.m_cmp}/{wl.m_slc}/{wl.m_win}, top-k={T}, fwd+bwd",
-                   "n_tokens": n, "blocks_cmp_slc_win": list(blk.counts())},
-        "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4), "build_blocks_ms": round(build_ms, 3),
-        "tokens_per_s_incl_build_blocks": round(n / ((ms + build_ms) * 1e-3), 1),
-        "prep_sort_pool_algorithmic_gbps": prep_gbps,
-        "algorithmic_tflop_per_step": round(total_flops / 1e12, 4),
-        "mfma_frac_whole_step": round(total_flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-        "kernel_ms": {k_: round(v_, 4) for k_, v_ in kern_ms.items()},
-        "roofline": roofline, "cpu_baseline": cpu,
-    }
-    print(json.dumps(line), flush=True)
+    if args.all_configs:
+        # the five workload configurations, one JSON line each (forward only where the configuration says so); fewer
+        # timed steps and a smaller oracle sample than the default line so the whole table stays within minutes
+        for name in ("tiny", "g64", "g128", "batch4", "g128_thick"):
+            steps = args.steps if name in ("tiny", "g64", "g128") else max(3, args.steps // 4)
+            print(json.dumps(bench_workload(name, args, steps, max(2, args.warmup // 2), args.cpu_seconds / 4)), flush=True)
+        return
+    print(json.dumps(bench_workload(args.workload, args, args.steps, args.warmup, args.cpu_seconds)), flush=True)
 
 
 if __name__ == "__main__":

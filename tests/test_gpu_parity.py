@@ -163,11 +163,11 @@ def test_batch_of_four_shapes_sampled():
     full_parity(wl, backward=True, queries=np.arange(11, wl.n_tokens, 389, dtype=np.int32))
 
 
-@pytest.mark.parametrize("topk,m_win", [(16, 8), (32, 4)])
+@pytest.mark.parametrize("topk,m_win", [(8, 4), (8, 8), (16, 4), (16, 8), (32, 4), (32, 8)])
 def test_g128_thick_d128_sampled(topk, m_win):
-    """Stress config: thick shell (~150k tokens), head_dim 128, top-k and window size varied."""
+    """Stress config: thick shell (~150k tokens), head_dim 128, every point of the top-k x window sweep."""
     wl = inputs.make_workload("g128_thick", topk=topk, m=(4, 8, m_win))
-    full_parity(wl, backward=True, queries=np.arange(3, wl.n_tokens, 613, dtype=np.int32))
+    full_parity(wl, backward=True, queries=np.arange(3 + topk + m_win, wl.n_tokens, 613, dtype=np.int32))
 
 
 def test_forward_backward_are_deterministic():
