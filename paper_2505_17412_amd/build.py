@@ -13,7 +13,7 @@ LIB = os.path.join(HERE, "lib", "libssa_hip.so")
 
 SOURCES = ["ssa_api.hip", "build_blocks.hip", "generic_kernels.hip", "mfma_path.hip", "mfma_fwd.hip", "mfma_bwd.hip", "cmp_module.hip", "gate.hip", "linear.hip", "layer.hip", "sel_index.hip", "profile.hip"]
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-result",
     "-fno-honor-nans", "-mno-amdgpu-ieee",  # no NaN is ever produced on purpose; saves the canonicalising v_max

@@ -1,8 +1,9 @@
-// Generic SSA path: fp32 arithmetic on the vector ALUs, one wavefront per (token, query head).
+// Generic SSA path: fp32 arithmetic on the vector ALUs, one wavefront per (token, query head) or per key row.
 // Serves SSA_F32 problems and every shape the bf16 MFMA kernels do not cover.  Same mathematics as the MFMA
 // path (paper eq. (2)-(6), Algorithm 1, window paragraph), written for clarity, not speed.
 #include "ssa_internal.h"
 #include "topk_device.h"
+#include "mfma_launch.h"
 
 namespace {
 
@@ -47,8 +48,10 @@ __global__ void g_sort_pool(const T *__restrict__ K, const T *__restrict__ V, Bl
       sk += kk;
       sv += vv;
     }
-    Kc[(size_t)c * row + i] = sk * inv;
-    Vc[(size_t)c * row + i] = sv * inv;
+    // rounded to the element type: a bf16 problem sees the same pooled rows here as in the matrix-core kernels, whose
+    // forward may have produced the lse this path's backward is given
+    Kc[(size_t)c * row + i] = io<T>::round(sk * inv);
+    Vc[(size_t)c * row + i] = io<T>::round(sv * inv);
   }
 }
 
@@ -204,14 +207,13 @@ struct BwdRow {
   float dq0, dq1;
 };
 
-__device__ inline void attend_range_bwd(BwdRow &r, const float *qs /*unscaled*/, const float *gb, float *ps, float *dss,
-                                        float lse, float delta, float scale, const float *__restrict__ Kb,
-                                        const float *__restrict__ Vb, float *__restrict__ dKb, float *__restrict__ dVb,
-                                        int kb, int ke, int Hkv, int g, int d) {
+__device__ inline void attend_range_bwd(BwdRow &r, const float *qs /*unscaled*/, const float *gb, float *dss, float lse,
+                                        float delta, float scale, const float *__restrict__ Kb,
+                                        const float *__restrict__ Vb, int kb, int ke, int Hkv, int g, int d) {
   const int lane = threadIdx.x;
   for (int k0 = kb; k0 < ke; k0 += WAVE) {
     const int key = k0 + lane;
-    float p = 0.f, ds = 0.f;
+    float ds = 0.f;
     if (key < ke) {
       const float *kr = Kb + ((size_t)key * Hkv + g) * d;
       const float *vr = Vb + ((size_t)key * Hkv + g) * d;
@@ -220,41 +222,29 @@ __device__ inline void attend_range_bwd(BwdRow &r, const float *qs /*unscaled*/,
         s += qs[i] * kr[i];
         dp += gb[i] * vr[i];
       }
-      p = __expf(s * scale - lse);
-      ds = p * (dp - delta) * scale;
+      ds = __expf(s * scale - lse) * (dp - delta) * scale;
     }
-    ps[lane] = p;
     dss[lane] = ds;
     __syncthreads();
     const int n = min(WAVE, ke - k0);
     for (int kk = 0; kk < n; ++kk) {
       const size_t row = ((size_t)(k0 + kk) * Hkv + g) * d;
-      const float pv = ps[kk], dv = dss[kk];
-      if (lane < d) {
-        atomicAdd(dVb + row + lane, pv * gb[lane]);
-        atomicAdd(dKb + row + lane, dv * qs[lane]);
-        r.dq0 += dv * Kb[row + lane];
-      }
-      if (lane + WAVE < d) {
-        atomicAdd(dVb + row + lane + WAVE, pv * gb[lane + WAVE]);
-        atomicAdd(dKb + row + lane + WAVE, dv * qs[lane + WAVE]);
-        r.dq1 += dv * Kb[row + lane + WAVE];
-      }
+      const float dv = dss[kk];
+      if (lane < d) r.dq0 += dv * Kb[row + lane];
+      if (lane + WAVE < d) r.dq1 += dv * Kb[row + lane + WAVE];
     }
     __syncthreads();
   }
 }
 
-// Softmax-attention gradient of all three branches for one (sorted position, head); dK/dV go to fp32
-// accumulators in sorted order (token-level) and per compression block.
+// dQ of all three branches for one (sorted position, head): query-centric, the keys of each branch in turn.
 template <typename T>
-__global__ void g_attn_bwd(const T *__restrict__ Q, const T *__restrict__ dO, const T *__restrict__ gates, BlkView bv,
-                           const int32_t *__restrict__ idx, int N, int Hq, int Hkv, int d, int Tk, float scale,
-                           const float *__restrict__ Ks, const float *__restrict__ Vs, const float *__restrict__ Kc,
-                           const float *__restrict__ Vc, const float *__restrict__ lse, const float *__restrict__ delta,
-                           float *__restrict__ dKs, float *__restrict__ dVs, float *__restrict__ dKc,
-                           float *__restrict__ dVc, T *__restrict__ dQ) {
-  __shared__ float qs[128], go[128], gb[128], ps[WAVE], dss[WAVE];
+__global__ void g_attn_bwd_dq(const T *__restrict__ Q, const T *__restrict__ dO, const T *__restrict__ gates, BlkView bv,
+                              const int32_t *__restrict__ idx, int N, int Hq, int Hkv, int d, int Tk, float scale,
+                              const float *__restrict__ Ks, const float *__restrict__ Vs, const float *__restrict__ Kc,
+                              const float *__restrict__ Vc, const float *__restrict__ lse, const float *__restrict__ delta,
+                              T *__restrict__ dQ) {
+  __shared__ float qs[128], go[128], gb[128], dss[WAVE];
   const int pos = blockIdx.x / Hq, h = blockIdx.x % Hq, hs = Hq / Hkv, g = h / hs, lane = threadIdx.x;
   const int tok = bv.perm[pos];
   const size_t th = (size_t)tok * Hq + h;
@@ -271,24 +261,97 @@ __global__ void g_attn_bwd(const T *__restrict__ Q, const T *__restrict__ dO, co
     const float l = lse[(size_t)branch * N * Hq + th], dl = delta[(size_t)branch * N * Hq + th];
     if (branch == 0) {
       const int item = bv.tok_item[pos];
-      attend_range_bwd(r, qs, gb, ps, dss, l, dl, scale, Kc, Vc, dKc, dVc, bv.cmp_batch[item], bv.cmp_batch[item + 1],
-                       Hkv, g, d);
+      attend_range_bwd(r, qs, gb, dss, l, dl, scale, Kc, Vc, bv.cmp_batch[item], bv.cmp_batch[item + 1], Hkv, g, d);
     } else if (branch == 2) {
       const int wdw = bv.tok_win[pos];
-      attend_range_bwd(r, qs, gb, ps, dss, l, dl, scale, Ks, Vs, dKs, dVs, bv.win_start[wdw], bv.win_start[wdw + 1], Hkv,
-                       g, d);
+      attend_range_bwd(r, qs, gb, dss, l, dl, scale, Ks, Vs, bv.win_start[wdw], bv.win_start[wdw + 1], Hkv, g, d);
     } else {
       const int32_t *row = idx + ((size_t)tok * Hkv + g) * Tk;
       for (int j = 0; j < Tk; ++j) {
         const int b = row[j];
         if (b < 0) break;
-        attend_range_bwd(r, qs, gb, ps, dss, l, dl, scale, Ks, Vs, dKs, dVs, bv.slc_start[b], bv.slc_start[b + 1], Hkv, g,
-                         d);
+        attend_range_bwd(r, qs, gb, dss, l, dl, scale, Ks, Vs, bv.slc_start[b], bv.slc_start[b + 1], Hkv, g, d);
       }
     }
   }
   if (lane < d) io<T>::st(dQ + th * d + lane, r.dq0);
   if (lane + WAVE < d) io<T>::st(dQ + th * d + lane + WAVE, r.dq1);
+}
+
+// dK, dV of one key row (sorted token, or compression block when `pooled`) and KV head: key-centric, so that every sum
+// runs in one fixed order and no floating-point atomic is needed (results are the same from run to run).  The queries
+// that attend the key: for a token, the tokens of its window (window branch), then the tokens whose selected sets hold
+// its selection block, in ascending sorted position (selection branch; lists from the inverse selection index); for a
+// compression block, every token of its batch item.  64 query rows (token x head of the group) at a time: each lane
+// forms its row's probability and dS, then the lanes, now standing for output dims, add the 64 contributions in order.
+template <typename T>
+__global__ void g_attn_bwd_dkv(int pooled, const T *__restrict__ Q, const T *__restrict__ dO, const T *__restrict__ gates,
+                               BlkView bv, const int32_t *__restrict__ tok_slc, const int32_t *__restrict__ item_start,
+                               const int32_t *__restrict__ sel_start, const int32_t *__restrict__ sel_list, int N, int B,
+                               int Ns, int Hq, int Hkv, int d, float scale, const float *__restrict__ Kr,
+                               const float *__restrict__ Vr, const float *__restrict__ lse,
+                               const float *__restrict__ delta, float *__restrict__ dK, float *__restrict__ dV) {
+  __shared__ float ks[128], vs[128], ps[WAVE], dss[WAVE];
+  __shared__ size_t qth[WAVE];
+  const int key = blockIdx.x, g = blockIdx.y, hs = Hq / Hkv, lane = threadIdx.x;
+  const size_t krow = ((size_t)key * Hkv + g) * d;
+  for (int i = lane; i < d; i += WAVE) {
+    ks[i] = Kr[krow + i];
+    vs[i] = Vr[krow + i];
+  }
+  __syncthreads();
+  float dk0 = 0.f, dk1 = 0.f, dv0 = 0.f, dv1 = 0.f;
+  const size_t NH = (size_t)N * Hq;
+  // queries e = 0 .. count*hs-1: token number e / hs of the list, head g*hs + e % hs
+  auto run = [&](int branch, const int32_t *list, int first, int count) {
+    for (int e0 = 0; e0 < count * hs; e0 += WAVE) {
+      const int e = e0 + lane;
+      float p = 0.f, ds = 0.f;
+      size_t th = 0;
+      if (e < count * hs) {
+        const int pos = list ? list[first + e / hs] : first + e / hs;
+        th = (size_t)bv.perm[pos] * Hq + g * hs + e % hs;
+        const float w = io<T>::ld(gates + th * 3 + branch);
+        float s = 0.f, dp = 0.f;
+        for (int i = 0; i < d; ++i) {
+          s += io<T>::ld(Q + th * d + i) * ks[i];
+          dp += io<T>::ld(dO + th * d + i) * vs[i];
+        }
+        const float pr = __expf(s * scale - lse[branch * NH + th]);
+        ds = pr * (w * dp - delta[branch * NH + th]) * scale;
+        p = pr * w;
+      }
+      ps[lane] = p;
+      dss[lane] = ds;
+      qth[lane] = th;
+      __syncthreads();
+      const int n = min(WAVE, count * hs - e0);
+      for (int kk = 0; kk < n; ++kk) {
+        const size_t row = qth[kk] * d;
+        if (lane < d) {
+          dv0 += ps[kk] * io<T>::ld(dO + row + lane);
+          dk0 += dss[kk] * io<T>::ld(Q + row + lane);
+        }
+        if (lane + WAVE < d) {
+          dv1 += ps[kk] * io<T>::ld(dO + row + lane + WAVE);
+          dk1 += dss[kk] * io<T>::ld(Q + row + lane + WAVE);
+        }
+      }
+      __syncthreads();
+    }
+  };
+  if (pooled) {
+    int item = 0;
+    while (item + 1 < B && key >= bv.cmp_batch[item + 1]) ++item;
+    run(0, nullptr, item_start[item], item_start[item + 1] - item_start[item]);
+  } else {
+    const int w = bv.tok_win[key];
+    run(2, nullptr, bv.win_start[w], bv.win_start[w + 1] - bv.win_start[w]);
+    const int sk = g * Ns + tok_slc[key];
+    run(1, sel_list, sel_start[sk], sel_start[sk + 1] - sel_start[sk]);
+  }
+  if (lane < d) { dK[krow + lane] = dk0; dV[krow + lane] = dv0; }
+  if (lane + WAVE < d) { dK[krow + lane + WAVE] = dk1; dV[krow + lane + WAVE] = dv1; }
 }
 
 // dK[tok] = dKs[pos] + dKc[cmp(pos)] / count (gradient of the mean pool), scattered back to caller order.
@@ -308,7 +371,7 @@ __global__ void g_unpool_scatter(BlkView bv, size_t N, int row, const float *__r
 }
 
 struct GenericPlan {
-  size_t ks, vs, kc, vc, ob, lse, idx, delta, dks, dvs, dkc, dvc, total;
+  size_t ks, vs, kc, vc, ob, lse, idx, delta, dks, dvs, dkc, dvc, sel, total;
 };
 
 GenericPlan plan(const ssa_ctx &c, bool bwd) {
@@ -326,6 +389,7 @@ GenericPlan plan(const ssa_ctx &c, bool bwd) {
   } else {
     p.delta = take((size_t)3 * c.N * c.Hq * 4 + 4);
     p.dks = take(kv); p.dvs = take(kv); p.dkc = take(kvc); p.dvc = take(kvc);
+    p.sel = take(sel_index_bytes(c.N, c.Hkv, c.T, c.blk->Ns));
   }
   p.total = off;
   return p;
@@ -357,11 +421,6 @@ int forward_t(const ssa_ctx &c, const void *q, const void *k, const void *v, con
   return hipGetLastError() == hipSuccess ? SSA_OK : SSA_ERR_HIP;
 }
 
-__global__ void g_zero_f32(float *p, size_t n) {
-  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = 0.f;
-}
-
 template <typename T>
 int backward_t(const ssa_ctx &c, const void *q, const void *k, const void *v, const void *gates, const void *out_branch,
                const float *lse, const int32_t *topk_idx, const void *dout, void *dq, void *dk, void *dv, void *dgates,
@@ -372,14 +431,21 @@ int backward_t(const ssa_ctx &c, const void *q, const void *k, const void *v, co
   float *delta = (float *)(ws + p.delta);
   float *dKs = (float *)(ws + p.dks), *dVs = (float *)(ws + p.dvs), *dKc = (float *)(ws + p.dkc), *dVc = (float *)(ws + p.dvc);
   const int N = c.N, row = c.Hkv * c.d;
-  // the four accumulators are contiguous in the plan; cleared by a kernel, so that a caller may capture the call in a graph
-  const size_t n_acc = (p.total - p.dks) / sizeof(float);
-  g_zero_f32<<<(unsigned)((n_acc + 255) / 256), 256, 0, c.stream>>>(dKs, n_acc);
   g_sort_pool<T><<<c.blk->Nc, 256, 0, c.stream>>>((const T *)k, (const T *)v, bv, row, Ks, Vs, Kc, Vc);
   g_bwd_pre<T><<<N * c.Hq, WAVE, 0, c.stream>>>((const T *)dout, (const T *)out_branch, (const T *)gates, (size_t)N, c.Hq, c.d,
                                                 (T *)dgates, delta);
-  g_attn_bwd<T><<<N * c.Hq, WAVE, 0, c.stream>>>((const T *)q, (const T *)dout, (const T *)gates, bv, topk_idx, N, c.Hq, c.Hkv, c.d,
-                                                 c.T, c.scale, Ks, Vs, Kc, Vc, lse, delta, dKs, dVs, dKc, dVc, (T *)dq);
+  g_attn_bwd_dq<T><<<N * c.Hq, WAVE, 0, c.stream>>>((const T *)q, (const T *)dout, (const T *)gates, bv, topk_idx, N, c.Hq, c.Hkv,
+                                                    c.d, c.T, c.scale, Ks, Vs, Kc, Vc, lse, delta, (T *)dq);
+  const SelIndex sel = sel_index_carve(ws + p.sel, N, c.Hkv, c.T, c.blk->Ns, 1024, 1024);
+  const int rc = sel_index_build(topk_idx, c.blk->perm, c.blk->slc_start, N, c.Hkv, c.T, c.blk->Ns, sel, c.stream);
+  if (rc != SSA_OK) return rc;
+  g_attn_bwd_dkv<T><<<dim3(N, c.Hkv), WAVE, 0, c.stream>>>(0, (const T *)q, (const T *)dout, (const T *)gates, bv, c.blk->tok_slc,
+                                                          c.blk->item_start, sel.start, sel.list, N, c.B, c.blk->Ns, c.Hq, c.Hkv,
+                                                          c.d, c.scale, Ks, Vs, lse, delta, dKs, dVs);
+  g_attn_bwd_dkv<T><<<dim3(c.blk->Nc, c.Hkv), WAVE, 0, c.stream>>>(1, (const T *)q, (const T *)dout, (const T *)gates, bv,
+                                                                  c.blk->tok_slc, c.blk->item_start, sel.start, sel.list, N, c.B,
+                                                                  c.blk->Ns, c.Hq, c.Hkv, c.d, c.scale, Kc, Vc, lse, delta, dKc,
+                                                                  dVc);
   const size_t total = (size_t)N * row;
   g_unpool_scatter<T><<<(unsigned)((total + 255) / 256), 256, 0, c.stream>>>(bv, (size_t)N, row, dKs, dVs, dKc, dVc, (T *)dk,
                                                                             (T *)dv);

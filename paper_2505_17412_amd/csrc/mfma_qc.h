@@ -387,47 +387,3 @@ __device__ inline void topk_wave_u32(const uint32_t *S, int n, int T, int base, 
   }
   for (int w = written + lane; w < T; w += 64) out[w] = -1;
 }
-
-// Selection branch: copy the selected-block rows I[t,g,:] of the workgroup's TW tokens into LDS (Irows), form the
-// union of their block ids in ascending order (ub) with the blocks' token ranges (us, ue), and store the union
-// size in *count.  bits: LDS scratch of ceil(Ns/32) words.  Ends with a workgroup barrier.
-__device__ inline void build_union(const MfmaView &v, const int32_t *idx, int wg_pos0, int g, int TW, int *Irows, int *ub,
-                                   int *us, int *ue, uint32_t *bits, int *count) {
-  const int T = v.T, Ns = v.Ns, lane = threadIdx.x & 63;
-  const int words = (Ns + 31) >> 5;
-  for (int i = threadIdx.x; i < TW * T; i += blockDim.x) {
-    const int pos = wg_pos0 + i / T;
-    Irows[i] = pos < v.N ? idx[((size_t)v.perm[pos] * v.Hkv + g) * T + i % T] : -1;
-  }
-  for (int i = threadIdx.x; i < words; i += blockDim.x) bits[i] = 0u;
-  __syncthreads();
-  for (int i = threadIdx.x; i < TW * T; i += blockDim.x) {
-    const int b = Irows[i];
-    if (b >= 0 && b < Ns) atomicOr(&bits[b >> 5], 1u << (b & 31));
-  }
-  __syncthreads();
-  if (threadIdx.x < 64) {  // ordered compaction of the union into (id, start, end) lists
-    int base = 0;
-    for (int w0 = 0; w0 < words; w0 += 64) {
-      uint32_t w = (w0 + lane) < words ? bits[w0 + lane] : 0u;
-      const int c = __popc(w);
-      int incl = c;
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const int o = __shfl_up(incl, off);
-        if (lane >= off) incl += o;
-      }
-      int at = base + incl - c;
-      while (w) {
-        const int b = (w0 + lane) * 32 + __ffs(w) - 1;
-        ub[at] = b; us[at] = v.slc_start[b]; ue[at] = v.slc_start[b + 1];
-        ++at;
-        w &= w - 1;
-      }
-      base += __shfl(incl, 63);
-    }
-    if (lane == 0) *count = base;
-  }
-  __syncthreads();
-}
-

@@ -64,10 +64,12 @@ template <typename T> struct io;
 template <> struct io<float> {
   __device__ static inline float ld(const float *p) { return *p; }
   __device__ static inline void st(float *p, float v) { *p = v; }
+  __device__ static inline float round(float v) { return v; }
 };
 template <> struct io<uint16_t> {
   __device__ static inline float ld(const uint16_t *p) { return bf16_to_f32(*p); }
   __device__ static inline void st(uint16_t *p, float v) { *p = f32_to_bf16(v); }
+  __device__ static inline float round(float v) { return bf16_to_f32(f32_to_bf16(v)); }
 };
 
 // ---- resolved problem description handed to the launch functions

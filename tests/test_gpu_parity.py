@@ -170,9 +170,17 @@ def test_g128_thick_d128_sampled(topk, m_win):
     full_parity(wl, backward=True, queries=np.arange(3 + topk + m_win, wl.n_tokens, 613, dtype=np.int32))
 
 
-def test_forward_backward_are_deterministic():
-    """Two runs on the same inputs give bit-identical outputs (no order-dependent float atomics in the bf16 path)."""
-    wl = inputs.make_workload("g64")
+@pytest.mark.parametrize("which", ["g64_bf16_matrix_cores", "tiny_f32_generic", "bf16_two_heads_per_kv_head"])
+def test_forward_backward_are_deterministic(which):
+    """Two runs on the same inputs give bit-identical outputs: no floating-point sum depends on scheduling, on the
+    matrix-core path (h_s = 8), on the fp32 path and on the bf16 shapes whose backward runs on the fp32-arithmetic
+    kernels (h_s = 2)."""
+    if which == "g64_bf16_matrix_cores":
+        wl = inputs.make_workload("g64")
+    elif which == "tiny_f32_generic":
+        wl = inputs.make_workload("tiny")
+    else:
+        wl = inputs.random_points_workload(44, 32, (1500, 900), 8, 4, 64, (4, 8, 8), 5, "bf16")
     a = util.run_gpu(wl, backward=True)
     b = util.run_gpu(wl, backward=True)
     for name in ("out", "lse", "topk_idx", "dq", "dk", "dv", "dgates"):
