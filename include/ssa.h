@@ -123,7 +123,14 @@ int ssa_blocks_export(const ssa_blocks_t *blocks, int which, void *dst_dev, size
 /* Free the handle and its device arrays (NULL is allowed). */
 void ssa_blocks_destroy(ssa_blocks_t *blocks);
 
-/* Bytes of device workspace ssa_forward (for_backward == 0) or ssa_backward (!= 0) needs; 0 on bad input. */
+/*
+ * Bytes of device workspace ssa_forward (for_backward == 0) or ssa_backward (!= 0) needs; 0 on bad input.
+ * How it scales (bf16 matrix-core path; N tokens, Hq/Hkv heads, head_dim d, top-k T, Ns selection blocks): both passes
+ * keep one bf16 partial result per (token, query head, selected block), N*Hq*T*d*2 bytes (2.0 GB at the benchmark
+ * shape N = 62k, Hq = 16, T = 16, d = 64; the forward adds N*Hq*T*8 bytes of softmax statistics), and the inverse of the
+ * selection: a bit matrix of Hkv*Ns*N/8 bytes plus N*Hkv*T*4 bytes of lists.  Backward adds sorted copies of q and
+ * dout (2*N*Hq*d*2 bytes), an fp32 partial dq (N*Hq*d*4 bytes) and up to about 1 GiB of per-chunk partial dk/dv sums.
+ */
 size_t ssa_workspace_bytes(const ssa_params_t *params, const ssa_blocks_t *blocks, int for_backward);
 
 /*
@@ -146,7 +153,11 @@ int ssa_forward(const ssa_params_t *params, const ssa_blocks_t *blocks, const vo
  * SSA backward: gradients of sum(dout * out) w.r.t. q, k, v, gates, with the selected index sets held
  * constant (no gradient flows through the selection scores or the top-k).  The paper states no backward;
  * this is the softmax-attention gradient of eq. (2)-(4) and of the mean pool of eq. (5).
- *   q,k,v,gates as in ssa_forward; out_branch, lse, topk_idx: what ssa_forward wrote for the same inputs
+ *   q,k,v,gates as in ssa_forward; out_branch, lse, topk_idx: what ssa_forward wrote for the same inputs.  A caller
+ *   that supplies its own topk_idx (Algorithm 1 takes I as an input) must keep ssa_forward's row format: distinct
+ *   selection-block ids of the token's own batch item, the -1 padding at the end of the row; the order of the ids does
+ *   not matter.  Rows that break this are not detected: ids out of range are ignored, duplicates and -1 in the middle
+ *   of a row give undefined gradients.
  *   dout   dev [N,Hq,d]
  *   dq     dev [N,Hq,d]   dk, dv dev [N,Hkv,d]   dgates dev [N,Hq,3]   all overwritten
  * Errors: as ssa_forward.

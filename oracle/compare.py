@@ -50,3 +50,30 @@ def check_topk(gpu_idx: np.ndarray, orc_fwd, orc, dtype: str, queries=None):
             for blk in set(av.tolist()) ^ set(ov.tolist()):
                 assert abs(sc[blk - s0] - kth) <= eps * kth, (t, g, blk, sc[blk - s0], kth)
     return differing
+
+
+def check_block_arrays(arr: dict, n_tokens: int, n_batch: int) -> None:
+    """Bounds of the index arrays a block handle exports (names of the binding's ARRAYS): every index that a kernel
+    follows without a check of its own must stay inside the array it points into.  perm / inv_perm are inverse
+    permutations of 0..N-1; the *_start arrays rise strictly from 0 to the size of what they cut (no empty block);
+    the per-item ranges rise weakly (an item may be empty); tok_win names an existing window and is constant exactly
+    on the window's own run of positions."""
+    n = n_tokens
+    perm, inv = arr["perm"].astype(np.int64), arr["inv_perm"].astype(np.int64)
+    assert perm.shape == inv.shape == (n,)
+    assert np.array_equal(np.sort(perm), np.arange(n)) and np.array_equal(inv[perm], np.arange(n))
+    for name in ("cmp_start", "slc_start", "win_start"):
+        s = arr[name].astype(np.int64)
+        assert s[0] == 0 and s[-1] == n and np.all(np.diff(s) > 0), name
+    nc, ns, nw = (len(arr[k]) - 1 for k in ("cmp_start", "slc_start", "win_start"))
+    ch = arr["slc_child_start"].astype(np.int64)
+    assert len(ch) == ns + 1 and ch[0] == 0 and ch[-1] == nc and np.all(np.diff(ch) > 0)
+    for name, total in (("cmp_batch", nc), ("slc_batch", ns)):
+        s = arr[name].astype(np.int64)
+        assert len(s) == n_batch + 1 and s[0] == 0 and s[-1] == total and np.all(np.diff(s) >= 0), name
+    tw = arr["tok_win"].astype(np.int64)
+    assert tw.shape == (n,)
+    if n:
+        assert tw.min() >= 0 and tw.max() == nw - 1
+        ws = arr["win_start"].astype(np.int64)
+        assert np.array_equal(tw, np.repeat(np.arange(nw), np.diff(ws)))

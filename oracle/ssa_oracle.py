@@ -49,7 +49,8 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        _lib = C.CDLL(build_library())
+        # SSA_ORACLE_LIB: another build of ssa_oracle.c to load instead (the sanitizer run of the pins uses it)
+        _lib = C.CDLL(os.environ.get("SSA_ORACLE_LIB") or build_library())
         _lib.ssa_oracle_threads.restype = C.c_int
     return _lib
 

@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 
 from oracle.blocks import build_blocks
+from oracle.compare import check_block_arrays
 from paper_2505_17412_amd import inputs
 from tests import util
 
@@ -21,9 +22,12 @@ def check(wl):
     expect = dict(perm=ref.perm, inv_perm=ref.inv_perm, cmp_start=ref.start["cmp"], slc_start=ref.start["slc"],
                   win_start=ref.start["win"], slc_child_start=ref.slc_child_start, cmp_batch=ref.cmp_batch,
                   slc_batch=ref.slc_batch, tok_win=ref.tok_win)
+    exported = {}
     for name in ARRS:
         got = blk.export(name).cpu().numpy()
         assert got.dtype == np.int32 and np.array_equal(got, expect[name]), name
+        exported[name] = got
+    check_block_arrays(exported, wl.n_tokens, wl.n_batch)  # every index a kernel follows stays in bounds
     blk.destroy()
 
 

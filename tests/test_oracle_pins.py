@@ -351,3 +351,28 @@ def test_block_structure_against_python_grouping(dup):
     assert b.cmp_batch[1] == b.cmp_batch[2]  # the empty item owns no block
     assert b.cmp_batch[-1] == b.n_blocks["cmp"] and b.slc_batch[-1] == b.n_blocks["slc"]
     assert np.array_equal(b.tok_win, b.ids["win"][b.perm])
+
+
+def test_block_arrays_stay_in_bounds():
+    """The bounds rule the GPU tests apply to the arrays a handle exports, applied to the oracle's own arrays (voxel
+    grids with duplicates and empty items, and sequences): a rule the reference itself broke would prove nothing."""
+    from oracle.blocks import build_blocks_1d
+    from oracle.compare import check_block_arrays
+    cases = [inputs.random_points_workload(5, 16, (90, 0, 70), 2, 1, 8, (2, 4, 8), 2),
+             inputs.random_points_workload(6, 4, (200,), 2, 1, 8, (1, 2, 4), 2, allow_duplicates=True),
+             inputs.make_workload("tiny", with_tensors=False)]
+    for wl in cases:
+        b = build_blocks(wl.coords, wl.batch_offsets, wl.grid, wl.m_cmp, wl.m_slc, wl.m_win)
+        arr = dict(perm=b.perm, inv_perm=b.inv_perm, cmp_start=b.start["cmp"], slc_start=b.start["slc"], win_start=b.start["win"],
+                   slc_child_start=b.slc_child_start, cmp_batch=b.cmp_batch, slc_batch=b.slc_batch, tok_win=b.tok_win)
+        check_block_arrays(arr, wl.n_tokens, wl.n_batch)
+    offs = np.array([0, 70, 70, 333], dtype=np.int32)
+    b = build_blocks_1d(offs, 6, 18, 25)
+    arr = dict(perm=b.perm, inv_perm=b.inv_perm, cmp_start=b.start["cmp"], slc_start=b.start["slc"], win_start=b.start["win"],
+               slc_child_start=b.slc_child_start, cmp_batch=b.cmp_batch, slc_batch=b.slc_batch, tok_win=b.tok_win)
+    check_block_arrays(arr, 333, 3)
+    bad = dict(arr)
+    bad["slc_start"] = arr["slc_start"].copy()
+    bad["slc_start"][1] = bad["slc_start"][2]          # a planted empty block must be caught
+    with pytest.raises(AssertionError):
+        check_block_arrays(bad, 333, 3)
