@@ -357,15 +357,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
       for (int t = 0; t < MAXT; ++t)
         if (t < nfull) bc_dq_tile<D, false>(acc, cur, kt + t * P::BYTES, vt + t * P::BYTES, ln, 32 * t, nk, sl2);
       if (nk & 31) bc_dq_tile<D, true>(acc, cur, kt + nfull * P::BYTES, vt + nfull * P::BYTES, ln, 32 * nfull, nk, sl2);
-      if (cur.valid) {
-#pragma unroll
-        for (int dt = 0; dt < D / 16; ++dt) {
-          bf16x4 x;
-#pragma unroll
-          for (int i = 0; i < 4; ++i) x[i] = (__bf16)acc[dt][i];
-          *reinterpret_cast<bf16x4 *>(a.pdq + (size_t)cur.prow * D + 16 * dt + 4 * quad) = x;
-        }
-      }
+      store_partial_row<D>(a.pdq + (size_t)cur.prow * D, acc, cur.valid);
       cur = nxt;
     }
   }
@@ -575,7 +567,8 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
         (const __attribute__((address_space(3))) float *)((lds_cptr)stage + SG::TILES_B) + 8 * quad;
 #pragma unroll
     for (int rt = 0; rt < ST; ++rt) {
-      if (qb + rt * slots >= qend) break;
+      // (row tiles past the end of the list are not skipped: their rows carry lse = +inf and add exact zeros, and a
+      // stage without branches lets the tiles' matrix and vector work interleave)
       const lds_cptr Qt = st0 + rt * P::BYTES, Dt = st0 + (ST + rt) * P::BYTES;
       f32x4 s[KB][2], dp[KB][2];
 #pragma unroll

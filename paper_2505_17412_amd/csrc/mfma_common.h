@@ -60,6 +60,73 @@ __device__ inline float group_sum(float v, int hs) {
   return v;
 }
 
+// Store the accumulator tile of one query column block to row-major rows of D bf16: on entry lane (n, quad) holds, for
+// every dim block dt, the 4 dims 16*dt + 4*quad .. +3 of column n (the C layout of the matrix instruction), i.e. 8 bytes
+// in each of D/16 places of its row.  A 4x4 transpose between the dim-block index and the quad index (two rounds of
+// lane-row swaps, v_permlane32_swap and v_permlane16_swap: lanes 32 and 16 apart hold the same column) leaves every
+// lane with 16 consecutive dims, so a row goes out as 32-byte pieces, four lanes covering 64 consecutive dims, instead
+// of 8-byte pieces.  `row`: this lane's row (column n); scale: factor applied before rounding; lanes with !valid take
+// part in the exchange and store nothing.  D = 64 or 128.
+template <int D>
+__device__ inline void store_row_tile_if(bf16_t *row, const f32x4 (&o)[D / 16], float scale, bool valid) {
+  static_assert(D % 64 == 0, "groups of four dim blocks");
+  const int quad = threadIdx.x >> 4 & 3;
+#pragma unroll
+  for (int h = 0; h < D / 64; ++h) {
+    unsigned lo[4], hi[4];  // packed bf16 pairs: dims (0,1) and (2,3) of the lane's 4-dim group of dim block 4*h + j
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      bf16x4 x;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) x[i] = (__bf16)(o[4 * h + j][i] * scale);
+      typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+      const u32x2 w = __builtin_bit_cast(u32x2, x);
+      lo[j] = w[0];
+      hi[j] = w[1];
+    }
+    auto swap32 = [](unsigned &a, unsigned &b) {
+      const auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
+      a = r[0]; b = r[1];
+    };
+    auto swap16 = [](unsigned &a, unsigned &b) {
+      const auto r = __builtin_amdgcn_permlane16_swap(a, b, false, false);
+      a = r[0]; b = r[1];
+    };
+    // bit 1 of the dim-block index <-> bit 1 of quad, then bit 0 <-> bit 0
+    swap32(lo[0], lo[2]); swap32(hi[0], hi[2]); swap32(lo[1], lo[3]); swap32(hi[1], hi[3]);
+    swap16(lo[0], lo[1]); swap16(hi[0], hi[1]); swap16(lo[2], lo[3]); swap16(hi[2], hi[3]);
+    // register j now holds the group that came from quad j of dim block `quad`: dims 64*h + 16*quad + 4*j .. +3
+    typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+    if (valid) {
+      u32x4 *dst = reinterpret_cast<u32x4 *>(row + 64 * h + 16 * quad);
+      // written once, read once much later by the merge kernel: streaming stores, so the rows do not push the query
+      // rows (which every selected block reads again) out of the caches
+      __builtin_nontemporal_store(u32x4{lo[0], hi[0], lo[1], hi[1]}, dst);
+      __builtin_nontemporal_store(u32x4{lo[2], hi[2], lo[3], hi[3]}, dst + 1);
+    }
+  }
+}
+
+// One row of D bf16 per query column from the accumulator tile `o` (unscaled); lanes with !valid store nothing (the
+// lanes of a column agree on valid).  Wide stores where the dim blocks come in fours, 8-byte pieces otherwise.
+template <int D>
+__device__ inline void store_partial_row(bf16_t *row, const f32x4 (&o)[D / 16], bool valid) {
+  if constexpr (D % 64 == 0) {
+    store_row_tile_if<D>(row, o, 1.0f, valid);  // the lane exchange runs with every lane on; only the stores are conditional
+  } else {
+    const int quad = threadIdx.x >> 4 & 3;
+    if (valid) {
+#pragma unroll
+      for (int dt = 0; dt < D / 16; ++dt) {
+        bf16x4 x;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[i] = (__bf16)o[dt][i];
+        *reinterpret_cast<bf16x4 *>(row + 16 * dt + 4 * quad) = x;
+      }
+    }
+  }
+}
+
 // Row of the A operand a lane feeds for sub-tile `a` of the key tile starting at kb.
 __device__ inline int tile_key_row(int kb, int a) {
   const int r = threadIdx.x & 15;

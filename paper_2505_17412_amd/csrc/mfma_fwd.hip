@@ -475,16 +475,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
         if (t < nfull) bc_fwd_tile<D, false>(st, cur.qop, kl + t * P::BYTES, vl + t * P::BYTES, ln, 32 * t, nk, sl2, slack, ones);
       if (nk & 31)
         bc_fwd_tile<D, true>(st, cur.qop, kl + nfull * P::BYTES, vl + nfull * P::BYTES, ln, 32 * nfull, nk, sl2, slack, ones);
-      if (cur.valid) {
-#pragma unroll
-        for (int dt = 0; dt < D / 16; ++dt) {
-          bf16x4 x;
-#pragma unroll
-          for (int i = 0; i < 4; ++i) x[i] = (__bf16)st.o[0][dt][i];
-          *reinterpret_cast<bf16x4 *>(a.po + (size_t)cur.prow * D + 16 * dt + 4 * quad) = x;
-        }
-        if (quad == 0) *reinterpret_cast<float2 *>(a.pml + (size_t)cur.prow * 2) = make_float2(st.m[0], st.l[0][0]);
-      }
+      // (a column past the end of the chunk points at row 0 of the partial arrays and is not stored)
+      store_partial_row<D>(a.po + (size_t)cur.prow * D, st.o[0], cur.valid);
+      if (cur.valid && quad == 0) *reinterpret_cast<float2 *>(a.pml + (size_t)cur.prow * 2) = make_float2(st.m[0], st.l[0][0]);
       cur = nxt;
     }
   }
