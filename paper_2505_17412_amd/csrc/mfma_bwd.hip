@@ -712,7 +712,8 @@ template <> struct BcDqShape<128> { static constexpr int NW = 8, KSEG = 256; };
 constexpr int KB_KEYS_MAX = 2;  // key blocks of 16 per wavefront in the dK/dV kernels (1 at head_dim 128: registers)
 // wavefronts per workgroup there (16*KB_KEYS keys each): blocks and windows hold ~130 tokens, an item's pooled keys
 // thousands, so the compression branch takes wider workgroups (fewer passes over the query rows)
-constexpr int DKV_WAVES = 4, DKV_WAVES_CMP = 4;
+template <int D> struct DkvWaves { static constexpr int N = 4; };
+template <> struct DkvWaves<128> { static constexpr int N = 8; };  // 16 keys per wavefront there: 128 keys per workgroup again
 // 32-row tiles of query rows per LDS stage (one barrier per stage)
 template <int D> struct DkvShape { static constexpr int ST = 2; };
 
@@ -762,6 +763,7 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
     m_dq_merge<<<(unsigned)((threads + 255) / 256), 256, 0, s>>>(m);
   }
   constexpr int KB_KEYS = D >= 128 ? 1 : KB_KEYS_MAX;
+  constexpr int DKV_WAVES = DkvWaves<D>::N, DKV_WAVES_CMP = DkvWaves<D>::N;
   constexpr int WG_KEYS = 16 * KB_KEYS * DKV_WAVES, WG_KEYS_CMP = 16 * KB_KEYS * DKV_WAVES_CMP;
   static_assert(WG_KEYS <= SSA_KEY_PAD && WG_KEYS_CMP <= SSA_KEY_PAD, "key tiles may read up to WG_KEYS rows past a block");
   constexpr int ST = DkvShape<D>::ST;
