@@ -437,7 +437,7 @@ int backward_t(const ssa_ctx &c, const void *q, const void *k, const void *v, co
   g_attn_bwd_dq<T><<<N * c.Hq, WAVE, 0, c.stream>>>((const T *)q, (const T *)dout, (const T *)gates, bv, topk_idx, N, c.Hq, c.Hkv,
                                                     c.d, c.T, c.scale, Ks, Vs, Kc, Vc, lse, delta, (T *)dq);
   const SelIndex sel = sel_index_carve(ws + p.sel, N, c.Hkv, c.T, c.blk->Ns, 1024, 1024);
-  const int rc = sel_index_build(topk_idx, c.blk->perm, c.blk->slc_start, N, c.Hkv, c.T, c.blk->Ns, sel, c.stream);
+  const int rc = sel_index_build(topk_idx, c.blk->perm, c.blk->slc_start, N, c.Hkv, c.T, c.blk->Ns, sel, false, c.stream);
   if (rc != SSA_OK) return rc;
   g_attn_bwd_dkv<T><<<dim3(N, c.Hkv), WAVE, 0, c.stream>>>(0, (const T *)q, (const T *)dout, (const T *)gates, bv, c.blk->tok_slc,
                                                           c.blk->item_start, sel.start, sel.list, N, c.B, c.blk->Ns, c.Hq, c.Hkv,

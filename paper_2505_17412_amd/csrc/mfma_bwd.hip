@@ -238,7 +238,7 @@ struct BcDqArgs {
   const bf16_t *Qs, *dOs;             // [N(pos)][Hq][D] sorted copies
   const float *lse2s, *deltas, *gws;  // selection branch: [N(pos)][Hq]
   const int32_t *idx;                 // [N,Hkv,T]
-  const int32_t *sel_start, *sel_list, *chunk_start;
+  const int32_t *sel_start, *sel_list, *chunk_start, *chunk_order;
   bf16_t *pdq;                        // [N(pos)][Hkv][T][hs][D]
 };
 
@@ -307,9 +307,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
   int *tl = (int *)(Vt + MAXT * P::BYTES), *sl = tl + BC_CHUNK;
   const int wid = threadIdx.x >> 6, quad = threadIdx.x >> 4 & 3;
   const int hs = a.v.hs, Hkv = a.v.Hkv, T = a.v.T, Ns = a.v.Ns;
-  const int w = bc_chunk_of_workgroup(a.chunk_start[Hkv * Ns]);
+  const int wi = bc_chunk_of_workgroup(a.chunk_start[Hkv * Ns]);
   int key, chunk;
-  if (w < 0 || !bc_find_chunk(a.chunk_start, Hkv * Ns, w, key, chunk)) return;
+  if (wi < 0 || !bc_find_chunk(a.chunk_start, Hkv * Ns, a.chunk_order[wi], key, chunk)) return;
   const int g = key / Ns, blk = key % Ns;
   const int kbeg = a.v.slc_start[blk], kend = a.v.slc_start[blk + 1];
   const int qbeg = a.sel_start[key] + chunk * BC_CHUNK, cnt = min(a.sel_start[key + 1] - qbeg, BC_CHUNK);
@@ -410,6 +410,7 @@ struct DkvArgs {
   const int32_t *sel_start, *sel_list;  // selection branch: query positions per (g, block)
   float *dK, *dV;                       // [rows][Hkv][D] fp32 (rows: sorted tokens, or compression blocks)
   const int32_t *chunk_start;           // selection branch: [Hkv*Ns+1] first work chunk of each (g, block)
+  const int32_t *chunk_order;           // selection branch: execution order of the work chunks
   const int32_t *part_row_start;        // selection branch: [Hkv*Ns+1] first row of each (g, block)'s partial sums
   int chunk_len;                        // selection branch: query tokens per work chunk
   int tiles_per_block;                  // key tiles reserved per block in the grid
@@ -450,9 +451,9 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
     // time, so the chunk's query rows are fetched into that L2 once.  Find the chunk's (g, block) by bisection over
     // the chunk prefix sums.
     const int per8 = 8 * a.tiles_per_block;
-    const int nkeys = a.v.Hkv * a.v.Ns, w = (int)(blockIdx.x / per8) * 8 + (int)(blockIdx.x % 8);
+    const int nkeys = a.v.Hkv * a.v.Ns, wi = (int)(blockIdx.x / per8) * 8 + (int)(blockIdx.x % 8);
     int key, chunk;
-    if (!bc_find_chunk(a.chunk_start, nkeys, w, key, chunk)) return;
+    if (wi >= a.chunk_start[nkeys] || !bc_find_chunk(a.chunk_start, nkeys, a.chunk_order[wi], key, chunk)) return;
     g = key / a.v.Ns; blk = key % a.v.Ns; tile = (int)(blockIdx.x % per8) / 8;
     kbeg = a.v.slc_start[blk]; kend = a.v.slc_start[blk + 1];
     qbeg = a.sel_start[key] + chunk * a.chunk_len;
@@ -745,7 +746,7 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
   }
   {
     ProfScope ps(PROF_BWD_INVERT, s);
-    const int rc = sel_index_build(idx, v.perm, v.slc_start, N, Hkv, v.T, v.Ns, w.sel, s);
+    const int rc = sel_index_build(idx, v.perm, v.slc_start, N, Hkv, v.T, v.Ns, w.sel, true, s);
     if (rc != SSA_OK) return rc;
   }
   {
@@ -753,7 +754,7 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
     const size_t entries = (size_t)N * Hkv * v.T;
     const unsigned chunks = (unsigned)(entries / BC_CHUNK + (size_t)Hkv * v.Ns);
     BcDqArgs b{v, w.Qs, w.dOs, w.lse2s + NH, w.deltas + NH, w.gws + NH, idx, w.sel.start, w.sel.list, w.sel.bc_chunk_start,
-               w.part.o};
+               w.sel.bc_order, w.part.o};
     m_bwd_dq_bc<D, BS::NW, BS::KSEG><<<dim3((chunks + 7) / 8 * 8), 64 * BS::NW, bc_dq_lds_bytes<D, BS::KSEG>(), s>>>(b);
   }
   {
@@ -775,7 +776,7 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
     (void)hipFuncSetAttribute((const void *)m_bwd_dkv<D, KB_KEYS, DKV_CMP, DKV_WAVES_CMP, ST>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
   });
   DkvArgs base{v, w.Qs, w.dOs, nullptr, nullptr, nullptr, w.sel.start, w.sel.list,
-               w.dKs, w.dVs, w.sel.chunk_start, w.sel.part_row_start, w.sel.chunk_len, 1, 1};
+               w.dKs, w.dVs, w.sel.chunk_start, w.sel.order, w.sel.part_row_start, w.sel.chunk_len, 1, 1};
   {
     ProfScope ps(PROF_BWD_DKV_WIN, s);
     DkvArgs a = base;

@@ -339,7 +339,7 @@ struct BcFwdArgs {
   MfmaView v;
   const bf16_t *Q;
   const int32_t *idx;  // [N,Hkv,T]
-  const int32_t *sel_start, *sel_list, *chunk_start;
+  const int32_t *sel_start, *sel_list, *chunk_start, *chunk_order;
   bf16_t *po;  // [N][Hkv][T][hs][D]
   float *pml;  // [N][Hkv][T][hs][2]
 };
@@ -419,9 +419,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
   int *tl = (int *)(Vt + MAXT * P::BYTES), *sl = tl + BC_CHUNK;
   const int wid = threadIdx.x >> 6, quad = threadIdx.x >> 4 & 3;
   const int hs = a.v.hs, Hkv = a.v.Hkv, T = a.v.T, Ns = a.v.Ns;
-  const int w = bc_chunk_of_workgroup(a.chunk_start[Hkv * Ns]);
+  const int wi = bc_chunk_of_workgroup(a.chunk_start[Hkv * Ns]);
   int key, chunk;
-  if (w < 0 || !bc_find_chunk(a.chunk_start, Hkv * Ns, w, key, chunk)) return;
+  if (wi < 0 || !bc_find_chunk(a.chunk_start, Hkv * Ns, a.chunk_order[wi], key, chunk)) return;
   const int g = key / Ns, blk = key % Ns;
   const int kbeg = a.v.slc_start[blk], kend = a.v.slc_start[blk + 1];
   const int qbeg = a.sel_start[key] + chunk * BC_CHUNK, cnt = min(a.sel_start[key + 1] - qbeg, BC_CHUNK);
@@ -610,7 +610,7 @@ int launch_forward(FwdArgs a, const bf16_t *gates, bf16_t *out, const SelIndex &
   }
   {
     ProfScope ps(PROF_FWD_INVERT, s);
-    const int rc = sel_index_build(a.idx, a.v.perm, a.v.slc_start, a.v.N, a.v.Hkv, a.v.T, a.v.Ns, sel, s);
+    const int rc = sel_index_build(a.idx, a.v.perm, a.v.slc_start, a.v.N, a.v.Hkv, a.v.T, a.v.Ns, sel, false, s);
     if (rc != SSA_OK) return rc;
   }
   {
@@ -618,7 +618,7 @@ int launch_forward(FwdArgs a, const bf16_t *gates, bf16_t *out, const SelIndex &
     // upper bound of the number of chunks: every list adds at most one partly filled chunk
     const size_t entries = (size_t)a.v.N * a.v.Hkv * a.v.T;
     const unsigned chunks = (unsigned)(entries / BC_CHUNK + (size_t)a.v.Hkv * a.v.Ns);
-    BcFwdArgs b{a.v, a.Q, a.idx, sel.start, sel.list, sel.bc_chunk_start, part.o, part.ml};
+    BcFwdArgs b{a.v, a.Q, a.idx, sel.start, sel.list, sel.bc_chunk_start, sel.bc_order, part.o, part.ml};
     m_slc_fwd_bc<D, BS::NW, BS::KSEG><<<dim3((chunks + 7) / 8 * 8), 64 * BS::NW, lds_bc, s>>>(b);
   }
   {

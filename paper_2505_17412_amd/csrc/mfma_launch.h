@@ -16,12 +16,13 @@ struct SelIndex {
   int32_t *start, *list;          // [Hkv*Ns+1], [N*Hkv*T]
   int32_t *chunk_start, *part_row_start;  // [Hkv*Ns+1] each: dK/dV work chunks and partial-sum rows per key
   int32_t *bc_chunk_start;        // [Hkv*Ns+1]: work chunks of the block-centric forward / dQ kernels
-  int chunk_len, bc_chunk_len;    // query tokens per chunk of either kind
+  int32_t *order, *bc_order;      // execution order of the chunks of either chunking (chunk ids; see m_chunk_order)
+  int chunk_len, bc_chunk_len;    // query tokens per chunk of either kind (at least 256)
 };
 size_t sel_index_bytes(int N, int Hkv, int T, int Ns);
 SelIndex sel_index_carve(void *ws, int N, int Hkv, int T, int Ns, int chunk_len, int bc_chunk_len);
 int sel_index_build(const int32_t *idx, const int32_t *perm, const int32_t *slc_start, int N, int Hkv, int T, int Ns,
-                    const SelIndex &x, hipStream_t s);
+                    const SelIndex &x, bool want_dkv_order, hipStream_t s);
 
 // Block-centric selection kernels: query tokens per work chunk, and the per-(token, KV head, rank) partial results.
 constexpr int BC_CHUNK = 256;

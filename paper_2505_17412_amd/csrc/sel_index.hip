@@ -130,7 +130,53 @@ __global__ __launch_bounds__(256) void m_sel_fill(const uint32_t *__restrict__ b
   }
 }
 
-struct Plan { size_t bits, counts, start, list, cstart, prow, bcstart, total; };
+// Execution order of the work chunks of one chunking: chunks sorted by (KV head, first query position of the chunk), in
+// buckets of `bucket` positions (counting sort in LDS, one workgroup).  Chunks that run at the same time then belong to
+// different blocks but to the same stretch of tokens, whose query rows they all gather: the rows are fetched into the
+// L2 once instead of once per selected block.  The order only decides WHEN a chunk runs, never what it computes, so the
+// arbitrary order inside a bucket (LDS atomics) does not touch any result.  order[i] = chunk id; total = chunk_start[n].
+constexpr int ORDER_BINS = 8192;
+__global__ __launch_bounds__(1024) void m_chunk_order(const int32_t *__restrict__ start, const int32_t *__restrict__ chunk_start,
+                                                      const int32_t *__restrict__ list, int n, int Ns, int chunk_len,
+                                                      int bucket, int bins_per_head, int32_t *__restrict__ order) {
+  __shared__ uint32_t bin[ORDER_BINS];
+  const int nbins = (n / Ns) * bins_per_head;
+  for (int i = threadIdx.x; i < nbins; i += 1024) bin[i] = 0u;
+  __syncthreads();
+  const int total = chunk_start[n];
+  // chunk w -> its key by bisection over the chunk prefix sums, then the bucket of the chunk's first query position
+  auto bin_of = [&](int w) {
+    int lo = 0, hi = n;  // chunk_start[lo] <= w < chunk_start[hi]
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (chunk_start[mid] <= w) lo = mid; else hi = mid;
+    }
+    return (lo / Ns) * bins_per_head + list[start[lo] + (w - chunk_start[lo]) * chunk_len] / bucket;
+  };
+  for (int w = threadIdx.x; w < total; w += 1024) atomicAdd(&bin[bin_of(w)], 1u);
+  __syncthreads();
+  {  // exclusive scan of the counters: every thread owns 8 consecutive bins
+    __shared__ uint32_t part[1024];
+    const int b0 = threadIdx.x * (ORDER_BINS / 1024);
+    uint32_t own = 0;
+    for (int i = 0; i < ORDER_BINS / 1024; ++i) own += b0 + i < nbins ? bin[b0 + i] : 0u;
+    part[threadIdx.x] = own;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {
+      const uint32_t v = threadIdx.x >= off ? part[threadIdx.x - off] : 0u;
+      __syncthreads();
+      part[threadIdx.x] += v;
+      __syncthreads();
+    }
+    uint32_t run = part[threadIdx.x] - own;
+    for (int i = 0; i < ORDER_BINS / 1024; ++i)
+      if (b0 + i < nbins) { const uint32_t c = bin[b0 + i]; bin[b0 + i] = run; run += c; }
+  }
+  __syncthreads();
+  for (int w = threadIdx.x; w < total; w += 1024) order[atomicAdd(&bin[bin_of(w)], 1u)] = w;
+}
+
+struct Plan { size_t bits, counts, start, list, cstart, prow, bcstart, bcorder, order, total; };
 
 Plan plan(int N, int Hkv, int T, int Ns) {
   Plan p{};
@@ -140,6 +186,8 @@ Plan plan(int N, int Hkv, int T, int Ns) {
   p.bits = take(keys * words * 4); p.counts = take(keys * 4 + 4); p.start = take((keys + 1) * 4);
   p.list = take(entries * 4);
   p.cstart = take((keys + 1) * 4); p.prow = take((keys + 1) * 4); p.bcstart = take((keys + 1) * 4);
+  // at most one partly filled chunk per key on top of the full ones (chunks of at least 256 tokens)
+  p.bcorder = take((entries / 256 + keys + 8) * 4); p.order = take((entries / 256 + keys + 8) * 4);
   p.total = off;
   return p;
 }
@@ -156,12 +204,13 @@ SelIndex sel_index_carve(void *ws_, int N, int Hkv, int T, int Ns, int chunk_len
   x.list = (int32_t *)(ws + p.list);
   x.chunk_start = (int32_t *)(ws + p.cstart); x.part_row_start = (int32_t *)(ws + p.prow);
   x.bc_chunk_start = (int32_t *)(ws + p.bcstart);
+  x.bc_order = (int32_t *)(ws + p.bcorder); x.order = (int32_t *)(ws + p.order);
   x.chunk_len = chunk_len; x.bc_chunk_len = bc_chunk_len;
   return x;
 }
 
 int sel_index_build(const int32_t *idx, const int32_t *perm, const int32_t *slc_start, int N, int Hkv, int T, int Ns,
-                    const SelIndex &x, hipStream_t s) {
+                    const SelIndex &x, bool want_dkv_order, hipStream_t s) {
   const int words = (N + 31) / 32, keys = Hkv * Ns;
   // bit matrix: tiles of up to 32 words per block row held in LDS (64 KB), or global atomics when a KV head has more
   // than 16 384 blocks
@@ -178,5 +227,12 @@ int sel_index_build(const int32_t *idx, const int32_t *perm, const int32_t *slc_
   m_scan_counts<<<1, 1024, 0, s>>>(x.counts, keys, Ns, x.chunk_len, x.bc_chunk_len, slc_start, x.start, x.chunk_start,
                                    x.part_row_start, x.bc_chunk_start);
   m_sel_fill<<<keys, 256, 0, s>>>(x.bits, words, x.start, x.list);
+  // execution orders of both chunkings; bucket width so that Hkv * ceil(N / bucket) bins fit the LDS table
+  int bucket = 64;
+  while ((long long)Hkv * ((N + bucket - 1) / bucket) > ORDER_BINS) bucket *= 2;
+  const int bph = (N + bucket - 1) / bucket;
+  m_chunk_order<<<1, 1024, 0, s>>>(x.start, x.bc_chunk_start, x.list, keys, Ns, x.bc_chunk_len, bucket, bph, x.bc_order);
+  if (want_dkv_order)
+    m_chunk_order<<<1, 1024, 0, s>>>(x.start, x.chunk_start, x.list, keys, Ns, x.chunk_len, bucket, bph, x.order);
   return hipGetLastError() == hipSuccess ? SSA_OK : SSA_ERR_HIP;
 }
