@@ -418,11 +418,12 @@ struct DkvArgs {
 };
 
 // LDS stage of the dK/dV kernels: ST tiles of 32 query rows each, of Q and of dO (PTile layout: read both as they are
-// and through the transposing LDS load), and the rows' scalars (lse in log2 units, delta, gate).
+// and through the transposing LDS load), and the rows' scalars (lse in log2 units, -delta*scale, gate, gate*scale:
+// the products are formed once by the staging thread instead of by every lane of every wavefront).
 template <int D, int ST>
 struct DkvStage {
   static constexpr int TILES_B = 2 * ST * PTile<D>::BYTES;  // Q tiles, then dO tiles
-  static constexpr int BYTES = TILES_B + 3 * 32 * ST * 4;   // + [3][32*ST] floats
+  static constexpr int BYTES = TILES_B + 4 * 32 * ST * 4;   // + [4][32*ST] floats
 };
 
 // A workgroup owns 16*KB*NW keys of one block (16*KB per wavefront, held in registers as MFMA B operands with their
@@ -506,13 +507,19 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
     it_slot[i] = rt * slots + row / hs;
     it_col[i] = (g * hs + row % hs) * D + seg * 8;
   }
-  static_assert(3 * 32 * ST <= NTHR, "one scalar per thread and stage");
-  const bool has_sc = threadIdx.x < 3 * 32 * ST;
+  static_assert(4 * 32 * ST <= NTHR, "one scalar per thread and stage");
+  const bool has_sc = threadIdx.x < 4 * 32 * ST;
   const int sc_arr = threadIdx.x / (32 * ST), sc_r = threadIdx.x % (32 * ST);
   const int sc_slot = (sc_r >> 5) * slots + (sc_r & 31) / hs, sc_head = g * hs + (sc_r & 31) % hs;
   const float *sc_src = sc_arr == 0 ? a.lse2s : (sc_arr == 1 ? a.deltas : a.gws);
+  const float sc_mul = sc_arr == 1 ? -scale : (sc_arr == 3 ? scale : 1.0f);
   // sorted position of the token at list index li (-1: past the end)
-  auto position = [&](int li) { return li < qend ? (MODE == DKV_SLC ? a.sel_list[li] : li) : -1; };
+  // (every load of the staging code is unconditional, with a clamped index: loads under a branch would make the
+  // compiler wait for ALL outstanding loads at the next use instead of for the oldest ones)
+  auto position = [&](int li) {
+    const int v = MODE == DKV_SLC ? a.sel_list[min(li, qend - 1)] : li;
+    return li < qend ? v : -1;
+  };
   // Two register sets and two position sets, used alternately: while stage i is consumed, the rows of stage i+2 are
   // requested (two stages of loads in flight) with the positions read during stage i-1, and the positions of stage
   // i+3 are read.  Inside a stage the positions are requested BEFORE the rows, so that waiting for them (the next
@@ -525,7 +532,7 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
   auto load_positions = [&](int qb, StagePos &p) {
 #pragma unroll
     for (int i = 0; i < NI; ++i) p.it[i] = position(qb + it_slot[i]);
-    p.sc = has_sc ? position(qb + sc_slot) : -1;
+    p.sc = position(qb + sc_slot);
   };
   auto load_stage = [&](StageRegs &r, const StagePos &p) {
 #pragma unroll
@@ -534,7 +541,7 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
       r.rq[i] = ld8(a.Qs + off);
       r.rd[i] = ld8(a.dOs + off);
     }
-    r.sc = has_sc ? sc_src[(uint32_t)max(p.sc, 0) * Hq + sc_head] : 0.f;
+    r.sc = sc_src[(uint32_t)max(p.sc, 0) * Hq + sc_head];  // (threads past the scalars load one they never store)
     r.missing = sc_arr == 0 && p.sc < 0;  // a missing row gets lse = +inf: it contributes exp2(-inf) = 0
   };
   auto store_stage = [&](const StageRegs &r, unsigned char *stage) {
@@ -543,7 +550,7 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
       *reinterpret_cast<bf16x8 *>(stage + it_off[i]) = r.rq[i];
       *reinterpret_cast<bf16x8 *>(stage + ST * P::BYTES + it_off[i]) = r.rd[i];
     }
-    if (has_sc) ((float *)(stage + SG::TILES_B))[threadIdx.x] = r.missing ? INFINITY : r.sc;
+    if (has_sc) ((float *)(stage + SG::TILES_B))[threadIdx.x] = r.missing ? INFINITY : r.sc * sc_mul;
   };
 
   load_positions(qbeg, pos[0]);
@@ -557,10 +564,8 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
     unsigned char *stage = smem + (size_t)buf * SG::BYTES;
     store_stage(r, stage);
     __syncthreads();
-    if (qb + 2 * stage_slots < qend) {
-      load_positions(qb + 3 * stage_slots, p_next);
-      load_stage(r, p_rows);
-    }
+    load_positions(qb + 3 * stage_slots, p_next);  // (past the end of the list: position -1, row 0 is loaded and dropped)
+    load_stage(r, p_rows);
     buf ^= 1;
     if (!wave_on) return;
     const lds_cptr st0 = (lds_cptr)stage;
@@ -588,17 +593,19 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
           }
         }
       // this lane's eight consecutive query rows 8*quad .. +7 of the tile
-      float lse2[8], delta[8], gw[8];
+      float lse2[8], nds[8], gw[8], gws[8];  // lse (log2 units), -delta*scale, gate, gate*scale
       {
         typedef const __attribute__((address_space(3))) f32x4 *f4p;
         const f32x4 l0 = *(f4p)(scal + 32 * rt), l1 = *(f4p)(scal + 32 * rt + 4);
         const f32x4 d0 = *(f4p)(scal + 32 * (ST + rt)), d1 = *(f4p)(scal + 32 * (ST + rt) + 4);
         const f32x4 g0 = *(f4p)(scal + 32 * (2 * ST + rt)), g1 = *(f4p)(scal + 32 * (2 * ST + rt) + 4);
+        const f32x4 h0 = *(f4p)(scal + 32 * (3 * ST + rt)), h1 = *(f4p)(scal + 32 * (3 * ST + rt) + 4);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           lse2[j] = l0[j]; lse2[4 + j] = l1[j];
-          delta[j] = d0[j]; delta[4 + j] = d1[j];
+          nds[j] = d0[j]; nds[4 + j] = d1[j];
           gw[j] = g0[j]; gw[4 + j] = g1[j];
+          gws[j] = h0[j]; gws[4 + j] = h1[j];
         }
       }
       bf16x8 pw[KB], ds[KB];
@@ -610,7 +617,7 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
           const float dpv = j < 4 ? dp[kbk][0][j & 3] : dp[kbk][1][j & 3];
           const float p = fast_exp2(__builtin_fmaf(sv, sl2, -lse2[j]));
           pw[kbk][j] = (__bf16)(p * gw[j]);
-          ds[kbk][j] = (__bf16)(p * __builtin_fmaf(gw[j] * scale, dpv, -delta[j] * scale));
+          ds[kbk][j] = (__bf16)(p * __builtin_fmaf(gws[j], dpv, nds[j]));
         }
 #pragma unroll
       for (int dt = 0; dt < D / 16; ++dt) {
@@ -625,7 +632,8 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
   };
   for (int qb = qbeg; qb < qend; qb += 2 * stage_slots) {
     do_stage(qb, regs[0], pos[0], pos[1]);
-    if (qb + stage_slots < qend) do_stage(qb + stage_slots, regs[1], pos[1], pos[0]);
+    do_stage(qb + stage_slots, regs[1], pos[1], pos[0]);  // (may lie wholly past the end: adds exact zeros; a branch
+                                                          // here would again cost a wait for all loads per iteration)
   }
   if (!wave_on) return;
   // --- store: lane holds dims 16*dt + 4*quad + i of key column n

@@ -103,7 +103,7 @@ __device__ inline void fwd_tile(FwdState<D, CB> &st, const QRows<D, CB> &q, lds_
     }
     float pm = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
     if (!on[cb]) pm = -INFINITY;
-    if (__any(pm > st.m[cb] + slack)) {
+    if (__builtin_expect(__any(pm > st.m[cb] + slack), 0)) {  // rare after the first tiles: keep the common path free of copies
       float tmax = fmaxf(pm, __shfl_xor(pm, 16));
       tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
       const float mn = fmaxf(st.m[cb], tmax);
@@ -391,7 +391,7 @@ __device__ inline void bc_fwd_tile(FwdState<D, 1> &st, const bf16x8 (&qop)[D / 3
       if (first + j >= nk) v[j] = -INFINITY;
   }
   const float pm = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
-  if (__any(pm > st.m[0] + slack)) {
+  if (__builtin_expect(__any(pm > st.m[0] + slack), 0)) {
     float tmax = fmaxf(pm, __shfl_xor(pm, 16));
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
     const float mn = fmaxf(st.m[0], tmax);
