@@ -40,6 +40,43 @@ __global__ void m_prep(const bf16_t *__restrict__ K, const bf16_t *__restrict__ 
   }
 }
 
+// The same with 16-byte accesses, for rows of R8 = Hkv*D/8 pieces with R8 dividing the 128 threads: thread t keeps
+// piece t % R8 of tokens b + t/R8, b + t/R8 + 128/R8, ...; the 128/R8 partial sums of a piece meet in LDS and are
+// added in a fixed order.
+__global__ __launch_bounds__(128) void m_prep8(const bf16_t *__restrict__ K, const bf16_t *__restrict__ V,
+                                               const int32_t *__restrict__ perm, const int32_t *__restrict__ cmp_start,
+                                               int R8, PrepOut o) {
+  __shared__ float part[2][128][8];
+  const int c = blockIdx.x, b = cmp_start[c], e = cmp_start[c + 1];
+  const int seg = threadIdx.x % R8, grp = threadIdx.x / R8, ngrp = 128 / R8;
+  float sk[8], sv[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) sk[j] = sv[j] = 0.f;
+  for (int pos = b + grp; pos < e; pos += ngrp) {
+    const size_t src = ((size_t)perm[pos] * R8 + seg) * 8, dst = ((size_t)pos * R8 + seg) * 8;
+    const bf16x8 kk = ld8(K + src), vv = ld8(V + src);
+    *reinterpret_cast<bf16x8 *>(o.Ks + dst) = kk;
+    *reinterpret_cast<bf16x8 *>(o.Vs + dst) = vv;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { sk[j] += (float)kk[j]; sv[j] += (float)vv[j]; }
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) { part[0][threadIdx.x][j] = sk[j]; part[1][threadIdx.x][j] = sv[j]; }
+  __syncthreads();
+  if (threadIdx.x < 2 * R8) {
+    const int arr = threadIdx.x / R8, sg = threadIdx.x % R8;
+    const float inv = 1.0f / (float)(e - b);
+    bf16x8 out;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      float t = 0.f;
+      for (int gi = 0; gi < ngrp; ++gi) t += part[arr][gi * R8 + sg][j];
+      out[j] = (__bf16)(t * inv);
+    }
+    *reinterpret_cast<bf16x8 *>((arr == 0 ? o.Kc : o.Vc) + ((size_t)c * R8 + sg) * 8) = out;
+  }
+}
+
 size_t padded_rows(int n) { return align_up((size_t)n, 8) + SSA_KEY_PAD; }
 
 struct FwdPlan { size_t ks, vs, kc, vc, ob, lse, idx, sel, po, pml, total; };
@@ -81,7 +118,11 @@ int run_prep(const ssa_ctx &c, const void *k, const void *v, const PrepOut &o) {
   const size_t t0 = (size_t)(c.N / 8) * 8 * row, c0 = (size_t)(c.blk->Nc / 8) * 8 * row;
   Tails ts{{{o.Ks, t0, nt}, {o.Vs, t0, nt}, {o.Kc, c0, nc}, {o.Vc, c0, nc}}};
   m_zero_tails<<<dim3(8, 4), 256, 0, c.stream>>>(ts);
-  m_prep<<<c.blk->Nc, 128, 0, c.stream>>>((const bf16_t *)k, (const bf16_t *)v, c.blk->perm, c.blk->cmp_start, c.Hkv, c.d, o);
+  const int r8 = c.Hkv * c.d / 8;
+  if ((c.Hkv * c.d) % 8 == 0 && r8 <= 64 && 128 % r8 == 0)
+    m_prep8<<<c.blk->Nc, 128, 0, c.stream>>>((const bf16_t *)k, (const bf16_t *)v, c.blk->perm, c.blk->cmp_start, r8, o);
+  else
+    m_prep<<<c.blk->Nc, 128, 0, c.stream>>>((const bf16_t *)k, (const bf16_t *)v, c.blk->perm, c.blk->cmp_start, c.Hkv, c.d, o);
   return hipGetLastError() == hipSuccess ? SSA_OK : SSA_ERR_HIP;
 }
 
