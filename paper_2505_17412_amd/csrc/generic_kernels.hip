@@ -2,6 +2,7 @@
 // Serves SSA_F32 problems and every shape the bf16 MFMA kernels do not cover.  Same mathematics as the MFMA
 // path (paper eq. (2)-(6), Algorithm 1, window paragraph), written for clarity, not speed.
 #include "ssa_internal.h"
+#include "profile.h"
 #include "topk_device.h"
 #include "mfma_launch.h"
 
@@ -461,6 +462,7 @@ int generic_forward(const ssa_ctx &c, const void *q, const void *k, const void *
                     float *lse, int32_t *topk_idx, void *out_branch, void *ws, size_t ws_bytes) {
   if (ws_bytes < plan(c, false).total) return SSA_ERR_WORKSPACE;
   if (c.N == 0) return SSA_OK;
+  ProfScope ps(PROF_GENERIC, c.stream);
   return c.dtype == SSA_F32
              ? forward_t<float>(c, q, k, v, gates, out, lse, topk_idx, out_branch, (char *)ws)
              : forward_t<uint16_t>(c, q, k, v, gates, out, lse, topk_idx, out_branch, (char *)ws);
@@ -471,6 +473,7 @@ int generic_backward(const ssa_ctx &c, const void *q, const void *k, const void 
                      void *dk, void *dv, void *dgates, void *ws, size_t ws_bytes) {
   if (ws_bytes < plan(c, true).total) return SSA_ERR_WORKSPACE;
   if (c.N == 0) return SSA_OK;
+  ProfScope ps(PROF_GENERIC, c.stream);
   return c.dtype == SSA_F32
              ? backward_t<float>(c, q, k, v, gates, out_branch, lse, topk_idx, dout, dq, dk, dv, dgates, (char *)ws)
              : backward_t<uint16_t>(c, q, k, v, gates, out_branch, lse, topk_idx, dout, dq, dk, dv, dgates, (char *)ws);

@@ -205,7 +205,6 @@ int mfma_backward(const ssa_ctx &c, const void *q, const void *k, const void *v,
                   const void *out_branch, const float *lse, const int32_t *topk_idx, const void *dout, void *dq,
                   void *dk, void *dv, void *dgates, void *ws_, size_t ws_bytes) {
   if (!mfma_bwd_supported(c)) {  // head groupings the key-centric kernels do not cover
-    ProfScope ps(PROF_GENERIC, c.stream);
     return generic_backward(c, q, k, v, gates, out_branch, lse, topk_idx, dout, dq, dk, dv, dgates, ws_, ws_bytes);
   }
   const BwdPlan p = bwd_plan(c);
