@@ -491,7 +491,7 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
     for (int dt = 0; dt < D / 16; ++dt) dk[kbk][dt] = dv[kbk][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   extern __shared__ __align__(16) unsigned char smem[];
-  const int slots = 32 / hs;              // token slots per 32-row tile (hs is 8 or 16)
+  const int slots = 32 / hs;              // token slots per 32-row tile (hs divides 16)
   const int stage_slots = ST * slots;     // token slots per stage
   const float sl2 = a.v.sl2, scale = a.v.scale;
   const typename P::Lanes ln = P::lanes();

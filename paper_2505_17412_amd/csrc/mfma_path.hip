@@ -180,7 +180,8 @@ BwdPlan bwd_plan(const ssa_ctx &c) {
   return p;
 }
 
-bool mfma_bwd_supported(const ssa_ctx &c) { return c.hs == 8 || c.hs == 16; }
+// (every backward kernel takes the same head groupings as the forward ones: a 32-row tile holds 32/h_s token slots)
+bool mfma_bwd_supported(const ssa_ctx &c) { return c.hs == 1 || c.hs == 2 || c.hs == 4 || c.hs == 8 || c.hs == 16; }
 
 }  // namespace
 
@@ -193,6 +194,9 @@ bool mfma_supported(const ssa_ctx &c) {
   // the kernels index their staged arrays with 32-bit element offsets
   if ((unsigned long long)(c.N + 2 * SSA_KEY_PAD) * c.Hq * c.d >= (1ull << 31)) return false;
   if (mfma_fwd_lds_bytes(c.d, c.hs, c.blk->s_max) > 150 * 1024) return false;
+  // rows of the per-(token, head, selected block) partial arrays are numbered in 32 bits, list entries in int
+  if ((unsigned long long)c.N * c.Hq * c.T >= (1ull << 32)) return false;
+  if ((unsigned long long)c.N * c.Hkv * c.T >= (1ull << 31)) return false;
   return true;
 }
 
