@@ -63,7 +63,7 @@ __global__ __launch_bounds__(128) void m_prep8(const bf16_t *__restrict__ K, con
 #pragma unroll
   for (int j = 0; j < 8; ++j) { part[0][threadIdx.x][j] = sk[j]; part[1][threadIdx.x][j] = sv[j]; }
   __syncthreads();
-  if (threadIdx.x < 2 * R8) {
+  if ((int)threadIdx.x < 2 * R8) {
     const int arr = threadIdx.x / R8, sg = threadIdx.x % R8;
     const float inv = 1.0f / (float)(e - b);
     bf16x8 out;

@@ -163,7 +163,7 @@ __global__ __launch_bounds__(1024) void m_chunk_order(const int32_t *__restrict_
     part[threadIdx.x] = own;
     __syncthreads();
     for (int off = 1; off < 1024; off <<= 1) {
-      const uint32_t v = threadIdx.x >= off ? part[threadIdx.x - off] : 0u;
+      const uint32_t v = (int)threadIdx.x >= off ? part[threadIdx.x - off] : 0u;
       __syncthreads();
       part[threadIdx.x] += v;
       __syncthreads();
