@@ -5,8 +5,11 @@
 // branch b with gate w_b:  P = exp(S - lse_b),  dP = <dO, V>,  dS = P (w_b dP - delta_b) scale,
 // delta_b = w_b <dO, O_b>;  dV += w_b P dO,  dQ += dS K,  dK += dS Q.
 //
-// Two kernel families, both free of floating-point atomics (results do not depend on scheduling):
-//   * m_bwd_dq: query-centric, same walk as the forward kernels (transposed scores, keys in the lanes);
+// Three kernel families, all free of floating-point atomics (results do not depend on scheduling):
+//   * m_bwd_dq: query-centric, same walk as the forward kernels (transposed scores, keys in the lanes), for the
+//     compression and window branches;
+//   * m_bwd_dq_bc: the selection branch's dQ, block-centric like its forward kernel (one partial dQ row per selected
+//     block, added per token in rank order by m_dq_merge);
 //   * m_bwd_dkv: key-centric; a wavefront owns 16*KB keys and streams the query rows that attend to them
 //     (scores with the query rows in the lanes); the contractions over query rows take Q^T and dO^T from the
 //     staged row-major tiles through the transposing LDS read.

@@ -1,8 +1,9 @@
 // bf16 MFMA forward kernels of SSA (paper eq. (4)-(6), Algorithm 1, window paragraph) for gfx950.
 //
-// A workgroup of 4 wavefronts owns 4*CB*16 query rows = consecutive sorted tokens x the h_s heads of one KV
-// group; each wavefront keeps CB blocks of 16 query columns and their running softmax state (Algorithm 1's
-// m, l, o) in registers.  Scores are produced TRANSPOSED (S^T = K Q^T, keys x queries) so that the
+// Compression and window kernels: a workgroup of 4 wavefronts owns 4*CB*16 query rows = consecutive sorted tokens x
+// the h_s heads of one KV group; each wavefront keeps CB blocks of 16 query columns and their running softmax state
+// (Algorithm 1's m, l, o) in registers.  The selection kernel turns the loops round (per selected block, over the
+// tokens that selected it: see the block-centric section below) with the same tile arithmetic.  Scores are produced TRANSPOSED (S^T = K Q^T, keys x queries) so that the
 // probabilities land in the lanes exactly as the B operand of the second contraction O^T = V^T P^T needs them.
 // Key tiles (K rows and V rows, both row-major) are staged through LDS once per workgroup (see mfma_qc.h); the K
 // operand is one 16-byte LDS read, the V^T operand comes from the same row-major V tile through the transposing

@@ -1,10 +1,11 @@
-// Query-centric tile pipeline shared by the forward and the dQ kernels (gfx950, wave64).
+// LDS tile layout of all attention kernels, and the query-centric tile pipeline of the compression and window
+// kernels, forward and dQ (gfx950, wave64).
 //
-// A workgroup of 4 wavefronts owns 4*CB*16 query rows (consecutive sorted tokens x the heads of one KV group);
-// each wavefront keeps CB blocks of 16 query columns in registers.  The workgroup walks a list of key ranges
-// (one range for the compression and window branches, the union of the selected blocks for the selection
-// branch).  Every 32-key tile is loaded once per workgroup, global -> registers -> LDS, double buffered so the
-// loads of tile i+1 fly while tile i is consumed; all four wavefronts then take their MFMA A operands from LDS.
+// Pipeline: a workgroup of 4 wavefronts owns 4*CB*16 query rows (consecutive sorted tokens x the heads of one KV
+// group); each wavefront keeps CB blocks of 16 query columns in registers.  The workgroup walks a contiguous key range
+// (the item's pooled keys, the token's window).  Every 32-key tile is loaded once per workgroup, global -> registers ->
+// LDS, double buffered so the loads of the next tiles fly while a tile is consumed; all four wavefronts then take their
+// MFMA A operands from LDS.  (The selection branch has kernels of its own: see mfma_bc.h.)
 #pragma once
 
 #include "mfma_common.h"
