@@ -230,178 +230,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// dQ of the selection branch, block-centric: the same exchange of loops as the forward kernel m_slc_fwd_bc.  A workgroup
-// holds one selection block's K and V rows in LDS and runs through a chunk of the tokens that selected it; every
-// wavefront takes 16/h_s tokens per step on its own (query and dO rows in registers, no barrier, no column that did
-// not select the block).  One bf16 partial dQ per (token, KV head, selected block) goes to memory; m_dq_merge adds them
-// in rank order onto the fp32 compression + window part.
-// ---------------------------------------------------------------------------------------------------------
-struct BcDqArgs {
-  MfmaView v;
-  const bf16_t *Qs, *dOs;             // [N(pos)][Hq][D] sorted copies
-  const float *lse2s, *deltas, *gws;  // selection branch: [N(pos)][Hq]
-  const int32_t *idx;                 // [N,Hkv,T]
-  const int32_t *sel_start, *sel_list, *chunk_start, *chunk_order;
-  bf16_t *pdq;                        // [N(pos)][Hkv][T][hs][D]
-};
-
-template <int D>
-struct BcDqRows {
-  bf16x8 qop[D / 32], dop[D / 32];
-  float lse2, gws, dls;  // lse in log2 units; gate and delta with the softmax scale folded in
-  uint32_t prow;         // ((pos*Hkv + g)*T + rank)*hs + head
-  bool valid;
-};
-
-template <int D>
-__device__ inline void bc_dq_load_rows(const BcDqArgs &a, const int *tl, const int *sl, int step, int cnt, int g, BcDqRows<D> &r) {
-  const int n = threadIdx.x & 15, quad = threadIdx.x >> 4 & 3;
-  const int hs = a.v.hs, hl = n % hs;
-  const int e = step * (16 / hs) + n / hs;
-  r.valid = e < cnt;
-  const int pos = r.valid ? tl[e] : 0, rank = r.valid ? sl[e] : 0;
-  const size_t th = (size_t)pos * a.v.Hq + g * hs + hl;
-#pragma unroll
-  for (int ks = 0; ks < D / 32; ++ks) {
-    r.qop[ks] = r.valid ? ld8(a.Qs + th * D + 8 * quad + 32 * ks) : zero8();
-    r.dop[ks] = r.valid ? ld8(a.dOs + th * D + 8 * quad + 32 * ks) : zero8();
-  }
-  r.lse2 = r.valid ? a.lse2s[th] : INFINITY;  // a missing column gets P = exp2(-inf) = 0
-  r.gws = a.gws[th] * a.v.scale;
-  r.dls = a.deltas[th] * a.v.scale;
-  r.prow = (uint32_t)((((size_t)pos * a.v.Hkv + g) * a.v.T + rank) * hs + hl);
-}
-
-// One 32-key LDS tile: transposed scores (K rows) and dP (V rows), dS^T = P (gate dP - delta) scale, then
-// dQ^T += K^T dS^T with K^T read from the same K tile through the transposing LDS load.
-template <int D, bool MASK>
-__device__ inline void bc_dq_tile(f32x4 (&acc)[D / 16], const BcDqRows<D> &r, lds_cptr kt, lds_cptr vt,
-                                  const typename PTile<D, false>::Lanes &ln, int key0, int nk, float sl2) {
-  f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0, p0 = s0, p1 = s0;
-#pragma unroll
-  for (int ks = 0; ks < D / 32; ++ks) {
-    s0 = mfma16(p_row_operand<D, false>(kt, ln, 0, ks), r.qop[ks], s0);
-    s1 = mfma16(p_row_operand<D, false>(kt, ln, 1, ks), r.qop[ks], s1);
-    p0 = mfma16(p_row_operand<D, false>(vt, ln, 0, ks), r.dop[ks], p0);
-    p1 = mfma16(p_row_operand<D, false>(vt, ln, 1, ks), r.dop[ks], p1);
-  }
-  bf16x8 ds;
-  const int first = key0 + 8 * (int)(threadIdx.x >> 4 & 3);
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const float sv = j < 4 ? s0[j & 3] : s1[j & 3], dp = j < 4 ? p0[j & 3] : p1[j & 3];
-    float p = fast_exp2(__builtin_fmaf(sv, sl2, -r.lse2));
-    if (MASK && first + j >= nk) p = 0.f;
-    ds[j] = (__bf16)(p * __builtin_fmaf(r.gws, dp, -r.dls));
-  }
-#pragma unroll
-  for (int dt = 0; dt < D / 16; ++dt) acc[dt] = mfma16(p_tr_operand<D, false>(kt, ln, dt), ds, acc[dt]);
-}
-
-template <int D, int KSEG>
-constexpr size_t bc_dq_lds_bytes() { return (size_t)2 * (KSEG / 32) * PTile<D, false>::BYTES + (size_t)2 * BC_CHUNK * sizeof(int); }
-
-template <int D, int NW, int KSEG>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4 : 2))) void m_bwd_dq_bc(BcDqArgs a) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  using P = PTile<D, false>;
-  constexpr int MAXT = KSEG / 32;
-  unsigned char *Kt = smem, *Vt = Kt + MAXT * P::BYTES;
-  int *tl = (int *)(Vt + MAXT * P::BYTES), *sl = tl + BC_CHUNK;
-  const int wid = threadIdx.x >> 6, quad = threadIdx.x >> 4 & 3;
-  const int hs = a.v.hs, Hkv = a.v.Hkv, T = a.v.T, Ns = a.v.Ns;
-  const int wi = bc_chunk_of_workgroup(a.chunk_start[Hkv * Ns]);
-  int key, chunk;
-  if (wi < 0 || !bc_find_chunk(a.chunk_start, Hkv * Ns, a.chunk_order[wi], key, chunk)) return;
-  const int g = key / Ns, blk = key % Ns;
-  const int kbeg = a.v.slc_start[blk], kend = a.v.slc_start[blk + 1];
-  const int qbeg = a.sel_start[key] + chunk * BC_CHUNK, cnt = min(a.sel_start[key + 1] - qbeg, BC_CHUNK);
-  // the chunk's tokens (sorted positions) and the rank of this block in each token's row of I
-  for (int i = threadIdx.x; i < cnt; i += 64 * NW) {
-    const int pos = a.sel_list[qbeg + i];
-    const int32_t *row = a.idx + ((size_t)a.v.perm[pos] * Hkv + g) * T;
-    int j = 0;
-    while (j < T - 1 && row[j] != blk) ++j;
-    tl[i] = pos;
-    sl[i] = j;
-  }
-  const int tpw = 16 / hs;
-  const int n_it = (cnt + tpw - 1) / tpw;
-  const uint32_t kstride = (uint32_t)(Hkv * D);
-  const float sl2 = a.v.sl2;
-  const typename P::Lanes ln = P::lanes();
-  const lds_cptr kt = (lds_cptr)Kt, vt = (lds_cptr)Vt;
-  __syncthreads();
-  BcDqRows<D> cur;
-  if (wid < n_it) bc_dq_load_rows<D>(a, tl, sl, wid, cnt, g, cur);
-  for (int k0 = kbeg; k0 < kend; k0 += KSEG) {
-    const int nk = min(KSEG, kend - k0), nfull = nk >> 5;
-    if (k0 > kbeg) {
-      __syncthreads();
-      if (wid < n_it) bc_dq_load_rows<D>(a, tl, sl, wid, cnt, g, cur);
-    }
-    p_stage2<D, false, 64 * NW>(a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D, kstride, k0, (nk + 31) >> 5, Kt, Vt);
-    __syncthreads();
-    for (int it = wid; it < n_it; it += NW) {
-      BcDqRows<D> nxt;
-      if (it + NW < n_it) bc_dq_load_rows<D>(a, tl, sl, it + NW, cnt, g, nxt);
-      f32x4 acc[D / 16];
-#pragma unroll
-      for (int dt = 0; dt < D / 16; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-      if (k0 > kbeg && cur.valid) {  // continue from the partial of the earlier segments
-#pragma unroll
-        for (int dt = 0; dt < D / 16; ++dt) {
-          const bf16x4 x = *reinterpret_cast<const bf16x4 *>(a.pdq + (size_t)cur.prow * D + 16 * dt + 4 * quad);
-#pragma unroll
-          for (int i = 0; i < 4; ++i) acc[dt][i] = (float)x[i];
-        }
-      }
-#pragma unroll
-      for (int t = 0; t < MAXT; ++t)
-        if (t < nfull) bc_dq_tile<D, false>(acc, cur, kt + t * P::BYTES, vt + t * P::BYTES, ln, 32 * t, nk, sl2);
-      if (nk & 31) bc_dq_tile<D, true>(acc, cur, kt + nfull * P::BYTES, vt + nfull * P::BYTES, ln, 32 * nfull, nk, sl2);
-      store_partial_row<D>(a.pdq + (size_t)cur.prow * D, acc, cur.valid);
-      cur = nxt;
-    }
-  }
-}
-
-// dQ[tok] = (compression + window part, fp32, by sorted position) + sum over the token's selected blocks, in rank
-// order, of the partial dQ.  One thread per (sorted position, query head, 8 dims).
-struct DqMergeArgs {
-  const bf16_t *pdq;
-  const float *dQp;
-  const int32_t *idx, *perm;
-  bf16_t *dQ;
-  int N, Hq, Hkv, hs, T, D;
-};
-
-__global__ __launch_bounds__(256) void m_dq_merge(DqMergeArgs a) {
-  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int per_row = a.D / 8;
-  if (i >= (size_t)a.N * a.Hq * per_row) return;
-  const int c8 = (int)(i % per_row), h = (int)(i / per_row % a.Hq), pos = (int)(i / ((size_t)per_row * a.Hq));
-  const int g = h / a.hs, hl = h % a.hs, tok = a.perm[pos];
-  const int32_t *row = a.idx + ((size_t)tok * a.Hkv + g) * a.T;
-  int nv = 0;  // rows are ascending with the -1 padding at the end
-  for (int j = 0; j < a.T; ++j) nv += row[j] >= 0 ? 1 : 0;
-  const float *base = a.dQp + ((size_t)pos * a.Hq + h) * a.D + 8 * c8;
-  const float4 b0 = *reinterpret_cast<const float4 *>(base), b1 = *reinterpret_cast<const float4 *>(base + 4);
-  float acc[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
-  const size_t slot0 = ((size_t)pos * a.Hkv + g) * a.T;
-#pragma unroll 4
-  for (int j = 0; j < nv; ++j) {
-    const bf16x8 x = ld8(a.pdq + ((slot0 + j) * a.hs + hl) * a.D + 8 * c8);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] += (float)x[e];
-  }
-  bf16x8 o;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) o[e] = (__bf16)acc[e];
-  *reinterpret_cast<bf16x8 *>(a.dQ + ((size_t)tok * a.Hq + h) * a.D + 8 * c8) = o;
-}
-
-// ---------------------------------------------------------------------------------------------------------
 // dK/dV: key-centric
 // ---------------------------------------------------------------------------------------------------------
 enum { DKV_WIN = 0, DKV_SLC = 1, DKV_CMP = 2 };
@@ -719,8 +547,6 @@ __global__ void m_bwd_finish(const int32_t *__restrict__ perm, const int32_t *__
 }
 
 // Shape of the block-centric selection dQ kernel per head dimension: wavefronts per workgroup, keys held in LDS at a time.
-template <int D> struct BcDqShape { static constexpr int NW = 8, KSEG = 256; };
-template <> struct BcDqShape<128> { static constexpr int NW = 8, KSEG = 256; };
 constexpr int KB_KEYS_MAX = 2;  // key blocks of 16 per wavefront in the dK/dV kernels (1 at head_dim 128: registers)
 // wavefronts per workgroup there (16*KB_KEYS keys each): blocks and windows hold ~130 tokens, an item's pooled keys
 // thousands, so the compression branch takes wider workgroups (fewer passes over the query rows)
@@ -741,12 +567,9 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
               N, Hq, Hkv, v.hs, D, (bf16_t *)dgates, w.lse2s, w.deltas, w.gws, w.Qs, w.dOs};
     m_bwd_pre<<<N, 256, (size_t)Hq * D * sizeof(bf16_t), s>>>(a);
   }
-  using BS = BcDqShape<D>;
-  static std::once_flag dq_once;  // raise the dynamic LDS limit once per process for these instantiations
+  static std::once_flag dq_once;  // raise the dynamic LDS limit once per process for this instantiation
   std::call_once(dq_once, [] {
     (void)hipFuncSetAttribute((const void *)m_bwd_dq<D, 1, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    (void)hipFuncSetAttribute((const void *)m_bwd_dq_bc<D, BS::NW, BS::KSEG>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              160 * 1024);
   });
   {
     ProfScope ps0(PROF_BWD_DQ_CMP, s);
@@ -762,17 +585,13 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
   }
   {
     ProfScope ps1(PROF_BWD_DQ, s);
-    const size_t entries = (size_t)N * Hkv * v.T;
-    const unsigned chunks = (unsigned)(entries / BC_CHUNK + (size_t)Hkv * v.Ns);
-    BcDqArgs b{v, w.Qs, w.dOs, w.lse2s + NH, w.deltas + NH, w.gws + NH, idx, w.sel.start, w.sel.list, w.sel.bc_chunk_start,
-               w.sel.bc_order, w.part.o};
-    m_bwd_dq_bc<D, BS::NW, BS::KSEG><<<dim3((chunks + 7) / 8 * 8), 64 * BS::NW, bc_dq_lds_bytes<D, BS::KSEG>(), s>>>(b);
+    const int rc = slc_dq_kernel(v, D, w, idx, s);
+    if (rc != SSA_OK) return rc;
   }
   {
     ProfScope ps2(PROF_BWD_DQ_MERGE, s);
-    DqMergeArgs m{w.part.o, w.dQp, idx, v.perm, (bf16_t *)dq, N, Hq, Hkv, v.hs, v.T, D};
-    const size_t threads = (size_t)N * Hq * (D / 8);
-    m_dq_merge<<<(unsigned)((threads + 255) / 256), 256, 0, s>>>(m);
+    const int rc = slc_dq_merge_kernel(v, D, w, idx, dq, s);
+    if (rc != SSA_OK) return rc;
   }
   constexpr int KB_KEYS = D >= 128 ? 1 : KB_KEYS_MAX;
   constexpr int DKV_WAVES = DkvWaves<D>::N, DKV_WAVES_CMP = DkvWaves<D>::N;

@@ -1,4 +1,5 @@
-// Launch functions of the bf16 MFMA kernels (defined in mfma_fwd.hip / mfma_bwd.hip), called by mfma_path.hip.
+// Launch functions of the bf16 MFMA kernels (defined in mfma_fwd.hip / mfma_bwd.hip / mfma_slc.hip), called by
+// mfma_path.hip and by one another.
 #pragma once
 #include "mfma_common.h"
 
@@ -31,6 +32,13 @@ struct SlcPartials {
   float *ml;    // [N][Hkv][T][hs][2]: running maximum (raw score units) and sum of the partial softmax (forward only)
 };
 
+// Block-centric selection kernels (mfma_slc.hip), forward: partials per selected block, then the per-token merge that
+// also writes the gated sum of eq. (4) (out_branch [3,N,Hq,D]: branches 0 and 2 read, 1 written; lse [3,N,Hq]).
+int slc_forward_kernel(const MfmaView &v, int D, const void *q, const int32_t *idx, const SelIndex &sel,
+                       const SlcPartials &part, hipStream_t s);
+int slc_merge_kernel(const MfmaView &v, int D, const SlcPartials &part, const int32_t *idx, const void *gates,
+                     void *out_branch, float *lse, void *out, hipStream_t s);
+
 // Device buffers of the backward pass (carved from the caller's workspace).
 struct BwdBuffers {
   float *lse2s, *deltas, *gws;  // [3][N(pos)][Hq]: lse*log2(e), gate*<dO,O_b>, gate
@@ -45,6 +53,10 @@ struct BwdBuffers {
   float *dKc_out, *dVc_out;     // [Nc][Hkv][D] or NULL: where the pooled-key/value gradients go instead of being un-pooled
   SlcPartials part;             // partial dQ of the selection branch
 };
+// Block-centric selection kernels, backward: partial dQ per selected block (w.part.o), then the per-token sum onto the
+// fp32 dQ of the other two branches (w.dQp), written to dq.
+int slc_dq_kernel(const MfmaView &v, int D, const BwdBuffers &w, const int32_t *idx, hipStream_t s);
+int slc_dq_merge_kernel(const MfmaView &v, int D, const BwdBuffers &w, const int32_t *idx, void *dq, hipStream_t s);
 int mfma_backward_kernels(const MfmaView &v, int D, const BwdBuffers &w, const void *q, const void *gates,
                           const void *out_branch, const float *lse, const int32_t *idx, const void *dout, void *dq,
                           void *dk, void *dv, void *dgates, const ssa_blocks *blk, int B, hipStream_t s);

@@ -243,6 +243,26 @@ __device__ inline void load_rows(const bf16_t *Q, const MfmaView &v, int wg_pos0
   }
 }
 
+// Running softmax state of CB blocks of 16 query columns (Algorithm 1's o, l, m), shared by the pipeline kernels and
+// the block-centric selection kernel.
+template <int D, int CB>
+struct FwdState {
+  f32x4 o[CB][D / 16];  // o[cb][dt][i]: output dim 16*dt + 4*quad + i of query column n
+  f32x4 l[CB];          // l[cb][0]: running sum of column n over all keys seen (the other three elements are unused)
+  float m[CB];          // running max (raw score units)
+};
+
+template <int D, int CB>
+__device__ inline void init_state(FwdState<D, CB> &st) {
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb) {
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) st.o[cb][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    st.m[cb] = -INFINITY;
+    st.l[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+}
+
 // Walk the tiles of the key ranges rng_s/rng_e[0..nr) (LDS, workgroup-uniform).  Global loads run PF tiles (1 or 2)
 // ahead of the tile being consumed, through PF register sets used alternately; LDS holds two stages: the stage
 // written at step i is read at step i and overwritten at step i+2, with one barrier per step in between.
