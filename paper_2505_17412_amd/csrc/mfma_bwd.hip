@@ -351,14 +351,14 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
     const int v = MODE == DKV_SLC ? a.sel_list[min(li, qend - 1)] : li;
     return li < qend ? v : -1;
   };
-  // Two register sets and two position sets, used alternately: while stage i is consumed, the rows of stage i+2 are
-  // requested (two stages of loads in flight) with the positions read during stage i-1, and the positions of stage
-  // i+3 are read.  Inside a stage the positions are requested BEFORE the rows, so that waiting for them (the next
-  // stage needs them for its addresses) leaves the younger row loads in flight; nothing loaded is touched before the
-  // stage that stores it into LDS.
+  // One register set and two position sets: while stage i is consumed, the rows of stage i+1 are in flight (requested
+  // right after the barrier, with the positions read during stage i-1) and the positions of stage i+2 are read.  One
+  // stage of lookahead is enough because the chunks run in token order (the rows mostly come from the L2), and the
+  // registers a second set would take are worth more to the tile code.  Nothing loaded is touched before the stage that
+  // stores it into LDS.
   struct StageRegs { bf16x8 rq[NI], rd[NI]; float sc; bool missing; };
   struct StagePos { int it[NI], sc; };
-  StageRegs regs[2];
+  StageRegs regs;
   StagePos pos[2];
   auto load_positions = [&](int qb, StagePos &p) {
 #pragma unroll
@@ -386,17 +386,15 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
 
   load_positions(qbeg, pos[0]);
   load_positions(qbeg + stage_slots, pos[1]);
-  load_stage(regs[0], pos[0]);
-  load_stage(regs[1], pos[1]);
-  load_positions(qbeg + 2 * stage_slots, pos[0]);
+  load_stage(regs, pos[0]);
   int buf = 0;
-  // stage qb: `r` holds its rows; `p_rows` the positions of stage qb+2, `p_next` is refilled with those of stage qb+3
-  auto do_stage = [&](int qb, StageRegs &r, StagePos &p_rows, StagePos &p_next) {
+  // stage qb: `regs` holds its rows; `p_rows` the positions of stage qb+1, `p_next` is refilled with those of stage qb+2
+  auto do_stage = [&](int qb, const StagePos &p_rows, StagePos &p_next) {
     unsigned char *stage = smem + (size_t)buf * SG::BYTES;
-    store_stage(r, stage);
+    store_stage(regs, stage);
     __syncthreads();
-    load_positions(qb + 3 * stage_slots, p_next);  // (past the end of the list: position -1, row 0 is loaded and dropped)
-    load_stage(r, p_rows);
+    load_stage(regs, p_rows);                       // rows of the next stage; their positions were read one stage ago
+    load_positions(qb + 2 * stage_slots, p_next);   // (past the end of the list: position -1, row 0 is loaded and dropped)
     buf ^= 1;
     if (!wave_on) return;
     const lds_cptr st0 = (lds_cptr)stage;
@@ -462,9 +460,9 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
     }
   };
   for (int qb = qbeg; qb < qend; qb += 2 * stage_slots) {
-    do_stage(qb, regs[0], pos[0], pos[1]);
-    do_stage(qb + stage_slots, regs[1], pos[1], pos[0]);  // (may lie wholly past the end: adds exact zeros; a branch
-                                                          // here would again cost a wait for all loads per iteration)
+    do_stage(qb, pos[1], pos[0]);
+    do_stage(qb + stage_slots, pos[0], pos[1]);  // (may lie wholly past the end: adds exact zeros; a branch here would
+                                                 // cost a wait for all outstanding loads per iteration)
   }
   if (!wave_on) return;
   // --- store: lane holds dims 16*dt + 4*quad + i of key column n
