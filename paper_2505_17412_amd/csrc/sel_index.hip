@@ -135,18 +135,29 @@ __global__ __launch_bounds__(256) void m_sel_fill(const uint32_t *__restrict__ b
 // different blocks but to the same stretch of tokens, whose query rows they all gather: the rows are fetched into the
 // L2 once instead of once per selected block.  The order only decides WHEN a chunk runs, never what it computes, so the
 // arbitrary order inside a bucket (LDS atomics) does not touch any result.  order[i] = chunk id; total = chunk_start[n].
-constexpr int ORDER_BINS = 8192;
+constexpr int ORDER_BINS = 8192, ORDER_CS = 4096;
 __global__ __launch_bounds__(1024) void m_chunk_order(const int32_t *__restrict__ start, const int32_t *__restrict__ chunk_start,
                                                       const int32_t *__restrict__ list, int n, int Ns, int chunk_len,
                                                       int bucket, int bins_per_head, int32_t *__restrict__ order) {
   __shared__ uint32_t bin[ORDER_BINS];
+  __shared__ int32_t cs_lds[ORDER_CS];  // copy of the chunk prefix sums when they fit: the bisections then stay in LDS
   const int nbins = (n / Ns) * bins_per_head;
+  const bool in_lds = n + 1 <= ORDER_CS;
   for (int i = threadIdx.x; i < nbins; i += 1024) bin[i] = 0u;
+  if (in_lds)
+    for (int i = threadIdx.x; i <= n; i += 1024) cs_lds[i] = chunk_start[i];
   __syncthreads();
   const int total = chunk_start[n];
   // chunk w -> its key by bisection over the chunk prefix sums, then the bucket of the chunk's first query position
   auto bin_of = [&](int w) {
     int lo = 0, hi = n;  // chunk_start[lo] <= w < chunk_start[hi]
+    if (in_lds) {
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (cs_lds[mid] <= w) lo = mid; else hi = mid;
+      }
+      return (lo / Ns) * bins_per_head + list[start[lo] + (w - cs_lds[lo]) * chunk_len] / bucket;
+    }
     while (hi - lo > 1) {
       const int mid = (lo + hi) >> 1;
       if (chunk_start[mid] <= w) lo = mid; else hi = mid;
