@@ -156,8 +156,8 @@ int ssa_forward(const ssa_params_t *params, const ssa_blocks_t *blocks, const vo
  *   q,k,v,gates as in ssa_forward; out_branch, lse, topk_idx: what ssa_forward wrote for the same inputs.  A caller
  *   that supplies its own topk_idx (Algorithm 1 takes I as an input) must keep ssa_forward's row format: distinct
  *   selection-block ids of the token's own batch item, the -1 padding at the end of the row; the order of the ids does
- *   not matter.  Rows that break this are not detected: ids out of range are ignored, duplicates and -1 in the middle
- *   of a row give undefined gradients.
+ *   not matter.  Rows that break this are not detected: ids out of range, duplicates and -1 in the middle of a row
+ *   give undefined gradient values (no memory outside the outputs and the workspace is touched).
  *   dout   dev [N,Hq,d]
  *   dq     dev [N,Hq,d]   dk, dv dev [N,Hkv,d]   dgates dev [N,Hq,3]   all overwritten
  * Errors: as ssa_forward.

@@ -49,9 +49,11 @@ def build_blocks_gpu(wl: inputs.Workload):
     return p, ssa.ssa_build_blocks(p, coords, offs)
 
 
-def run_gpu(wl: inputs.Workload, backward: bool = True, dout: Optional[np.ndarray] = None, blocks=None) -> GpuRun:
+def run_gpu(wl: inputs.Workload, backward: bool = True, dout: Optional[np.ndarray] = None, blocks=None,
+            idx_for_backward=None) -> GpuRun:
     """One forward (+ backward) of the workload through the C ABI; every output starts as NaN / a negative index so a
-    value the library does not write shows up."""
+    value the library does not write shows up.  idx_for_backward: a function of the forward's index tensor (numpy
+    int32 [N,Hkv,T]) returning the tensor the backward call is handed instead (Algorithm 1 takes I as an input)."""
     import torch
     from . import ssa
     if blocks is None:
@@ -74,6 +76,8 @@ def run_gpu(wl: inputs.Workload, backward: bool = True, dout: Optional[np.ndarra
         dk = torch.full_like(k, float("nan"))
         dv = torch.full_like(v, float("nan"))
         dg = torch.full_like(g, float("nan"))
+        if idx_for_backward is not None:
+            idx = torch.from_numpy(np.ascontiguousarray(idx_for_backward(r.topk_idx), dtype=np.int32)).cuda()
         ssa.ssa_backward(p, blk, q, k, v, g, ob, lse, idx, do, dq, dk, dv, dg)
         torch.cuda.synchronize()
         r.dq, r.dk, r.dv, r.dgates = to_np(dq), to_np(dk), to_np(dv), to_np(dg)

@@ -344,3 +344,29 @@ def test_forward_backward_replay_from_a_hip_graph():
         torch.cuda.synchronize()
         for name, got, want in zip(("out", "lse", "idx", "dq", "dk", "dv", "dgates"), (out, lse, idx, dq, dk, dv, dg), eager):
             assert torch.equal(got, want), (r, name)
+
+
+@pytest.mark.parametrize("which", ["bf16_matrix_cores", "f32_generic"])
+def test_backward_takes_selected_ids_in_any_order(which):
+    """ssa_backward's contract for a caller-supplied I: distinct ids, the -1 padding at the end, any order.  The
+    gradients with every row's ids shuffled must match those with the forward's ascending rows (the sums are taken in
+    another order, so to the tolerance of the dtype, not bit for bit)."""
+    if which == "bf16_matrix_cores":
+        wl = inputs.random_points_workload(51, 32, (1400, 600), 16, 2, 64, (4, 8, 8), 6, "bf16")
+    else:
+        wl = inputs.random_points_workload(52, 16, (500, 300), 4, 2, 16, (2, 4, 4), 5, "f32")
+
+    def shuffled(idx):
+        rng = np.random.default_rng(7)
+        out = idx.copy()
+        for t in range(idx.shape[0]):
+            for g in range(idx.shape[1]):
+                nv = int(np.sum(idx[t, g] >= 0))
+                out[t, g, :nv] = rng.permutation(idx[t, g, :nv])
+        return out
+
+    a = util.run_gpu(wl, backward=True)
+    b = util.run_gpu(wl, backward=True, idx_for_backward=shuffled)
+    assert np.array_equal(a.topk_idx, b.topk_idx)
+    for name in ("dq", "dk", "dv", "dgates"):
+        util.assert_close(getattr(b, name), getattr(a, name), wl.dtype, name)
