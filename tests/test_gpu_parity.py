@@ -268,8 +268,8 @@ def test_many_selection_blocks(seed, n, expect_blocks):
 
 
 def test_many_blocks_over_many_items_sampled():
-    """Twelve items with ~500 selection blocks each: more (KV head, block) counters than the token-order histogram
-    keeps in LDS, so its global-memory path runs; every item small, queries sampled."""
+    """Twelve items with ~500 selection blocks each: more (KV head, block) keys than the chunk-ordering kernel copies
+    into LDS, so its bisections run on global memory; every item small, queries sampled."""
     wl = inputs.random_points_workload(33, 32, (1500,) * 12, 16, 2, 64, (2, 4, 4), 6, "bf16")
     assert 2 * oracle_for(wl).blocks.n_blocks["slc"] > 8192
     full_parity(wl, queries=np.arange(3, wl.n_tokens, 9, dtype=np.int32))
