@@ -150,7 +150,7 @@ __host__ __device__ inline size_t dq_lds_bytes() { return (size_t)2 * StageLayou
 // dQ of the compression branch, then of the (small) window branch, in the sorted token order; the sum is kept in fp32 by
 // sorted position (dQp) for the merge with the selection branch's partials.
 template <int D, int CB, int NW>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4 : 2))) void m_bwd_dq(DqArgs a) {
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64 && CB == 1 ? 4 : 2))) void m_bwd_dq(DqArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   using L = StageLayout<D, 2>;
   bf16_t *stage0 = (bf16_t *)smem;
@@ -545,6 +545,10 @@ __global__ void m_bwd_finish(const int32_t *__restrict__ perm, const int32_t *__
 }
 
 // Shape of the block-centric selection dQ kernel per head dimension: wavefronts per workgroup, keys held in LDS at a time.
+// 16-column blocks per wavefront of the compression + window dQ kernel: with two, every K and V operand read from LDS
+// feeds two matrix instructions (202 registers, two waves per SIMD; 1.15 -> 1.09 ms at the benchmark shape); head_dim
+// 128 keeps one (its accumulators alone would double).
+template <int D> constexpr int dq_cb() { return D <= 64 ? 2 : 1; }
 constexpr int KB_KEYS_MAX = 2;  // key blocks of 16 per wavefront in the dK/dV kernels (1 at head_dim 128: registers)
 // wavefronts per workgroup there (16*KB_KEYS keys each): blocks and windows hold ~130 tokens, an item's pooled keys
 // thousands, so the compression branch takes wider workgroups (fewer passes over the query rows)
@@ -567,12 +571,12 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
   }
   static std::once_flag dq_once;  // raise the dynamic LDS limit once per process for this instantiation
   std::call_once(dq_once, [] {
-    (void)hipFuncSetAttribute((const void *)m_bwd_dq<D, 1, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    (void)hipFuncSetAttribute((const void *)m_bwd_dq<D, dq_cb<D>(), 4>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
   });
   {
     ProfScope ps0(PROF_BWD_DQ_CMP, s);
     DqArgs a{v, (const bf16_t *)q, (const bf16_t *)dout, w.lse2s, w.deltas, w.gws, w.dQp};
-    constexpr int CB = 1, NW0 = 4;
+    constexpr int CB = dq_cb<D>(), NW0 = 4;
     const int tw0 = NW0 * CB * 16 / v.hs;
     m_bwd_dq<D, CB, NW0><<<dim3(xcd_grid_size((N + tw0 - 1) / tw0, Hkv)), 64 * NW0, dq_lds_bytes<D>(), s>>>(a);
   }
