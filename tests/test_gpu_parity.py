@@ -61,6 +61,7 @@ def test_tiny_fp32_head_groupings(hq, hkv):
     (14, 32, (900,), 16, 1, 64, (4, 8, 4), 6, "bf16"),
     (15, 32, (640,), 16, 2, 128, (4, 8, 8), 5, "bf16"),
     (16, 16, (500,), 4, 4, 32, (2, 4, 4), 3, "bf16"),
+    (18, 32, (800, 450), 24, 3, 64, (4, 8, 8), 5, "bf16"),  # three KV heads: rows the 16-byte pooling kernel does not take
     (17, 8, (400,), 4, 2, 24, (1, 2, 2), 2, "f32"),        # duplicates allowed below, odd head_dim
 ])
 def test_random_points(seed, grid, n, hq, hkv, d, m, topk, dtype):
