@@ -371,3 +371,21 @@ def test_backward_takes_selected_ids_in_any_order(which):
     assert np.array_equal(a.topk_idx, b.topk_idx)
     for name in ("dq", "dk", "dv", "dgates"):
         util.assert_close(getattr(b, name), getattr(a, name), wl.dtype, name)
+
+
+@pytest.mark.parametrize("which", ["bf16_matrix_cores", "f32_generic"])
+def test_gates_of_any_sign_and_zero(which):
+    """Eq. (4) is linear in the gates, and the interface takes any real gate tensor (the gate predictor's sigmoid is
+    only one producer): negative gates, and gates that are exactly zero for a whole branch of some tokens, must give the
+    oracle's output and gradients (a zero gate: no contribution to out, dq, dk, dv, but a dgates entry all the same)."""
+    if which == "bf16_matrix_cores":
+        wl = inputs.random_points_workload(61, 32, (1100, 500), 16, 2, 64, (4, 8, 8), 5, "bf16")
+    else:
+        wl = inputs.random_points_workload(62, 16, (400, 250), 4, 2, 16, (2, 4, 4), 4, "f32")
+    rng = np.random.default_rng(5)
+    gates = rng.standard_normal(wl.gates.shape).astype(np.float32)
+    gates[rng.random(wl.gates.shape) < 0.15] = 0.0
+    gates[::7, :, 1] = 0.0  # every 7th token: selection branch switched off for all heads
+    wl.gates = inputs.round_to_bf16(gates) if wl.dtype == "bf16" else gates
+    assert (wl.gates < 0).any() and (wl.gates == 0).any()
+    full_parity(wl)
