@@ -108,8 +108,8 @@ __device__ inline void dq_tile(f32x4 (&acc)[CB][D / 16], const QRows<D, CB> &q, 
   for (int cb = 0; cb < CB; ++cb) s0[cb] = s1[cb] = p0[cb] = p1[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int ks = 0; ks < D / 32; ++ks) {
-    const bf16x8 k0 = p_row_operand<D, true>(kt, ln, 0, ks), k1 = p_row_operand<D, true>(kt, ln, 1, ks);
-    const bf16x8 v0 = p_row_operand<D, true>(vt, ln, 0, ks), v1 = p_row_operand<D, true>(vt, ln, 1, ks);
+    const bf16x8 k0 = p_row_operand<D>(kt, ln, 0, ks), k1 = p_row_operand<D>(kt, ln, 1, ks);
+    const bf16x8 v0 = p_row_operand<D>(vt, ln, 0, ks), v1 = p_row_operand<D>(vt, ln, 1, ks);
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
       if (act[cb]) {
@@ -136,7 +136,7 @@ __device__ inline void dq_tile(f32x4 (&acc)[CB][D / 16], const QRows<D, CB> &q, 
   }
 #pragma unroll
   for (int dt = 0; dt < D / 16; ++dt) {
-    const bf16x8 ktd = p_tr_operand<D, true>(kt, ln, dt);
+    const bf16x8 ktd = p_tr_operand<D>(kt, ln, dt);
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
       if (act[cb]) acc[cb][dt] = mfma16(ktd, dsb[cb], acc[cb][dt]);
@@ -225,7 +225,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
   for (int cb = 0; cb < CB; ++cb) {
     if (!q.valid[cb]) continue;
 #pragma unroll
-    for (int dt = 0; dt < D / 16; ++dt) *reinterpret_cast<f32x4 *>(a.dQp + rs_[cb] * D + 16 * dt + 4 * quad) = acc[cb][dt];
+    for (int dt = 0; dt < D / 16; ++dt) *reinterpret_cast<f32x4 *>(a.dQp + rs_[cb] * D + acc_dim(dt, quad)) = acc[cb][dt];
   }
 }
 
@@ -414,7 +414,7 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
       for (int sa = 0; sa < 2; ++sa)
 #pragma unroll
         for (int ks = 0; ks < D / 32; ++ks) {
-          const bf16x8 qa = p_row_operand<D, true>(Qt, ln, sa, ks), da = p_row_operand<D, true>(Dt, ln, sa, ks);
+          const bf16x8 qa = p_row_operand<D>(Qt, ln, sa, ks), da = p_row_operand<D>(Dt, ln, sa, ks);
 #pragma unroll
           for (int kbk = 0; kbk < KB; ++kbk) {
             s[kbk][sa] = mfma16(qa, kop[kbk][ks], s[kbk][sa]);
@@ -450,7 +450,7 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
         }
 #pragma unroll
       for (int dt = 0; dt < D / 16; ++dt) {
-        const bf16x8 qt = p_tr_operand<D, true>(Qt, ln, dt), dot = p_tr_operand<D, true>(Dt, ln, dt);
+        const bf16x8 qt = p_tr_operand<D>(Qt, ln, dt), dot = p_tr_operand<D>(Dt, ln, dt);
 #pragma unroll
         for (int kbk = 0; kbk < KB; ++kbk) {
           dv[kbk][dt] = mfma16(dot, pw[kbk], dv[kbk][dt]);
@@ -465,19 +465,19 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
                                                  // cost a wait for all outstanding loads per iteration)
   }
   if (!wave_on) return;
-  // --- store: lane holds dims 16*dt + 4*quad + i of key column n
+  // --- store: lane holds dims acc_dim(dt, quad) + i of key column n
 #pragma unroll
   for (int kbk = 0; kbk < KB; ++kbk) {
     const int key = k0 + 16 * kbk + n;
     if (key >= kend) continue;
-    size_t off = ((size_t)key * a.v.Hkv + g) * D + 4 * quad;
+    size_t off = ((size_t)key * a.v.Hkv + g) * D;
     if (MODE == DKV_CMP) off += (size_t)blockIdx.z * a.v.Nc * kstride;
-    if (MODE == DKV_SLC) off = (out_row0 + (size_t)(key - kbeg)) * D + 4 * quad;  // partial sums: [row][D]
+    if (MODE == DKV_SLC) off = (out_row0 + (size_t)(key - kbeg)) * D;  // partial sums: [row][D]
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt) {
-      *reinterpret_cast<float4 *>(a.dK + off + 16 * dt) =
+      *reinterpret_cast<float4 *>(a.dK + off + acc_dim(dt, quad)) =
           make_float4(dk[kbk][dt][0], dk[kbk][dt][1], dk[kbk][dt][2], dk[kbk][dt][3]);
-      *reinterpret_cast<float4 *>(a.dV + off + 16 * dt) =
+      *reinterpret_cast<float4 *>(a.dV + off + acc_dim(dt, quad)) =
           make_float4(dv[kbk][dt][0], dv[kbk][dt][1], dv[kbk][dt][2], dv[kbk][dt][3]);
     }
   }

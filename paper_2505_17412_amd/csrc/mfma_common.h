@@ -32,6 +32,15 @@ __device__ inline bf16x8 zero8() {
 __device__ inline f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
+// All-ones A operand of the matrix instruction (sums the 32 contraction entries of every column).  Build it once per
+// kernel: the empty asm makes the value opaque, so it stays in its four registers instead of being rebuilt with
+// three moves in front of every use.
+__device__ inline bf16x8 ones_operand() {
+  const float w1 = __builtin_bit_cast(float, 0x3F803F80u);  // two bf16 ones
+  f32x4 w = {w1, w1, w1, w1};
+  asm volatile("" : "+v"(w));
+  return __builtin_bit_cast(bf16x8, w);
+}
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ inline int wave_min_i(int v) {
@@ -60,13 +69,21 @@ __device__ inline float group_sum(float v, int hs) {
   return v;
 }
 
+// Dims of an accumulator whose rows came from a transposed tile operand.  The transposing LDS read takes the 16 rows
+// of dim block dt from two 16-byte segments of a row that lie 32 bytes apart (see PTile in mfma_qc.h: that pairing is
+// what keeps the read free of bank conflicts), so the block covers dims b .. b + 7 and b + 16 .. b + 23 with
+// b = 32*(dt >> 1) + 8*(dt & 1).  tr_dim: dim of row n of the block; acc_dim: the first of the 4 consecutive dims that a
+// lane of row group `quad` holds in its accumulator register of block dt (C layout: rows 4*quad .. +3).
+__device__ inline int tr_dim(int dt, int n) { return 32 * (dt >> 1) + 8 * (dt & 1) + 16 * (n >> 3) + (n & 7); }
+__device__ inline int acc_dim(int dt, int quad) { return tr_dim(dt, 4 * quad); }
+
 // Store the accumulator tile of one query column block to row-major rows of D bf16: on entry lane (n, quad) holds, for
-// every dim block dt, the 4 dims 16*dt + 4*quad .. +3 of column n (the C layout of the matrix instruction), i.e. 8 bytes
-// in each of D/16 places of its row.  A 4x4 transpose between the dim-block index and the quad index (two rounds of
-// lane-row swaps, v_permlane32_swap and v_permlane16_swap: lanes 32 and 16 apart hold the same column) leaves every
-// lane with 16 consecutive dims, so a row goes out as 32-byte pieces, four lanes covering 64 consecutive dims, instead
-// of 8-byte pieces.  `row`: this lane's row (column n); scale: factor applied before rounding; lanes with !valid take
-// part in the exchange and store nothing.  D = 64 or 128.
+// every dim block dt, the 4 dims acc_dim(dt, quad) .. +3 of column n, i.e. 8 bytes in each of D/16 places of its row.
+// Within a group of four dim blocks (64 dims) the dim index is 32*dt1 + 16*quad1 + 8*dt0 + 4*quad0 + i (dt1, dt0 and
+// quad1, quad0 the bits of dt & 3 and of quad): exchanging dt1 with quad0 (one round of v_permlane16_swap: lanes 16
+// apart hold the same column) leaves every lane with 16 consecutive dims, so a row goes out as 32-byte pieces, four
+// lanes covering 64 consecutive dims, instead of 8-byte pieces.  `row`: this lane's row (column n); scale: factor
+// applied before rounding; lanes with !valid take part in the exchange and store nothing.  D = 64 or 128.
 template <int D>
 __device__ inline void store_row_tile_if(bf16_t *row, const f32x4 (&o)[D / 16], float scale, bool valid) {
   static_assert(D % 64 == 0, "groups of four dim blocks");
@@ -84,25 +101,19 @@ __device__ inline void store_row_tile_if(bf16_t *row, const f32x4 (&o)[D / 16], 
       lo[j] = w[0];
       hi[j] = w[1];
     }
-    auto swap32 = [](unsigned &a, unsigned &b) {
-      const auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
-      a = r[0]; b = r[1];
-    };
-    auto swap16 = [](unsigned &a, unsigned &b) {
+    auto swap16 = [](unsigned &a, unsigned &b) {  // odd 16-lane rows of a <-> even 16-lane rows of b
       const auto r = __builtin_amdgcn_permlane16_swap(a, b, false, false);
       a = r[0]; b = r[1];
     };
-    // bit 1 of the dim-block index <-> bit 1 of quad, then bit 0 <-> bit 0
-    swap32(lo[0], lo[2]); swap32(hi[0], hi[2]); swap32(lo[1], lo[3]); swap32(hi[1], hi[3]);
-    swap16(lo[0], lo[1]); swap16(hi[0], hi[1]); swap16(lo[2], lo[3]); swap16(hi[2], hi[3]);
-    // register j now holds the group that came from quad j of dim block `quad`: dims 64*h + 16*quad + 4*j .. +3
+    swap16(lo[0], lo[2]); swap16(hi[0], hi[2]); swap16(lo[1], lo[3]); swap16(hi[1], hi[3]);
+    // register j = 2*j1 + j0 now holds dims 64*h + 32*quad0 + 16*quad1 + 8*j0 + 4*j1 .. +3
     typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
     if (valid) {
-      u32x4 *dst = reinterpret_cast<u32x4 *>(row + 64 * h + 16 * quad);
+      u32x4 *dst = reinterpret_cast<u32x4 *>(row + 64 * h + 32 * (quad & 1) + 16 * (quad >> 1));
       // written once, read once much later by the merge kernel: streaming stores, so the rows do not push the query
       // rows (which every selected block reads again) out of the caches
-      __builtin_nontemporal_store(u32x4{lo[0], hi[0], lo[1], hi[1]}, dst);
-      __builtin_nontemporal_store(u32x4{lo[2], hi[2], lo[3], hi[3]}, dst + 1);
+      __builtin_nontemporal_store(u32x4{lo[0], hi[0], lo[2], hi[2]}, dst);
+      __builtin_nontemporal_store(u32x4{lo[1], hi[1], lo[3], hi[3]}, dst + 1);
     }
   }
 }
@@ -121,7 +132,7 @@ __device__ inline void store_partial_row(bf16_t *row, const f32x4 (&o)[D / 16], 
         bf16x4 x;
 #pragma unroll
         for (int i = 0; i < 4; ++i) x[i] = (__bf16)o[dt][i];
-        *reinterpret_cast<bf16x4 *>(row + 16 * dt + 4 * quad) = x;
+        *reinterpret_cast<bf16x4 *>(row + acc_dim(dt, quad)) = x;
       }
     }
   }

@@ -36,7 +36,7 @@ __device__ inline void score_tile(lds_cptr kt, const typename PTile<D>::Lanes &l
   for (int cb = 0; cb < CB; ++cb) s0[cb] = s1[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int ks = 0; ks < D / 32; ++ks) {
-    const bf16x8 a0 = p_row_operand<D, true>(kt, ln, 0, ks), a1 = p_row_operand<D, true>(kt, ln, 1, ks);
+    const bf16x8 a0 = p_row_operand<D>(kt, ln, 0, ks), a1 = p_row_operand<D>(kt, ln, 1, ks);
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
       if (act[cb]) {
@@ -65,13 +65,11 @@ template <int D, int CB, bool MASK>
 __device__ inline void fwd_tile(FwdState<D, CB> &st, const QRows<D, CB> &q, lds_cptr kt, lds_cptr vt,
                                 const typename PTile<D>::Lanes &ln, int kb,
                                 const int (&lo)[CB], const int (&hi)[CB], const bool (&on)[CB], const bool (&act)[CB],
-                                float sl2, float slack) {
+                                float sl2, float slack, const bf16x8 &ones) {
   const int quad = threadIdx.x >> 4 & 3;
   float s[CB][8];
   score_tile<D, CB>(kt, ln, q, act, s);
-  bf16x8 pb[CB], ones;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) ones[j] = (__bf16)1.0f;
+  bf16x8 pb[CB];
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb) {
     if (!act[cb]) continue;
@@ -106,7 +104,7 @@ __device__ inline void fwd_tile(FwdState<D, CB> &st, const QRows<D, CB> &q, lds_
   }
 #pragma unroll
   for (int dt = 0; dt < D / 16; ++dt) {
-    const bf16x8 av = p_tr_operand<D, true>(vt, ln, dt);
+    const bf16x8 av = p_tr_operand<D>(vt, ln, dt);
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
       if (act[cb]) st.o[cb][dt] = mfma16(av, pb[cb], st.o[cb][dt]);
@@ -123,13 +121,13 @@ __device__ inline void finish(const FwdArgs &a, FwdState<D, CB> &st, int branch,
     const float inv = l > 0.f ? 1.0f / l : 0.f;
     lse2[cb] = l > 0.f ? st.m[cb] * a.v.sl2 + __log2f(l) : -INFINITY;
     if (q.valid[cb]) {
-      bf16_t *o = a.Ob + (((size_t)branch * a.v.N + q.tok[cb]) * a.v.Hq + q.h[cb]) * D + 4 * quad;
+      bf16_t *o = a.Ob + (((size_t)branch * a.v.N + q.tok[cb]) * a.v.Hq + q.h[cb]) * D;
 #pragma unroll
       for (int dt = 0; dt < D / 16; ++dt) {
         bf16x4 w;
 #pragma unroll
         for (int i = 0; i < 4; ++i) w[i] = (__bf16)(st.o[cb][dt][i] * inv);
-        *reinterpret_cast<bf16x4 *>(o + 16 * dt) = w;
+        *reinterpret_cast<bf16x4 *>(o + acc_dim(dt, quad)) = w;
       }
       if (quad == 0) a.lse[((size_t)branch * a.v.N + q.tok[cb]) * a.v.Hq + q.h[cb]] = lse2[cb] * LN2;
     }
@@ -185,15 +183,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
   TileSrc<2> src{{a.v.Kc + (size_t)g * D, a.v.Vc + (size_t)g * D}, (uint32_t)(a.v.Hkv * D)};
   FwdState<D, CB> st;
   init_state(st);
+  const bf16x8 ones = ones_operand();
   const float sl2 = a.v.sl2;
   const typename PTile<D>::Lanes ln = PTile<D>::lanes();
   run_pipeline<D, 2>(
       src, stage0, ints + 4, ints + 5, nr, [](int) {},
       [&](const bf16_t *stg, int kb, int) {
         if (uniform && kb >= rs && kb + 32 <= re)
-          fwd_tile<D, CB, false>(st, q, (lds_cptr)L::row_tile((bf16_t *)stg, 0), (lds_cptr)L::row_tile((bf16_t *)stg, 1), ln, kb, lo, hi, on, act, sl2, slack);
+          fwd_tile<D, CB, false>(st, q, (lds_cptr)L::row_tile((bf16_t *)stg, 0), (lds_cptr)L::row_tile((bf16_t *)stg, 1), ln, kb, lo, hi, on, act, sl2, slack, ones);
         else
-          fwd_tile<D, CB, true>(st, q, (lds_cptr)L::row_tile((bf16_t *)stg, 0), (lds_cptr)L::row_tile((bf16_t *)stg, 1), ln, kb, lo, hi, on, act, sl2, slack);
+          fwd_tile<D, CB, true>(st, q, (lds_cptr)L::row_tile((bf16_t *)stg, 0), (lds_cptr)L::row_tile((bf16_t *)stg, 1), ln, kb, lo, hi, on, act, sl2, slack, ones);
       });
   float lse2[CB];
   finish<D, CB>(a, st, 0, q, lse2);
@@ -246,7 +245,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
               for (int cb = 0; cb < CB; ++cb) c[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
               for (int ks = 0; ks < D / 32; ++ks) {
-                const bf16x8 kop = p_row_operand<D, true>((lds_cptr)stg, ln, sub, ks);
+                const bf16x8 kop = p_row_operand<D>((lds_cptr)stg, ln, sub, ks);
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb) c[cb] = mfma16(q.qop[cb][ks], kop, c[cb]);
               }
@@ -338,15 +337,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 64 ? 4
   TileSrc<2> src{{a.v.Ks + (size_t)g * D, a.v.Vs + (size_t)g * D}, (uint32_t)(a.v.Hkv * D)};
   FwdState<D, CB> st;
   init_state(st);
+  const bf16x8 ones = ones_operand();
   const float sl2 = a.v.sl2;
   const typename PTile<D>::Lanes ln = PTile<D>::lanes();
   run_pipeline<D, 2>(
       src, stage0, ints + 4, ints + 5, re > rs ? 1 : 0, [](int) {},
       [&](const bf16_t *stg, int kb, int) {
         if (uniform && kb >= rs && kb + 32 <= re)
-          fwd_tile<D, CB, false>(st, q, (lds_cptr)L::row_tile((bf16_t *)stg, 0), (lds_cptr)L::row_tile((bf16_t *)stg, 1), ln, kb, lo, hi, on, act, sl2, slack);
+          fwd_tile<D, CB, false>(st, q, (lds_cptr)L::row_tile((bf16_t *)stg, 0), (lds_cptr)L::row_tile((bf16_t *)stg, 1), ln, kb, lo, hi, on, act, sl2, slack, ones);
         else
-          fwd_tile<D, CB, true>(st, q, (lds_cptr)L::row_tile((bf16_t *)stg, 0), (lds_cptr)L::row_tile((bf16_t *)stg, 1), ln, kb, lo, hi, on, act, sl2, slack);
+          fwd_tile<D, CB, true>(st, q, (lds_cptr)L::row_tile((bf16_t *)stg, 0), (lds_cptr)L::row_tile((bf16_t *)stg, 1), ln, kb, lo, hi, on, act, sl2, slack, ones);
       });
   float lse2[CB];
   finish<D, CB>(a, st, 2, q, lse2);

@@ -34,12 +34,21 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 
 // Tile layout of the attention kernels in LDS.  A 32-row tile of a row-major bf16 array is kept as D/8 planes of 512
 // bytes, one per 16-byte segment of a row; a plane holds the 32 rows' segments in the slot order sigma(row) (the order
-// in which the lanes of the two 16-row matrix sub-tiles read them).  With SWZ the slot is XORed with (segment & 7):
-// the 8 threads that stage one row (8 planes, 512 bytes apart) then land in 8 different 16-byte bank groups, which
-// matters for kernels that restage tiles all the time; kernels that stage a block once and read it many times take
-// the plain form, whose transposing reads are a little faster.  (Measured per wave instruction on one CU with 8 waves:
-// row read 2.4 ns either way, transposing read 2.05 ns swizzled / 1.8 ns plain, staging write 6.1 ns swizzled /
-// 27 ns plain; padding the planes instead of swizzling slows the row reads to 3.5 ns.)
+// in which the lanes of the two 16-row matrix sub-tiles read them).  The slot is XORed with a per-plane constant,
+// swz(seg), chosen so that all three access patterns are free of LDS bank conflicts (measured with the LDS counters:
+// 0 conflict cycles per instruction for each):
+//   * staging writes: the 8 threads that stage one row write 8 planes, 512 bytes apart; the low three bits of swz
+//     (seg & 7, present with SWZ only) put them in 8 different 16-byte bank groups.  Kernels that stage a block once
+//     and read it many times leave them out (SWZ = false): their lane offsets then differ between contraction steps
+//     and between dim blocks by constants only, which saves the registers that hold them;
+//   * row operands (16-byte reads): the four quads of a wavefront read planes 4*ks .. 4*ks + 3, each 16 consecutive
+//     slots; the two quads served together (0,1 and 2,3) must not differ in bit 3 of swz, so that bit is the same for
+//     segments 4*ks, 4*ks + 1 and for 4*ks + 2, 4*ks + 3;
+//   * transposed operands (8-byte transposing reads): one read takes 4-element pieces from TWO planes; planes whose
+//     swz agrees in bit 3 would collide (they are a multiple of 512 bytes apart), so a dim block pairs segment s with
+//     segment s + 2, whose bit 3 differs.  The 16 output rows of dim block dt are therefore not the dims 16*dt .. +15
+//     but tr_dim(dt, 0..15): dims 8*s .. 8*s + 7 and 8*s + 16 .. 8*s + 23 with s = tr_seg(dt).  Every consumer of an
+//     accumulator indexed by dt goes through acc_dim() (mfma_common.h), which states the same map per lane.
 // Operand addresses are lane part + compile-time constant: the lane part depends on the contraction step (row
 // operands) or the output-dim block (transposed operands) only through the swizzle, so a kernel keeps D/32 + D/16
 // lane offsets in registers (Lanes) and the sub-tile, the row half, the tile index and the LDS stage all move the
@@ -50,11 +59,14 @@ struct PTile {
   static constexpr int PLANE_B = 512;            // bytes per plane: 32 row slots of 16 bytes
   static constexpr int BYTES = SEGS * PLANE_B;   // bytes per 32-row tile
   static constexpr int ITEMS = 32 * SEGS;        // 16-byte items per tile
-  __device__ static inline int slot_off(int slot, int seg) { return seg * PLANE_B + ((SWZ ? slot ^ (seg & 7) : slot) << 4); }
+  __device__ static inline int swz(int seg) { return (SWZ ? seg & 7 : 0) ^ (((seg >> 1) & 1) << 3); }
+  __device__ static inline int slot_off(int slot, int seg) { return seg * PLANE_B + ((slot ^ swz(seg)) << 4); }
   __device__ static inline int off(int row, int seg) { return slot_off(TileGeom<D>::sigma(row), seg); }
+  // first of the two segments (s, s + 2) that dim block dt of a transposed operand is read from
+  __device__ static inline int tr_seg(int dt) { return 4 * (dt >> 1) + (dt & 1); }
   struct Lanes {
     int row[D / 32];  // row operand (rows = the tile's rows), contraction step ks; sub-tile a adds a*256
-    int tr[D / 16];   // transposed operand (rows = dims 16*dt + n, contraction over rows 8*quad .. +7); rows +4 .. +7 add 256
+    int tr[D / 16];   // transposed operand (rows = dims tr_dim(dt, n), contraction over rows 8*quad .. +7); rows +4 .. +7 add 256
   };
   __device__ static inline Lanes lanes() {
     const int n = threadIdx.x & 15, quad = threadIdx.x >> 4 & 3;
@@ -62,7 +74,7 @@ struct PTile {
 #pragma unroll
     for (int ks = 0; ks < D / 32; ++ks) l.row[ks] = slot_off(n, 4 * ks + quad);
 #pragma unroll
-    for (int dt = 0; dt < D / 16; ++dt) l.tr[dt] = slot_off(4 * quad + (n >> 2), 2 * dt + ((n & 3) >> 1)) + (n & 1) * 8;
+    for (int dt = 0; dt < D / 16; ++dt) l.tr[dt] = slot_off(4 * quad + (n >> 2), tr_seg(dt) + ((n & 3) >> 1) * 2) + (n & 1) * 8;
     return l;
   }
 };
@@ -70,17 +82,18 @@ struct PTile {
 typedef const __attribute__((address_space(3))) unsigned char *lds_cptr;
 
 // A operand of sub-tile a, contraction step ks (row = key, see tile_key_row) from the tile at `tile` (uniform address).
-template <int D, bool SWZ>
+template <int D, bool SWZ = true>
 __device__ inline bf16x8 p_row_operand(lds_cptr tile, const typename PTile<D, SWZ>::Lanes &l, int a, int ks) {
   return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8 *>(tile + l.row[ks] + a * 256);
 }
 
-// Transposed A operand (row = dim 16*dt + n, contraction over the tile's rows 8*quad .. +7), taken from the same
+// Transposed A operand (row n = dim tr_dim(dt, n), contraction over the tile's rows 8*quad .. +7), taken from the same
 // row-major tile with the transposing LDS read of gfx950 (ds_read_b64_tr_b16): inside a 16-lane group lane p hands in
 // the address of 4 consecutive elements and lane i receives element (i & 3) of lanes (i >> 2), 4 + (i >> 2),
-// 8 + (i >> 2), 12 + (i >> 2).  With lane p pointing at row 8*quad + (p >> 2), dims 16*dt + 4*(p & 3) .. +3, lane i
-// ends up with dim 16*dt + i of rows 8*quad .. +3; a second read covers rows +4 .. +7.
-template <int D, bool SWZ>
+// 8 + (i >> 2), 12 + (i >> 2).  With lane p pointing at row 8*quad + (p >> 2) and at the 4-dim piece (p & 3) of the
+// block (pieces 0, 1 in segment tr_seg(dt), pieces 2, 3 in the segment two further), lane i ends up with dim
+// tr_dim(dt, i) of rows 8*quad .. +3; a second read covers rows +4 .. +7.
+template <int D, bool SWZ = true>
 __device__ inline bf16x8 p_tr_operand(lds_cptr tile, const typename PTile<D, SWZ>::Lanes &l, int dt) {
   typedef __attribute__((address_space(3))) s16x4 *tr_ptr;
   const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tr_ptr)(tile + l.tr[dt]));
@@ -247,7 +260,7 @@ __device__ inline void load_rows(const bf16_t *Q, const MfmaView &v, int wg_pos0
 // the block-centric selection kernel.
 template <int D, int CB>
 struct FwdState {
-  f32x4 o[CB][D / 16];  // o[cb][dt][i]: output dim 16*dt + 4*quad + i of query column n
+  f32x4 o[CB][D / 16];  // o[cb][dt][i]: output dim acc_dim(dt, quad) + i of query column n
   f32x4 l[CB];          // l[cb][0]: running sum of column n over all keys seen (the other three elements are unused)
   float m[CB];          // running max (raw score units)
 };

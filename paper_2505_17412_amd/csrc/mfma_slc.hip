@@ -126,9 +126,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
   const int n_it = (cnt + tpw - 1) / tpw;
   const uint32_t kstride = (uint32_t)(Hkv * D);
   const float sl2 = a.v.sl2, slack = 8.0f / sl2;
-  bf16x8 ones;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) ones[j] = (__bf16)1.0f;
+  const bf16x8 ones = ones_operand();
   const typename P::Lanes ln = P::lanes();
   const lds_cptr kl = (lds_cptr)Kt, vl = (lds_cptr)Vt;
   __syncthreads();
@@ -153,7 +151,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
         st.l[0][0] = ml.y;
 #pragma unroll
         for (int dt = 0; dt < D / 16; ++dt) {
-          const bf16x4 x = *reinterpret_cast<const bf16x4 *>(a.po + (size_t)cur.prow * D + 16 * dt + 4 * quad);
+          const bf16x4 x = *reinterpret_cast<const bf16x4 *>(a.po + (size_t)cur.prow * D + acc_dim(dt, quad));
 #pragma unroll
           for (int i = 0; i < 4; ++i) st.o[0][dt][i] = (float)x[i];
         }
@@ -347,7 +345,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
       if (k0 > kbeg && cur.valid) {  // continue from the partial of the earlier segments
 #pragma unroll
         for (int dt = 0; dt < D / 16; ++dt) {
-          const bf16x4 x = *reinterpret_cast<const bf16x4 *>(a.pdq + (size_t)cur.prow * D + 16 * dt + 4 * quad);
+          const bf16x4 x = *reinterpret_cast<const bf16x4 *>(a.pdq + (size_t)cur.prow * D + acc_dim(dt, quad));
 #pragma unroll
           for (int i = 0; i < 4; ++i) acc[dt][i] = (float)x[i];
         }
