@@ -34,7 +34,7 @@ struct PreArgs {
   int N, Hq, Hkv, hs, D;
   bf16_t *dgates;               // [N,Hq,3] caller order
   float *lse2s, *deltas, *gws;  // [3][N(pos)][Hq]
-  bf16_t *Qs, *dOs;             // [N(pos)][Hq][D] sorted row-major copies
+  bf16_t *Qs, *dOg;             // sorted row-major copies: Q [N(pos)][Hq][D], gate_b * dO [3][N(pos)][Hq][D]
 };
 
 __global__ __launch_bounds__(256) void m_bwd_pre(PreArgs a) {
@@ -43,11 +43,21 @@ __global__ __launch_bounds__(256) void m_bwd_pre(PreArgs a) {
   const int HD = a.Hq * a.D;
   const size_t base = (size_t)tok * HD;
   bf16_t *td = tile;
+  // The kernels that contract over dO rows of one branch (selection dQ, all dK/dV) take gate_b * dO: with it
+  // dP_b = gate_b * (dO V^T) and dV_b = P^T (gate_b * dO) carry the gate of eq. (4) without any per-row multiplication.
   for (int e = threadIdx.x * 8; e < HD; e += blockDim.x * 8) {
     const bf16x8 xq = ld8(a.Q + base + e), xd = ld8(a.dO + base + e);
     *reinterpret_cast<bf16x8 *>(td + e) = xd;
     *reinterpret_cast<bf16x8 *>(a.Qs + (size_t)pos * HD + e) = xq;
-    *reinterpret_cast<bf16x8 *>(a.dOs + (size_t)pos * HD + e) = xd;
+    const bf16_t *gt = a.gates + ((size_t)tok * a.Hq + e / a.D) * 3;
+#pragma unroll
+    for (int b = 0; b < 3; ++b) {
+      const float w = bf16_to_f32(gt[b]);
+      bf16x8 y;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) y[j] = (__bf16)(w * (float)xd[j]);
+      *reinterpret_cast<bf16x8 *>(a.dOg + ((size_t)b * a.N + pos) * HD + e) = y;
+    }
   }
   __syncthreads();
   // dgates and the row scalars: D/8 lanes per head (8 elements each), 256 / (D/8) heads per pass
@@ -236,8 +246,8 @@ enum { DKV_WIN = 0, DKV_SLC = 1, DKV_CMP = 2 };
 
 struct DkvArgs {
   MfmaView v;
-  const bf16_t *Qs, *dOs;             // sorted copies: [N(pos)][Hq][D]
-  const float *lse2s, *deltas, *gws;  // already offset to the branch: [N(pos)][Hq]
+  const bf16_t *Qs, *dOs;             // sorted copies [N(pos)][Hq][D]: Q, and the branch's gate * dO
+  const float *lse2s, *deltas;        // already offset to the branch: [N(pos)][Hq]
   const int32_t *sel_start, *sel_list;  // selection branch: query positions per (g, block)
   float *dK, *dV;                       // [rows][Hkv][D] fp32 (rows: sorted tokens, or compression blocks)
   const int32_t *chunk_start;           // selection branch: [Hkv*Ns+1] first work chunk of each (g, block)
@@ -248,13 +258,14 @@ struct DkvArgs {
   int q_splits;                         // compression branch: query range split into this many parts
 };
 
-// LDS stage of the dK/dV kernels: ST tiles of 32 query rows each, of Q and of dO (PTile layout: read both as they are
-// and through the transposing LDS load), and the rows' scalars (lse in log2 units, -delta*scale, gate, gate*scale:
-// the products are formed once by the staging thread instead of by every lane of every wavefront).
+// LDS stage of the dK/dV kernels: ST tiles of 32 query rows each, of Q and of gate * dO (PTile layout: read both as
+// they are and through the transposing LDS load), and two scalars per row: lse in log2 units and -delta*scale (the
+// product is formed once by the staging thread instead of by every lane of every wavefront).  The gate needs no
+// scalar of its own: it rides on the dO rows, so dP = (gate dO) V^T and dV += P^T (gate dO) already carry it.
 template <int D, int ST>
 struct DkvStage {
   static constexpr int TILES_B = 2 * ST * PTile<D>::BYTES;  // Q tiles, then dO tiles
-  static constexpr int BYTES = TILES_B + 4 * 32 * ST * 4;   // + [4][32*ST] floats
+  static constexpr int BYTES = TILES_B + 2 * 32 * ST * 4;   // + [2][32*ST] floats
 };
 
 // A workgroup owns 16*KB*NW keys of one block (16*KB per wavefront, held in registers as MFMA B operands with their
@@ -338,12 +349,12 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
     it_slot[i] = rt * slots + row / hs;
     it_col[i] = (g * hs + row % hs) * D + seg * 8;
   }
-  static_assert(4 * 32 * ST <= NTHR, "one scalar per thread and stage");
-  const bool has_sc = threadIdx.x < 4 * 32 * ST;
-  const int sc_arr = threadIdx.x / (32 * ST), sc_r = threadIdx.x % (32 * ST);
+  static_assert(2 * 32 * ST <= NTHR, "one scalar per thread and stage");
+  const bool has_sc = threadIdx.x < 2 * 32 * ST;
+  const int sc_arr = (threadIdx.x / (32 * ST)) & 1, sc_r = threadIdx.x % (32 * ST);
   const int sc_slot = (sc_r >> 5) * slots + (sc_r & 31) / hs, sc_head = g * hs + (sc_r & 31) % hs;
-  const float *sc_src = sc_arr == 0 ? a.lse2s : (sc_arr == 1 ? a.deltas : a.gws);
-  const float sc_mul = sc_arr == 1 ? -scale : (sc_arr == 3 ? scale : 1.0f);
+  const float *sc_src = sc_arr == 0 ? a.lse2s : a.deltas;
+  const float sc_mul = sc_arr == 1 ? -scale : 1.0f;
   // sorted position of the token at list index li (-1: past the end)
   // (every load of the staging code is unconditional, with a clamped index: loads under a branch would make the
   // compiler wait for ALL outstanding loads at the next use instead of for the oldest ones)
@@ -422,19 +433,15 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
           }
         }
       // this lane's eight consecutive query rows 8*quad .. +7 of the tile
-      float lse2[8], nds[8], gw[8], gws[8];  // lse (log2 units), -delta*scale, gate, gate*scale
+      float lse2[8], nds[8];  // lse (log2 units), -delta*scale
       {
         typedef const __attribute__((address_space(3))) f32x4 *f4p;
         const f32x4 l0 = *(f4p)(scal + 32 * rt), l1 = *(f4p)(scal + 32 * rt + 4);
         const f32x4 d0 = *(f4p)(scal + 32 * (ST + rt)), d1 = *(f4p)(scal + 32 * (ST + rt) + 4);
-        const f32x4 g0 = *(f4p)(scal + 32 * (2 * ST + rt)), g1 = *(f4p)(scal + 32 * (2 * ST + rt) + 4);
-        const f32x4 h0 = *(f4p)(scal + 32 * (3 * ST + rt)), h1 = *(f4p)(scal + 32 * (3 * ST + rt) + 4);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           lse2[j] = l0[j]; lse2[4 + j] = l1[j];
           nds[j] = d0[j]; nds[4 + j] = d1[j];
-          gw[j] = g0[j]; gw[4 + j] = g1[j];
-          gws[j] = h0[j]; gws[4 + j] = h1[j];
         }
       }
       bf16x8 pw[KB], ds[KB];
@@ -443,10 +450,10 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           const float sv = j < 4 ? s[kbk][0][j & 3] : s[kbk][1][j & 3];
-          const float dpv = j < 4 ? dp[kbk][0][j & 3] : dp[kbk][1][j & 3];
+          const float dpv = j < 4 ? dp[kbk][0][j & 3] : dp[kbk][1][j & 3];  // gate * dP
           const float p = fast_exp2(__builtin_fmaf(sv, sl2, -lse2[j]));
-          pw[kbk][j] = (__bf16)(p * gw[j]);
-          ds[kbk][j] = (__bf16)(p * __builtin_fmaf(gws[j], dpv, nds[j]));
+          pw[kbk][j] = (__bf16)p;
+          ds[kbk][j] = (__bf16)(p * __builtin_fmaf(scale, dpv, nds[j]));
         }
 #pragma unroll
       for (int dt = 0; dt < D / 16; ++dt) {
@@ -566,7 +573,7 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
   {
     ProfScope ps(PROF_BWD_PRE, s);
     PreArgs a{(const bf16_t *)q, (const bf16_t *)dout, (const bf16_t *)out_branch, (const bf16_t *)gates, lse, v.perm,
-              N, Hq, Hkv, v.hs, D, (bf16_t *)dgates, w.lse2s, w.deltas, w.gws, w.Qs, w.dOs};
+              N, Hq, Hkv, v.hs, D, (bf16_t *)dgates, w.lse2s, w.deltas, w.gws, w.Qs, w.dOg};
     m_bwd_pre<<<N, 256, (size_t)Hq * D * sizeof(bf16_t), s>>>(a);
   }
   static std::once_flag dq_once;  // raise the dynamic LDS limit once per process for this instantiation
@@ -607,19 +614,19 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
     (void)hipFuncSetAttribute((const void *)m_bwd_dkv<D, KB_KEYS, DKV_SLC, DKV_WAVES, ST>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     (void)hipFuncSetAttribute((const void *)m_bwd_dkv<D, KB_KEYS, DKV_CMP, DKV_WAVES_CMP, ST>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
   });
-  DkvArgs base{v, w.Qs, w.dOs, nullptr, nullptr, nullptr, w.sel.start, w.sel.list,
+  DkvArgs base{v, w.Qs, nullptr, nullptr, nullptr, w.sel.start, w.sel.list,
                w.dKs, w.dVs, w.sel.chunk_start, w.sel.order, w.sel.part_row_start, w.sel.chunk_len, 1, 1};
   {
     ProfScope ps(PROF_BWD_DKV_WIN, s);
     DkvArgs a = base;
-    a.lse2s = w.lse2s + 2 * NH; a.deltas = w.deltas + 2 * NH; a.gws = w.gws + 2 * NH;
+    a.lse2s = w.lse2s + 2 * NH; a.deltas = w.deltas + 2 * NH; a.dOs = w.dOg + 2 * NH * D;
     a.tiles_per_block = (blk->win_tok_max + WG_KEYS - 1) / WG_KEYS;
     m_bwd_dkv<D, KB_KEYS, DKV_WIN, DKV_WAVES, ST><<<dim3(blk->Nw * a.tiles_per_block, Hkv), 64 * DKV_WAVES, dkv_lds, s>>>(a);
   }
   {
     ProfScope ps(PROF_BWD_DKV_SLC, s);
     DkvArgs a = base;
-    a.lse2s = w.lse2s + NH; a.deltas = w.deltas + NH; a.gws = w.gws + NH;
+    a.lse2s = w.lse2s + NH; a.deltas = w.deltas + NH; a.dOs = w.dOg + NH * D;
     a.dK = w.pK; a.dV = w.pV;
     a.tiles_per_block = (blk->slc_tok_max + WG_KEYS - 1) / WG_KEYS;
     m_bwd_dkv<D, KB_KEYS, DKV_SLC, DKV_WAVES, ST><<<dim3((w.max_chunks + 7) / 8 * 8 * a.tiles_per_block), 64 * DKV_WAVES, dkv_lds, s>>>(a);
@@ -630,7 +637,7 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
   {
     ProfScope ps(PROF_BWD_DKV_CMP, s);
     DkvArgs a = base;
-    a.lse2s = w.lse2s; a.deltas = w.deltas; a.gws = w.gws;
+    a.lse2s = w.lse2s; a.deltas = w.deltas; a.dOs = w.dOg;
     a.dK = w.dKc; a.dV = w.dVc;
     a.tiles_per_block = (blk->c_max + WG_KEYS_CMP - 1) / WG_KEYS_CMP;
     a.q_splits = w.q_splits;

@@ -42,7 +42,7 @@ int slc_merge_kernel(const MfmaView &v, int D, const SlcPartials &part, const in
 // Device buffers of the backward pass (carved from the caller's workspace).
 struct BwdBuffers {
   float *lse2s, *deltas, *gws;  // [3][N(pos)][Hq]: lse*log2(e), gate*<dO,O_b>, gate
-  bf16_t *Qs, *dOs;             // [N(pos)][Hq][D]: Q and dO in sorted token order
+  bf16_t *Qs, *dOg;             // sorted token order: Q [N(pos)][Hq][D]; gate_b * dO [3][N(pos)][Hq][D], one copy per branch b
   float *dKs, *dVs;             // [N(pos)][Hkv][D] token-level gradients in sorted order
   float *dQp;                   // [N(pos)][Hq][D] compression-branch part of dQ (fp32)
   float *dKc, *dVc;             // [q_splits][Nc][Hkv][D] partial gradients of the pooled keys/values

@@ -232,8 +232,8 @@ __global__ __launch_bounds__(256) void m_slc_merge(MergeArgs a) {
 // ---------------------------------------------------------------------------------------------------------
 struct BcDqArgs {
   MfmaView v;
-  const bf16_t *Qs, *dOs;             // [N(pos)][Hq][D] sorted copies
-  const float *lse2s, *deltas, *gws;  // selection branch: [N(pos)][Hq]
+  const bf16_t *Qs, *dOs;             // [N(pos)][Hq][D] sorted copies: Q, and the selection gate times dO
+  const float *lse2s, *deltas;        // selection branch: [N(pos)][Hq]
   const int32_t *idx;                 // [N,Hkv,T]
   const int32_t *sel_start, *sel_list, *chunk_start, *chunk_order;
   bf16_t *pdq;                        // [N(pos)][Hkv][T][hs][D]
@@ -242,7 +242,7 @@ struct BcDqArgs {
 template <int D>
 struct BcDqRows {
   bf16x8 qop[D / 32], dop[D / 32];
-  float lse2, gws, dls;  // lse in log2 units; gate and delta with the softmax scale folded in
+  float lse2, dls;  // lse in log2 units; delta (gate * <dO, O>) with the softmax scale folded in
   uint32_t prow;         // ((pos*Hkv + g)*T + rank)*hs + head
   bool valid;
 };
@@ -261,16 +261,15 @@ __device__ inline void bc_dq_load_rows(const BcDqArgs &a, const int *tl, const i
     r.dop[ks] = r.valid ? ld8(a.dOs + th * D + 8 * quad + 32 * ks) : zero8();
   }
   r.lse2 = r.valid ? a.lse2s[th] : INFINITY;  // a missing column gets P = exp2(-inf) = 0
-  r.gws = a.gws[th] * a.v.scale;
   r.dls = a.deltas[th] * a.v.scale;
   r.prow = (uint32_t)((((size_t)pos * a.v.Hkv + g) * a.v.T + rank) * hs + hl);
 }
 
-// One 32-key LDS tile: transposed scores (K rows) and dP (V rows), dS^T = P (gate dP - delta) scale, then
+// One 32-key LDS tile: transposed scores (K rows) and dP (V rows, against gate * dO), dS^T = P (dP - delta) scale, then
 // dQ^T += K^T dS^T with K^T read from the same K tile through the transposing LDS load.
 template <int D, bool MASK>
 __device__ inline void bc_dq_tile(f32x4 (&acc)[D / 16], const BcDqRows<D> &r, lds_cptr kt, lds_cptr vt,
-                                  const typename PTile<D, false>::Lanes &ln, int key0, int nk, float sl2) {
+                                  const typename PTile<D, false>::Lanes &ln, int key0, int nk, float sl2, float scale) {
   f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0, p0 = s0, p1 = s0;
 #pragma unroll
   for (int ks = 0; ks < D / 32; ++ks) {
@@ -286,7 +285,7 @@ __device__ inline void bc_dq_tile(f32x4 (&acc)[D / 16], const BcDqRows<D> &r, ld
     const float sv = j < 4 ? s0[j & 3] : s1[j & 3], dp = j < 4 ? p0[j & 3] : p1[j & 3];
     float p = fast_exp2(__builtin_fmaf(sv, sl2, -r.lse2));
     if (MASK && first + j >= nk) p = 0.f;
-    ds[j] = (__bf16)(p * __builtin_fmaf(r.gws, dp, -r.dls));
+    ds[j] = (__bf16)(p * __builtin_fmaf(scale, dp, -r.dls));  // dp already carries the gate: the dO rows are gate * dO
   }
 #pragma unroll
   for (int dt = 0; dt < D / 16; ++dt) acc[dt] = mfma16(p_tr_operand<D, false>(kt, ln, dt), ds, acc[dt]);
@@ -322,7 +321,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
   const int tpw = 16 / hs;
   const int n_it = (cnt + tpw - 1) / tpw;
   const uint32_t kstride = (uint32_t)(Hkv * D);
-  const float sl2 = a.v.sl2;
+  const float sl2 = a.v.sl2, scale = a.v.scale;
   const typename P::Lanes ln = P::lanes();
   const lds_cptr kt = (lds_cptr)Kt, vt = (lds_cptr)Vt;
   __syncthreads();
@@ -352,8 +351,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
       }
 #pragma unroll
       for (int t = 0; t < MAXT; ++t)
-        if (t < nfull) bc_dq_tile<D, false>(acc, cur, kt + t * P::BYTES, vt + t * P::BYTES, ln, 32 * t, nk, sl2);
-      if (nk & 31) bc_dq_tile<D, true>(acc, cur, kt + nfull * P::BYTES, vt + nfull * P::BYTES, ln, 32 * nfull, nk, sl2);
+        if (t < nfull) bc_dq_tile<D, false>(acc, cur, kt + t * P::BYTES, vt + t * P::BYTES, ln, 32 * t, nk, sl2, scale);
+      if (nk & 31) bc_dq_tile<D, true>(acc, cur, kt + nfull * P::BYTES, vt + nfull * P::BYTES, ln, 32 * nfull, nk, sl2, scale);
       store_partial_row<D>(a.pdq + (size_t)cur.prow * D, acc, cur.valid);
       cur = nxt;
     }
@@ -427,7 +426,7 @@ int launch_slc_dq(const MfmaView &v, const BwdBuffers &w, const int32_t *idx, hi
                               160 * 1024);
   });
   const size_t NH = (size_t)v.N * v.Hq;
-  BcDqArgs b{v, w.Qs, w.dOs, w.lse2s + NH, w.deltas + NH, w.gws + NH, idx, w.sel.start, w.sel.list, w.sel.bc_chunk_start,
+  BcDqArgs b{v, w.Qs, w.dOg + NH * D, w.lse2s + NH, w.deltas + NH, idx, w.sel.start, w.sel.list, w.sel.bc_chunk_start,
              w.sel.bc_order, w.part.o};
   m_bwd_dq_bc<D, BS::NW, BS::KSEG><<<dim3((chunk_bound(v) + 7) / 8 * 8), 64 * BS::NW, bc_dq_lds_bytes<D, BS::KSEG>(), s>>>(b);
   return hipGetLastError() == hipSuccess ? SSA_OK : SSA_ERR_HIP;
