@@ -259,8 +259,7 @@ struct DkvArgs {
 };
 
 // LDS stage of the dK/dV kernels: ST tiles of 32 query rows each, of Q and of gate * dO (PTile layout: read both as
-// they are and through the transposing LDS load), and two scalars per row: lse in log2 units and -delta*scale (the
-// product is formed once by the staging thread instead of by every lane of every wavefront).  The gate needs no
+// they are and through the transposing LDS load), and two scalars per row: lse in log2 units and -delta.  The gate needs no
 // scalar of its own: it rides on the dO rows, so dP = (gate dO) V^T and dV += P^T (gate dO) already carry it.
 template <int D, int ST>
 struct DkvStage {
@@ -354,7 +353,7 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
   const int sc_arr = (threadIdx.x / (32 * ST)) & 1, sc_r = threadIdx.x % (32 * ST);
   const int sc_slot = (sc_r >> 5) * slots + (sc_r & 31) / hs, sc_head = g * hs + (sc_r & 31) % hs;
   const float *sc_src = sc_arr == 0 ? a.lse2s : a.deltas;
-  const float sc_mul = sc_arr == 1 ? -scale : 1.0f;
+  const float sc_mul = sc_arr == 1 ? -1.0f : 1.0f;
   // sorted position of the token at list index li (-1: past the end)
   // (every load of the staging code is unconditional, with a clamped index: loads under a branch would make the
   // compiler wait for ALL outstanding loads at the next use instead of for the oldest ones)
@@ -416,11 +415,30 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
       // (row tiles past the end of the list are not skipped: their rows carry lse = +inf and add exact zeros, and a
       // stage without branches lets the tiles' matrix and vector work interleave)
       const lds_cptr Qt = st0 + rt * P::BYTES, Dt = st0 + (ST + rt) * P::BYTES;
+      // this lane's eight consecutive query rows 8*quad .. +7 of the tile: row j is element j & 3 of sub-tile j >> 2
+      float lse2[8], nd[8];  // lse (log2 units), -delta
       f32x4 s[KB][2], dp[KB][2];
+      // dS = P (dP - delta) scale: the scale is applied once to the dK sums at the end.  With 32 keys per wavefront the
+      // dP accumulators START from -delta of their rows, so the matrix instruction leaves dP - delta and dS costs one
+      // multiplication per element; with 16 keys per wavefront (d = 128) the tile is too short to wait for the scalars
+      // before its first matrix instruction, and -delta is added afterwards.
+      constexpr bool DELTA_FIRST = KB > 1;
+      {
+        typedef const __attribute__((address_space(3))) f32x4 *f4p;
+        const f32x4 l0 = *(f4p)(scal + 32 * rt), l1 = *(f4p)(scal + 32 * rt + 4);
+        const f32x4 d0 = *(f4p)(scal + 32 * (ST + rt)), d1 = *(f4p)(scal + 32 * (ST + rt) + 4);
 #pragma unroll
-      for (int kbk = 0; kbk < KB; ++kbk)
+        for (int j = 0; j < 4; ++j) {
+          lse2[j] = l0[j]; lse2[4 + j] = l1[j];
+          nd[j] = d0[j]; nd[4 + j] = d1[j];
+        }
 #pragma unroll
-        for (int sa = 0; sa < 2; ++sa) s[kbk][sa] = dp[kbk][sa] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int kbk = 0; kbk < KB; ++kbk) {
+          s[kbk][0] = s[kbk][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+          dp[kbk][0] = DELTA_FIRST ? d0 : f32x4{0.f, 0.f, 0.f, 0.f};
+          dp[kbk][1] = DELTA_FIRST ? d1 : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+      }
 #pragma unroll
       for (int sa = 0; sa < 2; ++sa)
 #pragma unroll
@@ -432,28 +450,16 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
             dp[kbk][sa] = mfma16(da, vop[kbk][ks], dp[kbk][sa]);
           }
         }
-      // this lane's eight consecutive query rows 8*quad .. +7 of the tile
-      float lse2[8], nds[8];  // lse (log2 units), -delta*scale
-      {
-        typedef const __attribute__((address_space(3))) f32x4 *f4p;
-        const f32x4 l0 = *(f4p)(scal + 32 * rt), l1 = *(f4p)(scal + 32 * rt + 4);
-        const f32x4 d0 = *(f4p)(scal + 32 * (ST + rt)), d1 = *(f4p)(scal + 32 * (ST + rt) + 4);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          lse2[j] = l0[j]; lse2[4 + j] = l1[j];
-          nds[j] = d0[j]; nds[4 + j] = d1[j];
-        }
-      }
       bf16x8 pw[KB], ds[KB];
 #pragma unroll
       for (int kbk = 0; kbk < KB; ++kbk)
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           const float sv = j < 4 ? s[kbk][0][j & 3] : s[kbk][1][j & 3];
-          const float dpv = j < 4 ? dp[kbk][0][j & 3] : dp[kbk][1][j & 3];  // gate * dP
+          const float dpv = j < 4 ? dp[kbk][0][j & 3] : dp[kbk][1][j & 3];  // gate * dP (- delta)
           const float p = fast_exp2(__builtin_fmaf(sv, sl2, -lse2[j]));
           pw[kbk][j] = (__bf16)p;
-          ds[kbk][j] = (__bf16)(p * __builtin_fmaf(scale, dpv, nds[j]));
+          ds[kbk][j] = (__bf16)(p * (DELTA_FIRST ? dpv : dpv + nd[j]));
         }
 #pragma unroll
       for (int dt = 0; dt < D / 16; ++dt) {
@@ -483,7 +489,7 @@ __global__ __launch_bounds__(64 * NW) void m_bwd_dkv(DkvArgs a) {
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt) {
       *reinterpret_cast<float4 *>(a.dK + off + acc_dim(dt, quad)) =
-          make_float4(dk[kbk][dt][0], dk[kbk][dt][1], dk[kbk][dt][2], dk[kbk][dt][3]);
+          make_float4(dk[kbk][dt][0] * scale, dk[kbk][dt][1] * scale, dk[kbk][dt][2] * scale, dk[kbk][dt][3] * scale);
       *reinterpret_cast<float4 *>(a.dV + off + acc_dim(dt, quad)) =
           make_float4(dv[kbk][dt][0], dv[kbk][dt][1], dv[kbk][dt][2], dv[kbk][dt][3]);
     }

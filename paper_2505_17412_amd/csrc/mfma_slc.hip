@@ -242,7 +242,7 @@ struct BcDqArgs {
 template <int D>
 struct BcDqRows {
   bf16x8 qop[D / 32], dop[D / 32];
-  float lse2, dls;  // lse in log2 units; delta (gate * <dO, O>) with the softmax scale folded in
+  float lse2, nd;   // lse in log2 units; -delta (delta = gate * <dO, O>)
   uint32_t prow;         // ((pos*Hkv + g)*T + rank)*hs + head
   bool valid;
 };
@@ -261,16 +261,18 @@ __device__ inline void bc_dq_load_rows(const BcDqArgs &a, const int *tl, const i
     r.dop[ks] = r.valid ? ld8(a.dOs + th * D + 8 * quad + 32 * ks) : zero8();
   }
   r.lse2 = r.valid ? a.lse2s[th] : INFINITY;  // a missing column gets P = exp2(-inf) = 0
-  r.dls = a.deltas[th] * a.v.scale;
+  r.nd = -a.deltas[th];
   r.prow = (uint32_t)((((size_t)pos * a.v.Hkv + g) * a.v.T + rank) * hs + hl);
 }
 
-// One 32-key LDS tile: transposed scores (K rows) and dP (V rows, against gate * dO), dS^T = P (dP - delta) scale, then
-// dQ^T += K^T dS^T with K^T read from the same K tile through the transposing LDS load.
+// One 32-key LDS tile: transposed scores (K rows) and dP (V rows, against gate * dO; the accumulators start from
+// -delta of their column, so the matrix instruction leaves dP - delta), dS^T = P (dP - delta), then dQ^T += K^T dS^T
+// with K^T read from the same K tile through the transposing LDS load.  The softmax scale of dS is applied by the merge
+// kernel, once per output element.
 template <int D, bool MASK>
 __device__ inline void bc_dq_tile(f32x4 (&acc)[D / 16], const BcDqRows<D> &r, lds_cptr kt, lds_cptr vt,
-                                  const typename PTile<D, false>::Lanes &ln, int key0, int nk, float sl2, float scale) {
-  f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0, p0 = s0, p1 = s0;
+                                  const typename PTile<D, false>::Lanes &ln, int key0, int nk, float sl2) {
+  f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0, p0 = {r.nd, r.nd, r.nd, r.nd}, p1 = p0;
 #pragma unroll
   for (int ks = 0; ks < D / 32; ++ks) {
     s0 = mfma16(p_row_operand<D, false>(kt, ln, 0, ks), r.qop[ks], s0);
@@ -285,7 +287,7 @@ __device__ inline void bc_dq_tile(f32x4 (&acc)[D / 16], const BcDqRows<D> &r, ld
     const float sv = j < 4 ? s0[j & 3] : s1[j & 3], dp = j < 4 ? p0[j & 3] : p1[j & 3];
     float p = fast_exp2(__builtin_fmaf(sv, sl2, -r.lse2));
     if (MASK && first + j >= nk) p = 0.f;
-    ds[j] = (__bf16)(p * __builtin_fmaf(scale, dp, -r.dls));  // dp already carries the gate: the dO rows are gate * dO
+    ds[j] = (__bf16)(p * dp);  // dp = gate * dP - delta: the dO rows are gate * dO
   }
 #pragma unroll
   for (int dt = 0; dt < D / 16; ++dt) acc[dt] = mfma16(p_tr_operand<D, false>(kt, ln, dt), ds, acc[dt]);
@@ -321,7 +323,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
   const int tpw = 16 / hs;
   const int n_it = (cnt + tpw - 1) / tpw;
   const uint32_t kstride = (uint32_t)(Hkv * D);
-  const float sl2 = a.v.sl2, scale = a.v.scale;
+  const float sl2 = a.v.sl2;
   const typename P::Lanes ln = P::lanes();
   const lds_cptr kt = (lds_cptr)Kt, vt = (lds_cptr)Vt;
   __syncthreads();
@@ -351,22 +353,24 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 64
       }
 #pragma unroll
       for (int t = 0; t < MAXT; ++t)
-        if (t < nfull) bc_dq_tile<D, false>(acc, cur, kt + t * P::BYTES, vt + t * P::BYTES, ln, 32 * t, nk, sl2, scale);
-      if (nk & 31) bc_dq_tile<D, true>(acc, cur, kt + nfull * P::BYTES, vt + nfull * P::BYTES, ln, 32 * nfull, nk, sl2, scale);
+        if (t < nfull) bc_dq_tile<D, false>(acc, cur, kt + t * P::BYTES, vt + t * P::BYTES, ln, 32 * t, nk, sl2);
+      if (nk & 31) bc_dq_tile<D, true>(acc, cur, kt + nfull * P::BYTES, vt + nfull * P::BYTES, ln, 32 * nfull, nk, sl2);
       store_partial_row<D>(a.pdq + (size_t)cur.prow * D, acc, cur.valid);
       cur = nxt;
     }
   }
 }
 
-// dQ[tok] = (compression + window part, fp32, by sorted position) + sum over the token's selected blocks, in rank
-// order, of the partial dQ.  One thread per (sorted position, query head, 8 dims).
+// dQ[tok] = (compression + window part, fp32, by sorted position) + scale * sum over the token's selected blocks, in
+// rank order, of the partial dQ (which the block-centric kernel leaves without the softmax scale).  One thread per
+// (sorted position, query head, 8 dims).
 struct DqMergeArgs {
   const bf16_t *pdq;
   const float *dQp;
   const int32_t *idx, *perm;
   bf16_t *dQ;
   int N, Hq, Hkv, hs, T, D;
+  float scale;
 };
 
 __global__ __launch_bounds__(256) void m_dq_merge(DqMergeArgs a) {
@@ -380,7 +384,8 @@ __global__ __launch_bounds__(256) void m_dq_merge(DqMergeArgs a) {
   for (int j = 0; j < a.T; ++j) nv += row[j] >= 0 ? 1 : 0;
   const float *base = a.dQp + ((size_t)pos * a.Hq + h) * a.D + 8 * c8;
   const float4 b0 = *reinterpret_cast<const float4 *>(base), b1 = *reinterpret_cast<const float4 *>(base + 4);
-  float acc[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+  const float part[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   const size_t slot0 = ((size_t)pos * a.Hkv + g) * a.T;
 #pragma unroll 4
   for (int j = 0; j < nv; ++j) {
@@ -390,7 +395,7 @@ __global__ __launch_bounds__(256) void m_dq_merge(DqMergeArgs a) {
   }
   bf16x8 o;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) o[e] = (__bf16)acc[e];
+  for (int e = 0; e < 8; ++e) o[e] = (__bf16)__builtin_fmaf(a.scale, acc[e], part[e]);
   *reinterpret_cast<bf16x8 *>(a.dQ + ((size_t)tok * a.Hq + h) * a.D + 8 * c8) = o;
 }
 
@@ -463,7 +468,7 @@ int slc_dq_kernel(const MfmaView &v, int D, const BwdBuffers &w, const int32_t *
 }
 
 int slc_dq_merge_kernel(const MfmaView &v, int D, const BwdBuffers &w, const int32_t *idx, void *dq, hipStream_t s) {
-  DqMergeArgs m{w.part.o, w.dQp, idx, v.perm, (bf16_t *)dq, v.N, v.Hq, v.Hkv, v.hs, v.T, D};
+  DqMergeArgs m{w.part.o, w.dQp, idx, v.perm, (bf16_t *)dq, v.N, v.Hq, v.Hkv, v.hs, v.T, D, v.scale};
   const size_t threads = (size_t)v.N * v.Hq * (D / 8);
   m_dq_merge<<<(unsigned)((threads + 255) / 256), 256, 0, s>>>(m);
   return hipGetLastError() == hipSuccess ? SSA_OK : SSA_ERR_HIP;
