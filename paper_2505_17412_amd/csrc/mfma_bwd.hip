@@ -34,6 +34,7 @@ struct PreArgs {
   int N, Hq, Hkv, hs, D;
   bf16_t *dgates;               // [N,Hq,3] caller order
   float *lse2s, *deltas, *gws;  // [3][N(pos)][Hq]
+  float *deltag;                // [3][N(pos)][Hq]: delta taken over the rounded gate * dO rows (see below)
   bf16_t *Qs, *dOg;             // sorted row-major copies: Q [N(pos)][Hq][D], gate_b * dO [3][N(pos)][Hq][D]
 };
 
@@ -64,19 +65,30 @@ __global__ __launch_bounds__(256) void m_bwd_pre(PreArgs a) {
   const int per = a.D / 8;  // 4, 8 or 16 lanes per head
   for (int h0 = 0; h0 < a.Hq; h0 += 256 / per) {
     const int h = h0 + threadIdx.x / per, part = threadIdx.x % per;
-    float acc[3] = {0.f, 0.f, 0.f};
+    // acc: <dO, O_b> (dgates, and delta_b = gate_b * it).  accg: <gate_b * dO as it was rounded into dOg, O_b>: the
+    // kernels that read dOg subtract THIS delta from their dP, so that the two stay the same sum over the same numbers
+    // (a softmax over one or two keys has dP = delta up to rounding, and dS = P (dP - delta) is what is left of it).
+    float acc[3] = {0.f, 0.f, 0.f}, accg[3] = {0.f, 0.f, 0.f};
     if (h < a.Hq) {
       const bf16x8 go = *reinterpret_cast<const bf16x8 *>(td + h * a.D + 8 * part);
+      const bf16_t *gt = a.gates + ((size_t)tok * a.Hq + h) * 3;
 #pragma unroll
       for (int b = 0; b < 3; ++b) {
         const bf16x8 ob = ld8(a.Ob + (((size_t)b * a.N + tok) * a.Hq + h) * a.D + 8 * part);
+        const float w = bf16_to_f32(gt[b]);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[b] += (float)go[j] * (float)ob[j];
+        for (int j = 0; j < 8; ++j) {
+          acc[b] += (float)go[j] * (float)ob[j];
+          accg[b] += (float)(__bf16)(w * (float)go[j]) * (float)ob[j];
+        }
       }
     }
     for (int off = 1; off < per; off <<= 1)
 #pragma unroll
-      for (int b = 0; b < 3; ++b) acc[b] += __shfl_xor(acc[b], off);
+      for (int b = 0; b < 3; ++b) {
+        acc[b] += __shfl_xor(acc[b], off);
+        accg[b] += __shfl_xor(accg[b], off);
+      }
     if (h < a.Hq && part < 3) {
       const int b = part;
       const float dot = b == 0 ? acc[0] : (b == 1 ? acc[1] : acc[2]);
@@ -87,6 +99,7 @@ __global__ __launch_bounds__(256) void m_bwd_pre(PreArgs a) {
       a.lse2s[s] = a.lse[((size_t)b * a.N + tok) * a.Hq + h] * LOG2E;
       a.deltas[s] = w * dot;
       a.gws[s] = w;
+      a.deltag[s] = b == 0 ? accg[0] : (b == 1 ? accg[1] : accg[2]);
     }
   }
 }
@@ -247,7 +260,7 @@ enum { DKV_WIN = 0, DKV_SLC = 1, DKV_CMP = 2 };
 struct DkvArgs {
   MfmaView v;
   const bf16_t *Qs, *dOs;             // sorted copies [N(pos)][Hq][D]: Q, and the branch's gate * dO
-  const float *lse2s, *deltas;        // already offset to the branch: [N(pos)][Hq]
+  const float *lse2s, *deltas;        // already offset to the branch: [N(pos)][Hq]; delta over the rounded gate * dO rows
   const int32_t *sel_start, *sel_list;  // selection branch: query positions per (g, block)
   float *dK, *dV;                       // [rows][Hkv][D] fp32 (rows: sorted tokens, or compression blocks)
   const int32_t *chunk_start;           // selection branch: [Hkv*Ns+1] first work chunk of each (g, block)
@@ -579,7 +592,7 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
   {
     ProfScope ps(PROF_BWD_PRE, s);
     PreArgs a{(const bf16_t *)q, (const bf16_t *)dout, (const bf16_t *)out_branch, (const bf16_t *)gates, lse, v.perm,
-              N, Hq, Hkv, v.hs, D, (bf16_t *)dgates, w.lse2s, w.deltas, w.gws, w.Qs, w.dOg};
+              N, Hq, Hkv, v.hs, D, (bf16_t *)dgates, w.lse2s, w.deltas, w.gws, w.deltag, w.Qs, w.dOg};
     m_bwd_pre<<<N, 256, (size_t)Hq * D * sizeof(bf16_t), s>>>(a);
   }
   static std::once_flag dq_once;  // raise the dynamic LDS limit once per process for this instantiation
@@ -625,14 +638,14 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
   {
     ProfScope ps(PROF_BWD_DKV_WIN, s);
     DkvArgs a = base;
-    a.lse2s = w.lse2s + 2 * NH; a.deltas = w.deltas + 2 * NH; a.dOs = w.dOg + 2 * NH * D;
+    a.lse2s = w.lse2s + 2 * NH; a.deltas = w.deltag + 2 * NH; a.dOs = w.dOg + 2 * NH * D;
     a.tiles_per_block = (blk->win_tok_max + WG_KEYS - 1) / WG_KEYS;
     m_bwd_dkv<D, KB_KEYS, DKV_WIN, DKV_WAVES, ST><<<dim3(blk->Nw * a.tiles_per_block, Hkv), 64 * DKV_WAVES, dkv_lds, s>>>(a);
   }
   {
     ProfScope ps(PROF_BWD_DKV_SLC, s);
     DkvArgs a = base;
-    a.lse2s = w.lse2s + NH; a.deltas = w.deltas + NH; a.dOs = w.dOg + NH * D;
+    a.lse2s = w.lse2s + NH; a.deltas = w.deltag + NH; a.dOs = w.dOg + NH * D;
     a.dK = w.pK; a.dV = w.pV;
     a.tiles_per_block = (blk->slc_tok_max + WG_KEYS - 1) / WG_KEYS;
     m_bwd_dkv<D, KB_KEYS, DKV_SLC, DKV_WAVES, ST><<<dim3((w.max_chunks + 7) / 8 * 8 * a.tiles_per_block), 64 * DKV_WAVES, dkv_lds, s>>>(a);
@@ -643,7 +656,7 @@ int launch_backward(const MfmaView &v, const BwdBuffers &w, const void *q, const
   {
     ProfScope ps(PROF_BWD_DKV_CMP, s);
     DkvArgs a = base;
-    a.lse2s = w.lse2s; a.deltas = w.deltas; a.dOs = w.dOg;
+    a.lse2s = w.lse2s; a.deltas = w.deltag; a.dOs = w.dOg;
     a.dK = w.dKc; a.dV = w.dVc;
     a.tiles_per_block = (blk->c_max + WG_KEYS_CMP - 1) / WG_KEYS_CMP;
     a.q_splits = w.q_splits;

@@ -42,6 +42,7 @@ int slc_merge_kernel(const MfmaView &v, int D, const SlcPartials &part, const in
 // Device buffers of the backward pass (carved from the caller's workspace).
 struct BwdBuffers {
   float *lse2s, *deltas, *gws;  // [3][N(pos)][Hq]: lse*log2(e), gate*<dO,O_b>, gate
+  float *deltag;                // [3][N(pos)][Hq]: <gate*dO as rounded into dOg, O_b>: the delta of the kernels that read dOg
   bf16_t *Qs, *dOg;             // sorted token order: Q [N(pos)][Hq][D]; gate_b * dO [3][N(pos)][Hq][D], one copy per branch b
   float *dKs, *dVs;             // [N(pos)][Hkv][D] token-level gradients in sorted order
   float *dQp;                   // [N(pos)][Hq][D] compression-branch part of dQ (fp32)

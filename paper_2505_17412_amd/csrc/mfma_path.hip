@@ -136,7 +136,7 @@ int override_pooled(const ssa_ctx &c, const PrepOut &o) {
 }
 
 struct BwdPlan {
-  size_t ks, vs, kc, vc, lse2s, deltas, gws, qs, dos, dqp, dks, dvs, dkc, dvc, sel, pk, pv, pdq, total;
+  size_t ks, vs, kc, vc, lse2s, deltas, gws, deltag, qs, dos, dqp, dks, dvs, dkc, dvc, sel, pk, pv, pdq, total;
   int q_splits, chunk_len, max_chunks;
 };
 
@@ -155,7 +155,7 @@ BwdPlan bwd_plan(const ssa_ctx &c) {
   p.ks = take(padded_rows(c.N) * row * 2); p.vs = take(padded_rows(c.N) * row * 2);
   p.kc = take(padded_rows(b->Nc) * row * 2); p.vc = take(padded_rows(b->Nc) * row * 2);
   const size_t nh = (size_t)3 * c.N * c.Hq * 4;
-  p.lse2s = take(nh); p.deltas = take(nh); p.gws = take(nh);
+  p.lse2s = take(nh); p.deltas = take(nh); p.gws = take(nh); p.deltag = take(nh);
   p.qs = take((size_t)c.N * c.Hq * c.d * 2); p.dos = take((size_t)3 * c.N * c.Hq * c.d * 2);
   p.dqp = take((size_t)c.N * c.Hq * c.d * 4);
   p.dks = take((size_t)c.N * row * 4); p.dvs = take((size_t)c.N * row * 4);
@@ -226,6 +226,7 @@ int mfma_backward(const ssa_ctx &c, const void *q, const void *k, const void *v,
   BwdBuffers w{};
   w.dKc_out = c.dkc_out; w.dVc_out = c.dvc_out;
   w.lse2s = (float *)(ws + p.lse2s); w.deltas = (float *)(ws + p.deltas); w.gws = (float *)(ws + p.gws);
+  w.deltag = (float *)(ws + p.deltag);
   w.Qs = (bf16_t *)(ws + p.qs); w.dOg = (bf16_t *)(ws + p.dos); w.dQp = (float *)(ws + p.dqp);
   w.dKs = (float *)(ws + p.dks); w.dVs = (float *)(ws + p.dvs); w.dKc = (float *)(ws + p.dkc); w.dVc = (float *)(ws + p.dvc);
   w.sel = sel_index_carve(ws + p.sel, c.N, c.Hkv, c.T, c.blk->Ns, p.chunk_len, BC_CHUNK);

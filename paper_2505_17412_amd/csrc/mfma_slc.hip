@@ -431,7 +431,7 @@ int launch_slc_dq(const MfmaView &v, const BwdBuffers &w, const int32_t *idx, hi
                               160 * 1024);
   });
   const size_t NH = (size_t)v.N * v.Hq;
-  BcDqArgs b{v, w.Qs, w.dOg + NH * D, w.lse2s + NH, w.deltas + NH, idx, w.sel.start, w.sel.list, w.sel.bc_chunk_start,
+  BcDqArgs b{v, w.Qs, w.dOg + NH * D, w.lse2s + NH, w.deltag + NH, idx, w.sel.start, w.sel.list, w.sel.bc_chunk_start,
              w.sel.bc_order, w.part.o};
   m_bwd_dq_bc<D, BS::NW, BS::KSEG><<<dim3((chunk_bound(v) + 7) / 8 * 8), 64 * BS::NW, bc_dq_lds_bytes<D, BS::KSEG>(), s>>>(b);
   return hipGetLastError() == hipSuccess ? SSA_OK : SSA_ERR_HIP;

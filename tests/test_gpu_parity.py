@@ -389,3 +389,15 @@ def test_gates_of_any_sign_and_zero(which):
     wl.gates = inputs.round_to_bf16(gates) if wl.dtype == "bf16" else gates
     assert (wl.gates < 0).any() and (wl.gates == 0).any()
     full_parity(wl)
+
+
+@pytest.mark.parametrize("seed,grid,n,hq,hkv,d,m,topk", [
+    (167765, 64, (73,), 16, 1, 64, (1, 2, 4), 1),
+    (7, 32, (150, 90), 8, 1, 64, (1, 2, 4), 1),
+])
+def test_softmaxes_over_one_or_two_keys(seed, grid, n, hq, hkv, d, m, topk):
+    """A few dozen scattered tokens, one-voxel compression blocks, one selected block: most selection and window
+    softmaxes run over one or two keys, where dP equals delta up to rounding and dS = P (dP - delta) is what the
+    roundings leave.  The two sums must then be taken over the same rounded numbers (the backward kernels that read the
+    gate-weighted dO rows subtract a delta formed from those same rows), or dK drifts out of the tolerance."""
+    full_parity(inputs.random_points_workload(seed, grid, n, hq, hkv, d, m, topk, "bf16"))
