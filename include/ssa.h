@@ -128,8 +128,9 @@ void ssa_blocks_destroy(ssa_blocks_t *blocks);
  * How it scales (bf16 matrix-core path; N tokens, Hq/Hkv heads, head_dim d, top-k T, Ns selection blocks): both passes
  * keep one bf16 partial result per (token, query head, selected block), N*Hq*T*d*2 bytes (2.0 GB at the benchmark
  * shape N = 62k, Hq = 16, T = 16, d = 64; the forward adds N*Hq*T*8 bytes of softmax statistics), and the inverse of the
- * selection: a bit matrix of Hkv*Ns*N/8 bytes plus N*Hkv*T*4 bytes of lists.  Backward adds sorted copies of q and
- * dout (2*N*Hq*d*2 bytes), an fp32 partial dq (N*Hq*d*4 bytes) and up to about 1 GiB of per-chunk partial dk/dv sums.
+ * selection: a bit matrix of Hkv*Ns*N/8 bytes plus N*Hkv*T*4 bytes of lists.  Backward adds sorted copies of q and of
+ * gate*dout, one per branch (4*N*Hq*d*2 bytes), an fp32 partial dq (N*Hq*d*4 bytes) and up to about 1 GiB of per-chunk
+ * partial dk/dv sums.
  */
 size_t ssa_workspace_bytes(const ssa_params_t *params, const ssa_blocks_t *blocks, int for_backward);
 
